@@ -1,0 +1,323 @@
+"""Pins of the CPU oracle's layer / stack functions (CPU only).
+
+Witness: a float64 decoder layer assembled from tensor-library primitives (matmul,
+scaled_dot_product_attention, silu, complex multiplication for the rotary embedding) plus
+the single operators that tests/test_oracle_ops.py pins on their own."""
+import math
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+import oracle
+from paper_2605_10875_amd import synth
+
+SHAPE = synth.ModelShape(d_model=64, n_q_heads=4, n_kv_heads=2, head_dim=16, d_ff=96, n_layers=2, vocab=50)
+DENSE = [synth.DENSE_ACTION]
+
+
+def _rms(x, w, eps):
+    return x * torch.rsqrt(x.pow(2).mean(-1, keepdim=True) + eps) * w
+
+
+def _rope_complex(x, pos, theta):
+    # x [..., T, H, dh]; pairs (c, c + dh/2) seen as complex numbers rotated by pos * theta^(-2c/dh)
+    dh = x.shape[-1]
+    half = dh // 2
+    inv = theta ** (-torch.arange(half, dtype=torch.float64) * 2.0 / dh)
+    ang = pos.double()[:, None] * inv[None, :]                       # [T, half]
+    rot = torch.polar(torch.ones_like(ang), ang)[:, None, :]         # [T, 1, half]
+    xc = torch.complex(x[..., :half], x[..., half:]) * rot
+    return torch.cat([xc.real, xc.imag], -1)
+
+
+def witness_layer(shape, w, x, table, ids, keep_mask=None, quant_sites=oracle.QS_NORTHSTAR, prune_site=0):
+    """float64 layer for pos0 = 0. keep_mask [n,T,Hq,T] (from the oracle's tap) or None = causal dense."""
+    W = {k: torch.from_numpy(v).double() for k, v in w.items()}
+    x = torch.from_numpy(x).double()
+    n, T, d = x.shape
+    Hq, Hkv, dh = shape.n_q_heads, shape.n_kv_heads, shape.head_dim
+
+    def fq(t, site):
+        if not (quant_sites & site):
+            return t
+        out = t.clone()
+        for s in range(n):
+            for i in range(T):
+                bits = table[ids[s, i]][4]
+                out[s, i] = torch.from_numpy(oracle.fake_quant(t[s, i].float().numpy(), bits)[0]).double()
+        return out
+
+    def prune(t):
+        out = t.clone()
+        for s in range(n):
+            for i in range(T):
+                num, den = table[ids[s, i]][2:4]
+                m = max(1, min(t.shape[-1], math.ceil(num * t.shape[-1] / den)))
+                keep = oracle.topm_mask(t[s, i].float().numpy(), m)
+                out[s, i] = t[s, i] * torch.from_numpy(keep).double()
+        return out
+
+    h1 = fq(_rms(x, W["w_in_norm"], shape.rms_eps).float().double(), oracle.QS_QKV_IN)
+    pos = torch.arange(T)
+    q = _rope_complex((h1 @ W["wq"].T).view(n, T, Hq, dh), pos, shape.rope_theta)
+    k = _rope_complex((h1 @ W["wk"].T).view(n, T, Hkv, dh), pos, shape.rope_theta)
+    v = (h1 @ W["wv"].T).view(n, T, Hkv, dh)
+    qh = q.permute(0, 2, 1, 3)
+    kh = k.permute(0, 2, 1, 3).repeat_interleave(Hq // Hkv, dim=1)
+    vh = v.permute(0, 2, 1, 3).repeat_interleave(Hq // Hkv, dim=1)
+    if keep_mask is None:
+        o = F.scaled_dot_product_attention(qh, kh, vh, is_causal=True)
+    else:
+        km = torch.from_numpy(keep_mask[:, :, :, :T].astype(bool)).permute(0, 2, 1, 3)   # [n,Hq,T,T]
+        bias = torch.where(km, 0.0, -math.inf).double()
+        o = F.scaled_dot_product_attention(qh, kh, vh, attn_mask=bias)
+    o = o.permute(0, 2, 1, 3).reshape(n, T, Hq * dh)
+    o = fq(o.float().double(), oracle.QS_O_IN)
+    x2 = x + o @ W["wo"].T
+    h2 = _rms(x2, W["w_post_norm"], shape.rms_eps).float().double()
+    if prune_site == 1:
+        h2 = prune(h2)
+    h2 = fq(h2, oracle.QS_GATEUP_IN)
+    a = (F.silu(h2 @ W["w_gate"].T) * (h2 @ W["w_up"].T)).float().double()
+    if prune_site == 0:
+        a = prune(a)
+    a = fq(a, oracle.QS_DOWN_IN)
+    z = a @ W["w_down"].T
+    z = fq(z.float().double(), oracle.QS_MLP_OUT)
+    scores = (qh @ kh.transpose(-1, -2)) / math.sqrt(dh)
+    return (x2 + z).numpy(), scores.numpy(), a.numpy()
+
+
+def _caches(shape, n_seq, L):
+    z = np.zeros((n_seq, shape.n_kv_heads, L, shape.head_dim), np.float32)
+    return z, z.copy()
+
+
+def test_dense_action_is_the_textbook_layer():
+    w = synth.layer_weights(SHAPE, 11, std=0.15)
+    x = synth.hidden_states(2, 12, SHAPE.d_model, 12)
+    cfg, tab = oracle.make_cfg(SHAPE), oracle.make_table(DENSE)
+    kc, vc = _caches(SHAPE, 2, 12)
+    out, _ = oracle.layer_forward(cfg, tab, w, x, np.zeros((2, 12), np.int32), kc, vc)
+    want, _, _ = witness_layer(SHAPE, w, x, DENSE, np.zeros((2, 12), np.int32))
+    assert np.abs(out - want).max() < 1e-5 * np.abs(want).max()
+    # the paper's preset (pages, sinks, MLP-input prune, MLP-output quant) is dense too under a dense action
+    cfg_p = oracle.make_cfg(SHAPE, page_size=4, n_sink=4, n_window=2, prune_site=1, quant_sites=oracle.QS_PAPER)
+    kc2, vc2 = _caches(SHAPE, 2, 12)
+    out_p, _ = oracle.layer_forward(cfg_p, tab, w, x, np.zeros((2, 12), np.int32), kc2, vc2)
+    assert np.array_equal(out_p, out) and np.array_equal(kc2, kc)
+
+
+@pytest.mark.parametrize("preset", ["northstar", "paper_sites"])
+def test_action_conditioned_layer_against_witness(preset):
+    table = synth.action_table((0.25, 0.5, 1.0), (0.0, 0.25, 0.5), (4, 8, 16))
+    w = synth.layer_weights(SHAPE, 21, std=0.15)
+    n, T = 2, 14
+    x = synth.hidden_states(n, T, SHAPE.d_model, 22)
+    ids = synth.iid_actions(len(table), (n, T), 23)
+    if preset == "northstar":
+        kw = dict()
+        wkw = dict()
+    else:
+        kw = dict(prune_site=1, quant_sites=oracle.QS_PAPER)
+        wkw = dict(prune_site=1, quant_sites=oracle.QS_PAPER)
+    cfg, tab = oracle.make_cfg(SHAPE, **kw), oracle.make_table(table)
+    kc, vc = _caches(SHAPE, n, T)
+    out, taps = oracle.layer_forward(cfg, tab, w, x, ids, kc, vc, taps=("keep_mask", "mlp_act"))
+    want, scores, a = witness_layer(SHAPE, w, x, table, ids, keep_mask=taps["keep_mask"], **wkw)
+    assert np.abs(out - want).max() < 2e-5 * np.abs(want).max()
+    assert np.abs(taps["mlp_act"] - a).max() < 2e-5 * np.abs(a).max()
+    # the attended sets are the top-ceil(kappa*n) causal scores of the witness
+    km = taps["keep_mask"]
+    for s in range(n):
+        for i in range(T):
+            num, den = table[ids[s, i]][:2]
+            b = max(1, math.ceil(num * (i + 1) / den))
+            for h in range(SHAPE.n_q_heads):
+                row = scores[s, h, i, :i + 1].astype(np.float32)
+                top = sorted(range(i + 1), key=lambda j: (-row[j], j))[:b]
+                assert km[s, i, h, :i + 1].sum() == b and km[s, i, h, i + 1:].sum() == 0
+                assert set(np.nonzero(km[s, i, h])[0]) == set(top)
+            if preset == "northstar" and table[ids[s, i]][4] >= 16:   # small codes round to 0
+                mnum, mden = table[ids[s, i]][2:4]
+                m = math.ceil(mnum * SHAPE.d_ff / mden)
+                assert np.count_nonzero(taps["mlp_act"][s, i]) == m
+
+
+def test_keep_all_budget_is_bitwise_dense_attention():
+    # a keep fraction so close to 1 that ceil(kappa*n) = n for every row: same bits as kappa = 1
+    table = [(1, 1, 1, 1, 16), (4095, 4096, 1, 1, 16)]
+    w = synth.layer_weights(SHAPE, 31, std=0.15)
+    x = synth.hidden_states(1, 20, SHAPE.d_model, 32)
+    cfg, tab = oracle.make_cfg(SHAPE), oracle.make_table(table)
+    outs = []
+    for a in (0, 1):
+        kc, vc = _caches(SHAPE, 1, 20)
+        outs.append(oracle.layer_forward(cfg, tab, w, x, np.full((1, 20), a, np.int32), kc, vc)[0])
+    assert np.array_equal(outs[0], outs[1])
+
+
+def test_single_axis_actions_leave_the_other_paths_alone():
+    w = synth.layer_weights(SHAPE, 41, std=0.15)
+    x = synth.hidden_states(1, 16, SHAPE.d_model, 42)
+    table = [(1, 1, 1, 1, 16), (1, 4, 1, 1, 16), (1, 1, 1, 2, 16), (1, 1, 1, 1, 4)]
+    cfg, tab = oracle.make_cfg(SHAPE), oracle.make_table(table)
+    res = []
+    for a in range(4):
+        kc, vc = _caches(SHAPE, 1, 16)
+        out, taps = oracle.layer_forward(cfg, tab, w, x, np.full((1, 16), a, np.int32), kc, vc,
+                                         taps=("attn_out", "x_mid", "mlp_act"))
+        res.append((out, taps, kc.copy(), vc.copy()))
+    dense = res[0]
+    # sparse attention only: K/V identical (projections untouched), attention output differs
+    assert np.array_equal(res[1][2], dense[2]) and np.array_equal(res[1][3], dense[3])
+    assert not np.array_equal(res[1][1]["attn_out"], dense[1]["attn_out"])
+    assert np.array_equal(res[1][1]["attn_out"][0, :1], dense[1]["attn_out"][0, :1])   # one allowed key: kept
+    # MLP pruning only: everything up to the MLP input identical; half of the channels zero
+    assert np.array_equal(res[2][1]["x_mid"], dense[1]["x_mid"])
+    assert np.all(np.count_nonzero(res[2][1]["mlp_act"], axis=-1) == SHAPE.d_ff // 2)
+    kept = res[2][1]["mlp_act"] != 0
+    assert np.array_equal(res[2][1]["mlp_act"][kept], dense[1]["mlp_act"][kept])
+    # quantisation only: at most 2*q_max+1 = 15 distinct values per token at the down-proj input
+    for i in range(16):
+        assert len(np.unique(res[3][1]["mlp_act"][0, i])) <= 15
+    assert not np.array_equal(res[3][2], dense[2])                   # K/V are committed under the action
+
+
+def test_row_zero_of_sparse_attention_matches_dense_row():
+    # with one allowed key every budget keeps it
+    w = synth.layer_weights(SHAPE, 41, std=0.15)
+    x = synth.hidden_states(1, 3, SHAPE.d_model, 43)
+    table = [(1, 1, 1, 1, 16), (1, 16, 1, 1, 16)]
+    cfg, tab = oracle.make_cfg(SHAPE), oracle.make_table(table)
+    o = []
+    for a in (0, 1):
+        kc, vc = _caches(SHAPE, 1, 3)
+        o.append(oracle.layer_forward(cfg, tab, w, x, np.full((1, 3), a, np.int32), kc, vc, taps=("attn_out",))[1]["attn_out"])
+    assert np.array_equal(o[0][0, 0], o[1][0, 0]) and not np.array_equal(o[0][0, 2], o[1][0, 2])
+
+
+def _stack(shape, seed, std=0.15):
+    layers = [synth.layer_weights(shape, seed + l, std=std) for l in range(shape.n_layers)]
+    head = synth.head_weights(shape, seed + 100, std=std)
+    return layers, head
+
+
+def test_batched_pass_equals_stepwise_decode_bitwise():
+    table = synth.TABLE_C1
+    layers, head = _stack(SHAPE, 51)
+    B, G, T = 2, 2, 9
+    tokens, targets = synth.tokens_and_targets(B, T, SHAPE.vocab, 52)
+    ids = synth.iid_actions(len(table), (B, G, T), 53)
+    for kw in (dict(), dict(page_size=4, n_sink=2, n_window=1, prune_site=1, quant_sites=oracle.QS_PAPER),
+               dict(act_bf16=True)):
+        cfg, tab = oracle.make_cfg(SHAPE, **kw), oracle.make_table(table)
+        nll, hid = oracle.schedule_loglik(cfg, tab, head["embed"], layers, head["w_final_norm"], head["lm_head"],
+                                          tokens, targets, ids, want_hidden=True)
+        N = B * G
+        kcs = [np.zeros((N, SHAPE.n_kv_heads, T, SHAPE.head_dim), np.float32) for _ in layers]
+        vcs = [np.zeros((N, SHAPE.n_kv_heads, T, SHAPE.head_dim), np.float32) for _ in layers]
+        flat_ids = ids.reshape(N, T)
+        tok_n = np.repeat(tokens, G, axis=0)
+        tgt_n = np.repeat(targets, G, axis=0)
+        for t in range(T):
+            x0 = head["embed"][tok_n[:, t]]
+            h, nl = oracle.decode_step(cfg, tab, layers, x0, flat_ids[:, t], np.full(N, t, np.int32), kcs, vcs,
+                                       head["w_final_norm"], head["lm_head"], tgt_n[:, t])
+            assert np.array_equal(h, hid.reshape(N, T, -1)[:, t])
+            assert np.array_equal(nl, nll.reshape(N, T)[:, t])
+
+
+def test_identical_schedules_identical_likelihoods_and_batch_independence():
+    table = synth.TABLE_C1
+    layers, head = _stack(SHAPE, 61)
+    B, G, T = 2, 3, 10
+    tokens, targets = synth.tokens_and_targets(B, T, SHAPE.vocab, 62)
+    one = synth.iid_actions(len(table), (B, 1, T), 63)
+    ids = np.repeat(one, G, axis=1)
+    cfg, tab = oracle.make_cfg(SHAPE), oracle.make_table(table)
+    nll = oracle.schedule_loglik(cfg, tab, head["embed"], layers, head["w_final_norm"], head["lm_head"],
+                                 tokens, targets, ids)
+    for g in range(1, G):
+        assert np.array_equal(nll[:, g], nll[:, 0])
+    # a sequence's result does not depend on what else is in the batch, nor on its slot
+    solo = oracle.schedule_loglik(cfg, tab, head["embed"], layers, head["w_final_norm"], head["lm_head"],
+                                  tokens[1:], targets[1:], ids[1:])
+    assert np.array_equal(solo[0], nll[1])
+    # dense schedule == plain stack: NLL equals -log_softmax of a float64 witness stack
+    dense_ids = np.zeros((B, 1, T), np.int32)
+    cfg_d, tab_d = oracle.make_cfg(SHAPE), oracle.make_table(DENSE)
+    nll_d = oracle.schedule_loglik(cfg_d, tab_d, head["embed"], layers, head["w_final_norm"], head["lm_head"],
+                                   tokens, targets, dense_ids)
+    x = head["embed"][tokens]
+    for w in layers:
+        x = witness_layer(SHAPE, w, x.astype(np.float32), DENSE, np.zeros((B, T), np.int32))[0]
+    hf = _rms(torch.from_numpy(x).double(), torch.from_numpy(head["w_final_norm"]).double(), SHAPE.rms_eps)
+    lsm = torch.log_softmax(hf @ torch.from_numpy(head["lm_head"]).double().T, -1)
+    want = -torch.gather(lsm, -1, torch.from_numpy(targets).long()[..., None])[..., 0]
+    assert np.abs(nll_d[:, 0] - want.numpy()).max() < 5e-5
+
+
+def test_causality_and_kv_pollution_impulse():
+    # compress a burst of steps, then return to dense: positions before the burst keep their bits,
+    # positions after it differ because they attend to K/V committed under the compressed actions
+    table = [synth.DENSE_ACTION, (1, 4, 1, 2, 4)]
+    layers, head = _stack(SHAPE, 71)
+    T, t0, burst = 16, 5, 4
+    tokens, targets = synth.tokens_and_targets(1, T, SHAPE.vocab, 72)
+    ids = np.zeros((1, 2, T), np.int32)
+    ids[0, 1, t0:t0 + burst] = 1
+    cfg, tab = oracle.make_cfg(SHAPE), oracle.make_table(table)
+    nll, hid = oracle.schedule_loglik(cfg, tab, head["embed"], layers, head["w_final_norm"], head["lm_head"],
+                                      tokens, targets, ids, want_hidden=True)
+    assert np.array_equal(hid[0, 0, :t0], hid[0, 1, :t0]) and np.array_equal(nll[0, 0, :t0], nll[0, 1, :t0])
+    for t in range(t0, T):
+        assert not np.array_equal(hid[0, 0, t], hid[0, 1, t])
+
+
+def test_prefix_cache_positions():
+    # running tokens [0,T) in one call equals running [0,T1) then [T1,T) with pos0 = T1 on the same cache
+    table = synth.TABLE_C1
+    w = synth.layer_weights(SHAPE, 81, std=0.15)
+    T, T1 = 12, 7
+    x = synth.hidden_states(1, T, SHAPE.d_model, 82)
+    ids = synth.iid_actions(len(table), (1, T), 83)
+    cfg, tab = oracle.make_cfg(SHAPE), oracle.make_table(table)
+    kc, vc = _caches(SHAPE, 1, T)
+    full, _ = oracle.layer_forward(cfg, tab, w, x, ids, kc, vc)
+    kc2, vc2 = _caches(SHAPE, 1, T)
+    a, _ = oracle.layer_forward(cfg, tab, w, x[:, :T1], ids[:, :T1], kc2, vc2)
+    b, _ = oracle.layer_forward(cfg, tab, w, x[:, T1:], ids[:, T1:], kc2, vc2, pos0=np.array([T1], np.int32))
+    assert np.array_equal(np.concatenate([a, b], 1), full) and np.array_equal(kc2, kc)
+
+
+def test_bf16_mode_rounds_the_handed_over_tensors():
+    table = synth.TABLE_C1
+    w = synth.layer_weights(SHAPE, 91, std=0.15, bf16=True)
+    x = synth.hidden_states(1, 8, SHAPE.d_model, 92, bf16=True)
+    ids = synth.iid_actions(len(table), (1, 8), 93)
+    cfg, tab = oracle.make_cfg(SHAPE, act_bf16=True), oracle.make_table(table)
+    kc, vc = _caches(SHAPE, 1, 8)
+    out, taps = oracle.layer_forward(cfg, tab, w, x, ids, kc, vc, taps=("mlp_act",))
+    for t in (out, kc, vc, taps["mlp_act"]):
+        assert np.array_equal(t, synth.round_to_bf16(t))
+    cfg32 = oracle.make_cfg(SHAPE)
+    kc3, vc3 = _caches(SHAPE, 1, 8)
+    out32, _ = oracle.layer_forward(cfg32, tab, w, x, ids, kc3, vc3)
+    assert np.abs(out - out32).max() < 0.2 * np.abs(out32).max()
+
+
+def test_argument_errors():
+    w = synth.layer_weights(SHAPE, 1)
+    x = synth.hidden_states(1, 4, SHAPE.d_model, 2)
+    cfg = oracle.make_cfg(SHAPE)
+    kc, vc = _caches(SHAPE, 1, 4)
+    with pytest.raises(ValueError, match="-4"):
+        oracle.layer_forward(cfg, oracle.make_table(DENSE), w, x, np.full((1, 4), 3, np.int32), kc, vc)
+    with pytest.raises(ValueError, match="-4"):
+        oracle.layer_forward(cfg, oracle.make_table([(0, 1, 1, 1, 16)]), w, x, np.zeros((1, 4), np.int32), kc, vc)
+    with pytest.raises(ValueError, match="-5"):
+        oracle.layer_forward(cfg, oracle.make_table(DENSE), w, x, np.zeros((1, 4), np.int32), kc, vc,
+                             pos0=np.array([1], np.int32))
