@@ -1,0 +1,195 @@
+/*
+ * sol.h -- C ABI of the MI355X (gfx950) library for the action-conditioned forward pass of a
+ * frozen Llama decoder layer (SOL: a per-token discrete "efficiency action" selects an attention
+ * keep-rate, an MLP channel keep-rate and an activation bit-width inside the same frozen model).
+ *
+ * Conventions that hold for every entry point
+ *   - Pointers named in a "device" comment are DEVICE pointers (HIP global memory, e.g. a torch
+ *     tensor's data_ptr()); structs (sol_model_cfg, sol_action_def[], sol_layer_weights,
+ *     sol_model_weights and the per-layer cache pointer arrays) are HOST memory read during the
+ *     call only.
+ *   - Ownership: every buffer is allocated and owned by the caller. The library borrows it for
+ *     the call, never frees it, and allocates device memory only inside sol_create.
+ *     Weights are read-only (the base model is frozen; Method, first paragraph).
+ *   - Asynchrony: work is enqueued on `stream` (a hipStream_t, NULL = default stream). No entry
+ *     point synchronises; outputs are valid once the caller has synchronised the stream.
+ *   - Errors: an int status is returned, no exception crosses the ABI; sol_last_error gives text.
+ *     Everything that can be checked on the host (null pointers, shapes, table contents,
+ *     workspace size, static cache overflow) is checked before the first launch. Conditions that
+ *     live in device memory (an action id outside the table, pos0[s] + T > L_max) make the kernels
+ *     treat the token as a dense-action token / skip the sequence and raise a sticky flag that
+ *     sol_device_status reports.
+ *   - Layouts: row-major. Weight matrices are [out_features][in_features]. Activations are
+ *     [n_seq][T][d_model]. KV caches are [n_seq][n_kv_heads][L_max][head_dim] with keys stored
+ *     after the rotary embedding. Element type of weights, activations and caches is cfg.dtype.
+ *   - Determinism: a sequence's outputs do not depend on what else is in the batch, nor on its
+ *     slot; no floating-point atomics, no data-dependent reduction order.
+ *
+ * Numerics with dtype = SOL_BF16: contractions run on bf16 inputs with fp32 accumulation; the
+ * tensors handed between operators (normed+quantised linear inputs, q, k, v, attention output,
+ * SiLU(gate)*up, layer output) are bf16; the residual inside a layer and all selection /
+ * quantisation decisions are fp32. With SOL_F32 everything is fp32.
+ */
+#ifndef SOL_H
+#define SOL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SOL_OK = 0,
+    SOL_ERR_INVALID_ARG = -1,   /* null pointer, non-positive size, inconsistent shape          */
+    SOL_ERR_UNSUPPORTED = -2,   /* valid request this build has no kernel for                    */
+    SOL_ERR_WORKSPACE = -3,     /* workspace pointer null / smaller than sol_workspace_bytes     */
+    SOL_ERR_ACTION = -4,        /* action table entry or action id out of range                  */
+    SOL_ERR_CACHE_OVERFLOW = -5,/* tokens would be written past L_max                            */
+    SOL_ERR_HIP = -6            /* a HIP runtime call failed (text in sol_last_error)            */
+} sol_status;
+
+typedef enum { SOL_F32 = 0, SOL_BF16 = 1 } sol_dtype;
+
+/* quant_sites bits: linear-layer inputs that receive the per-token fake-quantiser. */
+#define SOL_QS_QKV_IN    1u
+#define SOL_QS_O_IN      2u
+#define SOL_QS_GATEUP_IN 4u
+#define SOL_QS_DOWN_IN   8u
+#define SOL_QS_ALL_LINEAR_INPUTS 15u
+
+/* One row of the action table a -> (kappa(a), rho(a), q(a)) (Method, "Actions and controlled
+ * compute"). Fractions are rationals so that ceil(kappa * n) is exact integer arithmetic.
+ * 0 < keep_num <= keep_den, 0 < mlp_keep_num <= mlp_keep_den, bits >= 4; bits >= 16 bypasses
+ * the quantiser (Appendix "Quantizer": q >= 16 returns the input unchanged). */
+typedef struct {
+    uint32_t keep_num, keep_den;          /* kappa: attention keep fraction */
+    uint32_t mlp_keep_num, mlp_keep_den;  /* rho:   MLP channel keep fraction */
+    uint32_t bits;                        /* q */
+} sol_action_def;
+
+typedef struct {
+    int32_t d_model, n_q_heads, n_kv_heads, head_dim, d_ff, n_layers, vocab;
+    float   rms_eps, rope_theta;
+    int32_t dtype;          /* sol_dtype of weights, activations and caches                      */
+    int32_t max_positions;  /* rotary table length; every L_max must be <= this                  */
+    int32_t page_size;      /* key-selection page size; this build supports 1 (exact top-k)      */
+    int32_t n_sink;         /* always-kept first keys; this build supports 0                     */
+    int32_t n_window;       /* always-kept last keys;  this build supports 0                     */
+    int32_t prune_site;     /* 0 = SiLU(gate)*up intermediate (supported), 1 = MLP input (not)   */
+    uint32_t quant_sites;   /* subset of SOL_QS_ALL_LINEAR_INPUTS                                */
+} sol_model_cfg;
+
+typedef struct {  /* device pointers, element type cfg.dtype */
+    const void *w_in_norm;   /* [d_model]                         */
+    const void *wq;          /* [n_q_heads*head_dim][d_model]     */
+    const void *wk;          /* [n_kv_heads*head_dim][d_model]    */
+    const void *wv;          /* [n_kv_heads*head_dim][d_model]    */
+    const void *wo;          /* [d_model][n_q_heads*head_dim]     */
+    const void *w_post_norm; /* [d_model]                         */
+    const void *w_gate;      /* [d_ff][d_model]                   */
+    const void *w_up;        /* [d_ff][d_model]                   */
+    const void *w_down;      /* [d_model][d_ff]                   */
+} sol_layer_weights;
+
+typedef struct {
+    const void *embed;                /* device [vocab][d_model]; may be NULL if never looked up */
+    const sol_layer_weights *layers;  /* host array of cfg.n_layers entries                      */
+    const void *w_final_norm;         /* device [d_model]                                        */
+    const void *lm_head;              /* device [vocab][d_model]; may alias embed                */
+} sol_model_weights;
+
+typedef enum { SOL_OP_LAYER_FORWARD = 0, SOL_OP_DECODE_STEP = 1, SOL_OP_SCHEDULE_LOGLIK = 2 } sol_op;
+
+typedef struct sol_ctx sol_ctx;
+
+/* Host-only check of a configuration and an action table (no GPU needed).
+ * SOL_ERR_ACTION: a table entry violates the ranges above (e.g. kappa = 0, which would leave a
+ * softmax over no keys). SOL_ERR_UNSUPPORTED: page_size/n_sink/n_window/prune_site/quant_sites
+ * outside what this build implements. SOL_ERR_INVALID_ARG: bad shape. */
+int sol_validate_config(const sol_model_cfg *cfg, const sol_action_def *table, int n_actions);
+
+/* Creates a context on the current HIP device: copies the action table, builds the rotary table
+ * (cos/sin of pos * theta^(-2c/head_dim), computed in double on the host) and uploads both.
+ * The only entry point that allocates device memory. */
+int sol_create(const sol_model_cfg *cfg, const sol_action_def *table, int n_actions, sol_ctx **out);
+void sol_destroy(sol_ctx *ctx);
+/* Text of the last error on this context (or of the last failed sol_create if ctx is NULL). */
+const char *sol_last_error(const sol_ctx *ctx);
+
+/* Bytes of device workspace the operation needs for these sizes (host-only arithmetic).
+ * LAYER_FORWARD: (n_seq, T, L_max). DECODE_STEP: (B, ignored, L_max).
+ * SCHEDULE_LOGLIK: (B*G, T, ignored). Returns 0 for an invalid request. */
+size_t sol_workspace_bytes(const sol_model_cfg *cfg, int op, int n_seq, int T, int L_max);
+
+/* One decoder layer over T tokens per sequence, each under its own action:
+ *   input RMSNorm -> [quant] -> q/k/v projections -> rotary -> K/V written to the cache as
+ *   computed under the token's action (Background, "Decoding is a stateful process") ->
+ *   causal scores over cache positions 0..pos -> keep the ceil(kappa*n) best keys per query head,
+ *   ties to the lower position; budget = all keys bypasses selection (Appendix "Token sparsity
+ *   via Quest", one key per page) -> softmax over kept keys, times V -> [quant] -> output
+ *   projection + residual -> post RMSNorm -> [quant] -> SiLU(gate)*up -> keep the ceil(rho*d_ff)
+ *   largest magnitudes per token, ties to the lower channel (Appendix "Structured MLP activation
+ *   pruning", operator applied at the intermediate) -> [quant] -> down projection + residual.
+ *   [quant] = per-token symmetric fake-quantiser at the token's bit-width (Appendix "Activation
+ *   quantization") at the sites enabled in cfg.quant_sites.
+ * x_in, x_out: device [n_seq][T][d_model] (may not alias). action_ids: device int32 [n_seq][T].
+ * pos0: device int32 [n_seq], tokens already in each sequence's cache (NULL = all zero); token i
+ * sits at position pos0[s]+i. k_cache, v_cache: device, read at [0,pos] and written at
+ * [pos0, pos0+T). workspace: device, >= sol_workspace_bytes(cfg, SOL_OP_LAYER_FORWARD, ...). */
+int sol_layer_forward(sol_ctx *ctx, const sol_layer_weights *w, const void *x_in, void *x_out,
+                      const int32_t *action_ids, const int32_t *pos0,
+                      void *k_cache, void *v_cache, int n_seq, int T, int L_max,
+                      void *workspace, size_t ws_bytes, void *stream);
+
+/* One token per sequence through all cfg.n_layers layers (the decode step). The token's K/V are
+ * appended at cache_len[s] in every layer. Input is token_ids (device int32 [B], looked up in
+ * weights->embed) or, if token_ids is NULL, x_in (device [B][d_model]). action_ids, cache_len:
+ * device int32 [B]. k_cache, v_cache: host arrays of n_layers device pointers.
+ * x_out: device [B][d_model], the last layer's output (before the final norm); may be NULL.
+ * If nll_out (device float [B]) is non-NULL, targets (device int32 [B]) is required and
+ * nll_out[s] = logsumexp(W_lm hf) - (W_lm hf)[target], hf = final RMSNorm (Method, Eq. 1). */
+int sol_decode_step(sol_ctx *ctx, const sol_model_weights *weights,
+                    const int32_t *token_ids, const void *x_in,
+                    const int32_t *action_ids, const int32_t *cache_len,
+                    void *const *k_cache, void *const *v_cache, int B, int L_max,
+                    void *x_out, const int32_t *targets, float *nll_out,
+                    void *workspace, size_t ws_bytes, void *stream);
+
+/* Teacher-forced pass over G compute schedules that share one token path (Method, "GRPO with
+ * per-sequence budget sampling"): for every input b, schedule g and position t,
+ *   nll_out[b][g][t] = -log p_t^{a}(targets[b][t])  in nats (Method, Eq. 1, negated),
+ * the full stack run under action_ids[b][g][.] with the same action in every layer of a step.
+ * tokens, targets: device int32 [B][T]; action_ids: device int32 [B][G][T];
+ * nll_out: device float [B][G][T]. KV caches live in the workspace. */
+int sol_schedule_loglik(sol_ctx *ctx, const sol_model_weights *weights,
+                        const int32_t *tokens, const int32_t *targets, const int32_t *action_ids,
+                        int B, int G, int T, float *nll_out,
+                        void *workspace, size_t ws_bytes, void *stream);
+
+/* Synchronises `stream`, returns and clears the sticky device flags:
+ * SOL_OK, SOL_ERR_ACTION (an action id outside the table was met and treated as dense) or
+ * SOL_ERR_CACHE_OVERFLOW (a sequence was skipped because pos0 + T > L_max). */
+int sol_device_status(sol_ctx *ctx, void *stream);
+
+/* ---- unit hooks: the selection / quantisation device code on caller-supplied fp32 data ----
+ * All pointers device; results are exact integer decisions and must match the definitions
+ * bit for bit. */
+
+/* Row r holds n_cols fp32 scores of which the first n_valid[r] are allowed; keep_out[r][j] = 1
+ * for the k[r] largest allowed scores (ties to the lower j), 0 elsewhere. 1 <= k[r] <= n_valid[r]. */
+int sol_test_topk_select(const float *scores, int rows, int n_cols, const int32_t *n_valid,
+                         const int32_t *k, uint8_t *keep_out, void *stream);
+/* keep_out[r][c] = 1 for the m[r] largest |a[r][c]| (ties to the lower c). */
+int sol_test_prune_mask(const float *a, int rows, int n, const int32_t *m, uint8_t *keep_out,
+                        void *stream);
+/* Per-row fake-quantiser: codes_out[r][j] (int32), scale_out[r], dequantised z_hat_out[r][j].
+ * bits[r] >= 16: codes 0, scale 0, z_hat = z. */
+int sol_test_quant_codes(const float *z, int rows, int n, const int32_t *bits,
+                         int32_t *codes_out, float *scale_out, float *zhat_out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,491 @@
+// Host side of the C ABI: validation, context, workspace carve-up and the launch sequence of the
+// action-conditioned decoder layer, the decode step and the teacher-forced schedule pass.
+#include "../../include/sol.h"
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <string>
+#include <utility>
+#include <vector>
+
+#include "sol_internal.h"
+
+using namespace sol;
+
+struct sol_ctx {
+    sol_model_cfg cfg;
+    int n_actions = 0;
+    int n_buckets = 1;
+    ActionDev *d_table = nullptr;
+    float2 *d_rope = nullptr;
+    int *d_flags = nullptr;
+    std::string err;
+};
+
+static thread_local std::string g_create_err;
+static const int MAX_ACTIONS = 4096;
+
+static int fail(sol_ctx *ctx, int code, const std::string &msg)
+{
+    if (ctx) ctx->err = msg; else g_create_err = msg;
+    return code;
+}
+
+#define SOL_HIP(ctx, call)                                                                            \
+    do {                                                                                              \
+        hipError_t e_ = (call);                                                                       \
+        if (e_ != hipSuccess)                                                                         \
+            return fail(ctx, SOL_ERR_HIP, std::string(#call) + ": " + hipGetErrorString(e_));         \
+    } while (0)
+
+static size_t esize(int dtype) { return dtype == SOL_BF16 ? 2 : 4; }
+
+// ------------------------------------------------------------------------------------------------
+// validation (host only)
+// ------------------------------------------------------------------------------------------------
+static int validate(const sol_model_cfg *c, const sol_action_def *t, int n, std::string &msg)
+{
+    if (!c) { msg = "cfg is NULL"; return SOL_ERR_INVALID_ARG; }
+    if (c->d_model <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->head_dim <= 0 || c->d_ff <= 0 ||
+        c->n_layers <= 0 || c->vocab < 0 || c->max_positions <= 0) {
+        msg = "non-positive model dimension"; return SOL_ERR_INVALID_ARG;
+    }
+    if (c->n_q_heads % c->n_kv_heads) { msg = "n_q_heads must be a multiple of n_kv_heads"; return SOL_ERR_INVALID_ARG; }
+    if (c->head_dim & 1) { msg = "head_dim must be even (rotary pairs)"; return SOL_ERR_INVALID_ARG; }
+    if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) { msg = "bad rms_eps / rope_theta"; return SOL_ERR_INVALID_ARG; }
+    if (c->dtype != SOL_F32 && c->dtype != SOL_BF16) { msg = "dtype must be SOL_F32 or SOL_BF16"; return SOL_ERR_INVALID_ARG; }
+    if (c->page_size < 1 || c->n_sink < 0 || c->n_window < 0) { msg = "bad page_size / n_sink / n_window"; return SOL_ERR_INVALID_ARG; }
+    if (!t || n <= 0) { msg = "empty action table"; return SOL_ERR_INVALID_ARG; }
+    if (n > MAX_ACTIONS) { msg = "more than 4096 actions"; return SOL_ERR_UNSUPPORTED; }
+    for (int a = 0; a < n; ++a) {
+        const sol_action_def &d = t[a];
+        if (d.keep_den == 0 || d.keep_num == 0 || d.keep_num > d.keep_den) {
+            msg = "action " + std::to_string(a) + ": attention keep fraction must be in (0,1]"; return SOL_ERR_ACTION;
+        }
+        if (d.mlp_keep_den == 0 || d.mlp_keep_num == 0 || d.mlp_keep_num > d.mlp_keep_den) {
+            msg = "action " + std::to_string(a) + ": MLP keep fraction must be in (0,1]"; return SOL_ERR_ACTION;
+        }
+        if (d.bits < 4) { msg = "action " + std::to_string(a) + ": bits must be >= 4"; return SOL_ERR_ACTION; }
+    }
+    if (c->page_size != 1) { msg = "page_size > 1 (Quest page bound) is not built"; return SOL_ERR_UNSUPPORTED; }
+    if (c->n_sink != 0 || c->n_window != 0) { msg = "sink / window keys are not built"; return SOL_ERR_UNSUPPORTED; }
+    if (c->prune_site != 0) { msg = "MLP-input prune site is not built"; return SOL_ERR_UNSUPPORTED; }
+    if (c->quant_sites & ~SOL_QS_ALL_LINEAR_INPUTS) { msg = "quant site outside the linear-layer inputs is not built"; return SOL_ERR_UNSUPPORTED; }
+    const int vec = c->dtype == SOL_BF16 ? 8 : 4;
+    const int lpk = c->head_dim / vec;
+    if (c->head_dim % vec || lpk > 64 || (lpk & (lpk - 1))) {
+        msg = "head_dim must be 8*2^k (bf16) or 4*2^k (fp32), at most 512/256"; return SOL_ERR_UNSUPPORTED;
+    }
+    return SOL_OK;
+}
+
+extern "C" int sol_validate_config(const sol_model_cfg *cfg, const sol_action_def *table, int n_actions)
+{
+    std::string msg;
+    const int rc = validate(cfg, table, n_actions, msg);
+    if (rc) g_create_err = msg;
+    return rc;
+}
+
+extern "C" const char *sol_last_error(const sol_ctx *ctx) { return ctx ? ctx->err.c_str() : g_create_err.c_str(); }
+
+// ------------------------------------------------------------------------------------------------
+// context
+// ------------------------------------------------------------------------------------------------
+extern "C" int sol_create(const sol_model_cfg *cfg, const sol_action_def *table, int n_actions, sol_ctx **out)
+{
+    if (!out) return fail(nullptr, SOL_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    std::string msg;
+    int rc = validate(cfg, table, n_actions, msg);
+    if (rc) return fail(nullptr, rc, msg);
+    sol_ctx *ctx = new sol_ctx();
+    ctx->cfg = *cfg;
+    ctx->n_actions = n_actions;
+    // MLP buckets: actions that share (kept channels, effective bit-width) share a bucket
+    std::vector<ActionDev> host(n_actions);
+    std::map<std::pair<int64_t, int>, int> bucket_of;
+    const bool q_down = (cfg->quant_sites & SOL_QS_DOWN_IN) != 0;
+    for (int a = 0; a < n_actions; ++a) {
+        const sol_action_def &d = table[a];
+        uint64_t m = ((uint64_t)d.mlp_keep_num * (uint64_t)cfg->d_ff + d.mlp_keep_den - 1) / d.mlp_keep_den;
+        if (m < 1) m = 1;
+        if (m > (uint64_t)cfg->d_ff) m = (uint64_t)cfg->d_ff;
+        const int b_eff = (!q_down || d.bits >= 16) ? 16 : (int)d.bits;
+        bucket_of.emplace(std::make_pair(-(int64_t)m, -b_eff), 0);   // dense-most bucket first
+    }
+    int nb = 0;
+    for (auto &kv : bucket_of) kv.second = nb++;
+    ctx->n_buckets = nb;
+    for (int a = 0; a < n_actions; ++a) {
+        const sol_action_def &d = table[a];
+        uint64_t m = ((uint64_t)d.mlp_keep_num * (uint64_t)cfg->d_ff + d.mlp_keep_den - 1) / d.mlp_keep_den;
+        if (m < 1) m = 1;
+        if (m > (uint64_t)cfg->d_ff) m = (uint64_t)cfg->d_ff;
+        const int b_eff = (!q_down || d.bits >= 16) ? 16 : (int)d.bits;
+        host[a] = ActionDev{d.keep_num, d.keep_den, d.mlp_keep_num, d.mlp_keep_den, d.bits,
+                            bucket_of[std::make_pair(-(int64_t)m, -b_eff)]};
+    }
+    // rotary table: cos/sin(pos * theta^(-2c/dh)), double precision on the host
+    const int half = cfg->head_dim / 2;
+    std::vector<float2> rope((size_t)cfg->max_positions * half);
+    for (int c = 0; c < half; ++c) {
+        const double inv_freq = std::pow((double)cfg->rope_theta, -2.0 * (double)c / (double)cfg->head_dim);
+        for (int p = 0; p < cfg->max_positions; ++p) {
+            const double ang = (double)p * inv_freq;
+            rope[(size_t)p * half + c] = make_float2((float)std::cos(ang), (float)std::sin(ang));
+        }
+    }
+    auto cleanup = [&](int code, const std::string &m2) {
+        if (ctx->d_table) (void)hipFree(ctx->d_table);
+        if (ctx->d_rope) (void)hipFree(ctx->d_rope);
+        if (ctx->d_flags) (void)hipFree(ctx->d_flags);
+        delete ctx;
+        return fail(nullptr, code, m2);
+    };
+    hipError_t e;
+    if ((e = hipMalloc((void **)&ctx->d_table, sizeof(ActionDev) * n_actions)) != hipSuccess)
+        return cleanup(SOL_ERR_HIP, std::string("hipMalloc(table): ") + hipGetErrorString(e));
+    if ((e = hipMalloc((void **)&ctx->d_rope, sizeof(float2) * rope.size())) != hipSuccess)
+        return cleanup(SOL_ERR_HIP, std::string("hipMalloc(rope): ") + hipGetErrorString(e));
+    if ((e = hipMalloc((void **)&ctx->d_flags, 256)) != hipSuccess)
+        return cleanup(SOL_ERR_HIP, std::string("hipMalloc(flags): ") + hipGetErrorString(e));
+    if ((e = hipMemcpy(ctx->d_table, host.data(), sizeof(ActionDev) * n_actions, hipMemcpyHostToDevice)) != hipSuccess ||
+        (e = hipMemcpy(ctx->d_rope, rope.data(), sizeof(float2) * rope.size(), hipMemcpyHostToDevice)) != hipSuccess ||
+        (e = hipMemset(ctx->d_flags, 0, 256)) != hipSuccess)
+        return cleanup(SOL_ERR_HIP, std::string("upload: ") + hipGetErrorString(e));
+    *out = ctx;
+    return SOL_OK;
+}
+
+extern "C" void sol_destroy(sol_ctx *ctx)
+{
+    if (!ctx) return;
+    (void)hipFree(ctx->d_table);
+    (void)hipFree(ctx->d_rope);
+    (void)hipFree(ctx->d_flags);
+    delete ctx;
+}
+
+extern "C" int sol_device_status(sol_ctx *ctx, void *stream)
+{
+    if (!ctx) return SOL_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    SOL_HIP(ctx, hipStreamSynchronize(st));
+    int f = 0;
+    SOL_HIP(ctx, hipMemcpy(&f, ctx->d_flags, sizeof(int), hipMemcpyDeviceToHost));
+    if (f) SOL_HIP(ctx, hipMemset(ctx->d_flags, 0, sizeof(int)));
+    if (f & FLAG_CACHE_OVERFLOW) return fail(ctx, SOL_ERR_CACHE_OVERFLOW, "a sequence's tokens did not fit its cache and were skipped");
+    if (f & FLAG_BAD_ACTION) return fail(ctx, SOL_ERR_ACTION, "an action id outside the table was treated as the dense action");
+    return SOL_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// workspace
+// ------------------------------------------------------------------------------------------------
+struct Carver {
+    char *base;
+    size_t off = 0;
+    explicit Carver(void *b) : base((char *)b) {}
+    void *take(size_t bytes)
+    {
+        off = (off + 255) & ~(size_t)255;
+        void *p = base ? base + off : nullptr;
+        off += bytes;
+        return p;
+    }
+};
+
+struct LayerWs {
+    RowAct *ra; int32_t *row_bucket, *perm, *bucket_off;
+    void *h, *qb, *a;
+    float *big32, *o32, *x2;
+};
+
+static void carve_layer(Carver &c, const sol_model_cfg &g, int64_t M, LayerWs &w)
+{
+    const size_t es = esize(g.dtype);
+    const int64_t nq = (int64_t)g.n_q_heads * g.head_dim, nkv = (int64_t)g.n_kv_heads * g.head_dim;
+    int64_t wide = nq + 2 * nkv;
+    if (2 * (int64_t)g.d_ff > wide) wide = 2 * (int64_t)g.d_ff;
+    if (g.d_model > wide) wide = g.d_model;
+    w.ra = (RowAct *)c.take(sizeof(RowAct) * M);
+    w.row_bucket = (int32_t *)c.take(4 * M);
+    w.perm = (int32_t *)c.take(4 * M);
+    w.bucket_off = (int32_t *)c.take(4 * (MAX_ACTIONS + 1));
+    w.h = c.take(es * M * g.d_model);
+    w.qb = c.take(es * M * nq);
+    w.a = c.take(es * M * g.d_ff);
+    w.big32 = (float *)c.take(4 * M * wide);
+    w.o32 = (float *)c.take(4 * M * nq);
+    w.x2 = (float *)c.take(4 * M * g.d_model);
+}
+
+static int64_t lm_chunk_rows(const sol_model_cfg &g, int64_t M)
+{
+    int64_t rows = (int64_t)(256u << 20) / (4 * (int64_t)(g.vocab > 0 ? g.vocab : 1));
+    if (rows < 64) rows = 64;
+    return rows < M ? rows : M;
+}
+
+struct StackWs {
+    LayerWs layer;
+    void *xa, *xb, *hf, *kc, *vc;
+    float *logits;
+};
+
+static void carve_stack(Carver &c, const sol_model_cfg &g, int64_t n_seq, int64_t T, bool own_cache, StackWs &w)
+{
+    const size_t es = esize(g.dtype);
+    const int64_t M = n_seq * T;
+    carve_layer(c, g, M, w.layer);
+    w.xa = c.take(es * M * g.d_model);
+    w.xb = c.take(es * M * g.d_model);
+    w.hf = c.take(es * M * g.d_model);
+    const size_t cache = own_cache ? es * n_seq * g.n_kv_heads * T * g.head_dim : 0;
+    w.kc = c.take(cache);
+    w.vc = c.take(cache);
+    w.logits = (float *)c.take(4 * lm_chunk_rows(g, M) * (size_t)(g.vocab > 0 ? g.vocab : 1));
+}
+
+extern "C" size_t sol_workspace_bytes(const sol_model_cfg *cfg, int op, int n_seq, int T, int L_max)
+{
+    (void)L_max;
+    if (!cfg || n_seq <= 0) return 0;
+    Carver c(nullptr);
+    if (op == SOL_OP_LAYER_FORWARD) {
+        if (T <= 0) return 0;
+        LayerWs w; carve_layer(c, *cfg, (int64_t)n_seq * T, w);
+    } else if (op == SOL_OP_DECODE_STEP) {
+        StackWs w; carve_stack(c, *cfg, n_seq, 1, false, w);
+    } else if (op == SOL_OP_SCHEDULE_LOGLIK) {
+        if (T <= 0) return 0;
+        StackWs w; carve_stack(c, *cfg, n_seq, T, true, w);
+    } else return 0;
+    return c.off + 256;
+}
+
+// ------------------------------------------------------------------------------------------------
+// the layer
+// ------------------------------------------------------------------------------------------------
+static void prepare_actions(sol_ctx *ctx, const int32_t *ids, int64_t M, LayerWs &w, hipStream_t st)
+{
+    launch_prepare_rows(ids, ctx->d_table, ctx->n_actions, ctx->cfg.d_ff, M, w.ra, w.row_bucket, ctx->d_flags, st);
+    launch_bucket_sort(w.row_bucket, M, ctx->n_buckets, w.perm, w.bucket_off, st);
+}
+
+// Launch sequence of one decoder layer (actions already decoded into w.ra / w.perm).
+static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_in, void *x_out, const int32_t *pos0,
+                      void *kc, void *vc, int n_seq, int T, int L_max, LayerWs &w, hipStream_t st)
+{
+    const sol_model_cfg &g = ctx->cfg;
+    const int dt = g.dtype;
+    const int64_t M = (int64_t)n_seq * T;
+    const int d = g.d_model, Hq = g.n_q_heads, Hkv = g.n_kv_heads, dh = g.head_dim, dff = g.d_ff;
+    const int nq = Hq * dh, nkv = Hkv * dh, nqkv = nq + 2 * nkv;
+    const uint32_t qs = g.quant_sites;
+
+    // input norm + quantise (linear-input site of q/k/v)
+    launch_rmsnorm_fq(x_in, dt, nullptr, nullptr, lw->w_in_norm, dt, w.h, dt, w.ra, qs & SOL_QS_QKV_IN, M, d, g.rms_eps, st);
+    // q/k/v projections, rotary, cache write
+    launch_gemm_generic(w.h, dt, d, lw->wq, dt, d, w.big32, nqkv, M, nq, d, st);
+    launch_gemm_generic(w.h, dt, d, lw->wk, dt, d, w.big32 + nq, nqkv, M, nkv, d, st);
+    launch_gemm_generic(w.h, dt, d, lw->wv, dt, d, w.big32 + nq + nkv, nqkv, M, nkv, d, st);
+    launch_rope_store(w.big32, w.qb, kc, vc, dt, ctx->d_rope, pos0, n_seq, T, L_max, Hq, Hkv, dh, ctx->d_flags, st);
+    // scores, budgeted selection, softmax over kept keys, times V
+    if (!launch_attn_rows(w.qb, kc, vc, dt, w.o32, w.ra, pos0, n_seq, T, L_max, Hq, Hkv, dh, ctx->d_flags, st))
+        return fail(ctx, SOL_ERR_UNSUPPORTED, "attention: L_max too long for the on-chip score rows of this build");
+    // quantise (o-proj input), output projection, residual
+    launch_fq_rows(w.o32, w.qb, dt, w.ra, qs & SOL_QS_O_IN, M, nq, st);
+    launch_gemm_generic(w.qb, dt, nq, lw->wo, dt, nq, w.big32, d, M, d, nq, st);
+    // x2 = x + attn ; post norm + quantise (gate/up input)
+    launch_rmsnorm_fq(x_in, dt, w.big32, w.x2, lw->w_post_norm, dt, w.h, dt, w.ra, qs & SOL_QS_GATEUP_IN, M, d, g.rms_eps, st);
+    // gate / up, SiLU(gate)*up
+    launch_gemm_generic(w.h, dt, d, lw->w_gate, dt, d, w.big32, 2 * (int64_t)dff, M, dff, d, st);
+    launch_gemm_generic(w.h, dt, d, lw->w_up, dt, d, w.big32 + dff, 2 * (int64_t)dff, M, dff, d, st);
+    launch_silu_mul(w.big32, w.a, dt, M, dff, st);
+    // magnitude pruning + quantise (down input), rows visited in bucket order
+    launch_prune_fq(w.a, dt, w.ra, w.perm, qs & SOL_QS_DOWN_IN, M, dff, st);
+    // down projection + residual
+    launch_gemm_generic(w.a, dt, dff, lw->w_down, dt, dff, w.big32, d, M, d, dff, st);
+    launch_resid_out(w.x2, w.big32, x_out, dt, M, d, st);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(ctx, SOL_ERR_HIP, std::string("kernel launch: ") + hipGetErrorString(e));
+    return SOL_OK;
+}
+
+static int check_layer_weights(sol_ctx *ctx, const sol_layer_weights *w)
+{
+    if (!w || !w->w_in_norm || !w->wq || !w->wk || !w->wv || !w->wo || !w->w_post_norm || !w->w_gate || !w->w_up ||
+        !w->w_down)
+        return fail(ctx, SOL_ERR_INVALID_ARG, "a layer weight pointer is NULL");
+    return SOL_OK;
+}
+
+extern "C" int sol_layer_forward(sol_ctx *ctx, const sol_layer_weights *w, const void *x_in, void *x_out,
+                                 const int32_t *action_ids, const int32_t *pos0, void *k_cache, void *v_cache,
+                                 int n_seq, int T, int L_max, void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!ctx) return SOL_ERR_INVALID_ARG;
+    if (n_seq < 0 || T < 0 || L_max <= 0) return fail(ctx, SOL_ERR_INVALID_ARG, "negative size");
+    if (n_seq == 0 || T == 0) return SOL_OK;                        // empty batch: nothing to do
+    if (int rc = check_layer_weights(ctx, w)) return rc;
+    if (!x_in || !x_out || !action_ids || !k_cache || !v_cache) return fail(ctx, SOL_ERR_INVALID_ARG, "a data pointer is NULL");
+    if (x_in == x_out) return fail(ctx, SOL_ERR_INVALID_ARG, "x_in and x_out must not alias");
+    if (L_max > ctx->cfg.max_positions) return fail(ctx, SOL_ERR_INVALID_ARG, "L_max exceeds cfg.max_positions");
+    if (T > L_max) return fail(ctx, SOL_ERR_CACHE_OVERFLOW, "T tokens cannot fit a cache of L_max positions");
+    const size_t need = sol_workspace_bytes(&ctx->cfg, SOL_OP_LAYER_FORWARD, n_seq, T, L_max);
+    if (!workspace || ws_bytes < need)
+        return fail(ctx, SOL_ERR_WORKSPACE, "workspace too small: need " + std::to_string(need) + " bytes");
+    hipStream_t st = (hipStream_t)stream;
+    Carver c(workspace);
+    LayerWs lw; carve_layer(c, ctx->cfg, (int64_t)n_seq * T, lw);
+    prepare_actions(ctx, action_ids, (int64_t)n_seq * T, lw, st);
+    return layer_impl(ctx, w, x_in, x_out, pos0, k_cache, v_cache, n_seq, T, L_max, lw, st);
+}
+
+// ------------------------------------------------------------------------------------------------
+// final norm + LM head + NLL
+// ------------------------------------------------------------------------------------------------
+static int nll_impl(sol_ctx *ctx, const sol_model_weights *mw, const void *x, int64_t M, StackWs &w,
+                    const int32_t *targets, int G, int T, bool broadcast_g, float *nll_out, hipStream_t st)
+{
+    const sol_model_cfg &g = ctx->cfg;
+    const int dt = g.dtype;
+    launch_rmsnorm_fq(x, dt, nullptr, nullptr, mw->w_final_norm, dt, w.hf, dt, nullptr, false, M, g.d_model, g.rms_eps, st);
+    const int64_t chunk = lm_chunk_rows(g, M);
+    const size_t es = esize(dt);
+    for (int64_t r0 = 0; r0 < M; r0 += chunk) {
+        const int64_t rows = (M - r0 < chunk) ? M - r0 : chunk;
+        launch_gemm_generic((const char *)w.hf + es * r0 * g.d_model, dt, g.d_model, mw->lm_head, dt, g.d_model,
+                            w.logits, g.vocab, rows, g.vocab, g.d_model, st);
+        launch_nll_rows(w.logits, rows, g.vocab, targets, r0, G, T, broadcast_g, nll_out, st);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(ctx, SOL_ERR_HIP, std::string("kernel launch: ") + hipGetErrorString(e));
+    return SOL_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// decode step
+// ------------------------------------------------------------------------------------------------
+extern "C" int sol_decode_step(sol_ctx *ctx, const sol_model_weights *mw, const int32_t *token_ids, const void *x_in,
+                               const int32_t *action_ids, const int32_t *cache_len, void *const *k_cache,
+                               void *const *v_cache, int B, int L_max, void *x_out, const int32_t *targets,
+                               float *nll_out, void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!ctx) return SOL_ERR_INVALID_ARG;
+    const sol_model_cfg &g = ctx->cfg;
+    if (!mw || !mw->layers) return fail(ctx, SOL_ERR_INVALID_ARG, "weights are NULL");
+    for (int l = 0; l < g.n_layers; ++l)
+        if (int rc = check_layer_weights(ctx, &mw->layers[l])) return rc;
+    if (!token_ids && !x_in) return fail(ctx, SOL_ERR_INVALID_ARG, "token_ids and x_in are both NULL");
+    if (token_ids && !mw->embed) return fail(ctx, SOL_ERR_INVALID_ARG, "token_ids given but weights->embed is NULL");
+    if (!action_ids || !cache_len || !k_cache || !v_cache) return fail(ctx, SOL_ERR_INVALID_ARG, "a data pointer is NULL");
+    for (int l = 0; l < g.n_layers; ++l)
+        if (!k_cache[l] || !v_cache[l]) return fail(ctx, SOL_ERR_INVALID_ARG, "a per-layer cache pointer is NULL");
+    if (nll_out && (!targets || !mw->w_final_norm || !mw->lm_head || g.vocab <= 0))
+        return fail(ctx, SOL_ERR_INVALID_ARG, "nll_out needs targets, w_final_norm, lm_head and vocab > 0");
+    if (B < 0 || L_max <= 0) return fail(ctx, SOL_ERR_INVALID_ARG, "negative size");
+    if (L_max > g.max_positions) return fail(ctx, SOL_ERR_INVALID_ARG, "L_max exceeds cfg.max_positions");
+    if (B == 0) return SOL_OK;
+    const size_t need = sol_workspace_bytes(&g, SOL_OP_DECODE_STEP, B, 1, L_max);
+    if (!workspace || ws_bytes < need)
+        return fail(ctx, SOL_ERR_WORKSPACE, "workspace too small: need " + std::to_string(need) + " bytes");
+    hipStream_t st = (hipStream_t)stream;
+    Carver c(workspace);
+    StackWs w; carve_stack(c, g, B, 1, false, w);
+    prepare_actions(ctx, action_ids, B, w.layer, st);
+    const void *cur = x_in;
+    if (token_ids) {
+        launch_embed(mw->embed, token_ids, w.hf, g.dtype, B, 1, 1, g.d_model, g.vocab, st);
+        cur = w.hf;
+    }
+    for (int l = 0; l < g.n_layers; ++l) {
+        void *dst = (l & 1) ? w.xb : w.xa;
+        if (l == g.n_layers - 1 && x_out) dst = x_out;
+        if (dst == cur) return fail(ctx, SOL_ERR_INVALID_ARG, "x_in and x_out must not alias");
+        if (int rc = layer_impl(ctx, &mw->layers[l], cur, dst, cache_len, k_cache[l], v_cache[l], B, 1, L_max, w.layer, st))
+            return rc;
+        cur = dst;
+    }
+    if (nll_out) return nll_impl(ctx, mw, cur, B, w, targets, 1, 1, false, nll_out, st);
+    return SOL_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// teacher-forced pass over G schedules
+// ------------------------------------------------------------------------------------------------
+extern "C" int sol_schedule_loglik(sol_ctx *ctx, const sol_model_weights *mw, const int32_t *tokens,
+                                   const int32_t *targets, const int32_t *action_ids, int B, int G, int T,
+                                   float *nll_out, void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!ctx) return SOL_ERR_INVALID_ARG;
+    const sol_model_cfg &g = ctx->cfg;
+    if (!mw || !mw->layers || !mw->embed || !mw->w_final_norm || !mw->lm_head)
+        return fail(ctx, SOL_ERR_INVALID_ARG, "weights are NULL");
+    for (int l = 0; l < g.n_layers; ++l)
+        if (int rc = check_layer_weights(ctx, &mw->layers[l])) return rc;
+    if (!tokens || !targets || !action_ids || !nll_out) return fail(ctx, SOL_ERR_INVALID_ARG, "a data pointer is NULL");
+    if (B < 0 || G < 0 || T < 0) return fail(ctx, SOL_ERR_INVALID_ARG, "negative size");
+    if (g.vocab <= 0) return fail(ctx, SOL_ERR_INVALID_ARG, "vocab must be positive");
+    if (T > g.max_positions) return fail(ctx, SOL_ERR_INVALID_ARG, "T exceeds cfg.max_positions");
+    if ((int64_t)B * G * T == 0) return SOL_OK;
+    const int N = B * G;
+    const size_t need = sol_workspace_bytes(&g, SOL_OP_SCHEDULE_LOGLIK, N, T, T);
+    if (!workspace || ws_bytes < need)
+        return fail(ctx, SOL_ERR_WORKSPACE, "workspace too small: need " + std::to_string(need) + " bytes");
+    hipStream_t st = (hipStream_t)stream;
+    Carver c(workspace);
+    StackWs w; carve_stack(c, g, N, T, true, w);
+    const int64_t M = (int64_t)N * T;
+    prepare_actions(ctx, action_ids, M, w.layer, st);          // one plan, reused by every layer
+    launch_embed(mw->embed, tokens, w.xa, g.dtype, B, G, T, g.d_model, g.vocab, st);
+    void *cur = w.xa, *nxt = w.xb;
+    for (int l = 0; l < g.n_layers; ++l) {
+        if (int rc = layer_impl(ctx, &mw->layers[l], cur, nxt, nullptr, w.kc, w.vc, N, T, T, w.layer, st)) return rc;
+        std::swap(cur, nxt);
+    }
+    return nll_impl(ctx, mw, cur, M, w, targets, G, T, true, nll_out, st);
+}
+
+// ------------------------------------------------------------------------------------------------
+// unit hooks
+// ------------------------------------------------------------------------------------------------
+static int launch_status()
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { g_create_err = std::string("kernel launch: ") + hipGetErrorString(e); return SOL_ERR_HIP; }
+    return SOL_OK;
+}
+
+extern "C" int sol_test_topk_select(const float *scores, int rows, int n_cols, const int32_t *n_valid, const int32_t *k,
+                                    uint8_t *keep_out, void *stream)
+{
+    if (rows < 0 || n_cols < 0) return SOL_ERR_INVALID_ARG;
+    if (rows == 0 || n_cols == 0) return SOL_OK;
+    if (!scores || !n_valid || !k || !keep_out) return SOL_ERR_INVALID_ARG;
+    launch_test_topk(scores, rows, n_cols, n_valid, k, keep_out, (hipStream_t)stream);
+    return launch_status();
+}
+
+extern "C" int sol_test_prune_mask(const float *a, int rows, int n, const int32_t *m, uint8_t *keep_out, void *stream)
+{
+    if (rows < 0 || n < 0) return SOL_ERR_INVALID_ARG;
+    if (rows == 0 || n == 0) return SOL_OK;
+    if (!a || !m || !keep_out) return SOL_ERR_INVALID_ARG;
+    launch_test_prune(a, rows, n, m, keep_out, (hipStream_t)stream);
+    return launch_status();
+}
+
+extern "C" int sol_test_quant_codes(const float *z, int rows, int n, const int32_t *bits, int32_t *codes_out,
+                                    float *scale_out, float *zhat_out, void *stream)
+{
+    if (rows < 0 || n < 0) return SOL_ERR_INVALID_ARG;
+    if (rows == 0 || n == 0) return SOL_OK;
+    if (!z || !bits || !codes_out || !scale_out || !zhat_out) return SOL_ERR_INVALID_ARG;
+    launch_test_quant(z, rows, n, bits, codes_out, scale_out, zhat_out, (hipStream_t)stream);
+    return launch_status();
+}

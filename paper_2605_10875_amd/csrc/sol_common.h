@@ -1,0 +1,242 @@
+// Device-side helpers shared by the gfx950 kernels: bf16 <-> fp32, element I/O, wave / block
+// reductions, exact k-th-largest selection (radix select on order-preserving keys) and the
+// per-token fake-quantiser.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sol {
+
+typedef uint16_t bf16_t;   // raw bfloat16 bits
+
+// Per-row decoded action (one 16-byte load per kernel that needs it).
+struct RowAct {
+    uint32_t keep_num, keep_den;  // attention keep fraction
+    int32_t  m;                   // MLP channels kept = ceil(rho * d_ff), in [1, d_ff]
+    int32_t  bits;                // activation bit-width; >= 16 bypasses the quantiser
+};
+
+enum { FLAG_BAD_ACTION = 1, FLAG_CACHE_OVERFLOW = 2 };
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// round to nearest, ties to even
+__device__ __forceinline__ bf16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7F800000u) == 0x7F800000u)
+        return (bf16_t)((u >> 16) | ((u & 0x007FFFFFu) ? 0x0040u : 0u));
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float ld(const float *p) { return *p; }
+__device__ __forceinline__ float ld(const bf16_t *p) { return bf16_to_f32(*p); }
+__device__ __forceinline__ void st(float *p, float v) { *p = v; }
+__device__ __forceinline__ void st(bf16_t *p, float v) { *p = f32_to_bf16(v); }
+// value after a round trip through the storage type
+__device__ __forceinline__ float rnd(float v, const float *) { return v; }
+__device__ __forceinline__ float rnd(float v, const bf16_t *) { return bf16_to_f32(f32_to_bf16(v)); }
+
+// 16-byte vector of elements: 4 floats or 8 bf16
+template <typename T> struct Vec16;
+template <> struct Vec16<float> {
+    static constexpr int N = 4;
+    float4 raw;
+    __device__ __forceinline__ void load(const float *p) { raw = *reinterpret_cast<const float4 *>(p); }
+    __device__ __forceinline__ void store(float *p) const { *reinterpret_cast<float4 *>(p) = raw; }
+    __device__ __forceinline__ float get(int i) const { return i == 0 ? raw.x : i == 1 ? raw.y : i == 2 ? raw.z : raw.w; }
+    __device__ __forceinline__ void unpack(float *f) const { f[0] = raw.x; f[1] = raw.y; f[2] = raw.z; f[3] = raw.w; }
+    __device__ __forceinline__ void pack(const float *f) { raw = make_float4(f[0], f[1], f[2], f[3]); }
+};
+template <> struct Vec16<bf16_t> {
+    static constexpr int N = 8;
+    uint4 raw;
+    __device__ __forceinline__ void load(const bf16_t *p) { raw = *reinterpret_cast<const uint4 *>(p); }
+    __device__ __forceinline__ void store(bf16_t *p) const { *reinterpret_cast<uint4 *>(p) = raw; }
+    __device__ __forceinline__ void unpack(float *f) const
+    {
+        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            f[2 * i]     = __uint_as_float(w[i] << 16);
+            f[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+        }
+    }
+    __device__ __forceinline__ void pack(const float *f)
+    {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            w[i] = (uint32_t)f32_to_bf16(f[2 * i]) | ((uint32_t)f32_to_bf16(f[2 * i + 1]) << 16);
+        raw = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+};
+
+// ---- reductions (fixed shuffle pattern => deterministic) -----------------------------------
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ __forceinline__ int wave_sum_i(int v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// Block-wide sum / max. `red` is LDS scratch of at least BLOCK/64 floats. All threads get the
+// result. Contains two barriers, so `red` may be reused right after the call.
+template <int BLOCK> __device__ __forceinline__ float block_sum(float v, float *red)
+{
+    v = wave_sum(v);
+    const int w = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) red[w] = v;
+    __syncthreads();
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < BLOCK / 64; ++i) t += red[i];
+    __syncthreads();
+    return t;
+}
+template <int BLOCK> __device__ __forceinline__ float block_max(float v, float *red)
+{
+    v = wave_max(v);
+    const int w = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) red[w] = v;
+    __syncthreads();
+    float t = red[0];
+#pragma unroll
+    for (int i = 1; i < BLOCK / 64; ++i) t = fmaxf(t, red[i]);
+    __syncthreads();
+    return t;
+}
+
+// ---- order-preserving integer keys ----------------------------------------------------------
+// float -> uint32 such that a < b  <=>  key(a) < key(b)   (-0 and +0 map to neighbouring keys;
+// scores are compared as IEEE values by the definition, so fold -0 into +0 first)
+__device__ __forceinline__ uint32_t score_key(float s)
+{
+    uint32_t u = __float_as_uint(s + 0.0f);      // -0 + 0 = +0
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+// |a| as key: non-negative floats order like their bit patterns
+__device__ __forceinline__ uint32_t mag_key(float a) { return __float_as_uint(a) & 0x7FFFFFFFu; }
+
+// ---- exact k-th largest of n keys -----------------------------------------------------------
+// keyfn(i) yields key i (i in [0,n)). 1 <= k <= n. On return (uniform across the block):
+//   thr   = the k-th largest key,
+//   quota = how many of the keys equal to thr belong to the k largest (>= 1),
+//   n_eq  = how many keys equal thr in total.
+// hist: LDS int[256]; sh: LDS int[4]. Every thread of the block must call it.
+template <int BLOCK, typename KeyFn>
+__device__ __forceinline__ void block_radix_select(KeyFn keyfn, int n, int k, int *hist, int *sh,
+                                                   uint32_t &thr, int &quota, int &n_eq)
+{
+    const int tid = threadIdx.x;
+    uint32_t prefix = 0, mask = 0;
+    int remaining = k;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        for (int i = tid; i < 256; i += BLOCK) hist[i] = 0;
+        __syncthreads();
+        for (int i = tid; i < n; i += BLOCK) {
+            const uint32_t u = keyfn(i);
+            if ((u & mask) == prefix) atomicAdd(&hist[(u >> shift) & 255u], 1);
+        }
+        __syncthreads();
+        if (tid < 64) {
+            // lane l owns bins 255-4l .. 252-4l; scan from the largest digit downwards
+            const int b0 = 255 - 4 * tid;
+            const int c0 = hist[b0], c1 = hist[b0 - 1], c2 = hist[b0 - 2], c3 = hist[b0 - 3];
+            const int s = c0 + c1 + c2 + c3;
+            int incl = s;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int t = __shfl_up(incl, o, 64);
+                if (tid >= o) incl += t;
+            }
+            const int excl = incl - s;
+            if (excl < remaining && remaining <= incl) {
+                const int r = remaining - excl;
+                int bin, above, cnt;
+                if (r <= c0) { bin = b0; above = 0; cnt = c0; }
+                else if (r <= c0 + c1) { bin = b0 - 1; above = c0; cnt = c1; }
+                else if (r <= c0 + c1 + c2) { bin = b0 - 2; above = c0 + c1; cnt = c2; }
+                else { bin = b0 - 3; above = c0 + c1 + c2; cnt = c3; }
+                sh[0] = bin;
+                sh[1] = r - above;
+                sh[2] = cnt;
+            }
+        }
+        __syncthreads();
+        prefix |= ((uint32_t)sh[0]) << shift;
+        mask |= 0xFFu << shift;
+        remaining = sh[1];
+        n_eq = sh[2];
+        __syncthreads();
+    }
+    thr = prefix;
+    quota = remaining;
+}
+
+// Among the keys equal to thr, the `quota` of lowest index win. Returns the largest index J such
+// that exactly `quota` keys equal to thr have index <= J (uniform across the block).
+// Only needed when quota < n_eq. wcnt: LDS int[BLOCK/64]; sh: LDS int[4].
+template <int BLOCK, typename KeyFn>
+__device__ __forceinline__ int block_tie_cutoff(KeyFn keyfn, int n, uint32_t thr, int quota, int *wcnt, int *sh)
+{
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    int taken = 0;
+    if (tid == 0) sh[3] = n - 1;
+    __syncthreads();
+    for (int base = 0; base < n; base += BLOCK) {
+        const int i = base + tid;
+        const bool tie = (i < n) && (keyfn(i) == thr);
+        const unsigned long long bal = __ballot(tie);
+        const int before = __popcll(bal & ((1ull << lane) - 1ull));
+        if (lane == 0) wcnt[w] = __popcll(bal);
+        __syncthreads();
+        int wave_off = 0, total = 0;
+#pragma unroll
+        for (int j = 0; j < BLOCK / 64; ++j) {
+            const int c = wcnt[j];
+            if (j < w) wave_off += c;
+            total += c;
+        }
+        if (tie && taken + wave_off + before + 1 == quota) sh[3] = i;
+        __syncthreads();
+        taken += total;
+        if (taken >= quota) break;     // uniform
+    }
+    __syncthreads();
+    return sh[3];
+}
+
+// ---- per-token symmetric fake-quantiser ------------------------------------------------------
+// q_max = 2^(bits-1)-1, s = absmax / q_max, z_hat = clamp(rint(z / s), -q_max, q_max) * s,
+// all in IEEE fp32 (true division, round half to even).
+__device__ __forceinline__ float fq_qmax(int bits) { return (float)((1 << (bits - 1)) - 1); }
+__device__ __forceinline__ float fq_code(float z, float s, float qmax)
+{
+    float c = rintf(z / s);
+    c = fminf(fmaxf(c, -qmax), qmax);
+    return c;
+}
+
+__device__ __forceinline__ int budget_ceil(uint32_t num, uint32_t den, int n)
+{
+    unsigned long long b = ((unsigned long long)num * (unsigned long long)n + den - 1ull) / den;
+    if (b < 1ull) b = 1ull;
+    if (b > (unsigned long long)n) b = (unsigned long long)n;
+    return (int)b;
+}
+
+}  // namespace sol

@@ -1,0 +1,72 @@
+// Host-visible launchers of the gfx950 kernels. Every launcher only enqueues work on `stream`.
+// T-typed pointers are passed as void* with a dtype tag (0 = fp32, 1 = bf16).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "sol_common.h"
+
+namespace sol {
+
+struct ActionDev {  // device copy of one action-table row, with the MLP bucket it belongs to
+    uint32_t keep_num, keep_den, mlp_keep_num, mlp_keep_den, bits;
+    int32_t  bucket;
+};
+
+// ---- rows (sol_rows.hip) ---------------------------------------------------------------------
+// Decodes action ids into RowAct (invalid id => dense action + FLAG_BAD_ACTION) and writes each
+// row's MLP bucket.
+void launch_prepare_rows(const int32_t *action_ids, const ActionDev *table, int n_actions, int d_ff,
+                         int64_t M, RowAct *ra, int32_t *row_bucket, int *flags, hipStream_t st);
+// Stable counting sort of rows by bucket: perm[slot] = row, bucket_off[b] = first slot of bucket b
+// (n_buckets + 1 entries).
+void launch_bucket_sort(const int32_t *row_bucket, int64_t M, int n_buckets, int32_t *perm,
+                        int32_t *bucket_off, hipStream_t st);
+// h = FQ(RMSNorm(x [+ add]) * w, bits) ; optionally writes xsum = x + add (fp32).
+// x: [M][d] of x_dtype; add: fp32 [M][d] or NULL; ra NULL or quant disabled => no quantiser.
+void launch_rmsnorm_fq(const void *x, int x_dtype, const float *add, float *xsum, const void *w, int w_dtype,
+                       void *h, int h_dtype, const RowAct *ra, bool quant, int64_t M, int d, float eps,
+                       hipStream_t st);
+// out = FQ(in, bits) row-wise; in fp32 [M][n] -> out dtype.
+void launch_fq_rows(const float *in, void *out, int out_dtype, const RowAct *ra, bool quant, int64_t M, int n,
+                    hipStream_t st);
+// rotary + scatter: qkv32 [M][(Hq+2Hkv)*dh] -> q [M][Hq*dh], K/V caches at position pos0[s]+i.
+void launch_rope_store(const float *qkv32, void *q, void *k_cache, void *v_cache, int dtype, const float2 *rope,
+                       const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv, int dh, int *flags,
+                       hipStream_t st);
+// a = silu(g) * u ; gu32 [M][2*dff] (gate cols first) -> a [M][dff]
+void launch_silu_mul(const float *gu32, void *a, int dtype, int64_t M, int dff, hipStream_t st);
+// in place on a [M][dff]: keep the ra.m largest |a| (ties to lower channel), then FQ.
+// Rows are visited in bucket order through perm (NULL = identity).
+void launch_prune_fq(void *a, int dtype, const RowAct *ra, const int32_t *perm, bool quant, int64_t M, int dff,
+                     hipStream_t st);
+// out = x2 + z
+void launch_resid_out(const float *x2, const float *z, void *out, int dtype, int64_t M, int d, hipStream_t st);
+// x[n][t] = embed[tokens[b][t]]  for n = b*G + g
+void launch_embed(const void *embed, const int32_t *tokens, void *x, int dtype, int B, int G, int T, int d,
+                  int vocab, hipStream_t st);
+// nll[r] = logsumexp(logits[r]) - logits[r][target]; targets indexed through tgt_index(r)
+void launch_nll_rows(const float *logits, int64_t rows, int V, const int32_t *targets, int64_t row0, int G, int T,
+                     bool broadcast_g, float *nll, hipStream_t st);
+// unit hooks
+void launch_test_topk(const float *scores, int rows, int n_cols, const int32_t *n_valid, const int32_t *k,
+                      uint8_t *keep, hipStream_t st);
+void launch_test_prune(const float *a, int rows, int n, const int32_t *m, uint8_t *keep, hipStream_t st);
+void launch_test_quant(const float *z, int rows, int n, const int32_t *bits, int32_t *codes, float *scale,
+                       float *zhat, hipStream_t st);
+
+// ---- GEMM (sol_gemm.hip) ---------------------------------------------------------------------
+// C[M][N] (fp32, ldc) = A[M][K] (a_dtype, lda) * W[N][K]^T (w_dtype, ldw). Any shape.
+void launch_gemm_generic(const void *A, int a_dtype, int64_t lda, const void *W, int w_dtype, int64_t ldw,
+                         float *C, int64_t ldc, int64_t M, int N, int K, hipStream_t st);
+
+// ---- attention (sol_attn.hip) ----------------------------------------------------------------
+// One query row per workgroup group: scores over cache positions [0, pos], budgeted top-k,
+// softmax over kept keys, times V. o32: fp32 [M][Hq*dh]. Returns false if the shape is unsupported.
+bool launch_attn_rows(const void *q, const void *k_cache, const void *v_cache, int dtype, float *o32,
+                      const RowAct *ra, const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv,
+                      int dh, int *flags, hipStream_t st);
+size_t attn_rows_lds_bytes(int L_max, int hpb, int block);
+
+}  // namespace sol

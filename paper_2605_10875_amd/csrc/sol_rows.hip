@@ -1,0 +1,544 @@
+// Row-wise kernels (one workgroup per token row): action decode + bucketing, RMSNorm with the
+// fake-quantise epilogue, magnitude pruning + quantise, rotary/scatter, residuals, NLL rows and
+// the unit hooks. All HBM-bound; rows are contiguous, so accesses are coalesced.
+#include "sol_internal.h"
+
+namespace sol {
+
+// ------------------------------------------------------------------------------------------------
+// action decode (Method, "Actions and controlled compute": a -> (kappa, rho, q))
+// ------------------------------------------------------------------------------------------------
+__global__ void k_prepare_rows(const int32_t *__restrict__ ids, const ActionDev *__restrict__ table, int n_actions,
+                               int d_ff, int64_t M, RowAct *__restrict__ ra, int32_t *__restrict__ row_bucket,
+                               int *flags)
+{
+    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= M) return;
+    const int id = ids[r];
+    RowAct a;
+    int bucket = 0;
+    if (id < 0 || id >= n_actions) {
+        atomicOr(flags, FLAG_BAD_ACTION);
+        a.keep_num = 1; a.keep_den = 1; a.m = d_ff; a.bits = 16;
+        bucket = 0;
+    } else {
+        const ActionDev t = table[id];
+        a.keep_num = t.keep_num; a.keep_den = t.keep_den;
+        a.m = budget_ceil(t.mlp_keep_num, t.mlp_keep_den, d_ff);
+        a.bits = (int)t.bits;
+        bucket = t.bucket;
+    }
+    ra[r] = a;
+    row_bucket[r] = bucket;
+}
+
+void launch_prepare_rows(const int32_t *action_ids, const ActionDev *table, int n_actions, int d_ff, int64_t M,
+                         RowAct *ra, int32_t *row_bucket, int *flags, hipStream_t st)
+{
+    if (M <= 0) return;
+    hipLaunchKernelGGL(k_prepare_rows, dim3((unsigned)((M + 255) / 256)), dim3(256), 0, st, action_ids, table,
+                       n_actions, d_ff, M, ra, row_bucket, flags);
+}
+
+// ------------------------------------------------------------------------------------------------
+// stable counting sort of rows by MLP bucket (one workgroup; M is at most a few 10^5 rows)
+// ------------------------------------------------------------------------------------------------
+constexpr int SORT_BLOCK = 1024;
+constexpr int SORT_GROUP = 8;
+
+__global__ void __launch_bounds__(SORT_BLOCK)
+k_bucket_sort(const int32_t *__restrict__ row_bucket, int64_t M, int n_buckets, int32_t *__restrict__ perm,
+              int32_t *__restrict__ bucket_off)
+{
+    __shared__ int wtot[SORT_BLOCK / 64];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int64_t seg = (M + SORT_BLOCK - 1) / SORT_BLOCK;
+    const int64_t r0 = (int64_t)tid * seg;
+    const int64_t r1 = (r0 + seg < M) ? r0 + seg : M;
+    int base = 0;
+    for (int g0 = 0; g0 < n_buckets; g0 += SORT_GROUP) {
+        int cnt[SORT_GROUP];
+#pragma unroll
+        for (int b = 0; b < SORT_GROUP; ++b) cnt[b] = 0;
+        for (int64_t r = r0; r < r1; ++r) {
+            const int b = row_bucket[r] - g0;
+#pragma unroll
+            for (int bb = 0; bb < SORT_GROUP; ++bb) cnt[bb] += (b == bb);
+        }
+        int start[SORT_GROUP];
+#pragma unroll
+        for (int b = 0; b < SORT_GROUP; ++b) {
+            int incl = cnt[b];
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int t = __shfl_up(incl, o, 64);
+                if (lane >= o) incl += t;
+            }
+            if (lane == 63) wtot[w] = incl;
+            __syncthreads();
+            int woff = 0, total = 0;
+#pragma unroll
+            for (int j = 0; j < SORT_BLOCK / 64; ++j) {
+                const int c = wtot[j];
+                if (j < w) woff += c;
+                total += c;
+            }
+            __syncthreads();
+            start[b] = base + woff + incl - cnt[b];
+            if (tid == 0 && g0 + b < n_buckets) bucket_off[g0 + b] = base;
+            base += total;
+        }
+        for (int64_t r = r0; r < r1; ++r) {
+            const int b = row_bucket[r] - g0;
+#pragma unroll
+            for (int bb = 0; bb < SORT_GROUP; ++bb)
+                if (b == bb) perm[start[bb]++] = (int32_t)r;
+        }
+    }
+    if (tid == 0) bucket_off[n_buckets] = base;
+}
+
+void launch_bucket_sort(const int32_t *row_bucket, int64_t M, int n_buckets, int32_t *perm, int32_t *bucket_off,
+                        hipStream_t st)
+{
+    if (M <= 0) return;
+    hipLaunchKernelGGL(k_bucket_sort, dim3(1), dim3(SORT_BLOCK), 0, st, row_bucket, M, n_buckets, perm, bucket_off);
+}
+
+// ------------------------------------------------------------------------------------------------
+// RMSNorm (+ optional residual add) + per-token fake-quantise epilogue
+// ------------------------------------------------------------------------------------------------
+constexpr int ROW_BLOCK = 256;
+
+template <typename TX, typename TW, typename TH>
+__global__ void __launch_bounds__(ROW_BLOCK)
+k_rmsnorm_fq(const TX *__restrict__ x, const float *__restrict__ add, float *__restrict__ xsum,
+             const TW *__restrict__ w, TH *__restrict__ h, const RowAct *__restrict__ ra, int quant, int d,
+             float eps)
+{
+    extern __shared__ float row[];
+    __shared__ float red[ROW_BLOCK / 64];
+    const int64_t r = blockIdx.x;
+    const int tid = threadIdx.x;
+    const TX *xr = x + r * d;
+    float ss = 0.f;
+    for (int j = tid; j < d; j += ROW_BLOCK) {
+        float v = ld(xr + j);
+        if (add) v += add[r * d + j];
+        if (xsum) xsum[r * d + j] = v;
+        row[j] = v;
+        ss += v * v;
+    }
+    ss = block_sum<ROW_BLOCK>(ss, red);
+    const float rinv = 1.0f / sqrtf(ss / (float)d + eps);
+    float amax = 0.f;
+    for (int j = tid; j < d; j += ROW_BLOCK) {
+        const float v = row[j] * rinv * ld(w + j);
+        row[j] = v;
+        amax = fmaxf(amax, fabsf(v));
+    }
+    const int bits = (quant && ra) ? ra[r].bits : 16;
+    TH *hr = h + r * d;
+    if (bits < 16) {
+        amax = block_max<ROW_BLOCK>(amax, red);
+        if (amax > 0.f) {
+            const float qmax = fq_qmax(bits);
+            const float s = amax / qmax;
+            for (int j = tid; j < d; j += ROW_BLOCK) st(hr + j, fq_code(row[j], s, qmax) * s);
+            return;
+        }
+    }
+    for (int j = tid; j < d; j += ROW_BLOCK) st(hr + j, row[j]);
+}
+
+template <typename TX, typename TW, typename TH>
+static void rmsnorm_dispatch3(const void *x, const float *add, float *xsum, const void *w, void *h, const RowAct *ra,
+                              bool quant, int64_t M, int d, float eps, hipStream_t st)
+{
+    hipLaunchKernelGGL((k_rmsnorm_fq<TX, TW, TH>), dim3((unsigned)M), dim3(ROW_BLOCK), (size_t)d * sizeof(float), st,
+                       (const TX *)x, add, xsum, (const TW *)w, (TH *)h, ra, quant ? 1 : 0, d, eps);
+}
+
+void launch_rmsnorm_fq(const void *x, int x_dtype, const float *add, float *xsum, const void *w, int w_dtype, void *h,
+                       int h_dtype, const RowAct *ra, bool quant, int64_t M, int d, float eps, hipStream_t st)
+{
+    if (M <= 0) return;
+    const int key = (x_dtype << 2) | (w_dtype << 1) | h_dtype;
+    switch (key) {
+    case 0: rmsnorm_dispatch3<float, float, float>(x, add, xsum, w, h, ra, quant, M, d, eps, st); break;
+    case 7: rmsnorm_dispatch3<bf16_t, bf16_t, bf16_t>(x, add, xsum, w, h, ra, quant, M, d, eps, st); break;
+    case 3: rmsnorm_dispatch3<float, bf16_t, bf16_t>(x, add, xsum, w, h, ra, quant, M, d, eps, st); break;
+    default: break;   // no other combination is ever requested by the host code
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// row-wise fake-quantise of an fp32 matrix into the storage type (attention output -> o-proj input)
+// ------------------------------------------------------------------------------------------------
+template <typename TO>
+__global__ void __launch_bounds__(ROW_BLOCK)
+k_fq_rows(const float *__restrict__ in, TO *__restrict__ out, const RowAct *__restrict__ ra, int quant, int n)
+{
+    __shared__ float red[ROW_BLOCK / 64];
+    const int64_t r = blockIdx.x;
+    const int tid = threadIdx.x;
+    const float *ir = in + r * n;
+    TO *orow = out + r * n;
+    const int bits = (quant && ra) ? ra[r].bits : 16;
+    if (bits < 16) {
+        float amax = 0.f;
+        for (int j = tid; j < n; j += ROW_BLOCK) amax = fmaxf(amax, fabsf(ir[j]));
+        amax = block_max<ROW_BLOCK>(amax, red);
+        if (amax > 0.f) {
+            const float qmax = fq_qmax(bits);
+            const float s = amax / qmax;
+            for (int j = tid; j < n; j += ROW_BLOCK) st(orow + j, fq_code(ir[j], s, qmax) * s);
+            return;
+        }
+    }
+    for (int j = tid; j < n; j += ROW_BLOCK) st(orow + j, ir[j]);
+}
+
+void launch_fq_rows(const float *in, void *out, int out_dtype, const RowAct *ra, bool quant, int64_t M, int n,
+                    hipStream_t st)
+{
+    if (M <= 0) return;
+    if (out_dtype == 0)
+        hipLaunchKernelGGL((k_fq_rows<float>), dim3((unsigned)M), dim3(ROW_BLOCK), 0, st, in, (float *)out, ra,
+                           quant ? 1 : 0, n);
+    else
+        hipLaunchKernelGGL((k_fq_rows<bf16_t>), dim3((unsigned)M), dim3(ROW_BLOCK), 0, st, in, (bf16_t *)out, ra,
+                           quant ? 1 : 0, n);
+}
+
+// ------------------------------------------------------------------------------------------------
+// rotary embedding (rotate-half pairs (c, c + dh/2)) and scatter of q, k, v
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(ROW_BLOCK)
+k_rope_store(const float *__restrict__ qkv, T *__restrict__ q, T *__restrict__ kc, T *__restrict__ vc,
+             const float2 *__restrict__ rope, const int32_t *__restrict__ pos0, int Tn, int L_max, int Hq, int Hkv,
+             int dh, int *flags)
+{
+    const int64_t r = blockIdx.x;
+    const int s = (int)(r / Tn), i = (int)(r % Tn);
+    const int p0 = pos0 ? pos0[s] : 0;
+    if (p0 < 0 || p0 + Tn > L_max) {
+        if (threadIdx.x == 0) atomicOr(flags, FLAG_CACHE_OVERFLOW);
+        return;
+    }
+    const int pos = p0 + i, half = dh >> 1;
+    const int ncol = (Hq + 2 * Hkv) * dh;
+    const float *in = qkv + r * ncol;
+    const float2 *cs = rope + (int64_t)pos * half;
+    for (int idx = threadIdx.x; idx < Hq * half; idx += ROW_BLOCK) {
+        const int hh = idx / half, c = idx - hh * half;
+        const float x0 = in[hh * dh + c], x1 = in[hh * dh + c + half];
+        const float2 t = cs[c];
+        st(q + r * (int64_t)(Hq * dh) + hh * dh + c, x0 * t.x - x1 * t.y);
+        st(q + r * (int64_t)(Hq * dh) + hh * dh + c + half, x1 * t.x + x0 * t.y);
+    }
+    const float *kin = in + Hq * dh;
+    const float *vin = kin + Hkv * dh;
+    for (int idx = threadIdx.x; idx < Hkv * half; idx += ROW_BLOCK) {
+        const int hh = idx / half, c = idx - hh * half;
+        const float x0 = kin[hh * dh + c], x1 = kin[hh * dh + c + half];
+        const float2 t = cs[c];
+        T *dst = kc + (((int64_t)s * Hkv + hh) * L_max + pos) * dh;
+        st(dst + c, x0 * t.x - x1 * t.y);
+        st(dst + c + half, x1 * t.x + x0 * t.y);
+    }
+    for (int idx = threadIdx.x; idx < Hkv * dh; idx += ROW_BLOCK) {
+        const int hh = idx / dh, c = idx - hh * dh;
+        st(vc + (((int64_t)s * Hkv + hh) * L_max + pos) * dh + c, vin[idx]);
+    }
+}
+
+void launch_rope_store(const float *qkv32, void *q, void *k_cache, void *v_cache, int dtype, const float2 *rope,
+                       const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv, int dh, int *flags,
+                       hipStream_t st)
+{
+    const int64_t M = (int64_t)n_seq * T;
+    if (M <= 0) return;
+    if (dtype == 0)
+        hipLaunchKernelGGL((k_rope_store<float>), dim3((unsigned)M), dim3(ROW_BLOCK), 0, st, qkv32, (float *)q,
+                           (float *)k_cache, (float *)v_cache, rope, pos0, T, L_max, Hq, Hkv, dh, flags);
+    else
+        hipLaunchKernelGGL((k_rope_store<bf16_t>), dim3((unsigned)M), dim3(ROW_BLOCK), 0, st, qkv32, (bf16_t *)q,
+                           (bf16_t *)k_cache, (bf16_t *)v_cache, rope, pos0, T, L_max, Hq, Hkv, dh, flags);
+}
+
+// ------------------------------------------------------------------------------------------------
+// SwiGLU elementwise: a = g * sigmoid(g) * u
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ float silu_mul(float g, float u) { return (g / (1.0f + expf(-g))) * u; }
+
+template <typename T>
+__global__ void k_silu_mul(const float *__restrict__ gu, T *__restrict__ a, int64_t M, int dff)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= M * dff) return;
+    const int64_t r = idx / dff;
+    const int c = (int)(idx - r * dff);
+    st(a + idx, silu_mul(gu[r * 2 * dff + c], gu[r * 2 * dff + dff + c]));
+}
+
+void launch_silu_mul(const float *gu32, void *a, int dtype, int64_t M, int dff, hipStream_t st)
+{
+    const int64_t n = M * dff;
+    if (n <= 0) return;
+    const unsigned grid = (unsigned)((n + 255) / 256);
+    if (dtype == 0) hipLaunchKernelGGL((k_silu_mul<float>), dim3(grid), dim3(256), 0, st, gu32, (float *)a, M, dff);
+    else hipLaunchKernelGGL((k_silu_mul<bf16_t>), dim3(grid), dim3(256), 0, st, gu32, (bf16_t *)a, M, dff);
+}
+
+// ------------------------------------------------------------------------------------------------
+// per-token magnitude pruning + fake-quantise, in place (down-projection input)
+// ------------------------------------------------------------------------------------------------
+struct MagKeyLds {
+    const float *row;
+    __device__ __forceinline__ uint32_t operator()(int i) const { return mag_key(row[i]); }
+};
+
+template <typename T>
+__global__ void __launch_bounds__(ROW_BLOCK)
+k_prune_fq(T *__restrict__ a, const RowAct *__restrict__ ra, const int32_t *__restrict__ perm, int quant, int dff)
+{
+    extern __shared__ float row[];
+    __shared__ int hist[256];
+    __shared__ int sh[4];
+    __shared__ int wcnt[ROW_BLOCK / 64];
+    __shared__ float red[ROW_BLOCK / 64];
+    const int64_t r = perm ? perm[blockIdx.x] : (int64_t)blockIdx.x;
+    const RowAct act = ra[r];
+    const int bits = quant ? act.bits : 16;
+    const int m = act.m;
+    if (m >= dff && bits >= 16) return;          // dense bucket: the row is already final
+    const int tid = threadIdx.x;
+    T *ar = a + r * dff;
+    float amax = 0.f;
+    for (int j = tid; j < dff; j += ROW_BLOCK) {
+        const float v = ld(ar + j);
+        row[j] = v;
+        amax = fmaxf(amax, fabsf(v));
+    }
+    __syncthreads();
+    if (m < dff) {
+        MagKeyLds kf{row};
+        uint32_t thr; int quota, n_eq;
+        block_radix_select<ROW_BLOCK>(kf, dff, m, hist, sh, thr, quota, n_eq);
+        int J = dff;
+        if (quota < n_eq) J = block_tie_cutoff<ROW_BLOCK>(kf, dff, thr, quota, wcnt, sh);
+        for (int j = tid; j < dff; j += ROW_BLOCK) {
+            const uint32_t key = mag_key(row[j]);
+            const bool keep = key > thr || (key == thr && j <= J);
+            if (!keep) row[j] = 0.f;
+        }
+    }
+    if (bits < 16) {
+        amax = block_max<ROW_BLOCK>(amax, red);   // the largest magnitude is always kept
+        if (amax > 0.f) {
+            const float qmax = fq_qmax(bits);
+            const float s = amax / qmax;
+            for (int j = tid; j < dff; j += ROW_BLOCK) st(ar + j, fq_code(row[j], s, qmax) * s);
+            return;
+        }
+    }
+    for (int j = tid; j < dff; j += ROW_BLOCK) st(ar + j, row[j]);
+}
+
+void launch_prune_fq(void *a, int dtype, const RowAct *ra, const int32_t *perm, bool quant, int64_t M, int dff,
+                     hipStream_t st)
+{
+    if (M <= 0) return;
+    const size_t lds = (size_t)dff * sizeof(float);
+    if (dtype == 0)
+        hipLaunchKernelGGL((k_prune_fq<float>), dim3((unsigned)M), dim3(ROW_BLOCK), lds, st, (float *)a, ra, perm,
+                           quant ? 1 : 0, dff);
+    else
+        hipLaunchKernelGGL((k_prune_fq<bf16_t>), dim3((unsigned)M), dim3(ROW_BLOCK), lds, st, (bf16_t *)a, ra, perm,
+                           quant ? 1 : 0, dff);
+}
+
+// ------------------------------------------------------------------------------------------------
+// residual add into the output type; embedding gather
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void k_resid_out(const float *__restrict__ x2, const float *__restrict__ z, T *__restrict__ out, int64_t n)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx < n) st(out + idx, x2[idx] + z[idx]);
+}
+
+void launch_resid_out(const float *x2, const float *z, void *out, int dtype, int64_t M, int d, hipStream_t st)
+{
+    const int64_t n = M * d;
+    if (n <= 0) return;
+    const unsigned grid = (unsigned)((n + 255) / 256);
+    if (dtype == 0) hipLaunchKernelGGL((k_resid_out<float>), dim3(grid), dim3(256), 0, st, x2, z, (float *)out, n);
+    else hipLaunchKernelGGL((k_resid_out<bf16_t>), dim3(grid), dim3(256), 0, st, x2, z, (bf16_t *)out, n);
+}
+
+template <typename T>
+__global__ void k_embed(const T *__restrict__ embed, const int32_t *__restrict__ tokens, T *__restrict__ x, int G,
+                        int Tn, int d, int vocab)
+{
+    const int64_t r = blockIdx.x;                 // row = (b*G + g)*T + t
+    const int t = (int)(r % Tn);
+    const int b = (int)(r / ((int64_t)G * Tn));
+    int tok = tokens[(int64_t)b * Tn + t];
+    tok = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok);
+    for (int j = threadIdx.x; j < d; j += blockDim.x) x[r * d + j] = embed[(int64_t)tok * d + j];
+}
+
+void launch_embed(const void *embed, const int32_t *tokens, void *x, int dtype, int B, int G, int T, int d, int vocab,
+                  hipStream_t st)
+{
+    const int64_t M = (int64_t)B * G * T;
+    if (M <= 0) return;
+    if (dtype == 0)
+        hipLaunchKernelGGL((k_embed<float>), dim3((unsigned)M), dim3(256), 0, st, (const float *)embed, tokens,
+                           (float *)x, G, T, d, vocab);
+    else
+        hipLaunchKernelGGL((k_embed<bf16_t>), dim3((unsigned)M), dim3(256), 0, st, (const bf16_t *)embed, tokens,
+                           (bf16_t *)x, G, T, d, vocab);
+}
+
+// ------------------------------------------------------------------------------------------------
+// NLL of materialised logits rows: logsumexp(l) - l[target]   (Method, Eq. 1, negated)
+// ------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(ROW_BLOCK)
+k_nll_rows(const float *__restrict__ logits, int V, const int32_t *__restrict__ targets, int64_t row0, int G, int Tn,
+           int broadcast_g, float *__restrict__ nll)
+{
+    __shared__ float red[ROW_BLOCK / 64];
+    const int64_t lr = blockIdx.x, r = row0 + lr;
+    const float *l = logits + lr * V;
+    float mx = -INFINITY;
+    for (int v = threadIdx.x; v < V; v += ROW_BLOCK) mx = fmaxf(mx, l[v]);
+    mx = block_max<ROW_BLOCK>(mx, red);
+    float se = 0.f;
+    for (int v = threadIdx.x; v < V; v += ROW_BLOCK) se += expf(l[v] - mx);
+    se = block_sum<ROW_BLOCK>(se, red);
+    if (threadIdx.x == 0) {
+        const int64_t ti = broadcast_g ? (r / ((int64_t)G * Tn)) * Tn + (r % Tn) : r;
+        int tg = targets[ti];
+        tg = tg < 0 ? 0 : (tg >= V ? V - 1 : tg);
+        nll[r] = (mx + logf(se)) - l[tg];
+    }
+}
+
+void launch_nll_rows(const float *logits, int64_t rows, int V, const int32_t *targets, int64_t row0, int G, int T,
+                     bool broadcast_g, float *nll, hipStream_t st)
+{
+    if (rows <= 0) return;
+    hipLaunchKernelGGL(k_nll_rows, dim3((unsigned)rows), dim3(ROW_BLOCK), 0, st, logits, V, targets, row0, G, T,
+                       broadcast_g ? 1 : 0, nll);
+}
+
+// ------------------------------------------------------------------------------------------------
+// unit hooks
+// ------------------------------------------------------------------------------------------------
+struct ScoreKeyGlobal {
+    const float *row;
+    __device__ __forceinline__ uint32_t operator()(int i) const { return score_key(row[i]); }
+};
+struct MagKeyGlobal {
+    const float *row;
+    __device__ __forceinline__ uint32_t operator()(int i) const { return mag_key(row[i]); }
+};
+
+template <typename KeyFn>
+__device__ __forceinline__ void select_row_to_mask(KeyFn kf, int n_valid, int n_cols, int k, uint8_t *keep)
+{
+    __shared__ int hist[256];
+    __shared__ int sh[4];
+    __shared__ int wcnt[ROW_BLOCK / 64];
+    const int tid = threadIdx.x;
+    if (k >= n_valid) {
+        for (int j = tid; j < n_cols; j += ROW_BLOCK) keep[j] = j < n_valid;
+        return;
+    }
+    if (k <= 0) {
+        for (int j = tid; j < n_cols; j += ROW_BLOCK) keep[j] = 0;
+        return;
+    }
+    uint32_t thr; int quota, n_eq;
+    block_radix_select<ROW_BLOCK>(kf, n_valid, k, hist, sh, thr, quota, n_eq);
+    int J = n_valid;
+    if (quota < n_eq) J = block_tie_cutoff<ROW_BLOCK>(kf, n_valid, thr, quota, wcnt, sh);
+    for (int j = tid; j < n_cols; j += ROW_BLOCK) {
+        uint8_t kp = 0;
+        if (j < n_valid) {
+            const uint32_t key = kf(j);
+            kp = key > thr || (key == thr && j <= J);
+        }
+        keep[j] = kp;
+    }
+}
+
+__global__ void __launch_bounds__(ROW_BLOCK)
+k_test_topk(const float *__restrict__ scores, int n_cols, const int32_t *__restrict__ n_valid,
+            const int32_t *__restrict__ k, uint8_t *__restrict__ keep)
+{
+    const int64_t r = blockIdx.x;
+    int nv = n_valid[r];
+    nv = nv < 0 ? 0 : (nv > n_cols ? n_cols : nv);
+    ScoreKeyGlobal kf{scores + r * n_cols};
+    select_row_to_mask(kf, nv, n_cols, k[r], keep + r * n_cols);
+}
+
+__global__ void __launch_bounds__(ROW_BLOCK)
+k_test_prune(const float *__restrict__ a, int n, const int32_t *__restrict__ m, uint8_t *__restrict__ keep)
+{
+    const int64_t r = blockIdx.x;
+    MagKeyGlobal kf{a + r * n};
+    select_row_to_mask(kf, n, n, m[r], keep + r * n);
+}
+
+__global__ void __launch_bounds__(ROW_BLOCK)
+k_test_quant(const float *__restrict__ z, int n, const int32_t *__restrict__ bits, int32_t *__restrict__ codes,
+             float *__restrict__ scale, float *__restrict__ zhat)
+{
+    __shared__ float red[ROW_BLOCK / 64];
+    const int64_t r = blockIdx.x;
+    const int tid = threadIdx.x;
+    const float *zr = z + r * n;
+    const int b = bits[r];
+    float amax = 0.f;
+    for (int j = tid; j < n; j += ROW_BLOCK) amax = fmaxf(amax, fabsf(zr[j]));
+    amax = block_max<ROW_BLOCK>(amax, red);
+    if (b >= 16 || !(amax > 0.f)) {
+        for (int j = tid; j < n; j += ROW_BLOCK) { codes[r * n + j] = 0; zhat[r * n + j] = zr[j]; }
+        if (tid == 0) scale[r] = 0.f;
+        return;
+    }
+    const float qmax = fq_qmax(b);
+    const float s = amax / qmax;
+    if (tid == 0) scale[r] = s;
+    for (int j = tid; j < n; j += ROW_BLOCK) {
+        const float c = fq_code(zr[j], s, qmax);
+        codes[r * n + j] = (int32_t)c;
+        zhat[r * n + j] = c * s;
+    }
+}
+
+void launch_test_topk(const float *scores, int rows, int n_cols, const int32_t *n_valid, const int32_t *k,
+                      uint8_t *keep, hipStream_t st)
+{
+    if (rows <= 0 || n_cols <= 0) return;
+    hipLaunchKernelGGL(k_test_topk, dim3(rows), dim3(ROW_BLOCK), 0, st, scores, n_cols, n_valid, k, keep);
+}
+void launch_test_prune(const float *a, int rows, int n, const int32_t *m, uint8_t *keep, hipStream_t st)
+{
+    if (rows <= 0 || n <= 0) return;
+    hipLaunchKernelGGL(k_test_prune, dim3(rows), dim3(ROW_BLOCK), 0, st, a, n, m, keep);
+}
+void launch_test_quant(const float *z, int rows, int n, const int32_t *bits, int32_t *codes, float *scale,
+                       float *zhat, hipStream_t st)
+{
+    if (rows <= 0 || n <= 0) return;
+    hipLaunchKernelGGL(k_test_quant, dim3(rows), dim3(ROW_BLOCK), 0, st, z, n, bits, codes, scale, zhat);
+}
+
+}  // namespace sol

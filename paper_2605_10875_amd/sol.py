@@ -1,0 +1,281 @@
+"""Thin ctypes binding of libsol.so (the C ABI declared in include/sol.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP kernels. torch is
+used for device memory and streams. There is no CPU fallback: a missing library is an error.
+"""
+import ctypes as C
+import os
+
+import torch
+
+from . import build as _build
+
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_ACTION, ERR_CACHE_OVERFLOW, ERR_HIP = 0, -1, -2, -3, -4, -5, -6
+F32, BF16 = 0, 1
+QS_QKV_IN, QS_O_IN, QS_GATEUP_IN, QS_DOWN_IN = 1, 2, 4, 8
+QS_ALL_LINEAR_INPUTS = 15
+OP_LAYER_FORWARD, OP_DECODE_STEP, OP_SCHEDULE_LOGLIK = 0, 1, 2
+
+EXPORTS = ("sol_validate_config", "sol_create", "sol_destroy", "sol_last_error", "sol_workspace_bytes",
+           "sol_layer_forward", "sol_decode_step", "sol_schedule_loglik", "sol_device_status",
+           "sol_test_topk_select", "sol_test_prune_mask", "sol_test_quant_codes")
+
+
+class ActionDef(C.Structure):
+    _fields_ = [("keep_num", C.c_uint32), ("keep_den", C.c_uint32), ("mlp_keep_num", C.c_uint32),
+                ("mlp_keep_den", C.c_uint32), ("bits", C.c_uint32)]
+
+
+class ModelCfg(C.Structure):
+    _fields_ = [("d_model", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("d_ff", C.c_int32), ("n_layers", C.c_int32), ("vocab", C.c_int32),
+                ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("dtype", C.c_int32),
+                ("max_positions", C.c_int32), ("page_size", C.c_int32), ("n_sink", C.c_int32),
+                ("n_window", C.c_int32), ("prune_site", C.c_int32), ("quant_sites", C.c_uint32)]
+
+
+_W_NAMES = ("w_in_norm", "wq", "wk", "wv", "wo", "w_post_norm", "w_gate", "w_up", "w_down")
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _W_NAMES]
+
+
+class ModelWeights(C.Structure):
+    _fields_ = [("embed", C.c_void_p), ("layers", C.POINTER(LayerWeights)), ("w_final_norm", C.c_void_p),
+                ("lm_head", C.c_void_p)]
+
+
+class SolError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"sol status {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib_path():
+    return _build.LIB
+
+
+def lib():
+    """Loads libsol.so, building it first only if it has never been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_build.LIB):
+            _build.build()
+        L = C.CDLL(_build.LIB)
+        L.sol_last_error.restype = C.c_char_p
+        L.sol_last_error.argtypes = [C.c_void_p]
+        L.sol_workspace_bytes.restype = C.c_size_t
+        L.sol_workspace_bytes.argtypes = [C.POINTER(ModelCfg), C.c_int, C.c_int, C.c_int, C.c_int]
+        L.sol_validate_config.argtypes = [C.POINTER(ModelCfg), C.POINTER(ActionDef), C.c_int]
+        L.sol_create.argtypes = [C.POINTER(ModelCfg), C.POINTER(ActionDef), C.c_int, C.POINTER(C.c_void_p)]
+        L.sol_destroy.argtypes = [C.c_void_p]
+        L.sol_destroy.restype = None
+        L.sol_device_status.argtypes = [C.c_void_p, C.c_void_p]
+        L.sol_layer_forward.argtypes = [C.c_void_p, C.POINTER(LayerWeights), C.c_void_p, C.c_void_p, C.c_void_p,
+                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
+                                        C.c_void_p, C.c_size_t, C.c_void_p]
+        L.sol_decode_step.argtypes = [C.c_void_p, C.POINTER(ModelWeights), C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int, C.c_int,
+                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.sol_schedule_loglik.argtypes = [C.c_void_p, C.POINTER(ModelWeights), C.c_void_p, C.c_void_p, C.c_void_p,
+                                          C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.sol_test_topk_select.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.sol_test_prune_mask.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.sol_test_quant_codes.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
+                                           C.c_void_p, C.c_void_p]
+        _lib = L
+    return _lib
+
+
+def make_cfg(shape, dtype, max_positions, quant_sites=QS_ALL_LINEAR_INPUTS, page_size=1, n_sink=0, n_window=0,
+             prune_site=0):
+    return ModelCfg(shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_ff, shape.n_layers,
+                    shape.vocab, shape.rms_eps, shape.rope_theta, dtype, max_positions, page_size, n_sink, n_window,
+                    prune_site, quant_sites)
+
+
+def make_table(actions):
+    arr = (ActionDef * len(actions))()
+    for i, a in enumerate(actions):
+        arr[i] = ActionDef(*[int(v) for v in a])
+    return arr
+
+
+def validate_config(cfg, actions):
+    L = lib()
+    tab = make_table(actions) if len(actions) else None
+    rc = L.sol_validate_config(C.byref(cfg), tab, len(actions))
+    return rc, (L.sol_last_error(None) or b"").decode() if rc else ""
+
+
+def workspace_bytes(cfg, op, n_seq, T, L_max):
+    return int(lib().sol_workspace_bytes(C.byref(cfg), op, n_seq, T, L_max))
+
+
+def _ptr(t):
+    return C.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def _stream(stream):
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return C.c_void_p(s.cuda_stream)
+
+
+def _dtype_code(t):
+    if t.dtype == torch.bfloat16:
+        return BF16
+    if t.dtype == torch.float32:
+        return F32
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _i32(t):
+    assert t is None or (t.dtype == torch.int32 and t.is_cuda and t.is_contiguous())
+    return t
+
+
+class Sol:
+    """One library context: a model configuration plus an action table, on the current device."""
+
+    def __init__(self, shape, actions, dtype=BF16, max_positions=8192, quant_sites=QS_ALL_LINEAR_INPUTS, **kw):
+        self.L = lib()
+        self.cfg = make_cfg(shape, dtype, max_positions, quant_sites, **kw)
+        self.dtype = dtype
+        self.tdtype = torch.bfloat16 if dtype == BF16 else torch.float32
+        self.table = make_table(actions)
+        self.handle = C.c_void_p()
+        rc = self.L.sol_create(C.byref(self.cfg), self.table, len(actions), C.byref(self.handle))
+        if rc:
+            raise SolError(rc, (self.L.sol_last_error(None) or b"").decode())
+        self._ws = None
+
+    def close(self):
+        if self.handle:
+            self.L.sol_destroy(self.handle)
+            self.handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc):
+        if rc:
+            raise SolError(rc, (self.L.sol_last_error(self.handle) or b"").decode())
+
+    def workspace(self, op, n_seq, T, L_max):
+        need = workspace_bytes(self.cfg, op, n_seq, T, L_max)
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+        return self._ws
+
+    def _layer_struct(self, w):
+        s = LayerWeights()
+        for n in _W_NAMES:
+            t = w[n]
+            assert t.is_cuda and t.is_contiguous() and t.dtype == self.tdtype, n
+            setattr(s, n, t.data_ptr())
+        return s
+
+    def _model_struct(self, layers, head):
+        arr = (LayerWeights * len(layers))()
+        for i, w in enumerate(layers):
+            arr[i] = self._layer_struct(w)
+        mw = ModelWeights()
+        mw.layers = C.cast(arr, C.POINTER(LayerWeights))
+        if head is not None:
+            for n in ("embed", "w_final_norm", "lm_head"):
+                t = head.get(n)
+                if t is not None:
+                    assert t.is_cuda and t.is_contiguous() and t.dtype == self.tdtype, n
+                    setattr(mw, n, t.data_ptr())
+        return mw, arr
+
+    def layer_forward(self, w, x_in, action_ids, k_cache, v_cache, pos0=None, x_out=None, workspace=None,
+                      stream=None):
+        """x_in [n_seq][T][d]; action_ids int32 [n_seq][T]; caches [n_seq][Hkv][L_max][dh] (updated)."""
+        n_seq, T, d = x_in.shape
+        L_max = k_cache.shape[2]
+        assert x_in.is_contiguous() and k_cache.is_contiguous() and v_cache.is_contiguous()
+        assert x_in.dtype == self.tdtype and k_cache.dtype == self.tdtype and v_cache.dtype == self.tdtype
+        if x_out is None:
+            x_out = torch.empty_like(x_in)
+        ws = workspace if workspace is not None else self.workspace(OP_LAYER_FORWARD, n_seq, T, L_max)
+        ls = self._layer_struct(w)
+        rc = self.L.sol_layer_forward(self.handle, C.byref(ls), _ptr(x_in), _ptr(x_out), _ptr(_i32(action_ids)),
+                                      _ptr(_i32(pos0)), _ptr(k_cache), _ptr(v_cache), n_seq, T, L_max,
+                                      _ptr(ws), ws.numel(), _stream(stream))
+        self._check(rc)
+        return x_out
+
+    def decode_step(self, layers, head, action_ids, cache_len, k_caches, v_caches, token_ids=None, x_in=None,
+                    targets=None, want_hidden=True, workspace=None, stream=None):
+        """One token per sequence through all layers. Returns (hidden [B][d] or None, nll [B] or None)."""
+        B = action_ids.shape[0]
+        L_max = k_caches[0].shape[2]
+        mw, keep = self._model_struct(layers, head)
+        kp = (C.c_void_p * len(k_caches))(*[t.data_ptr() for t in k_caches])
+        vp = (C.c_void_p * len(v_caches))(*[t.data_ptr() for t in v_caches])
+        x_out = torch.empty((B, self.cfg.d_model), dtype=self.tdtype, device="cuda") if want_hidden else None
+        nll = torch.empty(B, dtype=torch.float32, device="cuda") if targets is not None else None
+        ws = workspace if workspace is not None else self.workspace(OP_DECODE_STEP, B, 1, L_max)
+        rc = self.L.sol_decode_step(self.handle, C.byref(mw), _ptr(_i32(token_ids)), _ptr(x_in),
+                                    _ptr(_i32(action_ids)), _ptr(_i32(cache_len)), kp, vp, B, L_max, _ptr(x_out),
+                                    _ptr(_i32(targets)), _ptr(nll), _ptr(ws), ws.numel(), _stream(stream))
+        del keep
+        self._check(rc)
+        return x_out, nll
+
+    def schedule_loglik(self, layers, head, tokens, targets, action_ids, nll_out=None, workspace=None, stream=None):
+        """tokens/targets int32 [B][T]; action_ids int32 [B][G][T]. Returns nll float32 [B][G][T] (nats)."""
+        B, G, T = action_ids.shape
+        mw, keep = self._model_struct(layers, head)
+        if nll_out is None:
+            nll_out = torch.empty((B, G, T), dtype=torch.float32, device="cuda")
+        ws = workspace if workspace is not None else self.workspace(OP_SCHEDULE_LOGLIK, B * G, T, T)
+        rc = self.L.sol_schedule_loglik(self.handle, C.byref(mw), _ptr(_i32(tokens)), _ptr(_i32(targets)),
+                                        _ptr(_i32(action_ids)), B, G, T, _ptr(nll_out), _ptr(ws), ws.numel(),
+                                        _stream(stream))
+        del keep
+        self._check(rc)
+        return nll_out
+
+    def device_status(self, stream=None):
+        return int(self.L.sol_device_status(self.handle, _stream(stream)))
+
+
+def topk_select(scores, n_valid, k, stream=None):
+    """scores float32 [rows][n_cols] (cuda); n_valid, k int32 [rows]. Returns uint8 keep mask."""
+    rows, n_cols = scores.shape
+    keep = torch.zeros((rows, n_cols), dtype=torch.uint8, device="cuda")
+    rc = lib().sol_test_topk_select(_ptr(scores), rows, n_cols, _ptr(_i32(n_valid)), _ptr(_i32(k)), _ptr(keep),
+                                    _stream(stream))
+    if rc:
+        raise SolError(rc, "sol_test_topk_select")
+    return keep
+
+
+def prune_mask(a, m, stream=None):
+    rows, n = a.shape
+    keep = torch.zeros((rows, n), dtype=torch.uint8, device="cuda")
+    rc = lib().sol_test_prune_mask(_ptr(a), rows, n, _ptr(_i32(m)), _ptr(keep), _stream(stream))
+    if rc:
+        raise SolError(rc, "sol_test_prune_mask")
+    return keep
+
+
+def quant_codes(z, bits, stream=None):
+    rows, n = z.shape
+    codes = torch.zeros((rows, n), dtype=torch.int32, device="cuda")
+    scale = torch.zeros(rows, dtype=torch.float32, device="cuda")
+    zhat = torch.zeros((rows, n), dtype=torch.float32, device="cuda")
+    rc = lib().sol_test_quant_codes(_ptr(z), rows, n, _ptr(_i32(bits)), _ptr(codes), _ptr(scale), _ptr(zhat),
+                                    _stream(stream))
+    if rc:
+        raise SolError(rc, "sol_test_quant_codes")
+    return codes, scale, zhat

@@ -1,0 +1,273 @@
+"""GPU parity proper: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded synthetic inputs.
+
+Tolerances (written here, derived in the design doc). max-rel = max|gpu - ref| / max|ref| over the tensor,
+evaluated per token row.
+  fp32 configuration: rows within 1e-4, NLL within 1e-3 nats.
+  bf16 configuration: rows within 2e-2 and NLL within 1e-2 nats against the oracle run with the
+    same storage precision (it rounds the tensors handed between operators to bf16), so that both
+    sides take the quantisation / selection decisions on equally precise numbers.
+  The method is discontinuous: one quantisation code (a step of absmax/7 at 4 bits) or one selected
+  key that flips at a rounding boundary moves that token's row by far more than any rounding error.
+  Such flips cannot be excluded between two correct implementations that differ in accumulation
+  order: an fp32-vs-fp64 difference of 1e-6 turns, at the next bf16 rounding, into a one-ulp (0.4 %)
+  difference on ~1e-3 of the elements, and after one more contraction and rounding a few elements
+  per row sit on the other side of a 4-bit rounding boundary (measured: ~12 % of 4-bit rows at
+  d_ff = 8192). So tests with quantising actions bound the MEDIAN row by the bf16 noise floor
+  (5e-3), the share of rows over 2e-2, and every row by a cap; tests whose actions do not quantise
+  (selection and pruning only, whose flips swap near-equal elements) hold EVERY row to 2e-2.
+  Against the fp32-storage oracle only tokens under the dense action are comparable at 2e-2
+  (4-bit rows of the fp32- and bf16-storage oracles differ from each other by 10-20 %)."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_10875_amd import sol, synth
+
+from gpu_util import check_rows, dev, dev_weights, host, rel_err
+
+pytestmark = pytest.mark.gpu
+
+SMALL_GQA = synth.ModelShape(d_model=256, n_q_heads=8, n_kv_heads=2, head_dim=64, d_ff=768, n_layers=2, vocab=1000)
+
+
+def _oracle_layer(shape, table, w, x, ids, L_max, act_bf16, pos0=None, kc=None, vc=None, taps=()):
+    cfg = oracle.make_cfg(shape, act_bf16=act_bf16)
+    n_seq = x.shape[0]
+    if kc is None:
+        kc = np.zeros((n_seq, shape.n_kv_heads, L_max, shape.head_dim), np.float32)
+        vc = np.zeros_like(kc)
+    out, tp = oracle.layer_forward(cfg, oracle.make_table(table), w, x, ids, kc, vc, pos0=pos0, taps=taps)
+    return out, kc, vc, tp
+
+
+def _gpu_layer(shape, table, dt, w, x, ids, L_max, pos0=None, kc=None, vc=None, max_positions=None):
+    ctx = sol.Sol(shape, table, dtype=dt, max_positions=max_positions or max(L_max, 16))
+    n_seq = x.shape[0]
+    if kc is None:
+        kc_d = torch.zeros((n_seq, shape.n_kv_heads, L_max, shape.head_dim), dtype=ctx.tdtype, device="cuda")
+        vc_d = torch.zeros_like(kc_d)
+    else:
+        kc_d, vc_d = dev(kc, dt), dev(vc, dt)
+    out = ctx.layer_forward(dev_weights(w, dt), dev(x, dt), dev(ids), kc_d, vc_d,
+                            pos0=dev(pos0) if pos0 is not None else None)
+    assert ctx.device_status() == sol.OK
+    res = host(out), host(kc_d), host(vc_d)
+    ctx.close()
+    return res
+
+
+def test_c1_tiny_fp32_layer():
+    shape, table = synth.TINY, synth.TABLE_C1
+    w = synth.layer_weights(shape, 1234)
+    x = synth.hidden_states(4, 128, shape.d_model, 1235, std=0.02)
+    ids = synth.iid_actions(len(table), (4, 128), 1236)
+    ref, kr, vr, _ = _oracle_layer(shape, table, w, x, ids, 128, False)
+    out, kg, vg = _gpu_layer(shape, table, sol.F32, w, x, ids, 128)
+    check_rows(kg, kr, 1e-5, 2e-2, 0.01, "K cache")
+    check_rows(vg, vr, 1e-5, 2e-2, 0.01, "V cache")
+    check_rows(out, ref, 1e-4, 2e-2, 0.02, "layer output")
+
+
+def test_c1_tiny_fp32_schedule_loglik():
+    shape, table = synth.TINY, synth.TABLE_C1
+    layers = [synth.layer_weights(shape, 1234)]
+    head = synth.head_weights(shape, 1240)
+    B, G, T = 1, 4, 128
+    tokens, targets = synth.tokens_and_targets(B, T, shape.vocab, 1241)
+    ids = synth.iid_actions(len(table), (B, G, T), 1242)
+    ref = oracle.schedule_loglik(oracle.make_cfg(shape), oracle.make_table(table), head["embed"], layers,
+                                 head["w_final_norm"], head["lm_head"], tokens, targets, ids)
+    ctx = sol.Sol(shape, table, dtype=sol.F32, max_positions=T)
+    nll = ctx.schedule_loglik([dev_weights(layers[0], sol.F32)], dev_weights(head, sol.F32), dev(tokens), dev(targets),
+                              dev(ids))
+    assert ctx.device_status() == sol.OK
+    err = np.abs(host(nll) - ref)
+    assert np.quantile(err, 0.98) < 1e-3 and err.max() < 1e-2, (np.quantile(err, 0.98), err.max())
+
+
+NOQUANT_TABLE = synth.action_table((0.125, 0.25, 0.5, 1.0), (0.0, 0.25, 0.5, 0.75), (16,))
+
+SHAPES = [
+    (SMALL_GQA, 3, 70),                                   # ragged everything
+    (synth.LLAMA_1B, 2, 160),                             # Llama-3.2-1B layer shape, several tiles + tail
+    (synth.LLAMA_8B, 1, 72),                              # Llama-3.1-8B layer shape (head_dim 128)
+]
+
+
+@pytest.mark.parametrize("shape,n_seq,T", SHAPES)
+def test_bf16_layer_selection_and_pruning_every_row(shape, n_seq, T):
+    table = NOQUANT_TABLE
+    w = synth.layer_weights(shape, 2000, bf16=True)
+    x = synth.hidden_states(n_seq, T, shape.d_model, 2001, bf16=True)
+    ids = synth.iid_actions(len(table), (n_seq, T), 2002)
+    out, kg, vg = _gpu_layer(shape, table, sol.BF16, w, x, ids, T)
+    refbf, kbf, vbf, _ = _oracle_layer(shape, table, w, x, ids, T, True)
+    check_rows(kg.transpose(0, 2, 1, 3), kbf.transpose(0, 2, 1, 3), 2e-2, 2e-2, 0.0, "K cache")
+    check_rows(vg.transpose(0, 2, 1, 3), vbf.transpose(0, 2, 1, 3), 2e-2, 2e-2, 0.0, "V cache")
+    check_rows(out, refbf, 2e-2, 2e-2, 0.0, "layer output, no quantising action", median=5e-3)
+    # dense-action tokens are comparable with the fp32-storage oracle as well
+    ref32, _, _, _ = _oracle_layer(shape, table, w, x, ids, T, False)
+    sel = ids == table.index(synth.DENSE_ACTION)
+    if sel.any():
+        check_rows(out[sel], ref32[sel], 2e-2, 2e-2, 0.0, "dense-action rows vs fp32-storage oracle")
+
+
+@pytest.mark.parametrize("shape,n_seq,T", SHAPES)
+def test_bf16_layer_full_action_space(shape, n_seq, T):
+    table = synth.TABLE_C2
+    w = synth.layer_weights(shape, 2000, bf16=True)
+    x = synth.hidden_states(n_seq, T, shape.d_model, 2001, bf16=True)
+    ids = synth.iid_actions(len(table), (n_seq, T), 2002)
+    out, kg, vg = _gpu_layer(shape, table, sol.BF16, w, x, ids, T)
+    refbf, kbf, vbf, _ = _oracle_layer(shape, table, w, x, ids, T, True)
+    check_rows(kg.transpose(0, 2, 1, 3), kbf.transpose(0, 2, 1, 3), 2e-2, 0.3, 0.02, "K cache")
+    check_rows(vg.transpose(0, 2, 1, 3), vbf.transpose(0, 2, 1, 3), 2e-2, 0.3, 0.02, "V cache")
+    # per bit-width class: a flipped code moves an element by absmax / q_max, and two quantised sites
+    # in a row amplify the flips, so the row bound scales with the step: max(2e-2, 6 / 2^(bits-1))
+    bits = np.array([a[4] for a in table])[ids]
+    for b in sorted(set(bits.reshape(-1).tolist())):
+        cap = 2e-2 if b >= 16 else max(2e-2, 6.0 / 2 ** (b - 1))
+        check_rows(out[bits == b], refbf[bits == b], cap, cap, 0.0, f"rows of {b}-bit actions")
+
+
+def test_bf16_layer_with_prefix_cache_and_stepwise_equivalence():
+    shape, table = SMALL_GQA, synth.TABLE_C2
+    w = synth.layer_weights(shape, 2100, bf16=True)
+    T, T1 = 40, 23
+    x = synth.hidden_states(2, T, shape.d_model, 2101, bf16=True)
+    ids = synth.iid_actions(len(table), (2, T), 2102)
+    full, kf, vf = _gpu_layer(shape, table, sol.BF16, w, x, ids, T)
+    ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=T)
+    wd = dev_weights(w, sol.BF16)
+    kc = torch.zeros((2, shape.n_kv_heads, T, shape.head_dim), dtype=torch.bfloat16, device="cuda")
+    vc = torch.zeros_like(kc)
+    a = ctx.layer_forward(wd, dev(x[:, :T1], sol.BF16), dev(ids[:, :T1]), kc, vc)
+    b = ctx.layer_forward(wd, dev(x[:, T1:], sol.BF16), dev(ids[:, T1:]), kc, vc,
+                          pos0=dev(np.array([T1, T1], np.int32)))
+    two = np.concatenate([host(a), host(b)], 1)
+    check_rows(two, full, 2e-2, 0.3, 0.1, "two chunks vs one call", median=5e-3)
+    assert rel_err(host(kc), kf) < 2e-2
+    # the oracle agrees on the second chunk given the same prefix cache
+    refb, _, _, _ = _oracle_layer(shape, table, w, x[:, T1:], ids[:, T1:], T, True, pos0=np.array([T1, T1], np.int32),
+                                  kc=kf.copy(), vc=vf.copy())
+    check_rows(host(b), refb, 2e-2, 0.3, 0.2, "second chunk vs bf16 oracle", median=5e-3)
+    ctx.close()
+
+
+def _stack(shape, seed, bf16):
+    layers = [synth.layer_weights(shape, seed + l, bf16=bf16) for l in range(shape.n_layers)]
+    return layers, synth.head_weights(shape, seed + 100, bf16=bf16)
+
+
+@pytest.mark.parametrize("shape,B,L", [
+    (SMALL_GQA, 5, 300),
+    (dataclasses.replace(synth.LLAMA_1B, n_layers=2, vocab=2000), 4, 2100),     # 1024-thread decode path
+])
+def test_bf16_decode_step(shape, B, L):
+    table = synth.TABLE_C4
+    layers, head = _stack(shape, 3000, True)
+    rng = np.random.default_rng(3001)
+    L_max = L + 8
+    cache_len = rng.integers(1, L + 1, B).astype(np.int32)
+    cache_len[0] = L
+    ids = synth.iid_actions(len(table), (B,), 3002)
+    tokens, targets = synth.tokens_and_targets(B, 1, shape.vocab, 3003)
+    kcs, vcs = [], []
+    for l in range(shape.n_layers):
+        k, v = synth.kv_cache(B, shape.n_kv_heads, L_max, shape.head_dim, 3010 + l, bf16=True)
+        kcs.append(k); vcs.append(v)
+    ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=L_max)
+    kd = [dev(k, sol.BF16) for k in kcs]
+    vd = [dev(v, sol.BF16) for v in vcs]
+    hid, nll = ctx.decode_step([dev_weights(w, sol.BF16) for w in layers], dev_weights(head, sol.BF16), dev(ids),
+                               dev(cache_len), kd, vd, token_ids=dev(tokens[:, 0]), targets=dev(targets[:, 0]))
+    assert ctx.device_status() == sol.OK
+    x0 = head["embed"][tokens[:, 0]]
+    kc2 = [k.copy() for k in kcs]
+    vc2 = [v.copy() for v in vcs]
+    h_ref, nll_ref = oracle.decode_step(oracle.make_cfg(shape, act_bf16=True), oracle.make_table(table), layers, x0,
+                                        ids, cache_len, kc2, vc2, head["w_final_norm"], head["lm_head"], targets[:, 0])
+    check_rows(host(hid), h_ref, 2e-2, 1.0, 0.6, "decode hidden vs bf16 oracle", median=2e-2)
+    nerr = np.abs(host(nll) - nll_ref)
+    print("decode nll err", nerr)
+    assert np.median(nerr) < 1e-2 and nerr.max() < 0.5
+    for l in range(shape.n_layers):
+        kg, vg = host(kd[l]), host(vd[l])
+        for s in range(B):
+            p = cache_len[s]
+            if l == 0:                       # layer 0's K/V depend on the input quantiser only
+                assert rel_err(kg[s, :, p], kc2[l][s, :, p]) < 2e-2
+                assert rel_err(vg[s, :, p], vc2[l][s, :, p]) < 2e-2
+            # nothing else in the cache was touched
+            assert np.array_equal(kg[s, :, :p], kcs[l][s, :, :p]) and np.array_equal(kg[s, :, p + 1:], kcs[l][s, :, p + 1:])
+            assert np.array_equal(vg[s, :, :p], vcs[l][s, :, :p]) and np.array_equal(vg[s, :, p + 1:], vcs[l][s, :, p + 1:])
+    ctx.close()
+
+
+def test_bf16_schedule_loglik_determinism_and_parity():
+    shape, table = SMALL_GQA, synth.TABLE_C2
+    layers, head = _stack(shape, 4000, True)
+    B, G, T = 2, 3, 48
+    tokens, targets = synth.tokens_and_targets(B, T, shape.vocab, 4001)
+    ids = synth.markov_actions(len(table), B * G, T, 4002).reshape(B, G, T)
+    ids[:, 2] = ids[:, 0]                                   # schedule 2 repeats schedule 0
+    ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=T)
+    lw = [dev_weights(w, sol.BF16) for w in layers]
+    hw = dev_weights(head, sol.BF16)
+    nll = host(ctx.schedule_loglik(lw, hw, dev(tokens), dev(targets), dev(ids)))
+    assert ctx.device_status() == sol.OK
+    assert np.array_equal(nll[:, 2], nll[:, 0])             # identical schedules, identical likelihoods
+    again = host(ctx.schedule_loglik(lw, hw, dev(tokens), dev(targets), dev(ids)))
+    assert np.array_equal(again, nll)                       # run-to-run bitwise
+    solo = host(ctx.schedule_loglik(lw, hw, dev(tokens[1:]), dev(targets[1:]), dev(ids[1:])))
+    assert np.array_equal(solo[0], nll[1])                  # independent of the rest of the batch
+    ref = oracle.schedule_loglik(oracle.make_cfg(shape, act_bf16=True), oracle.make_table(table), head["embed"],
+                                 layers, head["w_final_norm"], head["lm_head"], tokens, targets, ids)
+    err = np.abs(nll - ref)
+    print("nll err: median %.2e  q98 %.2e  max %.2e" % (np.median(err), np.quantile(err, 0.98), err.max()))
+    assert np.median(err) < 1e-3 and np.quantile(err, 0.8) < 1e-2 and err.max() < 0.5
+    # schedules that never quantise: every token within 1e-2 nats
+    ctx2 = sol.Sol(shape, NOQUANT_TABLE, dtype=sol.BF16, max_positions=T)
+    ids2 = synth.iid_actions(len(NOQUANT_TABLE), (B, G, T), 4003)
+    nll2 = host(ctx2.schedule_loglik(lw, hw, dev(tokens), dev(targets), dev(ids2)))
+    ref2 = oracle.schedule_loglik(oracle.make_cfg(shape, act_bf16=True), oracle.make_table(NOQUANT_TABLE),
+                                  head["embed"], layers, head["w_final_norm"], head["lm_head"], tokens, targets, ids2)
+    e2 = np.abs(nll2 - ref2)
+    print("no-quant nll err: median %.2e q95 %.2e max %.2e" % (np.median(e2), np.quantile(e2, 0.95), e2.max()))
+    assert np.quantile(e2, 0.95) < 1e-2 and e2.max() < 0.2
+    ctx2.close()
+    ctx.close()
+
+
+def test_device_flags_and_host_errors():
+    shape, table = SMALL_GQA, synth.TABLE_C2
+    w = dev_weights(synth.layer_weights(shape, 5000, bf16=True), sol.BF16)
+    ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=64)
+    x = dev(synth.hidden_states(1, 8, shape.d_model, 5001, bf16=True), sol.BF16)
+    kc = torch.zeros((1, shape.n_kv_heads, 16, shape.head_dim), dtype=torch.bfloat16, device="cuda")
+    vc = torch.zeros_like(kc)
+    ids = np.zeros((1, 8), np.int32)
+    ids[0, 3] = len(table) + 5
+    ctx.layer_forward(w, x, dev(ids), kc, vc)
+    assert ctx.device_status() == sol.ERR_ACTION and ctx.device_status() == sol.OK
+    ctx.layer_forward(w, x, dev(np.zeros((1, 8), np.int32)), kc, vc, pos0=dev(np.array([9], np.int32)))
+    assert ctx.device_status() == sol.ERR_CACHE_OVERFLOW
+    with pytest.raises(sol.SolError) as e:
+        ctx.layer_forward(w, x, dev(ids), kc, vc, workspace=torch.empty(1024, dtype=torch.uint8, device="cuda"))
+    assert e.value.code == sol.ERR_WORKSPACE
+    big = torch.zeros((1, shape.n_kv_heads, 128, shape.head_dim), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(sol.SolError) as e:
+        ctx.layer_forward(w, x, dev(ids), big, big.clone())          # L_max > max_positions
+    assert e.value.code == sol.ERR_INVALID_ARG
+    small = torch.zeros((1, shape.n_kv_heads, 4, shape.head_dim), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(sol.SolError) as e:
+        ctx.layer_forward(w, x, dev(ids), small, small.clone())      # T > L_max
+    assert e.value.code == sol.ERR_CACHE_OVERFLOW
+    # empty batch is a no-op
+    x0 = torch.zeros((0, 8, shape.d_model), dtype=torch.bfloat16, device="cuda")
+    ctx.layer_forward(w, x0, torch.zeros((0, 8), dtype=torch.int32, device="cuda"), kc[:0], vc[:0])
+    ctx.close()
