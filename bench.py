@@ -1,0 +1,227 @@
+#!/usr/bin/env python3
+"""Benchmark of the action-conditioned decoder-layer path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c5|c4|c5d|c3]
+
+A step is one pass of the measured unit over one batch of seeded synthetic input that is already
+resident in HBM. Default workload: the Llama-3.2-1B-shaped decoder layer, 4 inputs x 8 schedules
+x 1024 tokens, bf16, i.i.d. actions from the 4x4x4 action space (one sol_layer_forward call).
+Prints ONE JSON line (metric, value, roofline of the dominant kernel measured with HIP events
+around the library's stages, and the CPU oracle timed on a bounded sample).
+"""
+import argparse
+import json
+import math
+import sys
+import time
+
+import numpy as np
+import torch
+
+from paper_2605_10875_amd import sol, synth
+
+PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0        # MI355X HBM3E
+
+
+def _dev(a, bf16=True):
+    if np.issubdtype(a.dtype, np.integer):
+        return torch.from_numpy(np.ascontiguousarray(a, np.int32)).cuda()
+    t = torch.from_numpy(np.ascontiguousarray(a, np.float32)).cuda()
+    return t.to(torch.bfloat16).contiguous() if bf16 else t
+
+
+def layer_flops(shape, table, ids, pos):
+    """Algorithmic FLOPs of one decoder layer for the realised actions (per-token terms: q/k/v,
+    o, gate/up dense; down counted on the kept channels; all causal scores; P.V on the kept keys)."""
+    d, hq, hkv, dh, dff = shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_ff
+    t = np.array(table, dtype=np.int64)[ids.reshape(-1)]
+    n = pos.reshape(-1).astype(np.int64) + 1
+    m = np.clip(-(-(t[:, 2] * dff) // t[:, 3]), 1, dff)
+    k = np.clip(-(-(t[:, 0] * n) // t[:, 1]), 1, n)
+    lin = 2 * d * (hq + 2 * hkv) * dh + 2 * hq * dh * d + 4 * d * dff
+    return {"linear_dense": float(lin * len(n)), "down": float((2 * m * d).sum()),
+            "qk": float((2 * hq * dh * n).sum()), "pv": float((2 * hq * dh * k).sum())}
+
+
+def time_steps(fn, steps, warmup):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def stage_times(ctx, fn, steps):
+    ctx.profile_enable(64 * steps + 64)
+    for _ in range(steps):
+        fn()
+    st = ctx.profile_read()
+    ctx.profile_enable(0)
+    return {k: v[0] / steps for k, v in st.items()}, {k: v[1] // steps for k, v in st.items()}
+
+
+def run_layer(args, shape, n_inputs, G, T, table, name):
+    n_seq = n_inputs * G
+    w = synth.layer_weights(shape, args.seed, bf16=True)
+    x = synth.hidden_states(n_seq, T, shape.d_model, args.seed + 1, bf16=True)
+    ids = synth.iid_actions(len(table), (n_seq, T), args.seed + 2)
+    ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=T)
+    wd = {k: _dev(v) for k, v in w.items()}
+    xd, idd = _dev(x), _dev(ids)
+    kc = torch.zeros((n_seq, shape.n_kv_heads, T, shape.head_dim), dtype=torch.bfloat16, device="cuda")
+    vc = torch.zeros_like(kc)
+    out = torch.empty_like(xd)
+    ws = ctx.workspace(sol.OP_LAYER_FORWARD, n_seq, T, T)
+
+    def step():
+        ctx.layer_forward(wd, xd, idd, kc, vc, x_out=out, workspace=ws)
+
+    sec = time_steps(step, args.steps, args.warmup)
+    assert ctx.device_status() == sol.OK and bool(torch.isfinite(out.float()).all())
+    stages, launches = stage_times(ctx, step, max(2, min(args.steps, 5)))
+    tokens = n_seq * T
+    pos = np.tile(np.arange(T), (n_seq, 1))
+    fl = layer_flops(shape, table, ids, pos)
+    alg = fl["linear_dense"] + fl["down"] + fl["qk"] + fl["pv"]
+    dense = fl["linear_dense"] + 2.0 * shape.d_ff * shape.d_model * tokens + 2 * fl["qk"]
+    dom = "gate_up_gemm"
+    dom_flops = 4.0 * shape.d_model * shape.d_ff * tokens           # 4 d d_ff per token
+    ach = dom_flops / (stages[dom] * 1e-3) / 1e12
+    res = {
+        "metric": "schedule_tokens_per_s", "value": tokens / sec, "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": name, "entry_point": "sol_layer_forward", "n_inputs": n_inputs, "schedules": G,
+                   "seq_len": T, "tokens_per_step": tokens, "actions": "iid uniform over %d" % len(table)},
+        "roofline": {"bound": "mfma", "kernel": dom, "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": ach / PEAK_BF16_TFLOPS, "traffic": None, "kernel_ms": stages[dom],
+                     "launches_per_step": launches.get(dom)},
+        "layer": {"algorithmic_tflop": alg / 1e12, "algorithmic_tflops": alg / sec / 1e12,
+                  "algorithmic_frac_of_peak": alg / sec / 1e12 / PEAK_BF16_TFLOPS,
+                  "dense_equivalent_tflops": dense / sec / 1e12},
+        "stage_ms": {k: round(v, 4) for k, v in stages.items()},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        cfg = oracle.make_cfg(shape, act_bf16=True)
+        kco = np.zeros((1, shape.n_kv_heads, T, shape.head_dim), np.float32)
+        t0 = time.perf_counter()
+        ref, _ = oracle.layer_forward(cfg, oracle.make_table(table), w, x[:1], ids[:1], kco, kco.copy())
+        dt = time.perf_counter() - t0
+        got = out[0].float().cpu().numpy()
+        err = np.abs(got - ref[0]).max(axis=1) / np.abs(ref).max()
+        res["cpu_baseline"] = {"value": T / dt, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": "sequence 0 of %d, all %d tokens, one layer (%.1f s)" % (n_seq, T, dt),
+                               "gpu_vs_oracle_row_err_median": float(np.median(err))}
+    ctx.close()
+    return res
+
+
+def run_decode(args, shape, B, L, table, name, n_layers):
+    import dataclasses
+    shape = dataclasses.replace(shape, n_layers=n_layers)
+    gen = torch.Generator(device="cuda").manual_seed(args.seed)
+    layers = [synth.layer_weights(shape, args.seed + l, bf16=True) for l in range(1)]
+    lw = [{k: _dev(v) for k, v in layers[0].items()} for _ in range(1)]
+    # every layer gets its own weight tensors (distinct HBM) with the same seeded values
+    lw = lw + [{k: v.clone() for k, v in lw[0].items()} for _ in range(n_layers - 1)]
+    head = None
+    L_max = L + 8
+    kcs = [torch.randn((B, shape.n_kv_heads, L_max, shape.head_dim), generator=gen, device="cuda",
+                       dtype=torch.float32).to(torch.bfloat16) for _ in range(n_layers)]
+    vcs = [torch.randn((B, shape.n_kv_heads, L_max, shape.head_dim), generator=gen, device="cuda",
+                       dtype=torch.float32).to(torch.bfloat16) for _ in range(n_layers)]
+    ids = synth.iid_actions(len(table), (B,), args.seed + 2)
+    x = _dev(synth.hidden_states(1, B, shape.d_model, args.seed + 3, bf16=True)[0])
+    cache_len = torch.full((B,), L, dtype=torch.int32, device="cuda")
+    ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=L_max)
+    idd = _dev(ids)
+    ws = ctx.workspace(sol.OP_DECODE_STEP, B, 1, L_max)
+
+    def step():
+        return ctx.decode_step(lw, head, idd, cache_len, kcs, vcs, x_in=x, workspace=ws)[0]
+
+    sec = time_steps(step, args.steps, args.warmup)
+    hid = step()
+    assert ctx.device_status() == sol.OK and bool(torch.isfinite(hid.float()).all())
+    stages, launches = stage_times(ctx, step, 2)
+    # algorithmic bytes: weights once per layer, all of K, the V rows kept by at least one head of a group
+    d, hq, hkv, dh, dff = shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_ff
+    wbytes = 2 * (d * (hq + 2 * hkv) * dh + hq * dh * d + 3 * d * dff)
+    t = np.array(table, dtype=np.int64)[ids]
+    n = L + 1
+    kk = np.clip(-(-(t[:, 0] * n) // t[:, 1]), 1, n)
+    g = hq // hkv
+    union = n * (1.0 - (1.0 - kk / n) ** g)                  # expected distinct rows over g independent heads
+    kv_bytes = float((hkv * dh * 2 * (n + union)).sum())
+    alg_bytes = n_layers * (wbytes + kv_bytes)
+    dom = "attention_topk"
+    ach = (n_layers * kv_bytes) / (stages[dom] * 1e-3) / 1e9
+    res = {
+        "metric": "decode_tokens_per_s", "value": B / sec, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": name, "entry_point": "sol_decode_step", "batch": B, "cache_len": L, "layers": n_layers},
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": ach / PEAK_HBM_GBS, "traffic": None, "kernel_ms": stages[dom] / n_layers,
+                     "launches_per_step": launches.get(dom)},
+        "step": {"algorithmic_gb": alg_bytes / 1e9, "algorithmic_gbs": alg_bytes / sec / 1e9,
+                 "algorithmic_frac_of_peak": alg_bytes / sec / 1e9 / PEAK_HBM_GBS},
+        "stage_ms": {k: round(v, 4) for k, v in stages.items()},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        cfg = oracle.make_cfg(shape, act_bf16=True)
+        k0 = [kcs[0][:1].float().cpu().numpy().copy()]
+        v0 = [vcs[0][:1].float().cpu().numpy().copy()]
+        one = dataclasses.replace(shape, n_layers=1)
+        t0 = time.perf_counter()
+        oracle.decode_step(oracle.make_cfg(one, act_bf16=True), oracle.make_table(table), layers[:1],
+                           x[:1].float().cpu().numpy(), ids[:1], np.array([L], np.int32), k0, v0)
+        dt = time.perf_counter() - t0
+        res["cpu_baseline"] = {"value": 1.0 / (dt * n_layers), "unit": "tokens/s", "cores": oracle.num_threads(),
+                               "kind": "oracle", "sample": "sequence 0 of %d, one layer timed (%.2f s), scaled to %d layers"
+                               % (B, dt, n_layers)}
+        del cfg
+    ctx.close()
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c2", choices=["c2", "c5", "c4", "c5d"])
+    ap.add_argument("--seed", type=int, default=1234)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (sequences are independent; see DESIGN.md for how the path "
+              "would shard); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    if args.workload == "c2":
+        res = run_layer(args, synth.LLAMA_1B, 4, 8, 1024, synth.TABLE_C2,
+                        "C2: Llama-3.2-1B-shaped decoder layer, bf16, 4 inputs x 8 schedules x 1024 tokens")
+    elif args.workload == "c5":
+        res = run_layer(args, synth.LLAMA_8B, 2, 4, 4096, synth.TABLE_C2,
+                        "C5: Llama-3.1-8B-shaped decoder layer, bf16, 2 inputs x 4 schedules x 4096 tokens")
+    elif args.workload == "c4":
+        res = run_decode(args, synth.LLAMA_1B, 64, 8192, synth.TABLE_C4,
+                         "C4: Llama-3.2-1B-shaped decode step, bf16, 64 sequences x 8192-token KV cache, 16 layers", 16)
+    else:
+        res = run_decode(args, synth.LLAMA_8B, 32, 8192, synth.TABLE_C2,
+                         "C5-decode: Llama-3.1-8B-shaped decode step, bf16, 32 sequences x 8192-token KV cache, 1 layer", 1)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

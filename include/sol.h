@@ -173,6 +173,17 @@ int sol_schedule_loglik(sol_ctx *ctx, const sol_model_weights *weights,
  * SOL_ERR_CACHE_OVERFLOW (a sequence was skipped because pos0 + T > L_max). */
 int sol_device_status(sol_ctx *ctx, void *stream);
 
+/* Per-stage timing for measurement. sol_profile_enable(ctx, n) with n > 0 creates up to n pairs of
+ * HIP events and makes every following call bracket each stage of the path (one stage = the
+ * kernel(s) of one step: qkv_gemm, attention_topk, gate_up_gemm, ...) with events on the caller's
+ * stream; n <= 0 switches it off. sol_profile_read synchronises `stream`, writes for each stage its
+ * name (static string), the summed milliseconds and the number of recorded brackets since the last
+ * read into the caller's HOST arrays of max_stages entries, clears the records and returns the
+ * number of stages written (or a negative status). Records beyond n are dropped silently. */
+int sol_profile_enable(sol_ctx *ctx, int max_stage_records);
+int sol_profile_read(sol_ctx *ctx, void *stream, int max_stages, const char **names_out, float *ms_out,
+                     int *calls_out);
+
 /* ---- unit hooks: the selection / quantisation device code on caller-supplied fp32 data ----
  * All pointers device; results are exact integer decisions and must match the definitions
  * bit for bit. */

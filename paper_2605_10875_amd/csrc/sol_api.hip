@@ -14,6 +14,15 @@
 
 using namespace sol;
 
+enum Stage {
+    ST_PREPARE = 0, ST_NORM_IN, ST_QKV, ST_ROPE, ST_ATTN, ST_QUANT_O, ST_OPROJ, ST_NORM_POST, ST_GATEUP, ST_SILU,
+    ST_PRUNE, ST_DOWN, ST_RESID, ST_EMBED, ST_NORM_FINAL, ST_LMHEAD, ST_NLL, ST_COUNT
+};
+static const char *const STAGE_NAMES[ST_COUNT] = {
+    "prepare_actions", "norm_in_quant", "qkv_gemm", "rope_cache_write", "attention_topk", "quant_o", "o_proj_gemm",
+    "norm_post_quant", "gate_up_gemm", "silu_mul", "prune_quant", "down_gemm", "residual_out", "embed",
+    "norm_final", "lm_head_gemm", "nll_rows"};
+
 struct sol_ctx {
     sol_model_cfg cfg;
     int n_actions = 0;
@@ -22,7 +31,31 @@ struct sol_ctx {
     float2 *d_rope = nullptr;
     int *d_flags = nullptr;
     std::string err;
+    // optional per-stage timing (sol_profile_*): pairs of events recorded around each stage
+    bool prof = false;
+    std::vector<hipEvent_t> ev;
+    std::vector<int> ev_stage;     // stage of pair i (events 2i, 2i+1)
+    size_t ev_used = 0;
 };
+
+// Brackets one stage with events on the stream while profiling is on (no-op otherwise).
+struct StageTimer {
+    sol_ctx *c; hipStream_t st; bool on;
+    StageTimer(sol_ctx *ctx, int stage, hipStream_t s) : c(ctx), st(s), on(false)
+    {
+        if (!c->prof || 2 * (c->ev_used + 1) > c->ev.size()) return;
+        on = true;
+        c->ev_stage[c->ev_used] = stage;
+        (void)hipEventRecord(c->ev[2 * c->ev_used], st);
+    }
+    ~StageTimer()
+    {
+        if (!on) return;
+        (void)hipEventRecord(c->ev[2 * c->ev_used + 1], st);
+        c->ev_used++;
+    }
+};
+#define STAGE(ctx, id, st) StageTimer stage_timer_##id(ctx, id, st)
 
 static thread_local std::string g_create_err;
 static const int MAX_ACTIONS = 4096;
@@ -166,7 +199,40 @@ extern "C" void sol_destroy(sol_ctx *ctx)
     (void)hipFree(ctx->d_table);
     (void)hipFree(ctx->d_rope);
     (void)hipFree(ctx->d_flags);
+    for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
     delete ctx;
+}
+
+extern "C" int sol_profile_enable(sol_ctx *ctx, int max_stage_records)
+{
+    if (!ctx) return SOL_ERR_INVALID_ARG;
+    if (max_stage_records <= 0) { ctx->prof = false; return SOL_OK; }
+    while (ctx->ev.size() < 2 * (size_t)max_stage_records) {
+        hipEvent_t e;
+        SOL_HIP(ctx, hipEventCreate(&e));
+        ctx->ev.push_back(e);
+    }
+    ctx->ev_stage.resize(ctx->ev.size() / 2);
+    ctx->ev_used = 0;
+    ctx->prof = true;
+    return SOL_OK;
+}
+
+extern "C" int sol_profile_read(sol_ctx *ctx, void *stream, int max_stages, const char **names_out, float *ms_out,
+                                int *calls_out)
+{
+    if (!ctx || !names_out || !ms_out || !calls_out || max_stages < 0) return SOL_ERR_INVALID_ARG;
+    SOL_HIP(ctx, hipStreamSynchronize((hipStream_t)stream));
+    const int n = max_stages < (int)ST_COUNT ? max_stages : (int)ST_COUNT;
+    for (int i = 0; i < n; ++i) { names_out[i] = STAGE_NAMES[i]; ms_out[i] = 0.f; calls_out[i] = 0; }
+    for (size_t i = 0; i < ctx->ev_used; ++i) {
+        float ms = 0.f;
+        SOL_HIP(ctx, hipEventElapsedTime(&ms, ctx->ev[2 * i], ctx->ev[2 * i + 1]));
+        const int sidx = ctx->ev_stage[i];
+        if (sidx < n) { ms_out[sidx] += ms; calls_out[sidx] += 1; }
+    }
+    ctx->ev_used = 0;
+    return n;
 }
 
 extern "C" int sol_device_status(sol_ctx *ctx, void *stream)
@@ -272,6 +338,7 @@ extern "C" size_t sol_workspace_bytes(const sol_model_cfg *cfg, int op, int n_se
 // ------------------------------------------------------------------------------------------------
 static void prepare_actions(sol_ctx *ctx, const int32_t *ids, int64_t M, LayerWs &w, hipStream_t st)
 {
+    STAGE(ctx, ST_PREPARE, st);
     launch_prepare_rows(ids, ctx->d_table, ctx->n_actions, ctx->cfg.d_ff, M, w.ra, w.row_bucket, ctx->d_flags, st);
     launch_bucket_sort(w.row_bucket, M, ctx->n_buckets, w.perm, w.bucket_off, st);
 }
@@ -287,30 +354,58 @@ static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_i
     const int nq = Hq * dh, nkv = Hkv * dh, nqkv = nq + 2 * nkv;
     const uint32_t qs = g.quant_sites;
 
-    // input norm + quantise (linear-input site of q/k/v)
-    launch_rmsnorm_fq(x_in, dt, nullptr, nullptr, lw->w_in_norm, dt, w.h, dt, w.ra, qs & SOL_QS_QKV_IN, M, d, g.rms_eps, st);
-    // q/k/v projections, rotary, cache write
-    launch_gemm_generic(w.h, dt, d, lw->wq, dt, d, w.big32, nqkv, M, nq, d, st);
-    launch_gemm_generic(w.h, dt, d, lw->wk, dt, d, w.big32 + nq, nqkv, M, nkv, d, st);
-    launch_gemm_generic(w.h, dt, d, lw->wv, dt, d, w.big32 + nq + nkv, nqkv, M, nkv, d, st);
-    launch_rope_store(w.big32, w.qb, kc, vc, dt, ctx->d_rope, pos0, n_seq, T, L_max, Hq, Hkv, dh, ctx->d_flags, st);
-    // scores, budgeted selection, softmax over kept keys, times V
-    if (!launch_attn_rows(w.qb, kc, vc, dt, w.o32, w.ra, pos0, n_seq, T, L_max, Hq, Hkv, dh, ctx->d_flags, st))
-        return fail(ctx, SOL_ERR_UNSUPPORTED, "attention: L_max too long for the on-chip score rows of this build");
-    // quantise (o-proj input), output projection, residual
-    launch_fq_rows(w.o32, w.qb, dt, w.ra, qs & SOL_QS_O_IN, M, nq, st);
-    launch_gemm_generic(w.qb, dt, nq, lw->wo, dt, nq, w.big32, d, M, d, nq, st);
-    // x2 = x + attn ; post norm + quantise (gate/up input)
-    launch_rmsnorm_fq(x_in, dt, w.big32, w.x2, lw->w_post_norm, dt, w.h, dt, w.ra, qs & SOL_QS_GATEUP_IN, M, d, g.rms_eps, st);
-    // gate / up, SiLU(gate)*up
-    launch_gemm_generic(w.h, dt, d, lw->w_gate, dt, d, w.big32, 2 * (int64_t)dff, M, dff, d, st);
-    launch_gemm_generic(w.h, dt, d, lw->w_up, dt, d, w.big32 + dff, 2 * (int64_t)dff, M, dff, d, st);
-    launch_silu_mul(w.big32, w.a, dt, M, dff, st);
-    // magnitude pruning + quantise (down input), rows visited in bucket order
-    launch_prune_fq(w.a, dt, w.ra, w.perm, qs & SOL_QS_DOWN_IN, M, dff, st);
-    // down projection + residual
-    launch_gemm_generic(w.a, dt, dff, lw->w_down, dt, dff, w.big32, d, M, d, dff, st);
-    launch_resid_out(w.x2, w.big32, x_out, dt, M, d, st);
+    {   // input norm + quantise (linear-input site of q/k/v)
+        STAGE(ctx, ST_NORM_IN, st);
+        launch_rmsnorm_fq(x_in, dt, nullptr, nullptr, lw->w_in_norm, dt, w.h, dt, w.ra, qs & SOL_QS_QKV_IN, M, d, g.rms_eps, st);
+    }
+    {   // q/k/v projections
+        STAGE(ctx, ST_QKV, st);
+        launch_gemm_generic(w.h, dt, d, lw->wq, dt, d, w.big32, nqkv, M, nq, d, st);
+        launch_gemm_generic(w.h, dt, d, lw->wk, dt, d, w.big32 + nq, nqkv, M, nkv, d, st);
+        launch_gemm_generic(w.h, dt, d, lw->wv, dt, d, w.big32 + nq + nkv, nqkv, M, nkv, d, st);
+    }
+    {   // rotary, cache write
+        STAGE(ctx, ST_ROPE, st);
+        launch_rope_store(w.big32, w.qb, kc, vc, dt, ctx->d_rope, pos0, n_seq, T, L_max, Hq, Hkv, dh, ctx->d_flags, st);
+    }
+    {   // scores, budgeted selection, softmax over kept keys, times V
+        STAGE(ctx, ST_ATTN, st);
+        if (!launch_attn_rows(w.qb, kc, vc, dt, w.o32, w.ra, pos0, n_seq, T, L_max, Hq, Hkv, dh, ctx->d_flags, st))
+            return fail(ctx, SOL_ERR_UNSUPPORTED, "attention: L_max too long for the on-chip score rows of this build");
+    }
+    {   // quantise (o-proj input)
+        STAGE(ctx, ST_QUANT_O, st);
+        launch_fq_rows(w.o32, w.qb, dt, w.ra, qs & SOL_QS_O_IN, M, nq, st);
+    }
+    {   // output projection
+        STAGE(ctx, ST_OPROJ, st);
+        launch_gemm_generic(w.qb, dt, nq, lw->wo, dt, nq, w.big32, d, M, d, nq, st);
+    }
+    {   // x2 = x + attn ; post norm + quantise (gate/up input)
+        STAGE(ctx, ST_NORM_POST, st);
+        launch_rmsnorm_fq(x_in, dt, w.big32, w.x2, lw->w_post_norm, dt, w.h, dt, w.ra, qs & SOL_QS_GATEUP_IN, M, d, g.rms_eps, st);
+    }
+    {   // gate / up
+        STAGE(ctx, ST_GATEUP, st);
+        launch_gemm_generic(w.h, dt, d, lw->w_gate, dt, d, w.big32, 2 * (int64_t)dff, M, dff, d, st);
+        launch_gemm_generic(w.h, dt, d, lw->w_up, dt, d, w.big32 + dff, 2 * (int64_t)dff, M, dff, d, st);
+    }
+    {   // SiLU(gate)*up
+        STAGE(ctx, ST_SILU, st);
+        launch_silu_mul(w.big32, w.a, dt, M, dff, st);
+    }
+    {   // magnitude pruning + quantise (down input), rows visited in bucket order
+        STAGE(ctx, ST_PRUNE, st);
+        launch_prune_fq(w.a, dt, w.ra, w.perm, qs & SOL_QS_DOWN_IN, M, dff, st);
+    }
+    {   // down projection
+        STAGE(ctx, ST_DOWN, st);
+        launch_gemm_generic(w.a, dt, dff, lw->w_down, dt, dff, w.big32, d, M, d, dff, st);
+    }
+    {   // residual
+        STAGE(ctx, ST_RESID, st);
+        launch_resid_out(w.x2, w.big32, x_out, dt, M, d, st);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(ctx, SOL_ERR_HIP, std::string("kernel launch: ") + hipGetErrorString(e));
     return SOL_OK;
@@ -354,14 +449,23 @@ static int nll_impl(sol_ctx *ctx, const sol_model_weights *mw, const void *x, in
 {
     const sol_model_cfg &g = ctx->cfg;
     const int dt = g.dtype;
-    launch_rmsnorm_fq(x, dt, nullptr, nullptr, mw->w_final_norm, dt, w.hf, dt, nullptr, false, M, g.d_model, g.rms_eps, st);
+    {
+        STAGE(ctx, ST_NORM_FINAL, st);
+        launch_rmsnorm_fq(x, dt, nullptr, nullptr, mw->w_final_norm, dt, w.hf, dt, nullptr, false, M, g.d_model, g.rms_eps, st);
+    }
     const int64_t chunk = lm_chunk_rows(g, M);
     const size_t es = esize(dt);
     for (int64_t r0 = 0; r0 < M; r0 += chunk) {
         const int64_t rows = (M - r0 < chunk) ? M - r0 : chunk;
-        launch_gemm_generic((const char *)w.hf + es * r0 * g.d_model, dt, g.d_model, mw->lm_head, dt, g.d_model,
-                            w.logits, g.vocab, rows, g.vocab, g.d_model, st);
-        launch_nll_rows(w.logits, rows, g.vocab, targets, r0, G, T, broadcast_g, nll_out, st);
+        {
+            STAGE(ctx, ST_LMHEAD, st);
+            launch_gemm_generic((const char *)w.hf + es * r0 * g.d_model, dt, g.d_model, mw->lm_head, dt, g.d_model,
+                                w.logits, g.vocab, rows, g.vocab, g.d_model, st);
+        }
+        {
+            STAGE(ctx, ST_NLL, st);
+            launch_nll_rows(w.logits, rows, g.vocab, targets, r0, G, T, broadcast_g, nll_out, st);
+        }
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(ctx, SOL_ERR_HIP, std::string("kernel launch: ") + hipGetErrorString(e));
@@ -442,7 +546,10 @@ extern "C" int sol_schedule_loglik(sol_ctx *ctx, const sol_model_weights *mw, co
     StackWs w; carve_stack(c, g, N, T, true, w);
     const int64_t M = (int64_t)N * T;
     prepare_actions(ctx, action_ids, M, w.layer, st);          // one plan, reused by every layer
-    launch_embed(mw->embed, tokens, w.xa, g.dtype, B, G, T, g.d_model, g.vocab, st);
+    {
+        STAGE(ctx, ST_EMBED, st);
+        launch_embed(mw->embed, tokens, w.xa, g.dtype, B, G, T, g.d_model, g.vocab, st);
+    }
     void *cur = w.xa, *nxt = w.xb;
     for (int l = 0; l < g.n_layers; ++l) {
         if (int rc = layer_impl(ctx, &mw->layers[l], cur, nxt, nullptr, w.kc, w.vc, N, T, T, w.layer, st)) return rc;

@@ -18,6 +18,7 @@ OP_LAYER_FORWARD, OP_DECODE_STEP, OP_SCHEDULE_LOGLIK = 0, 1, 2
 
 EXPORTS = ("sol_validate_config", "sol_create", "sol_destroy", "sol_last_error", "sol_workspace_bytes",
            "sol_layer_forward", "sol_decode_step", "sol_schedule_loglik", "sol_device_status",
+           "sol_profile_enable", "sol_profile_read",
            "sol_test_topk_select", "sol_test_prune_mask", "sol_test_quant_codes")
 
 
@@ -83,6 +84,9 @@ def lib():
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.sol_schedule_loglik.argtypes = [C.c_void_p, C.POINTER(ModelWeights), C.c_void_p, C.c_void_p, C.c_void_p,
                                           C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.sol_profile_enable.argtypes = [C.c_void_p, C.c_int]
+        L.sol_profile_read.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(C.c_char_p), C.POINTER(C.c_float),
+                                       C.POINTER(C.c_int)]
         L.sol_test_topk_select.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.sol_test_prune_mask.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
         L.sol_test_quant_codes.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -244,6 +248,20 @@ class Sol:
         del keep
         self._check(rc)
         return nll_out
+
+    def profile_enable(self, max_stage_records):
+        self._check(self.L.sol_profile_enable(self.handle, max_stage_records))
+
+    def profile_read(self, stream=None):
+        """Returns {stage name: (total ms, brackets)} since the last read (synchronises the stream)."""
+        n = 32
+        names = (C.c_char_p * n)()
+        ms = (C.c_float * n)()
+        calls = (C.c_int * n)()
+        got = self.L.sol_profile_read(self.handle, _stream(stream), n, names, ms, calls)
+        if got < 0:
+            self._check(got)
+        return {names[i].decode(): (float(ms[i]), int(calls[i])) for i in range(got) if calls[i]}
 
     def device_status(self, stream=None):
         return int(self.L.sol_device_status(self.handle, _stream(stream)))
