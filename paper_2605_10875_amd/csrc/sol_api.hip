@@ -358,13 +358,19 @@ static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_i
         STAGE(ctx, ST_NORM_IN, st);
         launch_rmsnorm_fq(x_in, dt, nullptr, nullptr, lw->w_in_norm, dt, w.h, dt, w.ra, qs & SOL_QS_QKV_IN, M, d, g.rms_eps, st);
     }
-    {   // q/k/v projections
+    const bool mfma = dt == SOL_BF16;
+    bool fused_qkv = false;
+    {   // q/k/v projections (+ rotary and cache write when fused)
         STAGE(ctx, ST_QKV, st);
-        launch_gemm_generic(w.h, dt, d, lw->wq, dt, d, w.big32, nqkv, M, nq, d, st);
-        launch_gemm_generic(w.h, dt, d, lw->wk, dt, d, w.big32 + nq, nqkv, M, nkv, d, st);
-        launch_gemm_generic(w.h, dt, d, lw->wv, dt, d, w.big32 + nq + nkv, nqkv, M, nkv, d, st);
+        fused_qkv = mfma && launch_gemm_qkv_rope(w.h, lw->wq, lw->wk, lw->wv, w.qb, kc, vc, ctx->d_rope, pos0, n_seq, T,
+                                                 L_max, Hq, Hkv, dh, d, ctx->d_flags, st);
+        if (!fused_qkv) {
+            launch_gemm_generic(w.h, dt, d, lw->wq, dt, d, w.big32, nqkv, M, nq, d, st);
+            launch_gemm_generic(w.h, dt, d, lw->wk, dt, d, w.big32 + nq, nqkv, M, nkv, d, st);
+            launch_gemm_generic(w.h, dt, d, lw->wv, dt, d, w.big32 + nq + nkv, nqkv, M, nkv, d, st);
+        }
     }
-    {   // rotary, cache write
+    if (!fused_qkv) {   // rotary, cache write
         STAGE(ctx, ST_ROPE, st);
         launch_rope_store(w.big32, w.qb, kc, vc, dt, ctx->d_rope, pos0, n_seq, T, L_max, Hq, Hkv, dh, ctx->d_flags, st);
     }
@@ -377,20 +383,29 @@ static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_i
         STAGE(ctx, ST_QUANT_O, st);
         launch_fq_rows(w.o32, w.qb, dt, w.ra, qs & SOL_QS_O_IN, M, nq, st);
     }
-    {   // output projection
+    bool fused_o = false;
+    {   // output projection (+ residual when fused: x2 = x + attn)
         STAGE(ctx, ST_OPROJ, st);
-        launch_gemm_generic(w.qb, dt, nq, lw->wo, dt, nq, w.big32, d, M, d, nq, st);
+        fused_o = mfma && launch_gemm_resid_f32(w.qb, lw->wo, x_in, w.x2, M, d, nq, st);
+        if (!fused_o) launch_gemm_generic(w.qb, dt, nq, lw->wo, dt, nq, w.big32, d, M, d, nq, st);
     }
-    {   // x2 = x + attn ; post norm + quantise (gate/up input)
+    {   // post norm + quantise (gate/up input)
         STAGE(ctx, ST_NORM_POST, st);
-        launch_rmsnorm_fq(x_in, dt, w.big32, w.x2, lw->w_post_norm, dt, w.h, dt, w.ra, qs & SOL_QS_GATEUP_IN, M, d, g.rms_eps, st);
+        if (fused_o)
+            launch_rmsnorm_fq(w.x2, SOL_F32, nullptr, nullptr, lw->w_post_norm, dt, w.h, dt, w.ra, qs & SOL_QS_GATEUP_IN, M, d, g.rms_eps, st);
+        else
+            launch_rmsnorm_fq(x_in, dt, w.big32, w.x2, lw->w_post_norm, dt, w.h, dt, w.ra, qs & SOL_QS_GATEUP_IN, M, d, g.rms_eps, st);
     }
-    {   // gate / up
+    bool fused_gu = false;
+    {   // gate / up (+ SiLU(gate)*up when fused)
         STAGE(ctx, ST_GATEUP, st);
-        launch_gemm_generic(w.h, dt, d, lw->w_gate, dt, d, w.big32, 2 * (int64_t)dff, M, dff, d, st);
-        launch_gemm_generic(w.h, dt, d, lw->w_up, dt, d, w.big32 + dff, 2 * (int64_t)dff, M, dff, d, st);
+        fused_gu = mfma && launch_gemm_gateup_silu(w.h, lw->w_gate, lw->w_up, w.a, M, dff, d, st);
+        if (!fused_gu) {
+            launch_gemm_generic(w.h, dt, d, lw->w_gate, dt, d, w.big32, 2 * (int64_t)dff, M, dff, d, st);
+            launch_gemm_generic(w.h, dt, d, lw->w_up, dt, d, w.big32 + dff, 2 * (int64_t)dff, M, dff, d, st);
+        }
     }
-    {   // SiLU(gate)*up
+    if (!fused_gu) {   // SiLU(gate)*up
         STAGE(ctx, ST_SILU, st);
         launch_silu_mul(w.big32, w.a, dt, M, dff, st);
     }
@@ -398,11 +413,13 @@ static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_i
         STAGE(ctx, ST_PRUNE, st);
         launch_prune_fq(w.a, dt, w.ra, w.perm, qs & SOL_QS_DOWN_IN, M, dff, st);
     }
-    {   // down projection
+    bool fused_down = false;
+    {   // down projection (+ residual when fused)
         STAGE(ctx, ST_DOWN, st);
-        launch_gemm_generic(w.a, dt, dff, lw->w_down, dt, dff, w.big32, d, M, d, dff, st);
+        fused_down = mfma && launch_gemm_resid_out(w.a, lw->w_down, w.x2, x_out, M, d, dff, st);
+        if (!fused_down) launch_gemm_generic(w.a, dt, dff, lw->w_down, dt, dff, w.big32, d, M, d, dff, st);
     }
-    {   // residual
+    if (!fused_down) {   // residual
         STAGE(ctx, ST_RESID, st);
         launch_resid_out(w.x2, w.big32, x_out, dt, M, d, st);
     }

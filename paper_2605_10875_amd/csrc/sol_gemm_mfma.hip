@@ -1,0 +1,362 @@
+// bf16 MFMA GEMM for gfx950 with fused epilogues:  C[M][Nv] = A[M][K] * Wv[Nv][K]^T, fp32 accumulate.
+//
+// Both operands are K-contiguous, which is the layout v_mfma_f32_32x32x16_bf16 wants for A and B
+// alike (each lane supplies 8 consecutive k of one row / one column). "Nv" is a virtual column
+// space: a column maps to a row of one of up to three weight matrices (q|k|v stacked, or gate and
+// up interleaved in 64-column halves so that SiLU(gate)*up is formed inside one wave tile).
+//
+// Tiling: workgroup tile BM x BN, K step 64; waves in a (BM/WM) x (BN/WN) grid, each wave owning
+// WM x WN = (WM/32) x (WN/32) MFMA tiles of 32x32 in accumulator registers. A and B K-slices are
+// staged through LDS (two stages, XOR-swizzled 16-byte chunks so that the 128-bit fragment reads
+// are bank-conflict free) with the next slice prefetched into registers while the MFMAs of the
+// current slice issue. Workgroups are mapped to tiles XCD-aware: each of the 8 XCDs walks its own
+// contiguous band of the tile grid in groups of GROUP_M tile rows, so the tiles resident on an
+// XCD at any time share A rows and B columns in that XCD's L2.
+//
+// Epilogue: accumulators are spilled 32 rows at a time through LDS into row-contiguous order and
+// handed to an epilogue functor 4 columns per lane (rotary + cache write, residual add,
+// SiLU(gate)*up, plain store).
+#include "sol_internal.h"
+
+namespace sol {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16_t;
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));   // native 16-byte vector (stays in registers)
+
+constexpr int BK = 64;               // K step (bf16 elements); one LDS row = 128 bytes = 8 chunks of 16 B
+constexpr int GROUP_M = 8;           // tile rows walked together by an XCD
+
+struct BMap {                        // virtual column -> weight row
+    const bf16_t *base[3];
+    int seg_end[3];                  // mode 0: virtual columns [seg_end[i-1], seg_end[i]) belong to base[i]
+    int mode;                        // 0 = stacked segments, 1 = gate/up interleaved in halves of `half`
+    int half;
+    int64_t ld;
+    __device__ __forceinline__ const bf16_t *row(int v) const
+    {
+        if (mode == 0) {
+            if (v < seg_end[0]) return base[0] + (int64_t)v * ld;
+            if (v < seg_end[1]) return base[1] + (int64_t)(v - seg_end[0]) * ld;
+            return base[2] + (int64_t)(v - seg_end[1]) * ld;
+        }
+        const int blk = v / (2 * half), w = v - blk * 2 * half;
+        const int r = blk * half + (w < half ? w : w - half);
+        return (w < half ? base[0] : base[1]) + (int64_t)r * ld;
+    }
+};
+
+// ------------------------------------------------------------------------------------------------
+// epilogues: apply(row, vcol0, lc, lrow) handles local columns [lc, lc+4) of a wave-tile row whose
+// first virtual column is vcol0; lrow points at the fp32 row in LDS (WN floats).
+// ------------------------------------------------------------------------------------------------
+struct EpiStoreF32 {
+    float *C; int64_t ldc;
+    template <int WN> __device__ __forceinline__ void apply(int64_t row, int vcol0, int lc, const float *lrow) const
+    {
+        *reinterpret_cast<float4 *>(C + row * ldc + vcol0 + lc) = *reinterpret_cast<const float4 *>(lrow + lc);
+    }
+};
+
+// x2 = resid + acc  (fp32 out), resid in bf16
+struct EpiResidF32 {
+    const bf16_t *resid; float *out; int64_t ld;
+    template <int WN> __device__ __forceinline__ void apply(int64_t row, int vcol0, int lc, const float *lrow) const
+    {
+        const float4 v = *reinterpret_cast<const float4 *>(lrow + lc);
+        const uint2 r = *reinterpret_cast<const uint2 *>(resid + row * ld + vcol0 + lc);
+        float4 o;
+        o.x = v.x + __uint_as_float(r.x << 16);
+        o.y = v.y + __uint_as_float(r.x & 0xFFFF0000u);
+        o.z = v.z + __uint_as_float(r.y << 16);
+        o.w = v.w + __uint_as_float(r.y & 0xFFFF0000u);
+        *reinterpret_cast<float4 *>(out + row * ld + vcol0 + lc) = o;
+    }
+};
+
+// out = bf16(x2 + acc), x2 in fp32
+struct EpiResidOut {
+    const float *x2; bf16_t *out; int64_t ld;
+    template <int WN> __device__ __forceinline__ void apply(int64_t row, int vcol0, int lc, const float *lrow) const
+    {
+        const float4 v = *reinterpret_cast<const float4 *>(lrow + lc);
+        const float4 r = *reinterpret_cast<const float4 *>(x2 + row * ld + vcol0 + lc);
+        uint2 o;
+        o.x = (uint32_t)f32_to_bf16(v.x + r.x) | ((uint32_t)f32_to_bf16(v.y + r.y) << 16);
+        o.y = (uint32_t)f32_to_bf16(v.z + r.z) | ((uint32_t)f32_to_bf16(v.w + r.w) << 16);
+        *reinterpret_cast<uint2 *>(out + row * ld + vcol0 + lc) = o;
+    }
+};
+
+// a = bf16(silu(gate) * up); the wave tile's first WN/2 columns are gate, the rest the matching up
+struct EpiSiluMul {
+    bf16_t *a; int64_t ld;   // [M][d_ff]
+    template <int WN> __device__ __forceinline__ void apply(int64_t row, int vcol0, int lc, const float *lrow) const
+    {
+        if (lc >= WN / 2) return;
+        const float4 g = *reinterpret_cast<const float4 *>(lrow + lc);
+        const float4 u = *reinterpret_cast<const float4 *>(lrow + WN / 2 + lc);
+        const float a0 = (g.x / (1.0f + expf(-g.x))) * u.x, a1 = (g.y / (1.0f + expf(-g.y))) * u.y;
+        const float a2 = (g.z / (1.0f + expf(-g.z))) * u.z, a3 = (g.w / (1.0f + expf(-g.w))) * u.w;
+        uint2 o;
+        o.x = (uint32_t)f32_to_bf16(a0) | ((uint32_t)f32_to_bf16(a1) << 16);
+        o.y = (uint32_t)f32_to_bf16(a2) | ((uint32_t)f32_to_bf16(a3) << 16);
+        *reinterpret_cast<uint2 *>(a + row * ld + (vcol0 / WN) * (WN / 2) + lc) = o;
+    }
+};
+
+// rotary embedding on q and k heads (pairs (c, c + dh/2)), q -> [M][nq], k/v -> caches
+struct EpiQkvRope {
+    bf16_t *q, *kc, *vc;
+    const float2 *rope; const int32_t *pos0;
+    int Tn, L_max, Hq, Hkv, dh; int *flags;
+    template <int WN> __device__ __forceinline__ void apply(int64_t row, int vcol0, int lc, const float *lrow) const
+    {
+        const int s = (int)(row / Tn), i = (int)(row - (int64_t)s * Tn);
+        const int p0 = pos0 ? pos0[s] : 0;
+        if (p0 < 0 || p0 + Tn > L_max) { if (lc == 0 && vcol0 == 0 && i == 0) atomicOr(flags, FLAG_CACHE_OVERFLOW); return; }
+        const int pos = p0 + i, half = dh >> 1;
+        const int v = vcol0 + lc;                       // virtual column of the first of 4 values
+        const int nq = Hq * dh, nkv = Hkv * dh;
+        const float4 x = *reinterpret_cast<const float4 *>(lrow + lc);
+        float o[4] = {x.x, x.y, x.z, x.w};
+        if (v < nq + nkv) {                             // q or k: rotate
+            const int c = v % dh;                       // position inside the head (4 values stay in one half)
+            const bool lo = c < half;
+            const float4 y = *reinterpret_cast<const float4 *>(lrow + lc + (lo ? half : -half));
+            const float yy[4] = {y.x, y.y, y.z, y.w};
+            const float2 *cs = rope + (int64_t)pos * half + (lo ? c : c - half);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float2 t = cs[e];
+                o[e] = lo ? (o[e] * t.x - yy[e] * t.y) : (o[e] * t.x + yy[e] * t.y);
+            }
+        }
+        uint2 pk;
+        pk.x = (uint32_t)f32_to_bf16(o[0]) | ((uint32_t)f32_to_bf16(o[1]) << 16);
+        pk.y = (uint32_t)f32_to_bf16(o[2]) | ((uint32_t)f32_to_bf16(o[3]) << 16);
+        bf16_t *dst;
+        if (v < nq) dst = q + row * (int64_t)nq + v;
+        else if (v < nq + nkv) { const int w = v - nq; dst = kc + (((int64_t)s * Hkv + w / dh) * L_max + pos) * dh + w % dh; }
+        else { const int w = v - nq - nkv; dst = vc + (((int64_t)s * Hkv + w / dh) * L_max + pos) * dh + w % dh; }
+        *reinterpret_cast<uint2 *>(dst) = pk;
+    }
+};
+
+// ------------------------------------------------------------------------------------------------
+// the kernel
+// ------------------------------------------------------------------------------------------------
+template <int BM, int BN, int WM, int WN, class Epi>
+__global__ void __launch_bounds__((BM / WM) * (BN / WN) * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
+k_gemm_mfma(const bf16_t *__restrict__ A, int64_t lda, BMap bmap, int64_t M, int Nv, int K, int tiles_m, int tiles_n,
+            Epi epi)
+{
+    constexpr int NWM = BM / WM, NWN = BN / WN, NT = NWM * NWN * 64;
+    constexpr int TM = WM / 32, TN = WN / 32;
+    constexpr int ROWS_PER_PASS = NT / 8;                 // 8 threads (16-byte chunks) per 128-byte row
+    constexpr int A_PASSES = BM / ROWS_PER_PASS, B_PASSES = BN / ROWS_PER_PASS;
+    constexpr int STAGE_BYTES = (BM + BN) * 128;
+    static_assert(BM % ROWS_PER_PASS == 0 && BN % ROWS_PER_PASS == 0, "tile / thread mismatch");
+    extern __shared__ __align__(16) unsigned char lds[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / NWN, wn = wave - wm * NWN;
+
+    // ---- XCD-aware tile mapping: workgroup b runs on XCD b % 8; XCD x owns a contiguous band ----
+    const int n_tiles = tiles_m * tiles_n;
+    const int per_xcd = (n_tiles + 7) / 8;
+    const int lin = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    if (lin >= n_tiles) return;
+    const int group_sz = GROUP_M * tiles_n;
+    const int grp = lin / group_sz, in_grp = lin - grp * group_sz;
+    const int rows_here = (tiles_m - grp * GROUP_M) < GROUP_M ? (tiles_m - grp * GROUP_M) : GROUP_M;
+    const int tm = grp * GROUP_M + in_grp % rows_here, tn = in_grp / rows_here;
+    const int64_t m0 = (int64_t)tm * BM;
+    const int n0 = tn * BN;
+
+    // ---- per-thread global sources and LDS destinations of the staged K slices ----
+    const int chunk = tid & 7, r_in_pass = tid >> 3;
+    const bf16_t *a_src[A_PASSES];
+    const bf16_t *b_src[B_PASSES];
+    int a_dst[A_PASSES], b_dst[B_PASSES];
+#pragma unroll
+    for (int p = 0; p < A_PASSES; ++p) {
+        const int rl = p * ROWS_PER_PASS + r_in_pass;
+        int64_t gr = m0 + rl;
+        if (gr >= M) gr = M - 1;                            // ragged last tile: re-read the last row, never stored
+        a_src[p] = A + gr * lda + chunk * 8;
+        a_dst[p] = rl * 128 + ((chunk ^ (rl & 7)) << 4);
+    }
+#pragma unroll
+    for (int p = 0; p < B_PASSES; ++p) {
+        const int rl = p * ROWS_PER_PASS + r_in_pass;
+        b_src[p] = bmap.row(n0 + rl) + chunk * 8;
+        b_dst[p] = BM * 128 + rl * 128 + ((chunk ^ (rl & 7)) << 4);
+    }
+
+    floatx16_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    u32x4_t a_reg[A_PASSES], b_reg[B_PASSES];
+    const int KT = K / BK;
+#pragma unroll
+    for (int p = 0; p < A_PASSES; ++p) a_reg[p] = *reinterpret_cast<const u32x4_t *>(a_src[p]);
+#pragma unroll
+    for (int p = 0; p < B_PASSES; ++p) b_reg[p] = *reinterpret_cast<const u32x4_t *>(b_src[p]);
+#pragma unroll
+    for (int p = 0; p < A_PASSES; ++p) *reinterpret_cast<u32x4_t *>(lds + a_dst[p]) = a_reg[p];
+#pragma unroll
+    for (int p = 0; p < B_PASSES; ++p) *reinterpret_cast<u32x4_t *>(lds + b_dst[p]) = b_reg[p];
+    __syncthreads();
+
+    // fragment read offsets (row = lane % 32 of the MFMA tile, k chunk = 2*kk + lane/32)
+    const int frow = lane & 31, fk = lane >> 5, fsw = lane & 7;
+    const int a_frag0 = (wm * WM + frow) * 128;
+    const int b_frag0 = BM * 128 + (wn * WN + frow) * 128;
+
+    for (int kt = 0; kt < KT; ++kt) {
+        const unsigned char *cur = lds + (kt & 1) * STAGE_BYTES;
+        unsigned char *nxt = lds + ((kt + 1) & 1) * STAGE_BYTES;
+        // prefetch the next K slice into registers (the last iteration re-reads its own slice: harmless)
+        const int koff = (kt + 1 < KT ? kt + 1 : kt) * BK;
+#pragma unroll
+        for (int p = 0; p < A_PASSES; ++p) a_reg[p] = *reinterpret_cast<const u32x4_t *>(a_src[p] + koff);
+#pragma unroll
+        for (int p = 0; p < B_PASSES; ++p) b_reg[p] = *reinterpret_cast<const u32x4_t *>(b_src[p] + koff);
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            const int coff = (((kk * 2 + fk) ^ fsw) << 4);
+            bf16x8_t af[TM], bfr[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                af[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t *>(cur + a_frag0 + i * 32 * 128 + coff));
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                bfr[j] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t *>(cur + b_frag0 + j * 32 * 128 + coff));
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        }
+#pragma unroll
+        for (int p = 0; p < A_PASSES; ++p) *reinterpret_cast<u32x4_t *>(nxt + a_dst[p]) = a_reg[p];
+#pragma unroll
+        for (int p = 0; p < B_PASSES; ++p) *reinterpret_cast<u32x4_t *>(nxt + b_dst[p]) = b_reg[p];
+        __syncthreads();
+    }
+
+    // ---- epilogue: 32 rows x WN columns per wave at a time through LDS ----
+    constexpr int LROW = WN + 4;                           // padded fp32 row
+    float *stage = reinterpret_cast<float *>(lds) + (size_t)wave * 32 * LROW;
+    constexpr int LPR = WN / 4;                            // lanes per row when each lane takes 4 columns
+    constexpr int RPP = 64 / LPR;                          // rows per pass
+    const int e_row = lane / LPR, e_col = (lane - e_row * LPR) * 4;
+    const int vcol0 = n0 + wn * WN;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int rr = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                stage[rr * LROW + j * 32 + (lane & 31)] = acc[i][j][r];
+            }
+        __syncthreads();
+#pragma unroll
+        for (int ps = 0; ps < 32 / RPP; ++ps) {
+            const int rr = ps * RPP + e_row;
+            const int64_t grow = m0 + wm * WM + i * 32 + rr;
+            if (grow < M) epi.template apply<WN>(grow, vcol0, e_col, stage + rr * LROW);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// launchers
+// ------------------------------------------------------------------------------------------------
+template <int BM, int BN, int WM, int WN, class Epi>
+static bool launch_mfma(const bf16_t *A, int64_t lda, const BMap &bmap, int64_t M, int Nv, int K, const Epi &epi,
+                        hipStream_t st)
+{
+    if (M <= 0) return true;
+    if (Nv % BN || K % BK || K < BK) return false;
+    constexpr int NT = (BM / WM) * (BN / WN) * 64;
+    constexpr size_t lds_main = 2 * (size_t)(BM + BN) * 128;
+    constexpr size_t lds_epi = (size_t)(NT / 64) * 32 * (WN + 4) * 4;
+    constexpr size_t lds = lds_main > lds_epi ? lds_main : lds_epi;
+    auto kern = k_gemm_mfma<BM, BN, WM, WN, Epi>;
+    static bool attr_done = false;
+    if (!attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds) != hipSuccess)
+            return false;
+        attr_done = true;
+    }
+    const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = Nv / BN;
+    const int n_tiles = tiles_m * tiles_n;
+    const int grid = ((n_tiles + 7) / 8) * 8;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), lds, st, A, lda, bmap, M, Nv, K, tiles_m, tiles_n, epi);
+    return true;
+}
+
+// default tile configuration of the fused layer GEMMs
+#define SOL_TILE 256, 256, 128, 128
+
+bool launch_gemm_qkv_rope(const void *h, const void *wq, const void *wk, const void *wv, void *q, void *kc, void *vc,
+                          const float2 *rope, const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv, int dh,
+                          int d, int *flags, hipStream_t st)
+{
+    const int nq = Hq * dh, nkv = Hkv * dh;
+    if (dh > 128 || 128 % dh || nq % 256 || nkv % 256) return false;      // heads must not straddle wave tiles
+    BMap bm{};
+    bm.base[0] = (const bf16_t *)wq; bm.base[1] = (const bf16_t *)wk; bm.base[2] = (const bf16_t *)wv;
+    bm.seg_end[0] = nq; bm.seg_end[1] = nq + nkv; bm.seg_end[2] = nq + 2 * nkv;
+    bm.mode = 0; bm.half = 0; bm.ld = d;
+    EpiQkvRope epi{(bf16_t *)q, (bf16_t *)kc, (bf16_t *)vc, rope, pos0, T, L_max, Hq, Hkv, dh, flags};
+    return launch_mfma<SOL_TILE>((const bf16_t *)h, d, bm, (int64_t)n_seq * T, nq + 2 * nkv, d, epi, st);
+}
+
+bool launch_gemm_resid_f32(const void *a, const void *w, const void *resid, float *out, int64_t M, int N, int K,
+                           hipStream_t st)
+{
+    BMap bm{};
+    bm.base[0] = (const bf16_t *)w; bm.seg_end[0] = bm.seg_end[1] = bm.seg_end[2] = N; bm.mode = 0; bm.ld = K;
+    EpiResidF32 epi{(const bf16_t *)resid, out, N};
+    return launch_mfma<SOL_TILE>((const bf16_t *)a, K, bm, M, N, K, epi, st);
+}
+
+bool launch_gemm_gateup_silu(const void *h, const void *wg, const void *wu, void *a, int64_t M, int dff, int d,
+                             hipStream_t st)
+{
+    if (dff % 128) return false;
+    BMap bm{};
+    bm.base[0] = (const bf16_t *)wg; bm.base[1] = (const bf16_t *)wu; bm.mode = 1; bm.half = 64; bm.ld = d;
+    EpiSiluMul epi{(bf16_t *)a, dff};
+    return launch_mfma<SOL_TILE>((const bf16_t *)h, d, bm, M, 2 * dff, d, epi, st);
+}
+
+bool launch_gemm_resid_out(const void *a, const void *w, const float *x2, void *out, int64_t M, int N, int K,
+                           hipStream_t st)
+{
+    BMap bm{};
+    bm.base[0] = (const bf16_t *)w; bm.seg_end[0] = bm.seg_end[1] = bm.seg_end[2] = N; bm.mode = 0; bm.ld = K;
+    EpiResidOut epi{x2, (bf16_t *)out, N};
+    return launch_mfma<SOL_TILE>((const bf16_t *)a, K, bm, M, N, K, epi, st);
+}
+
+bool launch_gemm_f32(const void *a, const void *w, float *C, int64_t ldc, int64_t M, int N, int K, hipStream_t st)
+{
+    BMap bm{};
+    bm.base[0] = (const bf16_t *)w; bm.seg_end[0] = bm.seg_end[1] = bm.seg_end[2] = N; bm.mode = 0; bm.ld = K;
+    EpiStoreF32 epi{C, ldc};
+    return launch_mfma<SOL_TILE>((const bf16_t *)a, K, bm, M, N, K, epi, st);
+}
+
+}  // namespace sol

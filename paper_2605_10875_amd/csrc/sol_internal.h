@@ -61,6 +61,25 @@ void launch_test_quant(const float *z, int rows, int n, const int32_t *bits, int
 void launch_gemm_generic(const void *A, int a_dtype, int64_t lda, const void *W, int w_dtype, int64_t ldw,
                          float *C, int64_t ldc, int64_t M, int N, int K, hipStream_t st);
 
+// ---- bf16 MFMA GEMMs with fused epilogues (sol_gemm_mfma.hip) -----------------------------------
+// Each returns false (and launches nothing) if the shape is outside what the tile configuration
+// covers; the caller then takes the generic path for that stage.
+// q/k/v projections + rotary + q store + K/V cache write.  h: [M][d] bf16.
+bool launch_gemm_qkv_rope(const void *h, const void *wq, const void *wk, const void *wv, void *q, void *kc, void *vc,
+                          const float2 *rope, const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv, int dh,
+                          int d, int *flags, hipStream_t st);
+// out(fp32)[M][N] = resid(bf16)[M][N] + a[M][K] * w[N][K]^T
+bool launch_gemm_resid_f32(const void *a, const void *w, const void *resid, float *out, int64_t M, int N, int K,
+                           hipStream_t st);
+// a(bf16)[M][dff] = silu(h wg^T) * (h wu^T)
+bool launch_gemm_gateup_silu(const void *h, const void *wg, const void *wu, void *a, int64_t M, int dff, int d,
+                             hipStream_t st);
+// out(bf16)[M][N] = x2(fp32)[M][N] + a[M][K] * w[N][K]^T
+bool launch_gemm_resid_out(const void *a, const void *w, const float *x2, void *out, int64_t M, int N, int K,
+                           hipStream_t st);
+// C(fp32, ldc) = a * w^T
+bool launch_gemm_f32(const void *a, const void *w, float *C, int64_t ldc, int64_t M, int N, int K, hipStream_t st);
+
 // ---- attention (sol_attn.hip) ----------------------------------------------------------------
 // One query row per workgroup group: scores over cache positions [0, pos], budgeted top-k,
 // softmax over kept keys, times V. o32: fp32 [M][Hq*dh]. Returns false if the shape is unsupported.
