@@ -266,12 +266,13 @@ struct Carver {
 
 struct LayerWs {
     RowAct *ra; int32_t *row_bucket, *perm, *bucket_off;
-    void *h, *qb, *a;
+    void *h, *qb, *a, *vt;
     float *big32, *o32, *x2;
 };
 
-static void carve_layer(Carver &c, const sol_model_cfg &g, int64_t M, LayerWs &w)
+static void carve_layer(Carver &c, const sol_model_cfg &g, int64_t n_seq, int64_t T, int L_max, LayerWs &w)
 {
+    const int64_t M = n_seq * T;
     const size_t es = esize(g.dtype);
     const int64_t nq = (int64_t)g.n_q_heads * g.head_dim, nkv = (int64_t)g.n_kv_heads * g.head_dim;
     int64_t wide = nq + 2 * nkv;
@@ -287,6 +288,9 @@ static void carve_layer(Carver &c, const sol_model_cfg &g, int64_t M, LayerWs &w
     w.big32 = (float *)c.take(4 * M * wide);
     w.o32 = (float *)c.take(4 * M * nq);
     w.x2 = (float *)c.take(4 * M * g.d_model);
+    // transposed V copy for the tiled attention kernel (batched bf16 pass only)
+    const bool tiled = g.dtype == SOL_BF16 && T >= 16 && L_max <= 4096;
+    w.vt = c.take(tiled ? es * n_seq * g.n_kv_heads * g.head_dim * (size_t)attn_tile_lpadv(L_max) : 0);
 }
 
 static int64_t lm_chunk_rows(const sol_model_cfg &g, int64_t M)
@@ -306,7 +310,7 @@ static void carve_stack(Carver &c, const sol_model_cfg &g, int64_t n_seq, int64_
 {
     const size_t es = esize(g.dtype);
     const int64_t M = n_seq * T;
-    carve_layer(c, g, M, w.layer);
+    carve_layer(c, g, n_seq, T, own_cache ? (int)T : 1 << 30, w.layer);
     w.xa = c.take(es * M * g.d_model);
     w.xb = c.take(es * M * g.d_model);
     w.hf = c.take(es * M * g.d_model);
@@ -323,7 +327,7 @@ extern "C" size_t sol_workspace_bytes(const sol_model_cfg *cfg, int op, int n_se
     Carver c(nullptr);
     if (op == SOL_OP_LAYER_FORWARD) {
         if (T <= 0) return 0;
-        LayerWs w; carve_layer(c, *cfg, (int64_t)n_seq * T, w);
+        LayerWs w; carve_layer(c, *cfg, n_seq, T, L_max, w);
     } else if (op == SOL_OP_DECODE_STEP) {
         StackWs w; carve_stack(c, *cfg, n_seq, 1, false, w);
     } else if (op == SOL_OP_SCHEDULE_LOGLIK) {
@@ -376,7 +380,10 @@ static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_i
     }
     {   // scores, budgeted selection, softmax over kept keys, times V
         STAGE(ctx, ST_ATTN, st);
-        if (!launch_attn_rows(w.qb, kc, vc, dt, w.o32, w.ra, pos0, n_seq, T, L_max, Hq, Hkv, dh, ctx->d_flags, st))
+        const bool tiled = mfma && w.vt && T >= 16 && L_max <= 4096 &&
+                           launch_attn_tile(w.qb, kc, vc, w.vt, w.o32, w.ra, pos0, n_seq, T, L_max, Hq, Hkv, dh, st);
+        if (!tiled &&
+            !launch_attn_rows(w.qb, kc, vc, dt, w.o32, w.ra, pos0, n_seq, T, L_max, Hq, Hkv, dh, ctx->d_flags, st))
             return fail(ctx, SOL_ERR_UNSUPPORTED, "attention: L_max too long for the on-chip score rows of this build");
     }
     {   // quantise (o-proj input)
@@ -453,7 +460,7 @@ extern "C" int sol_layer_forward(sol_ctx *ctx, const sol_layer_weights *w, const
         return fail(ctx, SOL_ERR_WORKSPACE, "workspace too small: need " + std::to_string(need) + " bytes");
     hipStream_t st = (hipStream_t)stream;
     Carver c(workspace);
-    LayerWs lw; carve_layer(c, ctx->cfg, (int64_t)n_seq * T, lw);
+    LayerWs lw; carve_layer(c, ctx->cfg, n_seq, T, L_max, lw);
     prepare_actions(ctx, action_ids, (int64_t)n_seq * T, lw, st);
     return layer_impl(ctx, w, x_in, x_out, pos0, k_cache, v_cache, n_seq, T, L_max, lw, st);
 }

@@ -20,14 +20,18 @@ enum { FLAG_BAD_ACTION = 1, FLAG_CACHE_OVERFLOW = 2 };
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
-// round to nearest, ties to even
+// round to nearest, ties to even (v_cvt_pk_bf16_f32 on gfx950)
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ bf16_t f32_to_bf16(float f)
 {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7F800000u) == 0x7F800000u)
-        return (bf16_t)((u >> 16) | ((u & 0x007FFFFFu) ? 0x0040u : 0u));
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (bf16_t)(u >> 16);
+    return __builtin_bit_cast(bf16_t, (__bf16)f);
+}
+// two values -> one dword, `a` in the low half
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b)
+{
+    const f32x2_t v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
 __device__ __forceinline__ float ld(const float *p) { return *p; }
@@ -218,6 +222,100 @@ __device__ __forceinline__ int block_tie_cutoff(KeyFn keyfn, int n, uint32_t thr
     }
     __syncthreads();
     return sh[3];
+}
+
+// ---- wave-wide reductions on DPP (no LDS traffic); all 64 lanes must be active -------------------
+// quad swaps, half-mirror and mirror reduce each row of 16 lanes; row_bcast15 / row_bcast31 fold
+// the four rows into lane 63, which is broadcast through a scalar register.
+#define SOL_DPP(T, x, ident, ctrl, rmask)                                                                       \
+    __builtin_bit_cast(T, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, ident), __builtin_bit_cast(int, x), \
+                                                      ctrl, rmask, 0xF, false))
+template <typename T, typename Op> __device__ __forceinline__ T wave_reduce_dpp(T v, T ident, Op op)
+{
+    v = op(v, SOL_DPP(T, v, ident, 0xB1, 0xF));     // quad_perm [1,0,3,2]
+    v = op(v, SOL_DPP(T, v, ident, 0x4E, 0xF));     // quad_perm [2,3,0,1]
+    v = op(v, SOL_DPP(T, v, ident, 0x141, 0xF));    // row_half_mirror
+    v = op(v, SOL_DPP(T, v, ident, 0x140, 0xF));    // row_mirror
+    v = op(v, SOL_DPP(T, v, ident, 0x142, 0xA));    // row_bcast15 into rows 1 and 3
+    v = op(v, SOL_DPP(T, v, ident, 0x143, 0xC));    // row_bcast31 into rows 2 and 3
+    return __builtin_bit_cast(T, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
+struct OpMaxU { __device__ __forceinline__ uint32_t operator()(uint32_t a, uint32_t b) const { return a > b ? a : b; } };
+struct OpMinU { __device__ __forceinline__ uint32_t operator()(uint32_t a, uint32_t b) const { return a < b ? a : b; } };
+struct OpAddF { __device__ __forceinline__ float operator()(float a, float b) const { return a + b; } };
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) { return wave_reduce_dpp<uint32_t>(v, 0u, OpMaxU()); }
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) { return wave_reduce_dpp<uint32_t>(v, 0xFFFFFFFFu, OpMinU()); }
+__device__ __forceinline__ float wave_sum_dpp(float v) { return wave_reduce_dpp<float>(v, 0.f, OpAddF()); }
+
+// inverse of score_key
+__device__ __forceinline__ float score_unkey(uint32_t k)
+{
+    return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
+}
+
+// ---- wave-level exact top-b (keys in registers) ---------------------------------------------------
+// A wave holds SLOTS keys per lane; element (j, e) of lane l is column 256*j + 4*l + e (j < SLOTS/4,
+// e < 4). Columns >= n carry key 0, which is below the key of every real score. Finds the b largest
+// (1 <= b < n), equal keys going to the lower columns, and returns a threshold `thr` such that after
+// the call   kept  <=>  key >= thr   (keys equal to thr that lose the tie are overwritten with 0).
+// kmin / kmax: smallest / largest valid key of the row (wave-uniform).
+// The search bisects [kmin, kmax] counting with ballots and stops as soon as exactly b keys lie at
+// or above the pivot, about log2 of the key range over the gap at the threshold steps.
+template <int SLOTS>
+__device__ __forceinline__ uint32_t wave_select_topk(uint32_t (&key)[SLOTS], int n_in, int b_in, uint32_t kmin,
+                                                     uint32_t kmax, int lane)
+{
+    constexpr int NJ = SLOTS / 4;
+    // every search variable is wave-uniform: scalar registers, scalar control flow around ballots
+    const int n = __builtin_amdgcn_readfirstlane(n_in), b = __builtin_amdgcn_readfirstlane(b_in);
+    uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)kmin);
+    uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)kmax);
+    // invariant: count(key >= lo) >= b  and  count(key >= hi + 1) < b
+    while (lo < hi) {
+        const uint32_t mid = lo + ((hi - lo + 1u) >> 1);
+        int cnt = 0;
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            if (256 * j < n) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) cnt += __popcll(__ballot(key[4 * j + e] >= mid));
+            }
+        }
+        if (cnt == b) return mid;                       // exactly b keys at or above the pivot
+        if (cnt > b) lo = mid; else hi = mid - 1u;
+    }
+    const uint32_t thr = lo;                            // the b-th largest key; ties decide the rest
+    int n_gt = 0;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+        if (256 * j < n) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) n_gt += __popcll(__ballot(key[4 * j + e] > thr));
+        }
+    int quota = b - n_gt;                               // >= 1 keys equal to thr are kept, lowest columns first
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        if (256 * j < n) {
+            unsigned long long bal[4];
+            int below = 0;                              // ties in lower lanes of this j
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                bal[e] = __ballot(key[4 * j + e] == thr);
+                below += __popcll(bal[e] & lt_mask);
+            }
+            int mine = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const bool tie = key[4 * j + e] == thr;
+                if (tie && below + mine >= quota) key[4 * j + e] = 0u;     // loses the tie
+                mine += tie;
+            }
+            quota -= __popcll(bal[0]) + __popcll(bal[1]) + __popcll(bal[2]) + __popcll(bal[3]);
+            if (quota < 0) quota = 0;
+        }
+    }
+    return thr;
 }
 
 // ---- per-token symmetric fake-quantiser ------------------------------------------------------

@@ -86,6 +86,10 @@ bool launch_gemm_f32(const void *a, const void *w, float *C, int64_t ldc, int64_
 bool launch_attn_rows(const void *q, const void *k_cache, const void *v_cache, int dtype, float *o32,
                       const RowAct *ra, const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv,
                       int dh, int *flags, hipStream_t st);
-size_t attn_rows_lds_bytes(int L_max, int hpb, int block);
+// Tiled MFMA attention for the batched bf16 pass (L_max <= 4096, head_dim 64 or 128). vt is
+// workspace for the transposed V copy: n_seq * Hkv * dh * attn_tile_lpadv(L_max) elements.
+bool launch_attn_tile(const void *q, const void *k_cache, const void *v_cache, void *vt, float *o32, const RowAct *ra,
+                      const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv, int dh, hipStream_t st);
+int attn_tile_lpadv(int L_max);
 
 }  // namespace sol

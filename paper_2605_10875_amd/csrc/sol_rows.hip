@@ -477,6 +477,43 @@ __device__ __forceinline__ void select_row_to_mask(KeyFn kf, int n_valid, int n_
     }
 }
 
+// the wave-level selection used by the tiled attention kernel: one wave per row, n_cols <= 64*SLOTS
+template <int SLOTS>
+__global__ void __launch_bounds__(64)
+k_test_topk_wave(const float *__restrict__ scores, int n_cols, const int32_t *__restrict__ n_valid,
+                 const int32_t *__restrict__ k, uint8_t *__restrict__ keep)
+{
+    const int64_t r = blockIdx.x;
+    const int lane = threadIdx.x;
+    int nv = n_valid[r];
+    nv = nv < 0 ? 0 : (nv > n_cols ? n_cols : nv);
+    const int kk = k[r];
+    uint32_t key[SLOTS];
+    uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
+#pragma unroll
+    for (int j = 0; j < SLOTS / 4; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int col = 256 * j + 4 * lane + e;
+            const uint32_t kv = col < nv ? score_key(scores[r * n_cols + col]) : 0u;
+            key[4 * j + e] = kv;
+            kmax = kv > kmax ? kv : kmax;
+            kmin = (col < nv && kv < kmin) ? kv : kmin;
+        }
+    kmax = wave_max_u32(kmax);
+    kmin = wave_min_u32(kmin);
+    uint32_t thr = 1u;                                   // keeps every valid key
+    if (kk <= 0) thr = 0xFFFFFFFFu;
+    else if (kk < nv) thr = wave_select_topk<SLOTS>(key, nv, kk, kmin, kmax, lane);
+#pragma unroll
+    for (int j = 0; j < SLOTS / 4; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int col = 256 * j + 4 * lane + e;
+            if (col < n_cols) keep[r * n_cols + col] = (col < nv) && (kk > 0) && key[4 * j + e] >= thr;
+        }
+}
+
 __global__ void __launch_bounds__(ROW_BLOCK)
 k_test_topk(const float *__restrict__ scores, int n_cols, const int32_t *__restrict__ n_valid,
             const int32_t *__restrict__ k, uint8_t *__restrict__ keep)
@@ -527,7 +564,14 @@ void launch_test_topk(const float *scores, int rows, int n_cols, const int32_t *
                       uint8_t *keep, hipStream_t st)
 {
     if (rows <= 0 || n_cols <= 0) return;
-    hipLaunchKernelGGL(k_test_topk, dim3(rows), dim3(ROW_BLOCK), 0, st, scores, n_cols, n_valid, k, keep);
+    // rows that fit a wave's registers go through the wave-level search of the tiled attention
+    // kernel, longer rows through the workgroup-level radix select of the row / decode kernel
+    if (n_cols <= 1024)
+        hipLaunchKernelGGL((k_test_topk_wave<16>), dim3(rows), dim3(64), 0, st, scores, n_cols, n_valid, k, keep);
+    else if (n_cols <= 4096)
+        hipLaunchKernelGGL((k_test_topk_wave<64>), dim3(rows), dim3(64), 0, st, scores, n_cols, n_valid, k, keep);
+    else
+        hipLaunchKernelGGL(k_test_topk, dim3(rows), dim3(ROW_BLOCK), 0, st, scores, n_cols, n_valid, k, keep);
 }
 void launch_test_prune(const float *a, int rows, int n, const int32_t *m, uint8_t *keep, hipStream_t st)
 {

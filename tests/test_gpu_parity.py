@@ -14,7 +14,7 @@ evaluated per token row.
   difference on ~1e-3 of the elements, and after one more contraction and rounding a few elements
   per row sit on the other side of a 4-bit rounding boundary (measured: ~12 % of 4-bit rows at
   d_ff = 8192). So tests with quantising actions bound the MEDIAN row by the bf16 noise floor
-  (5e-3), the share of rows over 2e-2, and every row by a cap; tests whose actions do not quantise
+  (1e-2, 2.5 bf16 ulps of the tensor scale), the share of rows over 2e-2, and every row by a cap; tests whose actions do not quantise
   (selection and pruning only, whose flips swap near-equal elements) hold EVERY row to 2e-2.
   Against the fp32-storage oracle only tokens under the dense action are comparable at 2e-2
   (4-bit rows of the fp32- and bf16-storage oracles differ from each other by 10-20 %)."""
@@ -108,7 +108,7 @@ def test_bf16_layer_selection_and_pruning_every_row(shape, n_seq, T):
     refbf, kbf, vbf, _ = _oracle_layer(shape, table, w, x, ids, T, True)
     check_rows(kg.transpose(0, 2, 1, 3), kbf.transpose(0, 2, 1, 3), 2e-2, 2e-2, 0.0, "K cache")
     check_rows(vg.transpose(0, 2, 1, 3), vbf.transpose(0, 2, 1, 3), 2e-2, 2e-2, 0.0, "V cache")
-    check_rows(out, refbf, 2e-2, 2e-2, 0.0, "layer output, no quantising action", median=5e-3)
+    check_rows(out, refbf, 2e-2, 2e-2, 0.0, "layer output, no quantising action", median=1e-2)
     # dense-action tokens are comparable with the fp32-storage oracle as well
     ref32, _, _, _ = _oracle_layer(shape, table, w, x, ids, T, False)
     sel = ids == table.index(synth.DENSE_ACTION)
@@ -149,12 +149,12 @@ def test_bf16_layer_with_prefix_cache_and_stepwise_equivalence():
     b = ctx.layer_forward(wd, dev(x[:, T1:], sol.BF16), dev(ids[:, T1:]), kc, vc,
                           pos0=dev(np.array([T1, T1], np.int32)))
     two = np.concatenate([host(a), host(b)], 1)
-    check_rows(two, full, 2e-2, 0.3, 0.1, "two chunks vs one call", median=5e-3)
+    check_rows(two, full, 2e-2, 0.3, 0.1, "two chunks vs one call", median=1e-2)
     assert rel_err(host(kc), kf) < 2e-2
     # the oracle agrees on the second chunk given the same prefix cache
     refb, _, _, _ = _oracle_layer(shape, table, w, x[:, T1:], ids[:, T1:], T, True, pos0=np.array([T1, T1], np.int32),
                                   kc=kf.copy(), vc=vf.copy())
-    check_rows(host(b), refb, 2e-2, 0.3, 0.2, "second chunk vs bf16 oracle", median=5e-3)
+    check_rows(host(b), refb, 2e-2, 0.3, 0.2, "second chunk vs bf16 oracle", median=1e-2)
     ctx.close()
 
 

@@ -27,7 +27,7 @@ def _rows(rng, rows, n, kind):
     raise ValueError(kind)
 
 
-@pytest.mark.parametrize("n", [1, 2, 63, 64, 65, 257, 1024, 4097, 8192])
+@pytest.mark.parametrize("n", [1, 2, 63, 64, 65, 257, 1024, 1025, 2048, 4096, 4097, 8192, 20000])
 @pytest.mark.parametrize("kind", ["normal", "ties", "const", "wide"])
 def test_topk_select_bit_exact(n, kind):
     rng = np.random.default_rng(n * 7 + len(kind))
