@@ -195,6 +195,12 @@ int sol_test_topk_select(const float *scores, int rows, int n_cols, const int32_
 /* keep_out[r][c] = 1 for the m[r] largest |a[r][c]| (ties to the lower c). */
 int sol_test_prune_mask(const float *a, int rows, int n, const int32_t *m, uint8_t *keep_out,
                         void *stream);
+/* The production "magnitude pruning + fake-quantise" kernel (the down-projection input step of the
+ * layer) in place on caller rows a[r][0..n) of element type dtype: keeps the m[r] largest |a|, ties
+ * to the lower channel, zeroes the rest, then quantises at bits[r] (>= 16: no quantiser) and rounds
+ * to dtype. scratch: device, >= 16 * rows bytes. n * 4 bytes must fit 60 KB of LDS. */
+int sol_test_prune_quant(void *a, int dtype, int rows, int n, const int32_t *m, const int32_t *bits,
+                         void *scratch, size_t scratch_bytes, void *stream);
 /* Per-row fake-quantiser: codes_out[r][j] (int32), scale_out[r], dequantised z_hat_out[r][j].
  * bits[r] >= 16: codes 0, scale 0, z_hat = z. */
 int sol_test_quant_codes(const float *z, int rows, int n, const int32_t *bits,

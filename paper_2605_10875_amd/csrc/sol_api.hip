@@ -611,6 +611,18 @@ extern "C" int sol_test_prune_mask(const float *a, int rows, int n, const int32_
     return launch_status();
 }
 
+extern "C" int sol_test_prune_quant(void *a, int dtype, int rows, int n, const int32_t *m, const int32_t *bits,
+                                    void *scratch, size_t scratch_bytes, void *stream)
+{
+    if (rows < 0 || n < 0 || (dtype != SOL_F32 && dtype != SOL_BF16)) return SOL_ERR_INVALID_ARG;
+    if (rows == 0 || n == 0) return SOL_OK;
+    if (!a || !m || !bits || !scratch) return SOL_ERR_INVALID_ARG;
+    if (scratch_bytes < (size_t)rows * sizeof(RowAct)) return SOL_ERR_WORKSPACE;
+    if ((size_t)n * 4 > 60 * 1024) return SOL_ERR_UNSUPPORTED;
+    launch_test_prune_quant(a, dtype, rows, n, m, bits, scratch, (hipStream_t)stream);
+    return launch_status();
+}
+
 extern "C" int sol_test_quant_codes(const float *z, int rows, int n, const int32_t *bits, int32_t *codes_out,
                                     float *scale_out, float *zhat_out, void *stream)
 {

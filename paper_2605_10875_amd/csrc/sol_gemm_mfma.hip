@@ -26,6 +26,12 @@ typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));   // native 16-byt
 
 constexpr int BK = 64;               // K step (bf16 elements); one LDS row = 128 bytes = 8 chunks of 16 B
 constexpr int GROUP_M = 8;           // tile rows walked together by an XCD
+// LDS has 64 banks of 4 bytes (256 B per clock): two 128-byte rows share one bank row, so the
+// 16-byte chunk index is XOR-ed with bits 1..3 of the row. Measured SQ_LDS_BANK_CONFLICT drops 32x
+// against swizzling with bits 0..2.
+#ifndef SOL_SWZ
+#define SOL_SWZ(r) (((r) >> 1) & 7)
+#endif
 
 struct BMap {                        // virtual column -> weight row
     const bf16_t *base[3];
@@ -82,8 +88,8 @@ struct EpiResidOut {
         const float4 v = *reinterpret_cast<const float4 *>(lrow + lc);
         const float4 r = *reinterpret_cast<const float4 *>(x2 + row * ld + vcol0 + lc);
         uint2 o;
-        o.x = (uint32_t)f32_to_bf16(v.x + r.x) | ((uint32_t)f32_to_bf16(v.y + r.y) << 16);
-        o.y = (uint32_t)f32_to_bf16(v.z + r.z) | ((uint32_t)f32_to_bf16(v.w + r.w) << 16);
+        o.x = pack_bf16x2(v.x + r.x, v.y + r.y);
+        o.y = pack_bf16x2(v.z + r.z, v.w + r.w);
         *reinterpret_cast<uint2 *>(out + row * ld + vcol0 + lc) = o;
     }
 };
@@ -96,11 +102,13 @@ struct EpiSiluMul {
         if (lc >= WN / 2) return;
         const float4 g = *reinterpret_cast<const float4 *>(lrow + lc);
         const float4 u = *reinterpret_cast<const float4 *>(lrow + WN / 2 + lc);
-        const float a0 = (g.x / (1.0f + expf(-g.x))) * u.x, a1 = (g.y / (1.0f + expf(-g.y))) * u.y;
-        const float a2 = (g.z / (1.0f + expf(-g.z))) * u.z, a3 = (g.w / (1.0f + expf(-g.w))) * u.w;
+        // g * sigmoid(g) * u with the hardware exp2 / reciprocal (about 1 ulp each, far below the
+        // bf16 rounding that follows)
+        const float a0 = g.x * __frcp_rn(1.0f + __expf(-g.x)) * u.x, a1 = g.y * __frcp_rn(1.0f + __expf(-g.y)) * u.y;
+        const float a2 = g.z * __frcp_rn(1.0f + __expf(-g.z)) * u.z, a3 = g.w * __frcp_rn(1.0f + __expf(-g.w)) * u.w;
         uint2 o;
-        o.x = (uint32_t)f32_to_bf16(a0) | ((uint32_t)f32_to_bf16(a1) << 16);
-        o.y = (uint32_t)f32_to_bf16(a2) | ((uint32_t)f32_to_bf16(a3) << 16);
+        o.x = pack_bf16x2(a0, a1);
+        o.y = pack_bf16x2(a2, a3);
         *reinterpret_cast<uint2 *>(a + row * ld + (vcol0 / WN) * (WN / 2) + lc) = o;
     }
 };
@@ -133,8 +141,8 @@ struct EpiQkvRope {
             }
         }
         uint2 pk;
-        pk.x = (uint32_t)f32_to_bf16(o[0]) | ((uint32_t)f32_to_bf16(o[1]) << 16);
-        pk.y = (uint32_t)f32_to_bf16(o[2]) | ((uint32_t)f32_to_bf16(o[3]) << 16);
+        pk.x = pack_bf16x2(o[0], o[1]);
+        pk.y = pack_bf16x2(o[2], o[3]);
         bf16_t *dst;
         if (v < nq) dst = q + row * (int64_t)nq + v;
         else if (v < nq + nkv) { const int w = v - nq; dst = kc + (((int64_t)s * Hkv + w / dh) * L_max + pos) * dh + w % dh; }
@@ -185,13 +193,13 @@ k_gemm_mfma(const bf16_t *__restrict__ A, int64_t lda, BMap bmap, int64_t M, int
         int64_t gr = m0 + rl;
         if (gr >= M) gr = M - 1;                            // ragged last tile: re-read the last row, never stored
         a_src[p] = A + gr * lda + chunk * 8;
-        a_dst[p] = rl * 128 + ((chunk ^ (rl & 7)) << 4);
+        a_dst[p] = rl * 128 + ((chunk ^ SOL_SWZ(rl)) << 4);
     }
 #pragma unroll
     for (int p = 0; p < B_PASSES; ++p) {
         const int rl = p * ROWS_PER_PASS + r_in_pass;
         b_src[p] = bmap.row(n0 + rl) + chunk * 8;
-        b_dst[p] = BM * 128 + rl * 128 + ((chunk ^ (rl & 7)) << 4);
+        b_dst[p] = BM * 128 + rl * 128 + ((chunk ^ SOL_SWZ(rl)) << 4);
     }
 
     floatx16_t acc[TM][TN];
@@ -202,54 +210,67 @@ k_gemm_mfma(const bf16_t *__restrict__ A, int64_t lda, BMap bmap, int64_t M, int
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    u32x4_t a_reg[A_PASSES], b_reg[B_PASSES];
+    // Software pipeline, three K slices deep: LDS holds slices kt and kt+1, one register set holds
+    // slice kt+2 (loaded one full iteration ago, so HBM latency is covered by two iterations of
+    // MFMAs), the other register set is being loaded with slice kt+3. One barrier per iteration:
+    // after it, slice kt's LDS stage is free and takes slice kt+2.
+    // (macros, not lambdas: register arrays captured by reference would be demoted to scratch)
+    u32x4_t ra0[A_PASSES], rb0[B_PASSES], ra1[A_PASSES], rb1[B_PASSES];
     const int KT = K / BK;
-#pragma unroll
-    for (int p = 0; p < A_PASSES; ++p) a_reg[p] = *reinterpret_cast<const u32x4_t *>(a_src[p]);
-#pragma unroll
-    for (int p = 0; p < B_PASSES; ++p) b_reg[p] = *reinterpret_cast<const u32x4_t *>(b_src[p]);
-#pragma unroll
-    for (int p = 0; p < A_PASSES; ++p) *reinterpret_cast<u32x4_t *>(lds + a_dst[p]) = a_reg[p];
-#pragma unroll
-    for (int p = 0; p < B_PASSES; ++p) *reinterpret_cast<u32x4_t *>(lds + b_dst[p]) = b_reg[p];
-    __syncthreads();
-
+#define SOL_G_LOAD(RA, RB, KT_)                                                                            \
+    {                                                                                                      \
+        const int koff_ = ((KT_) < KT ? (KT_) : KT - 1) * BK; /* past the end: re-read the last slice */   \
+        _Pragma("unroll") for (int p = 0; p < A_PASSES; ++p)                                               \
+            RA[p] = *reinterpret_cast<const u32x4_t *>(a_src[p] + koff_);                                  \
+        _Pragma("unroll") for (int p = 0; p < B_PASSES; ++p)                                               \
+            RB[p] = *reinterpret_cast<const u32x4_t *>(b_src[p] + koff_);                                  \
+    }
+#define SOL_L_STORE(RA, RB, STAGE_)                                                                        \
+    {                                                                                                      \
+        _Pragma("unroll") for (int p = 0; p < A_PASSES; ++p)                                               \
+            *reinterpret_cast<u32x4_t *>((STAGE_) + a_dst[p]) = RA[p];                                     \
+        _Pragma("unroll") for (int p = 0; p < B_PASSES; ++p)                                               \
+            *reinterpret_cast<u32x4_t *>((STAGE_) + b_dst[p]) = RB[p];                                     \
+    }
     // fragment read offsets (row = lane % 32 of the MFMA tile, k chunk = 2*kk + lane/32)
-    const int frow = lane & 31, fk = lane >> 5, fsw = lane & 7;
+    const int frow = lane & 31, fk = lane >> 5, fsw = SOL_SWZ(frow);
     const int a_frag0 = (wm * WM + frow) * 128;
     const int b_frag0 = BM * 128 + (wn * WN + frow) * 128;
-
-    for (int kt = 0; kt < KT; ++kt) {
-        const unsigned char *cur = lds + (kt & 1) * STAGE_BYTES;
-        unsigned char *nxt = lds + ((kt + 1) & 1) * STAGE_BYTES;
-        // prefetch the next K slice into registers (the last iteration re-reads its own slice: harmless)
-        const int koff = (kt + 1 < KT ? kt + 1 : kt) * BK;
-#pragma unroll
-        for (int p = 0; p < A_PASSES; ++p) a_reg[p] = *reinterpret_cast<const u32x4_t *>(a_src[p] + koff);
-#pragma unroll
-        for (int p = 0; p < B_PASSES; ++p) b_reg[p] = *reinterpret_cast<const u32x4_t *>(b_src[p] + koff);
-#pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            const int coff = (((kk * 2 + fk) ^ fsw) << 4);
-            bf16x8_t af[TM], bfr[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-                af[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t *>(cur + a_frag0 + i * 32 * 128 + coff));
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                bfr[j] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t *>(cur + b_frag0 + j * 32 * 128 + coff));
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-        }
-#pragma unroll
-        for (int p = 0; p < A_PASSES; ++p) *reinterpret_cast<u32x4_t *>(nxt + a_dst[p]) = a_reg[p];
-#pragma unroll
-        for (int p = 0; p < B_PASSES; ++p) *reinterpret_cast<u32x4_t *>(nxt + b_dst[p]) = b_reg[p];
-        __syncthreads();
+#define SOL_COMPUTE(CUR_)                                                                                  \
+    _Pragma("unroll") for (int kk = 0; kk < BK / 16; ++kk)                                                 \
+    {                                                                                                      \
+        const int coff = (((kk * 2 + fk) ^ fsw) << 4);                                                     \
+        bf16x8_t af[TM], bfr[TN];                                                                          \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i) af[i] = __builtin_bit_cast(                         \
+            bf16x8_t, *reinterpret_cast<const u32x4_t *>((CUR_) + a_frag0 + i * 32 * 128 + coff));         \
+        _Pragma("unroll") for (int j = 0; j < TN; ++j) bfr[j] = __builtin_bit_cast(                        \
+            bf16x8_t, *reinterpret_cast<const u32x4_t *>((CUR_) + b_frag0 + j * 32 * 128 + coff));         \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i) _Pragma("unroll") for (int j = 0; j < TN; ++j)      \
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);        \
     }
+
+    SOL_G_LOAD(ra0, rb0, 0);
+    SOL_G_LOAD(ra1, rb1, 1);
+    SOL_L_STORE(ra0, rb0, lds);
+    SOL_L_STORE(ra1, rb1, lds + STAGE_BYTES);
+    SOL_G_LOAD(ra0, rb0, 2);
+    __syncthreads();
+    for (int kt = 0; kt < KT; kt += 2) {                    // KT is even (K is a multiple of 128)
+        // even step: stage 0 holds slice kt; set 0 holds slice kt+2; load slice kt+3 into set 1
+        SOL_G_LOAD(ra1, rb1, kt + 3);
+        SOL_COMPUTE(lds);
+        __syncthreads();
+        SOL_L_STORE(ra0, rb0, lds);
+        // odd step: stage 1 holds slice kt+1; set 1 holds slice kt+3; load slice kt+4 into set 0
+        SOL_G_LOAD(ra0, rb0, kt + 4);
+        SOL_COMPUTE(lds + STAGE_BYTES);
+        __syncthreads();
+        SOL_L_STORE(ra1, rb1, lds + STAGE_BYTES);
+    }
+    __syncthreads();
+#undef SOL_G_LOAD
+#undef SOL_L_STORE
+#undef SOL_COMPUTE
 
     // ---- epilogue: 32 rows x WN columns per wave at a time through LDS ----
     constexpr int LROW = WN + 4;                           // padded fp32 row
@@ -286,7 +307,7 @@ static bool launch_mfma(const bf16_t *A, int64_t lda, const BMap &bmap, int64_t 
                         hipStream_t st)
 {
     if (M <= 0) return true;
-    if (Nv % BN || K % BK || K < BK) return false;
+    if (Nv % BN || K % (2 * BK) || K < 2 * BK) return false;
     constexpr int NT = (BM / WM) * (BN / WN) * 64;
     constexpr size_t lds_main = 2 * (size_t)(BM + BN) * 128;
     constexpr size_t lds_epi = (size_t)(NT / 64) * 32 * (WN + 4) * 4;
@@ -306,8 +327,11 @@ static bool launch_mfma(const bf16_t *A, int64_t lda, const BMap &bmap, int64_t 
     return true;
 }
 
-// default tile configuration of the fused layer GEMMs
-#define SOL_TILE 256, 256, 128, 128
+// Tile configurations of the fused layer GEMMs: 256 x 256 workgroup tiles, 8 waves (two per SIMD, so
+// one wave's LDS / barrier waits hide under the other's MFMAs). Wave tile 128 x 64 measured fastest;
+// the q/k/v epilogue needs a whole head (up to 128 columns) inside one wave tile, hence 64 x 128.
+#define SOL_TILE 256, 256, 128, 64
+#define SOL_TILE_QKV 256, 256, 64, 128
 
 bool launch_gemm_qkv_rope(const void *h, const void *wq, const void *wk, const void *wv, void *q, void *kc, void *vc,
                           const float2 *rope, const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv, int dh,
@@ -320,7 +344,7 @@ bool launch_gemm_qkv_rope(const void *h, const void *wq, const void *wk, const v
     bm.seg_end[0] = nq; bm.seg_end[1] = nq + nkv; bm.seg_end[2] = nq + 2 * nkv;
     bm.mode = 0; bm.half = 0; bm.ld = d;
     EpiQkvRope epi{(bf16_t *)q, (bf16_t *)kc, (bf16_t *)vc, rope, pos0, T, L_max, Hq, Hkv, dh, flags};
-    return launch_mfma<SOL_TILE>((const bf16_t *)h, d, bm, (int64_t)n_seq * T, nq + 2 * nkv, d, epi, st);
+    return launch_mfma<SOL_TILE_QKV>((const bf16_t *)h, d, bm, (int64_t)n_seq * T, nq + 2 * nkv, d, epi, st);
 }
 
 bool launch_gemm_resid_f32(const void *a, const void *w, const void *resid, float *out, int64_t M, int N, int K,
@@ -337,7 +361,7 @@ bool launch_gemm_gateup_silu(const void *h, const void *wg, const void *wu, void
 {
     if (dff % 128) return false;
     BMap bm{};
-    bm.base[0] = (const bf16_t *)wg; bm.base[1] = (const bf16_t *)wu; bm.mode = 1; bm.half = 64; bm.ld = d;
+    bm.base[0] = (const bf16_t *)wg; bm.base[1] = (const bf16_t *)wu; bm.mode = 1; bm.half = 32; bm.ld = d;   // half = WN / 2
     EpiSiluMul epi{(bf16_t *)a, dff};
     return launch_mfma<SOL_TILE>((const bf16_t *)h, d, bm, M, 2 * dff, d, epi, st);
 }

@@ -53,6 +53,9 @@ void launch_nll_rows(const float *logits, int64_t rows, int V, const int32_t *ta
 void launch_test_topk(const float *scores, int rows, int n_cols, const int32_t *n_valid, const int32_t *k,
                       uint8_t *keep, hipStream_t st);
 void launch_test_prune(const float *a, int rows, int n, const int32_t *m, uint8_t *keep, hipStream_t st);
+// the production prune + quantise kernel on caller rows (scratch: rows * 16 bytes)
+void launch_test_prune_quant(void *a, int dtype, int rows, int n, const int32_t *m, const int32_t *bits, void *scratch,
+                             hipStream_t st);
 void launch_test_quant(const float *z, int rows, int n, const int32_t *bits, int32_t *codes, float *scale,
                        float *zhat, hipStream_t st);
 

@@ -347,10 +347,134 @@ k_prune_fq(T *__restrict__ a, const RowAct *__restrict__ ra, const int32_t *__re
     for (int j = tid; j < dff; j += ROW_BLOCK) st(ar + j, row[j]);
 }
 
+// bf16 rows whose length is a multiple of 512: one WAVE per row, the whole row in registers as packed
+// bf16 pairs (lane l holds elements (c*64 + l)*8 .. +8 of chunk c), no LDS, no barriers.
+//   - |a| of a bf16 is a 15-bit integer key, so the m-th largest magnitude is found by bisecting at
+//     most 15 times; a pass counts keys below the pivot two at a time (packed 16-bit subtract, sign
+//     bits, popcount) and reduces over the wave on DPP.
+//   - bf16 magnitudes collide all the time (about 20 channels share the threshold value at
+//     d_ff = 8192), so the tie rule (lower channel wins) always runs: ballots per element slot give
+//     each tied channel its rank in channel order.
+//   - the quantiser then works on the kept values in fp32 with true IEEE division.
+typedef uint32_t u32x4_r __attribute__((ext_vector_type(4)));
+typedef short i16x2_r __attribute__((ext_vector_type(2)));
+
+template <int CHUNKS>
+__global__ void __launch_bounds__(256)
+k_prune_fq_wave(bf16_t *__restrict__ a, const RowAct *__restrict__ ra, const int32_t *__restrict__ perm, int quant,
+                int64_t M)
+{
+    constexpr int DFF = CHUNKS * 512;
+    const int lane = threadIdx.x & 63;
+    const int64_t slot = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (slot >= M) return;                                   // whole wave
+    const int64_t r = perm ? perm[slot] : slot;
+    const RowAct act = ra[r];
+    const int bits = __builtin_amdgcn_readfirstlane(quant ? act.bits : 16);
+    const int m = __builtin_amdgcn_readfirstlane(act.m);
+    if (m >= DFF && bits >= 16) return;                      // dense bucket: the row is already final
+    bf16_t *ar = a + r * DFF;
+    u32x4_r d[CHUNKS];
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) d[c] = *reinterpret_cast<const u32x4_r *>(ar + (c * 64 + lane) * 8);
+
+    // largest magnitude key of the row
+    uint32_t kmax = 0u;
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c)
+#pragma unroll
+        for (int wi = 0; wi < 4; ++wi) {
+            const uint32_t k2 = d[c][wi] & 0x7FFF7FFFu;
+            const uint32_t lo16 = k2 & 0xFFFFu, hi16 = k2 >> 16;
+            kmax = lo16 > kmax ? lo16 : kmax;
+            kmax = hi16 > kmax ? hi16 : kmax;
+        }
+    kmax = wave_max_u32(kmax);
+
+    if (m < DFF) {
+        // invariant: count(key >= lo) >= m, count(key >= hi + 1) < m
+        uint32_t lo = 0u, hi = kmax;
+        while (lo < hi) {
+            const uint32_t mid = lo + ((hi - lo + 1u) >> 1);
+            const uint32_t mid2 = mid | (mid << 16);
+            uint32_t below = 0u;                             // keys < mid held by this lane
+#pragma unroll
+            for (int c = 0; c < CHUNKS; ++c)
+#pragma unroll
+                for (int wi = 0; wi < 4; ++wi) {
+                    const i16x2_r diff = __builtin_bit_cast(i16x2_r, d[c][wi] & 0x7FFF7FFFu) - __builtin_bit_cast(i16x2_r, mid2);
+                    below += __popc(__builtin_bit_cast(uint32_t, diff) & 0x80008000u);
+                }
+            const int cnt = DFF - (int)wave_reduce_dpp<uint32_t>(below, 0u, [](uint32_t x, uint32_t y) { return x + y; });
+            if (cnt >= m) lo = mid; else hi = mid - 1u;
+        }
+        const uint32_t thr = lo, thr2 = thr | (thr << 16);
+        // keys above the threshold, then ties in channel order until the quota is used up
+        uint32_t above = 0u;
+#pragma unroll
+        for (int c = 0; c < CHUNKS; ++c)
+#pragma unroll
+            for (int wi = 0; wi < 4; ++wi) {
+                const i16x2_r diff = __builtin_bit_cast(i16x2_r, thr2) - __builtin_bit_cast(i16x2_r, d[c][wi] & 0x7FFF7FFFu);
+                above += __popc(__builtin_bit_cast(uint32_t, diff) & 0x80008000u);      // thr < key
+            }
+        int quota = m - (int)wave_reduce_dpp<uint32_t>(above, 0u, [](uint32_t x, uint32_t y) { return x + y; });
+        const unsigned long long lt_mask = (1ull << lane) - 1ull;
+#pragma unroll
+        for (int c = 0; c < CHUNKS; ++c) {
+            int before = 0, total = 0;                       // ties in lower lanes / in the whole chunk
+            bool tie[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t k = (e & 1) ? ((d[c][e >> 1] >> 16) & 0x7FFFu) : (d[c][e >> 1] & 0x7FFFu);
+                tie[e] = k == thr;
+                const unsigned long long bal = __ballot(tie[e]);
+                before += __popcll(bal & lt_mask);
+                total += __popcll(bal);
+            }
+            int mine = 0;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t k = (e & 1) ? ((d[c][e >> 1] >> 16) & 0x7FFFu) : (d[c][e >> 1] & 0x7FFFu);
+                const bool keep = k > thr || (tie[e] && before + mine < quota);
+                mine += tie[e];
+                if (!keep) d[c][e >> 1] &= (e & 1) ? 0x0000FFFFu : 0xFFFF0000u;
+            }
+            quota = quota > total ? quota - total : 0;
+        }
+    }
+    if (bits < 16 && kmax != 0u) {
+        const float qmax = fq_qmax(bits);
+        const float s = __uint_as_float(kmax << 16) / qmax;  // the largest magnitude is always kept
+#pragma unroll
+        for (int c = 0; c < CHUNKS; ++c)
+#pragma unroll
+            for (int wi = 0; wi < 4; ++wi) {
+                const float v0 = __uint_as_float(d[c][wi] << 16), v1 = __uint_as_float(d[c][wi] & 0xFFFF0000u);
+                d[c][wi] = pack_bf16x2(fq_code(v0, s, qmax) * s, fq_code(v1, s, qmax) * s);
+            }
+    }
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) *reinterpret_cast<u32x4_r *>(ar + (c * 64 + lane) * 8) = d[c];
+}
+
 void launch_prune_fq(void *a, int dtype, const RowAct *ra, const int32_t *perm, bool quant, int64_t M, int dff,
                      hipStream_t st)
 {
     if (M <= 0) return;
+    if (dtype == 1 && dff % 512 == 0) {
+        const dim3 grid((unsigned)((M + 3) / 4));
+#define SOL_PRUNE_CASE(C)                                                                                       \
+    case C:                                                                                                     \
+        hipLaunchKernelGGL((k_prune_fq_wave<C>), grid, dim3(256), 0, st, (bf16_t *)a, ra, perm, quant ? 1 : 0, M); \
+        return;
+        switch (dff / 512) {
+            SOL_PRUNE_CASE(2) SOL_PRUNE_CASE(4) SOL_PRUNE_CASE(8) SOL_PRUNE_CASE(16) SOL_PRUNE_CASE(22)
+            SOL_PRUNE_CASE(28)
+        default: break;
+        }
+#undef SOL_PRUNE_CASE
+    }
     const size_t lds = (size_t)dff * sizeof(float);
     if (dtype == 0)
         hipLaunchKernelGGL((k_prune_fq<float>), dim3((unsigned)M), dim3(ROW_BLOCK), lds, st, (float *)a, ra, perm,
@@ -558,6 +682,21 @@ k_test_quant(const float *__restrict__ z, int n, const int32_t *__restrict__ bit
         codes[r * n + j] = (int32_t)c;
         zhat[r * n + j] = c * s;
     }
+}
+
+__global__ void k_fill_rowact(const int32_t *__restrict__ m, const int32_t *__restrict__ bits, RowAct *__restrict__ ra, int rows)
+{
+    const int r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r < rows) ra[r] = RowAct{1u, 1u, m[r], bits[r]};
+}
+
+void launch_test_prune_quant(void *a, int dtype, int rows, int n, const int32_t *m, const int32_t *bits, void *scratch,
+                             hipStream_t st)
+{
+    if (rows <= 0 || n <= 0) return;
+    RowAct *ra = (RowAct *)scratch;
+    hipLaunchKernelGGL(k_fill_rowact, dim3((rows + 255) / 256), dim3(256), 0, st, m, bits, ra, rows);
+    launch_prune_fq(a, dtype, ra, nullptr, true, rows, n, st);
 }
 
 void launch_test_topk(const float *scores, int rows, int n_cols, const int32_t *n_valid, const int32_t *k,

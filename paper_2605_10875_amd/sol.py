@@ -19,7 +19,7 @@ OP_LAYER_FORWARD, OP_DECODE_STEP, OP_SCHEDULE_LOGLIK = 0, 1, 2
 EXPORTS = ("sol_validate_config", "sol_create", "sol_destroy", "sol_last_error", "sol_workspace_bytes",
            "sol_layer_forward", "sol_decode_step", "sol_schedule_loglik", "sol_device_status",
            "sol_profile_enable", "sol_profile_read",
-           "sol_test_topk_select", "sol_test_prune_mask", "sol_test_quant_codes")
+           "sol_test_topk_select", "sol_test_prune_mask", "sol_test_prune_quant", "sol_test_quant_codes")
 
 
 class ActionDef(C.Structure):
@@ -89,6 +89,8 @@ def lib():
                                        C.POINTER(C.c_int)]
         L.sol_test_topk_select.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.sol_test_prune_mask.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.sol_test_prune_quant.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
+                                           C.c_size_t, C.c_void_p]
         L.sol_test_quant_codes.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
                                            C.c_void_p, C.c_void_p]
         _lib = L
@@ -285,6 +287,18 @@ def prune_mask(a, m, stream=None):
     if rc:
         raise SolError(rc, "sol_test_prune_mask")
     return keep
+
+
+def prune_quant(a, m, bits, stream=None):
+    """Runs the layer's prune + quantise kernel in place on a copy of a [rows][n] (bf16 or fp32)."""
+    rows, n = a.shape
+    out = a.clone().contiguous()
+    scratch = torch.empty(max(16 * rows, 16), dtype=torch.uint8, device="cuda")
+    rc = lib().sol_test_prune_quant(_ptr(out), _dtype_code(out), rows, n, _ptr(_i32(m)), _ptr(_i32(bits)),
+                                    _ptr(scratch), scratch.numel(), _stream(stream))
+    if rc:
+        raise SolError(rc, "sol_test_prune_quant")
+    return out
 
 
 def quant_codes(z, bits, stream=None):
