@@ -285,6 +285,13 @@ static void carve_layer(Carver &c, const sol_model_cfg &g, int64_t n_seq, int64_
     w.h = c.take(es * M * g.d_model);
     w.qb = c.take(es * M * nq);
     w.a = c.take(es * M * g.d_ff);
+    if (g.dtype == SOL_BF16 && M <= 64) {               // decode: K-split partial sums of the skinny GEMMs
+        const int64_t cand[4] = {(int64_t)skinny_splits((int)M, (int)(nq + 2 * nkv), g.d_model) * (nq + 2 * nkv),
+                                 (int64_t)skinny_splits((int)M, g.d_model, (int)nq) * g.d_model,
+                                 (int64_t)skinny_splits((int)M, 2 * g.d_ff, g.d_model) * 2 * g.d_ff,
+                                 (int64_t)skinny_splits((int)M, g.d_model, g.d_ff) * g.d_model};
+        for (int64_t v : cand) if (v > wide) wide = v;
+    }
     w.big32 = (float *)c.take(4 * M * wide);
     w.o32 = (float *)c.take(4 * M * nq);
     w.x2 = (float *)c.take(4 * M * g.d_model);
@@ -363,26 +370,37 @@ static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_i
         launch_rmsnorm_fq(x_in, dt, nullptr, nullptr, lw->w_in_norm, dt, w.h, dt, w.ra, qs & SOL_QS_QKV_IN, M, d, g.rms_eps, st);
     }
     const bool mfma = dt == SOL_BF16;
+    const bool skinny = mfma && M <= 64 && d % 64 == 0 && nq % 64 == 0 && dff % 64 == 0;   // decode: HBM-bound GEMMs
     bool fused_qkv = false;
+    int ns_qkv = 1;
     {   // q/k/v projections (+ rotary and cache write when fused)
         STAGE(ctx, ST_QKV, st);
-        fused_qkv = mfma && launch_gemm_qkv_rope(w.h, lw->wq, lw->wk, lw->wv, w.qb, kc, vc, ctx->d_rope, pos0, n_seq, T,
-                                                 L_max, Hq, Hkv, dh, d, ctx->d_flags, st);
-        if (!fused_qkv) {
-            launch_gemm_generic(w.h, dt, d, lw->wq, dt, d, w.big32, nqkv, M, nq, d, st);
-            launch_gemm_generic(w.h, dt, d, lw->wk, dt, d, w.big32 + nq, nqkv, M, nkv, d, st);
-            launch_gemm_generic(w.h, dt, d, lw->wv, dt, d, w.big32 + nq + nkv, nqkv, M, nkv, d, st);
+        if (skinny) {
+            ns_qkv = skinny_splits((int)M, nqkv, d);
+            if (!launch_gemm_skinny(w.h, d, lw->wq, nq, lw->wk, nkv, lw->wv, nkv, (int)M, d, w.big32, ns_qkv, st))
+                return fail(ctx, SOL_ERR_UNSUPPORTED, "skinny GEMM: unsupported shape");
+        } else {
+            fused_qkv = mfma && launch_gemm_qkv_rope(w.h, lw->wq, lw->wk, lw->wv, w.qb, kc, vc, ctx->d_rope, pos0, n_seq,
+                                                     T, L_max, Hq, Hkv, dh, d, ctx->d_flags, st);
+            if (!fused_qkv) {
+                launch_gemm_generic(w.h, dt, d, lw->wq, dt, d, w.big32, nqkv, M, nq, d, st);
+                launch_gemm_generic(w.h, dt, d, lw->wk, dt, d, w.big32 + nq, nqkv, M, nkv, d, st);
+                launch_gemm_generic(w.h, dt, d, lw->wv, dt, d, w.big32 + nq + nkv, nqkv, M, nkv, d, st);
+            }
         }
     }
     if (!fused_qkv) {   // rotary, cache write
         STAGE(ctx, ST_ROPE, st);
-        launch_rope_store(w.big32, w.qb, kc, vc, dt, ctx->d_rope, pos0, n_seq, T, L_max, Hq, Hkv, dh, ctx->d_flags, st);
+        launch_rope_store(w.big32, w.qb, kc, vc, dt, ctx->d_rope, pos0, n_seq, T, L_max, Hq, Hkv, dh, ctx->d_flags, st,
+                          ns_qkv);
     }
     {   // scores, budgeted selection, softmax over kept keys, times V
         STAGE(ctx, ST_ATTN, st);
         const bool tiled = mfma && w.vt && T >= 16 && L_max <= 4096 &&
                            launch_attn_tile(w.qb, kc, vc, w.vt, w.o32, w.ra, pos0, n_seq, T, L_max, Hq, Hkv, dh, st);
-        if (!tiled &&
+        const bool dec = !tiled && mfma && T == 1 && pos0 &&
+                         launch_attn_decode(w.qb, kc, vc, w.o32, w.ra, pos0, n_seq, L_max, Hq, Hkv, dh, ctx->d_flags, st);
+        if (!tiled && !dec &&
             !launch_attn_rows(w.qb, kc, vc, dt, w.o32, w.ra, pos0, n_seq, T, L_max, Hq, Hkv, dh, ctx->d_flags, st))
             return fail(ctx, SOL_ERR_UNSUPPORTED, "attention: L_max too long for the on-chip score rows of this build");
     }
@@ -391,44 +409,62 @@ static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_i
         launch_fq_rows(w.o32, w.qb, dt, w.ra, qs & SOL_QS_O_IN, M, nq, st);
     }
     bool fused_o = false;
+    int ns_o = 1;
     {   // output projection (+ residual when fused: x2 = x + attn)
         STAGE(ctx, ST_OPROJ, st);
-        fused_o = mfma && launch_gemm_resid_f32(w.qb, lw->wo, x_in, w.x2, M, d, nq, st);
-        if (!fused_o) launch_gemm_generic(w.qb, dt, nq, lw->wo, dt, nq, w.big32, d, M, d, nq, st);
+        if (skinny) {
+            ns_o = skinny_splits((int)M, d, nq);
+            launch_gemm_skinny(w.qb, nq, lw->wo, d, nullptr, 0, nullptr, 0, (int)M, nq, w.big32, ns_o, st);
+        } else {
+            fused_o = mfma && launch_gemm_resid_f32(w.qb, lw->wo, x_in, w.x2, M, d, nq, st);
+            if (!fused_o) launch_gemm_generic(w.qb, dt, nq, lw->wo, dt, nq, w.big32, d, M, d, nq, st);
+        }
     }
     {   // post norm + quantise (gate/up input)
         STAGE(ctx, ST_NORM_POST, st);
         if (fused_o)
             launch_rmsnorm_fq(w.x2, SOL_F32, nullptr, nullptr, lw->w_post_norm, dt, w.h, dt, w.ra, qs & SOL_QS_GATEUP_IN, M, d, g.rms_eps, st);
         else
-            launch_rmsnorm_fq(x_in, dt, w.big32, w.x2, lw->w_post_norm, dt, w.h, dt, w.ra, qs & SOL_QS_GATEUP_IN, M, d, g.rms_eps, st);
+            launch_rmsnorm_fq(x_in, dt, w.big32, w.x2, lw->w_post_norm, dt, w.h, dt, w.ra, qs & SOL_QS_GATEUP_IN, M, d, g.rms_eps, st, ns_o);
     }
     bool fused_gu = false;
+    int ns_gu = 1;
     {   // gate / up (+ SiLU(gate)*up when fused)
         STAGE(ctx, ST_GATEUP, st);
-        fused_gu = mfma && launch_gemm_gateup_silu(w.h, lw->w_gate, lw->w_up, w.a, M, dff, d, st);
-        if (!fused_gu) {
-            launch_gemm_generic(w.h, dt, d, lw->w_gate, dt, d, w.big32, 2 * (int64_t)dff, M, dff, d, st);
-            launch_gemm_generic(w.h, dt, d, lw->w_up, dt, d, w.big32 + dff, 2 * (int64_t)dff, M, dff, d, st);
+        if (skinny) {
+            ns_gu = skinny_splits((int)M, 2 * dff, d);
+            launch_gemm_skinny(w.h, d, lw->w_gate, dff, lw->w_up, dff, nullptr, 0, (int)M, d, w.big32, ns_gu, st);
+        } else {
+            fused_gu = mfma && launch_gemm_gateup_silu(w.h, lw->w_gate, lw->w_up, w.a, M, dff, d, st);
+            if (!fused_gu) {
+                launch_gemm_generic(w.h, dt, d, lw->w_gate, dt, d, w.big32, 2 * (int64_t)dff, M, dff, d, st);
+                launch_gemm_generic(w.h, dt, d, lw->w_up, dt, d, w.big32 + dff, 2 * (int64_t)dff, M, dff, d, st);
+            }
         }
     }
     if (!fused_gu) {   // SiLU(gate)*up
         STAGE(ctx, ST_SILU, st);
-        launch_silu_mul(w.big32, w.a, dt, M, dff, st);
+        launch_silu_mul(w.big32, w.a, dt, M, dff, st, ns_gu);
     }
     {   // magnitude pruning + quantise (down input), rows visited in bucket order
         STAGE(ctx, ST_PRUNE, st);
         launch_prune_fq(w.a, dt, w.ra, w.perm, qs & SOL_QS_DOWN_IN, M, dff, st);
     }
     bool fused_down = false;
+    int ns_down = 1;
     {   // down projection (+ residual when fused)
         STAGE(ctx, ST_DOWN, st);
-        fused_down = mfma && launch_gemm_resid_out(w.a, lw->w_down, w.x2, x_out, M, d, dff, st);
-        if (!fused_down) launch_gemm_generic(w.a, dt, dff, lw->w_down, dt, dff, w.big32, d, M, d, dff, st);
+        if (skinny) {
+            ns_down = skinny_splits((int)M, d, dff);
+            launch_gemm_skinny(w.a, dff, lw->w_down, d, nullptr, 0, nullptr, 0, (int)M, dff, w.big32, ns_down, st);
+        } else {
+            fused_down = mfma && launch_gemm_resid_out(w.a, lw->w_down, w.x2, x_out, M, d, dff, st);
+            if (!fused_down) launch_gemm_generic(w.a, dt, dff, lw->w_down, dt, dff, w.big32, d, M, d, dff, st);
+        }
     }
     if (!fused_down) {   // residual
         STAGE(ctx, ST_RESID, st);
-        launch_resid_out(w.x2, w.big32, x_out, dt, M, d, st);
+        launch_resid_out(w.x2, w.big32, x_out, dt, M, d, st, ns_down);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(ctx, SOL_ERR_HIP, std::string("kernel launch: ") + hipGetErrorString(e));

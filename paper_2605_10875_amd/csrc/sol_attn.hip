@@ -457,6 +457,312 @@ k_attn_tile(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const b
     AT_STAMP(5);
 }
 
+// =================================================================================================
+// Decode attention (one query per sequence, bf16, HBM-bound): one workgroup of 16 waves per
+// (sequence, KV head) serves the HPB = 4 query heads that share that KV head, so K is streamed from
+// HBM once and V rows are fetched once if any of the four heads kept them.
+//   1. scores on MFMA: A = a tile of 16 keys (each lane loads 16 contiguous bytes of a K row straight
+//      from global memory, four tiles in flight per wave), B = the query heads as columns; fp32 scores
+//      of all four heads go to LDS.
+//   2. selection: the 4 waves of a head hold a quarter of the row each in registers and bisect the
+//      key range together, exchanging their ballot counts through LDS once per step.
+//   3. softmax numerators back to LDS, 4. V rows gathered where any head kept the key.
+// =================================================================================================
+constexpr int DEC_WAVES = 16, DEC_BLOCK = DEC_WAVES * 64, DEC_HPB = 4, DEC_GW = DEC_WAVES / DEC_HPB;
+
+template <int DH, int SLOTS>
+__global__ void __launch_bounds__(DEC_BLOCK)
+k_attn_decode(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf16_t *__restrict__ vc,
+              float *__restrict__ o32, const RowAct *__restrict__ ra, const int32_t *__restrict__ cache_len, int L_max,
+              int Hq, int Hkv, float scale, int *flags)
+{
+    constexpr int KK = DH / 32, SLICE = SLOTS * 64, LPAD = SLICE * DEC_GW, NJ = SLOTS / 4;
+    constexpr int VEC = 8, LPK = DH / VEC, KPI = DEC_BLOCK / LPK;
+    extern __shared__ __align__(16) float sc[];               // [DEC_HPB][LPAD]; later partial O [DEC_WAVES][HPB][DH]
+    __shared__ int s_cnt[2][DEC_WAVES];
+    __shared__ uint32_t s_min[DEC_WAVES], s_max[DEC_WAVES];
+    __shared__ int s_done[2][DEC_HPB];
+    __shared__ int s_gt[DEC_WAVES];
+    __shared__ float s_den[DEC_WAVES];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kvh = blockIdx.x, s = blockIdx.y;
+    const int p0 = __builtin_amdgcn_readfirstlane(cache_len[s]);
+    if (p0 < 0 || p0 + 1 > L_max) {
+        if (tid == 0) atomicOr(flags, FLAG_CACHE_OVERFLOW);
+        return;
+    }
+    const int n = p0 + 1;                                      // keys 0..p0 (the new token's key included)
+    const int h0 = kvh * DEC_HPB;
+    const bf16_t *kbase = kc + ((int64_t)s * Hkv + kvh) * (int64_t)L_max * DH;
+    const bf16_t *vbase = vc + ((int64_t)s * Hkv + kvh) * (int64_t)L_max * DH;
+    const int l16 = lane & 15, lg = lane >> 4;
+
+    // ---- 1. scores -----------------------------------------------------------------------------
+    {
+        bf16x8_a qf[KK];                                       // B operand: column = head (l16 < HPB), zero elsewhere
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+            u32x4_a v = {0u, 0u, 0u, 0u};
+            if (l16 < DEC_HPB)
+                v = *reinterpret_cast<const u32x4_a *>(q + (int64_t)s * (Hq * DH) + (int64_t)(h0 + l16) * DH + kk * 32 + lg * 8);
+            qf[kk] = __builtin_bit_cast(bf16x8_a, v);
+        }
+        const int n_kt = (n + 15) >> 4;
+        constexpr int U = 4;
+        for (int kt0 = w; kt0 < n_kt; kt0 += DEC_WAVES * U) {
+            bf16x8_a kf[U][KK];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                int key = (kt0 + u * DEC_WAVES) * 16 + l16;
+                if (key >= n) key = n - 1;
+                const bf16_t *kp = kbase + (int64_t)key * DH + lg * 8;
+#pragma unroll
+                for (int kk = 0; kk < KK; ++kk)
+                    kf[u][kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(kp + kk * 32));
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int kt = kt0 + u * DEC_WAVES;
+                if (kt < n_kt) {
+                    floatx4_a acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int kk = 0; kk < KK; ++kk)
+                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[u][kk], qf[kk], acc, 0, 0, 0);
+                    if (l16 < DEC_HPB) {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) sc[l16 * LPAD + kt * 16 + lg * 4 + r] = acc[r] * scale;
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- 2. selection: DEC_GW waves per head, each with SLICE columns in registers --------------
+    const int head = w / DEC_GW, wg = w - head * DEC_GW;
+    const int base = wg * SLICE;
+    int n_loc = n - base;
+    n_loc = n_loc < 0 ? 0 : (n_loc > SLICE ? SLICE : n_loc);   // valid columns held by this wave
+    float *row = sc + head * LPAD + base;
+    uint32_t key[SLOTS];                                        // the score itself is recovered from its key
+    uint32_t kmax = 0u, kmin = 0xFFFFFFFFu;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        if (256 * j < n_loc) {
+            const f32x4_a v = *reinterpret_cast<const f32x4_a *>(row + 256 * j + 4 * lane);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const bool valid = 256 * j + 4 * lane + e < n_loc;
+                const uint32_t kv = valid ? score_key(v[e]) : 0u;
+                key[4 * j + e] = kv;
+                kmax = kv > kmax ? kv : kmax;
+                kmin = (valid && kv < kmin) ? kv : kmin;
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) key[4 * j + e] = 0u;
+        }
+    }
+    kmax = wave_max_u32(kmax);
+    kmin = wave_min_u32(kmin);
+    if (lane == 0) { s_max[w] = kmax; s_min[w] = kmin; }
+    __syncthreads();
+    uint32_t lo = 0xFFFFFFFFu, hi = 0u;
+#pragma unroll
+    for (int i = 0; i < DEC_GW; ++i) {
+        const uint32_t a = s_min[head * DEC_GW + i], c = s_max[head * DEC_GW + i];
+        lo = a < lo ? a : lo;
+        hi = c > hi ? c : hi;
+    }
+    // values read back from LDS are wave-uniform: move them to scalar registers so that the search
+    // below is scalar control flow
+    lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)lo);
+    hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)hi);
+    const float mx = score_unkey(hi);                          // the head's best score, always kept
+    const RowAct act = ra[s];
+    const int b = __builtin_amdgcn_readfirstlane(budget_ceil(act.keep_num, act.keep_den, n));   // 64-bit divide runs on the VALU
+    uint32_t thr = 1u;                                         // budget keeps all: every valid key passes
+    bool done = b >= n, exact = true;
+    // invariant while searching: count(key >= lo) >= b, count(key >= hi + 1) < b
+    for (int it = 0; it < 34; ++it) {
+        const int par = it & 1;
+        uint32_t mid = 0u;
+        if (!done) {
+            mid = lo + ((hi - lo + 1u) >> 1);
+            const int c = wave_count_ge<SLOTS>(key, n_loc, mid);
+            if (lane == 0) s_cnt[par][w] = c;
+        }
+        if (wg == 0 && lane == 0) s_done[par][head] = done || lo >= hi;
+        __syncthreads();
+        if (!done) {
+            if (lo >= hi) { thr = lo; exact = false; done = true; }
+            else {
+                int cnt = 0;
+#pragma unroll
+                for (int i = 0; i < DEC_GW; ++i) cnt += s_cnt[par][head * DEC_GW + i];
+                cnt = __builtin_amdgcn_readfirstlane(cnt);
+                if (cnt == b) { thr = mid; done = true; }
+                else if (cnt > b) lo = mid; else hi = mid - 1u;
+            }
+        }
+        const bool all_done =
+            __builtin_amdgcn_readfirstlane(s_done[par][0] & s_done[par][1] & s_done[par][2] & s_done[par][3]) != 0;
+        if (all_done) break;                                   // uniform: every wave reads the same flags
+    }
+    // Ties at the threshold go to the lower columns. Rare for fp32 scores, so the fix-up is a plain
+    // loop by the first wave of the head over the row in LDS: tied keys beyond the quota get -inf.
+    {
+        const bool need = (b < n) && !exact;
+        int gt = 0;
+        if (need) {
+#pragma unroll
+            for (int i = 0; i < SLOTS; ++i) gt += __popcll(__ballot(key[i] > thr));
+        }
+        if (lane == 0) s_gt[w] = gt;
+        __syncthreads();
+        if (need && wg == 0) {
+            int quota = b;
+#pragma unroll
+            for (int i = 0; i < DEC_GW; ++i) quota -= s_gt[head * DEC_GW + i];
+            quota = __builtin_amdgcn_readfirstlane(quota);      // >= 1 tied keys stay
+            float *hrow = sc + head * LPAD;
+            int taken = 0;
+            for (int c0 = 0; c0 < n; c0 += 64) {
+                const int col = c0 + lane;
+                const bool tie = col < n && score_key(hrow[col]) == thr;
+                const unsigned long long bal = __ballot(tie);
+                const int rank = taken + __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0));
+                if (tie && rank >= quota) hrow[col] = -INFINITY;
+                taken += __popcll(bal);
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- 3. softmax numerators back to LDS ----------------------------------------------------------
+    float den = 0.f;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        if (256 * j < n_loc) {
+            const f32x4_a v = *reinterpret_cast<const f32x4_a *>(row + 256 * j + 4 * lane);
+            f32x4_a p;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const bool on = (256 * j + 4 * lane + e < n_loc) && score_key(v[e]) >= thr;
+                p[e] = on ? __expf(v[e] - mx) : 0.f;
+                den += p[e];
+            }
+            *reinterpret_cast<f32x4_a *>(row + 256 * j + 4 * lane) = p;
+        }
+    }
+    den = wave_sum_dpp(den);
+    if (lane == 0) s_den[w] = den;
+    __syncthreads();
+
+    // ---- 4. o = sum p_j v_j over rows any head kept ---------------------------------------------------
+    const int ks = tid / LPK, cs = tid - ks * LPK;
+    float acc[DEC_HPB][VEC];
+#pragma unroll
+    for (int hh = 0; hh < DEC_HPB; ++hh)
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[hh][e] = 0.f;
+    constexpr int UV = 4;
+    for (int j0 = ks; j0 < n; j0 += KPI * UV) {
+        float p[UV][DEC_HPB];
+        u32x4_a vv[UV];
+        bool any[UV];
+#pragma unroll
+        for (int u = 0; u < UV; ++u) {
+            const int j = j0 + u * KPI;
+            any[u] = false;
+#pragma unroll
+            for (int hh = 0; hh < DEC_HPB; ++hh) {
+                p[u][hh] = (j < n) ? sc[hh * LPAD + j] : 0.f;
+                any[u] |= p[u][hh] != 0.f;
+            }
+            vv[u] = u32x4_a{0u, 0u, 0u, 0u};
+            if (any[u]) vv[u] = *reinterpret_cast<const u32x4_a *>(vbase + (int64_t)j * DH + cs * VEC);
+        }
+#pragma unroll
+        for (int u = 0; u < UV; ++u) {
+            if (any[u]) {
+#pragma unroll
+                for (int wi = 0; wi < 4; ++wi) {
+                    const float v0 = __uint_as_float(vv[u][wi] << 16), v1 = __uint_as_float(vv[u][wi] & 0xFFFF0000u);
+#pragma unroll
+                    for (int hh = 0; hh < DEC_HPB; ++hh) {
+                        acc[hh][2 * wi] = fmaf(p[u][hh], v0, acc[hh][2 * wi]);
+                        acc[hh][2 * wi + 1] = fmaf(p[u][hh], v1, acc[hh][2 * wi + 1]);
+                    }
+                }
+            }
+        }
+    }
+    // reduce over the key slots of a wave (lanes with equal cs), then across waves in fixed order
+    for (int o = LPK; o < 64; o <<= 1)
+#pragma unroll
+        for (int hh = 0; hh < DEC_HPB; ++hh)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[hh][e] += __shfl_xor(acc[hh][e], o, 64);
+    __syncthreads();                                           // all reads of the numerators are done
+    float *ored = sc;                                          // [DEC_WAVES][HPB][DH]
+    if (lane < LPK) {
+#pragma unroll
+        for (int hh = 0; hh < DEC_HPB; ++hh)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) ored[((size_t)w * DEC_HPB + hh) * DH + lane * VEC + e] = acc[hh][e];
+    }
+    __syncthreads();
+    for (int idx = tid; idx < DEC_HPB * DH; idx += DEC_BLOCK) {
+        const int hh = idx / DH;
+        float t = 0.f, dsum = 0.f;
+        for (int ww = 0; ww < DEC_WAVES; ++ww) t += ored[(size_t)ww * DEC_HPB * DH + idx];
+#pragma unroll
+        for (int i = 0; i < DEC_GW; ++i) dsum += s_den[hh * DEC_GW + i];
+        o32[(int64_t)s * (Hq * DH) + (int64_t)h0 * DH + idx] = t / dsum;
+    }
+}
+
+template <int DH, int SLOTS>
+static bool launch_attn_decode_t(const void *q, const void *kc, const void *vc, float *o32, const RowAct *ra,
+                                 const int32_t *cache_len, int B, int L_max, int Hq, int Hkv, int *flags, hipStream_t st)
+{
+    auto kern = k_attn_decode<DH, SLOTS>;
+    const size_t lds = (size_t)DEC_HPB * SLOTS * 64 * DEC_GW * 4;
+    static bool attr_done = false;
+    if (!attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds) != hipSuccess)
+            return false;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(Hkv, B), dim3(DEC_BLOCK), lds, st, (const bf16_t *)q, (const bf16_t *)kc,
+                       (const bf16_t *)vc, o32, ra, cache_len, L_max, Hq, Hkv, 1.0f / sqrtf((float)DH), flags);
+    return true;
+}
+
+// One query per sequence (T = 1), bf16, 4 query heads per KV head, head_dim 64 / 128, L_max <= 9216.
+bool launch_attn_decode(const void *q, const void *k_cache, const void *v_cache, float *o32, const RowAct *ra,
+                        const int32_t *cache_len, int B, int L_max, int Hq, int Hkv, int dh, int *flags, hipStream_t st)
+{
+    if (B <= 0) return true;
+    if (!cache_len || Hq != DEC_HPB * Hkv || (dh != 64 && dh != 128) || L_max > 9216) return false;
+    const size_t red = (size_t)DEC_WAVES * DEC_HPB * dh * 4;
+#define SOL_DEC(SL)                                                                                             \
+    if ((size_t)DEC_HPB * SL * 64 * DEC_GW * 4 >= red)                                                           \
+        return dh == 64 ? launch_attn_decode_t<64, SL>(q, k_cache, v_cache, o32, ra, cache_len, B, L_max, Hq, Hkv, flags, st) \
+                        : launch_attn_decode_t<128, SL>(q, k_cache, v_cache, o32, ra, cache_len, B, L_max, Hq, Hkv, flags, st)
+    if (L_max <= 1024) { SOL_DEC(4); }
+    if (L_max <= 2048) { SOL_DEC(8); }
+    if (L_max <= 4096) { SOL_DEC(16); }
+    if (L_max <= 8192) { SOL_DEC(32); }
+    SOL_DEC(36);                                   // 9216 columns: an 8192-token cache plus the tokens being decoded
+#undef SOL_DEC
+    return false;
+}
+
 // V cache [s][kvh][key][dh] -> vt [s][kvh][dh][lpadv] for keys < pos0[s] + Tn, zero beyond.
 template <int DH>
 __global__ void __launch_bounds__(256)

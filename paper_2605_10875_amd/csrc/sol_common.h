@@ -253,6 +253,54 @@ __device__ __forceinline__ float score_unkey(uint32_t k)
     return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
 }
 
+// Keys equal to thr: the first `quota` of them in column order (column = 256*j + 4*lane + e) stay, the
+// others are overwritten with 0 so that afterwards  kept <=> key >= thr. Returns the number of keys
+// equal to thr that this wave held (before the overwrite).
+template <int SLOTS>
+__device__ __forceinline__ int wave_tie_fixup(uint32_t (&key)[SLOTS], int n, uint32_t thr, int quota, int lane)
+{
+    constexpr int NJ = SLOTS / 4;
+    (void)lane;
+    int total = 0;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        if (256 * j < n) {
+            int below = 0, here = 0;                    // ties in lower lanes of this j / in all lanes
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const unsigned long long bal = __ballot(key[4 * j + e] == thr);
+                below = __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, below));
+                here += __popcll(bal);
+            }
+            int mine = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const bool tie = key[4 * j + e] == thr;
+                if (tie && below + mine >= quota) key[4 * j + e] = 0u;     // loses the tie
+                mine += tie;
+            }
+            total += here;
+            quota = quota > here ? quota - here : 0;
+        }
+        __builtin_amdgcn_sched_barrier(0);              // keep the slot groups sequential: low register pressure
+    }
+    return total;
+}
+
+// number of keys >= pivot held by the wave (columns >= n carry key 0 and pivot >= 1)
+template <int SLOTS>
+__device__ __forceinline__ int wave_count_ge(const uint32_t (&key)[SLOTS], int n, uint32_t pivot)
+{
+    int cnt = 0;
+#pragma unroll
+    for (int j = 0; j < SLOTS / 4; ++j)
+        if (256 * j < n) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) cnt += __popcll(__ballot(key[4 * j + e] >= pivot));
+        }
+    return cnt;
+}
+
 // ---- wave-level exact top-b (keys in registers) ---------------------------------------------------
 // A wave holds SLOTS keys per lane; element (j, e) of lane l is column 256*j + 4*l + e (j < SLOTS/4,
 // e < 4). Columns >= n carry key 0, which is below the key of every real score. Finds the b largest
@@ -292,29 +340,7 @@ __device__ __forceinline__ uint32_t wave_select_topk(uint32_t (&key)[SLOTS], int
 #pragma unroll
             for (int e = 0; e < 4; ++e) n_gt += __popcll(__ballot(key[4 * j + e] > thr));
         }
-    int quota = b - n_gt;                               // >= 1 keys equal to thr are kept, lowest columns first
-    const unsigned long long lt_mask = (1ull << lane) - 1ull;
-#pragma unroll
-    for (int j = 0; j < NJ; ++j) {
-        if (256 * j < n) {
-            unsigned long long bal[4];
-            int below = 0;                              // ties in lower lanes of this j
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                bal[e] = __ballot(key[4 * j + e] == thr);
-                below += __popcll(bal[e] & lt_mask);
-            }
-            int mine = 0;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const bool tie = key[4 * j + e] == thr;
-                if (tie && below + mine >= quota) key[4 * j + e] = 0u;     // loses the tie
-                mine += tie;
-            }
-            quota -= __popcll(bal[0]) + __popcll(bal[1]) + __popcll(bal[2]) + __popcll(bal[3]);
-            if (quota < 0) quota = 0;
-        }
-    }
+    wave_tie_fixup<SLOTS>(key, n, thr, b - n_gt, lane);
     return thr;
 }
 

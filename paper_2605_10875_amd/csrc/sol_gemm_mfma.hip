@@ -383,4 +383,146 @@ bool launch_gemm_f32(const void *a, const void *w, float *C, int64_t ldc, int64_
     return launch_mfma<SOL_TILE>((const bf16_t *)a, K, bm, M, N, K, epi, st);
 }
 
+
+// =================================================================================================
+// Skinny GEMM for the decode step: out[M][Nv] = x[M][K] * Wv[Nv][K]^T with M <= 64 tokens.
+// HBM-bound: every weight byte is read exactly once, by exactly one wave. A wave owns 32 weight
+// rows (they are the MFMA's "A" rows) and streams them straight from global memory in 128-byte
+// pieces (lane (r, h) takes the 64 contiguous bytes of half h of row r, so every fetched line is
+// fully used); the activations are the "B" operand, staged per workgroup in LDS in K chunks of 512.
+// Since the same k-to-lane assignment is used for A and B the MFMA sum is exact. The K range may be
+// split over gridDim.y workgroups; partial sums go to fp32 partial[split][M][Nv] and are folded by
+// the consumer kernel in split order (fixed split count per shape => deterministic).
+// =================================================================================================
+constexpr int SK_KC = 512;                 // K chunk staged in LDS
+constexpr int SK_XROW = SK_KC * 2 + 16;    // padded LDS row of activations (bytes): rows shift 4 banks
+
+template <int MT>                           // MT tiles of 32 tokens (1: M <= 32, 2: M <= 64)
+__global__ void __launch_bounds__(256)
+k_gemm_skinny(const bf16_t *__restrict__ x, int64_t ldx, BMap bmap, int M, int Nv, int K, int k_per_split,
+              float *__restrict__ partial)
+{
+    extern __shared__ __align__(16) unsigned char xs[];      // [MT*32][SK_XROW]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n0 = (blockIdx.x * 4 + wave) * 32;
+    const int split = blockIdx.y;
+    const int k_begin = split * k_per_split;
+    const int k_end = (k_begin + k_per_split < K) ? k_begin + k_per_split : K;
+    const int r = lane & 31, h = lane >> 5;
+    const bool live = n0 < Nv;                                // whole wave
+    int nrow = n0 + r;
+    if (nrow >= Nv) nrow = Nv - 1;
+    const bf16_t *wrow = bmap.row(nrow) + h * 32;             // this lane's 64-byte half of each 128-byte piece
+    floatx16_t acc[MT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
+
+    for (int kc = k_begin; kc < k_end; kc += SK_KC) {
+        const int kw = (k_end - kc < SK_KC) ? (k_end - kc) : SK_KC;   // multiple of 64
+        __syncthreads();                                              // previous chunk fully consumed
+        // stage x[0..MT*32)[kc .. kc+kw) into LDS, 16 bytes per thread per step (rows >= M: zeros)
+        const int pieces = kw / 8;
+        for (int idx = tid; idx < MT * 32 * pieces; idx += 256) {
+            const int m = idx / pieces, p = idx - m * pieces;
+            u32x4_t v = {0u, 0u, 0u, 0u};
+            if (m < M) v = *reinterpret_cast<const u32x4_t *>(x + (int64_t)m * ldx + kc + p * 8);
+            *reinterpret_cast<u32x4_t *>(xs + m * SK_XROW + p * 16) = v;
+        }
+        __syncthreads();
+        if (live) {
+            for (int kb = 0; kb < kw; kb += 128) {                     // two 64-wide K blocks in flight
+                u32x4_t wa[2][4];
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const int ko = (kb + u * 64 < kw) ? kb + u * 64 : kb;   // odd tail: re-read, not used
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        wa[u][j] = *reinterpret_cast<const u32x4_t *>(wrow + kc + ko + j * 8);
+                }
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    if (kb + u * 64 < kw) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const bf16x8_t af = __builtin_bit_cast(bf16x8_t, wa[u][j]);
+#pragma unroll
+                            for (int t = 0; t < MT; ++t) {
+                                const unsigned char *xp = xs + (t * 32 + r) * SK_XROW + (kb + u * 64 + h * 32 + j * 8) * 2;
+                                const bf16x8_t bfr = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t *>(xp));
+                                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfr, acc[t], 0, 0, 0);
+                            }
+                        }
+                    }
+                }
+            }
+        }
+    }
+    if (!live) return;
+    // acc[t][i]: weight row n0 + 8*(i/4) + 4*h + (i%4), token t*32 + r
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+        const int m = t * 32 + r;
+        if (m < M) {
+            float *dst = partial + ((int64_t)split * M + m) * Nv + n0 + 4 * h;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                if (n0 + 8 * g + 4 * h + 3 < Nv) {
+                    const float4 v = make_float4(acc[t][4 * g], acc[t][4 * g + 1], acc[t][4 * g + 2], acc[t][4 * g + 3]);
+                    *reinterpret_cast<float4 *>(dst + 8 * g) = v;
+                }
+            }
+        }
+    }
+}
+
+// Number of K splits for the skinny kernel: enough waves to cover the chip, partial-sum traffic kept
+// below about a quarter of the weight traffic.
+int skinny_splits(int M, int Nv, int K)
+{
+    const int tiles = (Nv + 31) / 32;
+    int want = (1024 + tiles - 1) / tiles;
+    int cap = K / (8 * (M > 0 ? M : 1));
+    if (cap < 1) cap = 1;
+    int s = want < cap ? want : cap;
+    if (s < 1) s = 1;
+    while (s > 1 && (K / 64) % s != 0) --s;                 // every split gets a whole number of 64-wide blocks
+    return s;
+}
+
+static bool launch_skinny(const bf16_t *x, int64_t ldx, const BMap &bm, int M, int Nv, int K, float *partial, int nsplit,
+                          hipStream_t st)
+{
+    if (M <= 0) return true;
+    if (M > 64 || Nv % 4 || K % 64) return false;
+    const int k_per_split = K / nsplit;
+    if (k_per_split % 64) return false;
+    const dim3 grid((Nv + 127) / 128, nsplit);
+    static bool attr_done = false;
+    const size_t lds = (size_t)64 * SK_XROW;
+    if (!attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(k_gemm_skinny<2>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds) != hipSuccess) return false;
+        attr_done = true;
+    }
+    if (M <= 32)
+        hipLaunchKernelGGL((k_gemm_skinny<1>), grid, dim3(256), (size_t)32 * SK_XROW, st, x, ldx, bm, M, Nv, K, k_per_split, partial);
+    else
+        hipLaunchKernelGGL((k_gemm_skinny<2>), grid, dim3(256), lds, st, x, ldx, bm, M, Nv, K, k_per_split, partial);
+    return true;
+}
+
+// partial[nsplit][M][N] = x * [w0; w1; w2]^T  (rows of up to three stacked weight matrices)
+bool launch_gemm_skinny(const void *x, int64_t ldx, const void *w0, int n0, const void *w1, int n1, const void *w2,
+                        int n2, int M, int K, float *partial, int nsplit, hipStream_t st)
+{
+    BMap bm{};
+    bm.base[0] = (const bf16_t *)w0; bm.base[1] = (const bf16_t *)w1; bm.base[2] = (const bf16_t *)w2;
+    bm.seg_end[0] = n0; bm.seg_end[1] = n0 + n1; bm.seg_end[2] = n0 + n1 + n2;
+    bm.mode = 0; bm.half = 0; bm.ld = K;
+    return launch_skinny((const bf16_t *)x, ldx, bm, M, n0 + n1 + n2, K, partial, nsplit, st);
+}
+
 }  // namespace sol

@@ -27,22 +27,23 @@ void launch_bucket_sort(const int32_t *row_bucket, int64_t M, int n_buckets, int
 // x: [M][d] of x_dtype; add: fp32 [M][d] or NULL; ra NULL or quant disabled => no quantiser.
 void launch_rmsnorm_fq(const void *x, int x_dtype, const float *add, float *xsum, const void *w, int w_dtype,
                        void *h, int h_dtype, const RowAct *ra, bool quant, int64_t M, int d, float eps,
-                       hipStream_t st);
+                       hipStream_t st, int nsplit = 1);
 // out = FQ(in, bits) row-wise; in fp32 [M][n] -> out dtype.
 void launch_fq_rows(const float *in, void *out, int out_dtype, const RowAct *ra, bool quant, int64_t M, int n,
                     hipStream_t st);
 // rotary + scatter: qkv32 [M][(Hq+2Hkv)*dh] -> q [M][Hq*dh], K/V caches at position pos0[s]+i.
 void launch_rope_store(const float *qkv32, void *q, void *k_cache, void *v_cache, int dtype, const float2 *rope,
                        const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv, int dh, int *flags,
-                       hipStream_t st);
+                       hipStream_t st, int nsplit = 1);
 // a = silu(g) * u ; gu32 [M][2*dff] (gate cols first) -> a [M][dff]
-void launch_silu_mul(const float *gu32, void *a, int dtype, int64_t M, int dff, hipStream_t st);
+void launch_silu_mul(const float *gu32, void *a, int dtype, int64_t M, int dff, hipStream_t st, int nsplit = 1);
 // in place on a [M][dff]: keep the ra.m largest |a| (ties to lower channel), then FQ.
 // Rows are visited in bucket order through perm (NULL = identity).
 void launch_prune_fq(void *a, int dtype, const RowAct *ra, const int32_t *perm, bool quant, int64_t M, int dff,
                      hipStream_t st);
 // out = x2 + z
-void launch_resid_out(const float *x2, const float *z, void *out, int dtype, int64_t M, int d, hipStream_t st);
+void launch_resid_out(const float *x2, const float *z, void *out, int dtype, int64_t M, int d, hipStream_t st,
+                      int nsplit = 1);
 // x[n][t] = embed[tokens[b][t]]  for n = b*G + g
 void launch_embed(const void *embed, const int32_t *tokens, void *x, int dtype, int B, int G, int T, int d,
                   int vocab, hipStream_t st);
@@ -83,12 +84,22 @@ bool launch_gemm_resid_out(const void *a, const void *w, const float *x2, void *
 // C(fp32, ldc) = a * w^T
 bool launch_gemm_f32(const void *a, const void *w, float *C, int64_t ldc, int64_t M, int N, int K, hipStream_t st);
 
+// Skinny GEMM for M <= 64 rows (decode): partial[nsplit][M][n0+n1+n2] (fp32) = x * [w0; w1; w2]^T, K split over
+// nsplit workgroup rows; the consumer kernels above fold the partial sums (their nsplit argument). The fp32
+// inputs of those kernels (qkv32 / add / gu32 / z) are then laid out [nsplit][M][N].
+bool launch_gemm_skinny(const void *x, int64_t ldx, const void *w0, int n0, const void *w1, int n1, const void *w2,
+                        int n2, int M, int K, float *partial, int nsplit, hipStream_t st);
+int skinny_splits(int M, int Nv, int K);
+
 // ---- attention (sol_attn.hip) ----------------------------------------------------------------
 // One query row per workgroup group: scores over cache positions [0, pos], budgeted top-k,
 // softmax over kept keys, times V. o32: fp32 [M][Hq*dh]. Returns false if the shape is unsupported.
 bool launch_attn_rows(const void *q, const void *k_cache, const void *v_cache, int dtype, float *o32,
                       const RowAct *ra, const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv,
                       int dh, int *flags, hipStream_t st);
+// Decode attention: one query per sequence, bf16, 4 query heads per KV head, L_max <= 9216.
+bool launch_attn_decode(const void *q, const void *k_cache, const void *v_cache, float *o32, const RowAct *ra,
+                        const int32_t *cache_len, int B, int L_max, int Hq, int Hkv, int dh, int *flags, hipStream_t st);
 // Tiled MFMA attention for the batched bf16 pass (L_max <= 4096, head_dim 64 or 128). vt is
 // workspace for the transposed V copy: n_seq * Hkv * dh * attn_tile_lpadv(L_max) elements.
 bool launch_attn_tile(const void *q, const void *k_cache, const void *v_cache, void *vt, float *o32, const RowAct *ra,

@@ -112,9 +112,9 @@ constexpr int ROW_BLOCK = 256;
 
 template <typename TX, typename TW, typename TH>
 __global__ void __launch_bounds__(ROW_BLOCK)
-k_rmsnorm_fq(const TX *__restrict__ x, const float *__restrict__ add, float *__restrict__ xsum,
-             const TW *__restrict__ w, TH *__restrict__ h, const RowAct *__restrict__ ra, int quant, int d,
-             float eps)
+k_rmsnorm_fq(const TX *__restrict__ x, const float *__restrict__ add, int nsplit, int64_t split_stride,
+             float *__restrict__ xsum, const TW *__restrict__ w, TH *__restrict__ h, const RowAct *__restrict__ ra,
+             int quant, int d, float eps)
 {
     extern __shared__ float row[];
     __shared__ float red[ROW_BLOCK / 64];
@@ -124,7 +124,11 @@ k_rmsnorm_fq(const TX *__restrict__ x, const float *__restrict__ add, float *__r
     float ss = 0.f;
     for (int j = tid; j < d; j += ROW_BLOCK) {
         float v = ld(xr + j);
-        if (add) v += add[r * d + j];
+        if (add) {
+            float t = 0.f;
+            for (int sp = 0; sp < nsplit; ++sp) t += add[sp * split_stride + r * d + j];   // fixed split order
+            v += t;
+        }
         if (xsum) xsum[r * d + j] = v;
         row[j] = v;
         ss += v * v;
@@ -152,22 +156,22 @@ k_rmsnorm_fq(const TX *__restrict__ x, const float *__restrict__ add, float *__r
 }
 
 template <typename TX, typename TW, typename TH>
-static void rmsnorm_dispatch3(const void *x, const float *add, float *xsum, const void *w, void *h, const RowAct *ra,
-                              bool quant, int64_t M, int d, float eps, hipStream_t st)
+static void rmsnorm_dispatch3(const void *x, const float *add, int nsplit, float *xsum, const void *w, void *h,
+                              const RowAct *ra, bool quant, int64_t M, int d, float eps, hipStream_t st)
 {
     hipLaunchKernelGGL((k_rmsnorm_fq<TX, TW, TH>), dim3((unsigned)M), dim3(ROW_BLOCK), (size_t)d * sizeof(float), st,
-                       (const TX *)x, add, xsum, (const TW *)w, (TH *)h, ra, quant ? 1 : 0, d, eps);
+                       (const TX *)x, add, nsplit, M * (int64_t)d, xsum, (const TW *)w, (TH *)h, ra, quant ? 1 : 0, d, eps);
 }
 
 void launch_rmsnorm_fq(const void *x, int x_dtype, const float *add, float *xsum, const void *w, int w_dtype, void *h,
-                       int h_dtype, const RowAct *ra, bool quant, int64_t M, int d, float eps, hipStream_t st)
+                       int h_dtype, const RowAct *ra, bool quant, int64_t M, int d, float eps, hipStream_t st, int nsplit)
 {
     if (M <= 0) return;
     const int key = (x_dtype << 2) | (w_dtype << 1) | h_dtype;
     switch (key) {
-    case 0: rmsnorm_dispatch3<float, float, float>(x, add, xsum, w, h, ra, quant, M, d, eps, st); break;
-    case 7: rmsnorm_dispatch3<bf16_t, bf16_t, bf16_t>(x, add, xsum, w, h, ra, quant, M, d, eps, st); break;
-    case 3: rmsnorm_dispatch3<float, bf16_t, bf16_t>(x, add, xsum, w, h, ra, quant, M, d, eps, st); break;
+    case 0: rmsnorm_dispatch3<float, float, float>(x, add, nsplit, xsum, w, h, ra, quant, M, d, eps, st); break;
+    case 7: rmsnorm_dispatch3<bf16_t, bf16_t, bf16_t>(x, add, nsplit, xsum, w, h, ra, quant, M, d, eps, st); break;
+    case 3: rmsnorm_dispatch3<float, bf16_t, bf16_t>(x, add, nsplit, xsum, w, h, ra, quant, M, d, eps, st); break;
     default: break;   // no other combination is ever requested by the host code
     }
 }
@@ -216,10 +220,15 @@ void launch_fq_rows(const float *in, void *out, int out_dtype, const RowAct *ra,
 // ------------------------------------------------------------------------------------------------
 template <typename T>
 __global__ void __launch_bounds__(ROW_BLOCK)
-k_rope_store(const float *__restrict__ qkv, T *__restrict__ q, T *__restrict__ kc, T *__restrict__ vc,
-             const float2 *__restrict__ rope, const int32_t *__restrict__ pos0, int Tn, int L_max, int Hq, int Hkv,
-             int dh, int *flags)
+k_rope_store(const float *__restrict__ qkv, int nsplit, int64_t split_stride, T *__restrict__ q, T *__restrict__ kc,
+             T *__restrict__ vc, const float2 *__restrict__ rope, const int32_t *__restrict__ pos0, int Tn, int L_max,
+             int Hq, int Hkv, int dh, int *flags)
 {
+    auto val = [&](const float *p) {                       // folds K-split partial sums in split order
+        float t = 0.f;
+        for (int sp = 0; sp < nsplit; ++sp) t += p[sp * split_stride];
+        return t;
+    };
     const int64_t r = blockIdx.x;
     const int s = (int)(r / Tn), i = (int)(r % Tn);
     const int p0 = pos0 ? pos0[s] : 0;
@@ -233,7 +242,7 @@ k_rope_store(const float *__restrict__ qkv, T *__restrict__ q, T *__restrict__ k
     const float2 *cs = rope + (int64_t)pos * half;
     for (int idx = threadIdx.x; idx < Hq * half; idx += ROW_BLOCK) {
         const int hh = idx / half, c = idx - hh * half;
-        const float x0 = in[hh * dh + c], x1 = in[hh * dh + c + half];
+        const float x0 = val(in + hh * dh + c), x1 = val(in + hh * dh + c + half);
         const float2 t = cs[c];
         st(q + r * (int64_t)(Hq * dh) + hh * dh + c, x0 * t.x - x1 * t.y);
         st(q + r * (int64_t)(Hq * dh) + hh * dh + c + half, x1 * t.x + x0 * t.y);
@@ -242,7 +251,7 @@ k_rope_store(const float *__restrict__ qkv, T *__restrict__ q, T *__restrict__ k
     const float *vin = kin + Hkv * dh;
     for (int idx = threadIdx.x; idx < Hkv * half; idx += ROW_BLOCK) {
         const int hh = idx / half, c = idx - hh * half;
-        const float x0 = kin[hh * dh + c], x1 = kin[hh * dh + c + half];
+        const float x0 = val(kin + hh * dh + c), x1 = val(kin + hh * dh + c + half);
         const float2 t = cs[c];
         T *dst = kc + (((int64_t)s * Hkv + hh) * L_max + pos) * dh;
         st(dst + c, x0 * t.x - x1 * t.y);
@@ -250,21 +259,22 @@ k_rope_store(const float *__restrict__ qkv, T *__restrict__ q, T *__restrict__ k
     }
     for (int idx = threadIdx.x; idx < Hkv * dh; idx += ROW_BLOCK) {
         const int hh = idx / dh, c = idx - hh * dh;
-        st(vc + (((int64_t)s * Hkv + hh) * L_max + pos) * dh + c, vin[idx]);
+        st(vc + (((int64_t)s * Hkv + hh) * L_max + pos) * dh + c, val(vin + idx));
     }
 }
 
 void launch_rope_store(const float *qkv32, void *q, void *k_cache, void *v_cache, int dtype, const float2 *rope,
                        const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv, int dh, int *flags,
-                       hipStream_t st)
+                       hipStream_t st, int nsplit)
 {
     const int64_t M = (int64_t)n_seq * T;
     if (M <= 0) return;
+    const int64_t ss = M * (int64_t)((Hq + 2 * Hkv) * dh);
     if (dtype == 0)
-        hipLaunchKernelGGL((k_rope_store<float>), dim3((unsigned)M), dim3(ROW_BLOCK), 0, st, qkv32, (float *)q,
+        hipLaunchKernelGGL((k_rope_store<float>), dim3((unsigned)M), dim3(ROW_BLOCK), 0, st, qkv32, nsplit, ss, (float *)q,
                            (float *)k_cache, (float *)v_cache, rope, pos0, T, L_max, Hq, Hkv, dh, flags);
     else
-        hipLaunchKernelGGL((k_rope_store<bf16_t>), dim3((unsigned)M), dim3(ROW_BLOCK), 0, st, qkv32, (bf16_t *)q,
+        hipLaunchKernelGGL((k_rope_store<bf16_t>), dim3((unsigned)M), dim3(ROW_BLOCK), 0, st, qkv32, nsplit, ss, (bf16_t *)q,
                            (bf16_t *)k_cache, (bf16_t *)v_cache, rope, pos0, T, L_max, Hq, Hkv, dh, flags);
 }
 
@@ -274,22 +284,27 @@ void launch_rope_store(const float *qkv32, void *q, void *k_cache, void *v_cache
 __device__ __forceinline__ float silu_mul(float g, float u) { return (g / (1.0f + expf(-g))) * u; }
 
 template <typename T>
-__global__ void k_silu_mul(const float *__restrict__ gu, T *__restrict__ a, int64_t M, int dff)
+__global__ void k_silu_mul(const float *__restrict__ gu, int nsplit, T *__restrict__ a, int64_t M, int dff)
 {
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= M * dff) return;
     const int64_t r = idx / dff;
     const int c = (int)(idx - r * dff);
-    st(a + idx, silu_mul(gu[r * 2 * dff + c], gu[r * 2 * dff + dff + c]));
+    float g = 0.f, u = 0.f;
+    for (int sp = 0; sp < nsplit; ++sp) {                  // K-split partial sums, fixed order
+        g += gu[(sp * M + r) * 2 * dff + c];
+        u += gu[(sp * M + r) * 2 * dff + dff + c];
+    }
+    st(a + idx, silu_mul(g, u));
 }
 
-void launch_silu_mul(const float *gu32, void *a, int dtype, int64_t M, int dff, hipStream_t st)
+void launch_silu_mul(const float *gu32, void *a, int dtype, int64_t M, int dff, hipStream_t st, int nsplit)
 {
     const int64_t n = M * dff;
     if (n <= 0) return;
     const unsigned grid = (unsigned)((n + 255) / 256);
-    if (dtype == 0) hipLaunchKernelGGL((k_silu_mul<float>), dim3(grid), dim3(256), 0, st, gu32, (float *)a, M, dff);
-    else hipLaunchKernelGGL((k_silu_mul<bf16_t>), dim3(grid), dim3(256), 0, st, gu32, (bf16_t *)a, M, dff);
+    if (dtype == 0) hipLaunchKernelGGL((k_silu_mul<float>), dim3(grid), dim3(256), 0, st, gu32, nsplit, (float *)a, M, dff);
+    else hipLaunchKernelGGL((k_silu_mul<bf16_t>), dim3(grid), dim3(256), 0, st, gu32, nsplit, (bf16_t *)a, M, dff);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -488,19 +503,23 @@ void launch_prune_fq(void *a, int dtype, const RowAct *ra, const int32_t *perm, 
 // residual add into the output type; embedding gather
 // ------------------------------------------------------------------------------------------------
 template <typename T>
-__global__ void k_resid_out(const float *__restrict__ x2, const float *__restrict__ z, T *__restrict__ out, int64_t n)
+__global__ void k_resid_out(const float *__restrict__ x2, const float *__restrict__ z, int nsplit, T *__restrict__ out,
+                            int64_t n)
 {
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx < n) st(out + idx, x2[idx] + z[idx]);
+    if (idx >= n) return;
+    float t = 0.f;
+    for (int sp = 0; sp < nsplit; ++sp) t += z[sp * n + idx];
+    st(out + idx, x2[idx] + t);
 }
 
-void launch_resid_out(const float *x2, const float *z, void *out, int dtype, int64_t M, int d, hipStream_t st)
+void launch_resid_out(const float *x2, const float *z, void *out, int dtype, int64_t M, int d, hipStream_t st, int nsplit)
 {
     const int64_t n = M * d;
     if (n <= 0) return;
     const unsigned grid = (unsigned)((n + 255) / 256);
-    if (dtype == 0) hipLaunchKernelGGL((k_resid_out<float>), dim3(grid), dim3(256), 0, st, x2, z, (float *)out, n);
-    else hipLaunchKernelGGL((k_resid_out<bf16_t>), dim3(grid), dim3(256), 0, st, x2, z, (bf16_t *)out, n);
+    if (dtype == 0) hipLaunchKernelGGL((k_resid_out<float>), dim3(grid), dim3(256), 0, st, x2, z, nsplit, (float *)out, n);
+    else hipLaunchKernelGGL((k_resid_out<bf16_t>), dim3(grid), dim3(256), 0, st, x2, z, nsplit, (bf16_t *)out, n);
 }
 
 template <typename T>

@@ -163,11 +163,14 @@ def _stack(shape, seed, bf16):
     return layers, synth.head_weights(shape, seed + 100, bf16=bf16)
 
 
-@pytest.mark.parametrize("shape,B,L", [
-    (SMALL_GQA, 5, 300),
-    (dataclasses.replace(synth.LLAMA_1B, n_layers=2, vocab=2000), 4, 2100),     # 1024-thread decode path
+@pytest.mark.parametrize("shape,B,L,dup", [
+    (SMALL_GQA, 5, 300, False),
+    (SMALL_GQA, 41, 90, False),                                                 # two token tiles in the skinny GEMM
+    (SMALL_GQA, 6, 1500, True),                                                 # duplicated keys: tied scores at the threshold
+    (dataclasses.replace(synth.LLAMA_1B, n_layers=2, vocab=2000), 4, 2100, False),
+    (dataclasses.replace(synth.LLAMA_8B, n_layers=1, vocab=2000), 3, 5000, True),   # head_dim 128, long cache
 ])
-def test_bf16_decode_step(shape, B, L):
+def test_bf16_decode_step(shape, B, L, dup):
     table = synth.TABLE_C4
     layers, head = _stack(shape, 3000, True)
     rng = np.random.default_rng(3001)
@@ -179,6 +182,8 @@ def test_bf16_decode_step(shape, B, L):
     kcs, vcs = [], []
     for l in range(shape.n_layers):
         k, v = synth.kv_cache(B, shape.n_kv_heads, L_max, shape.head_dim, 3010 + l, bf16=True)
+        if dup:                                  # every key appears 4 times in a row: exact score ties
+            k = np.ascontiguousarray(np.repeat(k[:, :, ::4], 4, axis=2)[:, :, :L_max])
         kcs.append(k); vcs.append(v)
     ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=L_max)
     kd = [dev(k, sol.BF16) for k in kcs]
