@@ -433,17 +433,18 @@ k_gemm_skinny(const bf16_t *__restrict__ x, int64_t ldx, BMap bmap, int M, int N
         }
         __syncthreads();
         if (live) {
-            for (int kb = 0; kb < kw; kb += 128) {                     // two 64-wide K blocks in flight
-                u32x4_t wa[2][4];
+            constexpr int UK = 4;                                       // 64-wide K blocks in flight per wave
+            for (int kb = 0; kb < kw; kb += 64 * UK) {
+                u32x4_t wa[UK][4];
 #pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    const int ko = (kb + u * 64 < kw) ? kb + u * 64 : kb;   // odd tail: re-read, not used
+                for (int u = 0; u < UK; ++u) {
+                    const int ko = (kb + u * 64 < kw) ? kb + u * 64 : kb;   // ragged tail: re-read, not used
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
                         wa[u][j] = *reinterpret_cast<const u32x4_t *>(wrow + kc + ko + j * 8);
                 }
 #pragma unroll
-                for (int u = 0; u < 2; ++u) {
+                for (int u = 0; u < UK; ++u) {
                     if (kb + u * 64 < kw) {
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
