@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the action-conditioned decoder-layer path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c5|c4|c5d|c3]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c5|c4|c5d]
 
 A step is one pass of the measured unit over one batch of seeded synthetic input that is already
 resident in HBM. Default workload: the Llama-3.2-1B-shaped decoder layer, 4 inputs x 8 schedules
@@ -42,6 +42,27 @@ def layer_flops(shape, table, ids, pos):
     lin = 2 * d * (hq + 2 * hkv) * dh + 2 * hq * dh * d + 4 * d * dff
     return {"linear_dense": float(lin * len(n)), "down": float((2 * m * d).sum()),
             "qk": float((2 * hq * dh * n).sum()), "pv": float((2 * hq * dh * k).sum())}
+
+
+def copy_calibration():
+    """One plain device copy of known size (1 GiB read + 1 GiB written). It gives the hardware
+    counters FETCH_SIZE / WRITE_SIZE a reference point in the same rocprofv3 --pmc run."""
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    del src, dst
+
+
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (None if absent)."""
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(workload, {}).get(kernel)
+    except (OSError, ValueError):
+        return None
 
 
 def time_steps(fn, steps, warmup):
@@ -98,7 +119,8 @@ def run_layer(args, shape, n_inputs, G, T, table, name):
         "config": {"workload": name, "entry_point": "sol_layer_forward", "n_inputs": n_inputs, "schedules": G,
                    "seq_len": T, "tokens_per_step": tokens, "actions": "iid uniform over %d" % len(table)},
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": ach / PEAK_BF16_TFLOPS, "traffic": None, "kernel_ms": stages[dom],
+                     "frac": ach / PEAK_BF16_TFLOPS, "traffic": measured_traffic(args.workload, dom),
+                     "kernel_ms": stages[dom],
                      "launches_per_step": launches.get(dom)},
         "layer": {"algorithmic_tflop": alg / 1e12, "algorithmic_tflops": alg / sec / 1e12,
                   "algorithmic_frac_of_peak": alg / sec / 1e12 / PEAK_BF16_TFLOPS,
@@ -181,7 +203,8 @@ def run_decode(args, shape, B, L, table, name, n_layers):
         "config": {"workload": name, "entry_point": "sol_decode_step", "batch": B, "cache_len": L, "layers": n_layers,
                    "launch": "one HIP graph replay per step", "ms_per_step_eager_launches": sec_eager * 1e3},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                     "frac": ach / PEAK_HBM_GBS, "traffic": None, "kernel_ms": stages[dom] / n_layers,
+                     "frac": ach / PEAK_HBM_GBS, "traffic": measured_traffic(args.workload, dom),
+                     "kernel_ms": stages[dom] / n_layers,
                      "launches_per_step": launches.get(dom)},
         "step": {"algorithmic_gb": alg_bytes / 1e9, "algorithmic_gbs": alg_bytes / sec / 1e9,
                  "algorithmic_frac_of_peak": alg_bytes / sec / 1e9 / PEAK_HBM_GBS},
@@ -222,6 +245,7 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+    copy_calibration()
     if args.workload == "c2":
         res = run_layer(args, synth.LLAMA_1B, 4, 8, 1024, synth.TABLE_C2,
                         "C2: Llama-3.2-1B-shaped decoder layer, bf16, 4 inputs x 8 schedules x 1024 tokens")
