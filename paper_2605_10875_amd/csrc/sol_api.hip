@@ -397,7 +397,7 @@ static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_i
     {   // scores, budgeted selection, softmax over kept keys, times V
         STAGE(ctx, ST_ATTN, st);
         const bool tiled = mfma && w.vt && T >= 16 && L_max <= 4096 &&
-                           launch_attn_tile(w.qb, kc, vc, w.vt, w.o32, w.ra, pos0, n_seq, T, L_max, Hq, Hkv, dh, st);
+                           launch_attn_tile(w.qb, kc, vc, w.vt, w.big32, w.o32, w.ra, pos0, n_seq, T, L_max, Hq, Hkv, dh, st);
         const bool dec = !tiled && mfma && T == 1 && pos0 &&
                          launch_attn_decode(w.qb, kc, vc, w.o32, w.ra, pos0, n_seq, L_max, Hq, Hkv, dh, ctx->d_flags, st);
         if (!tiled && !dec &&

@@ -210,70 +210,147 @@ bool launch_attn_rows(const void *q, const void *k_cache, const void *v_cache, i
 }
 
 
-// =================================================================================================
-// Tiled attention for the batched (teacher-forced) pass, bf16.
-//
-// One workgroup (8 waves) per (sequence, query head, block of BQ consecutive query positions):
-//   A. S = Q K^T on MFMA (16x16x32 tiles, fp32 accumulate), waves striding over key tiles; the scaled
-//      fp32 scores of the whole block go to LDS, one padded row per query (selection needs the exact
-//      fp32 value of every causal score, so rows stay on chip instead of a 2 GB HBM round trip).
-//   B. One wave per row, scores in registers: budget b = ceil(kappa * n); if b < n the threshold of
-//      the b largest scores is found by bisection on order-preserving integer keys between the
-//      row's min and max, counting with ballots and stopping as soon as exactly b scores lie above
-//      the pivot (about log2(n) steps); equal scores at the threshold go to the lower positions.
-//      Softmax numerators of the kept keys are written back over the row as a pair of bf16 halves
-//      (p = hi + lo, zeros elsewhere), which fits the 4 bytes per key the fp32 score occupied.
-//   C. O = P V on MFMA with V read K-contiguous from a transposed copy, waves striding over key
-//      chunks, partial sums reduced through LDS in wave order, scaled by 1 / sum(p).
-// Rows whose budget keeps every key skip B's search. LDS: BQ * (Lpad + 4) * 4 bytes.
-// =================================================================================================
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_a;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4_a;
 typedef uint32_t u32x4_a __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2_a __attribute__((ext_vector_type(2)));
 typedef float f32x4_a __attribute__((ext_vector_type(4)));
 
+// =================================================================================================
+// Batched bf16 attention in two kernels.
+//
+//   k_attn_select   per (sequence, query head, BQ query rows): all causal scores of the rows by MFMA into
+//                   LDS as fp32, then per row the row maximum and -- when the budget is below the row
+//                   length -- the exact threshold of the b largest scores (wave bisection on ballots).
+//                   Output per (row, head): { thr, max, jstar }: a key is kept iff
+//                   s > thr  or  (s == thr and key index <= jstar).
+//   k_attn_pv       per (sequence, KV head, 32 query rows), one wave per query head of the group: streams
+//                   K and V^T chunks through LDS once for all heads of the group, recomputes the scores
+//                   with the same MFMA sequence (bit-identical to the first kernel's), applies the
+//                   threshold, and accumulates softmax numerators times V flash-style with scores and
+//                   probabilities never leaving registers (the row maximum is already known, so there
+//                   is no running rescale).
+// Both compute a score tile as S^T = K Q^T, so a lane owns one query and four keys per tile; in
+// k_attn_pv the keys of a 32-key chunk are assigned to MFMA rows such that each lane group ends up
+// with 8 consecutive keys, which is exactly the A operand of the P V product.
+// =================================================================================================
+struct __align__(16) SelRow { float thr, mx; int jstar; int pad; };
 
-#ifdef SOL_ATTN_TIMING   // probe builds only: per-phase s_memtime stamps of wave 0 of every workgroup
-__device__ unsigned long long *g_attn_stamps;
-#define AT_STAMP(i)                                                                                  \
-    if (threadIdx.x == 0 && g_attn_stamps)                                                           \
-        g_attn_stamps[((size_t)(blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 8 + (i)] = __builtin_readcyclecounter()
-#else
-#define AT_STAMP(i)
-#endif
-
-template <int BQ, int SLOTS, int DH, int AT_WAVES>
-__global__ void __launch_bounds__(AT_WAVES * 64)
-k_attn_tile(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf16_t *__restrict__ vt,
-            float *__restrict__ o32, const RowAct *__restrict__ ra, const int32_t *__restrict__ pos0, int Tn, int L_max,
-            int Hq, int Hkv, int lpadv, float scale)
+// column (256*j + 4*lane + e order) of the quota-th key equal to thr; quota >= 1 and at most the
+// number of such keys
+template <int SLOTS>
+__device__ __forceinline__ int wave_tie_last(const uint32_t (&key)[SLOTS], int n, uint32_t thr, int quota, int lane)
 {
-    constexpr int AT_BLOCK = AT_WAVES * 64;
-    constexpr int LPAD = SLOTS * 64, LS = LPAD + 4;
-    constexpr int RT = (BQ + 15) / 16, KK = DH / 32, DT = DH / 16, NJ = SLOTS / 4;
-    constexpr int UA = (SLOTS <= 16) ? 8 : 4;              // key tiles in flight per wave in phase A
-    constexpr int UC = (SLOTS <= 16) ? 4 : 2;                                  // key chunks in flight per wave in phase C
-    extern __shared__ __align__(16) float sc[];            // [BQ][LS] scores, then P (hi | lo bf16) in place, then partial O
-    __shared__ float inv_den[BQ];
+    int result = 0x7FFFFFFF;
+    bool found = false;
+#pragma unroll
+    for (int j = 0; j < SLOTS / 4; ++j) {
+        if (256 * j < n && !found) {
+            int below = 0, here = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const unsigned long long bal = __ballot(key[4 * j + e] == thr);
+                below = __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, below));
+                here += __popcll(bal);
+            }
+            if (quota <= here) {                         // the quota-th tie sits in this group of 256 columns
+                int mine = 0, col = -1;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const bool tie = key[4 * j + e] == thr;
+                    if (tie && below + mine == quota - 1) col = 256 * j + 4 * lane + e;
+                    mine += tie;
+                }
+                const unsigned long long who = __ballot(col >= 0);          // exactly one lane
+                result = __builtin_amdgcn_readlane(col, (int)__builtin_ctzll(who));
+                found = true;
+            } else {
+                quota -= here;
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    return result;
+}
+
+// finishes one row's search from the bracket [lo, hi] (see wave_select_topk): returns the threshold key
+// and the index of the last kept key among those equal to it (INT_MAX when all of them are kept)
+template <int SLOTS>
+__device__ __forceinline__ uint32_t wave_select_thr(const uint32_t (&key)[SLOTS], int n_in, int b_in, uint32_t lo_in,
+                                                    uint32_t hi_in, int lane, int &jstar)
+{
+    const int n = __builtin_amdgcn_readfirstlane(n_in), b = __builtin_amdgcn_readfirstlane(b_in);
+    uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)lo_in);
+    uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)hi_in);
+    jstar = 0x7FFFFFFF;
+    while (lo < hi) {
+        const uint32_t mid = lo + ((hi - lo + 1u) >> 1);
+        const int cnt = wave_count_ge<SLOTS>(key, n, mid);
+        if (cnt == b) return mid;
+        if (cnt > b) lo = mid; else hi = mid - 1u;
+    }
+    const int n_ge = wave_count_ge<SLOTS>(key, n, lo);
+    if (n_ge > b) {                                      // more keys equal to the threshold than the budget has room for
+        const int n_gt = (lo == 0xFFFFFFFFu) ? 0 : wave_count_ge<SLOTS>(key, n, lo + 1u);
+        jstar = wave_tie_last<SLOTS>(key, n, lo, b - n_gt, lane);
+    }
+    return lo;
+}
+
+// loads a score row from LDS: order-preserving keys (0 for columns >= n; -0.0 counts as +0.0 so that
+// equal floats have equal keys), row maximum and minimum key
+template <int SLOTS>
+__device__ __forceinline__ void sel_row_load(const float *row, int n, int lane, uint32_t (&key)[SLOTS], uint32_t &kmax_out,
+                                             uint32_t &kmin_out)
+{
+    uint32_t kmax = 0u, kmin = 0xFFFFFFFFu;
+#pragma unroll
+    for (int j = 0; j < SLOTS / 4; ++j) {
+        if (256 * j < n) {
+            const f32x4_a v = *reinterpret_cast<const f32x4_a *>(row + 256 * j + 4 * lane);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const bool valid = 256 * j + 4 * lane + e < n;
+                const uint32_t kv = valid ? score_key(v[e] + 0.0f) : 0u;
+                key[4 * j + e] = kv;
+                kmax = kv > kmax ? kv : kmax;
+                kmin = (valid && kv < kmin) ? kv : kmin;
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) key[4 * j + e] = 0u;
+        }
+    }
+    kmax_out = wave_max_u32(kmax);
+    kmin_out = wave_min_u32(kmin);
+}
+
+template <int BQ, int SLOTS, int DH, int NW>
+__global__ void __launch_bounds__(NW * 64)
+k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRow *__restrict__ sel,
+              const RowAct *__restrict__ ra, const int32_t *__restrict__ pos0, int Tn, int L_max, int Hq, int Hkv,
+              float scale)
+{
+    constexpr int LPAD = SLOTS * 64, LS = LPAD + 4;        // row stride = 4 mod 64 floats: the 16 query rows of a
+                                                           // 128-bit store hit 16 different bank groups
+    constexpr int RT = (BQ + 15) / 16, KK = DH / 32;
+    constexpr int UA = (SLOTS <= 16) ? 8 : 4;              // key tiles in flight per wave
+    extern __shared__ __align__(16) float sc[];            // [BQ][LS]
 
     const int tid = threadIdx.x, lane = tid & 63;
-    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave index, scalar
-    const int nqb = gridDim.x;
-    const int qb = nqb - 1 - (int)blockIdx.x;              // heaviest blocks first
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int qb = (int)gridDim.x - 1 - (int)blockIdx.x;   // heaviest blocks first
     const int h = blockIdx.y, s = blockIdx.z;
     const int p0 = pos0 ? pos0[s] : 0;
     if (p0 < 0 || p0 + Tn > L_max) return;                 // flagged by the projection kernel; sequence skipped
     const int q0 = qb * BQ;
-    const int rows = (Tn - q0 < BQ) ? (Tn - q0) : BQ;      // live rows of this block
-    const int n_max = p0 + q0 + rows;                      // keys seen by the block's last row
+    const int rows = (Tn - q0 < BQ) ? (Tn - q0) : BQ;
+    const int n_max = p0 + q0 + rows;
     const int kvh = h / (Hq / Hkv);
     const bf16_t *kbase = kc + ((int64_t)s * Hkv + kvh) * (int64_t)L_max * DH;
-    const bf16_t *vbase = vt + ((int64_t)s * Hkv + kvh) * (int64_t)DH * lpadv;
     const int l16 = lane & 15, lg = lane >> 4;
 
-    AT_STAMP(0);
-    // ---- A. scores ---------------------------------------------------------------------------
+    // ---- scores: S^T tile = K tile (rows) x Q^T (columns); lane (l16, lg) gets keys 4*lg..4*lg+3 of query l16 ----
     {
         bf16x8_a qf[RT][KK];
 #pragma unroll
@@ -286,11 +363,11 @@ k_attn_tile(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const b
                 qf[rt][kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(qp + kk * 32));
         }
         const int n_kt = (n_max + 15) >> 4;
-        for (int kt0 = w; kt0 < n_kt; kt0 += AT_WAVES * UA) {
+        for (int kt0 = w; kt0 < n_kt; kt0 += NW * UA) {
             bf16x8_a kf[UA][KK];
 #pragma unroll
-            for (int u = 0; u < UA; ++u) {                 // issue every load of the group before the first MFMA
-                int key = (kt0 + u * AT_WAVES) * 16 + l16;
+            for (int u = 0; u < UA; ++u) {
+                int key = (kt0 + u * NW) * 16 + l16;
                 if (key >= n_max) key = n_max - 1;
                 const bf16_t *kp = kbase + (int64_t)key * DH + lg * 8;
 #pragma unroll
@@ -299,162 +376,267 @@ k_attn_tile(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const b
             }
 #pragma unroll
             for (int u = 0; u < UA; ++u) {
-                const int kt = kt0 + u * AT_WAVES;
+                const int kt = kt0 + u * NW;
                 if (kt < n_kt) {
 #pragma unroll
                     for (int rt = 0; rt < RT; ++rt) {
                         floatx4_a acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                         for (int kk = 0; kk < KK; ++kk)
-                            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[rt][kk], kf[u][kk], acc, 0, 0, 0);
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            const int row = rt * 16 + lg * 4 + r;
-                            if (row < BQ) sc[row * LS + kt * 16 + l16] = acc[r] * scale;
-                        }
+                            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[u][kk], qf[rt][kk], acc, 0, 0, 0);
+                        const int row = rt * 16 + l16;
+                        if (row < BQ)
+                            *reinterpret_cast<f32x4_a *>(sc + row * LS + kt * 16 + 4 * lg) =
+                                f32x4_a{acc[0] * scale, acc[1] * scale, acc[2] * scale, acc[3] * scale};
                     }
                 }
             }
         }
     }
     __syncthreads();
-    AT_STAMP(1);
 
-    // ---- B. selection + softmax numerators, one wave per row --------------------------------------
-    for (int r = w; r < BQ; r += AT_WAVES) {
-        float *row = sc + r * LS;
-        uint32_t *prow = reinterpret_cast<uint32_t *>(row);           // P as bf16 pairs, in place
-        if (r >= rows) {                                              // dead row of a ragged block: P = 0
-#pragma unroll
-            for (int j = 0; j < NJ; ++j) {
-                *reinterpret_cast<u32x2_a *>(prow + (256 * j + 4 * lane) / 2) = u32x2_a{0u, 0u};
-                *reinterpret_cast<u32x2_a *>(prow + (LPAD + 256 * j + 4 * lane) / 2) = u32x2_a{0u, 0u};
+    // ---- per row: maximum, and the threshold when the budget is below the row length; rows go two at a
+    // time per wave so that one row's ballot -> count -> branch chain fills the other's latency ----
+    constexpr bool PAIR = (SLOTS <= 16) && (BQ >= 2 * NW);
+    constexpr int RSTEP = PAIR ? 2 * NW : NW;
+    for (int r = w; r < rows; r += RSTEP) {
+        const int rb = r + NW;
+        const bool live_b = PAIR && rb < rows;
+        const int na = p0 + q0 + r + 1;
+        const RowAct act_a = ra[(int64_t)s * Tn + q0 + r];
+        const int ba = budget_ceil(act_a.keep_num, act_a.keep_den, na);
+        uint32_t keya[SLOTS], kmax_a, kmin_a;
+        sel_row_load<SLOTS>(sc + r * LS, na, lane, keya, kmax_a, kmin_a);
+        uint32_t thr_a = 0u, thr_b = 0u;                   // key 0: below every score, everything kept
+        int js_a = 0x7FFFFFFF, js_b = 0x7FFFFFFF;
+        uint32_t kmax_b = 0u;
+        if constexpr (PAIR) {
+            if (live_b) {
+                const int nb = na + NW;
+                const RowAct act_b = ra[(int64_t)s * Tn + q0 + rb];
+                const int bb = budget_ceil(act_b.keep_num, act_b.keep_den, nb);
+                uint32_t keyb[SLOTS], kmin_b;
+                sel_row_load<SLOTS>(sc + rb * LS, nb, lane, keyb, kmax_b, kmin_b);
+                uint32_t loa = kmin_a, hia = kmax_a, lob = kmin_b, hib = kmax_b;
+                bool exact_a = false, exact_b = false;
+                if (ba < na && bb < nb) wave_bisect2<SLOTS>(keya, keyb, na, nb, ba, bb, loa, hia, lob, hib, exact_a, exact_b);
+                if (ba < na) thr_a = exact_a ? loa : wave_select_thr<SLOTS>(keya, na, ba, loa, hia, lane, js_a);
+                if (bb < nb) thr_b = exact_b ? lob : wave_select_thr<SLOTS>(keyb, nb, bb, lob, hib, lane, js_b);
+            } else if (ba < na) {
+                thr_a = wave_select_thr<SLOTS>(keya, na, ba, kmin_a, kmax_a, lane, js_a);
             }
-            if (lane == 0) inv_den[r] = 0.f;
-            continue;
+        } else if (ba < na) {
+            thr_a = wave_select_thr<SLOTS>(keya, na, ba, kmin_a, kmax_a, lane, js_a);
         }
-        const int n = p0 + q0 + r + 1;                                // wave-uniform
-        const RowAct act = ra[(int64_t)s * Tn + q0 + r];
-        const int b = budget_ceil(act.keep_num, act.keep_den, n);
-        float sv[SLOTS];
-        uint32_t key[SLOTS];
-        uint32_t kmax = 0u, kmin = 0xFFFFFFFFu;
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) {
-            if (256 * j < n) {
-                const f32x4_a v = *reinterpret_cast<const f32x4_a *>(row + 256 * j + 4 * lane);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const bool valid = 256 * j + 4 * lane + e < n;
-                    const uint32_t kv = valid ? score_key(v[e]) : 0u;   // 0 is below every real score
-                    sv[4 * j + e] = v[e];
-                    key[4 * j + e] = kv;
-                    kmax = kv > kmax ? kv : kmax;
-                    kmin = (valid && kv < kmin) ? kv : kmin;
-                }
-            } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) { sv[4 * j + e] = 0.f; key[4 * j + e] = 0u; }
-            }
+        if (lane == 0) {
+            sel[((int64_t)s * Tn + q0 + r) * Hq + h] =
+                SelRow{thr_a ? score_unkey(thr_a) : -__builtin_inff(), score_unkey(kmax_a), js_a, 0};
+            if (live_b)
+                sel[((int64_t)s * Tn + q0 + rb) * Hq + h] =
+                    SelRow{thr_b ? score_unkey(thr_b) : -__builtin_inff(), score_unkey(kmax_b), js_b, 0};
         }
-        kmax = wave_max_u32(kmax);
-        const float mx = score_unkey(kmax);                           // the best key is always kept
-        uint32_t thr = 1u;                                            // budget keeps all: every valid key passes
-        if (b < n) {
-            kmin = wave_min_u32(kmin);
-            thr = wave_select_topk<SLOTS>(key, n, b, kmin, kmax, lane);
-        }
-        float den = 0.f;
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) {
-            float p[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                p[e] = key[4 * j + e] >= thr ? __expf(sv[4 * j + e] - mx) : 0.f;
-                den += p[e];
-            }
-            // p = hi + lo with both halves bf16: the MFMA product with bf16 V is then exact to ~2^-17
-            u32x2_a pk, pl;
-            pk[0] = pack_bf16x2(p[0], p[1]);
-            pk[1] = pack_bf16x2(p[2], p[3]);
-            pl[0] = pack_bf16x2(p[0] - __uint_as_float(pk[0] << 16), p[1] - __uint_as_float(pk[0] & 0xFFFF0000u));
-            pl[1] = pack_bf16x2(p[2] - __uint_as_float(pk[1] << 16), p[3] - __uint_as_float(pk[1] & 0xFFFF0000u));
-            *reinterpret_cast<u32x2_a *>(prow + (256 * j + 4 * lane) / 2) = pk;
-            *reinterpret_cast<u32x2_a *>(prow + (LPAD + 256 * j + 4 * lane) / 2) = pl;
-        }
-        den = wave_sum_dpp(den);
-        if (lane == 0) inv_den[r] = 1.0f / den;
     }
-    AT_STAMP(2);
-    __syncthreads();
-    AT_STAMP(3);
+}
 
-    // ---- C. O = P V --------------------------------------------------------------------------------
-    floatx4_a oacc[RT][DT];
+// ---- k_attn_pv -------------------------------------------------------------------------------------
+// LDS chunk layouts (bf16, 16-byte pieces XOR-swizzled so that the 128-bit fragment reads of 16 lanes
+// hit 16 different bank groups):
+//   K chunk   [64 keys][DH]      piece' = piece ^ swzK(key row)
+//   V^T chunk [DH][64 keys]      piece' = piece ^ ((d >> 1) & 7)
+template <int DH> __device__ __forceinline__ int pv_swz_k(int row)
+{
+    if constexpr (DH == 64) return ((row >> 1) & 1) | (((row >> 3) & 3) << 1);   // rows {0-3, 8-11, 16-19, 24-27} (+4)
+    else return (row & 3) | (((row >> 3) & 3) << 2);
+}
+
+// softmax numerators of one 32-key sub-chunk for one query tile, as the A operand (hi and lo bf16
+// halves) of the P V product. st[kt][r] is the score of key  kbase + 8*lg + 4*kt + r.
+template <bool MASK, bool TIES>
+__device__ __forceinline__ void pv_probs(const floatx4_a (&st)[2], float scale, float thr, float mxl, int jstar, int pos,
+                                         int kfirst, float &den, bf16x8_a &phi, bf16x8_a &plo)
+{
+    float p[8];
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt)
+    for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) oacc[rt][dt] = floatx4_a{0.f, 0.f, 0.f, 0.f};
-    {
-        const int n_ch = (n_max + 31) >> 5;
-        for (int c0 = w; c0 < n_ch; c0 += AT_WAVES * UC) {
-            bf16x8_a vf[UC][DT];
+        for (int r = 0; r < 4; ++r) {
+            const float sv = st[kt][r] * scale;
+            const int j = kfirst + 4 * kt + r;
+            bool keep = sv >= thr;
+            if (TIES) keep = sv > thr || (sv == thr && j <= jstar);
+            if (MASK) keep = keep && j <= pos;
+            const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(sv, 1.44269504088896341f, -mxl));
+            p[4 * kt + r] = keep ? e : 0.f;
+            den += p[4 * kt + r];
+        }
+    u32x4_a hi, lo;
 #pragma unroll
-            for (int u = 0; u < UC; ++u) {
-                int c = c0 + u * AT_WAVES;
-                if (c >= n_ch) c = n_ch - 1;               // re-read the last chunk; its product is not used
+    for (int i = 0; i < 4; ++i) {
+        hi[i] = pack_bf16x2(p[2 * i], p[2 * i + 1]);
+        lo[i] = pack_bf16x2(p[2 * i] - __uint_as_float(hi[i] << 16), p[2 * i + 1] - __uint_as_float(hi[i] & 0xFFFF0000u));
+    }
+    phi = __builtin_bit_cast(bf16x8_a, hi);
+    plo = __builtin_bit_cast(bf16x8_a, lo);
+}
+
+template <int DH, int G>
+__global__ void __launch_bounds__(G * 64)
+k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf16_t *__restrict__ vt,
+          const SelRow *__restrict__ sel, float *__restrict__ o32, const int32_t *__restrict__ pos0, int Tn, int L_max, int Hq,
+          int Hkv, int lpadv, float scale)
+{
+    constexpr int NT = G * 64, KK = DH / 32, DT = DH / 16, KC = 64, QT = 32;
+    constexpr int KP = DH / 8;                              // 16-byte pieces per K row
+    constexpr int K_PIECES = KC * KP / NT, V_PIECES = DH * (KC / 8) / NT;
+    constexpr int K_BYTES = KC * DH * 2, STAGE = 2 * K_BYTES;
+    static_assert(KC * KP % NT == 0 && DH * (KC / 8) % NT == 0, "chunk / thread mismatch");
+    extern __shared__ __align__(16) unsigned char pvl[];   // 2 stages of { K chunk, V^T chunk }
+
+    const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, lg = lane >> 4;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int qb = (int)gridDim.x - 1 - (int)blockIdx.x;   // heaviest blocks first
+    const int kvh = blockIdx.y, s = blockIdx.z, h = kvh * G + w;
+    const int p0 = pos0 ? pos0[s] : 0;
+    if (p0 < 0 || p0 + Tn > L_max) return;
+    const int q0 = qb * QT;
+    const int rows = (Tn - q0 < QT) ? (Tn - q0) : QT;
+    const int n_max = p0 + q0 + rows;                      // keys seen by the block's last live row
+    const int n_chunks = (n_max + KC - 1) / KC;
+    const bf16_t *kbase = kc + ((int64_t)s * Hkv + kvh) * (int64_t)L_max * DH;
+    const bf16_t *vbase = vt + ((int64_t)s * Hkv + kvh) * (int64_t)DH * lpadv;
+
+    // per-lane query state: lane l16 of every lane group owns query q0 + 16*qt + l16
+    bf16x8_a qf[2][KK];
+    float thr[2], mxl[2], den[2] = {0.f, 0.f};
+    int jstar[2], pos[2];
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+        const int qi = q0 + 16 * qt + l16;
+        const bool live = qi < Tn;
+        const int qr = live ? qi : Tn - 1;
+        const bf16_t *qp = q + ((int64_t)s * Tn + qr) * (int64_t)(Hq * DH) + (int64_t)h * DH + lg * 8;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk)
+            qf[qt][kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(qp + kk * 32));
+        const SelRow sr = sel[((int64_t)s * Tn + qr) * Hq + h];
+        thr[qt] = live ? sr.thr : __builtin_inff();        // dead rows of a ragged block keep nothing
+        mxl[qt] = sr.mx * 1.44269504088896341f;
+        jstar[qt] = sr.jstar;
+        pos[qt] = p0 + qi;
+    }
+    const bool any_ties = __ballot(jstar[0] != 0x7FFFFFFF || jstar[1] != 0x7FFFFFFF) != 0ull;
+
+    floatx4_a oacc[2][DT];
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) oacc[qt][dt] = floatx4_a{0.f, 0.f, 0.f, 0.f};
+
+    // staging: global -> registers -> LDS, one chunk ahead
+    u32x4_a kreg[K_PIECES], vreg[V_PIECES];
+#define SOL_PV_GLOAD(CH_)                                                                                  \
+    {                                                                                                      \
+        const int key0_ = (CH_) * KC;                                                                      \
+        _Pragma("unroll") for (int i = 0; i < K_PIECES; ++i) {                                             \
+            const int pc = i * NT + tid, row = pc / KP, piece = pc - row * KP;                             \
+            int key = key0_ + row;                                                                         \
+            if (key >= n_max) key = n_max - 1;              /* never used unmasked: beyond every row */     \
+            kreg[i] = *reinterpret_cast<const u32x4_a *>(kbase + (int64_t)key * DH + piece * 8);           \
+        }                                                                                                  \
+        _Pragma("unroll") for (int i = 0; i < V_PIECES; ++i) {                                             \
+            const int pc = i * NT + tid, d = pc >> 3, piece = pc & 7;                                      \
+            vreg[i] = *reinterpret_cast<const u32x4_a *>(vbase + (int64_t)d * lpadv + key0_ + piece * 8);  \
+        }                                                                                                  \
+    }
+#define SOL_PV_LSTORE(STG_)                                                                                \
+    {                                                                                                      \
+        unsigned char *kb_ = pvl + (STG_) * STAGE, *vb_ = kb_ + K_BYTES;                                   \
+        _Pragma("unroll") for (int i = 0; i < K_PIECES; ++i) {                                             \
+            const int pc = i * NT + tid, row = pc / KP, piece = pc - row * KP;                             \
+            *reinterpret_cast<u32x4_a *>(kb_ + row * (DH * 2) + ((piece ^ pv_swz_k<DH>(row)) << 4)) = kreg[i]; \
+        }                                                                                                  \
+        _Pragma("unroll") for (int i = 0; i < V_PIECES; ++i) {                                             \
+            const int pc = i * NT + tid, d = pc >> 3, piece = pc & 7;                                      \
+            *reinterpret_cast<u32x4_a *>(vb_ + d * (KC * 2) + ((piece ^ ((d >> 1) & 7)) << 4)) = vreg[i];  \
+        }                                                                                                  \
+    }
+
+    SOL_PV_GLOAD(0);
+    SOL_PV_LSTORE(0);
+    __syncthreads();
+    for (int ch = 0; ch < n_chunks; ++ch) {
+        const int stg = ch & 1;
+        if (ch + 1 < n_chunks) SOL_PV_GLOAD(ch + 1);
+        const unsigned char *kb = pvl + stg * STAGE, *vb = kb + K_BYTES;
+#pragma unroll
+        for (int cc = 0; cc < 2; ++cc) {
+            const int kb32 = ch * KC + cc * 32;             // first key of this 32-key sub-chunk
+            if (kb32 < n_max) {
+                // scores: MFMA row m of tile kt is key  kb32 + 8*(m >> 2) + 4*kt + (m & 3)
+                floatx4_a st[2][2];                         // [qt][kt]
+#pragma unroll
+                for (int kt = 0; kt < 2; ++kt) {
+                    const int krow = cc * 32 + 8 * (l16 >> 2) + 4 * kt + (l16 & 3);
+                    bf16x8_a kf[KK];
+#pragma unroll
+                    for (int kk = 0; kk < KK; ++kk)
+                        kf[kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(
+                            kb + krow * (DH * 2) + (((kk * 4 + lg) ^ pv_swz_k<DH>(krow)) << 4)));
+#pragma unroll
+                    for (int qt = 0; qt < 2; ++qt) {
+                        floatx4_a acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                        for (int kk = 0; kk < KK; ++kk)
+                            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kk], qf[qt][kk], acc, 0, 0, 0);
+                        st[qt][kt] = acc;
+                    }
+                }
+                bf16x8_a phi[2], plo[2];
+                const int kfirst = kb32 + 8 * lg;
+                const bool diag = kb32 + 31 > p0 + q0;      // some key of the sub-chunk is beyond some query
+#pragma unroll
+                for (int qt = 0; qt < 2; ++qt) {
+                    if (any_ties) pv_probs<true, true>(st[qt], scale, thr[qt], mxl[qt], jstar[qt], pos[qt], kfirst, den[qt], phi[qt], plo[qt]);
+                    else if (diag) pv_probs<true, false>(st[qt], scale, thr[qt], mxl[qt], jstar[qt], pos[qt], kfirst, den[qt], phi[qt], plo[qt]);
+                    else pv_probs<false, false>(st[qt], scale, thr[qt], mxl[qt], jstar[qt], pos[qt], kfirst, den[qt], phi[qt], plo[qt]);
+                }
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt) {
-                    const bf16_t *vp = vbase + (int64_t)(dt * 16 + l16) * lpadv + c * 32 + lg * 8;
-                    vf[u][dt] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(vp));
-                }
-            }
+                    const int d = dt * 16 + l16;
+                    const bf16x8_a vf = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(
+                        vb + d * (KC * 2) + (((cc * 4 + lg) ^ ((d >> 1) & 7)) << 4)));
 #pragma unroll
-            for (int u = 0; u < UC; ++u) {
-                const int c = c0 + u * AT_WAVES;
-                if (c < n_ch) {
-                    bf16x8_a pf[RT], pl[RT];
-#pragma unroll
-                    for (int rt = 0; rt < RT; ++rt) {
-                        int pr = rt * 16 + l16;
-                        if (pr >= BQ) pr = BQ - 1;
-                        const unsigned char *pp =
-                            reinterpret_cast<const unsigned char *>(sc + pr * LS) + (c * 32 + lg * 8) * 2;
-                        pf[rt] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(pp));
-                        pl[rt] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(pp + 2 * LPAD));
+                    for (int qt = 0; qt < 2; ++qt) {
+                        oacc[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(plo[qt], vf, oacc[qt][dt], 0, 0, 0);
+                        oacc[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(phi[qt], vf, oacc[qt][dt], 0, 0, 0);
                     }
-#pragma unroll
-                    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                        for (int rt = 0; rt < RT; ++rt) {
-                            oacc[rt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pl[rt], vf[u][dt], oacc[rt][dt], 0, 0, 0);
-                            oacc[rt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf[rt], vf[u][dt], oacc[rt][dt], 0, 0, 0);
-                        }
                 }
             }
         }
+        if (ch + 1 < n_chunks) SOL_PV_LSTORE(stg ^ 1);
+        __syncthreads();
     }
-    AT_STAMP(4);
-    __syncthreads();                                          // every wave is done reading P
-    float *red = sc;                                          // [AT_WAVES][BQ][DH]
+#undef SOL_PV_GLOAD
+#undef SOL_PV_LSTORE
+
+    // ---- normalise and store: accumulator lane (l16, lg) register r is query 4*lg + r, column 16*dt + l16 ----
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt)
+    for (int qt = 0; qt < 2; ++qt) {
+        float dsum = den[qt];
+        dsum += __shfl_xor(dsum, 16);
+        dsum += __shfl_xor(dsum, 32);
+        const float inv = dsum > 0.f ? 1.0f / dsum : 0.f;
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
+        for (int r = 0; r < 4; ++r) {
+            const float iv = __shfl(inv, 4 * lg + r);
+            const int qi = q0 + 16 * qt + 4 * lg + r;
+            if (qi < Tn) {
+                float *op = o32 + ((int64_t)s * Tn + qi) * (int64_t)(Hq * DH) + (int64_t)h * DH + l16;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int row = rt * 16 + lg * 4 + r;
-                if (row < BQ) red[((size_t)w * BQ + row) * DH + dt * 16 + l16] = oacc[rt][dt][r];
+                for (int dt = 0; dt < DT; ++dt) op[dt * 16] = oacc[qt][dt][r] * iv;
             }
-    __syncthreads();
-    for (int idx = tid; idx < rows * DH; idx += AT_BLOCK) {
-        const int row = idx / DH, d = idx - row * DH;
-        float t = 0.f;
-#pragma unroll
-        for (int ww = 0; ww < AT_WAVES; ++ww) t += red[((size_t)ww * BQ + row) * DH + d];
-        o32[((int64_t)s * Tn + q0 + row) * (int64_t)(Hq * DH) + (int64_t)h * DH + d] = t * inv_den[row];
+        }
     }
-    AT_STAMP(5);
 }
 
 // =================================================================================================
@@ -787,16 +969,12 @@ k_transpose_v(const bf16_t *__restrict__ vc, bf16_t *__restrict__ vt, const int3
     }
 }
 
-template <int BQ, int SLOTS, int DH, int AT_WAVES>
-static bool launch_attn_tile_t(const void *q, const void *kc, const void *vt, float *o32, const RowAct *ra,
-                               const int32_t *pos0, int n_seq, int Tn, int L_max, int Hq, int Hkv, int lpadv,
-                               hipStream_t st)
+template <int BQ, int SLOTS, int DH, int NW>
+static bool launch_attn_select_t(const void *q, const void *kc, SelRow *sel, const RowAct *ra, const int32_t *pos0,
+                                 int n_seq, int Tn, int L_max, int Hq, int Hkv, hipStream_t st)
 {
-    constexpr int AT_BLOCK = AT_WAVES * 64;
-    auto kern = k_attn_tile<BQ, SLOTS, DH, AT_WAVES>;
-    const size_t score_bytes = (size_t)BQ * (SLOTS * 64 + 4) * 4;
-    const size_t red_bytes = (size_t)AT_WAVES * BQ * DH * 4;
-    const size_t lds = score_bytes > red_bytes ? score_bytes : red_bytes;
+    auto kern = k_attn_select<BQ, SLOTS, DH, NW>;
+    const size_t lds = (size_t)BQ * (SLOTS * 64 + 4) * 4;
     static bool attr_done = false;
     if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -804,20 +982,42 @@ static bool launch_attn_tile_t(const void *q, const void *kc, const void *vt, fl
             return false;
         attr_done = true;
     }
-    const float scale = 1.0f / sqrtf((float)DH);
-    hipLaunchKernelGGL(kern, dim3((Tn + BQ - 1) / BQ, Hq, n_seq), dim3(AT_BLOCK), lds, st, (const bf16_t *)q,
-                       (const bf16_t *)kc, (const bf16_t *)vt, o32, ra, pos0, Tn, L_max, Hq, Hkv, lpadv, scale);
+    hipLaunchKernelGGL(kern, dim3((Tn + BQ - 1) / BQ, Hq, n_seq), dim3(NW * 64), lds, st, (const bf16_t *)q,
+                       (const bf16_t *)kc, sel, ra, pos0, Tn, L_max, Hq, Hkv, 1.0f / sqrtf((float)DH));
+    return true;
+}
+
+template <int DH, int G>
+static bool launch_attn_pv_t(const void *q, const void *kc, const void *vt, const SelRow *sel, float *o32,
+                             const int32_t *pos0, int n_seq, int Tn, int L_max, int Hq, int Hkv, int lpadv, hipStream_t st)
+{
+    auto kern = k_attn_pv<DH, G>;
+    const size_t lds = 4 * (size_t)64 * DH * 2;
+    static bool attr_done = false;
+    if (!attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds) != hipSuccess)
+            return false;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((Tn + 31) / 32, Hkv, n_seq), dim3(G * 64), lds, st, (const bf16_t *)q, (const bf16_t *)kc,
+                       (const bf16_t *)vt, sel, o32, pos0, Tn, L_max, Hq, Hkv, lpadv, 1.0f / sqrtf((float)DH));
     return true;
 }
 
 int attn_tile_lpadv(int L_max) { return (L_max + 63) & ~63; }
+size_t attn_tile_sel_bytes(int64_t rows, int Hq) { return (size_t)rows * Hq * sizeof(SelRow); }
 
-bool launch_attn_tile(const void *q, const void *k_cache, const void *v_cache, void *vt, float *o32, const RowAct *ra,
-                      const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv, int dh, hipStream_t st)
+bool launch_attn_tile(const void *q, const void *k_cache, const void *v_cache, void *vt, void *sel_ws, float *o32,
+                      const RowAct *ra, const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv, int dh,
+                      hipStream_t st)
 {
     if ((int64_t)n_seq * T <= 0) return true;
-    if ((dh != 64 && dh != 128) || L_max > 4096 || T < 16) return false;
+    const int G = Hkv > 0 ? Hq / Hkv : 0;
+    if ((dh != 64 && dh != 128) || L_max > 4096 || T < 16 || G * Hkv != Hq || (G != 1 && G != 2 && G != 4 && G != 8))
+        return false;
     const int lpadv = attn_tile_lpadv(L_max);
+    SelRow *sel = (SelRow *)sel_ws;
     const dim3 tg((lpadv + 63) / 64, Hkv, n_seq);
     if (dh == 64)
         hipLaunchKernelGGL((k_transpose_v<64>), tg, dim3(256), 0, st, (const bf16_t *)v_cache, (bf16_t *)vt, pos0, T,
@@ -825,17 +1025,25 @@ bool launch_attn_tile(const void *q, const void *k_cache, const void *v_cache, v
     else
         hipLaunchKernelGGL((k_transpose_v<128>), tg, dim3(256), 0, st, (const bf16_t *)v_cache, (bf16_t *)vt, pos0, T,
                            L_max, Hkv, lpadv);
-#define SOL_AT(BQ, SL, NW)                                                                                                  \
-    return dh == 64 ? launch_attn_tile_t<BQ, SL, 64, NW>(q, k_cache, vt, o32, ra, pos0, n_seq, T, L_max, Hq, Hkv, lpadv, st) \
-                    : launch_attn_tile_t<BQ, SL, 128, NW>(q, k_cache, vt, o32, ra, pos0, n_seq, T, L_max, Hq, Hkv, lpadv, st)
-    if (L_max <= 256) { SOL_AT(32, 4, 8); }
-    // 16 rows keep the score rows of two workgroups resident per CU (2 x 66 KB of LDS), so one
-    // workgroup's load / MFMA phases overlap the other's selection phase: measured 3.1 ms against
-    // 4.7 ms for one 32-row workgroup per CU on the 32 x 1024-token layer
-    if (L_max <= 1024) { SOL_AT(16, 16, 8); }
-    if (L_max <= 2048) { SOL_AT(16, 32, 8); }
-    SOL_AT(8, 64, 8);
-#undef SOL_AT
+    // score rows of a workgroup stay in LDS: 16 rows x 1024 keys (66 KB) lets two workgroups share a CU
+    bool ok;
+#define SOL_SEL(BQ, SL)                                                                                              \
+    ok = dh == 64 ? launch_attn_select_t<BQ, SL, 64, 8>(q, k_cache, sel, ra, pos0, n_seq, T, L_max, Hq, Hkv, st)     \
+                  : launch_attn_select_t<BQ, SL, 128, 8>(q, k_cache, sel, ra, pos0, n_seq, T, L_max, Hq, Hkv, st)
+    if (L_max <= 256) { SOL_SEL(32, 4); }
+    else if (L_max <= 1024) { SOL_SEL(16, 16); }
+    else if (L_max <= 2048) { SOL_SEL(16, 32); }
+    else { SOL_SEL(8, 64); }
+#undef SOL_SEL
+    if (!ok) return false;
+#define SOL_PV(G_)                                                                                                   \
+    return dh == 64 ? launch_attn_pv_t<64, G_>(q, k_cache, vt, sel, o32, pos0, n_seq, T, L_max, Hq, Hkv, lpadv, st)  \
+                    : launch_attn_pv_t<128, G_>(q, k_cache, vt, sel, o32, pos0, n_seq, T, L_max, Hq, Hkv, lpadv, st)
+    if (G == 1) { SOL_PV(1); }
+    if (G == 2) { SOL_PV(2); }
+    if (G == 4) { SOL_PV(4); }
+    SOL_PV(8);
+#undef SOL_PV
 }
 
 }  // namespace sol

@@ -287,18 +287,69 @@ __device__ __forceinline__ int wave_tie_fixup(uint32_t (&key)[SLOTS], int n, uin
     return total;
 }
 
-// number of keys >= pivot held by the wave (columns >= n carry key 0 and pivot >= 1)
-template <int SLOTS>
-__device__ __forceinline__ int wave_count_ge(const uint32_t (&key)[SLOTS], int n, uint32_t pivot)
+// 64-bit lane mask of (key >= pivot) into a scalar register pair of the compiler's choice: unlike the
+// default VCC form, several of these can be in flight before the first population count reads one
+__device__ __forceinline__ unsigned long long mask_ge_u32(uint32_t key, uint32_t pivot)
+{
+    unsigned long long m;
+    asm("v_cmp_ge_u32_e64 %0, %1, %2" : "=s"(m) : "v"(key), "s"(pivot));
+    return m;
+}
+
+// number of keys >= pivot in the first NG groups of 256 columns (columns >= n carry key 0 and pivot >= 1)
+template <int SLOTS, int NG>
+__device__ __forceinline__ int wave_count_ge_g(const uint32_t (&key)[SLOTS], uint32_t pivot)
 {
     int cnt = 0;
 #pragma unroll
-    for (int j = 0; j < SLOTS / 4; ++j)
-        if (256 * j < n) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) cnt += __popcll(__ballot(key[4 * j + e] >= pivot));
-        }
+    for (int j = 0; j < NG; ++j) {
+        const unsigned long long m0 = mask_ge_u32(key[4 * j + 0], pivot), m1 = mask_ge_u32(key[4 * j + 1], pivot);
+        const unsigned long long m2 = mask_ge_u32(key[4 * j + 2], pivot), m3 = mask_ge_u32(key[4 * j + 3], pivot);
+        cnt += (__popcll(m0) + __popcll(m1)) + (__popcll(m2) + __popcll(m3));
+    }
     return cnt;
+}
+
+// number of keys >= pivot held by the wave (pivot wave-uniform)
+template <int SLOTS>
+__device__ __forceinline__ int wave_count_ge(const uint32_t (&key)[SLOTS], int n, uint32_t pivot)
+{
+    pivot = (uint32_t)__builtin_amdgcn_readfirstlane((int)pivot);
+    constexpr int NJ = SLOTS / 4;
+    const int ng = (n + 255) >> 8;
+    if constexpr (NJ <= 4) {
+        if (ng <= 1) return wave_count_ge_g<SLOTS, 1>(key, pivot);
+        if constexpr (NJ >= 2) if (ng == 2) return wave_count_ge_g<SLOTS, 2>(key, pivot);
+        if constexpr (NJ >= 3) if (ng == 3) return wave_count_ge_g<SLOTS, 3>(key, pivot);
+        return wave_count_ge_g<SLOTS, NJ>(key, pivot);
+    } else {
+        int cnt = 0;
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+            if (256 * j < n) {
+                const unsigned long long m0 = mask_ge_u32(key[4 * j + 0], pivot), m1 = mask_ge_u32(key[4 * j + 1], pivot);
+                const unsigned long long m2 = mask_ge_u32(key[4 * j + 2], pivot), m3 = mask_ge_u32(key[4 * j + 3], pivot);
+                cnt += (__popcll(m0) + __popcll(m1)) + (__popcll(m2) + __popcll(m3));
+            }
+        return cnt;
+    }
+}
+
+// the same for two rows with their own pivots, interleaved
+template <int SLOTS, int NG>
+__device__ __forceinline__ void wave_count_ge2_g(const uint32_t (&keya)[SLOTS], const uint32_t (&keyb)[SLOTS], uint32_t pa,
+                                                 uint32_t pb, int &ca, int &cb)
+{
+    ca = 0; cb = 0;
+#pragma unroll
+    for (int j = 0; j < NG; ++j) {
+        const unsigned long long a0 = mask_ge_u32(keya[4 * j + 0], pa), a1 = mask_ge_u32(keya[4 * j + 1], pa);
+        const unsigned long long b0 = mask_ge_u32(keyb[4 * j + 0], pb), b1 = mask_ge_u32(keyb[4 * j + 1], pb);
+        const unsigned long long a2 = mask_ge_u32(keya[4 * j + 2], pa), a3 = mask_ge_u32(keya[4 * j + 3], pa);
+        const unsigned long long b2 = mask_ge_u32(keyb[4 * j + 2], pb), b3 = mask_ge_u32(keyb[4 * j + 3], pb);
+        ca += (__popcll(a0) + __popcll(a1)) + (__popcll(a2) + __popcll(a3));
+        cb += (__popcll(b0) + __popcll(b1)) + (__popcll(b2) + __popcll(b3));
+    }
 }
 
 // ---- wave-level exact top-b (keys in registers) ---------------------------------------------------
@@ -321,27 +372,48 @@ __device__ __forceinline__ uint32_t wave_select_topk(uint32_t (&key)[SLOTS], int
     // invariant: count(key >= lo) >= b  and  count(key >= hi + 1) < b
     while (lo < hi) {
         const uint32_t mid = lo + ((hi - lo + 1u) >> 1);
-        int cnt = 0;
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) {
-            if (256 * j < n) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) cnt += __popcll(__ballot(key[4 * j + e] >= mid));
-            }
-        }
+        const int cnt = wave_count_ge<SLOTS>(key, n, mid);
         if (cnt == b) return mid;                       // exactly b keys at or above the pivot
         if (cnt > b) lo = mid; else hi = mid - 1u;
     }
     const uint32_t thr = lo;                            // the b-th largest key; ties decide the rest
-    int n_gt = 0;
-#pragma unroll
-    for (int j = 0; j < NJ; ++j)
-        if (256 * j < n) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) n_gt += __popcll(__ballot(key[4 * j + e] > thr));
-        }
+    const int n_gt = (thr == 0xFFFFFFFFu) ? 0 : wave_count_ge<SLOTS>(key, n, thr + 1u);
     wave_tie_fixup<SLOTS>(key, n, thr, b - n_gt, lane);
     return thr;
+}
+
+// Two rows searched in one loop: while both searches are open every step counts both rows, so the two
+// ballot -> count -> compare chains overlap. Leaves each row's bracket [lo, hi] (invariant of
+// wave_select_topk) and whether it stopped with exactly b keys at or above lo (then lo is the threshold).
+template <int SLOTS>
+__device__ __forceinline__ void wave_bisect2(const uint32_t (&keya)[SLOTS], const uint32_t (&keyb)[SLOTS], int na_in, int nb_in,
+                                             int ba_in, int bb_in, uint32_t &lo_a, uint32_t &hi_a, uint32_t &lo_b,
+                                             uint32_t &hi_b, bool &exact_a, bool &exact_b)
+{
+    constexpr int NJ = SLOTS / 4;
+    const int na = __builtin_amdgcn_readfirstlane(na_in), nb = __builtin_amdgcn_readfirstlane(nb_in);
+    const int ba = __builtin_amdgcn_readfirstlane(ba_in), bb = __builtin_amdgcn_readfirstlane(bb_in);
+    const int nm = na > nb ? na : nb;
+    uint32_t loa = (uint32_t)__builtin_amdgcn_readfirstlane((int)lo_a), hia = (uint32_t)__builtin_amdgcn_readfirstlane((int)hi_a);
+    uint32_t lob = (uint32_t)__builtin_amdgcn_readfirstlane((int)lo_b), hib = (uint32_t)__builtin_amdgcn_readfirstlane((int)hi_b);
+    exact_a = exact_b = false;
+    const int ng = (nm + 255) >> 8;
+    while (loa < hia && lob < hib) {
+        const uint32_t mida = loa + ((hia - loa + 1u) >> 1), midb = lob + ((hib - lob + 1u) >> 1);
+        int ca, cb;
+        if constexpr (NJ <= 4) {
+            if (ng <= 1) wave_count_ge2_g<SLOTS, 1>(keya, keyb, mida, midb, ca, cb);
+            else if (NJ >= 2 && ng == 2) wave_count_ge2_g<SLOTS, NJ >= 2 ? 2 : NJ>(keya, keyb, mida, midb, ca, cb);
+            else if (NJ >= 3 && ng == 3) wave_count_ge2_g<SLOTS, NJ >= 3 ? 3 : NJ>(keya, keyb, mida, midb, ca, cb);
+            else wave_count_ge2_g<SLOTS, NJ>(keya, keyb, mida, midb, ca, cb);
+        } else {
+            ca = wave_count_ge<SLOTS>(keya, na, mida);
+            cb = wave_count_ge<SLOTS>(keyb, nb, midb);
+        }
+        if (ca == ba) { loa = hia = mida; exact_a = true; } else if (ca > ba) loa = mida; else hia = mida - 1u;
+        if (cb == bb) { lob = hib = midb; exact_b = true; } else if (cb > bb) lob = midb; else hib = midb - 1u;
+    }
+    lo_a = loa; hi_a = hia; lo_b = lob; hi_b = hib;
 }
 
 // ---- per-token symmetric fake-quantiser ------------------------------------------------------

@@ -100,10 +100,14 @@ bool launch_attn_rows(const void *q, const void *k_cache, const void *v_cache, i
 // Decode attention: one query per sequence, bf16, 4 query heads per KV head, L_max <= 9216.
 bool launch_attn_decode(const void *q, const void *k_cache, const void *v_cache, float *o32, const RowAct *ra,
                         const int32_t *cache_len, int B, int L_max, int Hq, int Hkv, int dh, int *flags, hipStream_t st);
-// Tiled MFMA attention for the batched bf16 pass (L_max <= 4096, head_dim 64 or 128). vt is
-// workspace for the transposed V copy: n_seq * Hkv * dh * attn_tile_lpadv(L_max) elements.
-bool launch_attn_tile(const void *q, const void *k_cache, const void *v_cache, void *vt, float *o32, const RowAct *ra,
-                      const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv, int dh, hipStream_t st);
+// Batched bf16 attention (L_max <= 4096, head_dim 64 or 128, 1/2/4/8 query heads per KV head): a threshold
+// kernel followed by a flash-style masked softmax * V kernel. vt is workspace for the transposed V copy
+// (n_seq * Hkv * dh * attn_tile_lpadv(L_max) elements), sel_ws for the per-(row, head) thresholds
+// (attn_tile_sel_bytes(rows, Hq) bytes).
+bool launch_attn_tile(const void *q, const void *k_cache, const void *v_cache, void *vt, void *sel_ws, float *o32,
+                      const RowAct *ra, const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv, int dh,
+                      hipStream_t st);
+size_t attn_tile_sel_bytes(int64_t rows, int Hq);
 int attn_tile_lpadv(int L_max);
 
 }  // namespace sol
