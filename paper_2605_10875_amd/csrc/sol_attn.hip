@@ -283,11 +283,30 @@ __device__ __forceinline__ uint32_t wave_select_thr(const uint32_t (&key)[SLOTS]
     uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)lo_in);
     uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)hi_in);
     jstar = 0x7FFFFFFF;
-    while (lo < hi) {
-        const uint32_t mid = lo + ((hi - lo + 1u) >> 1);
+    // With g(x) = #(key >= x) - b + 1/2, g(lo) > 0 > g(hi + 1). The pivot is the zero of the straight line
+    // through the two ends in the score domain (regula falsi with the Illinois correction: an end that
+    // stays put twice has its weight halved); on smooth score distributions this lands between the b-th
+    // and (b+1)-th largest score in about 6 steps where bisection of the key needs about 14. A guess
+    // outside (lo, hi], or more than 12 steps, falls back to the midpoint of the key range, which bounds
+    // the worst case.
+    float flo = score_unkey(lo), fhi = score_unkey(hi), glo = (float)(n - b) + 0.5f, ghi = 0.5f - (float)b;
+    int side = 0;
+    for (int it = 0; lo < hi; ++it) {
+        const float fp = __builtin_fmaf(fhi - flo, glo * __builtin_amdgcn_rcpf(glo - ghi), flo);
+        uint32_t mid = (uint32_t)__builtin_amdgcn_readfirstlane((int)score_key(fp));
+        if (it >= 12 || !(mid > lo && mid <= hi)) mid = lo + ((hi - lo + 1u) >> 1);
         const int cnt = wave_count_ge<SLOTS>(key, n, mid);
         if (cnt == b) return mid;
-        if (cnt > b) lo = mid; else hi = mid - 1u;
+        const float g = (float)(cnt - b) + 0.5f;
+        if (cnt > b) {
+            lo = mid; flo = score_unkey(mid); glo = g;
+            if (side > 0) ghi *= 0.5f;
+            side = 1;
+        } else {
+            hi = mid - 1u; fhi = score_unkey(hi); ghi = g;
+            if (side < 0) glo *= 0.5f;
+            side = -1;
+        }
     }
     const int n_ge = wave_count_ge<SLOTS>(key, n, lo);
     if (n_ge > b) {                                      // more keys equal to the threshold than the budget has room for
@@ -306,12 +325,21 @@ __device__ __forceinline__ void sel_row_load(const float *row, int n, int lane, 
     uint32_t kmax = 0u, kmin = 0xFFFFFFFFu;
 #pragma unroll
     for (int j = 0; j < SLOTS / 4; ++j) {
-        if (256 * j < n) {
+        if (256 * (j + 1) <= n) {                          // every column of the group is a key of the row
+            const f32x4_a v = *reinterpret_cast<const f32x4_a *>(row + 256 * j + 4 * lane);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t kv = score_key(v[e]);
+                key[4 * j + e] = kv;
+                kmax = kv > kmax ? kv : kmax;
+                kmin = kv < kmin ? kv : kmin;
+            }
+        } else if (256 * j < n) {
             const f32x4_a v = *reinterpret_cast<const f32x4_a *>(row + 256 * j + 4 * lane);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const bool valid = 256 * j + 4 * lane + e < n;
-                const uint32_t kv = valid ? score_key(v[e] + 0.0f) : 0u;
+                const uint32_t kv = valid ? score_key(v[e]) : 0u;
                 key[4 * j + e] = kv;
                 kmax = kv > kmax ? kv : kmax;
                 kmin = (valid && kv < kmin) ? kv : kmin;
@@ -325,117 +353,158 @@ __device__ __forceinline__ void sel_row_load(const float *row, int n, int lane, 
     kmin_out = wave_min_u32(kmin);
 }
 
+#ifdef SOL_SEL_TIMING
+__device__ unsigned long long *g_sel_stamps;
+#endif
+// A workgroup walks several blocks of BQ query rows of one (sequence, head): while the waves search the
+// thresholds of one block, the q and K fragments of the next are already on their way into registers,
+// so the global-load latency of the score phase is hidden. Blocks are dealt to the nb workgroups of a
+// (sequence, head) in zigzag order (k-th visit: block nb*k + bi for even k, nb*k + nb-1-bi for odd k),
+// which gives every workgroup the same number of causal keys.
 template <int BQ, int SLOTS, int DH, int NW>
-__global__ void __launch_bounds__(NW * 64)
+__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(SLOTS <= 16 ? 4 : 2, SLOTS <= 16 ? 4 : 8)))
 k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRow *__restrict__ sel,
               const RowAct *__restrict__ ra, const int32_t *__restrict__ pos0, int Tn, int L_max, int Hq, int Hkv,
-              float scale)
+              float scale, int nb)
 {
     constexpr int LPAD = SLOTS * 64, LS = LPAD + 4;        // row stride = 4 mod 64 floats: the 16 query rows of a
                                                            // 128-bit store hit 16 different bank groups
     constexpr int RT = (BQ + 15) / 16, KK = DH / 32;
-    constexpr int UA = (SLOTS <= 16) ? 8 : 4;              // key tiles in flight per wave
+    constexpr int UA = (SLOTS <= 16 && DH <= 64) ? 8 : 4;  // key tiles in flight per wave
     extern __shared__ __align__(16) float sc[];            // [BQ][LS]
+    __shared__ int next_row;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int qb = (int)gridDim.x - 1 - (int)blockIdx.x;   // heaviest blocks first
-    const int h = blockIdx.y, s = blockIdx.z;
+    const int bi = blockIdx.x, h = blockIdx.y, s = blockIdx.z;
     const int p0 = pos0 ? pos0[s] : 0;
     if (p0 < 0 || p0 + Tn > L_max) return;                 // flagged by the projection kernel; sequence skipped
-    const int q0 = qb * BQ;
-    const int rows = (Tn - q0 < BQ) ? (Tn - q0) : BQ;
-    const int n_max = p0 + q0 + rows;
+    const int n_qb = (Tn + BQ - 1) / BQ;
     const int kvh = h / (Hq / Hkv);
+    // wave-uniform bases + 32-bit per-lane offsets: one address register per load instead of two
     const bf16_t *kbase = kc + ((int64_t)s * Hkv + kvh) * (int64_t)L_max * DH;
+    const bf16_t *qbase = q + (int64_t)s * Tn * (int64_t)(Hq * DH) + (int64_t)h * DH;
     const int l16 = lane & 15, lg = lane >> 4;
 
-    // ---- scores: S^T tile = K tile (rows) x Q^T (columns); lane (l16, lg) gets keys 4*lg..4*lg+3 of query l16 ----
-    {
-        bf16x8_a qf[RT][KK];
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
-            int qr = q0 + rt * 16 + l16;
-            if (qr >= Tn) qr = Tn - 1;
-            const bf16_t *qp = q + ((int64_t)s * Tn + qr) * (int64_t)(Hq * DH) + (int64_t)h * DH + lg * 8;
-#pragma unroll
-            for (int kk = 0; kk < KK; ++kk)
-                qf[rt][kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(qp + kk * 32));
-        }
+    bf16x8_a qf[RT][KK], kf[UA][KK];
+    // q fragments and the first group of K tiles of query block QB_ (lane (l16, lg): row l16, 8 values at 8*lg)
+#define SOL_SEL_LOAD(QB_)                                                                                  \
+    {                                                                                                      \
+        const int q0_ = (QB_) * BQ;                                                                        \
+        const int nmax_ = p0 + (Tn < q0_ + BQ ? Tn : q0_ + BQ);                                            \
+        _Pragma("unroll") for (int rt = 0; rt < RT; ++rt) {                                                \
+            int qr = q0_ + rt * 16 + l16;                                                                  \
+            if (qr >= Tn) qr = Tn - 1;                                                                     \
+            const uint32_t qo = (uint32_t)qr * (uint32_t)(Hq * DH) + (uint32_t)(lg * 8);                   \
+            _Pragma("unroll") for (int kk = 0; kk < KK; ++kk)                                              \
+                qf[rt][kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(qbase + qo + kk * 32)); \
+        }                                                                                                  \
+        int key0_ = w * 16 + l16;                                                                          \
+        asm volatile("" : "+v"(key0_));   /* recomputed per visit: hoisted copies of all UA indices spill */ \
+        _Pragma("unroll") for (int u = 0; u < UA; ++u) {                                                   \
+            if ((w + u * NW) * 16 < nmax_) {                /* tiles beyond the block's last key are never used */ \
+                int key = key0_ + u * NW * 16;                                                             \
+                if (key >= nmax_) key = nmax_ - 1;                                                         \
+                const uint32_t ko = (uint32_t)key * (uint32_t)DH + (uint32_t)(lg * 8);                     \
+                _Pragma("unroll") for (int kk = 0; kk < KK; ++kk)                                          \
+                    kf[u][kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(kbase + ko + kk * 32)); \
+            }                                                                                              \
+        }                                                                                                  \
+    }
+    // S^T tile = K tile (rows) x Q^T (columns): lane (l16, lg) gets keys 4*lg..4*lg+3 of query l16
+#define SOL_SEL_MFMA(U_, KT_)                                                                              \
+    _Pragma("unroll") for (int rt = 0; rt < RT; ++rt) {                                                    \
+        floatx4_a acc = {0.f, 0.f, 0.f, 0.f};                                                              \
+        _Pragma("unroll") for (int kk = 0; kk < KK; ++kk)                                                  \
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[U_][kk], qf[rt][kk], acc, 0, 0, 0);           \
+        const int row = rt * 16 + l16;                                                                     \
+        if (row < BQ)                                                                                      \
+            *reinterpret_cast<f32x4_a *>(sc + row * LS + (KT_) * 16 + 4 * lg) =                            \
+                f32x4_a{acc[0] * scale, acc[1] * scale, acc[2] * scale, acc[3] * scale};                   \
+    }
+
+    int visit = 0, qb = bi;
+    if (qb >= n_qb) return;
+    SOL_SEL_LOAD(qb);
+#ifdef SOL_SEL_TIMING
+    unsigned long long tacc[6] = {0, 0, 0, 0, 0, 0}, tprev = __builtin_readcyclecounter();
+#define SEL_T(i) { const unsigned long long t_ = __builtin_readcyclecounter(); tacc[i] += t_ - tprev; tprev = t_; }
+#else
+#define SEL_T(i)
+#endif
+    while (true) {
+        const int q0 = qb * BQ;
+        const int rows = (Tn - q0 < BQ) ? (Tn - q0) : BQ;
+        const int n_max = p0 + q0 + rows;
         const int n_kt = (n_max + 15) >> 4;
-        for (int kt0 = w; kt0 < n_kt; kt0 += NW * UA) {
-            bf16x8_a kf[UA][KK];
+        // ---- scores of this block into LDS ----
+#pragma unroll
+        for (int u = 0; u < UA; ++u) {
+            const int kt = w + u * NW;
+            if (kt < n_kt) { SOL_SEL_MFMA(u, kt); }
+        }
+        for (int kt0 = w + NW * UA; kt0 < n_kt; kt0 += NW * UA) {      // rows longer than the prefetched group
 #pragma unroll
             for (int u = 0; u < UA; ++u) {
                 int key = (kt0 + u * NW) * 16 + l16;
                 if (key >= n_max) key = n_max - 1;
-                const bf16_t *kp = kbase + (int64_t)key * DH + lg * 8;
+                const uint32_t ko = (uint32_t)key * (uint32_t)DH + (uint32_t)(lg * 8);
 #pragma unroll
                 for (int kk = 0; kk < KK; ++kk)
-                    kf[u][kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(kp + kk * 32));
+                    kf[u][kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(kbase + ko + kk * 32));
             }
 #pragma unroll
             for (int u = 0; u < UA; ++u) {
                 const int kt = kt0 + u * NW;
-                if (kt < n_kt) {
-#pragma unroll
-                    for (int rt = 0; rt < RT; ++rt) {
-                        floatx4_a acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                        for (int kk = 0; kk < KK; ++kk)
-                            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[u][kk], qf[rt][kk], acc, 0, 0, 0);
-                        const int row = rt * 16 + l16;
-                        if (row < BQ)
-                            *reinterpret_cast<f32x4_a *>(sc + row * LS + kt * 16 + 4 * lg) =
-                                f32x4_a{acc[0] * scale, acc[1] * scale, acc[2] * scale, acc[3] * scale};
-                    }
-                }
+                if (kt < n_kt) { SOL_SEL_MFMA(u, kt); }
             }
         }
-    }
-    __syncthreads();
+        SEL_T(0);
+        if (tid == 0) next_row = NW;
+        __syncthreads();
+        SEL_T(1);
+        // ---- next block's fragments on their way while this block's rows are searched ----
+        ++visit;
+        const int qb_next = nb * visit + ((visit & 1) ? nb - 1 - bi : bi);
+        const bool more = qb_next < n_qb;
+        if (more) SOL_SEL_LOAD(qb_next);
+        SEL_T(2);
 
-    // ---- per row: maximum, and the threshold when the budget is below the row length; rows go two at a
-    // time per wave so that one row's ballot -> count -> branch chain fills the other's latency ----
-    constexpr bool PAIR = (SLOTS <= 16) && (BQ >= 2 * NW);
-    constexpr int RSTEP = PAIR ? 2 * NW : NW;
-    for (int r = w; r < rows; r += RSTEP) {
-        const int rb = r + NW;
-        const bool live_b = PAIR && rb < rows;
-        const int na = p0 + q0 + r + 1;
-        const RowAct act_a = ra[(int64_t)s * Tn + q0 + r];
-        const int ba = budget_ceil(act_a.keep_num, act_a.keep_den, na);
-        uint32_t keya[SLOTS], kmax_a, kmin_a;
-        sel_row_load<SLOTS>(sc + r * LS, na, lane, keya, kmax_a, kmin_a);
-        uint32_t thr_a = 0u, thr_b = 0u;                   // key 0: below every score, everything kept
-        int js_a = 0x7FFFFFFF, js_b = 0x7FFFFFFF;
-        uint32_t kmax_b = 0u;
-        if constexpr (PAIR) {
-            if (live_b) {
-                const int nb = na + NW;
-                const RowAct act_b = ra[(int64_t)s * Tn + q0 + rb];
-                const int bb = budget_ceil(act_b.keep_num, act_b.keep_den, nb);
-                uint32_t keyb[SLOTS], kmin_b;
-                sel_row_load<SLOTS>(sc + rb * LS, nb, lane, keyb, kmax_b, kmin_b);
-                uint32_t loa = kmin_a, hia = kmax_a, lob = kmin_b, hib = kmax_b;
-                bool exact_a = false, exact_b = false;
-                if (ba < na && bb < nb) wave_bisect2<SLOTS>(keya, keyb, na, nb, ba, bb, loa, hia, lob, hib, exact_a, exact_b);
-                if (ba < na) thr_a = exact_a ? loa : wave_select_thr<SLOTS>(keya, na, ba, loa, hia, lane, js_a);
-                if (bb < nb) thr_b = exact_b ? lob : wave_select_thr<SLOTS>(keyb, nb, bb, lob, hib, lane, js_b);
-            } else if (ba < na) {
-                thr_a = wave_select_thr<SLOTS>(keya, na, ba, kmin_a, kmax_a, lane, js_a);
+        // ---- per row: maximum, and the threshold when the budget is below the row length ----
+        // the first NW rows go one to each wave, the others to whichever wave is free first
+        for (int r = w; r < rows;) {
+            const int n = p0 + q0 + r + 1;
+            const RowAct act = ra[(int64_t)s * Tn + q0 + r];
+            const int b = budget_ceil(act.keep_num, act.keep_den, n);
+            uint32_t key[SLOTS], kmax, kmin;
+            sel_row_load<SLOTS>(sc + r * LS, n, lane, key, kmax, kmin);
+            uint32_t thr = 0u;                             // key 0: below every score, everything kept
+            int js = 0x7FFFFFFF;
+            if (b < n) thr = wave_select_thr<SLOTS>(key, n, b, kmin, kmax, lane, js);
+            int r_next = 0;
+            if (lane == 0) {
+                sel[((int64_t)s * Tn + q0 + r) * Hq + h] =
+                    SelRow{thr ? score_unkey(thr) : -__builtin_inff(), score_unkey(kmax), js, 0};
+                r_next = atomicAdd(&next_row, 1);
             }
-        } else if (ba < na) {
-            thr_a = wave_select_thr<SLOTS>(keya, na, ba, kmin_a, kmax_a, lane, js_a);
+            r = __builtin_amdgcn_readfirstlane(r_next);
         }
-        if (lane == 0) {
-            sel[((int64_t)s * Tn + q0 + r) * Hq + h] =
-                SelRow{thr_a ? score_unkey(thr_a) : -__builtin_inff(), score_unkey(kmax_a), js_a, 0};
-            if (live_b)
-                sel[((int64_t)s * Tn + q0 + rb) * Hq + h] =
-                    SelRow{thr_b ? score_unkey(thr_b) : -__builtin_inff(), score_unkey(kmax_b), js_b, 0};
-        }
+        SEL_T(3);
+        if (!more) break;
+        __syncthreads();                                   // every row is in registers or done: LDS may be overwritten
+        SEL_T(4);
+        qb = qb_next;
     }
+#ifdef SOL_SEL_TIMING
+    if (tid == 0 && g_sel_stamps) {
+        unsigned long long *o = g_sel_stamps + ((size_t)(blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 8;
+        for (int i = 0; i < 5; ++i) o[i] = tacc[i];
+        o[5] = visit;
+    }
+#endif
+#undef SEL_T
+#undef SOL_SEL_LOAD
+#undef SOL_SEL_MFMA
 }
 
 // ---- k_attn_pv -------------------------------------------------------------------------------------
@@ -982,8 +1051,13 @@ static bool launch_attn_select_t(const void *q, const void *kc, SelRow *sel, con
             return false;
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3((Tn + BQ - 1) / BQ, Hq, n_seq), dim3(NW * 64), lds, st, (const bf16_t *)q,
-                       (const bf16_t *)kc, sel, ra, pos0, Tn, L_max, Hq, Hkv, 1.0f / sqrtf((float)DH));
+    // workgroups per (sequence, head): enough to fill the chip about eight times over, at most one per block
+    const int n_qb = (Tn + BQ - 1) / BQ;
+    int nb = (int)((4096 + (int64_t)Hq * n_seq - 1) / ((int64_t)Hq * n_seq));
+    if (nb > n_qb) nb = n_qb;
+    if (nb < 1) nb = 1;
+    hipLaunchKernelGGL(kern, dim3(nb, Hq, n_seq), dim3(NW * 64), lds, st, (const bf16_t *)q, (const bf16_t *)kc, sel, ra,
+                       pos0, Tn, L_max, Hq, Hkv, 1.0f / sqrtf((float)DH), nb);
     return true;
 }
 

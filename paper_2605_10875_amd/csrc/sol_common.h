@@ -429,7 +429,9 @@ __device__ __forceinline__ float fq_code(float z, float s, float qmax)
 
 __device__ __forceinline__ int budget_ceil(uint32_t num, uint32_t den, int n)
 {
-    unsigned long long b = ((unsigned long long)num * (unsigned long long)n + den - 1ull) / den;
+    const unsigned long long x = (unsigned long long)num * (unsigned long long)n + den - 1ull;
+    // the 32-bit quotient is an order of magnitude fewer instructions than the 64-bit one
+    unsigned long long b = (x >> 32) == 0ull ? (unsigned long long)((uint32_t)x / den) : x / den;
     if (b < 1ull) b = 1ull;
     if (b > (unsigned long long)n) b = (unsigned long long)n;
     return (int)b;
