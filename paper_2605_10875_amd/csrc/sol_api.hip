@@ -381,7 +381,7 @@ static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_i
                 return fail(ctx, SOL_ERR_UNSUPPORTED, "skinny GEMM: unsupported shape");
         } else {
             fused_qkv = mfma && launch_gemm_qkv_rope(w.h, lw->wq, lw->wk, lw->wv, w.qb, kc, vc, ctx->d_rope, pos0, n_seq,
-                                                     T, L_max, Hq, Hkv, dh, d, ctx->d_flags, st);
+                                                     T, L_max, Hq, Hkv, dh, d, ctx->d_flags, w.big32, st);
             if (!fused_qkv) {
                 launch_gemm_generic(w.h, dt, d, lw->wq, dt, d, w.big32, nqkv, M, nq, d, st);
                 launch_gemm_generic(w.h, dt, d, lw->wk, dt, d, w.big32 + nq, nqkv, M, nkv, d, st);

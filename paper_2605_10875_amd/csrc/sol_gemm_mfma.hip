@@ -13,9 +13,9 @@
 // contiguous band of the tile grid in groups of GROUP_M tile rows, so the tiles resident on an
 // XCD at any time share A rows and B columns in that XCD's L2.
 //
-// Epilogue: accumulators are spilled 32 rows at a time through LDS into row-contiguous order and
-// handed to an epilogue functor 4 columns per lane (rotary + cache write, residual add,
-// SiLU(gate)*up, plain store).
+// Epilogue: functors consume the accumulators in their MFMA register layout, two rows at a time
+// (rotary + cache write, residual add, SiLU(gate)*up, plain store); bf16 outputs are paired up across
+// neighbouring lanes into 4-byte stores.
 #include "sol_internal.h"
 
 namespace sol {
@@ -53,107 +53,254 @@ struct BMap {                        // virtual column -> weight row
 };
 
 // ------------------------------------------------------------------------------------------------
-// epilogues: apply(row, vcol0, lc, lrow) handles local columns [lc, lc+4) of a wave-tile row whose
-// first virtual column is vcol0; lrow points at the fp32 row in LDS (WN floats).
+// Epilogues work on the accumulator layout of v_mfma_f32_32x32x16 directly: for one (row-tile, register
+// pair) a lane holds, for two consecutive rows, the TN values at columns  c + 32*j  (c = lane % 32) of
+// the wave tile. An epilogue has two halves so that the kernel can issue every global read of a 32-row
+// tile before the first store (the compiler must assume that stores alias later loads):
+//   preload(row0, row1, ok0, ok1, vcol0, c, aux)      reads what the row pair needs from memory into aux
+//                                                     (row0 / row1 clamped to existing rows: no branches)
+//   rows2(row0, ok0, ok1, vcol0, c, v0, v1, aux)      combines and stores
+// row0 / row0 + 1 are the global rows, ok0 / ok1 say whether they exist (every lane still runs the code:
+// bf16 outputs exchange values between neighbouring lanes), vcol0 is the wave tile's first virtual column.
 // ------------------------------------------------------------------------------------------------
+
+// Two rows of bf16 outputs at column c: neighbouring lanes pair up so that every lane stores one 4-byte
+// pair: even lanes (row0, columns c, c+1), odd lanes (row1, columns c-1, c).
+__device__ __forceinline__ void store_bf16_rows2(bf16_t *p0, bf16_t *p1, bool ok0, bool ok1, int c, float x0, float x1)
+{
+    const float t0 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x0), 0xB1, 0xF, 0xF, false));
+    const float t1 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x1), 0xB1, 0xF, 0xF, false));
+    const bool even = (c & 1) == 0;
+    const uint32_t pk = even ? pack_bf16x2(x0, t0) : pack_bf16x2(t1, x1);
+    bf16_t *dst = even ? p0 + c : p1 + (c - 1);
+    if (even ? ok0 : ok1) *reinterpret_cast<uint32_t *>(dst) = pk;
+}
+
+struct NoAux {};
+
 struct EpiStoreF32 {
     float *C; int64_t ldc;
-    template <int WN> __device__ __forceinline__ void apply(int64_t row, int vcol0, int lc, const float *lrow) const
+    template <int TN> using Aux = NoAux;
+    template <int TN> __device__ __forceinline__ void preload0(int64_t, int64_t, NoAux &) const {}
+    template <int TN> __device__ __forceinline__ void preload(int64_t, int64_t, bool, bool, int, int, NoAux &) const {}
+    template <int TN>
+    __device__ __forceinline__ void rows2(int64_t row0, bool ok0, bool ok1, int vcol0, int c, const float (&v0)[TN],
+                                          const float (&v1)[TN], const NoAux &) const
     {
-        *reinterpret_cast<float4 *>(C + row * ldc + vcol0 + lc) = *reinterpret_cast<const float4 *>(lrow + lc);
+        float *p0 = C + row0 * ldc + vcol0 + c, *p1 = p0 + ldc;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            if (ok0) p0[32 * j] = v0[j];
+            if (ok1) p1[32 * j] = v1[j];
+        }
     }
 };
+
+template <int TN> struct AuxRows { float a0[TN], a1[TN]; };
 
 // x2 = resid + acc  (fp32 out), resid in bf16
 struct EpiResidF32 {
     const bf16_t *resid; float *out; int64_t ld;
-    template <int WN> __device__ __forceinline__ void apply(int64_t row, int vcol0, int lc, const float *lrow) const
+    template <int TN> using Aux = AuxRows<TN>;
+    template <int TN> __device__ __forceinline__ void preload0(int64_t, int64_t, AuxRows<TN> &) const {}
+    template <int TN>
+    __device__ __forceinline__ void preload(int64_t row0, int64_t row1, bool, bool, int vcol0, int c, AuxRows<TN> &x) const
     {
-        const float4 v = *reinterpret_cast<const float4 *>(lrow + lc);
-        const uint2 r = *reinterpret_cast<const uint2 *>(resid + row * ld + vcol0 + lc);
-        float4 o;
-        o.x = v.x + __uint_as_float(r.x << 16);
-        o.y = v.y + __uint_as_float(r.x & 0xFFFF0000u);
-        o.z = v.z + __uint_as_float(r.y << 16);
-        o.w = v.w + __uint_as_float(r.y & 0xFFFF0000u);
-        *reinterpret_cast<float4 *>(out + row * ld + vcol0 + lc) = o;
+        const int64_t o0 = row0 * ld + vcol0 + c, o1 = row1 * ld + vcol0 + c;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            x.a0[j] = bf16_to_f32(resid[o0 + 32 * j]);
+            x.a1[j] = bf16_to_f32(resid[o1 + 32 * j]);
+        }
+    }
+    template <int TN>
+    __device__ __forceinline__ void rows2(int64_t row0, bool ok0, bool ok1, int vcol0, int c, const float (&v0)[TN],
+                                          const float (&v1)[TN], const AuxRows<TN> &x) const
+    {
+        const int64_t o0 = row0 * ld + vcol0 + c, o1 = o0 + ld;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            if (ok0) out[o0 + 32 * j] = v0[j] + x.a0[j];
+            if (ok1) out[o1 + 32 * j] = v1[j] + x.a1[j];
+        }
     }
 };
 
 // out = bf16(x2 + acc), x2 in fp32
 struct EpiResidOut {
     const float *x2; bf16_t *out; int64_t ld;
-    template <int WN> __device__ __forceinline__ void apply(int64_t row, int vcol0, int lc, const float *lrow) const
+    template <int TN> using Aux = AuxRows<TN>;
+    template <int TN> __device__ __forceinline__ void preload0(int64_t, int64_t, AuxRows<TN> &) const {}
+    template <int TN>
+    __device__ __forceinline__ void preload(int64_t row0, int64_t row1, bool, bool, int vcol0, int c, AuxRows<TN> &x) const
     {
-        const float4 v = *reinterpret_cast<const float4 *>(lrow + lc);
-        const float4 r = *reinterpret_cast<const float4 *>(x2 + row * ld + vcol0 + lc);
-        uint2 o;
-        o.x = pack_bf16x2(v.x + r.x, v.y + r.y);
-        o.y = pack_bf16x2(v.z + r.z, v.w + r.w);
-        *reinterpret_cast<uint2 *>(out + row * ld + vcol0 + lc) = o;
+        const int64_t o0 = row0 * ld + vcol0 + c, o1 = row1 * ld + vcol0 + c;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            x.a0[j] = x2[o0 + 32 * j];
+            x.a1[j] = x2[o1 + 32 * j];
+        }
+    }
+    template <int TN>
+    __device__ __forceinline__ void rows2(int64_t row0, bool ok0, bool ok1, int vcol0, int c, const float (&v0)[TN],
+                                          const float (&v1)[TN], const AuxRows<TN> &x) const
+    {
+        const int64_t o0 = row0 * ld + vcol0, o1 = o0 + ld;
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+            store_bf16_rows2(out + o0 + 32 * j, out + o1 + 32 * j, ok0, ok1, c, v0[j] + x.a0[j], v1[j] + x.a1[j]);
     }
 };
 
 // a = bf16(silu(gate) * up); the wave tile's first WN/2 columns are gate, the rest the matching up
 struct EpiSiluMul {
     bf16_t *a; int64_t ld;   // [M][d_ff]
-    template <int WN> __device__ __forceinline__ void apply(int64_t row, int vcol0, int lc, const float *lrow) const
+    template <int TN> using Aux = NoAux;
+    template <int TN> __device__ __forceinline__ void preload0(int64_t, int64_t, NoAux &) const {}
+    template <int TN> __device__ __forceinline__ void preload(int64_t, int64_t, bool, bool, int, int, NoAux &) const {}
+    static __device__ __forceinline__ float silu_mul(float g, float u)
     {
-        if (lc >= WN / 2) return;
-        const float4 g = *reinterpret_cast<const float4 *>(lrow + lc);
-        const float4 u = *reinterpret_cast<const float4 *>(lrow + WN / 2 + lc);
-        // g * sigmoid(g) * u with the hardware exp2 / reciprocal (about 1 ulp each, far below the
-        // bf16 rounding that follows)
-        const float a0 = g.x * __frcp_rn(1.0f + __expf(-g.x)) * u.x, a1 = g.y * __frcp_rn(1.0f + __expf(-g.y)) * u.y;
-        const float a2 = g.z * __frcp_rn(1.0f + __expf(-g.z)) * u.z, a3 = g.w * __frcp_rn(1.0f + __expf(-g.w)) * u.w;
-        uint2 o;
-        o.x = pack_bf16x2(a0, a1);
-        o.y = pack_bf16x2(a2, a3);
-        *reinterpret_cast<uint2 *>(a + row * ld + (vcol0 / WN) * (WN / 2) + lc) = o;
+        // g * sigmoid(g) * u with the hardware exp2 / reciprocal (about 1 ulp each, far below the bf16
+        // rounding that follows)
+        return g * __frcp_rn(1.0f + __expf(-g)) * u;
+    }
+    template <int TN>
+    __device__ __forceinline__ void rows2(int64_t row0, bool ok0, bool ok1, int vcol0, int c, const float (&v0)[TN],
+                                          const float (&v1)[TN], const NoAux &) const
+    {
+        constexpr int WN = TN * 32;
+        bf16_t *p0 = a + row0 * ld + (vcol0 / WN) * (WN / 2), *p1 = p0 + ld;
+#pragma unroll
+        for (int j = 0; j < TN / 2; ++j)
+            store_bf16_rows2(p0 + 32 * j, p1 + 32 * j, ok0, ok1, c, silu_mul(v0[j], v0[j + TN / 2]),
+                             silu_mul(v1[j], v1[j + TN / 2]));
     }
 };
 
-// rotary embedding on q and k heads (pairs (c, c + dh/2)), q -> [M][nq], k/v -> caches
+// rotary embedding on q and k heads (pairs (c, c + dh/2)), q -> [M][nq], k/v -> caches.
+// row_sp[row] = (sequence, absolute position) of the row, position -1 if its sequence does not fit the
+// cache (written by k_row_positions before the GEMM).
+template <int TN> struct AuxRope { float2 t0[TN], t1[TN]; int2 sp0, sp1; };
+
+template <int DHT>                                      // head size: 64 or 128
 struct EpiQkvRope {
     bf16_t *q, *kc, *vc;
-    const float2 *rope; const int32_t *pos0;
-    int Tn, L_max, Hq, Hkv, dh; int *flags;
-    template <int WN> __device__ __forceinline__ void apply(int64_t row, int vcol0, int lc, const float *lrow) const
+    const float2 *rope; const int2 *row_sp;
+    int L_max, Hq, Hkv;
+    template <int TN> using Aux = AuxRope<TN>;
+    template <int TN> __device__ __forceinline__ void preload0(int64_t row0, int64_t row1, AuxRope<TN> &x) const
     {
-        const int s = (int)(row / Tn), i = (int)(row - (int64_t)s * Tn);
-        const int p0 = pos0 ? pos0[s] : 0;
-        if (p0 < 0 || p0 + Tn > L_max) { if (lc == 0 && vcol0 == 0 && i == 0) atomicOr(flags, FLAG_CACHE_OVERFLOW); return; }
-        const int pos = p0 + i, half = dh >> 1;
-        const int v = vcol0 + lc;                       // virtual column of the first of 4 values
-        const int nq = Hq * dh, nkv = Hkv * dh;
-        const float4 x = *reinterpret_cast<const float4 *>(lrow + lc);
-        float o[4] = {x.x, x.y, x.z, x.w};
-        if (v < nq + nkv) {                             // q or k: rotate
-            const int c = v % dh;                       // position inside the head (4 values stay in one half)
-            const bool lo = c < half;
-            const float4 y = *reinterpret_cast<const float4 *>(lrow + lc + (lo ? half : -half));
-            const float yy[4] = {y.x, y.y, y.z, y.w};
-            const float2 *cs = rope + (int64_t)pos * half + (lo ? c : c - half);
+        x.sp0 = row_sp[row0];
+        x.sp1 = row_sp[row1];
+    }
+    template <int TN>
+    __device__ __forceinline__ void preload(int64_t, int64_t, bool, bool, int vcol0, int c, AuxRope<TN> &x) const
+    {
+        constexpr int dh = DHT, half = DHT / 2;
+        if (vcol0 < (Hq + Hkv) * dh) {                   // q or k: cos / sin of the two positions
+            const int pa = x.sp0.y < 0 ? 0 : x.sp0.y, pb = x.sp1.y < 0 ? 0 : x.sp1.y;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float2 t = cs[e];
-                o[e] = lo ? (o[e] * t.x - yy[e] * t.y) : (o[e] * t.x + yy[e] * t.y);
+            for (int j = 0; j < TN; ++j) {
+                const int cj = (32 * j + c) & (dh - 1);  // position inside the head
+                const int ci = cj < half ? cj : cj - half;
+                x.t0[j] = rope[(int64_t)pa * half + ci];
+                x.t1[j] = rope[(int64_t)pb * half + ci];
             }
         }
-        uint2 pk;
-        pk.x = pack_bf16x2(o[0], o[1]);
-        pk.y = pack_bf16x2(o[2], o[3]);
-        bf16_t *dst;
-        if (v < nq) dst = q + row * (int64_t)nq + v;
-        else if (v < nq + nkv) { const int w = v - nq; dst = kc + (((int64_t)s * Hkv + w / dh) * L_max + pos) * dh + w % dh; }
-        else { const int w = v - nq - nkv; dst = vc + (((int64_t)s * Hkv + w / dh) * L_max + pos) * dh + w % dh; }
-        *reinterpret_cast<uint2 *>(dst) = pk;
+    }
+    template <int TN>
+    __device__ __forceinline__ void rows2(int64_t row0, bool ok0, bool ok1, int vcol0, int c, const float (&v0)[TN],
+                                          const float (&v1)[TN], const AuxRope<TN> &x) const
+    {
+        constexpr int dh = DHT, half = DHT / 2;
+        const int nq = Hq * dh, nkv = Hkv * dh;
+        ok0 = ok0 && x.sp0.y >= 0;
+        ok1 = ok1 && x.sp1.y >= 0;
+        // the wave tile (128 columns, heads of 64 or 128) lies inside one of q / k / v
+        const int seg = vcol0 < nq ? 0 : (vcol0 < nq + nkv ? 1 : 2);
+        const int w0 = vcol0 - (seg == 0 ? 0 : (seg == 1 ? nq : nq + nkv));   // column inside the segment
+        bf16_t *d0, *d1;                                 // destination of the wave tile's first column, rows 0 / 1
+        if (seg == 0) { d0 = q + row0 * (int64_t)nq + w0; d1 = d0 + nq; }
+        else {
+            bf16_t *cache = seg == 1 ? kc : vc;
+            const int hd = w0 / dh, wi = w0 - hd * dh;
+            d0 = cache + (((int64_t)x.sp0.x * Hkv + hd) * L_max + x.sp0.y) * dh + wi;
+            d1 = cache + (((int64_t)x.sp1.x * Hkv + hd) * L_max + x.sp1.y) * dh + wi;
+        }
+        const int hstep = (seg == 0 || dh >= TN * 32) ? 0 : (int)((int64_t)L_max * dh) - dh;   // next head inside the tile (dh = 64)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            float o0 = v0[j], o1 = v1[j];
+            if (seg < 2) {                               // q or k: rotate
+                const bool lo = ((32 * j) & (dh - 1)) < half;                 // the same for every c < 32
+                const int jp = lo ? j + half / 32 : j - half / 32;            // tile of the partner column
+                const float y0 = v0[jp], y1 = v1[jp];
+                o0 = lo ? (o0 * x.t0[j].x - y0 * x.t0[j].y) : (o0 * x.t0[j].x + y0 * x.t0[j].y);
+                o1 = lo ? (o1 * x.t1[j].x - y1 * x.t1[j].y) : (o1 * x.t1[j].x + y1 * x.t1[j].y);
+            }
+            const int hj = (32 * j) / dh;                // head inside the tile of column 32*j + c
+            const int64_t off = (seg == 0) ? 32 * j : (int64_t)hj * hstep + 32 * j;
+            store_bf16_rows2(d0 + off, d1 + off, ok0, ok1, c, o0, o1);
+        }
     }
 };
 
-// ------------------------------------------------------------------------------------------------
-// the kernel
-// ------------------------------------------------------------------------------------------------
+// row -> (sequence, absolute position), position -1 (and the overflow flag) if the sequence does not fit
+__global__ void __launch_bounds__(256)
+k_row_positions(const int32_t *__restrict__ pos0, int64_t M, int Tn, int L_max, int2 *__restrict__ row_sp, int *flags)
+{
+    const int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (row >= M) return;
+    const int s = (int)(row / Tn), i = (int)(row - (int64_t)s * Tn);
+    const int p0 = pos0 ? pos0[s] : 0;
+    const bool bad = p0 < 0 || p0 + Tn > L_max;
+    if (bad && i == 0) atomicOr(flags, FLAG_CACHE_OVERFLOW);
+    row_sp[row] = make_int2(s, bad ? -1 : p0 + i);
+}
+
+// Register r of accumulator tile (i, j) is row 32*i + 8*(r/4) + 4*(lane/32) + r%4, column 32*j + lane%32
+// of the wave tile (row_w already holds the wave tile's first row + 4*(lane/32)). Per 32-row tile all
+// global reads of the epilogue are issued first, then the row pairs are combined and stored.
+template <bool FULL, int TM, int TN, class Epi>
+__device__ __forceinline__ void gemm_epilogue(const floatx16_t (&acc)[TM][TN], const Epi &epi, int64_t row_w, int64_t M,
+                                              int vcol0, int c)
+{
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        typename Epi::template Aux<TN> aux[8];
+#pragma unroll
+        for (int rp = 0; rp < 8; ++rp) {
+            const int64_t row0 = row_w + i * 32 + 8 * (rp >> 1) + 2 * (rp & 1);
+            const bool ok0 = FULL || row0 < M, ok1 = FULL || row0 + 1 < M;
+            epi.template preload0<TN>(ok0 ? row0 : M - 1, ok1 ? row0 + 1 : M - 1, aux[rp]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int rp = 0; rp < 8; ++rp) {
+            const int64_t row0 = row_w + i * 32 + 8 * (rp >> 1) + 2 * (rp & 1);
+            const bool ok0 = FULL || row0 < M, ok1 = FULL || row0 + 1 < M;
+            epi.template preload<TN>(ok0 ? row0 : M - 1, ok1 ? row0 + 1 : M - 1, ok0, ok1, vcol0, c, aux[rp]);
+        }
+        __builtin_amdgcn_sched_barrier(0);                // keep the reads up here: sunk next to their uses they serialise
+#pragma unroll
+        for (int rp = 0; rp < 8; ++rp) {
+            const int r = 2 * rp;                         // registers r, r + 1: two consecutive rows
+            const int64_t row0 = row_w + i * 32 + 8 * (r >> 2) + (r & 3);
+            float v0[TN], v1[TN];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) { v0[j] = acc[i][j][r]; v1[j] = acc[i][j][r + 1]; }
+            epi.template rows2<TN>(row0, FULL || row0 < M, FULL || row0 + 1 < M, vcol0, c, v0, v1, aux[rp]);
+        }
+    }
+}
+
+#ifdef SOL_GEMM_TIMING
+__device__ unsigned long long *g_gemm_stamps;
+#define GT_STAMP(i) if (threadIdx.x == 0 && g_gemm_stamps) g_gemm_stamps[(size_t)blockIdx.x * 4 + (i)] = __builtin_readcyclecounter()
+#else
+#define GT_STAMP(i)
+#endif
+
 template <int BM, int BN, int WM, int WN, class Epi>
 __global__ void __launch_bounds__((BM / WM) * (BN / WN) * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
 k_gemm_mfma(const bf16_t *__restrict__ A, int64_t lda, BMap bmap, int64_t M, int Nv, int K, int tiles_m, int tiles_n,
@@ -183,24 +330,25 @@ k_gemm_mfma(const bf16_t *__restrict__ A, int64_t lda, BMap bmap, int64_t M, int
     const int n0 = tn * BN;
 
     // ---- per-thread global sources and LDS destinations of the staged K slices ----
+    // A pass covers ROWS_PER_PASS rows (8 threads x 16 bytes per 128-byte row). Sources are wave-uniform
+    // bases (scalar registers) plus one 32-bit lane offset each; the LDS swizzle does not depend on the
+    // pass (ROWS_PER_PASS is a multiple of 16), so one destination offset serves all passes.
+    static_assert(ROWS_PER_PASS % 16 == 0, "swizzle must repeat from pass to pass");
     const int chunk = tid & 7, r_in_pass = tid >> 3;
-    const bf16_t *a_src[A_PASSES];
-    const bf16_t *b_src[B_PASSES];
-    int a_dst[A_PASSES], b_dst[B_PASSES];
+    const bf16_t *const a_base = A + m0 * lda;              // uniform
+    uint32_t a_off[A_PASSES];
 #pragma unroll
     for (int p = 0; p < A_PASSES; ++p) {
-        const int rl = p * ROWS_PER_PASS + r_in_pass;
-        int64_t gr = m0 + rl;
-        if (gr >= M) gr = M - 1;                            // ragged last tile: re-read the last row, never stored
-        a_src[p] = A + gr * lda + chunk * 8;
-        a_dst[p] = rl * 128 + ((chunk ^ SOL_SWZ(rl)) << 4);
+        int64_t rl = p * ROWS_PER_PASS + r_in_pass;
+        if (m0 + rl >= M) rl = M - 1 - m0;                  // ragged last tile: re-read the last row, never stored
+        a_off[p] = (uint32_t)(rl * lda) + (uint32_t)(chunk * 8);
     }
+    const bf16_t *b_base[B_PASSES];                         // uniform: first weight row of each pass
 #pragma unroll
-    for (int p = 0; p < B_PASSES; ++p) {
-        const int rl = p * ROWS_PER_PASS + r_in_pass;
-        b_src[p] = bmap.row(n0 + rl) + chunk * 8;
-        b_dst[p] = BM * 128 + rl * 128 + ((chunk ^ SOL_SWZ(rl)) << 4);
-    }
+    for (int p = 0; p < B_PASSES; ++p) b_base[p] = bmap.row(n0 + p * ROWS_PER_PASS);
+    const uint32_t b_off = (uint32_t)r_in_pass * (uint32_t)bmap.ld + (uint32_t)(chunk * 8);
+    const int a_dst0 = r_in_pass * 128 + ((chunk ^ SOL_SWZ(r_in_pass)) << 4);
+    const int b_dst0 = BM * 128 + a_dst0;
 
     floatx16_t acc[TM][TN];
 #pragma unroll
@@ -210,93 +358,106 @@ k_gemm_mfma(const bf16_t *__restrict__ A, int64_t lda, BMap bmap, int64_t M, int
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // Software pipeline, three K slices deep: LDS holds slices kt and kt+1, one register set holds
-    // slice kt+2 (loaded one full iteration ago, so HBM latency is covered by two iterations of
-    // MFMAs), the other register set is being loaded with slice kt+3. One barrier per iteration:
-    // after it, slice kt's LDS stage is free and takes slice kt+2.
+    // Software pipeline, three K slices deep in memory and two fragment sets deep in registers.
+    // LDS holds slices kt and kt+1; one register set holds slice kt+2 (loaded two steps ago, so HBM
+    // latency is covered by two steps of MFMAs), the other is being loaded with slice kt+3. Inside a
+    // step the A/B fragments of k-group kk+1 are read from LDS while the MFMAs of k-group kk issue, and
+    // the single barrier of a step sits before its last k-group: after it the finished stage is
+    // overwritten with slice kt+2, the first fragments of the next stage are read and the next global
+    // loads are issued, all in the shadow of the last k-group's MFMAs.
     // (macros, not lambdas: register arrays captured by reference would be demoted to scratch)
     u32x4_t ra0[A_PASSES], rb0[B_PASSES], ra1[A_PASSES], rb1[B_PASSES];
+    bf16x8_t fa0[TM], fb0[TN], fa1[TM], fb1[TN];
     const int KT = K / BK;
 #define SOL_G_LOAD(RA, RB, KT_)                                                                            \
     {                                                                                                      \
         const int koff_ = ((KT_) < KT ? (KT_) : KT - 1) * BK; /* past the end: re-read the last slice */   \
         _Pragma("unroll") for (int p = 0; p < A_PASSES; ++p)                                               \
-            RA[p] = *reinterpret_cast<const u32x4_t *>(a_src[p] + koff_);                                  \
+            RA[p] = *reinterpret_cast<const u32x4_t *>(a_base + koff_ + a_off[p]);                         \
         _Pragma("unroll") for (int p = 0; p < B_PASSES; ++p)                                               \
-            RB[p] = *reinterpret_cast<const u32x4_t *>(b_src[p] + koff_);                                  \
+            RB[p] = *reinterpret_cast<const u32x4_t *>(b_base[p] + koff_ + b_off);                         \
     }
 #define SOL_L_STORE(RA, RB, STAGE_)                                                                        \
     {                                                                                                      \
         _Pragma("unroll") for (int p = 0; p < A_PASSES; ++p)                                               \
-            *reinterpret_cast<u32x4_t *>((STAGE_) + a_dst[p]) = RA[p];                                     \
+            *reinterpret_cast<u32x4_t *>((STAGE_) + a_dst0 + p * ROWS_PER_PASS * 128) = RA[p];             \
         _Pragma("unroll") for (int p = 0; p < B_PASSES; ++p)                                               \
-            *reinterpret_cast<u32x4_t *>((STAGE_) + b_dst[p]) = RB[p];                                     \
+            *reinterpret_cast<u32x4_t *>((STAGE_) + b_dst0 + p * ROWS_PER_PASS * 128) = RB[p];             \
     }
     // fragment read offsets (row = lane % 32 of the MFMA tile, k chunk = 2*kk + lane/32)
     const int frow = lane & 31, fk = lane >> 5, fsw = SOL_SWZ(frow);
     const int a_frag0 = (wm * WM + frow) * 128;
     const int b_frag0 = BM * 128 + (wn * WN + frow) * 128;
-#define SOL_COMPUTE(CUR_)                                                                                  \
-    _Pragma("unroll") for (int kk = 0; kk < BK / 16; ++kk)                                                 \
+#define SOL_F_READ(FA, FB, STAGE_, KK_)                                                                    \
     {                                                                                                      \
-        const int coff = (((kk * 2 + fk) ^ fsw) << 4);                                                     \
-        bf16x8_t af[TM], bfr[TN];                                                                          \
-        _Pragma("unroll") for (int i = 0; i < TM; ++i) af[i] = __builtin_bit_cast(                         \
-            bf16x8_t, *reinterpret_cast<const u32x4_t *>((CUR_) + a_frag0 + i * 32 * 128 + coff));         \
-        _Pragma("unroll") for (int j = 0; j < TN; ++j) bfr[j] = __builtin_bit_cast(                        \
-            bf16x8_t, *reinterpret_cast<const u32x4_t *>((CUR_) + b_frag0 + j * 32 * 128 + coff));         \
-        _Pragma("unroll") for (int i = 0; i < TM; ++i) _Pragma("unroll") for (int j = 0; j < TN; ++j)      \
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);        \
+        const int coff = ((((KK_) * 2 + fk) ^ fsw) << 4);                                                  \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i) FA[i] = __builtin_bit_cast(                         \
+            bf16x8_t, *reinterpret_cast<const u32x4_t *>((STAGE_) + a_frag0 + i * 32 * 128 + coff));       \
+        _Pragma("unroll") for (int j = 0; j < TN; ++j) FB[j] = __builtin_bit_cast(                         \
+            bf16x8_t, *reinterpret_cast<const u32x4_t *>((STAGE_) + b_frag0 + j * 32 * 128 + coff));       \
     }
+#define SOL_MMA(FA, FB)                                                                                    \
+    _Pragma("unroll") for (int i = 0; i < TM; ++i) _Pragma("unroll") for (int j = 0; j < TN; ++j)          \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(FA[i], FB[j], acc[i][j], 0, 0, 0);
+#define SOL_FENCE __builtin_amdgcn_sched_barrier(0)
+    // one step: CUR_ holds the slice being multiplied, NXT_ the next one; (RA, RB) holds the slice after that
+    // scheduling groups (in issue order): every LDS read of the next fragments, LDS write and global load
+    // rides in the issue shadow of an MFMA (a 32x32x16 MFMA keeps the matrix pipe busy for 32 cycles)
+#define SOL_ORDER_RM                                                                                       \
+    _Pragma("unroll") for (int i_ = 0; i_ < TM + TN; ++i_) {                                               \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                 \
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                                 \
+    }                                                                                                      \
+    __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - (TM + TN), 0);
+#define SOL_ORDER_TAIL                                                                                     \
+    _Pragma("unroll") for (int i_ = 0; i_ < TM * TN; ++i_) {                                               \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                 \
+        if (i_ < TM + TN) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                               \
+        __builtin_amdgcn_sched_group_barrier(0x200, (A_PASSES + B_PASSES + TM * TN - 1) / (TM * TN), 0);   \
+        __builtin_amdgcn_sched_group_barrier(0x020, (A_PASSES + B_PASSES + TM * TN - 1) / (TM * TN), 0);   \
+    }
+#define SOL_STEP(CUR_, NXT_, RA, RB, KT_LOAD_)                                                             \
+    SOL_F_READ(fa1, fb1, CUR_, 1); SOL_MMA(fa0, fb0); SOL_ORDER_RM; SOL_FENCE;                             \
+    SOL_F_READ(fa0, fb0, CUR_, 2); SOL_MMA(fa1, fb1); SOL_ORDER_RM; SOL_FENCE;                             \
+    SOL_F_READ(fa1, fb1, CUR_, 3); SOL_MMA(fa0, fb0); SOL_ORDER_RM; SOL_FENCE;                             \
+    __syncthreads();                                                                                       \
+    SOL_FENCE;                                                                                             \
+    SOL_F_READ(fa0, fb0, NXT_, 0); SOL_L_STORE(RA, RB, CUR_); SOL_G_LOAD(RA, RB, KT_LOAD_);                \
+    SOL_MMA(fa1, fb1); SOL_ORDER_TAIL; SOL_FENCE;
 
+    unsigned char *const stage0 = lds, *const stage1 = lds + STAGE_BYTES;
+    GT_STAMP(0);
     SOL_G_LOAD(ra0, rb0, 0);
     SOL_G_LOAD(ra1, rb1, 1);
-    SOL_L_STORE(ra0, rb0, lds);
-    SOL_L_STORE(ra1, rb1, lds + STAGE_BYTES);
+    SOL_L_STORE(ra0, rb0, stage0);
+    SOL_L_STORE(ra1, rb1, stage1);
     SOL_G_LOAD(ra0, rb0, 2);
+    SOL_G_LOAD(ra1, rb1, 3);
     __syncthreads();
+    SOL_F_READ(fa0, fb0, stage0, 0);
+    GT_STAMP(1);
     for (int kt = 0; kt < KT; kt += 2) {                    // KT is even (K is a multiple of 128)
-        // even step: stage 0 holds slice kt; set 0 holds slice kt+2; load slice kt+3 into set 1
-        SOL_G_LOAD(ra1, rb1, kt + 3);
-        SOL_COMPUTE(lds);
-        __syncthreads();
-        SOL_L_STORE(ra0, rb0, lds);
-        // odd step: stage 1 holds slice kt+1; set 1 holds slice kt+3; load slice kt+4 into set 0
-        SOL_G_LOAD(ra0, rb0, kt + 4);
-        SOL_COMPUTE(lds + STAGE_BYTES);
-        __syncthreads();
-        SOL_L_STORE(ra1, rb1, lds + STAGE_BYTES);
+        SOL_STEP(stage0, stage1, ra0, rb0, kt + 4);
+        SOL_STEP(stage1, stage0, ra1, rb1, kt + 5);
     }
     __syncthreads();
+    GT_STAMP(2);
 #undef SOL_G_LOAD
 #undef SOL_L_STORE
-#undef SOL_COMPUTE
+#undef SOL_F_READ
+#undef SOL_MMA
+#undef SOL_STEP
+#undef SOL_ORDER_RM
+#undef SOL_ORDER_TAIL
+#undef SOL_FENCE
 
-    // ---- epilogue: 32 rows x WN columns per wave at a time through LDS ----
-    constexpr int LROW = WN + 4;                           // padded fp32 row
-    float *stage = reinterpret_cast<float *>(lds) + (size_t)wave * 32 * LROW;
-    constexpr int LPR = WN / 4;                            // lanes per row when each lane takes 4 columns
-    constexpr int RPP = 64 / LPR;                          // rows per pass
-    const int e_row = lane / LPR, e_col = (lane - e_row * LPR) * 4;
+    // ---- epilogue straight from the accumulators (tiles that lie wholly inside the matrix take the
+    // version without row checks) ----
     const int vcol0 = n0 + wn * WN;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        __syncthreads();
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int rr = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                stage[rr * LROW + j * 32 + (lane & 31)] = acc[i][j][r];
-            }
-        __syncthreads();
-#pragma unroll
-        for (int ps = 0; ps < 32 / RPP; ++ps) {
-            const int rr = ps * RPP + e_row;
-            const int64_t grow = m0 + wm * WM + i * 32 + rr;
-            if (grow < M) epi.template apply<WN>(grow, vcol0, e_col, stage + rr * LROW);
-        }
-    }
+    const int64_t row_w = m0 + wm * WM + 4 * (lane >> 5);
+    if (m0 + BM <= M) gemm_epilogue<true, TM, TN>(acc, epi, row_w, M, vcol0, lane & 31);
+    else gemm_epilogue<false, TM, TN>(acc, epi, row_w, M, vcol0, lane & 31);
+    GT_STAMP(3);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -309,9 +470,7 @@ static bool launch_mfma(const bf16_t *A, int64_t lda, const BMap &bmap, int64_t 
     if (M <= 0) return true;
     if (Nv % BN || K % (2 * BK) || K < 2 * BK) return false;
     constexpr int NT = (BM / WM) * (BN / WN) * 64;
-    constexpr size_t lds_main = 2 * (size_t)(BM + BN) * 128;
-    constexpr size_t lds_epi = (size_t)(NT / 64) * 32 * (WN + 4) * 4;
-    constexpr size_t lds = lds_main > lds_epi ? lds_main : lds_epi;
+    constexpr size_t lds = 2 * (size_t)(BM + BN) * 128;
     auto kern = k_gemm_mfma<BM, BN, WM, WN, Epi>;
     static bool attr_done = false;
     if (!attr_done) {
@@ -327,24 +486,35 @@ static bool launch_mfma(const bf16_t *A, int64_t lda, const BMap &bmap, int64_t 
     return true;
 }
 
-// Tile configurations of the fused layer GEMMs: 256 x 256 workgroup tiles, 8 waves (two per SIMD, so
-// one wave's LDS / barrier waits hide under the other's MFMAs). Wave tile 128 x 64 measured fastest;
-// the q/k/v epilogue needs a whole head (up to 128 columns) inside one wave tile, hence 64 x 128.
-#define SOL_TILE 256, 256, 128, 64
-#define SOL_TILE_QKV 256, 256, 64, 128
+// Tile configuration of the fused layer GEMMs: 256 x 256 workgroup tiles, 4 waves (one per SIMD) with
+// 128 x 128 wave tiles: 256 accumulator registers per lane, the smallest LDS read traffic per MFMA
+// (128 KB per K slice), and latency hidden by the software pipeline rather than by a second wave.
+// The q/k/v epilogue needs a whole head (up to 128 columns) inside one wave tile.
+constexpr int SOL_WN = 128;
+#define SOL_TILE 256, 256, 128, SOL_WN
+#define SOL_TILE_QKV 256, 256, 128, SOL_WN
 
 bool launch_gemm_qkv_rope(const void *h, const void *wq, const void *wk, const void *wv, void *q, void *kc, void *vc,
                           const float2 *rope, const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv, int dh,
-                          int d, int *flags, hipStream_t st)
+                          int d, int *flags, void *row_sp_ws, hipStream_t st)
 {
     const int nq = Hq * dh, nkv = Hkv * dh;
-    if (dh > 128 || 128 % dh || nq % 256 || nkv % 256) return false;      // heads must not straddle wave tiles
+    if ((dh != 64 && dh != 128) || nq % 256 || nkv % 256) return false;      // heads must not straddle wave tiles
+    const int64_t M = (int64_t)n_seq * T;
+    if (M <= 0) return true;
+    if (d % (2 * BK) || d < 2 * BK) return false;
     BMap bm{};
     bm.base[0] = (const bf16_t *)wq; bm.base[1] = (const bf16_t *)wk; bm.base[2] = (const bf16_t *)wv;
     bm.seg_end[0] = nq; bm.seg_end[1] = nq + nkv; bm.seg_end[2] = nq + 2 * nkv;
     bm.mode = 0; bm.half = 0; bm.ld = d;
-    EpiQkvRope epi{(bf16_t *)q, (bf16_t *)kc, (bf16_t *)vc, rope, pos0, T, L_max, Hq, Hkv, dh, flags};
-    return launch_mfma<SOL_TILE_QKV>((const bf16_t *)h, d, bm, (int64_t)n_seq * T, nq + 2 * nkv, d, epi, st);
+    int2 *row_sp = (int2 *)row_sp_ws;
+    hipLaunchKernelGGL(k_row_positions, dim3((unsigned)((M + 255) / 256)), dim3(256), 0, st, pos0, M, T, L_max, row_sp, flags);
+    if (dh == 64) {
+        EpiQkvRope<64> epi{(bf16_t *)q, (bf16_t *)kc, (bf16_t *)vc, rope, row_sp, L_max, Hq, Hkv};
+        return launch_mfma<SOL_TILE_QKV>((const bf16_t *)h, d, bm, M, nq + 2 * nkv, d, epi, st);
+    }
+    EpiQkvRope<128> epi{(bf16_t *)q, (bf16_t *)kc, (bf16_t *)vc, rope, row_sp, L_max, Hq, Hkv};
+    return launch_mfma<SOL_TILE_QKV>((const bf16_t *)h, d, bm, M, nq + 2 * nkv, d, epi, st);
 }
 
 bool launch_gemm_resid_f32(const void *a, const void *w, const void *resid, float *out, int64_t M, int N, int K,
@@ -359,9 +529,9 @@ bool launch_gemm_resid_f32(const void *a, const void *w, const void *resid, floa
 bool launch_gemm_gateup_silu(const void *h, const void *wg, const void *wu, void *a, int64_t M, int dff, int d,
                              hipStream_t st)
 {
-    if (dff % 128) return false;
+    if (dff % (SOL_WN / 2)) return false;
     BMap bm{};
-    bm.base[0] = (const bf16_t *)wg; bm.base[1] = (const bf16_t *)wu; bm.mode = 1; bm.half = 32; bm.ld = d;   // half = WN / 2
+    bm.base[0] = (const bf16_t *)wg; bm.base[1] = (const bf16_t *)wu; bm.mode = 1; bm.half = SOL_WN / 2; bm.ld = d;
     EpiSiluMul epi{(bf16_t *)a, dff};
     return launch_mfma<SOL_TILE>((const bf16_t *)h, d, bm, M, 2 * dff, d, epi, st);
 }

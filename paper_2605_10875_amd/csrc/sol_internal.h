@@ -68,10 +68,11 @@ void launch_gemm_generic(const void *A, int a_dtype, int64_t lda, const void *W,
 // ---- bf16 MFMA GEMMs with fused epilogues (sol_gemm_mfma.hip) -----------------------------------
 // Each returns false (and launches nothing) if the shape is outside what the tile configuration
 // covers; the caller then takes the generic path for that stage.
-// q/k/v projections + rotary + q store + K/V cache write.  h: [M][d] bf16.
+// q/k/v projections + rotary + q store + K/V cache write.  h: [M][d] bf16. row_sp_ws: 8 bytes per row of
+// scratch for the rows' (sequence, position).
 bool launch_gemm_qkv_rope(const void *h, const void *wq, const void *wk, const void *wv, void *q, void *kc, void *vc,
                           const float2 *rope, const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv, int dh,
-                          int d, int *flags, hipStream_t st);
+                          int d, int *flags, void *row_sp_ws, hipStream_t st);
 // out(fp32)[M][N] = resid(bf16)[M][N] + a[M][K] * w[N][K]^T
 bool launch_gemm_resid_f32(const void *a, const void *w, const void *resid, float *out, int64_t M, int N, int K,
                            hipStream_t st);
