@@ -351,7 +351,8 @@ static void prepare_actions(sol_ctx *ctx, const int32_t *ids, int64_t M, LayerWs
 {
     STAGE(ctx, ST_PREPARE, st);
     launch_prepare_rows(ids, ctx->d_table, ctx->n_actions, ctx->cfg.d_ff, M, w.ra, w.row_bucket, ctx->d_flags, st);
-    launch_bucket_sort(w.row_bucket, M, ctx->n_buckets, w.perm, w.bucket_off, st);
+    if (prune_fq_wants_order(ctx->cfg.dtype, ctx->cfg.d_ff))
+        launch_bucket_sort(w.row_bucket, M, ctx->n_buckets, w.perm, w.bucket_off, st);
 }
 
 // Launch sequence of one decoder layer (actions already decoded into w.ra / w.perm).

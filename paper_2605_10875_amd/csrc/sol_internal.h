@@ -41,6 +41,8 @@ void launch_silu_mul(const float *gu32, void *a, int dtype, int64_t M, int dff, 
 // Rows are visited in bucket order through perm (NULL = identity).
 void launch_prune_fq(void *a, int dtype, const RowAct *ra, const int32_t *perm, bool quant, int64_t M, int dff,
                      hipStream_t st);
+// whether launch_prune_fq uses perm for this type / width (if not, the bucket sort can be skipped)
+bool prune_fq_wants_order(int dtype, int dff);
 // out = x2 + z
 void launch_resid_out(const float *x2, const float *z, void *out, int dtype, int64_t M, int d, hipStream_t st,
                       int nsplit = 1);

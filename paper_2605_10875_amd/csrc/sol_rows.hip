@@ -155,6 +155,111 @@ k_rmsnorm_fq(const TX *__restrict__ x, const float *__restrict__ add, int nsplit
     for (int j = tid; j < d; j += ROW_BLOCK) st(hr + j, row[j]);
 }
 
+// One wave per row, the row in registers (d = CH * 512: lane l holds elements [c*512 + 8*l, +8) of every chunk
+// c), 16-byte accesses, reductions on DPP: the layer's bf16 pass, where x is bf16 (layer input) or fp32 (the
+// residual stream inside the layer), the gain and the output are bf16 and there is nothing to add.
+typedef uint32_t u32x4_w __attribute__((ext_vector_type(4)));
+typedef float f32x4_w __attribute__((ext_vector_type(4)));
+
+template <typename TX, int CH>
+__global__ void __launch_bounds__(256)
+k_rmsnorm_fq_wave(const TX *__restrict__ x, const bf16_t *__restrict__ w, bf16_t *__restrict__ h,
+                  const RowAct *__restrict__ ra, int quant, int64_t M, float eps)
+{
+    constexpr int D = CH * 512;
+    const int lane = threadIdx.x & 63;
+    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= M) return;                                      // whole wave
+    float v[CH][8];
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        if constexpr (sizeof(TX) == 2) {
+            const u32x4_w t = *reinterpret_cast<const u32x4_w *>(x + r * D + c * 512 + lane * 8);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { v[c][2 * e] = __uint_as_float(t[e] << 16); v[c][2 * e + 1] = __uint_as_float(t[e] & 0xFFFF0000u); }
+        } else {
+            const f32x4_w t0 = *reinterpret_cast<const f32x4_w *>(x + r * D + c * 512 + lane * 8);
+            const f32x4_w t1 = *reinterpret_cast<const f32x4_w *>(x + r * D + c * 512 + lane * 8 + 4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { v[c][e] = t0[e]; v[c][4 + e] = t1[e]; }
+        }
+    }
+    float ss = 0.f;
+#pragma unroll
+    for (int c = 0; c < CH; ++c)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ss += v[c][e] * v[c][e];
+    ss = wave_sum_dpp(ss);
+    const float rinv = 1.0f / sqrtf(ss / (float)D + eps);
+    float amax = 0.f;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        const u32x4_w t = *reinterpret_cast<const u32x4_w *>(w + c * 512 + lane * 8);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            v[c][2 * e] = v[c][2 * e] * rinv * __uint_as_float(t[e] << 16);
+            v[c][2 * e + 1] = v[c][2 * e + 1] * rinv * __uint_as_float(t[e] & 0xFFFF0000u);
+            amax = fmaxf(amax, fmaxf(fabsf(v[c][2 * e]), fabsf(v[c][2 * e + 1])));
+        }
+    }
+    const int bits = (quant && ra) ? ra[r].bits : 16;
+    if (bits < 16) {
+        amax = __uint_as_float(wave_max_u32(__float_as_uint(amax)));     // non-negative floats order like their bits
+        if (amax > 0.f) {
+            const float qmax = fq_qmax(bits), s = amax / qmax;
+#pragma unroll
+            for (int c = 0; c < CH; ++c)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[c][e] = fq_code(v[c][e], s, qmax) * s;
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        u32x4_w o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = pack_bf16x2(v[c][2 * e], v[c][2 * e + 1]);
+        *reinterpret_cast<u32x4_w *>(h + r * D + c * 512 + lane * 8) = o;
+    }
+}
+
+// the same layout for the row-wise fake-quantiser of an fp32 matrix into bf16
+template <int CH>
+__global__ void __launch_bounds__(256)
+k_fq_rows_wave(const float *__restrict__ in, bf16_t *__restrict__ out, const RowAct *__restrict__ ra, int quant, int64_t M)
+{
+    constexpr int D = CH * 512;
+    const int lane = threadIdx.x & 63;
+    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= M) return;
+    float v[CH][8];
+    float amax = 0.f;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        const f32x4_w t0 = *reinterpret_cast<const f32x4_w *>(in + r * D + c * 512 + lane * 8);
+        const f32x4_w t1 = *reinterpret_cast<const f32x4_w *>(in + r * D + c * 512 + lane * 8 + 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { v[c][e] = t0[e]; v[c][4 + e] = t1[e]; amax = fmaxf(amax, fmaxf(fabsf(t0[e]), fabsf(t1[e]))); }
+    }
+    const int bits = (quant && ra) ? ra[r].bits : 16;
+    if (bits < 16) {
+        amax = __uint_as_float(wave_max_u32(__float_as_uint(amax)));
+        if (amax > 0.f) {
+            const float qmax = fq_qmax(bits), s = amax / qmax;
+#pragma unroll
+            for (int c = 0; c < CH; ++c)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[c][e] = fq_code(v[c][e], s, qmax) * s;
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        u32x4_w o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = pack_bf16x2(v[c][2 * e], v[c][2 * e + 1]);
+        *reinterpret_cast<u32x4_w *>(out + r * D + c * 512 + lane * 8) = o;
+    }
+}
+
 template <typename TX, typename TW, typename TH>
 static void rmsnorm_dispatch3(const void *x, const float *add, int nsplit, float *xsum, const void *w, void *h,
                               const RowAct *ra, bool quant, int64_t M, int d, float eps, hipStream_t st)
@@ -167,6 +272,16 @@ void launch_rmsnorm_fq(const void *x, int x_dtype, const float *add, float *xsum
                        int h_dtype, const RowAct *ra, bool quant, int64_t M, int d, float eps, hipStream_t st, int nsplit)
 {
     if (M <= 0) return;
+    if (!add && !xsum && w_dtype == 1 && h_dtype == 1 && nsplit == 1 && (d == 2048 || d == 4096)) {
+        const dim3 grid((unsigned)((M + 3) / 4));
+#define SOL_NORM_WAVE(TX, CH)                                                                                   \
+    hipLaunchKernelGGL((k_rmsnorm_fq_wave<TX, CH>), grid, dim3(256), 0, st, (const TX *)x, (const bf16_t *)w,  \
+                       (bf16_t *)h, ra, quant ? 1 : 0, M, eps)
+        if (x_dtype == 1) { if (d == 2048) SOL_NORM_WAVE(bf16_t, 4); else SOL_NORM_WAVE(bf16_t, 8); }
+        else { if (d == 2048) SOL_NORM_WAVE(float, 4); else SOL_NORM_WAVE(float, 8); }
+#undef SOL_NORM_WAVE
+        return;
+    }
     const int key = (x_dtype << 2) | (w_dtype << 1) | h_dtype;
     switch (key) {
     case 0: rmsnorm_dispatch3<float, float, float>(x, add, nsplit, xsum, w, h, ra, quant, M, d, eps, st); break;
@@ -207,6 +322,12 @@ void launch_fq_rows(const float *in, void *out, int out_dtype, const RowAct *ra,
                     hipStream_t st)
 {
     if (M <= 0) return;
+    if (out_dtype == 1 && (n == 2048 || n == 4096)) {
+        const dim3 grid((unsigned)((M + 3) / 4));
+        if (n == 2048) hipLaunchKernelGGL((k_fq_rows_wave<4>), grid, dim3(256), 0, st, in, (bf16_t *)out, ra, quant ? 1 : 0, M);
+        else hipLaunchKernelGGL((k_fq_rows_wave<8>), grid, dim3(256), 0, st, in, (bf16_t *)out, ra, quant ? 1 : 0, M);
+        return;
+    }
     if (out_dtype == 0)
         hipLaunchKernelGGL((k_fq_rows<float>), dim3((unsigned)M), dim3(ROW_BLOCK), 0, st, in, (float *)out, ra,
                            quant ? 1 : 0, n);
@@ -375,14 +496,16 @@ typedef uint32_t u32x4_r __attribute__((ext_vector_type(4)));
 typedef short i16x2_r __attribute__((ext_vector_type(2)));
 
 template <int CHUNKS>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(64)
 k_prune_fq_wave(bf16_t *__restrict__ a, const RowAct *__restrict__ ra, const int32_t *__restrict__ perm, int quant,
                 int64_t M)
 {
     constexpr int DFF = CHUNKS * 512;
-    const int lane = threadIdx.x & 63;
-    const int64_t slot = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (slot >= M) return;                                   // whole wave
+    // one wave per workgroup: rows of different actions take different numbers of search steps, and a
+    // workgroup's slot is only freed when its slowest wave is done
+    const int lane = threadIdx.x;
+    const int64_t slot = blockIdx.x;
+    if (slot >= M) return;
     const int64_t r = perm ? perm[slot] : slot;
     const RowAct act = ra[r];
     const int bits = __builtin_amdgcn_readfirstlane(quant ? act.bits : 16);
@@ -473,15 +596,27 @@ k_prune_fq_wave(bf16_t *__restrict__ a, const RowAct *__restrict__ ra, const int
     for (int c = 0; c < CHUNKS; ++c) *reinterpret_cast<u32x4_r *>(ar + (c * 64 + lane) * 8) = d[c];
 }
 
+static bool prune_wave_case(int dtype, int dff)
+{
+    if (dtype != 1 || dff % 512) return false;
+    const int c = dff / 512;
+    return c == 2 || c == 4 || c == 8 || c == 16 || c == 22 || c == 28;
+}
+
+// The one-row-per-workgroup kernel wants rows of one action next to each other (workgroups of a CU then
+// run the same number of search steps); the one-row-per-wave kernel has no use for the order.
+bool prune_fq_wants_order(int dtype, int dff) { return !prune_wave_case(dtype, dff); }
+
 void launch_prune_fq(void *a, int dtype, const RowAct *ra, const int32_t *perm, bool quant, int64_t M, int dff,
                      hipStream_t st)
 {
     if (M <= 0) return;
-    if (dtype == 1 && dff % 512 == 0) {
-        const dim3 grid((unsigned)((M + 3) / 4));
+    if (prune_wave_case(dtype, dff)) {
+        perm = nullptr;
+        const dim3 grid((unsigned)M);
 #define SOL_PRUNE_CASE(C)                                                                                       \
     case C:                                                                                                     \
-        hipLaunchKernelGGL((k_prune_fq_wave<C>), grid, dim3(256), 0, st, (bf16_t *)a, ra, perm, quant ? 1 : 0, M); \
+        hipLaunchKernelGGL((k_prune_fq_wave<C>), grid, dim3(64), 0, st, (bf16_t *)a, ra, perm, quant ? 1 : 0, M); \
         return;
         switch (dff / 512) {
             SOL_PRUNE_CASE(2) SOL_PRUNE_CASE(4) SOL_PRUNE_CASE(8) SOL_PRUNE_CASE(16) SOL_PRUNE_CASE(22)
