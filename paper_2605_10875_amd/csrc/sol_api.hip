@@ -520,8 +520,11 @@ static int nll_impl(sol_ctx *ctx, const sol_model_weights *mw, const void *x, in
         const int64_t rows = (M - r0 < chunk) ? M - r0 : chunk;
         {
             STAGE(ctx, ST_LMHEAD, st);
-            launch_gemm_generic((const char *)w.hf + es * r0 * g.d_model, dt, g.d_model, mw->lm_head, dt, g.d_model,
-                                w.logits, g.vocab, rows, g.vocab, g.d_model, st);
+            const void *hf = (const char *)w.hf + es * r0 * g.d_model;
+            // bf16 with a vocabulary that tiles: MFMA GEMM with a plain fp32 store; otherwise the generic kernel
+            if (!(dt == SOL_BF16 && launch_gemm_f32(hf, mw->lm_head, w.logits, g.vocab, rows, g.vocab, g.d_model, st)))
+                launch_gemm_generic(hf, dt, g.d_model, mw->lm_head, dt, g.d_model, w.logits, g.vocab, rows, g.vocab,
+                                    g.d_model, st);
         }
         {
             STAGE(ctx, ST_NLL, st);

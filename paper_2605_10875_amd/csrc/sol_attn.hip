@@ -738,7 +738,32 @@ k_attn_decode(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int kvh = blockIdx.x, s = blockIdx.y;
+    const int kvh = blockIdx.x;
+    // Longest sequences first: workgroups are handed to compute units in launch order, one per CU, so with
+    // mixed cache lengths the last round would otherwise wait for a long row that started late. Every
+    // workgroup ranks the (few) sequences itself; row blockIdx.y of the grid serves the sequence of that rank.
+    int s = blockIdx.y;
+    {
+        __shared__ int s_len[DEC_BLOCK];
+        __shared__ int s_pick;
+        const int nb = gridDim.y;
+        if (nb <= DEC_BLOCK) {
+            const int my_len = tid < nb ? cache_len[tid] : 0;
+            s_len[tid] = my_len;
+            __syncthreads();
+            if (tid < nb) {
+                int rank = 0;
+                for (int j = 0; j < nb; ++j) {
+                    const int lj = s_len[j];
+                    rank += (lj > my_len || (lj == my_len && j < tid)) ? 1 : 0;
+                }
+                if (rank == (int)blockIdx.y) s_pick = tid;
+            }
+            __syncthreads();
+            s = s_pick;
+        }
+    }
+    s = __builtin_amdgcn_readfirstlane(s);
     const int p0 = __builtin_amdgcn_readfirstlane(cache_len[s]);
     if (p0 < 0 || p0 + 1 > L_max) {
         if (tid == 0) atomicOr(flags, FLAG_CACHE_OVERFLOW);

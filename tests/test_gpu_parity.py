@@ -213,8 +213,9 @@ def test_bf16_decode_step(shape, B, L, dup):
     ctx.close()
 
 
-def test_bf16_schedule_loglik_determinism_and_parity():
-    shape, table = SMALL_GQA, synth.TABLE_C2
+@pytest.mark.parametrize("vocab", [1000, 1024])            # 1024 tiles: the LM head runs on the MFMA GEMM
+def test_bf16_schedule_loglik_determinism_and_parity(vocab):
+    shape, table = dataclasses.replace(SMALL_GQA, vocab=vocab), synth.TABLE_C2
     layers, head = _stack(shape, 4000, True)
     B, G, T = 2, 3, 48
     tokens, targets = synth.tokens_and_targets(B, T, shape.vocab, 4001)
