@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the action-conditioned decoder-layer path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c5|c4|c5d]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c5|c4|c5d]
 
 A step is one pass of the measured unit over one batch of seeded synthetic input that is already
 resident in HBM. Default workload: the Llama-3.2-1B-shaped decoder layer, 4 inputs x 8 schedules
@@ -143,6 +143,58 @@ def run_layer(args, shape, n_inputs, G, T, table, name):
     return res
 
 
+def run_stack(args, shape, B, G, T, table, name):
+    """Full stack + LM head + NLL (sol_schedule_loglik). Weights are drawn on the GPU (2.5 GB of them)."""
+    gen = torch.Generator(device="cuda").manual_seed(args.seed)
+
+    def rnd(*sz, std=0.02, mean=0.0):
+        return (torch.randn(sz, generator=gen, device="cuda") * std + mean).to(torch.bfloat16)
+
+    d, hq, hkv, dh, dff = shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_ff
+    layers = [{"w_in_norm": rnd(d, std=0.1, mean=1.0), "wq": rnd(hq * dh, d), "wk": rnd(hkv * dh, d),
+               "wv": rnd(hkv * dh, d), "wo": rnd(d, hq * dh), "w_post_norm": rnd(d, std=0.1, mean=1.0),
+               "w_gate": rnd(dff, d), "w_up": rnd(dff, d), "w_down": rnd(d, dff)} for _ in range(shape.n_layers)]
+    head = {"embed": rnd(shape.vocab, d), "w_final_norm": rnd(d, std=0.1, mean=1.0), "lm_head": rnd(shape.vocab, d)}
+    tokens, targets = synth.tokens_and_targets(B, T, shape.vocab, args.seed + 1)
+    ids = synth.markov_actions(len(table), B * G, T, args.seed + 2).reshape(B, G, T)
+    ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=T)
+    tk, tg, idd = _dev(tokens), _dev(targets), _dev(ids)
+    nll = torch.empty((B, G, T), dtype=torch.float32, device="cuda")
+    ws = ctx.workspace(sol.OP_SCHEDULE_LOGLIK, B * G, T, T)
+
+    def step():
+        ctx.schedule_loglik(layers, head, tk, tg, idd, nll_out=nll, workspace=ws)
+
+    sec = time_steps(step, args.steps, args.warmup)
+    assert ctx.device_status() == sol.OK and bool(torch.isfinite(nll).all())
+    stages, launches = stage_times(ctx, step, 2)
+    tokens_n = B * G * T
+    pos = np.tile(np.arange(T), (B * G, 1))
+    fl = layer_flops(shape, table, ids.reshape(B * G, T), pos)
+    alg = shape.n_layers * (fl["linear_dense"] + fl["down"] + fl["qk"] + fl["pv"]) + 2.0 * d * shape.vocab * tokens_n
+    dom = "gate_up_gemm"
+    dom_flops = 4.0 * d * dff * tokens_n                             # per launch (one layer)
+    per_launch_ms = stages[dom] / max(1, launches.get(dom, shape.n_layers))
+    ach = dom_flops / (per_launch_ms * 1e-3) / 1e12
+    res = {
+        "metric": "schedule_tokens_per_s", "value": tokens_n / sec, "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": name, "entry_point": "sol_schedule_loglik", "n_inputs": B, "schedules": G, "seq_len": T,
+                   "layers": shape.n_layers, "vocab": shape.vocab, "tokens_per_step": tokens_n,
+                   "actions": "Markov chain over %d actions, stay-probability 0.8" % len(table)},
+        "roofline": {"bound": "mfma", "kernel": dom, "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": ach / PEAK_BF16_TFLOPS, "traffic": None, "kernel_ms": per_launch_ms,
+                     "launches_per_step": launches.get(dom)},
+        "stack": {"algorithmic_tflop": alg / 1e12, "algorithmic_tflops": alg / sec / 1e12,
+                  "algorithmic_frac_of_peak": alg / sec / 1e12 / PEAK_BF16_TFLOPS,
+                  "mean_nll_nats": float(nll.mean()), "log_vocab": float(np.log(shape.vocab))},
+        "stage_ms": {k: round(v, 4) for k, v in stages.items()},
+    }
+    ctx.close()
+    return res
+
+
 def run_decode(args, shape, B, L, table, name, n_layers):
     import dataclasses
     shape = dataclasses.replace(shape, n_layers=n_layers)
@@ -233,7 +285,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c2", choices=["c2", "c5", "c4", "c5d"])
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c5", "c4", "c5d"])
     ap.add_argument("--seed", type=int, default=1234)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -249,6 +301,11 @@ def main():
     if args.workload == "c2":
         res = run_layer(args, synth.LLAMA_1B, 4, 8, 1024, synth.TABLE_C2,
                         "C2: Llama-3.2-1B-shaped decoder layer, bf16, 4 inputs x 8 schedules x 1024 tokens")
+    elif args.workload == "c3":
+        import dataclasses
+        shape = dataclasses.replace(synth.LLAMA_1B, n_layers=16, vocab=128256)
+        res = run_stack(args, shape, 2, 8, 2048, synth.TABLE_C2,
+                        "C3: Llama-3.2-1B-shaped 16-layer stack + LM head + NLL, bf16, 2 inputs x 8 schedules x 2048 tokens")
     elif args.workload == "c5":
         res = run_layer(args, synth.LLAMA_8B, 2, 4, 4096, synth.TABLE_C2,
                         "C5: Llama-3.1-8B-shaped decoder layer, bf16, 2 inputs x 4 schedules x 4096 tokens")

@@ -324,7 +324,10 @@ static void carve_stack(Carver &c, const sol_model_cfg &g, int64_t n_seq, int64_
     const size_t cache = own_cache ? es * n_seq * g.n_kv_heads * T * g.head_dim : 0;
     w.kc = c.take(cache);
     w.vc = c.take(cache);
-    w.logits = (float *)c.take(4 * lm_chunk_rows(g, M) * (size_t)(g.vocab > 0 ? g.vocab : 1));
+    size_t head_bytes = 4 * lm_chunk_rows(g, M) * (size_t)(g.vocab > 0 ? g.vocab : 1);          // a chunk of logits rows
+    if (g.dtype == SOL_BF16 && g.vocab > 0 && g.vocab % 256 == 0 && gemm_nll_scratch_bytes(M, g.vocab) > head_bytes)
+        head_bytes = gemm_nll_scratch_bytes(M, g.vocab);                                         // fused LM head + NLL
+    w.logits = (float *)c.take(head_bytes);
 }
 
 extern "C" size_t sol_workspace_bytes(const sol_model_cfg *cfg, int op, int n_seq, int T, int L_max)
@@ -514,17 +517,19 @@ static int nll_impl(sol_ctx *ctx, const sol_model_weights *mw, const void *x, in
         STAGE(ctx, ST_NORM_FINAL, st);
         launch_rmsnorm_fq(x, dt, nullptr, nullptr, mw->w_final_norm, dt, w.hf, dt, nullptr, false, M, g.d_model, g.rms_eps, st);
     }
+    bool fused = false;
+    if (dt == SOL_BF16) {   // logits stay on chip: per-tile (max, sum of exponentials), folded per row afterwards
+        STAGE(ctx, ST_LMHEAD, st);
+        fused = launch_gemm_nll(w.hf, mw->lm_head, targets, G, T, broadcast_g, nll_out, w.logits, M, g.vocab, g.d_model, st);
+    }
     const int64_t chunk = lm_chunk_rows(g, M);
     const size_t es = esize(dt);
-    for (int64_t r0 = 0; r0 < M; r0 += chunk) {
+    for (int64_t r0 = 0; !fused && r0 < M; r0 += chunk) {
         const int64_t rows = (M - r0 < chunk) ? M - r0 : chunk;
         {
             STAGE(ctx, ST_LMHEAD, st);
-            const void *hf = (const char *)w.hf + es * r0 * g.d_model;
-            // bf16 with a vocabulary that tiles: MFMA GEMM with a plain fp32 store; otherwise the generic kernel
-            if (!(dt == SOL_BF16 && launch_gemm_f32(hf, mw->lm_head, w.logits, g.vocab, rows, g.vocab, g.d_model, st)))
-                launch_gemm_generic(hf, dt, g.d_model, mw->lm_head, dt, g.d_model, w.logits, g.vocab, rows, g.vocab,
-                                    g.d_model, st);
+            launch_gemm_generic((const char *)w.hf + es * r0 * g.d_model, dt, g.d_model, mw->lm_head, dt, g.d_model,
+                                w.logits, g.vocab, rows, g.vocab, g.d_model, st);
         }
         {
             STAGE(ctx, ST_NLL, st);

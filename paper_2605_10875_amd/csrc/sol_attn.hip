@@ -1131,7 +1131,7 @@ bool launch_attn_tile(const void *q, const void *k_cache, const void *v_cache, v
                   : launch_attn_select_t<BQ, SL, 128, 8>(q, k_cache, sel, ra, pos0, n_seq, T, L_max, Hq, Hkv, st)
     if (L_max <= 256) { SOL_SEL(32, 4); }
     else if (L_max <= 1024) { SOL_SEL(16, 16); }
-    else if (L_max <= 2048) { SOL_SEL(16, 32); }
+    else if (L_max <= 2048) { SOL_SEL(8, 32); }
     else { SOL_SEL(8, 64); }
 #undef SOL_SEL
     if (!ok) return false;

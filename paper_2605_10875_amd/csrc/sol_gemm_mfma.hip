@@ -258,6 +258,92 @@ k_row_positions(const int32_t *__restrict__ pos0, int64_t M, int Tn, int L_max, 
     row_sp[row] = make_int2(s, bad ? -1 : p0 + i);
 }
 
+// LM head with the logits never written: per (row, 128-column wave tile) the maximum and the sum of
+// exp(logit - maximum), and the target's logit where the tile holds it; k_nll_finish folds the tiles of a
+// row into  logsumexp(logits) - logits[target]  (Method, Eq. 1, negated).
+template <class Op> __device__ __forceinline__ float reduce32(float v, Op op)
+{
+    // lanes 0..31 and 32..63 hold different rows: reduce within each half, result in every lane of the half
+    v = op(v, SOL_DPP(float, v, v, 0xB1, 0xF));     // quad_perm [1,0,3,2]
+    v = op(v, SOL_DPP(float, v, v, 0x4E, 0xF));     // quad_perm [2,3,0,1]
+    v = op(v, SOL_DPP(float, v, v, 0x141, 0xF));    // row_half_mirror
+    v = op(v, SOL_DPP(float, v, v, 0x140, 0xF));    // row_mirror
+    v = op(v, __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F)));   // lane ^ 16
+    return v;
+}
+struct OpMaxF { __device__ __forceinline__ float operator()(float a, float b) const { return fmaxf(a, b); } };
+
+struct AuxTgt { int t0, t1; };
+
+struct EpiNllPart {
+    float2 *part;               // [M][n_wt]
+    float *tgt_logit;           // [M]
+    const int32_t *row_tgt;     // [M] target token of each row, inside [0, V)
+    int n_wt;
+    template <int TN> using Aux = AuxTgt;
+    template <int TN> __device__ __forceinline__ void preload0(int64_t row0, int64_t row1, AuxTgt &x) const
+    {
+        x.t0 = row_tgt[row0];
+        x.t1 = row_tgt[row1];
+    }
+    template <int TN> __device__ __forceinline__ void preload(int64_t, int64_t, bool, bool, int, int, AuxTgt &) const {}
+    template <int TN>
+    __device__ __forceinline__ void one_row(int64_t row, bool ok, int vcol0, int c, const float (&v)[TN], int tg) const
+    {
+        float mx = v[0];
+#pragma unroll
+        for (int j = 1; j < TN; ++j) mx = fmaxf(mx, v[j]);
+        mx = reduce32(mx, OpMaxF());
+        float se = 0.f;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) se += __expf(v[j] - mx);
+        se = reduce32(se, OpAddF());
+        if (ok && c == 0) part[row * n_wt + vcol0 / (TN * 32)] = make_float2(mx, se);
+        const int rel = tg - vcol0;                     // the target's column inside this wave tile, if any
+        if (ok && rel >= 0 && rel < TN * 32 && (rel & 31) == c) {
+            float t = v[0];
+#pragma unroll
+            for (int j = 1; j < TN; ++j) t = (rel >> 5) == j ? v[j] : t;
+            tgt_logit[row] = t;
+        }
+    }
+    template <int TN>
+    __device__ __forceinline__ void rows2(int64_t row0, bool ok0, bool ok1, int vcol0, int c, const float (&v0)[TN],
+                                          const float (&v1)[TN], const AuxTgt &x) const
+    {
+        one_row<TN>(row0, ok0, vcol0, c, v0, x.t0);
+        one_row<TN>(row0 + 1, ok1, vcol0, c, v1, x.t1);
+    }
+};
+
+// target token of every row (teacher-forced rows (b, g, t) share the targets of input b when broadcast_g)
+__global__ void __launch_bounds__(256)
+k_row_targets(const int32_t *__restrict__ targets, int64_t M, int G, int Tn, int broadcast_g, int V, int32_t *__restrict__ row_tgt)
+{
+    const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (r >= M) return;
+    const int64_t ti = broadcast_g ? (r / ((int64_t)G * Tn)) * Tn + (r % Tn) : r;
+    int tg = targets[ti];
+    row_tgt[r] = tg < 0 ? 0 : (tg >= V ? V - 1 : tg);
+}
+
+// one wave per row: nll = max + log(sum_t s_t * exp(m_t - max)) - target logit
+__global__ void __launch_bounds__(256)
+k_nll_finish(const float2 *__restrict__ part, const float *__restrict__ tgt_logit, int n_wt, int64_t M, float *__restrict__ nll)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= M) return;
+    const float2 *p = part + r * n_wt;
+    float mx = -INFINITY;
+    for (int t = lane; t < n_wt; t += 64) mx = fmaxf(mx, p[t].x);
+    mx = wave_reduce_dpp<float>(mx, -INFINITY, OpMaxF());
+    float se = 0.f;
+    for (int t = lane; t < n_wt; t += 64) { const float2 q = p[t]; se += q.y * expf(q.x - mx); }
+    se = wave_sum_dpp(se);
+    if (lane == 0) nll[r] = (mx + logf(se)) - tgt_logit[r];
+}
+
 // Register r of accumulator tile (i, j) is row 32*i + 8*(r/4) + 4*(lane/32) + r%4, column 32*j + lane%32
 // of the wave tile (row_w already holds the wave tile's first row + 4*(lane/32)). Per 32-row tile all
 // global reads of the epilogue are issued first, then the row pairs are combined and stored.
@@ -553,6 +639,29 @@ bool launch_gemm_f32(const void *a, const void *w, float *C, int64_t ldc, int64_
     return launch_mfma<SOL_TILE>((const bf16_t *)a, K, bm, M, N, K, epi, st);
 }
 
+
+size_t gemm_nll_scratch_bytes(int64_t M, int V) { return (size_t)M * ((size_t)(V / SOL_WN) * sizeof(float2) + 8); }
+
+// nll[r] = logsumexp(hf[r] . lm_head^T) - (hf[r] . lm_head[target(r)]) without materialising the logits.
+// scratch: gemm_nll_scratch_bytes(M, V) bytes. Returns false (nothing launched) if the shape does not tile.
+bool launch_gemm_nll(const void *hf, const void *lm_head, const int32_t *targets, int G, int T, bool broadcast_g,
+                     float *nll, void *scratch, int64_t M, int V, int K, hipStream_t st)
+{
+    if (M <= 0) return true;
+    if (V % 256 || K % (2 * BK) || K < 2 * BK) return false;
+    const int n_wt = V / SOL_WN;
+    float2 *part = (float2 *)scratch;
+    float *tgt_logit = (float *)(part + (size_t)M * n_wt);
+    int32_t *row_tgt = (int32_t *)(tgt_logit + M);
+    hipLaunchKernelGGL(k_row_targets, dim3((unsigned)((M + 255) / 256)), dim3(256), 0, st, targets, M, G, T,
+                       broadcast_g ? 1 : 0, V, row_tgt);
+    BMap bm{};
+    bm.base[0] = (const bf16_t *)lm_head; bm.seg_end[0] = bm.seg_end[1] = bm.seg_end[2] = V; bm.mode = 0; bm.ld = K;
+    EpiNllPart epi{part, tgt_logit, row_tgt, n_wt};
+    if (!launch_mfma<SOL_TILE>((const bf16_t *)hf, K, bm, M, V, K, epi, st)) return false;
+    hipLaunchKernelGGL(k_nll_finish, dim3((unsigned)((M + 3) / 4)), dim3(256), 0, st, part, tgt_logit, n_wt, M, nll);
+    return true;
+}
 
 // =================================================================================================
 // Skinny GEMM for the decode step: out[M][Nv] = x[M][K] * Wv[Nv][K]^T with M <= 64 tokens.
