@@ -602,40 +602,49 @@ k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf1
         for (int dt = 0; dt < DT; ++dt) oacc[qt][dt] = floatx4_a{0.f, 0.f, 0.f, 0.f};
 
     // staging: global -> registers -> LDS, one chunk ahead
-    u32x4_a kreg[K_PIECES], vreg[V_PIECES];
-#define SOL_PV_GLOAD(CH_)                                                                                  \
+    u32x4_a kreg0[K_PIECES], vreg0[V_PIECES], kreg1[K_PIECES], vreg1[V_PIECES];
+#define SOL_PV_GLOAD(KR, VR, CH_)                                                                                  \
     {                                                                                                      \
         const int key0_ = (CH_) * KC;                                                                      \
         _Pragma("unroll") for (int i = 0; i < K_PIECES; ++i) {                                             \
             const int pc = i * NT + tid, row = pc / KP, piece = pc - row * KP;                             \
             int key = key0_ + row;                                                                         \
             if (key >= n_max) key = n_max - 1;              /* never used unmasked: beyond every row */     \
-            kreg[i] = *reinterpret_cast<const u32x4_a *>(kbase + (int64_t)key * DH + piece * 8);           \
+            KR[i] = *reinterpret_cast<const u32x4_a *>(kbase + (int64_t)key * DH + piece * 8);             \
         }                                                                                                  \
         _Pragma("unroll") for (int i = 0; i < V_PIECES; ++i) {                                             \
             const int pc = i * NT + tid, d = pc >> 3, piece = pc & 7;                                      \
-            vreg[i] = *reinterpret_cast<const u32x4_a *>(vbase + (int64_t)d * lpadv + key0_ + piece * 8);  \
+            VR[i] = *reinterpret_cast<const u32x4_a *>(vbase + (int64_t)d * lpadv + key0_ + piece * 8);    \
         }                                                                                                  \
     }
-#define SOL_PV_LSTORE(STG_)                                                                                \
+#define SOL_PV_LSTORE(KR, VR, STG_)                                                                                \
     {                                                                                                      \
         unsigned char *kb_ = pvl + (STG_) * STAGE, *vb_ = kb_ + K_BYTES;                                   \
         _Pragma("unroll") for (int i = 0; i < K_PIECES; ++i) {                                             \
             const int pc = i * NT + tid, row = pc / KP, piece = pc - row * KP;                             \
-            *reinterpret_cast<u32x4_a *>(kb_ + row * (DH * 2) + ((piece ^ pv_swz_k<DH>(row)) << 4)) = kreg[i]; \
+            *reinterpret_cast<u32x4_a *>(kb_ + row * (DH * 2) + ((piece ^ pv_swz_k<DH>(row)) << 4)) = KR[i]; \
         }                                                                                                  \
         _Pragma("unroll") for (int i = 0; i < V_PIECES; ++i) {                                             \
             const int pc = i * NT + tid, d = pc >> 3, piece = pc & 7;                                      \
-            *reinterpret_cast<u32x4_a *>(vb_ + d * (KC * 2) + ((piece ^ ((d >> 1) & 7)) << 4)) = vreg[i];  \
+            *reinterpret_cast<u32x4_a *>(vb_ + d * (KC * 2) + ((piece ^ ((d >> 1) & 7)) << 4)) = VR[i];    \
         }                                                                                                  \
     }
 
-    SOL_PV_GLOAD(0);
-    SOL_PV_LSTORE(0);
+    // chunk ch is multiplied out of LDS stage ch % 2 while chunk ch + 1 (fetched one iteration ago) moves from
+    // registers into the other stage and chunk ch + 2 is fetched: global latency has a whole iteration to hide in
+    SOL_PV_GLOAD(kreg0, vreg0, 0);
+    SOL_PV_LSTORE(kreg0, vreg0, 0);
+    if (1 < n_chunks) SOL_PV_GLOAD(kreg1, vreg1, 1);
     __syncthreads();
     for (int ch = 0; ch < n_chunks; ++ch) {
         const int stg = ch & 1;
-        if (ch + 1 < n_chunks) SOL_PV_GLOAD(ch + 1);
+        if (stg == 0) {
+            if (ch + 1 < n_chunks) SOL_PV_LSTORE(kreg1, vreg1, 1);
+            if (ch + 2 < n_chunks) SOL_PV_GLOAD(kreg0, vreg0, ch + 2);
+        } else {
+            if (ch + 1 < n_chunks) SOL_PV_LSTORE(kreg0, vreg0, 0);
+            if (ch + 2 < n_chunks) SOL_PV_GLOAD(kreg1, vreg1, ch + 2);
+        }
         const unsigned char *kb = pvl + stg * STAGE, *vb = kb + K_BYTES;
 #pragma unroll
         for (int cc = 0; cc < 2; ++cc) {
@@ -682,7 +691,6 @@ k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf1
                 }
             }
         }
-        if (ch + 1 < n_chunks) SOL_PV_LSTORE(stg ^ 1);
         __syncthreads();
     }
 #undef SOL_PV_GLOAD
