@@ -161,9 +161,10 @@ k_rmsnorm_fq(const TX *__restrict__ x, const float *__restrict__ add, int nsplit
 typedef uint32_t u32x4_w __attribute__((ext_vector_type(4)));
 typedef float f32x4_w __attribute__((ext_vector_type(4)));
 
-template <typename TX, int CH>
+template <typename TX, int CH, bool ADD>
 __global__ void __launch_bounds__(256)
-k_rmsnorm_fq_wave(const TX *__restrict__ x, const bf16_t *__restrict__ w, bf16_t *__restrict__ h,
+k_rmsnorm_fq_wave(const TX *__restrict__ x, const float *__restrict__ add, int nsplit, int64_t split_stride,
+                  float *__restrict__ xsum, const bf16_t *__restrict__ w, bf16_t *__restrict__ h,
                   const RowAct *__restrict__ ra, int quant, int64_t M, float eps)
 {
     constexpr int D = CH * 512;
@@ -182,6 +183,23 @@ k_rmsnorm_fq_wave(const TX *__restrict__ x, const bf16_t *__restrict__ w, bf16_t
             const f32x4_w t1 = *reinterpret_cast<const f32x4_w *>(x + r * D + c * 512 + lane * 8 + 4);
 #pragma unroll
             for (int e = 0; e < 4; ++e) { v[c][e] = t0[e]; v[c][4 + e] = t1[e]; }
+        }
+    }
+    if constexpr (ADD) {                                     // x + K-split partial sums (folded in split order), kept as xsum
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            float t[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            for (int sp = 0; sp < nsplit; ++sp) {
+                const float *ap = add + sp * split_stride + r * D + c * 512 + lane * 8;
+                const f32x4_w a0 = *reinterpret_cast<const f32x4_w *>(ap), a1 = *reinterpret_cast<const f32x4_w *>(ap + 4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { t[e] += a0[e]; t[4 + e] += a1[e]; }
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[c][e] += t[e];
+            float *xp = xsum + r * D + c * 512 + lane * 8;
+            *reinterpret_cast<f32x4_w *>(xp) = f32x4_w{v[c][0], v[c][1], v[c][2], v[c][3]};
+            *reinterpret_cast<f32x4_w *>(xp + 4) = f32x4_w{v[c][4], v[c][5], v[c][6], v[c][7]};
         }
     }
     float ss = 0.f;
@@ -272,13 +290,18 @@ void launch_rmsnorm_fq(const void *x, int x_dtype, const float *add, float *xsum
                        int h_dtype, const RowAct *ra, bool quant, int64_t M, int d, float eps, hipStream_t st, int nsplit)
 {
     if (M <= 0) return;
-    if (!add && !xsum && w_dtype == 1 && h_dtype == 1 && nsplit == 1 && (d == 2048 || d == 4096)) {
+    if (w_dtype == 1 && h_dtype == 1 && (d == 2048 || d == 4096) && (add != nullptr) == (xsum != nullptr)) {
         const dim3 grid((unsigned)((M + 3) / 4));
+        const int64_t ss = M * (int64_t)d;
 #define SOL_NORM_WAVE(TX, CH)                                                                                   \
-    hipLaunchKernelGGL((k_rmsnorm_fq_wave<TX, CH>), grid, dim3(256), 0, st, (const TX *)x, (const bf16_t *)w,  \
-                       (bf16_t *)h, ra, quant ? 1 : 0, M, eps)
-        if (x_dtype == 1) { if (d == 2048) SOL_NORM_WAVE(bf16_t, 4); else SOL_NORM_WAVE(bf16_t, 8); }
-        else { if (d == 2048) SOL_NORM_WAVE(float, 4); else SOL_NORM_WAVE(float, 8); }
+    if (add)                                                                                                    \
+        hipLaunchKernelGGL((k_rmsnorm_fq_wave<TX, CH, true>), grid, dim3(256), 0, st, (const TX *)x, add, nsplit, ss, \
+                           xsum, (const bf16_t *)w, (bf16_t *)h, ra, quant ? 1 : 0, M, eps);                    \
+    else                                                                                                        \
+        hipLaunchKernelGGL((k_rmsnorm_fq_wave<TX, CH, false>), grid, dim3(256), 0, st, (const TX *)x, add, nsplit, ss, \
+                           xsum, (const bf16_t *)w, (bf16_t *)h, ra, quant ? 1 : 0, M, eps)
+        if (x_dtype == 1) { if (d == 2048) { SOL_NORM_WAVE(bf16_t, 4); } else { SOL_NORM_WAVE(bf16_t, 8); } }
+        else { if (d == 2048) { SOL_NORM_WAVE(float, 4); } else { SOL_NORM_WAVE(float, 8); } }
 #undef SOL_NORM_WAVE
         return;
     }
@@ -340,7 +363,7 @@ void launch_fq_rows(const float *in, void *out, int out_dtype, const RowAct *ra,
 // rotary embedding (rotate-half pairs (c, c + dh/2)) and scatter of q, k, v
 // ------------------------------------------------------------------------------------------------
 template <typename T>
-__global__ void __launch_bounds__(ROW_BLOCK)
+__global__ void __launch_bounds__(256)
 k_rope_store(const float *__restrict__ qkv, int nsplit, int64_t split_stride, T *__restrict__ q, T *__restrict__ kc,
              T *__restrict__ vc, const float2 *__restrict__ rope, const int32_t *__restrict__ pos0, int Tn, int L_max,
              int Hq, int Hkv, int dh, int *flags)
@@ -350,37 +373,31 @@ k_rope_store(const float *__restrict__ qkv, int nsplit, int64_t split_stride, T 
         for (int sp = 0; sp < nsplit; ++sp) t += p[sp * split_stride];
         return t;
     };
+    // grid: (row, head slot) with head slots 0..Hq-1 = q heads, then the K heads, then the V heads; a
+    // workgroup of dh / 2 threads handles one head of one row, so all loads of a row are in flight at once
     const int64_t r = blockIdx.x;
+    const int slot = blockIdx.y;
     const int s = (int)(r / Tn), i = (int)(r % Tn);
     const int p0 = pos0 ? pos0[s] : 0;
     if (p0 < 0 || p0 + Tn > L_max) {
-        if (threadIdx.x == 0) atomicOr(flags, FLAG_CACHE_OVERFLOW);
+        if (threadIdx.x == 0 && slot == 0) atomicOr(flags, FLAG_CACHE_OVERFLOW);
         return;
     }
     const int pos = p0 + i, half = dh >> 1;
     const int ncol = (Hq + 2 * Hkv) * dh;
-    const float *in = qkv + r * ncol;
-    const float2 *cs = rope + (int64_t)pos * half;
-    for (int idx = threadIdx.x; idx < Hq * half; idx += ROW_BLOCK) {
-        const int hh = idx / half, c = idx - hh * half;
-        const float x0 = val(in + hh * dh + c), x1 = val(in + hh * dh + c + half);
-        const float2 t = cs[c];
-        st(q + r * (int64_t)(Hq * dh) + hh * dh + c, x0 * t.x - x1 * t.y);
-        st(q + r * (int64_t)(Hq * dh) + hh * dh + c + half, x1 * t.x + x0 * t.y);
-    }
-    const float *kin = in + Hq * dh;
-    const float *vin = kin + Hkv * dh;
-    for (int idx = threadIdx.x; idx < Hkv * half; idx += ROW_BLOCK) {
-        const int hh = idx / half, c = idx - hh * half;
-        const float x0 = val(kin + hh * dh + c), x1 = val(kin + hh * dh + c + half);
-        const float2 t = cs[c];
-        T *dst = kc + (((int64_t)s * Hkv + hh) * L_max + pos) * dh;
+    const float *in = qkv + r * ncol + (int64_t)slot * dh;
+    const int c = threadIdx.x;                             // < half
+    if (slot < Hq + Hkv) {                                 // q or k head: rotate the pair (c, c + half)
+        const float x0 = val(in + c), x1 = val(in + c + half);
+        const float2 t = rope[(int64_t)pos * half + c];
+        T *dst = slot < Hq ? q + r * (int64_t)(Hq * dh) + slot * dh
+                           : kc + (((int64_t)s * Hkv + (slot - Hq)) * L_max + pos) * dh;
         st(dst + c, x0 * t.x - x1 * t.y);
         st(dst + c + half, x1 * t.x + x0 * t.y);
-    }
-    for (int idx = threadIdx.x; idx < Hkv * dh; idx += ROW_BLOCK) {
-        const int hh = idx / dh, c = idx - hh * dh;
-        st(vc + (((int64_t)s * Hkv + hh) * L_max + pos) * dh + c, val(vin + idx));
+    } else {
+        T *dst = vc + (((int64_t)s * Hkv + (slot - Hq - Hkv)) * L_max + pos) * dh;
+        st(dst + c, val(in + c));
+        st(dst + c + half, val(in + c + half));
     }
 }
 
@@ -392,10 +409,10 @@ void launch_rope_store(const float *qkv32, void *q, void *k_cache, void *v_cache
     if (M <= 0) return;
     const int64_t ss = M * (int64_t)((Hq + 2 * Hkv) * dh);
     if (dtype == 0)
-        hipLaunchKernelGGL((k_rope_store<float>), dim3((unsigned)M), dim3(ROW_BLOCK), 0, st, qkv32, nsplit, ss, (float *)q,
+        hipLaunchKernelGGL((k_rope_store<float>), dim3((unsigned)M, Hq + 2 * Hkv), dim3(dh / 2), 0, st, qkv32, nsplit, ss, (float *)q,
                            (float *)k_cache, (float *)v_cache, rope, pos0, T, L_max, Hq, Hkv, dh, flags);
     else
-        hipLaunchKernelGGL((k_rope_store<bf16_t>), dim3((unsigned)M), dim3(ROW_BLOCK), 0, st, qkv32, nsplit, ss, (bf16_t *)q,
+        hipLaunchKernelGGL((k_rope_store<bf16_t>), dim3((unsigned)M, Hq + 2 * Hkv), dim3(dh / 2), 0, st, qkv32, nsplit, ss, (bf16_t *)q,
                            (bf16_t *)k_cache, (bf16_t *)v_cache, rope, pos0, T, L_max, Hq, Hkv, dh, flags);
 }
 
@@ -495,31 +512,49 @@ k_prune_fq(T *__restrict__ a, const RowAct *__restrict__ ra, const int32_t *__re
 typedef uint32_t u32x4_r __attribute__((ext_vector_type(4)));
 typedef short i16x2_r __attribute__((ext_vector_type(2)));
 
-template <int CHUNKS>
-__global__ void __launch_bounds__(64)
+// NWV waves share a row (NWV = 1: one wave per row, for many rows; NWV = 4: a workgroup per row, for the few
+// rows of a decode step, where the latency of one row's search is what counts). Wave v holds chunks
+// [v * CW, (v + 1) * CW) of 512 channels each; counts are combined through LDS.
+template <int CHUNKS, int NWV>
+__global__ void __launch_bounds__(64 * NWV)
 k_prune_fq_wave(bf16_t *__restrict__ a, const RowAct *__restrict__ ra, const int32_t *__restrict__ perm, int quant,
                 int64_t M)
 {
-    constexpr int DFF = CHUNKS * 512;
-    // one wave per workgroup: rows of different actions take different numbers of search steps, and a
-    // workgroup's slot is only freed when its slowest wave is done
-    const int lane = threadIdx.x;
+    constexpr int DFF = CHUNKS * 512, CW = CHUNKS / NWV;
+    static_assert(CHUNKS % NWV == 0, "chunks must split evenly over the waves");
+    __shared__ uint32_t s_x[2][NWV];                         // per-wave partial results, double-buffered
+    const int lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t slot = blockIdx.x;
     if (slot >= M) return;
     const int64_t r = perm ? perm[slot] : slot;
     const RowAct act = ra[r];
     const int bits = __builtin_amdgcn_readfirstlane(quant ? act.bits : 16);
     const int m = __builtin_amdgcn_readfirstlane(act.m);
-    if (m >= DFF && bits >= 16) return;                      // dense bucket: the row is already final
-    bf16_t *ar = a + r * DFF;
-    u32x4_r d[CHUNKS];
+    if (m >= DFF && bits >= 16) return;                      // dense bucket: the row is already final (whole workgroup)
+    bf16_t *ar = a + r * DFF + (int64_t)wv * CW * 512;
+    u32x4_r d[CW];
 #pragma unroll
-    for (int c = 0; c < CHUNKS; ++c) d[c] = *reinterpret_cast<const u32x4_r *>(ar + (c * 64 + lane) * 8);
+    for (int c = 0; c < CW; ++c) d[c] = *reinterpret_cast<const u32x4_r *>(ar + (c * 64 + lane) * 8);
+    int xpar = 0;
+    // sum (or maximum) of a wave-uniform value over the waves of the row
+#define SOL_ROW_COMBINE(V_, IS_MAX_)                                                                       \
+    if constexpr (NWV > 1) {                                                                               \
+        if (lane == 0) s_x[xpar][wv] = (V_);                                                               \
+        __syncthreads();                                                                                   \
+        uint32_t t_ = 0u;                                                                                  \
+        _Pragma("unroll") for (int i_ = 0; i_ < NWV; ++i_) {                                               \
+            const uint32_t y_ = s_x[xpar][i_];                                                             \
+            t_ = (IS_MAX_) ? (y_ > t_ ? y_ : t_) : t_ + y_;                                                \
+        }                                                                                                  \
+        (V_) = (uint32_t)__builtin_amdgcn_readfirstlane((int)t_);                                          \
+        xpar ^= 1;                                                                                         \
+    }
 
     // largest magnitude key of the row
     uint32_t kmax = 0u;
 #pragma unroll
-    for (int c = 0; c < CHUNKS; ++c)
+    for (int c = 0; c < CW; ++c)
 #pragma unroll
         for (int wi = 0; wi < 4; ++wi) {
             const uint32_t k2 = d[c][wi] & 0x7FFF7FFFu;
@@ -528,6 +563,7 @@ k_prune_fq_wave(bf16_t *__restrict__ a, const RowAct *__restrict__ ra, const int
             kmax = hi16 > kmax ? hi16 : kmax;
         }
     kmax = wave_max_u32(kmax);
+    SOL_ROW_COMBINE(kmax, true);
 
     if (m < DFF) {
         // invariant: count(key >= lo) >= m, count(key >= hi + 1) < m
@@ -537,29 +573,46 @@ k_prune_fq_wave(bf16_t *__restrict__ a, const RowAct *__restrict__ ra, const int
             const uint32_t mid2 = mid | (mid << 16);
             uint32_t below = 0u;                             // keys < mid held by this lane
 #pragma unroll
-            for (int c = 0; c < CHUNKS; ++c)
+            for (int c = 0; c < CW; ++c)
 #pragma unroll
                 for (int wi = 0; wi < 4; ++wi) {
                     const i16x2_r diff = __builtin_bit_cast(i16x2_r, d[c][wi] & 0x7FFF7FFFu) - __builtin_bit_cast(i16x2_r, mid2);
                     below += __popc(__builtin_bit_cast(uint32_t, diff) & 0x80008000u);
                 }
-            const int cnt = DFF - (int)wave_reduce_dpp<uint32_t>(below, 0u, [](uint32_t x, uint32_t y) { return x + y; });
+            uint32_t below_row = wave_reduce_dpp<uint32_t>(below, 0u, [](uint32_t x, uint32_t y) { return x + y; });
+            SOL_ROW_COMBINE(below_row, false);
+            const int cnt = DFF - (int)below_row;
             if (cnt >= m) lo = mid; else hi = mid - 1u;
         }
         const uint32_t thr = lo, thr2 = thr | (thr << 16);
         // keys above the threshold, then ties in channel order until the quota is used up
-        uint32_t above = 0u;
+        uint32_t above = 0u, ties = 0u;
 #pragma unroll
-        for (int c = 0; c < CHUNKS; ++c)
+        for (int c = 0; c < CW; ++c)
 #pragma unroll
             for (int wi = 0; wi < 4; ++wi) {
-                const i16x2_r diff = __builtin_bit_cast(i16x2_r, thr2) - __builtin_bit_cast(i16x2_r, d[c][wi] & 0x7FFF7FFFu);
+                const uint32_t k2 = d[c][wi] & 0x7FFF7FFFu;
+                const i16x2_r diff = __builtin_bit_cast(i16x2_r, thr2) - __builtin_bit_cast(i16x2_r, k2);
                 above += __popc(__builtin_bit_cast(uint32_t, diff) & 0x80008000u);      // thr < key
+                if constexpr (NWV > 1) ties += ((k2 & 0xFFFFu) == thr) + ((k2 >> 16) == thr);
             }
-        int quota = m - (int)wave_reduce_dpp<uint32_t>(above, 0u, [](uint32_t x, uint32_t y) { return x + y; });
+        uint32_t above_row = wave_reduce_dpp<uint32_t>(above, 0u, [](uint32_t x, uint32_t y) { return x + y; });
+        SOL_ROW_COMBINE(above_row, false);
+        int quota = m - (int)above_row;
+        if constexpr (NWV > 1) {                             // ties held by the waves before this one come first
+            const uint32_t ties_w = wave_reduce_dpp<uint32_t>(ties, 0u, [](uint32_t x, uint32_t y) { return x + y; });
+            if (lane == 0) s_x[xpar][wv] = ties_w;
+            __syncthreads();
+            int before_w = 0;
+#pragma unroll
+            for (int i = 0; i < NWV; ++i) before_w += i < wv ? (int)s_x[xpar][i] : 0;
+            xpar ^= 1;
+            quota -= __builtin_amdgcn_readfirstlane(before_w);
+            if (quota < 0) quota = 0;
+        }
         const unsigned long long lt_mask = (1ull << lane) - 1ull;
 #pragma unroll
-        for (int c = 0; c < CHUNKS; ++c) {
+        for (int c = 0; c < CW; ++c) {
             int before = 0, total = 0;                       // ties in lower lanes / in the whole chunk
             bool tie[8];
 #pragma unroll
@@ -581,11 +634,12 @@ k_prune_fq_wave(bf16_t *__restrict__ a, const RowAct *__restrict__ ra, const int
             quota = quota > total ? quota - total : 0;
         }
     }
+#undef SOL_ROW_COMBINE
     if (bits < 16 && kmax != 0u) {
         const float qmax = fq_qmax(bits);
         const float s = __uint_as_float(kmax << 16) / qmax;  // the largest magnitude is always kept
 #pragma unroll
-        for (int c = 0; c < CHUNKS; ++c)
+        for (int c = 0; c < CW; ++c)
 #pragma unroll
             for (int wi = 0; wi < 4; ++wi) {
                 const float v0 = __uint_as_float(d[c][wi] << 16), v1 = __uint_as_float(d[c][wi] & 0xFFFF0000u);
@@ -593,7 +647,7 @@ k_prune_fq_wave(bf16_t *__restrict__ a, const RowAct *__restrict__ ra, const int
             }
     }
 #pragma unroll
-    for (int c = 0; c < CHUNKS; ++c) *reinterpret_cast<u32x4_r *>(ar + (c * 64 + lane) * 8) = d[c];
+    for (int c = 0; c < CW; ++c) *reinterpret_cast<u32x4_r *>(ar + (c * 64 + lane) * 8) = d[c];
 }
 
 static bool prune_wave_case(int dtype, int dff)
@@ -614,9 +668,12 @@ void launch_prune_fq(void *a, int dtype, const RowAct *ra, const int32_t *perm, 
     if (prune_wave_case(dtype, dff)) {
         perm = nullptr;
         const dim3 grid((unsigned)M);
+        const bool few = M <= 512 && (dff / 512) % 4 == 0;  // a decode step: four waves per row
 #define SOL_PRUNE_CASE(C)                                                                                       \
     case C:                                                                                                     \
-        hipLaunchKernelGGL((k_prune_fq_wave<C>), grid, dim3(64), 0, st, (bf16_t *)a, ra, perm, quant ? 1 : 0, M); \
+        if (few) hipLaunchKernelGGL((k_prune_fq_wave<C, (C % 4 == 0 ? 4 : 1)>), grid, dim3(C % 4 == 0 ? 256 : 64), 0, st, \
+                                    (bf16_t *)a, ra, perm, quant ? 1 : 0, M);                                   \
+        else hipLaunchKernelGGL((k_prune_fq_wave<C, 1>), grid, dim3(64), 0, st, (bf16_t *)a, ra, perm, quant ? 1 : 0, M); \
         return;
         switch (dff / 512) {
             SOL_PRUNE_CASE(2) SOL_PRUNE_CASE(4) SOL_PRUNE_CASE(8) SOL_PRUNE_CASE(16) SOL_PRUNE_CASE(22)

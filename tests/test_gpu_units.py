@@ -81,21 +81,20 @@ def test_quant_codes_bit_exact(n):
         assert np.array_equal(zhat[r], o), r
 
 
-@pytest.mark.parametrize("n,dtype", [(1024, "bf16"), (8192, "bf16"), (14336, "bf16"), (11264, "bf16"), (768, "bf16"),
-                                     (1024, "f32"), (8192, "f32")])
-def test_prune_quant_kernel_bit_exact(n, dtype):
+@pytest.mark.parametrize("n,dtype,rows", [(1024, "bf16", 24), (8192, "bf16", 24), (8192, "bf16", 600), (14336, "bf16", 24),
+                                          (11264, "bf16", 24), (768, "bf16", 24), (1024, "f32", 24), (8192, "f32", 24)])
+def test_prune_quant_kernel_bit_exact(n, dtype, rows):
     """The production prune + quantise kernel (wave-per-row for bf16 rows of 512*k channels, workgroup
     radix select otherwise) against oracle top-m mask -> fake-quant -> storage rounding."""
     from paper_2605_10875_amd import synth
-    rng = np.random.default_rng(n)
-    rows = 24
+    rng = np.random.default_rng(n)                                   # up to 512 rows: four waves per row; more: one
     a = (rng.standard_normal((rows, n)) * rng.standard_normal((rows, n))).astype(np.float32) * 0.4
     a[3] = np.round(a[3] * 2) / 2                                   # few distinct values, many exact zeros
     a[4] = 0.0
     if dtype == "bf16":
         a = synth.round_to_bf16(a)
-    m = np.array([max(1, int(np.ceil(f * n))) for f in (1, .75, .5, .25, .5, .125)] * 4, np.int32)
-    bits = np.array([16] * 6 + [8] * 6 + [6] * 6 + [4] * 6, np.int32)
+    m = np.array([max(1, int(np.ceil(f * n))) for f in (1, .75, .5, .25, .5, .125)] * (rows // 6), np.int32)
+    bits = np.repeat(np.array([16, 8, 6, 4], np.int32), rows // 4)
     m[6] = n                                                        # quantise only
     t = dev(a).to(torch.bfloat16) if dtype == "bf16" else dev(a)
     out = host(sol.prune_quant(t, dev(m), dev(bits)))
