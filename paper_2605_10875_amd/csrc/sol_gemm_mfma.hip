@@ -699,7 +699,36 @@ k_gemm_skinny(const bf16_t *__restrict__ x, int64_t ldx, BMap bmap, int M, int N
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
 
-    for (int kc = k_begin; kc < k_end; kc += SK_KC) {
+    // The split's K range is walked in 64-wide blocks, UK blocks per batch, two batches per LDS chunk of
+    // activations. Weight loads run one batch ahead of the MFMAs (two register sets), and the first batch
+    // of a chunk is already in flight while the chunk's activations are staged, so a workgroup pays the
+    // global-memory latency about once instead of once per batch.
+    constexpr int UK = 4;                                             // 64-wide K blocks per batch
+    static_assert(SK_KC == 2 * UK * 64, "two batches per staged chunk");
+    const int nblk = (k_end - k_begin) / 64;
+    u32x4_t wa0[UK][4], wa1[UK][4];
+#define SOL_SK_LOADW(WA, B0_)                                                                              \
+    _Pragma("unroll") for (int u = 0; u < UK; ++u) {                                                       \
+        const int blk_ = ((B0_) + u < nblk) ? (B0_) + u : nblk - 1;     /* ragged tail: re-read, not used */ \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                      \
+            WA[u][j] = *reinterpret_cast<const u32x4_t *>(wrow + k_begin + blk_ * 64 + j * 8);             \
+    }
+#define SOL_SK_MMA(WA, B0_, KOFF_)          /* KOFF_: offset of the batch inside the staged chunk */          \
+    _Pragma("unroll") for (int u = 0; u < UK; ++u) {                                                       \
+        if ((B0_) + u < nblk) {                                                                            \
+            _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                \
+                const bf16x8_t af = __builtin_bit_cast(bf16x8_t, WA[u][j]);                                \
+                _Pragma("unroll") for (int t = 0; t < MT; ++t) {                                           \
+                    const unsigned char *xp = xs + (t * 32 + r) * SK_XROW + ((KOFF_) + u * 64 + h * 32 + j * 8) * 2; \
+                    const bf16x8_t bfr = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t *>(xp)); \
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfr, acc[t], 0, 0, 0);            \
+                }                                                                                          \
+            }                                                                                              \
+        }                                                                                                  \
+    }
+    if (live) SOL_SK_LOADW(wa0, 0);
+    for (int b0 = 0; b0 < nblk; b0 += 2 * UK) {
+        const int kc = k_begin + b0 * 64;
         const int kw = (k_end - kc < SK_KC) ? (k_end - kc) : SK_KC;   // multiple of 64
         __syncthreads();                                              // previous chunk fully consumed
         // stage x[0..MT*32)[kc .. kc+kw) into LDS, 16 bytes per thread per step (rows >= M: zeros)
@@ -712,34 +741,14 @@ k_gemm_skinny(const bf16_t *__restrict__ x, int64_t ldx, BMap bmap, int M, int N
         }
         __syncthreads();
         if (live) {
-            constexpr int UK = 4;                                       // 64-wide K blocks in flight per wave
-            for (int kb = 0; kb < kw; kb += 64 * UK) {
-                u32x4_t wa[UK][4];
-#pragma unroll
-                for (int u = 0; u < UK; ++u) {
-                    const int ko = (kb + u * 64 < kw) ? kb + u * 64 : kb;   // ragged tail: re-read, not used
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        wa[u][j] = *reinterpret_cast<const u32x4_t *>(wrow + kc + ko + j * 8);
-                }
-#pragma unroll
-                for (int u = 0; u < UK; ++u) {
-                    if (kb + u * 64 < kw) {
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const bf16x8_t af = __builtin_bit_cast(bf16x8_t, wa[u][j]);
-#pragma unroll
-                            for (int t = 0; t < MT; ++t) {
-                                const unsigned char *xp = xs + (t * 32 + r) * SK_XROW + (kb + u * 64 + h * 32 + j * 8) * 2;
-                                const bf16x8_t bfr = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t *>(xp));
-                                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfr, acc[t], 0, 0, 0);
-                            }
-                        }
-                    }
-                }
-            }
+            if (b0 + UK < nblk) SOL_SK_LOADW(wa1, b0 + UK);
+            SOL_SK_MMA(wa0, b0, 0);
+            if (b0 + 2 * UK < nblk) SOL_SK_LOADW(wa0, b0 + 2 * UK);
+            if (b0 + UK < nblk) SOL_SK_MMA(wa1, b0 + UK, UK * 64);
         }
     }
+#undef SOL_SK_LOADW
+#undef SOL_SK_MMA
     if (!live) return;
     // acc[t][i]: weight row n0 + 8*(i/4) + 4*h + (i%4), token t*32 + r
 #pragma unroll
@@ -763,8 +772,8 @@ k_gemm_skinny(const bf16_t *__restrict__ x, int64_t ldx, BMap bmap, int M, int N
 int skinny_splits(int M, int Nv, int K)
 {
     const int tiles = (Nv + 31) / 32;
-    int want = (1024 + tiles - 1) / tiles;
-    int cap = K / (8 * (M > 0 ? M : 1));
+    int want = (2048 + tiles - 1) / tiles;
+    int cap = K / (4 * (M > 0 ? M : 1));
     if (cap < 1) cap = 1;
     int s = want < cap ? want : cap;
     if (s < 1) s = 1;

@@ -189,7 +189,8 @@ k_rmsnorm_fq_wave(const TX *__restrict__ x, const float *__restrict__ add, int n
 #pragma unroll
         for (int c = 0; c < CH; ++c) {
             float t[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            for (int sp = 0; sp < nsplit; ++sp) {
+#pragma unroll 8
+            for (int sp = 0; sp < nsplit; ++sp) {           // unrolled: the loads of all splits go out together
                 const float *ap = add + sp * split_stride + r * D + c * 512 + lane * 8;
                 const f32x4_w a0 = *reinterpret_cast<const f32x4_w *>(ap), a1 = *reinterpret_cast<const f32x4_w *>(ap + 4);
 #pragma unroll
@@ -370,6 +371,7 @@ k_rope_store(const float *__restrict__ qkv, int nsplit, int64_t split_stride, T 
 {
     auto val = [&](const float *p) {                       // folds K-split partial sums in split order
         float t = 0.f;
+#pragma unroll 8
         for (int sp = 0; sp < nsplit; ++sp) t += p[sp * split_stride];
         return t;
     };
@@ -429,6 +431,7 @@ __global__ void k_silu_mul(const float *__restrict__ gu, int nsplit, T *__restri
     const int64_t r = idx / dff;
     const int c = (int)(idx - r * dff);
     float g = 0.f, u = 0.f;
+#pragma unroll 8
     for (int sp = 0; sp < nsplit; ++sp) {                  // K-split partial sums, fixed order
         g += gu[(sp * M + r) * 2 * dff + c];
         u += gu[(sp * M + r) * 2 * dff + dff + c];
@@ -701,6 +704,7 @@ __global__ void k_resid_out(const float *__restrict__ x2, const float *__restric
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= n) return;
     float t = 0.f;
+#pragma unroll 8
     for (int sp = 0; sp < nsplit; ++sp) t += z[sp * n + idx];
     st(out + idx, x2[idx] + t);
 }

@@ -199,7 +199,10 @@ def test_bf16_decode_step(shape, B, L, dup):
     check_rows(host(hid), h_ref, 2e-2, 1.0, 0.6, "decode hidden vs bf16 oracle", median=2e-2)
     nerr = np.abs(host(nll) - nll_ref)
     print("decode nll err", nerr)
-    assert np.median(nerr) < 1e-2 and nerr.max() < 0.5
+    bits = np.array([a[4] for a in table])[ids]
+    # sequences that never quantise: the 1e-2 nats of the contract; quantised ones may flip codes layer after
+    # layer (see test_oracle_sensitivity.py), so only their bulk is held close
+    assert (nerr[bits >= 16] < 1e-2).all() and np.median(nerr) < 2e-2 and nerr.max() < 0.5
     for l in range(shape.n_layers):
         kg, vg = host(kd[l]), host(vd[l])
         for s in range(B):
