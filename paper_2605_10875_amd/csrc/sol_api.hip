@@ -265,7 +265,7 @@ struct Carver {
 };
 
 struct LayerWs {
-    RowAct *ra; int32_t *row_bucket, *perm, *bucket_off;
+    RowAct *ra; int32_t *row_bucket, *perm, *bucket_off, *seq_order;
     void *h, *qb, *a, *vt;
     float *big32, *o32, *x2;
 };
@@ -282,6 +282,7 @@ static void carve_layer(Carver &c, const sol_model_cfg &g, int64_t n_seq, int64_
     w.row_bucket = (int32_t *)c.take(4 * M);
     w.perm = (int32_t *)c.take(4 * M);
     w.bucket_off = (int32_t *)c.take(4 * (MAX_ACTIONS + 1));
+    w.seq_order = (int32_t *)c.take(4 * n_seq);
     w.h = c.take(es * M * g.d_model);
     w.qb = c.take(es * M * nq);
     w.a = c.take(es * M * g.d_ff);
@@ -403,7 +404,7 @@ static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_i
         const bool tiled = mfma && w.vt && T >= 16 && L_max <= 4096 &&
                            launch_attn_tile(w.qb, kc, vc, w.vt, w.big32, w.o32, w.ra, pos0, n_seq, T, L_max, Hq, Hkv, dh, st);
         const bool dec = !tiled && mfma && T == 1 && pos0 &&
-                         launch_attn_decode(w.qb, kc, vc, w.o32, w.ra, pos0, n_seq, L_max, Hq, Hkv, dh, ctx->d_flags, st);
+                         launch_attn_decode(w.qb, kc, vc, w.o32, w.ra, pos0, w.seq_order, n_seq, L_max, Hq, Hkv, dh, ctx->d_flags, st);
         if (!tiled && !dec &&
             !launch_attn_rows(w.qb, kc, vc, dt, w.o32, w.ra, pos0, n_seq, T, L_max, Hq, Hkv, dh, ctx->d_flags, st))
             return fail(ctx, SOL_ERR_UNSUPPORTED, "attention: L_max too long for the on-chip score rows of this build");
@@ -502,6 +503,7 @@ extern "C" int sol_layer_forward(sol_ctx *ctx, const sol_layer_weights *w, const
     Carver c(workspace);
     LayerWs lw; carve_layer(c, ctx->cfg, n_seq, T, L_max, lw);
     prepare_actions(ctx, action_ids, (int64_t)n_seq * T, lw, st);
+    if (T == 1 && pos0) launch_seq_order(pos0, n_seq, lw.seq_order, st);
     return layer_impl(ctx, w, x_in, x_out, pos0, k_cache, v_cache, n_seq, T, L_max, lw, st);
 }
 
@@ -571,6 +573,7 @@ extern "C" int sol_decode_step(sol_ctx *ctx, const sol_model_weights *mw, const 
     Carver c(workspace);
     StackWs w; carve_stack(c, g, B, 1, false, w);
     prepare_actions(ctx, action_ids, B, w.layer, st);
+    launch_seq_order(cache_len, B, w.layer.seq_order, st);
     const void *cur = x_in;
     if (token_ids) {
         launch_embed(mw->embed, token_ids, w.hf, g.dtype, B, 1, 1, g.d_model, g.vocab, st);

@@ -728,12 +728,18 @@ k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf1
 //   3. softmax numerators back to LDS, 4. V rows gathered where any head kept the key.
 // =================================================================================================
 constexpr int DEC_WAVES = 16, DEC_BLOCK = DEC_WAVES * 64, DEC_HPB = 4, DEC_GW = DEC_WAVES / DEC_HPB;
+#ifdef SOL_DEC_TIMING
+__device__ unsigned long long *g_dec_stamps;
+#define DEC_T(i) if (threadIdx.x == 0 && g_dec_stamps) g_dec_stamps[((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 8 + (i)] = __builtin_readcyclecounter();
+#else
+#define DEC_T(i)
+#endif
 
 template <int DH, int SLOTS>
 __global__ void __launch_bounds__(DEC_BLOCK)
 k_attn_decode(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf16_t *__restrict__ vc,
-              float *__restrict__ o32, const RowAct *__restrict__ ra, const int32_t *__restrict__ cache_len, int L_max,
-              int Hq, int Hkv, float scale, int *flags)
+              float *__restrict__ o32, const RowAct *__restrict__ ra, const int32_t *__restrict__ cache_len,
+              const int32_t *__restrict__ seq_order, int L_max, int Hq, int Hkv, float scale, int *flags)
 {
     constexpr int KK = DH / 32, SLICE = SLOTS * 64, LPAD = SLICE * DEC_GW, NJ = SLOTS / 4;
     constexpr int VEC = 8, LPK = DH / VEC, KPI = DEC_BLOCK / LPK;
@@ -747,30 +753,11 @@ k_attn_decode(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kvh = blockIdx.x;
+    DEC_T(0)
     // Longest sequences first: workgroups are handed to compute units in launch order, one per CU, so with
-    // mixed cache lengths the last round would otherwise wait for a long row that started late. Every
-    // workgroup ranks the (few) sequences itself; row blockIdx.y of the grid serves the sequence of that rank.
-    int s = blockIdx.y;
-    {
-        __shared__ int s_len[DEC_BLOCK];
-        __shared__ int s_pick;
-        const int nb = gridDim.y;
-        if (nb <= DEC_BLOCK) {
-            const int my_len = tid < nb ? cache_len[tid] : 0;
-            s_len[tid] = my_len;
-            __syncthreads();
-            if (tid < nb) {
-                int rank = 0;
-                for (int j = 0; j < nb; ++j) {
-                    const int lj = s_len[j];
-                    rank += (lj > my_len || (lj == my_len && j < tid)) ? 1 : 0;
-                }
-                if (rank == (int)blockIdx.y) s_pick = tid;
-            }
-            __syncthreads();
-            s = s_pick;
-        }
-    }
+    // mixed cache lengths the last round would otherwise wait for a long row that started late. seq_order
+    // (k_seq_order, once per decode step) lists the sequences by decreasing cache length.
+    int s = seq_order ? seq_order[blockIdx.y] : (int)blockIdx.y;
     s = __builtin_amdgcn_readfirstlane(s);
     const int p0 = __builtin_amdgcn_readfirstlane(cache_len[s]);
     if (p0 < 0 || p0 + 1 > L_max) {
@@ -782,6 +769,7 @@ k_attn_decode(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const
     const bf16_t *kbase = kc + ((int64_t)s * Hkv + kvh) * (int64_t)L_max * DH;
     const bf16_t *vbase = vc + ((int64_t)s * Hkv + kvh) * (int64_t)L_max * DH;
     const int l16 = lane & 15, lg = lane >> 4;
+    DEC_T(1)
 
     // ---- 1. scores -----------------------------------------------------------------------------
     {
@@ -823,6 +811,7 @@ k_attn_decode(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const
         }
     }
     __syncthreads();
+    DEC_T(2)
 
     // ---- 2. selection: DEC_GW waves per head, each with SLICE columns in registers --------------
     const int head = w / DEC_GW, wg = w - head * DEC_GW;
@@ -865,17 +854,25 @@ k_attn_decode(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const
     lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)lo);
     hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)hi);
     const float mx = score_unkey(hi);                          // the head's best score, always kept
+    DEC_T(3)
     const RowAct act = ra[s];
     const int b = __builtin_amdgcn_readfirstlane(budget_ceil(act.keep_num, act.keep_den, n));   // 64-bit divide runs on the VALU
     uint32_t thr = 1u;                                         // budget keeps all: every valid key passes
     bool done = b >= n, exact = true;
-    // invariant while searching: count(key >= lo) >= b, count(key >= hi + 1) < b
-    for (int it = 0; it < 34; ++it) {
+    // invariant while searching: count(key >= lo) >= b, count(key >= hi + 1) < b. Pivots by regula falsi on
+    // g(x) = count(key >= x) - b + 1/2 in the score domain with the Illinois correction (about 7 counting
+    // rounds, each a workgroup barrier, instead of about 15 for bisection of the key); after 12 rounds, or when
+    // the guess leaves (lo, hi], the midpoint of the key range takes over, which bounds the search.
+    float flo = score_unkey(lo), fhi = score_unkey(hi), glo = (float)(n - b) + 0.5f, ghi = 0.5f - (float)b;
+    int side = 0;
+    for (int it = 0; it < 48; ++it) {
         const int par = it & 1;
         uint32_t mid = 0u;
         if (!done) {
-            mid = lo + ((hi - lo + 1u) >> 1);
-            const int c = wave_count_ge<SLOTS>(key, n_loc, mid);
+            const float fp = __builtin_fmaf(fhi - flo, glo * __builtin_amdgcn_rcpf(glo - ghi), flo);
+            mid = (uint32_t)__builtin_amdgcn_readfirstlane((int)score_key(fp));
+            if (it >= 12 || !(mid > lo && mid <= hi)) mid = lo + ((hi - lo + 1u) >> 1);
+            const int c = lo < hi ? wave_count_ge<SLOTS>(key, n_loc, mid) : 0;
             if (lane == 0) s_cnt[par][w] = c;
         }
         if (wg == 0 && lane == 0) s_done[par][head] = done || lo >= hi;
@@ -887,14 +884,24 @@ k_attn_decode(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const
 #pragma unroll
                 for (int i = 0; i < DEC_GW; ++i) cnt += s_cnt[par][head * DEC_GW + i];
                 cnt = __builtin_amdgcn_readfirstlane(cnt);
+                const float g = (float)(cnt - b) + 0.5f;
                 if (cnt == b) { thr = mid; done = true; }
-                else if (cnt > b) lo = mid; else hi = mid - 1u;
+                else if (cnt > b) {
+                    lo = mid; flo = score_unkey(mid); glo = g;
+                    if (side > 0) ghi *= 0.5f;
+                    side = 1;
+                } else {
+                    hi = mid - 1u; fhi = score_unkey(hi); ghi = g;
+                    if (side < 0) glo *= 0.5f;
+                    side = -1;
+                }
             }
         }
         const bool all_done =
             __builtin_amdgcn_readfirstlane(s_done[par][0] & s_done[par][1] & s_done[par][2] & s_done[par][3]) != 0;
         if (all_done) break;                                   // uniform: every wave reads the same flags
     }
+    DEC_T(4)
     // Ties at the threshold go to the lower columns. Rare for fp32 scores, so the fix-up is a plain
     // loop by the first wave of the head over the row in LDS: tied keys beyond the quota get -inf.
     {
@@ -926,16 +933,21 @@ k_attn_decode(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const
     }
 
     // ---- 3. softmax numerators back to LDS ----------------------------------------------------------
+    // The scores are still in registers (as keys); only a row the tie fix-up rewrote is read back.
     float den = 0.f;
+    const bool reread = (b < n) && !exact;
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
         if (256 * j < n_loc) {
-            const f32x4_a v = *reinterpret_cast<const f32x4_a *>(row + 256 * j + 4 * lane);
+            f32x4_a v = {0.f, 0.f, 0.f, 0.f};
+            if (reread) v = *reinterpret_cast<const f32x4_a *>(row + 256 * j + 4 * lane);
             f32x4_a p;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const bool on = (256 * j + 4 * lane + e < n_loc) && score_key(v[e]) >= thr;
-                p[e] = on ? __expf(v[e] - mx) : 0.f;
+                const uint32_t kv = reread ? score_key(v[e]) : key[4 * j + e];
+                const float sv = reread ? v[e] : score_unkey(key[4 * j + e]);
+                const bool on = (256 * j + 4 * lane + e < n_loc) && kv >= thr;
+                p[e] = on ? __expf(sv - mx) : 0.f;
                 den += p[e];
             }
             *reinterpret_cast<f32x4_a *>(row + 256 * j + 4 * lane) = p;
@@ -944,6 +956,7 @@ k_attn_decode(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const
     den = wave_sum_dpp(den);
     if (lane == 0) s_den[w] = den;
     __syncthreads();
+    DEC_T(5)
 
     // ---- 4. o = sum p_j v_j over rows any head kept ---------------------------------------------------
     const int ks = tid / LPK, cs = tid - ks * LPK;
@@ -984,34 +997,56 @@ k_attn_decode(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const
             }
         }
     }
-    // reduce over the key slots of a wave (lanes with equal cs), then across waves in fixed order
-    for (int o = LPK; o < 64; o <<= 1)
+    DEC_T(6)
+    // Reduce over the key slots of a wave (lanes with equal cs) by halving butterflies: at each step a lane
+    // keeps one half of its values and hands the other half to its partner, so the 4 * VEC values per lane
+    // end as 4 * VEC * LPK / 64 fully reduced ones; then across waves in fixed order.
+    float *accf = &acc[0][0];
+    int fbase = 0;                                             // first flattened (head, element) index this lane keeps
+    {
+        int nv = DEC_HPB * VEC;
 #pragma unroll
-        for (int hh = 0; hh < DEC_HPB; ++hh)
+        for (int o = LPK; o < 64; o <<= 1) {
+            nv >>= 1;
+            const bool up = (lane & o) != 0;
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) acc[hh][e] += __shfl_xor(acc[hh][e], o, 64);
+            for (int i = 0; i < DEC_HPB * VEC / 2; ++i) {
+                if (i < nv) {
+                    const float keep = up ? accf[i + nv] : accf[i];
+                    const float send = up ? accf[i] : accf[i + nv];
+                    accf[i] = keep + __shfl_xor(send, o, 64);
+                }
+            }
+            fbase += up ? nv : 0;
+        }
+    }
+    constexpr int NKEEP = DEC_HPB * VEC * LPK / 64;            // 4 (head_dim 64) or 8 (head_dim 128)
     __syncthreads();                                           // all reads of the numerators are done
     float *ored = sc;                                          // [DEC_WAVES][HPB][DH]
-    if (lane < LPK) {
+    {
+        const int hh = fbase / VEC, e0 = fbase - hh * VEC;     // NKEEP values of one head, elements e0..e0+NKEEP-1
+        float *dst = ored + ((size_t)w * DEC_HPB + hh) * DH + (lane & (LPK - 1)) * VEC + e0;
 #pragma unroll
-        for (int hh = 0; hh < DEC_HPB; ++hh)
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) ored[((size_t)w * DEC_HPB + hh) * DH + lane * VEC + e] = acc[hh][e];
+        for (int i = 0; i < NKEEP; i += 4)
+            *reinterpret_cast<f32x4_a *>(dst + i) = f32x4_a{accf[i], accf[i + 1], accf[i + 2], accf[i + 3]};
     }
     __syncthreads();
     for (int idx = tid; idx < DEC_HPB * DH; idx += DEC_BLOCK) {
         const int hh = idx / DH;
         float t = 0.f, dsum = 0.f;
+#pragma unroll
         for (int ww = 0; ww < DEC_WAVES; ++ww) t += ored[(size_t)ww * DEC_HPB * DH + idx];
 #pragma unroll
         for (int i = 0; i < DEC_GW; ++i) dsum += s_den[hh * DEC_GW + i];
         o32[(int64_t)s * (Hq * DH) + (int64_t)h0 * DH + idx] = t / dsum;
     }
+    DEC_T(7)
 }
 
 template <int DH, int SLOTS>
 static bool launch_attn_decode_t(const void *q, const void *kc, const void *vc, float *o32, const RowAct *ra,
-                                 const int32_t *cache_len, int B, int L_max, int Hq, int Hkv, int *flags, hipStream_t st)
+                                 const int32_t *cache_len, const int32_t *seq_order, int B, int L_max, int Hq, int Hkv,
+                                 int *flags, hipStream_t st)
 {
     auto kern = k_attn_decode<DH, SLOTS>;
     const size_t lds = (size_t)DEC_HPB * SLOTS * 64 * DEC_GW * 4;
@@ -1023,21 +1058,52 @@ static bool launch_attn_decode_t(const void *q, const void *kc, const void *vc, 
         attr_done = true;
     }
     hipLaunchKernelGGL(kern, dim3(Hkv, B), dim3(DEC_BLOCK), lds, st, (const bf16_t *)q, (const bf16_t *)kc,
-                       (const bf16_t *)vc, o32, ra, cache_len, L_max, Hq, Hkv, 1.0f / sqrtf((float)DH), flags);
+                       (const bf16_t *)vc, o32, ra, cache_len, seq_order, L_max, Hq, Hkv, 1.0f / sqrtf((float)DH), flags);
     return true;
 }
 
+// order[r] = the sequence with the r-th longest cache (equal lengths in index order); identity beyond 1024
+// sequences. One workgroup; the lengths are the same for every layer of a decode step.
+__global__ void __launch_bounds__(1024)
+k_seq_order(const int32_t *__restrict__ len, int n, int32_t *__restrict__ order)
+{
+    __shared__ int s_len[1024];
+    const int tid = threadIdx.x;
+    if (n > 1024) {
+        for (int i = tid; i < n; i += 1024) order[i] = i;
+        return;
+    }
+    const int my_len = tid < n ? len[tid] : 0;
+    s_len[tid] = my_len;
+    __syncthreads();
+    if (tid < n) {
+        int rank = 0;
+        for (int j = 0; j < n; ++j) {
+            const int lj = s_len[j];
+            rank += (lj > my_len || (lj == my_len && j < tid)) ? 1 : 0;
+        }
+        order[rank] = tid;
+    }
+}
+
+void launch_seq_order(const int32_t *cache_len, int B, int32_t *order, hipStream_t st)
+{
+    if (B > 0) hipLaunchKernelGGL(k_seq_order, dim3(1), dim3(1024), 0, st, cache_len, B, order);
+}
+
 // One query per sequence (T = 1), bf16, 4 query heads per KV head, head_dim 64 / 128, L_max <= 9216.
+// seq_order: sequences by decreasing cache length (launch_seq_order), or null for launch order.
 bool launch_attn_decode(const void *q, const void *k_cache, const void *v_cache, float *o32, const RowAct *ra,
-                        const int32_t *cache_len, int B, int L_max, int Hq, int Hkv, int dh, int *flags, hipStream_t st)
+                        const int32_t *cache_len, const int32_t *seq_order, int B, int L_max, int Hq, int Hkv, int dh,
+                        int *flags, hipStream_t st)
 {
     if (B <= 0) return true;
     if (!cache_len || Hq != DEC_HPB * Hkv || (dh != 64 && dh != 128) || L_max > 9216) return false;
     const size_t red = (size_t)DEC_WAVES * DEC_HPB * dh * 4;
 #define SOL_DEC(SL)                                                                                             \
     if ((size_t)DEC_HPB * SL * 64 * DEC_GW * 4 >= red)                                                           \
-        return dh == 64 ? launch_attn_decode_t<64, SL>(q, k_cache, v_cache, o32, ra, cache_len, B, L_max, Hq, Hkv, flags, st) \
-                        : launch_attn_decode_t<128, SL>(q, k_cache, v_cache, o32, ra, cache_len, B, L_max, Hq, Hkv, flags, st)
+        return dh == 64 ? launch_attn_decode_t<64, SL>(q, k_cache, v_cache, o32, ra, cache_len, seq_order, B, L_max, Hq, Hkv, flags, st) \
+                        : launch_attn_decode_t<128, SL>(q, k_cache, v_cache, o32, ra, cache_len, seq_order, B, L_max, Hq, Hkv, flags, st)
     if (L_max <= 1024) { SOL_DEC(4); }
     if (L_max <= 2048) { SOL_DEC(8); }
     if (L_max <= 4096) { SOL_DEC(16); }

@@ -107,8 +107,10 @@ bool launch_attn_rows(const void *q, const void *k_cache, const void *v_cache, i
                       const RowAct *ra, const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv,
                       int dh, int *flags, hipStream_t st);
 // Decode attention: one query per sequence, bf16, 4 query heads per KV head, L_max <= 9216.
+void launch_seq_order(const int32_t *cache_len, int B, int32_t *order, hipStream_t st);
 bool launch_attn_decode(const void *q, const void *k_cache, const void *v_cache, float *o32, const RowAct *ra,
-                        const int32_t *cache_len, int B, int L_max, int Hq, int Hkv, int dh, int *flags, hipStream_t st);
+                        const int32_t *cache_len, const int32_t *seq_order, int B, int L_max, int Hq, int Hkv, int dh,
+                        int *flags, hipStream_t st);
 // Batched bf16 attention (L_max <= 4096, head_dim 64 or 128, 1/2/4/8 query heads per KV head): a threshold
 // kernel followed by a flash-style masked softmax * V kernel. vt is workspace for the transposed V copy
 // (n_seq * Hkv * dh * attn_tile_lpadv(L_max) elements), sel_ws for the per-(row, head) thresholds
