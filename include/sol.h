@@ -58,6 +58,8 @@ typedef enum { SOL_F32 = 0, SOL_BF16 = 1 } sol_dtype;
 #define SOL_QS_GATEUP_IN 4u
 #define SOL_QS_DOWN_IN   8u
 #define SOL_QS_ALL_LINEAR_INPUTS 15u
+#define SOL_QS_MLP_OUT   16u  /* output of the MLP block, before the residual add (Appendix
+                                 "Activation quantization": the site the paper's own runs use) */
 
 /* One row of the action table a -> (kappa(a), rho(a), q(a)) (Method, "Actions and controlled
  * compute"). Fractions are rationals so that ceil(kappa * n) is exact integer arithmetic.
@@ -74,11 +76,19 @@ typedef struct {
     float   rms_eps, rope_theta;
     int32_t dtype;          /* sol_dtype of weights, activations and caches                      */
     int32_t max_positions;  /* rotary table length; every L_max must be <= this                  */
-    int32_t page_size;      /* key-selection page size; this build supports 1 (exact top-k)      */
-    int32_t n_sink;         /* always-kept first keys; this build supports 0                     */
-    int32_t n_window;       /* always-kept last keys;  this build supports 0                     */
-    int32_t prune_site;     /* 0 = SiLU(gate)*up intermediate (supported), 1 = MLP input (not)   */
-    uint32_t quant_sites;   /* subset of SOL_QS_ALL_LINEAR_INPUTS                                */
+    int32_t page_size;      /* S (Appendix "Quest masking"): 1 = exact per-key top-k; S > 1 =
+                               pages of S contiguous keys from key 0, ranked by the upper bound
+                               sum_c max(q_c max_c, q_c min_c) over the channel-wise extremes of
+                               their allowed keys; the top ceil(b/S) pages are kept whole        */
+    int32_t n_sink;         /* T_s: the first n_sink allowed keys are always kept                */
+    int32_t n_window;       /* T_w: the last n_window allowed keys are always kept. With S = 1
+                               forced keys count against the budget b; with S > 1 they are kept
+                               on top of the chosen pages                                        */
+    int32_t prune_site;     /* 0 = SiLU(gate)*up intermediate (keep ceil(rho d_ff) channels),
+                               1 = MLP input after the post-attention norm (ceil(rho d_model))   */
+    uint32_t quant_sites;   /* any subset of SOL_QS_ALL_LINEAR_INPUTS | SOL_QS_MLP_OUT.
+                               Configurations other than page_size 1, no forced keys run the
+                               general attention kernel (no tiled / decode fast path yet)        */
 } sol_model_cfg;
 
 typedef struct {  /* device pointers, element type cfg.dtype */
@@ -106,8 +116,8 @@ typedef struct sol_ctx sol_ctx;
 
 /* Host-only check of a configuration and an action table (no GPU needed).
  * SOL_ERR_ACTION: a table entry violates the ranges above (e.g. kappa = 0, which would leave a
- * softmax over no keys). SOL_ERR_UNSUPPORTED: page_size/n_sink/n_window/prune_site/quant_sites
- * outside what this build implements. SOL_ERR_INVALID_ARG: bad shape. */
+ * softmax over no keys). SOL_ERR_UNSUPPORTED: more than 4096 actions or a head_dim the kernels do
+ * not cover. SOL_ERR_INVALID_ARG: bad shape. */
 int sol_validate_config(const sol_model_cfg *cfg, const sol_action_def *table, int n_actions);
 
 /* Creates a context on the current HIP device: copies the action table, builds the rotary table

@@ -102,10 +102,8 @@ static int validate(const sol_model_cfg *c, const sol_action_def *t, int n, std:
         }
         if (d.bits < 4) { msg = "action " + std::to_string(a) + ": bits must be >= 4"; return SOL_ERR_ACTION; }
     }
-    if (c->page_size != 1) { msg = "page_size > 1 (Quest page bound) is not built"; return SOL_ERR_UNSUPPORTED; }
-    if (c->n_sink != 0 || c->n_window != 0) { msg = "sink / window keys are not built"; return SOL_ERR_UNSUPPORTED; }
-    if (c->prune_site != 0) { msg = "MLP-input prune site is not built"; return SOL_ERR_UNSUPPORTED; }
-    if (c->quant_sites & ~SOL_QS_ALL_LINEAR_INPUTS) { msg = "quant site outside the linear-layer inputs is not built"; return SOL_ERR_UNSUPPORTED; }
+    if (c->prune_site != 0 && c->prune_site != 1) { msg = "prune_site must be 0 or 1"; return SOL_ERR_INVALID_ARG; }
+    if (c->quant_sites & ~(SOL_QS_ALL_LINEAR_INPUTS | SOL_QS_MLP_OUT)) { msg = "unknown quant site bit"; return SOL_ERR_INVALID_ARG; }
     const int vec = c->dtype == SOL_BF16 ? 8 : 4;
     const int lpk = c->head_dim / vec;
     if (c->head_dim % vec || lpk > 64 || (lpk & (lpk - 1))) {
@@ -267,7 +265,7 @@ struct Carver {
 struct LayerWs {
     RowAct *ra; int32_t *row_bucket, *perm, *bucket_off, *seq_order;
     void *h, *qb, *a, *vt;
-    float *big32, *o32, *x2;
+    float *big32, *o32, *x2, *hn32;
 };
 
 static void carve_layer(Carver &c, const sol_model_cfg &g, int64_t n_seq, int64_t T, int L_max, LayerWs &w)
@@ -296,6 +294,7 @@ static void carve_layer(Carver &c, const sol_model_cfg &g, int64_t n_seq, int64_
     w.big32 = (float *)c.take(4 * M * wide);
     w.o32 = (float *)c.take(4 * M * nq);
     w.x2 = (float *)c.take(4 * M * g.d_model);
+    w.hn32 = (float *)c.take(g.prune_site == 1 ? 4 * M * g.d_model : 0);   // fp32 post-norm row, pruned at the MLP input
     // transposed V copy for the tiled attention kernel (batched bf16 pass only)
     const bool tiled = g.dtype == SOL_BF16 && T >= 16 && L_max <= 4096;
     w.vt = c.take(tiled ? es * n_seq * g.n_kv_heads * g.head_dim * (size_t)attn_tile_lpadv(L_max) : 0);
@@ -354,7 +353,8 @@ extern "C" size_t sol_workspace_bytes(const sol_model_cfg *cfg, int op, int n_se
 static void prepare_actions(sol_ctx *ctx, const int32_t *ids, int64_t M, LayerWs &w, hipStream_t st)
 {
     STAGE(ctx, ST_PREPARE, st);
-    launch_prepare_rows(ids, ctx->d_table, ctx->n_actions, ctx->cfg.d_ff, M, w.ra, w.row_bucket, ctx->d_flags, st);
+    launch_prepare_rows(ids, ctx->d_table, ctx->n_actions, ctx->cfg.prune_site ? ctx->cfg.d_model : ctx->cfg.d_ff, M,
+                        w.ra, w.row_bucket, ctx->d_flags, st);
     if (prune_fq_wants_order(ctx->cfg.dtype, ctx->cfg.d_ff))
         launch_bucket_sort(w.row_bucket, M, ctx->n_buckets, w.perm, w.bucket_off, st);
 }
@@ -401,12 +401,15 @@ static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_i
     }
     {   // scores, budgeted selection, softmax over kept keys, times V
         STAGE(ctx, ST_ATTN, st);
-        const bool tiled = mfma && w.vt && T >= 16 && L_max <= 4096 &&
+        AttnOpts opt;
+        opt.page = g.page_size; opt.n_sink = g.n_sink; opt.n_window = g.n_window;
+        const bool fast = mfma && opt.plain();       // the tiled and decode kernels know the plain top-k rule only
+        const bool tiled = fast && w.vt && T >= 16 && L_max <= 4096 &&
                            launch_attn_tile(w.qb, kc, vc, w.vt, w.big32, w.o32, w.ra, pos0, n_seq, T, L_max, Hq, Hkv, dh, st);
-        const bool dec = !tiled && mfma && T == 1 && pos0 &&
+        const bool dec = !tiled && fast && T == 1 && pos0 &&
                          launch_attn_decode(w.qb, kc, vc, w.o32, w.ra, pos0, w.seq_order, n_seq, L_max, Hq, Hkv, dh, ctx->d_flags, st);
         if (!tiled && !dec &&
-            !launch_attn_rows(w.qb, kc, vc, dt, w.o32, w.ra, pos0, n_seq, T, L_max, Hq, Hkv, dh, ctx->d_flags, st))
+            !launch_attn_rows(w.qb, kc, vc, dt, w.o32, w.ra, pos0, n_seq, T, L_max, Hq, Hkv, dh, ctx->d_flags, st, opt))
             return fail(ctx, SOL_ERR_UNSUPPORTED, "attention: L_max too long for the on-chip score rows of this build");
     }
     {   // quantise (o-proj input)
@@ -425,12 +428,20 @@ static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_i
             if (!fused_o) launch_gemm_generic(w.qb, dt, nq, lw->wo, dt, nq, w.big32, d, M, d, nq, st);
         }
     }
-    {   // post norm + quantise (gate/up input)
+    {   // post norm (+ pruning at the MLP-input site) + quantise (gate/up input)
         STAGE(ctx, ST_NORM_POST, st);
+        const bool prune_in = g.prune_site == 1;     // then: norm to fp32, prune + quantise in place, store
+        void *hdst = prune_in ? (void *)w.hn32 : w.h;
+        const int hdt = prune_in ? SOL_F32 : dt;
+        const bool q_here = !prune_in && (qs & SOL_QS_GATEUP_IN);
         if (fused_o)
-            launch_rmsnorm_fq(w.x2, SOL_F32, nullptr, nullptr, lw->w_post_norm, dt, w.h, dt, w.ra, qs & SOL_QS_GATEUP_IN, M, d, g.rms_eps, st);
+            launch_rmsnorm_fq(w.x2, SOL_F32, nullptr, nullptr, lw->w_post_norm, dt, hdst, hdt, w.ra, q_here, M, d, g.rms_eps, st);
         else
-            launch_rmsnorm_fq(x_in, dt, w.big32, w.x2, lw->w_post_norm, dt, w.h, dt, w.ra, qs & SOL_QS_GATEUP_IN, M, d, g.rms_eps, st, ns_o);
+            launch_rmsnorm_fq(x_in, dt, w.big32, w.x2, lw->w_post_norm, dt, hdst, hdt, w.ra, q_here, M, d, g.rms_eps, st, ns_o);
+        if (prune_in) {
+            launch_prune_fq(w.hn32, SOL_F32, w.ra, nullptr, qs & SOL_QS_GATEUP_IN, M, d, st);
+            launch_fq_rows(w.hn32, w.h, dt, w.ra, false, M, d, st);
+        }
     }
     bool fused_gu = false;
     int ns_gu = 1;
@@ -453,23 +464,26 @@ static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_i
     }
     {   // magnitude pruning + quantise (down input), rows visited in bucket order
         STAGE(ctx, ST_PRUNE, st);
-        launch_prune_fq(w.a, dt, w.ra, w.perm, qs & SOL_QS_DOWN_IN, M, dff, st);
+        launch_prune_fq(w.a, dt, w.ra, w.perm, qs & SOL_QS_DOWN_IN, M, dff, st, g.prune_site == 0);
     }
     bool fused_down = false;
     int ns_down = 1;
+    const bool q_out = (qs & SOL_QS_MLP_OUT) != 0;   // the MLP output is quantised as a whole row before the residual add
     {   // down projection (+ residual when fused)
         STAGE(ctx, ST_DOWN, st);
         if (skinny) {
             ns_down = skinny_splits((int)M, d, dff);
             launch_gemm_skinny(w.a, dff, lw->w_down, d, nullptr, 0, nullptr, 0, (int)M, dff, w.big32, ns_down, st);
         } else {
-            fused_down = mfma && launch_gemm_resid_out(w.a, lw->w_down, w.x2, x_out, M, d, dff, st);
-            if (!fused_down) launch_gemm_generic(w.a, dt, dff, lw->w_down, dt, dff, w.big32, d, M, d, dff, st);
+            fused_down = mfma && !q_out && launch_gemm_resid_out(w.a, lw->w_down, w.x2, x_out, M, d, dff, st);
+            if (!fused_down && !(mfma && launch_gemm_f32(w.a, lw->w_down, w.big32, d, M, d, dff, st)))
+                launch_gemm_generic(w.a, dt, dff, lw->w_down, dt, dff, w.big32, d, M, d, dff, st);
         }
     }
     if (!fused_down) {   // residual
         STAGE(ctx, ST_RESID, st);
-        launch_resid_out(w.x2, w.big32, x_out, dt, M, d, st, ns_down);
+        if (q_out) launch_resid_out_fq(w.x2, w.big32, x_out, dt, w.ra, M, d, st, ns_down);
+        else launch_resid_out(w.x2, w.big32, x_out, dt, M, d, st, ns_down);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(ctx, SOL_ERR_HIP, std::string("kernel launch: ") + hipGetErrorString(e));

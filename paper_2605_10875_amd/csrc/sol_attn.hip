@@ -6,8 +6,14 @@
 //      lower position; b = n: dense
 //   3. softmax over the kept keys (dropped keys contribute exp(-inf) = 0)
 //   4. o = sum_j p_j v_j, reading only V rows kept by at least one of the HPB heads
-// K is streamed once per workgroup (HPB heads share it), V rows are gathered. This is the decode
-// kernel (one query per sequence, HBM-bound) and the any-shape / fp32 path of the batched pass.
+// K is streamed once per workgroup (HPB heads share it), V rows are gathered. This is the any-shape /
+// fp32 path, and the only one that knows the other key-selection rules of the method (Appendix "Quest
+// masking"):
+//   - sink / window keys: the first n_sink and the last n_window allowed keys are always kept and
+//     count against the budget (the selection sees them with the largest possible key);
+//   - pages of S > 1 contiguous keys: a page's score is the upper bound sum_c max(q_c max_c, q_c min_c)
+//     over the channel-wise extremes of its allowed keys; the top ceil(b / S) pages are kept whole
+//     (ties to the lower page) together with the forced keys.
 #include "sol_internal.h"
 
 namespace sol {
@@ -17,17 +23,28 @@ struct ScoreKeyLds {
     __device__ __forceinline__ uint32_t operator()(int i) const { return score_key(row[i]); }
 };
 
+// selection key of key j when keys [0, sink_end) and [win_begin, n) are forced
+struct ForcedKeyLds {
+    const float *row;
+    int sink_end, win_begin;
+    __device__ __forceinline__ uint32_t operator()(int i) const
+    {
+        return (i < sink_end || i >= win_begin) ? 0xFFFFFFFFu : score_key(row[i]);
+    }
+};
+
 template <typename T, int HPB, int BLOCK>
 __global__ void __launch_bounds__(BLOCK)
 k_attn_rows(const T *__restrict__ q, const T *__restrict__ kc, const T *__restrict__ vc, float *__restrict__ o32,
             const RowAct *__restrict__ ra, const int32_t *__restrict__ pos0, int Tn, int L_max, int Hq, int Hkv,
-            int dh, int lpad, float scale, int *flags)
+            int dh, int lpad, float scale, int *flags, AttnOpts opt, int ppad)
 {
     constexpr int VEC = Vec16<T>::N;
     constexpr int NW = BLOCK / 64;
     extern __shared__ float smem[];
     float *sc = smem;                               // [HPB][lpad]
     float *ored = smem + (size_t)HPB * lpad;        // [NW][HPB][dh]
+    float *pgs = ored + (size_t)NW * HPB * dh;      // [HPB][ppad] page scores (page size > 1 only)
     __shared__ int hist[256];
     __shared__ int sh[4];
     __shared__ int wcnt[NW];
@@ -80,31 +97,100 @@ k_attn_rows(const T *__restrict__ q, const T *__restrict__ kc, const T *__restri
 #pragma unroll
             for (int h = 0; h < HPB; ++h) sc[h * lpad + j] = part[h] * scale;
     }
+    const RowAct act = ra[r];
+    const int b = budget_ceil(act.keep_num, act.keep_den, n);
+    const int S = opt.page;
+    const int n_pages = (n + S - 1) / S;
+    if (S > 1 && b < n) {
+        // ---- 1b. page bounds: a group of lpk lanes walks the allowed keys of one page --------------
+        for (int u0 = 0; u0 < n_pages; u0 += kpi) {
+            const int u = u0 + ks;
+            float part[HPB];
+#pragma unroll
+            for (int h = 0; h < HPB; ++h) part[h] = 0.f;
+            if (u < n_pages) {
+                const int j0 = u * S, j1 = (j0 + S < n) ? j0 + S : n;
+                float kmx[VEC], kmn[VEC];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) { kmx[e] = -INFINITY; kmn[e] = INFINITY; }
+                for (int j = j0; j < j1; ++j) {
+                    Vec16<T> kv;
+                    kv.load(kbase + (int64_t)j * dh + cs * VEC);
+                    float kf[VEC];
+                    kv.unpack(kf);
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) { kmx[e] = fmaxf(kmx[e], kf[e]); kmn[e] = fminf(kmn[e], kf[e]); }
+                }
+#pragma unroll
+                for (int h = 0; h < HPB; ++h)
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e)
+                        part[h] = fmaf(qf[h][e], qf[h][e] >= 0.f ? kmx[e] : kmn[e], part[h]);
+            }
+            for (int o = lpk >> 1; o > 0; o >>= 1)
+#pragma unroll
+                for (int h = 0; h < HPB; ++h) part[h] += __shfl_xor(part[h], o, 64);
+            if (cs == 0 && u < n_pages)
+#pragma unroll
+                for (int h = 0; h < HPB; ++h) pgs[h * ppad + u] = part[h];
+        }
+    }
     __syncthreads();
 
     // ---- 2 + 3. selection and softmax numerators, head by head ------------------------------
-    const RowAct act = ra[r];
-    const int b = budget_ceil(act.keep_num, act.keep_den, n);
+    // forced keys: [0, sink_end) and [win_begin, n)
+    const int sink_end = opt.n_sink < n ? opt.n_sink : n;
+    int win_begin = n - opt.n_window;
+    win_begin = win_begin < sink_end ? sink_end : win_begin;
+    const int forced = sink_end + (n - win_begin);
     float inv_den[HPB];
 #pragma unroll
     for (int h = 0; h < HPB; ++h) {
         float *row = sc + h * lpad;
-        uint32_t thr = 0u; int J = n;
+        uint32_t thr = 0u; int J = n;                // by key (S = 1) or by page (S > 1): kept if above thr, or tied and <= J
         if (b < n) {
-            ScoreKeyLds kf{row};
             int quota, n_eq;
-            block_radix_select<BLOCK>(kf, n, b, hist, sh, thr, quota, n_eq);
-            if (quota < n_eq) J = block_tie_cutoff<BLOCK>(kf, n, thr, quota, wcnt, sh);
+            if (S > 1) {
+                ScoreKeyLds kf{pgs + h * ppad};
+                int np = (b + S - 1) / S;
+                np = np < n_pages ? np : n_pages;
+                J = n_pages;
+                if (np < n_pages) {
+                    block_radix_select<BLOCK>(kf, n_pages, np, hist, sh, thr, quota, n_eq);
+                    if (quota < n_eq) J = block_tie_cutoff<BLOCK>(kf, n_pages, thr, quota, wcnt, sh);
+                }
+            } else if (forced == 0) {
+                ScoreKeyLds kf{row};
+                block_radix_select<BLOCK>(kf, n, b, hist, sh, thr, quota, n_eq);
+                if (quota < n_eq) J = block_tie_cutoff<BLOCK>(kf, n, thr, quota, wcnt, sh);
+            } else if (forced < n) {                 // forced keys rank first; the rest of the budget goes by score
+                ForcedKeyLds kf{row, sink_end, win_begin};
+                const int bb = b > forced ? b : forced;
+                block_radix_select<BLOCK>(kf, n, bb, hist, sh, thr, quota, n_eq);
+                if (quota < n_eq) J = block_tie_cutoff<BLOCK>(kf, n, thr, quota, wcnt, sh);
+            }
         }
-        float mx = -INFINITY;
-        for (int j = tid; j < n; j += BLOCK) mx = fmaxf(mx, row[j]);   // the best key is always kept
+        auto kept = [&](int j, float sv) -> bool {
+            if (b >= n) return true;
+            const bool f = j < sink_end || j >= win_begin;
+            if (S > 1) {
+                const int u = j / S;
+                const uint32_t key = score_key(pgs[h * ppad + u]);
+                return f || key > thr || (key == thr && u <= J);
+            }
+            const uint32_t key = f ? 0xFFFFFFFFu : score_key(sv);
+            return key > thr || (key == thr && j <= J);
+        };
+        float mx = -INFINITY;                        // over the kept keys (the best key may be dropped with its page)
+        for (int j = tid; j < n; j += BLOCK) {
+            const float sv = row[j];
+            if (kept(j, sv)) mx = fmaxf(mx, sv);
+        }
         mx = block_max<BLOCK>(mx, red);
         float den = 0.f;
         for (int j = tid; j < n; j += BLOCK) {
             const float sv = row[j];
-            const uint32_t key = score_key(sv);
-            const bool keep = key > thr || (key == thr && j <= J);
-            const float p = keep ? expf(sv - mx) : 0.f;
+            const float p = kept(j, sv) ? expf(sv - mx) : 0.f;
             row[j] = p;
             den += p;
         }
@@ -162,7 +248,7 @@ k_attn_rows(const T *__restrict__ q, const T *__restrict__ kc, const T *__restri
 template <typename T, int HPB, int BLOCK>
 static bool launch_attn_rows_t(const void *q, const void *kc, const void *vc, float *o32, const RowAct *ra,
                                const int32_t *pos0, int n_seq, int Tn, int L_max, int Hq, int Hkv, int dh, int lpad,
-                               size_t lds, int *flags, hipStream_t st)
+                               size_t lds, int *flags, AttnOpts opt, int ppad, hipStream_t st)
 {
     auto kern = k_attn_rows<T, HPB, BLOCK>;
     if (lds > 48 * 1024) {
@@ -172,15 +258,16 @@ static bool launch_attn_rows_t(const void *q, const void *kc, const void *vc, fl
     }
     const float scale = 1.0f / sqrtf((float)dh);
     hipLaunchKernelGGL(kern, dim3(Hq / HPB, (unsigned)((int64_t)n_seq * Tn)), dim3(BLOCK), lds, st, (const T *)q,
-                       (const T *)kc, (const T *)vc, o32, ra, pos0, Tn, L_max, Hq, Hkv, dh, lpad, scale, flags);
+                       (const T *)kc, (const T *)vc, o32, ra, pos0, Tn, L_max, Hq, Hkv, dh, lpad, scale, flags, opt, ppad);
     return true;
 }
 
 bool launch_attn_rows(const void *q, const void *k_cache, const void *v_cache, int dtype, float *o32,
                       const RowAct *ra, const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv, int dh,
-                      int *flags, hipStream_t st)
+                      int *flags, hipStream_t st, AttnOpts opt)
 {
     if ((int64_t)n_seq * T <= 0) return true;
+    if (opt.page < 1 || opt.n_sink < 0 || opt.n_window < 0) return false;
     const int vec = dtype == 0 ? 4 : 8;
     if (dh % vec) return false;
     const int lpk = dh / vec;
@@ -190,14 +277,15 @@ bool launch_attn_rows(const void *q, const void *k_cache, const void *v_cache, i
     // long caches (decode) get 1024-thread workgroups: more loads in flight per CU
     const int block = (L_max >= 2048) ? 1024 : 256;
     const size_t budget = 150 * 1024;
+    const int ppad = opt.page > 1 ? (L_max + opt.page - 1) / opt.page : 0;
     int hpb = 4;
     while (hpb > 1 && (g % hpb != 0 ||
-                       (size_t)hpb * lpad * 4 + (size_t)(block / 64) * hpb * dh * 4 > budget)) hpb >>= 1;
-    const size_t lds = (size_t)hpb * lpad * 4 + (size_t)(block / 64) * hpb * dh * 4;
+                       (size_t)hpb * (lpad + ppad) * 4 + (size_t)(block / 64) * hpb * dh * 4 > budget)) hpb >>= 1;
+    const size_t lds = (size_t)hpb * (lpad + ppad) * 4 + (size_t)(block / 64) * hpb * dh * 4;
     if (lds > budget) return false;
 #define SOL_ATTN_CASE(TT, H, B)                                                                                     \
     return launch_attn_rows_t<TT, H, B>(q, k_cache, v_cache, o32, ra, pos0, n_seq, T, L_max, Hq, Hkv, dh, lpad, lds, \
-                                        flags, st)
+                                        flags, opt, ppad, st)
     if (dtype == 0) {
         if (block == 256) { if (hpb == 4) SOL_ATTN_CASE(float, 4, 256); if (hpb == 2) SOL_ATTN_CASE(float, 2, 256); SOL_ATTN_CASE(float, 1, 256); }
         else { if (hpb == 4) SOL_ATTN_CASE(float, 4, 1024); if (hpb == 2) SOL_ATTN_CASE(float, 2, 1024); SOL_ATTN_CASE(float, 1, 1024); }

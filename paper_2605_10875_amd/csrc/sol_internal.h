@@ -16,7 +16,8 @@ struct ActionDev {  // device copy of one action-table row, with the MLP bucket 
 
 // ---- rows (sol_rows.hip) ---------------------------------------------------------------------
 // Decodes action ids into RowAct (invalid id => dense action + FLAG_BAD_ACTION) and writes each
-// row's MLP bucket.
+// row's MLP bucket. d_ff is the width of the vector the MLP keep fraction applies to (d_ff at the
+// SiLU(gate)*up site, d_model at the MLP-input site).
 void launch_prepare_rows(const int32_t *action_ids, const ActionDev *table, int n_actions, int d_ff,
                          int64_t M, RowAct *ra, int32_t *row_bucket, int *flags, hipStream_t st);
 // Stable counting sort of rows by bucket: perm[slot] = row, bucket_off[b] = first slot of bucket b
@@ -39,13 +40,17 @@ void launch_rope_store(const float *qkv32, void *q, void *k_cache, void *v_cache
 void launch_silu_mul(const float *gu32, void *a, int dtype, int64_t M, int dff, hipStream_t st, int nsplit = 1);
 // in place on a [M][dff]: keep the ra.m largest |a| (ties to lower channel), then FQ.
 // Rows are visited in bucket order through perm (NULL = identity).
+// prune = false: no pruning (ra.m then belongs to another site), quantiser only.
 void launch_prune_fq(void *a, int dtype, const RowAct *ra, const int32_t *perm, bool quant, int64_t M, int dff,
-                     hipStream_t st);
+                     hipStream_t st, bool prune = true);
 // whether launch_prune_fq uses perm for this type / width (if not, the bucket sort can be skipped)
 bool prune_fq_wants_order(int dtype, int dff);
 // out = x2 + z
 void launch_resid_out(const float *x2, const float *z, void *out, int dtype, int64_t M, int d, hipStream_t st,
                       int nsplit = 1);
+// out = x2 + FQ(z, ra.bits): quantiser on the MLP block's output
+void launch_resid_out_fq(const float *x2, const float *z, void *out, int dtype, const RowAct *ra, int64_t M, int d,
+                         hipStream_t st, int nsplit = 1);
 // x[n][t] = embed[tokens[b][t]]  for n = b*G + g
 void launch_embed(const void *embed, const int32_t *tokens, void *x, int dtype, int B, int G, int T, int d,
                   int vocab, hipStream_t st);
@@ -103,9 +108,15 @@ int skinny_splits(int M, int Nv, int K);
 // ---- attention (sol_attn.hip) ----------------------------------------------------------------
 // One query row per workgroup group: scores over cache positions [0, pos], budgeted top-k,
 // softmax over kept keys, times V. o32: fp32 [M][Hq*dh]. Returns false if the shape is unsupported.
+// opt: the key-selection rule (page size, sink and window keys); the other attention launchers below
+// implement the plain rule only (page 1, no forced keys).
+struct AttnOpts {
+    int page = 1, n_sink = 0, n_window = 0;
+    bool plain() const { return page == 1 && n_sink == 0 && n_window == 0; }
+};
 bool launch_attn_rows(const void *q, const void *k_cache, const void *v_cache, int dtype, float *o32,
                       const RowAct *ra, const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv,
-                      int dh, int *flags, hipStream_t st);
+                      int dh, int *flags, hipStream_t st, AttnOpts opt = AttnOpts());
 // Decode attention: one query per sequence, bf16, 4 query heads per KV head, L_max <= 9216.
 void launch_seq_order(const int32_t *cache_len, int B, int32_t *order, hipStream_t st);
 bool launch_attn_decode(const void *q, const void *k_cache, const void *v_cache, float *o32, const RowAct *ra,

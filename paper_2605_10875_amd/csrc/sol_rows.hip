@@ -9,7 +9,7 @@ namespace sol {
 // action decode (Method, "Actions and controlled compute": a -> (kappa, rho, q))
 // ------------------------------------------------------------------------------------------------
 __global__ void k_prepare_rows(const int32_t *__restrict__ ids, const ActionDev *__restrict__ table, int n_actions,
-                               int d_ff, int64_t M, RowAct *__restrict__ ra, int32_t *__restrict__ row_bucket,
+                               int d_ff /* width of the pruned vector */, int64_t M, RowAct *__restrict__ ra, int32_t *__restrict__ row_bucket,
                                int *flags)
 {
     const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -311,6 +311,8 @@ void launch_rmsnorm_fq(const void *x, int x_dtype, const float *add, float *xsum
     case 0: rmsnorm_dispatch3<float, float, float>(x, add, nsplit, xsum, w, h, ra, quant, M, d, eps, st); break;
     case 7: rmsnorm_dispatch3<bf16_t, bf16_t, bf16_t>(x, add, nsplit, xsum, w, h, ra, quant, M, d, eps, st); break;
     case 3: rmsnorm_dispatch3<float, bf16_t, bf16_t>(x, add, nsplit, xsum, w, h, ra, quant, M, d, eps, st); break;
+    case 6: rmsnorm_dispatch3<bf16_t, bf16_t, float>(x, add, nsplit, xsum, w, h, ra, quant, M, d, eps, st); break;
+    case 2: rmsnorm_dispatch3<float, bf16_t, float>(x, add, nsplit, xsum, w, h, ra, quant, M, d, eps, st); break;
     default: break;   // no other combination is ever requested by the host code
     }
 }
@@ -458,7 +460,8 @@ struct MagKeyLds {
 
 template <typename T>
 __global__ void __launch_bounds__(ROW_BLOCK)
-k_prune_fq(T *__restrict__ a, const RowAct *__restrict__ ra, const int32_t *__restrict__ perm, int quant, int dff)
+k_prune_fq(T *__restrict__ a, const RowAct *__restrict__ ra, const int32_t *__restrict__ perm, int quant, int prune,
+           int dff)
 {
     extern __shared__ float row[];
     __shared__ int hist[256];
@@ -468,7 +471,7 @@ k_prune_fq(T *__restrict__ a, const RowAct *__restrict__ ra, const int32_t *__re
     const int64_t r = perm ? perm[blockIdx.x] : (int64_t)blockIdx.x;
     const RowAct act = ra[r];
     const int bits = quant ? act.bits : 16;
-    const int m = act.m;
+    const int m = prune ? act.m : dff;
     if (m >= dff && bits >= 16) return;          // dense bucket: the row is already final
     const int tid = threadIdx.x;
     T *ar = a + r * dff;
@@ -521,7 +524,7 @@ typedef short i16x2_r __attribute__((ext_vector_type(2)));
 template <int CHUNKS, int NWV>
 __global__ void __launch_bounds__(64 * NWV)
 k_prune_fq_wave(bf16_t *__restrict__ a, const RowAct *__restrict__ ra, const int32_t *__restrict__ perm, int quant,
-                int64_t M)
+                int prune, int64_t M)
 {
     constexpr int DFF = CHUNKS * 512, CW = CHUNKS / NWV;
     static_assert(CHUNKS % NWV == 0, "chunks must split evenly over the waves");
@@ -533,7 +536,7 @@ k_prune_fq_wave(bf16_t *__restrict__ a, const RowAct *__restrict__ ra, const int
     const int64_t r = perm ? perm[slot] : slot;
     const RowAct act = ra[r];
     const int bits = __builtin_amdgcn_readfirstlane(quant ? act.bits : 16);
-    const int m = __builtin_amdgcn_readfirstlane(act.m);
+    const int m = __builtin_amdgcn_readfirstlane(prune ? act.m : DFF);
     if (m >= DFF && bits >= 16) return;                      // dense bucket: the row is already final (whole workgroup)
     bf16_t *ar = a + r * DFF + (int64_t)wv * CW * 512;
     u32x4_r d[CW];
@@ -665,7 +668,7 @@ static bool prune_wave_case(int dtype, int dff)
 bool prune_fq_wants_order(int dtype, int dff) { return !prune_wave_case(dtype, dff); }
 
 void launch_prune_fq(void *a, int dtype, const RowAct *ra, const int32_t *perm, bool quant, int64_t M, int dff,
-                     hipStream_t st)
+                     hipStream_t st, bool prune)
 {
     if (M <= 0) return;
     if (prune_wave_case(dtype, dff)) {
@@ -675,8 +678,9 @@ void launch_prune_fq(void *a, int dtype, const RowAct *ra, const int32_t *perm, 
 #define SOL_PRUNE_CASE(C)                                                                                       \
     case C:                                                                                                     \
         if (few) hipLaunchKernelGGL((k_prune_fq_wave<C, (C % 4 == 0 ? 4 : 1)>), grid, dim3(C % 4 == 0 ? 256 : 64), 0, st, \
-                                    (bf16_t *)a, ra, perm, quant ? 1 : 0, M);                                   \
-        else hipLaunchKernelGGL((k_prune_fq_wave<C, 1>), grid, dim3(64), 0, st, (bf16_t *)a, ra, perm, quant ? 1 : 0, M); \
+                                    (bf16_t *)a, ra, perm, quant ? 1 : 0, prune ? 1 : 0, M);                    \
+        else hipLaunchKernelGGL((k_prune_fq_wave<C, 1>), grid, dim3(64), 0, st, (bf16_t *)a, ra, perm, quant ? 1 : 0, \
+                                prune ? 1 : 0, M);                                                              \
         return;
         switch (dff / 512) {
             SOL_PRUNE_CASE(2) SOL_PRUNE_CASE(4) SOL_PRUNE_CASE(8) SOL_PRUNE_CASE(16) SOL_PRUNE_CASE(22)
@@ -688,10 +692,10 @@ void launch_prune_fq(void *a, int dtype, const RowAct *ra, const int32_t *perm, 
     const size_t lds = (size_t)dff * sizeof(float);
     if (dtype == 0)
         hipLaunchKernelGGL((k_prune_fq<float>), dim3((unsigned)M), dim3(ROW_BLOCK), lds, st, (float *)a, ra, perm,
-                           quant ? 1 : 0, dff);
+                           quant ? 1 : 0, prune ? 1 : 0, dff);
     else
         hipLaunchKernelGGL((k_prune_fq<bf16_t>), dim3((unsigned)M), dim3(ROW_BLOCK), lds, st, (bf16_t *)a, ra, perm,
-                           quant ? 1 : 0, dff);
+                           quant ? 1 : 0, prune ? 1 : 0, dff);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -716,6 +720,48 @@ void launch_resid_out(const float *x2, const float *z, void *out, int dtype, int
     const unsigned grid = (unsigned)((n + 255) / 256);
     if (dtype == 0) hipLaunchKernelGGL((k_resid_out<float>), dim3(grid), dim3(256), 0, st, x2, z, nsplit, (float *)out, n);
     else hipLaunchKernelGGL((k_resid_out<bf16_t>), dim3(grid), dim3(256), 0, st, x2, z, nsplit, (bf16_t *)out, n);
+}
+
+// out = x2 + FQ(z, bits): the quantiser on the MLP block's output (the paper's own site, Appendix
+// "Activation quantization"), one workgroup per row, the row of z in LDS.
+template <typename T>
+__global__ void __launch_bounds__(ROW_BLOCK)
+k_resid_out_fq(const float *__restrict__ x2, const float *__restrict__ z, int nsplit, int64_t split_stride,
+               T *__restrict__ out, const RowAct *__restrict__ ra, int d)
+{
+    extern __shared__ float row[];
+    __shared__ float red[ROW_BLOCK / 64];
+    const int64_t r = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int bits = ra[r].bits;
+    float amax = 0.f;
+    for (int j = tid; j < d; j += ROW_BLOCK) {
+        float t = 0.f;
+        for (int sp = 0; sp < nsplit; ++sp) t += z[sp * split_stride + r * d + j];   // K-split partial sums, fixed order
+        row[j] = t;
+        amax = fmaxf(amax, fabsf(t));
+    }
+    amax = block_max<ROW_BLOCK>(amax, red);        // (its barriers also publish row[])
+    const bool q = bits < 16 && amax > 0.f;
+    const float qmax = q ? fq_qmax(bits) : 1.f;
+    const float s = q ? amax / qmax : 1.f;
+    for (int j = tid; j < d; j += ROW_BLOCK) {
+        const float zz = q ? fq_code(row[j], s, qmax) * s : row[j];
+        st(out + r * d + j, x2[r * d + j] + zz);
+    }
+}
+
+void launch_resid_out_fq(const float *x2, const float *z, void *out, int dtype, const RowAct *ra, int64_t M, int d,
+                         hipStream_t st, int nsplit)
+{
+    if (M <= 0) return;
+    const size_t lds = (size_t)d * sizeof(float);
+    if (dtype == 0)
+        hipLaunchKernelGGL((k_resid_out_fq<float>), dim3((unsigned)M), dim3(ROW_BLOCK), lds, st, x2, z, nsplit,
+                           M * (int64_t)d, (float *)out, ra, d);
+    else
+        hipLaunchKernelGGL((k_resid_out_fq<bf16_t>), dim3((unsigned)M), dim3(ROW_BLOCK), lds, st, x2, z, nsplit,
+                           M * (int64_t)d, (bf16_t *)out, ra, d);
 }
 
 template <typename T>

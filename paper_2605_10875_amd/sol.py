@@ -12,8 +12,12 @@ from . import build as _build
 
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_ACTION, ERR_CACHE_OVERFLOW, ERR_HIP = 0, -1, -2, -3, -4, -5, -6
 F32, BF16 = 0, 1
-QS_QKV_IN, QS_O_IN, QS_GATEUP_IN, QS_DOWN_IN = 1, 2, 4, 8
+QS_QKV_IN, QS_O_IN, QS_GATEUP_IN, QS_DOWN_IN, QS_MLP_OUT = 1, 2, 4, 8, 16
 QS_ALL_LINEAR_INPUTS = 15
+# the configuration of the paper's own runs (Appendix "Quest masking", "Activation quantization"; sink / window
+# sizes from the experiment set-up): pages of 16 keys, 4 sink and 2 window keys, pruning at the MLP input,
+# quantiser on the MLP output only
+PAPER_PRESET = dict(page_size=16, n_sink=4, n_window=2, prune_site=1, quant_sites=QS_MLP_OUT)
 OP_LAYER_FORWARD, OP_DECODE_STEP, OP_SCHEDULE_LOGLIK = 0, 1, 2
 
 EXPORTS = ("sol_validate_config", "sol_create", "sol_destroy", "sol_last_error", "sol_workspace_bytes",

@@ -53,7 +53,7 @@ def test_validate_config_rejects_bad_actions(bad, code):
     assert rc == code and "action 1" in msg
 
 
-def test_validate_config_rejects_bad_shapes_and_unbuilt_variants():
+def test_validate_config_rejects_bad_shapes_and_accepts_every_variant():
     ok = dict(shape=synth.TINY, dtype=sol.F32, max_positions=128)
     tab = [synth.DENSE_ACTION]
     import dataclasses
@@ -65,9 +65,13 @@ def test_validate_config_rejects_bad_shapes_and_unbuilt_variants():
     assert rc == sol.ERR_INVALID_ARG
     rc, _ = sol.validate_config(sol.make_cfg(synth.TINY, sol.F32, 128), [])
     assert rc == sol.ERR_INVALID_ARG
-    for kw in (dict(page_size=4), dict(n_sink=4), dict(n_window=2), dict(prune_site=1), dict(quant_sites=16)):
+    for kw in (dict(page_size=4), dict(n_sink=4), dict(n_window=2), dict(prune_site=1), dict(quant_sites=16),
+               sol.PAPER_PRESET):
         rc, msg = sol.validate_config(sol.make_cfg(ok["shape"], ok["dtype"], ok["max_positions"], **kw), tab)
-        assert rc == sol.ERR_UNSUPPORTED and "not built" in msg
+        assert rc == sol.OK, msg
+    for kw in (dict(page_size=0), dict(n_sink=-1), dict(n_window=-2), dict(prune_site=2), dict(quant_sites=32)):
+        rc, _ = sol.validate_config(sol.make_cfg(ok["shape"], ok["dtype"], ok["max_positions"], **kw), tab)
+        assert rc == sol.ERR_INVALID_ARG
 
 
 def test_workspace_bytes_is_host_arithmetic():
