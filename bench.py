@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the action-conditioned decoder-layer path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c5|c4|c5d]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c5|c4|c5d|c4p]
 
 A step is one pass of the measured unit over one batch of seeded synthetic input that is already
 resident in HBM. Default workload: the Llama-3.2-1B-shaped decoder layer, 4 inputs x 8 schedules
@@ -195,7 +195,9 @@ def run_stack(args, shape, B, G, T, table, name):
     return res
 
 
-def run_decode(args, shape, B, L, table, name, n_layers):
+def run_decode(args, shape, B, L, table, name, n_layers, preset=None):
+    """preset: None = exact per-key top-k, quantiser on the linear-layer inputs; a dict of configuration fields
+    (sol.PAPER_PRESET) = that configuration, decoded with caller-kept page metadata."""
     import dataclasses
     shape = dataclasses.replace(shape, n_layers=n_layers)
     gen = torch.Generator(device="cuda").manual_seed(args.seed)
@@ -212,12 +214,13 @@ def run_decode(args, shape, B, L, table, name, n_layers):
     ids = synth.iid_actions(len(table), (B,), args.seed + 2)
     x = _dev(synth.hidden_states(1, B, shape.d_model, args.seed + 3, bf16=True)[0])
     cache_len = torch.full((B,), L, dtype=torch.int32, device="cuda")
-    ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=L_max)
+    ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=L_max, **(preset or {}))
     idd = _dev(ids)
     ws = ctx.workspace(sol.OP_DECODE_STEP, B, 1, L_max)
+    metas = [ctx.page_meta_build(k, cache_len) for k in kcs] if preset and preset.get("page_size", 1) > 1 else None
 
     def step():
-        return ctx.decode_step(lw, head, idd, cache_len, kcs, vcs, x_in=x, workspace=ws)[0]
+        return ctx.decode_step(lw, head, idd, cache_len, kcs, vcs, x_in=x, workspace=ws, page_meta=metas)[0]
 
     # The step is ~200 short kernels; replaying them as one HIP graph removes the host launch gaps
     # (the library only enqueues kernels on the caller's stream, so the caller may capture it).
@@ -245,6 +248,15 @@ def run_decode(args, shape, B, L, table, name, n_layers):
     g = hq // hkv
     union = n * (1.0 - (1.0 - kk / n) ** g)                  # expected distinct rows over g independent heads
     kv_bytes = float((hkv * dh * 2 * (n + union)).sum())
+    if metas is not None:
+        # page rule: the metadata rows (2 * dh values per page), then K and V rows of the pages kept by at least one
+        # head of a group (expected distinct pages over g independent heads) and of the sink / window keys
+        S = preset["page_size"]
+        n_pages = -(-n // S)
+        npg = np.minimum(-(-kk // S), n_pages)
+        upages = np.where(kk >= n, n_pages, n_pages * (1.0 - (1.0 - npg / n_pages) ** g))
+        rows = np.minimum(upages * S + preset.get("n_sink", 0) + preset.get("n_window", 0), n)
+        kv_bytes = float((hkv * dh * 2 * (2 * n_pages + 2 * rows)).sum())
     alg_bytes = n_layers * (wbytes + kv_bytes)
     dom = "attention_topk"
     ach = (n_layers * kv_bytes) / (stages[dom] * 1e-3) / 1e9
@@ -252,7 +264,8 @@ def run_decode(args, shape, B, L, table, name, n_layers):
         "metric": "decode_tokens_per_s", "value": B / sec, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": name, "entry_point": "sol_decode_step", "batch": B, "cache_len": L, "layers": n_layers,
+        "config": {"workload": name, "entry_point": "sol_decode_step_paged" if metas is not None else "sol_decode_step",
+                   "batch": B, "cache_len": L, "layers": n_layers,
                    "launch": "one HIP graph replay per step", "ms_per_step_eager_launches": sec_eager * 1e3},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                      "frac": ach / PEAK_HBM_GBS, "traffic": measured_traffic(args.workload, dom),
@@ -264,18 +277,18 @@ def run_decode(args, shape, B, L, table, name, n_layers):
     }
     if not args.no_cpu_baseline:
         import oracle
-        cfg = oracle.make_cfg(shape, act_bf16=True)
+        o_opts = dict(preset or {})
         k0 = [kcs[0][:1].float().cpu().numpy().copy()]
         v0 = [vcs[0][:1].float().cpu().numpy().copy()]
         one = dataclasses.replace(shape, n_layers=1)
         t0 = time.perf_counter()
-        oracle.decode_step(oracle.make_cfg(one, act_bf16=True), oracle.make_table(table), layers[:1],
+        oracle.decode_step(oracle.make_cfg(one, act_bf16=True, **o_opts), oracle.make_table(table), layers[:1],
                            x[:1].float().cpu().numpy(), ids[:1], np.array([L], np.int32), k0, v0)
         dt = time.perf_counter() - t0
         res["cpu_baseline"] = {"value": 1.0 / (dt * n_layers), "unit": "tokens/s", "cores": oracle.num_threads(),
                                "kind": "oracle", "sample": "sequence 0 of %d, one layer timed (%.2f s), scaled to %d layers"
                                % (B, dt, n_layers)}
-        del cfg
+        del o_opts
     ctx.close()
     return res
 
@@ -285,7 +298,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c5", "c4", "c5d"])
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c5", "c4", "c5d", "c4p"])
     ap.add_argument("--seed", type=int, default=1234)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -312,6 +325,11 @@ def main():
     elif args.workload == "c4":
         res = run_decode(args, synth.LLAMA_1B, 64, 8192, synth.TABLE_C4,
                          "C4: Llama-3.2-1B-shaped decode step, bf16, 64 sequences x 8192-token KV cache, 16 layers", 16)
+    elif args.workload == "c4p":
+        res = run_decode(args, synth.LLAMA_1B, 64, 8192, synth.TABLE_C4,
+                         "C4 under the configuration of the paper's runs (pages of 16 keys, 4 sink + 2 window keys, pruning at "
+                         "the MLP input, quantiser on the MLP output), page metadata kept by the caller: Llama-3.2-1B-shaped "
+                         "decode step, bf16, 64 sequences x 8192-token KV cache, 16 layers", 16, preset=sol.PAPER_PRESET)
     else:
         res = run_decode(args, synth.LLAMA_8B, 32, 8192, synth.TABLE_C2,
                          "C5-decode: Llama-3.1-8B-shaped decode step, bf16, 32 sequences x 8192-token KV cache, 1 layer", 1)

@@ -167,6 +167,28 @@ int sol_decode_step(sol_ctx *ctx, const sol_model_weights *weights,
                     void *x_out, const int32_t *targets, float *nll_out,
                     void *workspace, size_t ws_bytes, void *stream);
 
+/* Page metadata for decoding under the page rule (cfg.page_size = S >= 2; Appendix "Quest masking": the
+ * element-wise maximum and minimum of the keys of each page). One buffer per layer, device memory owned by
+ * the caller, sol_page_meta_bytes(cfg, n_seq, L_max) bytes, laid out
+ * [n_seq][n_kv_heads][ceil(L_max / S)][2 * head_dim] of cfg.dtype: per page the channel-wise maxima followed
+ * by the minima of the keys written so far. With it a decode step reads 2 / S of the key cache for the page
+ * bounds plus the pages it keeps, instead of every key. bf16, head_dim 64 or 128, 4 query heads per KV head;
+ * anything else: SOL_ERR_UNSUPPORTED (sol_decode_step itself handles every configuration, reading all keys).
+ *
+ * sol_page_meta_build: metadata of keys [0, cache_len[s]) of one layer's key cache (device
+ * [n_seq][n_kv_heads][L_max][head_dim]); pages past cache_len[s] are left untouched.
+ * sol_decode_step_paged: sol_decode_step with page_meta, a host array of n_layers device pointers; the
+ * new token's key is folded into its page in every layer, so the same buffers serve the next step. */
+size_t sol_page_meta_bytes(const sol_model_cfg *cfg, int n_seq, int L_max);
+int sol_page_meta_build(sol_ctx *ctx, const void *k_cache, const int32_t *cache_len, int n_seq, int L_max,
+                        void *page_meta, void *stream);
+int sol_decode_step_paged(sol_ctx *ctx, const sol_model_weights *weights,
+                          const int32_t *token_ids, const void *x_in,
+                          const int32_t *action_ids, const int32_t *cache_len,
+                          void *const *k_cache, void *const *v_cache, void *const *page_meta, int B, int L_max,
+                          void *x_out, const int32_t *targets, float *nll_out,
+                          void *workspace, size_t ws_bytes, void *stream);
+
 /* Teacher-forced pass over G compute schedules that share one token path (Method, "GRPO with
  * per-sequence budget sampling"): for every input b, schedule g and position t,
  *   nll_out[b][g][t] = -log p_t^{a}(targets[b][t])  in nats (Method, Eq. 1, negated),

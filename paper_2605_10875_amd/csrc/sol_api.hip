@@ -361,7 +361,8 @@ static void prepare_actions(sol_ctx *ctx, const int32_t *ids, int64_t M, LayerWs
 
 // Launch sequence of one decoder layer (actions already decoded into w.ra / w.perm).
 static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_in, void *x_out, const int32_t *pos0,
-                      void *kc, void *vc, int n_seq, int T, int L_max, LayerWs &w, hipStream_t st)
+                      void *kc, void *vc, int n_seq, int T, int L_max, LayerWs &w, hipStream_t st,
+                      void *page_meta = nullptr)
 {
     const sol_model_cfg &g = ctx->cfg;
     const int dt = g.dtype;
@@ -406,8 +407,15 @@ static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_i
         const bool fast = mfma && opt.plain();       // the tiled and decode kernels know the plain top-k rule only
         const bool tiled = fast && w.vt && T >= 16 && L_max <= 4096 &&
                            launch_attn_tile(w.qb, kc, vc, w.vt, w.big32, w.o32, w.ra, pos0, n_seq, T, L_max, Hq, Hkv, dh, st);
-        const bool dec = !tiled && fast && T == 1 && pos0 &&
-                         launch_attn_decode(w.qb, kc, vc, w.o32, w.ra, pos0, w.seq_order, n_seq, L_max, Hq, Hkv, dh, ctx->d_flags, st);
+        bool dec = !tiled && fast && T == 1 && pos0 &&
+                   launch_attn_decode(w.qb, kc, vc, w.o32, w.ra, pos0, w.seq_order, n_seq, L_max, Hq, Hkv, dh, ctx->d_flags, st);
+        if (!tiled && !dec && mfma && T == 1 && pos0 && page_meta && opt.page > 1) {
+            // page rule with caller-kept metadata: the new key joins its page, then bounds come from the metadata
+            dec = launch_page_meta_update(kc, pos0, page_meta, n_seq, L_max, Hkv, dh, opt.page, st) &&
+                  launch_attn_decode_paged(w.qb, kc, vc, page_meta, w.o32, w.ra, pos0, w.seq_order, n_seq, L_max, Hq, Hkv,
+                                           dh, opt, ctx->d_flags, st);
+            if (!dec) return fail(ctx, SOL_ERR_UNSUPPORTED, "paged decode attention: more pages or keys than the kernel holds on chip");
+        }
         if (!tiled && !dec &&
             !launch_attn_rows(w.qb, kc, vc, dt, w.o32, w.ra, pos0, n_seq, T, L_max, Hq, Hkv, dh, ctx->d_flags, st, opt))
             return fail(ctx, SOL_ERR_UNSUPPORTED, "attention: L_max too long for the on-chip score rows of this build");
@@ -430,11 +438,19 @@ static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_i
     }
     {   // post norm (+ pruning at the MLP-input site) + quantise (gate/up input)
         STAGE(ctx, ST_NORM_POST, st);
-        const bool prune_in = g.prune_site == 1;     // then: norm to fp32, prune + quantise in place, store
+        bool prune_in = g.prune_site == 1;
+        if (prune_in) {                              // one kernel when the wave-per-row norm covers the shape
+            const bool one = fused_o
+                ? launch_rmsnorm_fq(w.x2, SOL_F32, nullptr, nullptr, lw->w_post_norm, dt, w.h, dt, w.ra, qs & SOL_QS_GATEUP_IN, M, d, g.rms_eps, st, 1, true)
+                : launch_rmsnorm_fq(x_in, dt, w.big32, w.x2, lw->w_post_norm, dt, w.h, dt, w.ra, qs & SOL_QS_GATEUP_IN, M, d, g.rms_eps, st, ns_o, true);
+            if (one) prune_in = false;               // done
+        }
+        // otherwise: norm to fp32, prune + quantise in place, store
         void *hdst = prune_in ? (void *)w.hn32 : w.h;
         const int hdt = prune_in ? SOL_F32 : dt;
         const bool q_here = !prune_in && (qs & SOL_QS_GATEUP_IN);
-        if (fused_o)
+        if (g.prune_site == 1 && !prune_in) {
+        } else if (fused_o)
             launch_rmsnorm_fq(w.x2, SOL_F32, nullptr, nullptr, lw->w_post_norm, dt, hdst, hdt, w.ra, q_here, M, d, g.rms_eps, st);
         else
             launch_rmsnorm_fq(x_in, dt, w.big32, w.x2, lw->w_post_norm, dt, hdst, hdt, w.ra, q_here, M, d, g.rms_eps, st, ns_o);
@@ -560,10 +576,10 @@ static int nll_impl(sol_ctx *ctx, const sol_model_weights *mw, const void *x, in
 // ------------------------------------------------------------------------------------------------
 // decode step
 // ------------------------------------------------------------------------------------------------
-extern "C" int sol_decode_step(sol_ctx *ctx, const sol_model_weights *mw, const int32_t *token_ids, const void *x_in,
-                               const int32_t *action_ids, const int32_t *cache_len, void *const *k_cache,
-                               void *const *v_cache, int B, int L_max, void *x_out, const int32_t *targets,
-                               float *nll_out, void *workspace, size_t ws_bytes, void *stream)
+static int decode_step_impl(sol_ctx *ctx, const sol_model_weights *mw, const int32_t *token_ids, const void *x_in,
+                            const int32_t *action_ids, const int32_t *cache_len, void *const *k_cache,
+                            void *const *v_cache, void *const *page_meta, int B, int L_max, void *x_out,
+                            const int32_t *targets, float *nll_out, void *workspace, size_t ws_bytes, void *stream)
 {
     if (!ctx) return SOL_ERR_INVALID_ARG;
     const sol_model_cfg &g = ctx->cfg;
@@ -575,6 +591,13 @@ extern "C" int sol_decode_step(sol_ctx *ctx, const sol_model_weights *mw, const 
     if (!action_ids || !cache_len || !k_cache || !v_cache) return fail(ctx, SOL_ERR_INVALID_ARG, "a data pointer is NULL");
     for (int l = 0; l < g.n_layers; ++l)
         if (!k_cache[l] || !v_cache[l]) return fail(ctx, SOL_ERR_INVALID_ARG, "a per-layer cache pointer is NULL");
+    if (page_meta) {
+        if (g.page_size < 2 || g.dtype != SOL_BF16 || (g.head_dim != 64 && g.head_dim != 128) ||
+            g.n_q_heads != 4 * g.n_kv_heads)
+            return fail(ctx, SOL_ERR_UNSUPPORTED, "page metadata: needs page_size >= 2, bf16, head_dim 64/128, 4 query heads per KV head");
+        for (int l = 0; l < g.n_layers; ++l)
+            if (!page_meta[l]) return fail(ctx, SOL_ERR_INVALID_ARG, "a per-layer page metadata pointer is NULL");
+    }
     if (nll_out && (!targets || !mw->w_final_norm || !mw->lm_head || g.vocab <= 0))
         return fail(ctx, SOL_ERR_INVALID_ARG, "nll_out needs targets, w_final_norm, lm_head and vocab > 0");
     if (B < 0 || L_max <= 0) return fail(ctx, SOL_ERR_INVALID_ARG, "negative size");
@@ -597,11 +620,56 @@ extern "C" int sol_decode_step(sol_ctx *ctx, const sol_model_weights *mw, const 
         void *dst = (l & 1) ? w.xb : w.xa;
         if (l == g.n_layers - 1 && x_out) dst = x_out;
         if (dst == cur) return fail(ctx, SOL_ERR_INVALID_ARG, "x_in and x_out must not alias");
-        if (int rc = layer_impl(ctx, &mw->layers[l], cur, dst, cache_len, k_cache[l], v_cache[l], B, 1, L_max, w.layer, st))
+        if (int rc = layer_impl(ctx, &mw->layers[l], cur, dst, cache_len, k_cache[l], v_cache[l], B, 1, L_max, w.layer, st,
+                                page_meta ? page_meta[l] : nullptr))
             return rc;
         cur = dst;
     }
     if (nll_out) return nll_impl(ctx, mw, cur, B, w, targets, 1, 1, false, nll_out, st);
+    return SOL_OK;
+}
+
+extern "C" int sol_decode_step(sol_ctx *ctx, const sol_model_weights *mw, const int32_t *token_ids, const void *x_in,
+                               const int32_t *action_ids, const int32_t *cache_len, void *const *k_cache,
+                               void *const *v_cache, int B, int L_max, void *x_out, const int32_t *targets,
+                               float *nll_out, void *workspace, size_t ws_bytes, void *stream)
+{
+    return decode_step_impl(ctx, mw, token_ids, x_in, action_ids, cache_len, k_cache, v_cache, nullptr, B, L_max, x_out,
+                            targets, nll_out, workspace, ws_bytes, stream);
+}
+
+extern "C" int sol_decode_step_paged(sol_ctx *ctx, const sol_model_weights *mw, const int32_t *token_ids, const void *x_in,
+                                     const int32_t *action_ids, const int32_t *cache_len, void *const *k_cache,
+                                     void *const *v_cache, void *const *page_meta, int B, int L_max, void *x_out,
+                                     const int32_t *targets, float *nll_out, void *workspace, size_t ws_bytes,
+                                     void *stream)
+{
+    if (!ctx) return SOL_ERR_INVALID_ARG;
+    if (!page_meta) return fail(ctx, SOL_ERR_INVALID_ARG, "page_meta is NULL");
+    return decode_step_impl(ctx, mw, token_ids, x_in, action_ids, cache_len, k_cache, v_cache, page_meta, B, L_max, x_out,
+                            targets, nll_out, workspace, ws_bytes, stream);
+}
+
+extern "C" size_t sol_page_meta_bytes(const sol_model_cfg *cfg, int n_seq, int L_max)
+{
+    if (!cfg || cfg->page_size < 2 || n_seq <= 0 || L_max <= 0) return 0;
+    const size_t pages = (size_t)(L_max + cfg->page_size - 1) / cfg->page_size;
+    return (size_t)n_seq * cfg->n_kv_heads * pages * 2 * cfg->head_dim * esize(cfg->dtype);
+}
+
+extern "C" int sol_page_meta_build(sol_ctx *ctx, const void *k_cache, const int32_t *cache_len, int n_seq, int L_max,
+                                   void *page_meta, void *stream)
+{
+    if (!ctx) return SOL_ERR_INVALID_ARG;
+    const sol_model_cfg &g = ctx->cfg;
+    if (!k_cache || !cache_len || !page_meta) return fail(ctx, SOL_ERR_INVALID_ARG, "a data pointer is NULL");
+    if (n_seq < 0 || L_max <= 0) return fail(ctx, SOL_ERR_INVALID_ARG, "negative size");
+    if (g.dtype != SOL_BF16 ||
+        !launch_page_meta_build(k_cache, cache_len, page_meta, n_seq, L_max, g.n_kv_heads, g.head_dim, g.page_size,
+                                (hipStream_t)stream))
+        return fail(ctx, SOL_ERR_UNSUPPORTED, "page metadata: needs page_size >= 2, bf16, head_dim 64/128");
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(ctx, SOL_ERR_HIP, std::string("kernel launch: ") + hipGetErrorString(e));
     return SOL_OK;
 }
 

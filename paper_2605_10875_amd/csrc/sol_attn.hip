@@ -823,6 +823,100 @@ __device__ unsigned long long *g_dec_stamps;
 #define DEC_T(i)
 #endif
 
+// The last phases of the decode kernels: sc holds the softmax numerators of the HPB heads ([HPB][lpad], 0 for
+// dropped keys), s_den the per-wave partial denominators ([head][DEC_GW]); o_row receives HPB * DH outputs.
+//   4. o = sum_j p_j v_j, reading only V rows kept by at least one head; 5. reduction over lanes and waves.
+template <int DH>
+__device__ __forceinline__ void decode_pv_tail(float *sc, int lpad, int n, const bf16_t *__restrict__ vbase,
+                                               const float *s_den, float *__restrict__ o_row)
+{
+    constexpr int VEC = 8, LPK = DH / VEC, KPI = DEC_BLOCK / LPK;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // ---- 4. o = sum p_j v_j over rows any head kept ---------------------------------------------------
+    const int ks = tid / LPK, cs = tid - ks * LPK;
+    float acc[DEC_HPB][VEC];
+#pragma unroll
+    for (int hh = 0; hh < DEC_HPB; ++hh)
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[hh][e] = 0.f;
+    constexpr int UV = 4;
+    for (int j0 = ks; j0 < n; j0 += KPI * UV) {
+        float p[UV][DEC_HPB];
+        u32x4_a vv[UV];
+        bool any[UV];
+#pragma unroll
+        for (int u = 0; u < UV; ++u) {
+            const int j = j0 + u * KPI;
+            any[u] = false;
+#pragma unroll
+            for (int hh = 0; hh < DEC_HPB; ++hh) {
+                p[u][hh] = (j < n) ? sc[hh * lpad + j] : 0.f;
+                any[u] |= p[u][hh] != 0.f;
+            }
+            vv[u] = u32x4_a{0u, 0u, 0u, 0u};
+            if (any[u]) vv[u] = *reinterpret_cast<const u32x4_a *>(vbase + (int64_t)j * DH + cs * VEC);
+        }
+#pragma unroll
+        for (int u = 0; u < UV; ++u) {
+            if (any[u]) {
+#pragma unroll
+                for (int wi = 0; wi < 4; ++wi) {
+                    const float v0 = __uint_as_float(vv[u][wi] << 16), v1 = __uint_as_float(vv[u][wi] & 0xFFFF0000u);
+#pragma unroll
+                    for (int hh = 0; hh < DEC_HPB; ++hh) {
+                        acc[hh][2 * wi] = fmaf(p[u][hh], v0, acc[hh][2 * wi]);
+                        acc[hh][2 * wi + 1] = fmaf(p[u][hh], v1, acc[hh][2 * wi + 1]);
+                    }
+                }
+            }
+        }
+    }
+    DEC_T(6)
+    // Reduce over the key slots of a wave (lanes with equal cs) by halving butterflies: at each step a lane
+    // keeps one half of its values and hands the other half to its partner, so the 4 * VEC values per lane
+    // end as 4 * VEC * LPK / 64 fully reduced ones; then across waves in fixed order.
+    float *accf = &acc[0][0];
+    int fbase = 0;                                             // first flattened (head, element) index this lane keeps
+    {
+        int nv = DEC_HPB * VEC;
+#pragma unroll
+        for (int o = LPK; o < 64; o <<= 1) {
+            nv >>= 1;
+            const bool up = (lane & o) != 0;
+#pragma unroll
+            for (int i = 0; i < DEC_HPB * VEC / 2; ++i) {
+                if (i < nv) {
+                    const float keep = up ? accf[i + nv] : accf[i];
+                    const float send = up ? accf[i] : accf[i + nv];
+                    accf[i] = keep + __shfl_xor(send, o, 64);
+                }
+            }
+            fbase += up ? nv : 0;
+        }
+    }
+    constexpr int NKEEP = DEC_HPB * VEC * LPK / 64;            // 4 (head_dim 64) or 8 (head_dim 128)
+    __syncthreads();                                           // all reads of the numerators are done
+    float *ored = sc;                                          // [DEC_WAVES][HPB][DH]
+    {
+        const int hh = fbase / VEC, e0 = fbase - hh * VEC;     // NKEEP values of one head, elements e0..e0+NKEEP-1
+        float *dst = ored + ((size_t)w * DEC_HPB + hh) * DH + (lane & (LPK - 1)) * VEC + e0;
+#pragma unroll
+        for (int i = 0; i < NKEEP; i += 4)
+            *reinterpret_cast<f32x4_a *>(dst + i) = f32x4_a{accf[i], accf[i + 1], accf[i + 2], accf[i + 3]};
+    }
+    __syncthreads();
+    for (int idx = tid; idx < DEC_HPB * DH; idx += DEC_BLOCK) {
+        const int hh = idx / DH;
+        float t = 0.f, dsum = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < DEC_WAVES; ++ww) t += ored[(size_t)ww * DEC_HPB * DH + idx];
+#pragma unroll
+        for (int i = 0; i < DEC_GW; ++i) dsum += s_den[hh * DEC_GW + i];
+        o_row[idx] = t / dsum;
+    }
+}
+
 template <int DH, int SLOTS>
 __global__ void __launch_bounds__(DEC_BLOCK)
 k_attn_decode(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf16_t *__restrict__ vc,
@@ -1046,88 +1140,7 @@ k_attn_decode(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const
     __syncthreads();
     DEC_T(5)
 
-    // ---- 4. o = sum p_j v_j over rows any head kept ---------------------------------------------------
-    const int ks = tid / LPK, cs = tid - ks * LPK;
-    float acc[DEC_HPB][VEC];
-#pragma unroll
-    for (int hh = 0; hh < DEC_HPB; ++hh)
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[hh][e] = 0.f;
-    constexpr int UV = 4;
-    for (int j0 = ks; j0 < n; j0 += KPI * UV) {
-        float p[UV][DEC_HPB];
-        u32x4_a vv[UV];
-        bool any[UV];
-#pragma unroll
-        for (int u = 0; u < UV; ++u) {
-            const int j = j0 + u * KPI;
-            any[u] = false;
-#pragma unroll
-            for (int hh = 0; hh < DEC_HPB; ++hh) {
-                p[u][hh] = (j < n) ? sc[hh * LPAD + j] : 0.f;
-                any[u] |= p[u][hh] != 0.f;
-            }
-            vv[u] = u32x4_a{0u, 0u, 0u, 0u};
-            if (any[u]) vv[u] = *reinterpret_cast<const u32x4_a *>(vbase + (int64_t)j * DH + cs * VEC);
-        }
-#pragma unroll
-        for (int u = 0; u < UV; ++u) {
-            if (any[u]) {
-#pragma unroll
-                for (int wi = 0; wi < 4; ++wi) {
-                    const float v0 = __uint_as_float(vv[u][wi] << 16), v1 = __uint_as_float(vv[u][wi] & 0xFFFF0000u);
-#pragma unroll
-                    for (int hh = 0; hh < DEC_HPB; ++hh) {
-                        acc[hh][2 * wi] = fmaf(p[u][hh], v0, acc[hh][2 * wi]);
-                        acc[hh][2 * wi + 1] = fmaf(p[u][hh], v1, acc[hh][2 * wi + 1]);
-                    }
-                }
-            }
-        }
-    }
-    DEC_T(6)
-    // Reduce over the key slots of a wave (lanes with equal cs) by halving butterflies: at each step a lane
-    // keeps one half of its values and hands the other half to its partner, so the 4 * VEC values per lane
-    // end as 4 * VEC * LPK / 64 fully reduced ones; then across waves in fixed order.
-    float *accf = &acc[0][0];
-    int fbase = 0;                                             // first flattened (head, element) index this lane keeps
-    {
-        int nv = DEC_HPB * VEC;
-#pragma unroll
-        for (int o = LPK; o < 64; o <<= 1) {
-            nv >>= 1;
-            const bool up = (lane & o) != 0;
-#pragma unroll
-            for (int i = 0; i < DEC_HPB * VEC / 2; ++i) {
-                if (i < nv) {
-                    const float keep = up ? accf[i + nv] : accf[i];
-                    const float send = up ? accf[i] : accf[i + nv];
-                    accf[i] = keep + __shfl_xor(send, o, 64);
-                }
-            }
-            fbase += up ? nv : 0;
-        }
-    }
-    constexpr int NKEEP = DEC_HPB * VEC * LPK / 64;            // 4 (head_dim 64) or 8 (head_dim 128)
-    __syncthreads();                                           // all reads of the numerators are done
-    float *ored = sc;                                          // [DEC_WAVES][HPB][DH]
-    {
-        const int hh = fbase / VEC, e0 = fbase - hh * VEC;     // NKEEP values of one head, elements e0..e0+NKEEP-1
-        float *dst = ored + ((size_t)w * DEC_HPB + hh) * DH + (lane & (LPK - 1)) * VEC + e0;
-#pragma unroll
-        for (int i = 0; i < NKEEP; i += 4)
-            *reinterpret_cast<f32x4_a *>(dst + i) = f32x4_a{accf[i], accf[i + 1], accf[i + 2], accf[i + 3]};
-    }
-    __syncthreads();
-    for (int idx = tid; idx < DEC_HPB * DH; idx += DEC_BLOCK) {
-        const int hh = idx / DH;
-        float t = 0.f, dsum = 0.f;
-#pragma unroll
-        for (int ww = 0; ww < DEC_WAVES; ++ww) t += ored[(size_t)ww * DEC_HPB * DH + idx];
-#pragma unroll
-        for (int i = 0; i < DEC_GW; ++i) dsum += s_den[hh * DEC_GW + i];
-        o32[(int64_t)s * (Hq * DH) + (int64_t)h0 * DH + idx] = t / dsum;
-    }
+    decode_pv_tail<DH>(sc, LPAD, n, vbase, s_den, o32 + (int64_t)s * (Hq * DH) + (int64_t)h0 * DH);
     DEC_T(7)
 }
 
@@ -1198,6 +1211,477 @@ bool launch_attn_decode(const void *q, const void *k_cache, const void *v_cache,
     if (L_max <= 8192) { SOL_DEC(32); }
     SOL_DEC(36);                                   // 9216 columns: an 8192-token cache plus the tokens being decoded
 #undef SOL_DEC
+    return false;
+}
+
+// =================================================================================================
+// Decode attention under the page rule (Appendix "Quest masking", page size S > 1), bf16.
+//
+// Page metadata: for every page of S contiguous keys of a (sequence, KV head) one row of 2 * dh bf16 values,
+// [channel-wise maximum | channel-wise minimum] over the keys of the page written so far. The caller owns
+// the buffer ([n_seq][Hkv][ceil(L_max / S)][2 * dh]); k_page_meta_build fills it from a cache,
+// k_page_meta_update folds in the key a decode step has just written. With it the page bound
+//   sum_c max(q_c max_c, q_c min_c) = [max(q, 0) | min(q, 0)] . [max | min]
+// is a dot product of length 2 * dh, i.e. the score kernel's MFMA loop run over metadata rows, and a decode
+// step reads 2 / S of K for the bounds plus the K and V rows of the pages it keeps, not all of K.
+// =================================================================================================
+template <int DH>
+__global__ void __launch_bounds__(256)
+k_page_meta_build(const bf16_t *__restrict__ kc, const int32_t *__restrict__ len, bf16_t *__restrict__ meta, int S,
+                  int L_max, int P_max, int Hkv)
+{
+    constexpr int LPK = DH / 8, PPB = 256 / LPK;               // lanes per page row, pages per workgroup
+    const int s = blockIdx.z, kvh = blockIdx.y;
+    const int u = blockIdx.x * PPB + threadIdx.x / LPK, cs = threadIdx.x % LPK;
+    int n = len[s];
+    n = n < 0 ? 0 : (n > L_max ? L_max : n);
+    const int j0 = u * S;
+    if (u >= P_max || j0 >= n) return;
+    const int j1 = j0 + S < n ? j0 + S : n;
+    const bf16_t *kb = kc + ((int64_t)s * Hkv + kvh) * (int64_t)L_max * DH + cs * 8;
+    float mx[8], mn[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { mx[e] = -INFINITY; mn[e] = INFINITY; }
+    for (int j = j0; j < j1; ++j) {
+        const u32x4_a v = *reinterpret_cast<const u32x4_a *>(kb + (int64_t)j * DH);
+#pragma unroll
+        for (int wi = 0; wi < 4; ++wi) {
+            const float a = __uint_as_float(v[wi] << 16), b = __uint_as_float(v[wi] & 0xFFFF0000u);
+            mx[2 * wi] = fmaxf(mx[2 * wi], a); mn[2 * wi] = fminf(mn[2 * wi], a);
+            mx[2 * wi + 1] = fmaxf(mx[2 * wi + 1], b); mn[2 * wi + 1] = fminf(mn[2 * wi + 1], b);
+        }
+    }
+    bf16_t *mrow = meta + (((int64_t)s * Hkv + kvh) * P_max + u) * (2 * DH) + cs * 8;
+    u32x4_a omx, omn;                                          // extremes of bf16 values are bf16 values: exact
+#pragma unroll
+    for (int wi = 0; wi < 4; ++wi) {
+        omx[wi] = (__float_as_uint(mx[2 * wi]) >> 16) | (__float_as_uint(mx[2 * wi + 1]) & 0xFFFF0000u);
+        omn[wi] = (__float_as_uint(mn[2 * wi]) >> 16) | (__float_as_uint(mn[2 * wi + 1]) & 0xFFFF0000u);
+    }
+    *reinterpret_cast<u32x4_a *>(mrow) = omx;
+    *reinterpret_cast<u32x4_a *>(mrow + DH) = omn;
+}
+
+// the key at position pos[s] (just written) joins its page: first key of a page initialises the row
+template <int DH>
+__global__ void __launch_bounds__(64)
+k_page_meta_update(const bf16_t *__restrict__ kc, const int32_t *__restrict__ pos, bf16_t *__restrict__ meta, int S,
+                   int L_max, int P_max, int Hkv)
+{
+    constexpr int LPK = DH / 8;
+    const int s = blockIdx.y, kvh = blockIdx.x, cs = threadIdx.x;
+    const int p = pos[s];
+    if (cs >= LPK || p < 0 || p >= L_max) return;
+    const int u = p / S;
+    const u32x4_a v = *reinterpret_cast<const u32x4_a *>(kc + (((int64_t)s * Hkv + kvh) * L_max + p) * DH + cs * 8);
+    bf16_t *mrow = meta + (((int64_t)s * Hkv + kvh) * P_max + u) * (2 * DH) + cs * 8;
+    u32x4_a omx = v, omn = v;
+    if (p != u * S) {
+        const u32x4_a amx = *reinterpret_cast<const u32x4_a *>(mrow), amn = *reinterpret_cast<const u32x4_a *>(mrow + DH);
+#pragma unroll
+        for (int wi = 0; wi < 4; ++wi) {
+            const float a = __uint_as_float(v[wi] << 16), b = __uint_as_float(v[wi] & 0xFFFF0000u);
+            const float xa = fmaxf(a, __uint_as_float(amx[wi] << 16)), xb = fmaxf(b, __uint_as_float(amx[wi] & 0xFFFF0000u));
+            const float na = fminf(a, __uint_as_float(amn[wi] << 16)), nb = fminf(b, __uint_as_float(amn[wi] & 0xFFFF0000u));
+            omx[wi] = (__float_as_uint(xa) >> 16) | (__float_as_uint(xb) & 0xFFFF0000u);
+            omn[wi] = (__float_as_uint(na) >> 16) | (__float_as_uint(nb) & 0xFFFF0000u);
+        }
+    }
+    *reinterpret_cast<u32x4_a *>(mrow) = omx;
+    *reinterpret_cast<u32x4_a *>(mrow + DH) = omn;
+}
+
+bool launch_page_meta_build(const void *k_cache, const int32_t *len, void *meta, int n_seq, int L_max, int Hkv, int dh,
+                            int S, hipStream_t st)
+{
+    if (n_seq <= 0) return true;
+    if (S < 2 || (dh != 64 && dh != 128)) return false;
+    const int P_max = (L_max + S - 1) / S;
+    const int ppb = 256 / (dh / 8);
+    const dim3 grid((unsigned)((P_max + ppb - 1) / ppb), Hkv, n_seq);
+    if (dh == 64) hipLaunchKernelGGL(k_page_meta_build<64>, grid, dim3(256), 0, st, (const bf16_t *)k_cache, len, (bf16_t *)meta, S, L_max, P_max, Hkv);
+    else hipLaunchKernelGGL(k_page_meta_build<128>, grid, dim3(256), 0, st, (const bf16_t *)k_cache, len, (bf16_t *)meta, S, L_max, P_max, Hkv);
+    return true;
+}
+
+bool launch_page_meta_update(const void *k_cache, const int32_t *pos, void *meta, int n_seq, int L_max, int Hkv, int dh,
+                             int S, hipStream_t st)
+{
+    if (n_seq <= 0) return true;
+    if (S < 2 || (dh != 64 && dh != 128)) return false;
+    const int P_max = (L_max + S - 1) / S;
+    if (dh == 64) hipLaunchKernelGGL(k_page_meta_update<64>, dim3(Hkv, n_seq), dim3(64), 0, st, (const bf16_t *)k_cache, pos, (bf16_t *)meta, S, L_max, P_max, Hkv);
+    else hipLaunchKernelGGL(k_page_meta_update<128>, dim3(Hkv, n_seq), dim3(64), 0, st, (const bf16_t *)k_cache, pos, (bf16_t *)meta, S, L_max, P_max, Hkv);
+    return true;
+}
+
+// [max(q, 0) | min(q, 0)] of a pair of packed bf16 values: element e of the doubled query row
+__device__ __forceinline__ uint32_t q_split_pair(uint32_t x, bool neg_half)
+{
+    const bool nlo = (x & 0x8000u) != 0u, nhi = (x & 0x80000000u) != 0u;
+    const uint32_t lo = (nlo == neg_half) ? (x & 0xFFFFu) : 0u;
+    const uint32_t hi = (nhi == neg_half) ? (x & 0xFFFF0000u) : 0u;
+    return lo | hi;
+}
+
+// One workgroup of 16 waves per (sequence, KV head), the 4 query heads of the group together:
+//   1. page bounds on MFMA from the metadata rows (fp32, to LDS);
+//   2. per head, the threshold of the top ceil(b / S) bounds (same joint search as the per-key kernel, over
+//      pages), ties to the lower page; the kept pages of the 4 heads as bit flags in LDS;
+//   3. scores of the keys of kept pages and of the sink / window keys (K tiles no head needs are skipped),
+//      -inf elsewhere;  4. softmax numerators;  5. V rows gathered where any head kept the key.
+template <int DH, int SLOTS>
+__global__ void __launch_bounds__(DEC_BLOCK)
+k_attn_decode_paged(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf16_t *__restrict__ vc,
+                    const bf16_t *__restrict__ meta, float *__restrict__ o32, const RowAct *__restrict__ ra,
+                    const int32_t *__restrict__ cache_len, const int32_t *__restrict__ seq_order, int L_max, int P_max,
+                    int lpad, int Hq, int Hkv, float scale, AttnOpts opt, int *flags)
+{
+    constexpr int KK = DH / 32, KK2 = 2 * KK, SLICE = SLOTS * 64, PPAD = SLICE * DEC_GW, NJ = SLOTS / 4;
+    extern __shared__ __align__(16) float sc[];               // page bounds [HPB][PPAD], then scores [HPB][lpad], then partial O
+    __shared__ int s_pk[PPAD];                                 // bit h: head h keeps the page
+    __shared__ int s_cnt[2][DEC_WAVES];
+    __shared__ uint32_t s_min[DEC_WAVES], s_max[DEC_WAVES];
+    __shared__ int s_done[2][DEC_HPB];
+    __shared__ int s_gt[DEC_WAVES];
+    __shared__ float s_den[DEC_WAVES], s_mx[DEC_WAVES];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kvh = blockIdx.x;
+    const int s = __builtin_amdgcn_readfirstlane(seq_order ? seq_order[blockIdx.y] : (int)blockIdx.y);
+    const int p0 = __builtin_amdgcn_readfirstlane(cache_len[s]);
+    if (p0 < 0 || p0 + 1 > L_max) {
+        if (tid == 0) atomicOr(flags, FLAG_CACHE_OVERFLOW);
+        return;
+    }
+    const int n = p0 + 1;
+    const int S = opt.page;
+    const int n_pages = (n + S - 1) / S;
+    const int h0 = kvh * DEC_HPB;
+    const bf16_t *kbase = kc + ((int64_t)s * Hkv + kvh) * (int64_t)L_max * DH;
+    const bf16_t *vbase = vc + ((int64_t)s * Hkv + kvh) * (int64_t)L_max * DH;
+    const bf16_t *mbase = meta + ((int64_t)s * Hkv + kvh) * (int64_t)P_max * (2 * DH);
+    const int l16 = lane & 15, lg = lane >> 4;
+    const RowAct act = ra[s];
+    const int b = __builtin_amdgcn_readfirstlane(budget_ceil(act.keep_num, act.keep_den, n));
+    int np = (b + S - 1) / S;
+    np = np < n_pages ? np : n_pages;
+    const bool all_pages = b >= n || np >= n_pages;            // every page (or, b >= n, every key) is kept
+    const bool dense = b >= n;
+    const int head = w / DEC_GW, wg = w - head * DEC_GW;
+
+    for (int u = tid; u < PPAD; u += DEC_BLOCK) s_pk[u] = 0;
+
+    // the query heads as MFMA B operand (column = head)
+    u32x4_a qraw[KK];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+        qraw[kk] = u32x4_a{0u, 0u, 0u, 0u};
+        if (l16 < DEC_HPB)
+            qraw[kk] = *reinterpret_cast<const u32x4_a *>(q + (int64_t)s * (Hq * DH) + (int64_t)(h0 + l16) * DH + kk * 32 + lg * 8);
+    }
+
+    if (!all_pages) {
+        // ---- 1. page bounds ---------------------------------------------------------------------
+        bf16x8_a qq[KK2];                                      // [max(q, 0) | min(q, 0)], 2 * DH long
+#pragma unroll
+        for (int kk = 0; kk < KK2; ++kk) {
+            u32x4_a v;
+#pragma unroll
+            for (int wi = 0; wi < 4; ++wi) v[wi] = q_split_pair(qraw[kk % KK][wi], kk >= KK);
+            qq[kk] = __builtin_bit_cast(bf16x8_a, v);
+        }
+        const int n_pt = (n_pages + 15) >> 4;
+        constexpr int U = 2;
+        for (int pt0 = w; pt0 < n_pt; pt0 += DEC_WAVES * U) {
+            bf16x8_a mf[U][KK2];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                int pg = (pt0 + u * DEC_WAVES) * 16 + l16;
+                if (pg >= n_pages) pg = n_pages - 1;
+                const bf16_t *mp = mbase + (int64_t)pg * (2 * DH) + lg * 8;
+#pragma unroll
+                for (int kk = 0; kk < KK2; ++kk)
+                    mf[u][kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(mp + kk * 32));
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int pt = pt0 + u * DEC_WAVES;
+                if (pt < n_pt) {
+                    floatx4_a acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int kk = 0; kk < KK2; ++kk)
+                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(mf[u][kk], qq[kk], acc, 0, 0, 0);
+                    if (l16 < DEC_HPB) {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) sc[l16 * PPAD + pt * 16 + lg * 4 + r] = acc[r];
+                    }
+                }
+            }
+        }
+        __syncthreads();
+
+        // ---- 2. the np best pages of each head ------------------------------------------------------
+        const int base = wg * SLICE;
+        int n_loc = n_pages - base;
+        n_loc = n_loc < 0 ? 0 : (n_loc > SLICE ? SLICE : n_loc);
+        float *row = sc + head * PPAD + base;
+        uint32_t key[SLOTS];
+        uint32_t kmax = 0u, kmin = 0xFFFFFFFFu;
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            if (256 * j < n_loc) {
+                const f32x4_a v = *reinterpret_cast<const f32x4_a *>(row + 256 * j + 4 * lane);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const bool valid = 256 * j + 4 * lane + e < n_loc;
+                    const uint32_t kv = valid ? score_key(v[e]) : 0u;
+                    key[4 * j + e] = kv;
+                    kmax = kv > kmax ? kv : kmax;
+                    kmin = (valid && kv < kmin) ? kv : kmin;
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) key[4 * j + e] = 0u;
+            }
+        }
+        kmax = wave_max_u32(kmax);
+        kmin = wave_min_u32(kmin);
+        if (lane == 0) { s_max[w] = kmax; s_min[w] = kmin; }
+        __syncthreads();
+        uint32_t lo = 0xFFFFFFFFu, hi = 0u;
+#pragma unroll
+        for (int i = 0; i < DEC_GW; ++i) {
+            const uint32_t a = s_min[head * DEC_GW + i], c = s_max[head * DEC_GW + i];
+            lo = a < lo ? a : lo;
+            hi = c > hi ? c : hi;
+        }
+        lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)lo);
+        hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)hi);
+        uint32_t thr = 1u;
+        bool done = false, exact = true;
+        // invariant: count(key >= lo) >= np, count(key >= hi + 1) < np; regula falsi with the Illinois correction
+        // on g(x) = count(key >= x) - np + 1/2, the midpoint of the key range after 12 rounds or a bad guess
+        float flo = score_unkey(lo), fhi = score_unkey(hi), glo = (float)(n_pages - np) + 0.5f, ghi = 0.5f - (float)np;
+        int side = 0;
+        for (int it = 0; it < 48; ++it) {
+            const int par = it & 1;
+            uint32_t mid = 0u;
+            if (!done) {
+                const float fp = __builtin_fmaf(fhi - flo, glo * __builtin_amdgcn_rcpf(glo - ghi), flo);
+                mid = (uint32_t)__builtin_amdgcn_readfirstlane((int)score_key(fp));
+                if (it >= 12 || !(mid > lo && mid <= hi)) mid = lo + ((hi - lo + 1u) >> 1);
+                const int c = lo < hi ? wave_count_ge<SLOTS>(key, n_loc, mid) : 0;
+                if (lane == 0) s_cnt[par][w] = c;
+            }
+            if (wg == 0 && lane == 0) s_done[par][head] = done || lo >= hi;
+            __syncthreads();
+            if (!done) {
+                if (lo >= hi) { thr = lo; exact = false; done = true; }
+                else {
+                    int cnt = 0;
+#pragma unroll
+                    for (int i = 0; i < DEC_GW; ++i) cnt += s_cnt[par][head * DEC_GW + i];
+                    cnt = __builtin_amdgcn_readfirstlane(cnt);
+                    const float g = (float)(cnt - np) + 0.5f;
+                    if (cnt == np) { thr = mid; done = true; }
+                    else if (cnt > np) {
+                        lo = mid; flo = score_unkey(mid); glo = g;
+                        if (side > 0) ghi *= 0.5f;
+                        side = 1;
+                    } else {
+                        hi = mid - 1u; fhi = score_unkey(hi); ghi = g;
+                        if (side < 0) glo *= 0.5f;
+                        side = -1;
+                    }
+                }
+            }
+            const bool all_done =
+                __builtin_amdgcn_readfirstlane(s_done[par][0] & s_done[par][1] & s_done[par][2] & s_done[par][3]) != 0;
+            if (all_done) break;
+        }
+        // ties at the threshold go to the lower pages: the first wave of the head walks the row
+        {
+            const bool need = !exact;
+            int gt = 0;
+            if (need) {
+#pragma unroll
+                for (int i = 0; i < SLOTS; ++i) gt += __popcll(__ballot(key[i] > thr));
+            }
+            if (lane == 0) s_gt[w] = gt;
+            __syncthreads();
+            if (need && wg == 0) {
+                int quota = np;
+#pragma unroll
+                for (int i = 0; i < DEC_GW; ++i) quota -= s_gt[head * DEC_GW + i];
+                quota = __builtin_amdgcn_readfirstlane(quota);
+                float *hrow = sc + head * PPAD;
+                int taken = 0;
+                for (int c0 = 0; c0 < n_pages; c0 += 64) {
+                    const int col = c0 + lane;
+                    const bool tie = col < n_pages && score_key(hrow[col]) == thr;
+                    const unsigned long long bal = __ballot(tie);
+                    const int rank = taken + __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0));
+                    if (tie && rank >= quota) hrow[col] = -INFINITY;
+                    taken += __popcll(bal);
+                }
+            }
+            __syncthreads();
+        }
+        // kept pages of this head -> flags
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            if (256 * j < n_loc) {
+                const f32x4_a v = *reinterpret_cast<const f32x4_a *>(row + 256 * j + 4 * lane);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int u = 256 * j + 4 * lane + e;
+                    if (u < n_loc && score_key(v[e]) >= thr) atomicOr(&s_pk[base + u], 1 << head);
+                }
+            }
+        }
+    }
+    __syncthreads();                                           // flags complete; the page bounds in sc are dead
+
+    // ---- 3. scores of the kept keys ---------------------------------------------------------------
+    const int sink_end = opt.n_sink < n ? opt.n_sink : n;
+    int win_begin = n - opt.n_window;
+    win_begin = win_begin < sink_end ? sink_end : win_begin;
+    {
+        bf16x8_a qf[KK];
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) qf[kk] = __builtin_bit_cast(bf16x8_a, qraw[kk]);
+        const int n_kt = (n + 15) >> 4;
+        constexpr int U = 4;
+        for (int kt0 = w; kt0 < n_kt; kt0 += DEC_WAVES * U) {
+            bf16x8_a kf[U][KK];
+            bool need[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int kt = kt0 + u * DEC_WAVES;
+                const int j0 = kt * 16, j1 = j0 + 15 < n - 1 ? j0 + 15 : n - 1;
+                bool nd = false;
+                if (kt < n_kt) {
+                    nd = all_pages || j0 < sink_end || j1 >= win_begin;
+                    if (!nd)
+                        for (int pg = j0 / S; pg <= j1 / S; ++pg) nd |= s_pk[pg] != 0;
+                }
+                need[u] = __builtin_amdgcn_readfirstlane((int)nd) != 0;
+                if (need[u]) {
+                    int key = j0 + l16;
+                    if (key >= n) key = n - 1;
+                    const bf16_t *kp = kbase + (int64_t)key * DH + lg * 8;
+#pragma unroll
+                    for (int kk = 0; kk < KK; ++kk)
+                        kf[u][kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(kp + kk * 32));
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int kt = kt0 + u * DEC_WAVES;
+                if (kt < n_kt) {
+                    floatx4_a acc = {0.f, 0.f, 0.f, 0.f};
+                    if (need[u]) {
+#pragma unroll
+                        for (int kk = 0; kk < KK; ++kk)
+                            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[u][kk], qf[kk], acc, 0, 0, 0);
+                    }
+                    if (l16 < DEC_HPB) {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const int j = kt * 16 + lg * 4 + r;
+                            bool kept = false;
+                            if (need[u] && j < n)
+                                kept = dense || j < sink_end || j >= win_begin || all_pages || ((s_pk[j / S] >> l16) & 1) != 0;
+                            sc[l16 * lpad + j] = kept ? acc[r] * scale : -INFINITY;
+                        }
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- 4. softmax numerators over the kept keys ---------------------------------------------------
+    {
+        float *row = sc + head * lpad;
+        float mx = -INFINITY;
+        for (int j0 = wg * 256; j0 < n; j0 += DEC_GW * 256) {
+            const f32x4_a v = *reinterpret_cast<const f32x4_a *>(row + j0 + 4 * lane);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) mx = (j0 + 4 * lane + e < n) ? fmaxf(mx, v[e]) : mx;
+        }
+        mx = wave_reduce_dpp<float>(mx, -INFINITY, [](float x, float y) { return fmaxf(x, y); });
+        if (lane == 0) s_mx[w] = mx;
+        __syncthreads();
+        mx = s_mx[head * DEC_GW];
+#pragma unroll
+        for (int i = 1; i < DEC_GW; ++i) mx = fmaxf(mx, s_mx[head * DEC_GW + i]);
+        float den = 0.f;
+        for (int j0 = wg * 256; j0 < n; j0 += DEC_GW * 256) {
+            const f32x4_a v = *reinterpret_cast<const f32x4_a *>(row + j0 + 4 * lane);
+            f32x4_a p;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                p[e] = (j0 + 4 * lane + e < n) ? __expf(v[e] - mx) : 0.f;     // exp(-inf) = 0 for dropped keys
+                den += p[e];
+            }
+            *reinterpret_cast<f32x4_a *>(row + j0 + 4 * lane) = p;
+        }
+        den = wave_sum_dpp(den);
+        if (lane == 0) s_den[w] = den;
+        __syncthreads();
+    }
+    decode_pv_tail<DH>(sc, lpad, n, vbase, s_den, o32 + (int64_t)s * (Hq * DH) + (int64_t)h0 * DH);
+}
+
+template <int DH, int SLOTS>
+static bool launch_attn_decode_paged_t(const void *q, const void *kc, const void *vc, const void *meta, float *o32,
+                                       const RowAct *ra, const int32_t *cache_len, const int32_t *seq_order, int B,
+                                       int L_max, int P_max, int lpad, int Hq, int Hkv, AttnOpts opt, int *flags,
+                                       hipStream_t st)
+{
+    auto kern = k_attn_decode_paged<DH, SLOTS>;
+    size_t lds = (size_t)DEC_HPB * lpad * 4;
+    const size_t pg = (size_t)DEC_HPB * SLOTS * 64 * DEC_GW * 4, red = (size_t)DEC_WAVES * DEC_HPB * DH * 4;
+    lds = lds < pg ? pg : lds;
+    lds = lds < red ? red : lds;
+    if (lds + (size_t)SLOTS * 64 * DEC_GW * 4 + 1024 > 160 * 1024) return false;
+    static bool attr_done = false;
+    if (!attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                150 * 1024) != hipSuccess)
+            return false;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(Hkv, B), dim3(DEC_BLOCK), lds, st, (const bf16_t *)q, (const bf16_t *)kc,
+                       (const bf16_t *)vc, (const bf16_t *)meta, o32, ra, cache_len, seq_order, L_max, P_max, lpad, Hq, Hkv,
+                       1.0f / sqrtf((float)DH), opt, flags);
+    return true;
+}
+
+// One query per sequence under the page rule, with caller-kept page metadata (page_meta_build / _update).
+// bf16, 4 query heads per KV head, head_dim 64 / 128, at most 3072 pages and about 9000 keys.
+bool launch_attn_decode_paged(const void *q, const void *k_cache, const void *v_cache, const void *meta, float *o32,
+                              const RowAct *ra, const int32_t *cache_len, const int32_t *seq_order, int B, int L_max, int Hq,
+                              int Hkv, int dh, AttnOpts opt, int *flags, hipStream_t st)
+{
+    if (B <= 0) return true;
+    if (!cache_len || !meta || opt.page < 2 || Hq != DEC_HPB * Hkv || (dh != 64 && dh != 128)) return false;
+    const int P_max = (L_max + opt.page - 1) / opt.page;
+    const int lpad = (L_max + 1023) & ~1023;                   // rows are walked in steps of 4 waves x 256 columns
+    if ((size_t)DEC_HPB * lpad * 4 > 148 * 1024) return false;
+#define SOL_DECP(SL)                                                                                            \
+    if (P_max <= SL * 64 * DEC_GW)                                                                              \
+        return dh == 64 ? launch_attn_decode_paged_t<64, SL>(q, k_cache, v_cache, meta, o32, ra, cache_len, seq_order, B, \
+                                                             L_max, P_max, lpad, Hq, Hkv, opt, flags, st)       \
+                        : launch_attn_decode_paged_t<128, SL>(q, k_cache, v_cache, meta, o32, ra, cache_len, seq_order, B, \
+                                                              L_max, P_max, lpad, Hq, Hkv, opt, flags, st)
+    SOL_DECP(4);
+    SOL_DECP(8);
+    SOL_DECP(12);
+#undef SOL_DECP
     return false;
 }
 

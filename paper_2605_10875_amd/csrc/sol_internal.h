@@ -26,9 +26,12 @@ void launch_bucket_sort(const int32_t *row_bucket, int64_t M, int n_buckets, int
                         int32_t *bucket_off, hipStream_t st);
 // h = FQ(RMSNorm(x [+ add]) * w, bits) ; optionally writes xsum = x + add (fp32).
 // x: [M][d] of x_dtype; add: fp32 [M][d] or NULL; ra NULL or quant disabled => no quantiser.
-void launch_rmsnorm_fq(const void *x, int x_dtype, const float *add, float *xsum, const void *w, int w_dtype,
+// prune: between the norm and the quantiser keep the ra.m largest magnitudes of the row (pruning at the MLP
+// input); only the one-wave-per-row kernel does it: false (nothing launched) when that kernel does not cover the
+// types / width, and the caller then prunes with launch_prune_fq on an fp32 copy.
+bool launch_rmsnorm_fq(const void *x, int x_dtype, const float *add, float *xsum, const void *w, int w_dtype,
                        void *h, int h_dtype, const RowAct *ra, bool quant, int64_t M, int d, float eps,
-                       hipStream_t st, int nsplit = 1);
+                       hipStream_t st, int nsplit = 1, bool prune = false);
 // out = FQ(in, bits) row-wise; in fp32 [M][n] -> out dtype.
 void launch_fq_rows(const float *in, void *out, int out_dtype, const RowAct *ra, bool quant, int64_t M, int n,
                     hipStream_t st);
@@ -122,6 +125,17 @@ void launch_seq_order(const int32_t *cache_len, int B, int32_t *order, hipStream
 bool launch_attn_decode(const void *q, const void *k_cache, const void *v_cache, float *o32, const RowAct *ra,
                         const int32_t *cache_len, const int32_t *seq_order, int B, int L_max, int Hq, int Hkv, int dh,
                         int *flags, hipStream_t st);
+// Page metadata of a bf16 K cache for the page rule (page size S >= 2): meta [n_seq][Hkv][ceil(L_max/S)][2*dh],
+// per page the channel-wise [maximum | minimum] of its keys. build: from keys [0, len[s]); update: the key at
+// pos[s] joins its page. head_dim 64 / 128.
+bool launch_page_meta_build(const void *k_cache, const int32_t *len, void *meta, int n_seq, int L_max, int Hkv, int dh,
+                            int S, hipStream_t st);
+bool launch_page_meta_update(const void *k_cache, const int32_t *pos, void *meta, int n_seq, int L_max, int Hkv, int dh,
+                             int S, hipStream_t st);
+// Decode attention under the page rule with that metadata (which must already include the new key).
+bool launch_attn_decode_paged(const void *q, const void *k_cache, const void *v_cache, const void *meta, float *o32,
+                              const RowAct *ra, const int32_t *cache_len, const int32_t *seq_order, int B, int L_max, int Hq,
+                              int Hkv, int dh, AttnOpts opt, int *flags, hipStream_t st);
 // Batched bf16 attention (L_max <= 4096, head_dim 64 or 128, 1/2/4/8 query heads per KV head): a threshold
 // kernel followed by a flash-style masked softmax * V kernel. vt is workspace for the transposed V copy
 // (n_seq * Hkv * dh * attn_tile_lpadv(L_max) elements), sel_ws for the per-(row, head) thresholds

@@ -161,11 +161,89 @@ k_rmsnorm_fq(const TX *__restrict__ x, const float *__restrict__ add, int nsplit
 typedef uint32_t u32x4_w __attribute__((ext_vector_type(4)));
 typedef float f32x4_w __attribute__((ext_vector_type(4)));
 
+// Keeps the m entries of largest magnitude of a row held by one wave (lane l holds elements
+// (c * 64 + l) * 8 .. + 8 of chunk c) and zeroes the rest; equal magnitudes go to the lower channel.
+// |x| of an fp32 orders like its bit pattern, so the m-th largest magnitude is found on integer keys: pivots
+// by regula falsi (Illinois) on g(t) = #(|x| >= t) - m + 1/2 in the value domain, the midpoint of the key range
+// after 12 steps or a guess outside the bracket.
+template <int CH>
+__device__ __forceinline__ void wave_keep_topm(float (&v)[CH][8], int m, int lane)
+{
+    constexpr int D = CH * 512;
+    auto count_ge = [&](uint32_t t) -> int {
+        int cnt = 0;
+#pragma unroll
+        for (int c = 0; c < CH; ++c)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) cnt += __popcll(__ballot((__float_as_uint(v[c][e]) & 0x7FFFFFFFu) >= t));
+        return cnt;
+    };
+    uint32_t kmax = 0u;
+#pragma unroll
+    for (int c = 0; c < CH; ++c)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t k = __float_as_uint(v[c][e]) & 0x7FFFFFFFu;
+            kmax = k > kmax ? k : kmax;
+        }
+    uint32_t lo = 0u, hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)wave_max_u32(kmax));
+    // invariant: count(key >= lo) >= m, count(key >= hi + 1) < m
+    float glo = (float)(D - m) + 0.5f, ghi = 0.5f - (float)m;
+    int side = 0;
+    bool exact = false;
+    for (int it = 0; lo < hi; ++it) {
+        const float flo = __uint_as_float(lo), fhi = __uint_as_float(hi);
+        const float fp = __builtin_fmaf(fhi - flo, glo * __builtin_amdgcn_rcpf(glo - ghi), flo);
+        uint32_t mid = (uint32_t)__builtin_amdgcn_readfirstlane((int)(__float_as_uint(fp) & 0x7FFFFFFFu));
+        if (it >= 12 || !(mid > lo && mid <= hi)) mid = lo + ((hi - lo + 1u) >> 1);
+        const int cnt = count_ge(mid);
+        if (cnt == m) { lo = mid; exact = true; break; }
+        const float g = (float)(cnt - m) + 0.5f;
+        if (cnt > m) {
+            lo = mid; glo = g;
+            if (side > 0) ghi *= 0.5f;
+            side = 1;
+        } else {
+            hi = mid - 1u; ghi = g;
+            if (side < 0) glo *= 0.5f;
+            side = -1;
+        }
+    }
+    const uint32_t thr = lo;
+    int quota = D;                                           // ties kept, in channel order
+    if (!exact) {
+        const int n_ge = count_ge(thr);
+        if (n_ge > m) quota = m - count_ge(thr + 1u);
+    }
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        int before = 0, total = 0;                           // ties in lower lanes / in the whole chunk
+        bool tie[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            tie[e] = (__float_as_uint(v[c][e]) & 0x7FFFFFFFu) == thr;
+            const unsigned long long bal = __ballot(tie[e]);
+            before += __popcll(bal & lt_mask);
+            total += __popcll(bal);
+        }
+        int mine = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t k = __float_as_uint(v[c][e]) & 0x7FFFFFFFu;
+            const bool keep = k > thr || (tie[e] && before + mine < quota);
+            mine += tie[e];
+            if (!keep) v[c][e] = 0.f;
+        }
+        quota = quota > total ? quota - total : 0;
+    }
+}
+
 template <typename TX, int CH, bool ADD>
 __global__ void __launch_bounds__(256)
 k_rmsnorm_fq_wave(const TX *__restrict__ x, const float *__restrict__ add, int nsplit, int64_t split_stride,
                   float *__restrict__ xsum, const bf16_t *__restrict__ w, bf16_t *__restrict__ h,
-                  const RowAct *__restrict__ ra, int quant, int64_t M, float eps)
+                  const RowAct *__restrict__ ra, int quant, int64_t M, float eps, int prune)
 {
     constexpr int D = CH * 512;
     const int lane = threadIdx.x & 63;
@@ -220,6 +298,10 @@ k_rmsnorm_fq_wave(const TX *__restrict__ x, const float *__restrict__ add, int n
             v[c][2 * e + 1] = v[c][2 * e + 1] * rinv * __uint_as_float(t[e] & 0xFFFF0000u);
             amax = fmaxf(amax, fmaxf(fabsf(v[c][2 * e]), fabsf(v[c][2 * e + 1])));
         }
+    }
+    if (prune) {                                             // pruning at the MLP input: ra.m of the D channels stay
+        const int m = __builtin_amdgcn_readfirstlane(ra[r].m);
+        if (m < D) wave_keep_topm<CH>(v, m, lane);           // (the largest magnitude stays, so amax is unchanged)
     }
     const int bits = (quant && ra) ? ra[r].bits : 16;
     if (bits < 16) {
@@ -287,25 +369,27 @@ static void rmsnorm_dispatch3(const void *x, const float *add, int nsplit, float
                        (const TX *)x, add, nsplit, M * (int64_t)d, xsum, (const TW *)w, (TH *)h, ra, quant ? 1 : 0, d, eps);
 }
 
-void launch_rmsnorm_fq(const void *x, int x_dtype, const float *add, float *xsum, const void *w, int w_dtype, void *h,
-                       int h_dtype, const RowAct *ra, bool quant, int64_t M, int d, float eps, hipStream_t st, int nsplit)
+bool launch_rmsnorm_fq(const void *x, int x_dtype, const float *add, float *xsum, const void *w, int w_dtype, void *h,
+                       int h_dtype, const RowAct *ra, bool quant, int64_t M, int d, float eps, hipStream_t st, int nsplit,
+                       bool prune)
 {
-    if (M <= 0) return;
+    if (M <= 0) return true;
     if (w_dtype == 1 && h_dtype == 1 && (d == 2048 || d == 4096) && (add != nullptr) == (xsum != nullptr)) {
         const dim3 grid((unsigned)((M + 3) / 4));
         const int64_t ss = M * (int64_t)d;
 #define SOL_NORM_WAVE(TX, CH)                                                                                   \
     if (add)                                                                                                    \
         hipLaunchKernelGGL((k_rmsnorm_fq_wave<TX, CH, true>), grid, dim3(256), 0, st, (const TX *)x, add, nsplit, ss, \
-                           xsum, (const bf16_t *)w, (bf16_t *)h, ra, quant ? 1 : 0, M, eps);                    \
+                           xsum, (const bf16_t *)w, (bf16_t *)h, ra, quant ? 1 : 0, M, eps, prune ? 1 : 0);     \
     else                                                                                                        \
         hipLaunchKernelGGL((k_rmsnorm_fq_wave<TX, CH, false>), grid, dim3(256), 0, st, (const TX *)x, add, nsplit, ss, \
-                           xsum, (const bf16_t *)w, (bf16_t *)h, ra, quant ? 1 : 0, M, eps)
+                           xsum, (const bf16_t *)w, (bf16_t *)h, ra, quant ? 1 : 0, M, eps, prune ? 1 : 0)
         if (x_dtype == 1) { if (d == 2048) { SOL_NORM_WAVE(bf16_t, 4); } else { SOL_NORM_WAVE(bf16_t, 8); } }
         else { if (d == 2048) { SOL_NORM_WAVE(float, 4); } else { SOL_NORM_WAVE(float, 8); } }
 #undef SOL_NORM_WAVE
-        return;
+        return true;
     }
+    if (prune) return false;                                 // the caller prunes with the row kernels instead
     const int key = (x_dtype << 2) | (w_dtype << 1) | h_dtype;
     switch (key) {
     case 0: rmsnorm_dispatch3<float, float, float>(x, add, nsplit, xsum, w, h, ra, quant, M, d, eps, st); break;
@@ -315,6 +399,7 @@ void launch_rmsnorm_fq(const void *x, int x_dtype, const float *add, float *xsum
     case 2: rmsnorm_dispatch3<float, bf16_t, float>(x, add, nsplit, xsum, w, h, ra, quant, M, d, eps, st); break;
     default: break;   // no other combination is ever requested by the host code
     }
+    return true;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -751,10 +836,71 @@ k_resid_out_fq(const float *__restrict__ x2, const float *__restrict__ z, int ns
     }
 }
 
+// bf16 rows of 2048 / 4096: one workgroup of four waves per row, wave v holding chunks v, v + 4, .. of 512 values
+// in registers (the K-split partial sums of a decode step are many: four waves keep four times the loads in flight)
+template <int CH>
+__global__ void __launch_bounds__(256)
+k_resid_out_fq_wave(const float *__restrict__ x2, const float *__restrict__ z, int nsplit, int64_t split_stride,
+                    bf16_t *__restrict__ out, const RowAct *__restrict__ ra, int64_t M)
+{
+    constexpr int D = CH * 512, CW = CH / 4;
+    __shared__ float s_amax[4];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int64_t r = blockIdx.x;
+    float v[CW][8];
+    float amax = 0.f;
+#pragma unroll
+    for (int cc = 0; cc < CW; ++cc) {
+        const int c = wv + 4 * cc;
+        float t[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
+        for (int sp = 0; sp < nsplit; ++sp) {               // K-split partial sums, fixed order
+            const float *zp = z + sp * split_stride + r * D + c * 512 + lane * 8;
+            const f32x4_w a0 = *reinterpret_cast<const f32x4_w *>(zp), a1 = *reinterpret_cast<const f32x4_w *>(zp + 4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { t[e] += a0[e]; t[4 + e] += a1[e]; }
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { v[cc][e] = t[e]; amax = fmaxf(amax, fabsf(t[e])); }
+    }
+    const int bits = ra[r].bits;
+    if (bits < 16) {                                         // uniform over the workgroup
+        amax = __uint_as_float(wave_max_u32(__float_as_uint(amax)));
+        if (lane == 0) s_amax[wv] = amax;
+        __syncthreads();
+        amax = fmaxf(fmaxf(s_amax[0], s_amax[1]), fmaxf(s_amax[2], s_amax[3]));
+        if (amax > 0.f) {
+            const float qmax = fq_qmax(bits), s = amax / qmax;
+#pragma unroll
+            for (int cc = 0; cc < CW; ++cc)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[cc][e] = fq_code(v[cc][e], s, qmax) * s;
+        }
+    }
+#pragma unroll
+    for (int cc = 0; cc < CW; ++cc) {
+        const int c = wv + 4 * cc;
+        const float *xp = x2 + r * D + c * 512 + lane * 8;
+        const f32x4_w x0 = *reinterpret_cast<const f32x4_w *>(xp), x1 = *reinterpret_cast<const f32x4_w *>(xp + 4);
+        u32x4_w o;
+        o[0] = pack_bf16x2(x0[0] + v[cc][0], x0[1] + v[cc][1]);
+        o[1] = pack_bf16x2(x0[2] + v[cc][2], x0[3] + v[cc][3]);
+        o[2] = pack_bf16x2(x1[0] + v[cc][4], x1[1] + v[cc][5]);
+        o[3] = pack_bf16x2(x1[2] + v[cc][6], x1[3] + v[cc][7]);
+        *reinterpret_cast<u32x4_w *>(out + r * D + c * 512 + lane * 8) = o;
+    }
+}
+
 void launch_resid_out_fq(const float *x2, const float *z, void *out, int dtype, const RowAct *ra, int64_t M, int d,
                          hipStream_t st, int nsplit)
 {
     if (M <= 0) return;
+    if (dtype == 1 && (d == 2048 || d == 4096)) {
+        const dim3 grid((unsigned)M);
+        if (d == 2048) hipLaunchKernelGGL((k_resid_out_fq_wave<4>), grid, dim3(256), 0, st, x2, z, nsplit, M * (int64_t)d, (bf16_t *)out, ra, M);
+        else hipLaunchKernelGGL((k_resid_out_fq_wave<8>), grid, dim3(256), 0, st, x2, z, nsplit, M * (int64_t)d, (bf16_t *)out, ra, M);
+        return;
+    }
     const size_t lds = (size_t)d * sizeof(float);
     if (dtype == 0)
         hipLaunchKernelGGL((k_resid_out_fq<float>), dim3((unsigned)M), dim3(ROW_BLOCK), lds, st, x2, z, nsplit,

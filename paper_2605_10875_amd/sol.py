@@ -22,6 +22,7 @@ OP_LAYER_FORWARD, OP_DECODE_STEP, OP_SCHEDULE_LOGLIK = 0, 1, 2
 
 EXPORTS = ("sol_validate_config", "sol_create", "sol_destroy", "sol_last_error", "sol_workspace_bytes",
            "sol_layer_forward", "sol_decode_step", "sol_schedule_loglik", "sol_device_status",
+           "sol_page_meta_bytes", "sol_page_meta_build", "sol_decode_step_paged",
            "sol_profile_enable", "sol_profile_read",
            "sol_test_topk_select", "sol_test_prune_mask", "sol_test_prune_quant", "sol_test_quant_codes")
 
@@ -86,6 +87,13 @@ def lib():
         L.sol_decode_step.argtypes = [C.c_void_p, C.POINTER(ModelWeights), C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int, C.c_int,
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.sol_decode_step_paged.argtypes = [C.c_void_p, C.POINTER(ModelWeights), C.c_void_p, C.c_void_p, C.c_void_p,
+                                            C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
+                                            C.POINTER(C.c_void_p), C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
+                                            C.c_void_p, C.c_size_t, C.c_void_p]
+        L.sol_page_meta_bytes.restype = C.c_size_t
+        L.sol_page_meta_bytes.argtypes = [C.POINTER(ModelCfg), C.c_int, C.c_int]
+        L.sol_page_meta_build.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
         L.sol_schedule_loglik.argtypes = [C.c_void_p, C.POINTER(ModelWeights), C.c_void_p, C.c_void_p, C.c_void_p,
                                           C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.sol_profile_enable.argtypes = [C.c_void_p, C.c_int]
@@ -223,9 +231,21 @@ class Sol:
         self._check(rc)
         return x_out
 
+    def page_meta_build(self, k_cache, cache_len, stream=None):
+        """Page metadata (channel-wise maxima and minima per page) of one layer's key cache for keys
+        [0, cache_len[s]); returns the new buffer [n_seq][Hkv][pages][2 * head_dim]."""
+        n_seq, hkv, L_max, dh = k_cache.shape
+        pages = (L_max + self.cfg.page_size - 1) // self.cfg.page_size
+        assert self.L.sol_page_meta_bytes(C.byref(self.cfg), n_seq, L_max) == n_seq * hkv * pages * 2 * dh * k_cache.element_size()
+        meta = torch.zeros((n_seq, hkv, pages, 2 * dh), dtype=k_cache.dtype, device="cuda")
+        self._check(self.L.sol_page_meta_build(self.handle, _ptr(k_cache), _ptr(_i32(cache_len)), n_seq, L_max,
+                                               _ptr(meta), _stream(stream)))
+        return meta
+
     def decode_step(self, layers, head, action_ids, cache_len, k_caches, v_caches, token_ids=None, x_in=None,
-                    targets=None, want_hidden=True, workspace=None, stream=None):
-        """One token per sequence through all layers. Returns (hidden [B][d] or None, nll [B] or None)."""
+                    targets=None, want_hidden=True, workspace=None, stream=None, page_meta=None):
+        """One token per sequence through all layers. Returns (hidden [B][d] or None, nll [B] or None).
+        page_meta: per-layer metadata buffers (page_meta_build), updated in place, for the page rule."""
         B = action_ids.shape[0]
         L_max = k_caches[0].shape[2]
         mw, keep = self._model_struct(layers, head)
@@ -234,9 +254,16 @@ class Sol:
         x_out = torch.empty((B, self.cfg.d_model), dtype=self.tdtype, device="cuda") if want_hidden else None
         nll = torch.empty(B, dtype=torch.float32, device="cuda") if targets is not None else None
         ws = workspace if workspace is not None else self.workspace(OP_DECODE_STEP, B, 1, L_max)
-        rc = self.L.sol_decode_step(self.handle, C.byref(mw), _ptr(_i32(token_ids)), _ptr(x_in),
-                                    _ptr(_i32(action_ids)), _ptr(_i32(cache_len)), kp, vp, B, L_max, _ptr(x_out),
-                                    _ptr(_i32(targets)), _ptr(nll), _ptr(ws), ws.numel(), _stream(stream))
+        if page_meta is not None:
+            mp = (C.c_void_p * len(page_meta))(*[t.data_ptr() for t in page_meta])
+            rc = self.L.sol_decode_step_paged(self.handle, C.byref(mw), _ptr(_i32(token_ids)), _ptr(x_in),
+                                              _ptr(_i32(action_ids)), _ptr(_i32(cache_len)), kp, vp, mp, B, L_max,
+                                              _ptr(x_out), _ptr(_i32(targets)), _ptr(nll), _ptr(ws), ws.numel(),
+                                              _stream(stream))
+        else:
+            rc = self.L.sol_decode_step(self.handle, C.byref(mw), _ptr(_i32(token_ids)), _ptr(x_in),
+                                        _ptr(_i32(action_ids)), _ptr(_i32(cache_len)), kp, vp, B, L_max, _ptr(x_out),
+                                        _ptr(_i32(targets)), _ptr(nll), _ptr(ws), ws.numel(), _stream(stream))
         del keep
         self._check(rc)
         return x_out, nll

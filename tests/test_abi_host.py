@@ -95,3 +95,12 @@ def test_null_context_is_an_error_not_a_crash():
     cfg = sol.make_cfg(synth.TINY, sol.F32, 128)
     assert L.sol_create(C.byref(cfg), sol.make_table([(0, 1, 1, 1, 16)]), 1, C.byref(out)) == sol.ERR_ACTION
     assert not out.value
+
+
+def test_page_meta_bytes_is_host_arithmetic():
+    cfg = sol.make_cfg(synth.LLAMA_1B, sol.BF16, 8200, **sol.PAPER_PRESET)
+    pages = -(-8200 // 16)
+    assert sol.lib().sol_page_meta_bytes(C.byref(cfg), 64, 8200) == 64 * 8 * pages * 2 * 64 * 2
+    plain = sol.make_cfg(synth.LLAMA_1B, sol.BF16, 8200)
+    assert sol.lib().sol_page_meta_bytes(C.byref(plain), 64, 8200) == 0          # page size 1 has no metadata
+    assert sol.lib().sol_page_meta_bytes(C.byref(cfg), 0, 8200) == 0

@@ -148,3 +148,64 @@ def test_bf16_paper_preset_decode_step():
         err = float(np.abs(host(hid)[s] - h_ref[s]).max() / np.abs(h_ref[s]).max())
         assert err < shape.n_layers * cap, (s, err, cap)
         assert abs(float(nll[s]) - float(nll_ref[s])) < (1e-2 if bits[s] >= 16 else 0.5)
+
+
+# ---- decode under the page rule with caller-kept page metadata ------------------------------------------------
+def _meta_ref(k, lens, S):
+    """numpy definition: per page the channel-wise [max | min] over its keys j < len."""
+    n_seq, hkv, L_max, dh = k.shape
+    pages = (L_max + S - 1) // S
+    out = np.zeros((n_seq, hkv, pages, 2 * dh), np.float32)
+    for s in range(n_seq):
+        for u in range((int(lens[s]) + S - 1) // S):
+            blk = k[s, :, u * S:min(u * S + S, int(lens[s]))]
+            out[s, :, u, :dh] = blk.max(axis=1)
+            out[s, :, u, dh:] = blk.min(axis=1)
+    return out
+
+
+@pytest.mark.parametrize("S", [4, 16, 5])
+def test_page_metadata_build_is_exact(S):
+    shape = SMALL_GQA
+    rng = np.random.default_rng(5700 + S)
+    L_max = 100
+    k = synth.round_to_bf16(rng.standard_normal((4, shape.n_kv_heads, L_max, shape.head_dim)).astype(np.float32))
+    lens = np.array([0, 1, 37, 100], np.int32)
+    ctx = sol.Sol(shape, NOQUANT, dtype=sol.BF16, max_positions=L_max, page_size=S)
+    meta = host(ctx.page_meta_build(dev(k, sol.BF16), dev(lens)))
+    ctx.close()
+    assert np.array_equal(meta, _meta_ref(k, lens, S))
+
+
+@pytest.mark.parametrize("S,n_sink,n_window", [(4, 0, 0), (8, 4, 2), (16, 4, 2), (16, 30, 30)])
+def test_bf16_paged_decode_step(S, n_sink, n_window):
+    """Two layers, caches of mixed lengths (a fresh sequence, a page boundary, a full cache), page metadata built
+    once and carried by the step; against the oracle, and the metadata after the step against its definition."""
+    shape, table, seed = SMALL_GQA, NOQUANT, 5800 + S
+    B, L_max = 6, 200
+    layers = [synth.layer_weights(shape, seed + l, bf16=True) for l in range(shape.n_layers)]
+    head = synth.head_weights(shape, seed + 10, bf16=True)
+    rng = np.random.default_rng(seed + 11)
+    cache_len = np.array([0, 1, S, 63, 128, 199], np.int32)
+    kcs = [synth.round_to_bf16(rng.standard_normal((B, shape.n_kv_heads, L_max, shape.head_dim)).astype(np.float32))
+           for _ in range(shape.n_layers)]
+    vcs = [synth.round_to_bf16(rng.standard_normal((B, shape.n_kv_heads, L_max, shape.head_dim)).astype(np.float32))
+           for _ in range(shape.n_layers)]
+    ids = synth.iid_actions(len(table), (B,), seed + 12)
+    x = synth.hidden_states(1, B, shape.d_model, seed + 13, bf16=True)[0]
+    targets = rng.integers(0, shape.vocab, B).astype(np.int32)
+    opts = dict(page_size=S, n_sink=n_sink, n_window=n_window)
+    kr, vr = [k.copy() for k in kcs], [v.copy() for v in vcs]
+    h_ref, nll_ref = oracle.decode_step(oracle.make_cfg(shape, act_bf16=True, **opts), oracle.make_table(table), layers, x,
+                                        ids, cache_len, kr, vr, head["w_final_norm"], head["lm_head"], targets)
+    ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=L_max, **opts)
+    kd, vd = [dev(k, sol.BF16) for k in kcs], [dev(v, sol.BF16) for v in vcs]
+    metas = [ctx.page_meta_build(k, dev(cache_len)) for k in kd]
+    hid, nll = ctx.decode_step([dev_weights(w, sol.BF16) for w in layers], dev_weights(head, sol.BF16), dev(ids),
+                               dev(cache_len), kd, vd, x_in=dev(x, sol.BF16), targets=dev(targets), page_meta=metas)
+    assert ctx.device_status() == sol.OK
+    ctx.close()
+    check_rows(host(hid), h_ref, 2e-2, 5e-2, 0.2, f"paged decode, S={S}")
+    assert np.abs(host(nll) - nll_ref).max() < 2e-2
+    for l in range(shape.n_layers):      # the step folded the new keys into their pages
+        assert np.array_equal(host(metas[l]), _meta_ref(host(kd[l]), cache_len + 1, S))
