@@ -53,8 +53,12 @@ def test_c2_full_size_layer_sampled_sequences():
     ctx.close()
 
 
-def test_c4_full_size_decode_sampled_sequence():
-    """Llama-3.2-1B decode step, 64 sequences x 8192-token caches x 16 layers; sequence 5 against the oracle."""
+@pytest.mark.parametrize("preset", [None, sol.PAPER_PRESET], ids=["exact-topk", "paper-configuration"])
+def test_c4_full_size_decode_sampled_sequence(preset):
+    """Llama-3.2-1B decode step, 64 sequences x 8192-token caches x 16 layers; sequence 5 against the oracle.
+    Second case: the configuration of the paper's runs, decoded with caller-kept page metadata (bench.py's c4p)."""
+    opts = dict(preset or {})
+    qs = opts.pop("quant_sites", oracle.QS_NORTHSTAR)
     shape = dataclasses.replace(synth.LLAMA_1B, n_layers=16, vocab=4096)
     table, B, L, seed = synth.TABLE_C4, 64, 8192, 1234
     L_max = L + 8
@@ -74,13 +78,14 @@ def test_c4_full_size_decode_sampled_sequence():
     s = 5
     k_host = [k[s:s + 1].float().cpu().numpy().copy() for k in kcs]
     v_host = [v[s:s + 1].float().cpu().numpy().copy() for v in vcs]
-    ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=L_max)
+    ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=L_max, quant_sites=qs, **opts)
+    metas = [ctx.page_meta_build(k, dev(cache_len)) for k in kcs] if preset else None
     hid, nll = ctx.decode_step([dev_weights(w, sol.BF16) for w in layers], dev_weights(head, sol.BF16), dev(ids),
-                               dev(cache_len), kcs, vcs, x_in=dev(x, sol.BF16), targets=dev(targets))
+                               dev(cache_len), kcs, vcs, x_in=dev(x, sol.BF16), targets=dev(targets), page_meta=metas)
     assert ctx.device_status() == sol.OK
     # oracle with one quantising-free copy of the action is not needed: compare layer 0's committed K/V
     # exactly-ish and the final hidden state with the bit-width bound of the sequence's action
-    h_ref, nll_ref = oracle.decode_step(oracle.make_cfg(shape, act_bf16=True), oracle.make_table(table), layers,
+    h_ref, nll_ref = oracle.decode_step(oracle.make_cfg(shape, quant_sites=qs, act_bf16=True, **opts), oracle.make_table(table), layers,
                                         x[s:s + 1], ids[s:s + 1], cache_len[s:s + 1], k_host, v_host,
                                         head["w_final_norm"], head["lm_head"], targets[s:s + 1])
     p = int(cache_len[s])
