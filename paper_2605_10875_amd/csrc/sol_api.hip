@@ -480,7 +480,8 @@ static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_i
     }
     {   // magnitude pruning + quantise (down input), rows visited in bucket order
         STAGE(ctx, ST_PRUNE, st);
-        launch_prune_fq(w.a, dt, w.ra, w.perm, qs & SOL_QS_DOWN_IN, M, dff, st, g.prune_site == 0);
+        if (g.prune_site == 0 || (qs & SOL_QS_DOWN_IN))      // (pruning elsewhere and no quantiser here: nothing to do)
+            launch_prune_fq(w.a, dt, w.ra, w.perm, qs & SOL_QS_DOWN_IN, M, dff, st, g.prune_site == 0);
     }
     bool fused_down = false;
     int ns_down = 1;
