@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the action-conditioned decoder-layer path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c5|c4|c5d|c4p]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c5|c4|c5d|c4p|refresh]
 
 A step is one pass of the measured unit over one batch of seeded synthetic input that is already
 resident in HBM. Default workload: the Llama-3.2-1B-shaped decoder layer, 4 inputs x 8 schedules
@@ -293,12 +293,53 @@ def run_decode(args, shape, B, L, table, name, n_layers, preset=None):
     return res
 
 
+def run_refresh(args, shape, B, L, T, n_layers, name):
+    """Periodic KV-cache refresh: dense pass of the stack over the last T tokens of B sequences with L-token caches."""
+    import dataclasses
+    shape = dataclasses.replace(shape, n_layers=n_layers)
+    gen = torch.Generator(device="cuda").manual_seed(args.seed)
+    w0 = {k: _dev(v) for k, v in synth.layer_weights(shape, args.seed, bf16=True).items()}
+    lw = [w0] + [{k: v.clone() for k, v in w0.items()} for _ in range(n_layers - 1)]
+    L_max = L
+    kcs = [torch.randn((B, shape.n_kv_heads, L_max, shape.head_dim), generator=gen, device="cuda",
+                       dtype=torch.float32).to(torch.bfloat16) for _ in range(n_layers)]
+    vcs = [torch.randn((B, shape.n_kv_heads, L_max, shape.head_dim), generator=gen, device="cuda",
+                       dtype=torch.float32).to(torch.bfloat16) for _ in range(n_layers)]
+    x = _dev(synth.hidden_states(B, T, shape.d_model, args.seed + 3, bf16=True))
+    pos0 = torch.full((B,), L - T, dtype=torch.int32, device="cuda")
+    ctx = sol.Sol(shape, [synth.DENSE_ACTION], dtype=sol.BF16, max_positions=L_max)
+    ws = ctx.workspace(sol.OP_KV_REFRESH, B, T, L_max)
+
+    def step():
+        return ctx.kv_refresh(lw, None, pos0, kcs, vcs, x_in=x, workspace=ws)
+
+    sec = time_steps(step, args.steps, args.warmup)
+    out = step()
+    torch.cuda.synchronize()
+    assert ctx.device_status() == sol.OK and bool(torch.isfinite(out.float()).all())
+    stages, launches = stage_times(ctx, step, 2)
+    dom = max(stages, key=stages.get)
+    d, hq, hkv, dh, dff = shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_ff
+    kv_bytes = 2.0 * B * hkv * L * dh * 2                        # all of K and V once per layer (T queries share them)
+    ach = n_layers * kv_bytes / (stages["attention_topk"] * 1e-3) / 1e9
+    return {
+        "metric": "refreshed_tokens_per_s", "value": B * T / sec, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": name, "entry_point": "sol_kv_refresh", "batch": B, "cache_len": L, "T": T, "layers": n_layers},
+        "roofline": {"bound": "hbm", "kernel": "attention_topk", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": ach / PEAK_HBM_GBS, "traffic": None, "kernel_ms": stages["attention_topk"] / n_layers,
+                     "launches_per_step": launches.get("attention_topk")},
+        "stage_ms": {k: round(v, 4) for k, v in stages.items()}, "slowest_stage": dom,
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c5", "c4", "c5d", "c4p"])
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c5", "c4", "c5d", "c4p", "refresh"])
     ap.add_argument("--seed", type=int, default=1234)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -325,6 +366,10 @@ def main():
     elif args.workload == "c4":
         res = run_decode(args, synth.LLAMA_1B, 64, 8192, synth.TABLE_C4,
                          "C4: Llama-3.2-1B-shaped decode step, bf16, 64 sequences x 8192-token KV cache, 16 layers", 16)
+    elif args.workload == "refresh":
+        res = run_refresh(args, synth.LLAMA_1B, 64, 4096, 16, 16,
+                          "KV-cache refresh: Llama-3.2-1B-shaped 16-layer stack, bf16, 64 sequences x 4096-token caches, "
+                          "dense pass over the last 16 tokens")
     elif args.workload == "c4p":
         res = run_decode(args, synth.LLAMA_1B, 64, 8192, synth.TABLE_C4,
                          "C4 under the configuration of the paper's runs (pages of 16 keys, 4 sink + 2 window keys, pruning at "

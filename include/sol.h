@@ -110,7 +110,7 @@ typedef struct {
     const void *lm_head;              /* device [vocab][d_model]; may alias embed                */
 } sol_model_weights;
 
-typedef enum { SOL_OP_LAYER_FORWARD = 0, SOL_OP_DECODE_STEP = 1, SOL_OP_SCHEDULE_LOGLIK = 2 } sol_op;
+typedef enum { SOL_OP_LAYER_FORWARD = 0, SOL_OP_DECODE_STEP = 1, SOL_OP_SCHEDULE_LOGLIK = 2, SOL_OP_KV_REFRESH = 3 } sol_op;
 
 typedef struct sol_ctx sol_ctx;
 
@@ -188,6 +188,21 @@ int sol_decode_step_paged(sol_ctx *ctx, const sol_model_weights *weights,
                           void *const *k_cache, void *const *v_cache, void *const *page_meta, int B, int L_max,
                           void *x_out, const int32_t *targets, float *nll_out,
                           void *workspace, size_t ws_bytes, void *stream);
+
+/* Periodic KV-cache refresh (Background, "Episodes and control horizon"): a fully dense pass of all
+ * cfg.n_layers layers over the T already-known tokens of every sequence, token i of sequence s at position
+ * pos0[s] + i, attending to the cache before it; their K/V entries in every layer are overwritten with the dense
+ * values (every key kept, no pruning, every quantiser bypassed, whatever cfg says). Nothing is sampled.
+ * Input: token_ids (device int32 [n_seq][T], looked up in weights->embed) or, if NULL, x_in (device
+ * [n_seq][T][d_model]). pos0: device int32 [n_seq]; pos0[s] + T > L_max sets the cache-overflow flag and skips
+ * the sequence. k_cache, v_cache: host arrays of n_layers device pointers. page_meta: NULL, or the per-layer
+ * page metadata buffers, whose pages holding rewritten keys are rebuilt. x_out: device [n_seq][T][d_model], the
+ * last layer's output, may be NULL. Workspace: sol_workspace_bytes(cfg, SOL_OP_KV_REFRESH, n_seq, T, L_max). */
+int sol_kv_refresh(sol_ctx *ctx, const sol_model_weights *weights,
+                   const int32_t *token_ids, const void *x_in, const int32_t *pos0,
+                   void *const *k_cache, void *const *v_cache, void *const *page_meta,
+                   int n_seq, int T, int L_max, void *x_out,
+                   void *workspace, size_t ws_bytes, void *stream);
 
 /* Teacher-forced pass over G compute schedules that share one token path (Method, "GRPO with
  * per-sequence budget sampling"): for every input b, schedule g and position t,

@@ -218,6 +218,19 @@ def layer_forward(cfg, table, w, x_in, action_ids, k_cache, v_cache, pos0=None, 
     return x_out, res
 
 
+def kv_refresh(cfg, layers, x_in, pos0, k_caches, v_caches):
+    """Periodic KV-cache refresh (Background, "Episodes and control horizon"): a fully dense pass of the whole
+    stack over the T already-known tokens x_in [n_seq][T][d] at positions pos0[s].., which overwrites their K/V in
+    every layer's cache with the dense values. Written as the layer pass under the one-row table of the dense
+    action with every quantiser site off. Returns the last layer's output."""
+    dense = make_table([(1, 1, 1, 1, 16)])
+    x = _f32(x_in)
+    ids = np.zeros(x.shape[:2], np.int32)
+    for l, w in enumerate(layers):
+        x, _ = layer_forward(cfg, dense, w, x, ids, k_caches[l], v_caches[l], pos0=pos0)
+    return x
+
+
 def decode_step(cfg, table, layers, x0, action_ids, cache_len, k_caches, v_caches,
                 w_final_norm=None, lm_head=None, targets=None):
     """x0 [B][d]; k_caches / v_caches: lists (one per layer) of [B][Hkv][L_max][dh] float32 arrays,

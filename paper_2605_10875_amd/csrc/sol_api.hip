@@ -343,6 +343,12 @@ extern "C" size_t sol_workspace_bytes(const sol_model_cfg *cfg, int op, int n_se
     } else if (op == SOL_OP_SCHEDULE_LOGLIK) {
         if (T <= 0) return 0;
         StackWs w; carve_stack(c, *cfg, n_seq, T, true, w);
+    } else if (op == SOL_OP_KV_REFRESH) {
+        if (T <= 0 || L_max <= 0) return 0;
+        LayerWs w; carve_layer(c, *cfg, n_seq, T, L_max, w);
+        const size_t es = esize(cfg->dtype);
+        c.take(es * (size_t)n_seq * T * cfg->d_model);
+        c.take(es * (size_t)n_seq * T * cfg->d_model);
     } else return 0;
     return c.off + 256;
 }
@@ -362,7 +368,7 @@ static void prepare_actions(sol_ctx *ctx, const int32_t *ids, int64_t M, LayerWs
 // Launch sequence of one decoder layer (actions already decoded into w.ra / w.perm).
 static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_in, void *x_out, const int32_t *pos0,
                       void *kc, void *vc, int n_seq, int T, int L_max, LayerWs &w, hipStream_t st,
-                      void *page_meta = nullptr)
+                      void *page_meta = nullptr, bool dense_pass = false)
 {
     const sol_model_cfg &g = ctx->cfg;
     const int dt = g.dtype;
@@ -403,7 +409,7 @@ static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_i
     {   // scores, budgeted selection, softmax over kept keys, times V
         STAGE(ctx, ST_ATTN, st);
         AttnOpts opt;
-        opt.page = g.page_size; opt.n_sink = g.n_sink; opt.n_window = g.n_window;
+        if (!dense_pass) { opt.page = g.page_size; opt.n_sink = g.n_sink; opt.n_window = g.n_window; }   // dense rows keep every key under any rule
         const bool fast = mfma && opt.plain();       // the tiled and decode kernels know the plain top-k rule only
         const bool tiled = fast && w.vt && T >= 16 && L_max <= 4096 &&
                            launch_attn_tile(w.qb, kc, vc, w.vt, w.big32, w.o32, w.ra, pos0, n_seq, T, L_max, Hq, Hkv, dh, st);
@@ -669,6 +675,63 @@ extern "C" int sol_page_meta_build(sol_ctx *ctx, const void *k_cache, const int3
         !launch_page_meta_build(k_cache, cache_len, page_meta, n_seq, L_max, g.n_kv_heads, g.head_dim, g.page_size,
                                 (hipStream_t)stream))
         return fail(ctx, SOL_ERR_UNSUPPORTED, "page metadata: needs page_size >= 2, bf16, head_dim 64/128");
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(ctx, SOL_ERR_HIP, std::string("kernel launch: ") + hipGetErrorString(e));
+    return SOL_OK;
+}
+
+extern "C" int sol_kv_refresh(sol_ctx *ctx, const sol_model_weights *mw, const int32_t *token_ids, const void *x_in,
+                              const int32_t *pos0, void *const *k_cache, void *const *v_cache, void *const *page_meta,
+                              int n_seq, int T, int L_max, void *x_out, void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!ctx) return SOL_ERR_INVALID_ARG;
+    const sol_model_cfg &g = ctx->cfg;
+    if (!mw || !mw->layers) return fail(ctx, SOL_ERR_INVALID_ARG, "weights are NULL");
+    for (int l = 0; l < g.n_layers; ++l)
+        if (int rc = check_layer_weights(ctx, &mw->layers[l])) return rc;
+    if (!token_ids && !x_in) return fail(ctx, SOL_ERR_INVALID_ARG, "token_ids and x_in are both NULL");
+    if (token_ids && !mw->embed) return fail(ctx, SOL_ERR_INVALID_ARG, "token_ids given but weights->embed is NULL");
+    if (!pos0 || !k_cache || !v_cache) return fail(ctx, SOL_ERR_INVALID_ARG, "a data pointer is NULL");
+    for (int l = 0; l < g.n_layers; ++l)
+        if (!k_cache[l] || !v_cache[l] || (page_meta && !page_meta[l]))
+            return fail(ctx, SOL_ERR_INVALID_ARG, "a per-layer cache or metadata pointer is NULL");
+    if (n_seq < 0 || T < 0 || L_max <= 0) return fail(ctx, SOL_ERR_INVALID_ARG, "negative size");
+    if (L_max > g.max_positions) return fail(ctx, SOL_ERR_INVALID_ARG, "L_max exceeds cfg.max_positions");
+    if (T > L_max) return fail(ctx, SOL_ERR_CACHE_OVERFLOW, "T tokens cannot fit a cache of L_max positions");
+    if (page_meta && (g.page_size < 2 || g.dtype != SOL_BF16 || (g.head_dim != 64 && g.head_dim != 128)))
+        return fail(ctx, SOL_ERR_UNSUPPORTED, "page metadata: needs page_size >= 2, bf16, head_dim 64/128");
+    if ((int64_t)n_seq * T == 0) return SOL_OK;
+    const size_t need = sol_workspace_bytes(&g, SOL_OP_KV_REFRESH, n_seq, T, L_max);
+    if (!workspace || ws_bytes < need)
+        return fail(ctx, SOL_ERR_WORKSPACE, "workspace too small: need " + std::to_string(need) + " bytes");
+    hipStream_t st = (hipStream_t)stream;
+    Carver c(workspace);
+    LayerWs lw; carve_layer(c, g, n_seq, T, L_max, lw);
+    const size_t es = esize(g.dtype);
+    void *xa = c.take(es * (size_t)n_seq * T * g.d_model), *xb = c.take(es * (size_t)n_seq * T * g.d_model);
+    const int64_t M = (int64_t)n_seq * T;
+    {
+        STAGE(ctx, ST_PREPARE, st);
+        launch_dense_rows(g.prune_site ? g.d_model : g.d_ff, M, lw.ra, lw.row_bucket, st);
+        if (prune_fq_wants_order(g.dtype, g.d_ff)) launch_bucket_sort(lw.row_bucket, M, ctx->n_buckets, lw.perm, lw.bucket_off, st);
+        if (T == 1) launch_seq_order(pos0, n_seq, lw.seq_order, st);
+    }
+    const void *cur = x_in;
+    if (token_ids) {
+        launch_embed(mw->embed, token_ids, xa, g.dtype, n_seq, 1, T, g.d_model, g.vocab, st);
+        cur = xa;
+    }
+    for (int l = 0; l < g.n_layers; ++l) {
+        void *dst = (cur == xa) ? xb : xa;
+        if (l == g.n_layers - 1 && x_out) dst = x_out;
+        if (dst == cur) return fail(ctx, SOL_ERR_INVALID_ARG, "x_in and x_out must not alias");
+        if (int rc = layer_impl(ctx, &mw->layers[l], cur, dst, pos0, k_cache[l], v_cache[l], n_seq, T, L_max, lw, st, nullptr, true))
+            return rc;
+        if (page_meta &&
+            !launch_page_meta_build(k_cache[l], pos0, page_meta[l], n_seq, L_max, g.n_kv_heads, g.head_dim, g.page_size, st, pos0, T))
+            return fail(ctx, SOL_ERR_UNSUPPORTED, "page metadata: unsupported shape");
+        cur = dst;
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(ctx, SOL_ERR_HIP, std::string("kernel launch: ") + hipGetErrorString(e));
     return SOL_OK;

@@ -1228,15 +1228,16 @@ bool launch_attn_decode(const void *q, const void *k_cache, const void *v_cache,
 template <int DH>
 __global__ void __launch_bounds__(256)
 k_page_meta_build(const bf16_t *__restrict__ kc, const int32_t *__restrict__ len, bf16_t *__restrict__ meta, int S,
-                  int L_max, int P_max, int Hkv)
+                  int L_max, int P_max, int Hkv, const int32_t *__restrict__ first, int extra)
 {
     constexpr int LPK = DH / 8, PPB = 256 / LPK;               // lanes per page row, pages per workgroup
     const int s = blockIdx.z, kvh = blockIdx.y;
     const int u = blockIdx.x * PPB + threadIdx.x / LPK, cs = threadIdx.x % LPK;
-    int n = len[s];
+    int n = len[s] + extra;
     n = n < 0 ? 0 : (n > L_max ? L_max : n);
     const int j0 = u * S;
     if (u >= P_max || j0 >= n) return;
+    if (first && j0 + S <= first[s]) return;                   // page wholly before the rewritten keys
     const int j1 = j0 + S < n ? j0 + S : n;
     const bf16_t *kb = kc + ((int64_t)s * Hkv + kvh) * (int64_t)L_max * DH + cs * 8;
     float mx[8], mn[8];
@@ -1292,15 +1293,15 @@ k_page_meta_update(const bf16_t *__restrict__ kc, const int32_t *__restrict__ po
 }
 
 bool launch_page_meta_build(const void *k_cache, const int32_t *len, void *meta, int n_seq, int L_max, int Hkv, int dh,
-                            int S, hipStream_t st)
+                            int S, hipStream_t st, const int32_t *first, int extra)
 {
     if (n_seq <= 0) return true;
     if (S < 2 || (dh != 64 && dh != 128)) return false;
     const int P_max = (L_max + S - 1) / S;
     const int ppb = 256 / (dh / 8);
     const dim3 grid((unsigned)((P_max + ppb - 1) / ppb), Hkv, n_seq);
-    if (dh == 64) hipLaunchKernelGGL(k_page_meta_build<64>, grid, dim3(256), 0, st, (const bf16_t *)k_cache, len, (bf16_t *)meta, S, L_max, P_max, Hkv);
-    else hipLaunchKernelGGL(k_page_meta_build<128>, grid, dim3(256), 0, st, (const bf16_t *)k_cache, len, (bf16_t *)meta, S, L_max, P_max, Hkv);
+    if (dh == 64) hipLaunchKernelGGL(k_page_meta_build<64>, grid, dim3(256), 0, st, (const bf16_t *)k_cache, len, (bf16_t *)meta, S, L_max, P_max, Hkv, first, extra);
+    else hipLaunchKernelGGL(k_page_meta_build<128>, grid, dim3(256), 0, st, (const bf16_t *)k_cache, len, (bf16_t *)meta, S, L_max, P_max, Hkv, first, extra);
     return true;
 }
 

@@ -20,6 +20,8 @@ struct ActionDev {  // device copy of one action-table row, with the MLP bucket 
 // SiLU(gate)*up site, d_model at the MLP-input site).
 void launch_prepare_rows(const int32_t *action_ids, const ActionDev *table, int n_actions, int d_ff,
                          int64_t M, RowAct *ra, int32_t *row_bucket, int *flags, hipStream_t st);
+// Every row under the dense action (all keys, all `width` channels, no quantiser).
+void launch_dense_rows(int width, int64_t M, RowAct *ra, int32_t *row_bucket, hipStream_t st);
 // Stable counting sort of rows by bucket: perm[slot] = row, bucket_off[b] = first slot of bucket b
 // (n_buckets + 1 entries).
 void launch_bucket_sort(const int32_t *row_bucket, int64_t M, int n_buckets, int32_t *perm,
@@ -128,8 +130,9 @@ bool launch_attn_decode(const void *q, const void *k_cache, const void *v_cache,
 // Page metadata of a bf16 K cache for the page rule (page size S >= 2): meta [n_seq][Hkv][ceil(L_max/S)][2*dh],
 // per page the channel-wise [maximum | minimum] of its keys. build: from keys [0, len[s]); update: the key at
 // pos[s] joins its page. head_dim 64 / 128.
+// first (may be NULL): only pages that hold a key >= first[s] are rebuilt; extra: len[s] + extra keys are live.
 bool launch_page_meta_build(const void *k_cache, const int32_t *len, void *meta, int n_seq, int L_max, int Hkv, int dh,
-                            int S, hipStream_t st);
+                            int S, hipStream_t st, const int32_t *first = nullptr, int extra = 0);
 bool launch_page_meta_update(const void *k_cache, const int32_t *pos, void *meta, int n_seq, int L_max, int Hkv, int dh,
                              int S, hipStream_t st);
 // Decode attention under the page rule with that metadata (which must already include the new key).

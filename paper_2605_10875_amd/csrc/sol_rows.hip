@@ -32,6 +32,23 @@ __global__ void k_prepare_rows(const int32_t *__restrict__ ids, const ActionDev 
     row_bucket[r] = bucket;
 }
 
+// every row under the dense action: keep all keys, all `width` channels, quantiser bypassed
+__global__ void k_dense_rows(int width, int64_t M, RowAct *__restrict__ ra, int32_t *__restrict__ row_bucket)
+{
+    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= M) return;
+    RowAct a;
+    a.keep_num = 1; a.keep_den = 1; a.m = width; a.bits = 16;
+    ra[r] = a;
+    row_bucket[r] = 0;
+}
+
+void launch_dense_rows(int width, int64_t M, RowAct *ra, int32_t *row_bucket, hipStream_t st)
+{
+    if (M <= 0) return;
+    hipLaunchKernelGGL(k_dense_rows, dim3((unsigned)((M + 255) / 256)), dim3(256), 0, st, width, M, ra, row_bucket);
+}
+
 void launch_prepare_rows(const int32_t *action_ids, const ActionDev *table, int n_actions, int d_ff, int64_t M,
                          RowAct *ra, int32_t *row_bucket, int *flags, hipStream_t st)
 {

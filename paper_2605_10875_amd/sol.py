@@ -18,11 +18,11 @@ QS_ALL_LINEAR_INPUTS = 15
 # sizes from the experiment set-up): pages of 16 keys, 4 sink and 2 window keys, pruning at the MLP input,
 # quantiser on the MLP output only
 PAPER_PRESET = dict(page_size=16, n_sink=4, n_window=2, prune_site=1, quant_sites=QS_MLP_OUT)
-OP_LAYER_FORWARD, OP_DECODE_STEP, OP_SCHEDULE_LOGLIK = 0, 1, 2
+OP_LAYER_FORWARD, OP_DECODE_STEP, OP_SCHEDULE_LOGLIK, OP_KV_REFRESH = 0, 1, 2, 3
 
 EXPORTS = ("sol_validate_config", "sol_create", "sol_destroy", "sol_last_error", "sol_workspace_bytes",
            "sol_layer_forward", "sol_decode_step", "sol_schedule_loglik", "sol_device_status",
-           "sol_page_meta_bytes", "sol_page_meta_build", "sol_decode_step_paged",
+           "sol_page_meta_bytes", "sol_page_meta_build", "sol_decode_step_paged", "sol_kv_refresh",
            "sol_profile_enable", "sol_profile_read",
            "sol_test_topk_select", "sol_test_prune_mask", "sol_test_prune_quant", "sol_test_quant_codes")
 
@@ -91,6 +91,9 @@ def lib():
                                             C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
                                             C.POINTER(C.c_void_p), C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
                                             C.c_void_p, C.c_size_t, C.c_void_p]
+        L.sol_kv_refresh.argtypes = [C.c_void_p, C.POINTER(ModelWeights), C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int, C.c_int,
+                                     C.c_int, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.sol_page_meta_bytes.restype = C.c_size_t
         L.sol_page_meta_bytes.argtypes = [C.POINTER(ModelCfg), C.c_int, C.c_int]
         L.sol_page_meta_build.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
@@ -267,6 +270,25 @@ class Sol:
         del keep
         self._check(rc)
         return x_out, nll
+
+    def kv_refresh(self, layers, head, pos0, k_caches, v_caches, token_ids=None, x_in=None, page_meta=None,
+                   want_hidden=True, workspace=None, stream=None):
+        """Dense pass of all layers over the T known tokens at positions pos0[s].., rewriting their K/V (and the
+        pages of page_meta that hold them). Returns the last layer's output [n_seq][T][d] or None."""
+        src = token_ids if token_ids is not None else x_in
+        n_seq, T = src.shape[0], src.shape[1]
+        L_max = k_caches[0].shape[2]
+        mw, keep = self._model_struct(layers, head)
+        kp = (C.c_void_p * len(k_caches))(*[t.data_ptr() for t in k_caches])
+        vp = (C.c_void_p * len(v_caches))(*[t.data_ptr() for t in v_caches])
+        mp = (C.c_void_p * len(page_meta))(*[t.data_ptr() for t in page_meta]) if page_meta is not None else None
+        x_out = torch.empty((n_seq, T, self.cfg.d_model), dtype=self.tdtype, device="cuda") if want_hidden else None
+        ws = workspace if workspace is not None else self.workspace(OP_KV_REFRESH, n_seq, T, L_max)
+        rc = self.L.sol_kv_refresh(self.handle, C.byref(mw), _ptr(_i32(token_ids)), _ptr(x_in), _ptr(_i32(pos0)), kp, vp,
+                                   mp, n_seq, T, L_max, _ptr(x_out), _ptr(ws), ws.numel(), _stream(stream))
+        del keep
+        self._check(rc)
+        return x_out
 
     def schedule_loglik(self, layers, head, tokens, targets, action_ids, nll_out=None, workspace=None, stream=None):
         """tokens/targets int32 [B][T]; action_ids int32 [B][G][T]. Returns nll float32 [B][G][T] (nats)."""

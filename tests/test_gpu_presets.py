@@ -209,3 +209,54 @@ def test_bf16_paged_decode_step(S, n_sink, n_window):
     assert np.abs(host(nll) - nll_ref).max() < 2e-2
     for l in range(shape.n_layers):      # the step folded the new keys into their pages
         assert np.array_equal(host(metas[l]), _meta_ref(host(kd[l]), cache_len + 1, S))
+
+
+# ---- periodic KV-cache refresh ----------------------------------------------------------------------------------
+@pytest.mark.parametrize("dt,shape,T0,T,preset", [
+    (sol.F32, synth.TINY, 20, 8, {}),
+    (sol.BF16, SMALL_GQA, 37, 16, {}),                       # tiled attention at pos0 > 0
+    (sol.BF16, SMALL_GQA, 50, 5, dict(sol.PAPER_PRESET)),    # dense whatever the configuration says; metadata rebuilt
+], ids=["fp32", "bf16", "bf16-paper-configuration"])
+def test_kv_refresh(dt, shape, T0, T, preset):
+    """The entries of the last T tokens (filled with junk, as if written under aggressive actions) are rebuilt by a
+    dense pass of the whole stack; against the oracle's refresh on the same caches; the prefix is left alone."""
+    import dataclasses
+    bf = dt == sol.BF16
+    shape = dataclasses.replace(shape, n_layers=2)
+    n_seq, L_max, seed = 3, T0 + T + 3, 6000 + T
+    layers = [synth.layer_weights(shape, seed + l, bf16=bf) for l in range(2)]
+    rng = np.random.default_rng(seed + 5)
+    mk = lambda: rng.standard_normal((n_seq, shape.n_kv_heads, L_max, shape.head_dim)).astype(np.float32)
+    kcs, vcs = [mk() for _ in range(2)], [mk() for _ in range(2)]
+    if bf:
+        kcs, vcs = [synth.round_to_bf16(k) for k in kcs], [synth.round_to_bf16(v) for v in vcs]
+    x = synth.hidden_states(n_seq, T, shape.d_model, seed + 6, bf16=bf, **({} if bf else {"std": 0.5}))
+    pos0 = np.array([T0, T0 - 7, 0], np.int32)
+    opts = dict(preset)
+    qs = opts.pop("quant_sites", oracle.QS_NORTHSTAR)
+    kr, vr = [k.copy() for k in kcs], [v.copy() for v in vcs]
+    x_ref = oracle.kv_refresh(oracle.make_cfg(shape, quant_sites=qs, act_bf16=bf, **opts), layers, x, pos0, kr, vr)
+    ctx = sol.Sol(shape, [synth.DENSE_ACTION, (1, 4, 1, 4, 4)], dtype=dt, max_positions=L_max, quant_sites=qs, **opts)
+    kd, vd = [dev(k, dt) for k in kcs], [dev(v, dt) for v in vcs]
+    metas = None
+    if preset:
+        metas = [ctx.page_meta_build(k, dev(pos0)) for k in kd]
+    x_out = ctx.kv_refresh([dev_weights(w, dt) for w in layers], None, dev(pos0), kd, vd, x_in=dev(x, dt), page_meta=metas)
+    assert ctx.device_status() == sol.OK
+    tol = 2e-2 if bf else 1e-4
+    for l in range(2):
+        kg, vg = host(kd[l]), host(vd[l])
+        check_rows(kg.transpose(0, 2, 1, 3), kr[l].transpose(0, 2, 1, 3), tol, tol, 0.0, f"layer {l} K cache")
+        check_rows(vg.transpose(0, 2, 1, 3), vr[l].transpose(0, 2, 1, 3), tol, tol, 0.0, f"layer {l} V cache")
+        for s in range(n_seq):                                # outside [pos0, pos0 + T) nothing is written
+            p = int(pos0[s])
+            assert np.array_equal(kg[s, :, :p], kcs[l][s, :, :p]) and np.array_equal(kg[s, :, p + T:], kcs[l][s, :, p + T:])
+        if metas is not None:
+            S = preset["page_size"]
+            ref = _meta_ref(kg, pos0 + T, S)
+            got = host(metas[l])
+            for s in range(n_seq):
+                u1 = -(-(int(pos0[s]) + T) // S)
+                assert np.array_equal(got[s, :, :u1], ref[s, :, :u1])
+    check_rows(host(x_out), x_ref, tol, tol, 0.0, "refresh output", median=1e-2 if bf else None)
+    ctx.close()

@@ -321,3 +321,45 @@ def test_argument_errors():
     with pytest.raises(ValueError, match="-5"):
         oracle.layer_forward(cfg, oracle.make_table(DENSE), w, x, np.zeros((1, 4), np.int32), kc, vc,
                              pos0=np.array([1], np.int32))
+
+
+def test_kv_refresh_restores_the_dense_cache():
+    """Background, "Episodes and control horizon": after T steps under aggressive actions the K/V entries of those
+    steps differ from the dense ones (they are written as produced under each step's action); the refresh pass over
+    the same T tokens rebuilds exactly the entries of a dense pass over the whole sequence, and leaves the prefix alone."""
+    import dataclasses
+    shape = dataclasses.replace(synth.TINY, n_layers=2)
+    table = synth.action_table((0.25, 1.0), (0.0, 0.75), (4, 16))
+    dense_id = table.index(synth.DENSE_ACTION)
+    harsh_id = table.index((1, 4, 1, 4, 4))
+    cfg = oracle.make_cfg(shape)
+    tab = oracle.make_table(table)
+    layers = [synth.layer_weights(shape, 900 + l) for l in range(2)]
+    T0, T, L = 24, 8, 40
+    x = synth.hidden_states(1, T0 + T, shape.d_model, 910, std=0.5)
+
+    def run(ids):
+        kc = [np.zeros((1, shape.n_kv_heads, L, shape.head_dim), np.float32) for _ in range(2)]
+        vc = [np.zeros_like(kc[0]) for _ in range(2)]
+        h = x
+        for l in range(2):
+            h, _ = oracle.layer_forward(cfg, tab, layers[l], h, ids, kc[l], vc[l])
+        return kc, vc
+
+    ids_dense = np.full((1, T0 + T), dense_id, np.int32)
+    ids_mixed = ids_dense.copy()
+    ids_mixed[0, T0:] = harsh_id
+    k_ref, v_ref = run(ids_dense)
+    k_pol, v_pol = run(ids_mixed)
+    for l in range(2):                                              # the steps' entries are polluted, the prefix is not
+        assert np.abs(k_pol[l][:, :, T0:T0 + T] - k_ref[l][:, :, T0:T0 + T]).max() > 1e-3
+        assert np.array_equal(k_pol[l][:, :, :T0], k_ref[l][:, :, :T0])
+    out = oracle.kv_refresh(cfg, layers, x[:, T0:], np.array([T0], np.int32), k_pol, v_pol)
+    for l in range(2):
+        np.testing.assert_allclose(k_pol[l], k_ref[l], rtol=0, atol=1e-6)
+        np.testing.assert_allclose(v_pol[l], v_ref[l], rtol=0, atol=1e-6)
+    assert out.shape == (1, T, shape.d_model)
+    # a second refresh changes nothing
+    k2 = [k.copy() for k in k_pol]
+    oracle.kv_refresh(cfg, layers, x[:, T0:], np.array([T0], np.int32), k_pol, v_pol)
+    assert all(np.array_equal(a, b) for a, b in zip(k2, k_pol))
