@@ -279,3 +279,49 @@ def schedule_loglik(cfg, table, embed, layers, w_final_norm, lm_head, tokens, ta
     if rc != 0:
         raise ValueError(f"orc_schedule_loglik returned {rc}")
     return (nll, hid) if want_hidden else nll
+
+
+# ---------------------------------------------------------------------------------------------------
+# reward reduction (Method, "Actions and controlled compute", Eqs. 2-5; "GRPO with per-sequence budget
+# sampling"): plain numpy in float64, loops written out in the paper's order.
+# ---------------------------------------------------------------------------------------------------
+def hinge_penalty(delta, tau):
+    """psi(delta; tau) = (max(0, |delta| - tau))^2."""
+    return max(0.0, abs(float(delta)) - float(tau)) ** 2
+
+
+def reward_advantages(nll, action_ids, actions, targets, alpha, tau, gamma, eff=None, eps=1e-8):
+    """nll [B][K][T] (nats; the task reward is r_t = -nll, Eq. 2); action_ids [B][K][T] into `actions`, rows
+    (keep_num, keep_den, mlp_keep_num, mlp_keep_den, bits); targets [B][3] = (C_kappa, C_rho, C_eta) per input;
+    alpha = (a_kappa, a_rho, a_eta); eff [B][T] in {0, 1} or None (every step effective).
+    Returns dict: avg [B][K][3] (realised kappa, rho, eta averaged over the effective steps; an episode without
+    effective steps takes the targets, i.e. no penalty), penalty [B][K] (Eq. 3), returns [B][K][T] (Eq. 4),
+    signal [B][K][T] = returns - penalty (Eq. 5), adv [B][K][T]: the signal mean-centred over the K schedules of an
+    input at fixed t, then whitened over the whole batch, (x - mean) / (std + eps) with the population std."""
+    nll = np.asarray(nll, np.float64)
+    ids = np.asarray(action_ids)
+    B, K, T = nll.shape
+    tab = np.asarray(actions, np.float64)
+    knob = np.stack([tab[:, 0] / tab[:, 1], tab[:, 2] / tab[:, 3], np.minimum(tab[:, 4], 16.0) / 16.0], axis=1)   # kappa, rho, eta = q/16
+    targets = np.asarray(targets, np.float64)
+    e = np.ones((B, T)) if eff is None else np.asarray(eff, np.float64)
+    avg = np.zeros((B, K, 3))
+    pen = np.zeros((B, K))
+    ret = np.zeros((B, K, T))
+    for b in range(B):
+        n_eff = e[b].sum()
+        for k in range(K):
+            for ax in range(3):
+                if n_eff > 0:
+                    avg[b, k, ax] = sum(e[b, t] * knob[ids[b, k, t], ax] for t in range(T)) / n_eff
+                else:
+                    avg[b, k, ax] = targets[b, ax]
+                pen[b, k] += alpha[ax] * hinge_penalty(avg[b, k, ax] - targets[b, ax], tau)
+            g = 0.0
+            for t in range(T - 1, -1, -1):               # G_t = r_t + gamma * G_{t+1}
+                g = -nll[b, k, t] + gamma * g
+                ret[b, k, t] = g
+    signal = ret - pen[:, :, None]
+    centred = signal - signal.mean(axis=1, keepdims=True)
+    adv = (centred - centred.mean()) / (centred.std() + eps)
+    return {"avg": avg, "penalty": pen, "returns": ret, "signal": signal, "adv": adv}
