@@ -191,6 +191,20 @@ def run_stack(args, shape, B, G, T, table, name):
                   "mean_nll_nats": float(nll.mean()), "log_vocab": float(np.log(shape.vocab))},
         "stage_ms": {k: round(v, 4) for k, v in stages.items()},
     }
+    # the step right after this pass: reward reduction on its NLL tensor (not part of the timed step)
+    tg3 = torch.full((B, 3), 0.6, dtype=torch.float32, device="cuda")
+    rw = lambda: ctx.reward_advantages(nll, idd, tg3, (4.0, 4.0, 4.0), 0.02, 0.85)
+    rw()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        adv = rw()["adv"]
+    e1.record()
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(adv).all())
+    res["reward_reduction"] = {"entry_point": "sol_reward_advantages", "ms": e0.elapsed_time(e1) / 10,
+                               "values": tokens_n, "note": "includes the binding's five output allocations"}
     ctx.close()
     return res
 

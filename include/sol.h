@@ -110,7 +110,7 @@ typedef struct {
     const void *lm_head;              /* device [vocab][d_model]; may alias embed                */
 } sol_model_weights;
 
-typedef enum { SOL_OP_LAYER_FORWARD = 0, SOL_OP_DECODE_STEP = 1, SOL_OP_SCHEDULE_LOGLIK = 2, SOL_OP_KV_REFRESH = 3 } sol_op;
+typedef enum { SOL_OP_LAYER_FORWARD = 0, SOL_OP_DECODE_STEP = 1, SOL_OP_SCHEDULE_LOGLIK = 2, SOL_OP_KV_REFRESH = 3, SOL_OP_REWARD = 4 } sol_op;
 
 typedef struct sol_ctx sol_ctx;
 
@@ -203,6 +203,31 @@ int sol_kv_refresh(sol_ctx *ctx, const sol_model_weights *weights,
                    void *const *k_cache, void *const *v_cache, void *const *page_meta,
                    int n_seq, int T, int L_max, void *x_out,
                    void *workspace, size_t ws_bytes, void *stream);
+
+/* Reward reduction on the output of sol_schedule_loglik (Method, "Actions and controlled compute", Eqs. 2-5;
+ * "GRPO with per-sequence budget sampling"). With r_t = -nll[b][g][t] the task reward of step t:
+ *   avg[b][g]     = (kappa, rho, eta = min(q, 16) / 16) of the schedule's actions averaged over its effective steps
+ *                   (eff[b][t] != 0; eff NULL = every step; no effective step: the targets, so no penalty);
+ *   penalty[b][g] = sum over the three axes of alpha * max(0, |avg - target| - tau)^2      (Eq. 3)
+ *   returns       = G_t = sum_{u >= t} gamma^(u - t) r_u                                  (Eq. 4)
+ *   signal        = G_t - penalty[b][g]                                                   (Eq. 5)
+ *   adv           = signal minus its mean over the G schedules of input b at the same t, then whitened over all
+ *                   B * G * T values: (x - mean) / (population std + eps).
+ * nll, action_ids: device [B][G][T] (float / int32); eff: device int32 [B][T] or NULL; targets: device float
+ * [B][3] = (C_kappa, C_rho, C_eta) per input. Outputs are device float arrays: avg_out [B][G][3], penalty_out
+ * [B][G], returns_out [B][G][T] (each may be NULL), signal_out and adv_out [B][G][T] (required; they must not
+ * alias nll). An action id outside the table counts as action 0 and sets the bad-action flag.
+ * Workspace: sol_workspace_bytes(cfg, SOL_OP_REWARD, B, T, 0) bytes. */
+typedef struct {
+    float alpha_kappa, alpha_rho, alpha_eta;  /* trade-off weights, >= 0                     */
+    float tau;                                /* tolerance band, >= 0                        */
+    float gamma;                              /* discount in (0, 1]                          */
+    float eps;                                /* added to the standard deviation, >= 0       */
+} sol_reward_cfg;
+int sol_reward_advantages(sol_ctx *ctx, const float *nll, const int32_t *action_ids, const int32_t *eff,
+                          const float *targets, const sol_reward_cfg *rc, int B, int G, int T,
+                          float *avg_out, float *penalty_out, float *returns_out, float *signal_out, float *adv_out,
+                          void *workspace, size_t ws_bytes, void *stream);
 
 /* Teacher-forced pass over G compute schedules that share one token path (Method, "GRPO with
  * per-sequence budget sampling"): for every input b, schedule g and position t,

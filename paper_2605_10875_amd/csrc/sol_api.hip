@@ -343,6 +343,9 @@ extern "C" size_t sol_workspace_bytes(const sol_model_cfg *cfg, int op, int n_se
     } else if (op == SOL_OP_SCHEDULE_LOGLIK) {
         if (T <= 0) return 0;
         StackWs w; carve_stack(c, *cfg, n_seq, T, true, w);
+    } else if (op == SOL_OP_REWARD) {
+        if (T <= 0) return 0;
+        return reward_scratch_bytes(n_seq, T) + 256;
     } else if (op == SOL_OP_KV_REFRESH) {
         if (T <= 0 || L_max <= 0) return 0;
         LayerWs w; carve_layer(c, *cfg, n_seq, T, L_max, w);
@@ -732,6 +735,34 @@ extern "C" int sol_kv_refresh(sol_ctx *ctx, const sol_model_weights *mw, const i
             return fail(ctx, SOL_ERR_UNSUPPORTED, "page metadata: unsupported shape");
         cur = dst;
     }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(ctx, SOL_ERR_HIP, std::string("kernel launch: ") + hipGetErrorString(e));
+    return SOL_OK;
+}
+
+extern "C" int sol_reward_advantages(sol_ctx *ctx, const float *nll, const int32_t *action_ids, const int32_t *eff,
+                                     const float *targets, const sol_reward_cfg *rc, int B, int G, int T,
+                                     float *avg_out, float *penalty_out, float *returns_out, float *signal_out,
+                                     float *adv_out, void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!ctx) return SOL_ERR_INVALID_ARG;
+    if (!nll || !action_ids || !targets || !rc || !signal_out || !adv_out)
+        return fail(ctx, SOL_ERR_INVALID_ARG, "a data pointer is NULL");
+    if (B < 0 || G < 0 || T < 0) return fail(ctx, SOL_ERR_INVALID_ARG, "negative size");
+    if (!(rc->alpha_kappa >= 0.f) || !(rc->alpha_rho >= 0.f) || !(rc->alpha_eta >= 0.f) || !(rc->tau >= 0.f) ||
+        !(rc->gamma > 0.f && rc->gamma <= 1.f) || !(rc->eps >= 0.f))
+        return fail(ctx, SOL_ERR_INVALID_ARG, "reward cfg: weights, tau, eps must be >= 0 and gamma in (0, 1]");
+    if (signal_out == nll || adv_out == nll || signal_out == adv_out)
+        return fail(ctx, SOL_ERR_INVALID_ARG, "signal_out / adv_out must not alias nll or each other");
+    if ((int64_t)B * G * T == 0) return SOL_OK;
+    const size_t need = sol_workspace_bytes(&ctx->cfg, SOL_OP_REWARD, B, T, 0);
+    if (!workspace || ws_bytes < need)
+        return fail(ctx, SOL_ERR_WORKSPACE, "workspace too small: need " + std::to_string(need) + " bytes");
+    RewardCfg r{rc->alpha_kappa, rc->alpha_rho, rc->alpha_eta, rc->tau, rc->gamma, rc->eps};
+    Carver c(workspace);
+    void *scratch = c.take(reward_scratch_bytes(B, T));
+    launch_reward(nll, action_ids, ctx->d_table, ctx->n_actions, eff, targets, r, B, G, T, avg_out, penalty_out, returns_out,
+                  signal_out, adv_out, scratch, ctx->d_flags, (hipStream_t)stream);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(ctx, SOL_ERR_HIP, std::string("kernel launch: ") + hipGetErrorString(e));
     return SOL_OK;

@@ -149,4 +149,13 @@ bool launch_attn_tile(const void *q, const void *k_cache, const void *v_cache, v
 size_t attn_tile_sel_bytes(int64_t rows, int Hq);
 int attn_tile_lpadv(int L_max);
 
+// ---- reward reduction (sol_reward.hip) ----------------------------------------------------------
+struct RewardCfg { float alpha_kappa, alpha_rho, alpha_eta, tau, gamma, eps; };
+// nll, ids [B][K][T]; eff [B][T] or NULL; targets [B][3]; avg_out [B][K][3], pen_out [B][K], ret_out [B][K][T] may be
+// NULL; signal and adv [B][K][T]; scratch: reward_scratch_bytes(B, T).
+void launch_reward(const float *nll, const int32_t *ids, const ActionDev *table, int n_actions, const int32_t *eff,
+                   const float *targets, const RewardCfg &rc, int B, int K, int T, float *avg_out, float *pen_out,
+                   float *ret_out, float *signal, float *adv, void *scratch, int *flags, hipStream_t st);
+size_t reward_scratch_bytes(int B, int T);
+
 }  // namespace sol

@@ -18,13 +18,19 @@ QS_ALL_LINEAR_INPUTS = 15
 # sizes from the experiment set-up): pages of 16 keys, 4 sink and 2 window keys, pruning at the MLP input,
 # quantiser on the MLP output only
 PAPER_PRESET = dict(page_size=16, n_sink=4, n_window=2, prune_site=1, quant_sites=QS_MLP_OUT)
-OP_LAYER_FORWARD, OP_DECODE_STEP, OP_SCHEDULE_LOGLIK, OP_KV_REFRESH = 0, 1, 2, 3
+OP_LAYER_FORWARD, OP_DECODE_STEP, OP_SCHEDULE_LOGLIK, OP_KV_REFRESH, OP_REWARD = 0, 1, 2, 3, 4
 
 EXPORTS = ("sol_validate_config", "sol_create", "sol_destroy", "sol_last_error", "sol_workspace_bytes",
            "sol_layer_forward", "sol_decode_step", "sol_schedule_loglik", "sol_device_status",
            "sol_page_meta_bytes", "sol_page_meta_build", "sol_decode_step_paged", "sol_kv_refresh",
+           "sol_reward_advantages",
            "sol_profile_enable", "sol_profile_read",
            "sol_test_topk_select", "sol_test_prune_mask", "sol_test_prune_quant", "sol_test_quant_codes")
+
+
+class RewardCfg(C.Structure):
+    _fields_ = [("alpha_kappa", C.c_float), ("alpha_rho", C.c_float), ("alpha_eta", C.c_float), ("tau", C.c_float),
+                ("gamma", C.c_float), ("eps", C.c_float)]
 
 
 class ActionDef(C.Structure):
@@ -94,6 +100,9 @@ def lib():
         L.sol_kv_refresh.argtypes = [C.c_void_p, C.POINTER(ModelWeights), C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int, C.c_int,
                                      C.c_int, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.sol_reward_advantages.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                            C.POINTER(RewardCfg), C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.sol_page_meta_bytes.restype = C.c_size_t
         L.sol_page_meta_bytes.argtypes = [C.POINTER(ModelCfg), C.c_int, C.c_int]
         L.sol_page_meta_build.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
@@ -289,6 +298,22 @@ class Sol:
         del keep
         self._check(rc)
         return x_out
+
+    def reward_advantages(self, nll, action_ids, targets, alpha, tau, gamma, eff=None, eps=1e-8, stream=None):
+        """nll float32 / action_ids int32 [B][G][T], targets float32 [B][3], eff int32 [B][T] or None.
+        Returns dict of device tensors: avg [B][G][3], penalty [B][G], returns, signal, adv [B][G][T]."""
+        B, G, T = nll.shape
+        f = lambda *sh: torch.empty(sh, dtype=torch.float32, device="cuda")
+        out = {"avg": f(B, G, 3), "penalty": f(B, G), "returns": f(B, G, T), "signal": f(B, G, T), "adv": f(B, G, T)}
+        rc = RewardCfg(float(alpha[0]), float(alpha[1]), float(alpha[2]), float(tau), float(gamma), float(eps))
+        need = workspace_bytes(self.cfg, OP_REWARD, B, T, 0)
+        ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+        assert nll.dtype == torch.float32 and nll.is_contiguous() and targets.dtype == torch.float32
+        self._check(self.L.sol_reward_advantages(self.handle, _ptr(nll), _ptr(_i32(action_ids)), _ptr(_i32(eff)),
+                                                 _ptr(targets), C.byref(rc), B, G, T, _ptr(out["avg"]),
+                                                 _ptr(out["penalty"]), _ptr(out["returns"]), _ptr(out["signal"]),
+                                                 _ptr(out["adv"]), _ptr(ws), ws.numel(), _stream(stream)))
+        return out
 
     def schedule_loglik(self, layers, head, tokens, targets, action_ids, nll_out=None, workspace=None, stream=None):
         """tokens/targets int32 [B][T]; action_ids int32 [B][G][T]. Returns nll float32 [B][G][T] (nats)."""
