@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the action-conditioned decoder-layer path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c5|c4|c5d|c4p|refresh]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c5|c4|c5d|c4p|refresh|episode]
 
 A step is one pass of the measured unit over one batch of seeded synthetic input that is already
 resident in HBM. Default workload: the Llama-3.2-1B-shaped decoder layer, 4 inputs x 8 schedules
@@ -307,6 +307,54 @@ def run_decode(args, shape, B, L, table, name, n_layers, preset=None):
     return res
 
 
+def run_episode(args, shape, B, K, P, T, table, name):
+    """Episode pass (sol_episode_loglik): dense prefill of P tokens once per input, K schedules of T steps on it."""
+    gen = torch.Generator(device="cuda").manual_seed(args.seed)
+
+    def rnd(*sz, std=0.02, mean=0.0):
+        return (torch.randn(sz, generator=gen, device="cuda") * std + mean).to(torch.bfloat16)
+
+    d, hq, hkv, dh, dff = shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_ff
+    layers = [{"w_in_norm": rnd(d, std=0.1, mean=1.0), "wq": rnd(hq * dh, d), "wk": rnd(hkv * dh, d),
+               "wv": rnd(hkv * dh, d), "wo": rnd(d, hq * dh), "w_post_norm": rnd(d, std=0.1, mean=1.0),
+               "w_gate": rnd(dff, d), "w_up": rnd(dff, d), "w_down": rnd(d, dff)} for _ in range(shape.n_layers)]
+    head = {"embed": rnd(shape.vocab, d), "w_final_norm": rnd(d, std=0.1, mean=1.0), "lm_head": rnd(shape.vocab, d)}
+    rng = np.random.default_rng(args.seed)
+    prefix = _dev(rng.integers(0, shape.vocab, (B, P)).astype(np.int32))
+    tokens, targets = synth.tokens_and_targets(B, T, shape.vocab, args.seed + 1)
+    ids = synth.markov_actions(len(table), B * K, T, args.seed + 2).reshape(B, K, T)
+    ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=P + T)
+    tk, tg, idd = _dev(tokens), _dev(targets), _dev(ids)
+    nll = torch.empty((B, K, T), dtype=torch.float32, device="cuda")
+    need = int(ctx.L.sol_episode_workspace_bytes(ctx.cfg, B, K, P, T))
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+
+    def step():
+        ctx.episode_loglik(layers, head, prefix, tk, tg, idd, nll_out=nll, workspace=ws)
+
+    sec = time_steps(step, args.steps, args.warmup)
+    assert ctx.device_status() == sol.OK and bool(torch.isfinite(nll).all())
+    stages, launches = stage_times(ctx, step, 2)
+    dom = max(stages, key=stages.get)
+    # dense flops: every linear layer for the B*P prefix tokens and the B*K*T controlled tokens, plus the LM head on the latter
+    lin = 2.0 * (d * (hq + 2 * hkv) * dh + hq * dh * d + 3 * d * dff)
+    alg = shape.n_layers * lin * (B * P + B * K * T) + 2.0 * d * shape.vocab * B * K * T
+    res = {
+        "metric": "controlled_steps_per_s", "value": B * K * T / sec, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": name, "entry_point": "sol_episode_loglik", "n_inputs": B, "schedules": K, "prefix": P,
+                   "steps_per_episode": T, "layers": shape.n_layers, "vocab": shape.vocab,
+                   "tokens_through_the_stack": B * P + B * K * T, "same_work_without_sharing": B * K * (P + T),
+                   "workspace_gb": need / 1e9},
+        "roofline": {"bound": "mfma", "kernel": "whole pass (linear layers + LM head, dense flops)", "achieved": alg / sec / 1e12,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": alg / sec / 1e12 / PEAK_BF16_TFLOPS, "traffic": None},
+        "stage_ms": {k: round(v, 4) for k, v in stages.items()}, "slowest_stage": dom,
+    }
+    ctx.close()
+    return res
+
+
 def run_refresh(args, shape, B, L, T, n_layers, name):
     """Periodic KV-cache refresh: dense pass of the stack over the last T tokens of B sequences with L-token caches."""
     import dataclasses
@@ -353,7 +401,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c5", "c4", "c5d", "c4p", "refresh"])
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c5", "c4", "c5d", "c4p", "refresh", "episode"])
     ap.add_argument("--seed", type=int, default=1234)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -380,6 +428,12 @@ def main():
     elif args.workload == "c4":
         res = run_decode(args, synth.LLAMA_1B, 64, 8192, synth.TABLE_C4,
                          "C4: Llama-3.2-1B-shaped decode step, bf16, 64 sequences x 8192-token KV cache, 16 layers", 16)
+    elif args.workload == "episode":
+        import dataclasses
+        shape = dataclasses.replace(synth.LLAMA_1B, n_layers=16, vocab=128256)
+        res = run_episode(args, shape, 8, 32, 1024, 16, synth.TABLE_C2,
+                          "Episode pass: Llama-3.2-1B-shaped 16-layer stack + LM head + NLL, bf16, 8 inputs, dense prefill of "
+                          "1024 tokens once per input, 32 schedules x 16 controlled steps on it")
     elif args.workload == "refresh":
         res = run_refresh(args, synth.LLAMA_1B, 64, 4096, 16, 16,
                           "KV-cache refresh: Llama-3.2-1B-shaped 16-layer stack, bf16, 64 sequences x 4096-token caches, "

@@ -204,6 +204,21 @@ int sol_kv_refresh(sol_ctx *ctx, const sol_model_weights *weights,
                    int n_seq, int T, int L_max, void *x_out,
                    void *workspace, size_t ws_bytes, void *stream);
 
+/* Episode pass (Method, "GRPO with per-sequence budget sampling"): for every input a dense prefill of its P-token
+ * context prefix, run once, initialises the cache; K counterfactual schedules of T teacher-forced steps then share
+ * that prefix and the token path and differ only in their actions:
+ *   nll_out[b][k][t] = -log p(targets[b][t]) of step t of schedule k, the token at position P + t attending to the
+ *   dense prefix and to the schedule's own earlier steps, under action_ids[b][k][t].
+ * It equals sol_schedule_loglik on the P + T tokens with the dense action on the prefix, restricted to the last T
+ * positions, without running the prefix K times. prefix_tokens: device int32 [B][P]; tokens, targets: device int32
+ * [B][T]; action_ids: device int32 [B][K][T]; nll_out: device float [B][K][T]. The prefix is dense whatever cfg
+ * says. Workspace: sol_episode_workspace_bytes(cfg, B, K, P, T) (holds one layer's caches for B * K sequences). */
+size_t sol_episode_workspace_bytes(const sol_model_cfg *cfg, int B, int K, int P, int T);
+int sol_episode_loglik(sol_ctx *ctx, const sol_model_weights *weights, const int32_t *prefix_tokens,
+                       const int32_t *tokens, const int32_t *targets, const int32_t *action_ids,
+                       int B, int K, int P, int T, float *nll_out,
+                       void *workspace, size_t ws_bytes, void *stream);
+
 /* Reward reduction on the output of sol_schedule_loglik (Method, "Actions and controlled compute", Eqs. 2-5;
  * "GRPO with per-sequence budget sampling"). With r_t = -nll[b][g][t] the task reward of step t:
  *   avg[b][g]     = (kappa, rho, eta = min(q, 16) / 16) of the schedule's actions averaged over its effective steps

@@ -218,6 +218,22 @@ def layer_forward(cfg, table, w, x_in, action_ids, k_cache, v_cache, pos0=None, 
     return x_out, res
 
 
+def episode_loglik(cfg, table, dense_id, embed, layers, w_final_norm, lm_head, prefix_tokens, tokens, targets, action_ids):
+    """Episode pass (Method, "GRPO with per-sequence budget sampling"): dense prefill of the P-token prefix, then K
+    schedules of T teacher-forced steps. Written as its definition: the teacher-forced pass over the P + T tokens with
+    the dense action (table row dense_id) on the prefix, of which the last T positions are the episode.
+    prefix_tokens [B][P], tokens / targets [B][T], action_ids [B][K][T] -> nll [B][K][T]."""
+    prefix_tokens, tokens, targets = _i32(prefix_tokens), _i32(tokens), _i32(targets)
+    ids = _i32(action_ids)
+    B, K, T = ids.shape
+    P = prefix_tokens.shape[1]
+    full_tokens = np.concatenate([prefix_tokens, tokens], axis=1)
+    full_targets = np.concatenate([np.zeros((B, P), np.int32), targets], axis=1)      # prefix targets are not used
+    full_ids = np.concatenate([np.full((B, K, P), dense_id, np.int32), ids], axis=2)
+    nll = schedule_loglik(cfg, table, embed, layers, w_final_norm, lm_head, full_tokens, full_targets, full_ids)
+    return nll[:, :, P:]
+
+
 def kv_refresh(cfg, layers, x_in, pos0, k_caches, v_caches):
     """Periodic KV-cache refresh (Background, "Episodes and control horizon"): a fully dense pass of the whole
     stack over the T already-known tokens x_in [n_seq][T][d] at positions pos0[s].., which overwrites their K/V in

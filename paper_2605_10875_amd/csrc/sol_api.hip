@@ -808,6 +808,98 @@ extern "C" int sol_schedule_loglik(sol_ctx *ctx, const sol_model_weights *mw, co
 }
 
 // ------------------------------------------------------------------------------------------------
+// episode pass: dense prefill once per input, then K schedules of T controlled steps on top of it
+// ------------------------------------------------------------------------------------------------
+struct EpisodeWs {
+    LayerWs pre, suf;
+    void *pxa, *pxb, *pkc, *pvc;          // prefix activations (ping-pong) and one layer's prefix cache
+    StackWs st;                            // suffix activations, one layer's caches, LM head scratch
+    int32_t *pos0;
+};
+
+static void carve_episode(Carver &c, const sol_model_cfg &g, int64_t B, int64_t K, int64_t P, int64_t T, EpisodeWs &w)
+{
+    const size_t es = esize(g.dtype);
+    const int64_t N = B * K, M = N * T;
+    carve_layer(c, g, B, P, (int)P, w.pre);
+    w.pxa = c.take(es * B * P * g.d_model);
+    w.pxb = c.take(es * B * P * g.d_model);
+    const size_t pc = es * B * g.n_kv_heads * P * g.head_dim;
+    w.pkc = c.take(pc);
+    w.pvc = c.take(pc);
+    carve_layer(c, g, N, T, (int)(P + T), w.suf);
+    w.st.xa = c.take(es * M * g.d_model);
+    w.st.xb = c.take(es * M * g.d_model);
+    w.st.hf = c.take(es * M * g.d_model);
+    const size_t sc = es * N * g.n_kv_heads * (P + T) * g.head_dim;
+    w.st.kc = c.take(sc);
+    w.st.vc = c.take(sc);
+    size_t head_bytes = 4 * lm_chunk_rows(g, M) * (size_t)(g.vocab > 0 ? g.vocab : 1);
+    if (g.dtype == SOL_BF16 && g.vocab > 0 && g.vocab % 256 == 0 && gemm_nll_scratch_bytes(M, g.vocab) > head_bytes)
+        head_bytes = gemm_nll_scratch_bytes(M, g.vocab);
+    w.st.logits = (float *)c.take(head_bytes);
+    w.pos0 = (int32_t *)c.take(4 * N);
+}
+
+extern "C" size_t sol_episode_workspace_bytes(const sol_model_cfg *cfg, int B, int K, int P, int T)
+{
+    if (!cfg || B <= 0 || K <= 0 || P <= 0 || T <= 0) return 0;
+    Carver c(nullptr);
+    EpisodeWs w; carve_episode(c, *cfg, B, K, P, T, w);
+    return c.off + 256;
+}
+
+extern "C" int sol_episode_loglik(sol_ctx *ctx, const sol_model_weights *mw, const int32_t *prefix_tokens,
+                                  const int32_t *tokens, const int32_t *targets, const int32_t *action_ids, int B, int K,
+                                  int P, int T, float *nll_out, void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!ctx) return SOL_ERR_INVALID_ARG;
+    const sol_model_cfg &g = ctx->cfg;
+    if (!mw || !mw->layers || !mw->embed || !mw->w_final_norm || !mw->lm_head)
+        return fail(ctx, SOL_ERR_INVALID_ARG, "weights are NULL");
+    for (int l = 0; l < g.n_layers; ++l)
+        if (int rc = check_layer_weights(ctx, &mw->layers[l])) return rc;
+    if (!prefix_tokens || !tokens || !targets || !action_ids || !nll_out)
+        return fail(ctx, SOL_ERR_INVALID_ARG, "a data pointer is NULL");
+    if (B < 0 || K < 0 || T < 0 || P <= 0) return fail(ctx, SOL_ERR_INVALID_ARG, "negative size or empty prefix");
+    if (g.vocab <= 0) return fail(ctx, SOL_ERR_INVALID_ARG, "vocab must be positive");
+    if ((int64_t)P + T > g.max_positions) return fail(ctx, SOL_ERR_INVALID_ARG, "P + T exceeds cfg.max_positions");
+    if ((g.head_dim * esize(g.dtype)) % 16) return fail(ctx, SOL_ERR_UNSUPPORTED, "head rows must be a multiple of 16 bytes");
+    if ((int64_t)B * K * T == 0) return SOL_OK;
+    const size_t need = sol_episode_workspace_bytes(&g, B, K, P, T);
+    if (!workspace || ws_bytes < need)
+        return fail(ctx, SOL_ERR_WORKSPACE, "workspace too small: need " + std::to_string(need) + " bytes");
+    hipStream_t st = (hipStream_t)stream;
+    Carver c(workspace);
+    EpisodeWs w; carve_episode(c, g, B, K, P, T, w);
+    const int N = B * K, L = P + T;
+    const int64_t Mp = (int64_t)B * P, M = (int64_t)N * T;
+    {   // plans: the prefix runs dense, the suffix under its schedules
+        STAGE(ctx, ST_PREPARE, st);
+        launch_dense_rows(g.prune_site ? g.d_model : g.d_ff, Mp, w.pre.ra, w.pre.row_bucket, st);
+        if (prune_fq_wants_order(g.dtype, g.d_ff)) launch_bucket_sort(w.pre.row_bucket, Mp, ctx->n_buckets, w.pre.perm, w.pre.bucket_off, st);
+        launch_fill_i32(w.pos0, P, N, st);
+    }
+    prepare_actions(ctx, action_ids, M, w.suf, st);
+    {
+        STAGE(ctx, ST_EMBED, st);
+        launch_embed(mw->embed, prefix_tokens, w.pxa, g.dtype, B, 1, P, g.d_model, g.vocab, st);
+        launch_embed(mw->embed, tokens, w.st.xa, g.dtype, B, K, T, g.d_model, g.vocab, st);
+    }
+    void *pcur = w.pxa, *pnxt = w.pxb, *cur = w.st.xa, *nxt = w.st.xb;
+    for (int l = 0; l < g.n_layers; ++l) {
+        // layer l of the prefix (dense, once per input) fills the prefix cache; every schedule starts from a copy
+        if (int rc = layer_impl(ctx, &mw->layers[l], pcur, pnxt, nullptr, w.pkc, w.pvc, B, P, P, w.pre, st, nullptr, true)) return rc;
+        std::swap(pcur, pnxt);
+        launch_bcast_prefix(w.pkc, w.st.kc, N, K, g.n_kv_heads, P, L, g.head_dim, esize(g.dtype), st);
+        launch_bcast_prefix(w.pvc, w.st.vc, N, K, g.n_kv_heads, P, L, g.head_dim, esize(g.dtype), st);
+        if (int rc = layer_impl(ctx, &mw->layers[l], cur, nxt, w.pos0, w.st.kc, w.st.vc, N, T, L, w.suf, st)) return rc;
+        std::swap(cur, nxt);
+    }
+    return nll_impl(ctx, mw, cur, M, w.st, targets, K, T, true, nll_out, st);
+}
+
+// ------------------------------------------------------------------------------------------------
 // unit hooks
 // ------------------------------------------------------------------------------------------------
 static int launch_status()

@@ -20,6 +20,10 @@ struct ActionDev {  // device copy of one action-table row, with the MLP bucket 
 // SiLU(gate)*up site, d_model at the MLP-input site).
 void launch_prepare_rows(const int32_t *action_ids, const ActionDev *table, int n_actions, int d_ff,
                          int64_t M, RowAct *ra, int32_t *row_bucket, int *flags, hipStream_t st);
+// dst [N][Hkv][L_dst][dh] <- src [N / K][Hkv][P][dh] for positions < P (dh * esize a multiple of 16 bytes).
+void launch_bcast_prefix(const void *src, void *dst, int64_t N, int K, int Hkv, int P, int L_dst, int dh, size_t esize,
+                         hipStream_t st);
+void launch_fill_i32(int32_t *p, int v, int64_t n, hipStream_t st);
 // Every row under the dense action (all keys, all `width` channels, no quantiser).
 void launch_dense_rows(int width, int64_t M, RowAct *ra, int32_t *row_bucket, hipStream_t st);
 // Stable counting sort of rows by bucket: perm[slot] = row, bucket_off[b] = first slot of bucket b

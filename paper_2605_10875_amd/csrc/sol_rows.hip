@@ -32,6 +32,42 @@ __global__ void k_prepare_rows(const int32_t *__restrict__ ids, const ActionDev 
     row_bucket[r] = bucket;
 }
 
+// dst [N][Hkv][L_dst][dh] <- src [N / K][Hkv][P][dh] for positions < P (16-byte pieces): the K schedules of an
+// input start from the same prefix cache
+__global__ void __launch_bounds__(256)
+k_bcast_prefix(const uint4 *__restrict__ src, uint4 *__restrict__ dst, int K, int Hkv, int P, int L_dst, int row16, int64_t total)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const int c = (int)(i % row16);
+    int64_t t = i / row16;
+    const int j = (int)(t % P); t /= P;
+    const int h = (int)(t % Hkv);
+    const int64_t n = t / Hkv;
+    dst[((n * Hkv + h) * L_dst + j) * row16 + c] = src[(((n / K) * Hkv + h) * P + j) * row16 + c];
+}
+
+void launch_bcast_prefix(const void *src, void *dst, int64_t N, int K, int Hkv, int P, int L_dst, int dh, size_t esize,
+                         hipStream_t st)
+{
+    const int row16 = (int)(dh * esize / 16);
+    const int64_t total = N * Hkv * P * row16;
+    if (total <= 0) return;
+    hipLaunchKernelGGL(k_bcast_prefix, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const uint4 *)src,
+                       (uint4 *)dst, K, Hkv, P, L_dst, row16, total);
+}
+
+__global__ void k_fill_i32(int32_t *p, int v, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+void launch_fill_i32(int32_t *p, int v, int64_t n, hipStream_t st)
+{
+    if (n > 0) hipLaunchKernelGGL(k_fill_i32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, v, n);
+}
+
 // every row under the dense action: keep all keys, all `width` channels, quantiser bypassed
 __global__ void k_dense_rows(int width, int64_t M, RowAct *__restrict__ ra, int32_t *__restrict__ row_bucket)
 {

@@ -23,7 +23,7 @@ OP_LAYER_FORWARD, OP_DECODE_STEP, OP_SCHEDULE_LOGLIK, OP_KV_REFRESH, OP_REWARD =
 EXPORTS = ("sol_validate_config", "sol_create", "sol_destroy", "sol_last_error", "sol_workspace_bytes",
            "sol_layer_forward", "sol_decode_step", "sol_schedule_loglik", "sol_device_status",
            "sol_page_meta_bytes", "sol_page_meta_build", "sol_decode_step_paged", "sol_kv_refresh",
-           "sol_reward_advantages",
+           "sol_reward_advantages", "sol_episode_workspace_bytes", "sol_episode_loglik",
            "sol_profile_enable", "sol_profile_read",
            "sol_test_topk_select", "sol_test_prune_mask", "sol_test_prune_quant", "sol_test_quant_codes")
 
@@ -103,6 +103,11 @@ def lib():
         L.sol_reward_advantages.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                             C.POINTER(RewardCfg), C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.sol_episode_workspace_bytes.restype = C.c_size_t
+        L.sol_episode_workspace_bytes.argtypes = [C.POINTER(ModelCfg), C.c_int, C.c_int, C.c_int, C.c_int]
+        L.sol_episode_loglik.argtypes = [C.c_void_p, C.POINTER(ModelWeights), C.c_void_p, C.c_void_p, C.c_void_p,
+                                         C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                         C.c_size_t, C.c_void_p]
         L.sol_page_meta_bytes.restype = C.c_size_t
         L.sol_page_meta_bytes.argtypes = [C.POINTER(ModelCfg), C.c_int, C.c_int]
         L.sol_page_meta_build.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
@@ -298,6 +303,24 @@ class Sol:
         del keep
         self._check(rc)
         return x_out
+
+    def episode_loglik(self, layers, head, prefix_tokens, tokens, targets, action_ids, nll_out=None, workspace=None,
+                       stream=None):
+        """prefix_tokens int32 [B][P]; tokens/targets int32 [B][T]; action_ids int32 [B][K][T]: dense prefill once per
+        input, then K schedules of T controlled steps on it. Returns nll float32 [B][K][T] (nats)."""
+        B, K, T = action_ids.shape
+        P = prefix_tokens.shape[1]
+        mw, keep = self._model_struct(layers, head)
+        if nll_out is None:
+            nll_out = torch.empty((B, K, T), dtype=torch.float32, device="cuda")
+        need = int(self.L.sol_episode_workspace_bytes(C.byref(self.cfg), B, K, P, T))
+        ws = workspace if workspace is not None else torch.empty(need, dtype=torch.uint8, device="cuda")
+        rc = self.L.sol_episode_loglik(self.handle, C.byref(mw), _ptr(_i32(prefix_tokens)), _ptr(_i32(tokens)),
+                                       _ptr(_i32(targets)), _ptr(_i32(action_ids)), B, K, P, T, _ptr(nll_out), _ptr(ws),
+                                       ws.numel(), _stream(stream))
+        del keep
+        self._check(rc)
+        return nll_out
 
     def reward_advantages(self, nll, action_ids, targets, alpha, tau, gamma, eff=None, eps=1e-8, stream=None):
         """nll float32 / action_ids int32 [B][G][T], targets float32 [B][3], eff int32 [B][T] or None.

@@ -363,3 +363,36 @@ def test_kv_refresh_restores_the_dense_cache():
     k2 = [k.copy() for k in k_pol]
     oracle.kv_refresh(cfg, layers, x[:, T0:], np.array([T0], np.int32), k_pol, v_pol)
     assert all(np.array_equal(a, b) for a, b in zip(k2, k_pol))
+
+
+def test_episode_pass_equals_prefill_then_stepwise_decode():
+    """Method, "GRPO with per-sequence budget sampling": the episode NLLs (batched definition) against the same
+    episode walked the way it is deployed: dense prefill of the prefix layer by layer, then one decode step per token
+    under the schedule's action."""
+    import dataclasses
+    shape = dataclasses.replace(synth.TINY, n_layers=2, vocab=97)
+    table = synth.action_table((0.25, 1.0), (0.0, 0.75), (4, 16))
+    dense_id = table.index(synth.DENSE_ACTION)
+    cfg, tab = oracle.make_cfg(shape), oracle.make_table(table)
+    layers = [synth.layer_weights(shape, 950 + l) for l in range(2)]
+    head = synth.head_weights(shape, 960)
+    B, K, P, T = 1, 2, 10, 5
+    rng = np.random.default_rng(961)
+    prefix = rng.integers(0, shape.vocab, (B, P)).astype(np.int32)
+    tokens, targets = synth.tokens_and_targets(B, T, shape.vocab, 962)
+    ids = synth.iid_actions(len(table), (B, K, T), 963)
+    nll = oracle.episode_loglik(cfg, tab, dense_id, head["embed"], layers, head["w_final_norm"], head["lm_head"], prefix,
+                                tokens, targets, ids)
+    assert nll.shape == (B, K, T)
+    L = P + T
+    for k in range(K):
+        kc = [np.zeros((1, shape.n_kv_heads, L, shape.head_dim), np.float32) for _ in range(2)]
+        vc = [np.zeros_like(kc[0]) for _ in range(2)]
+        h = head["embed"][prefix[0]][None]
+        for l in range(2):
+            h, _ = oracle.layer_forward(cfg, tab, layers[l], h, np.full((1, P), dense_id, np.int32), kc[l], vc[l])
+        for t in range(T):
+            x0 = head["embed"][tokens[0, t]][None]
+            _, step_nll = oracle.decode_step(cfg, tab, layers, x0, ids[0, k, t:t + 1], np.array([P + t], np.int32), kc, vc,
+                                             head["w_final_norm"], head["lm_head"], targets[0, t:t + 1])
+            assert abs(float(step_nll[0]) - float(nll[0, k, t])) < 1e-4, (k, t)
