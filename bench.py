@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the action-conditioned decoder-layer path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c5|c4|c5d|c4p|refresh|episode]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c2p|c3|c5|c4|c5d|c4p|refresh|episode]
 
 A step is one pass of the measured unit over one batch of seeded synthetic input that is already
 resident in HBM. Default workload: the Llama-3.2-1B-shaped decoder layer, 4 inputs x 8 schedules
@@ -85,12 +85,12 @@ def stage_times(ctx, fn, steps):
     return {k: v[0] / steps for k, v in st.items()}, {k: v[1] // steps for k, v in st.items()}
 
 
-def run_layer(args, shape, n_inputs, G, T, table, name):
+def run_layer(args, shape, n_inputs, G, T, table, name, preset=None):
     n_seq = n_inputs * G
     w = synth.layer_weights(shape, args.seed, bf16=True)
     x = synth.hidden_states(n_seq, T, shape.d_model, args.seed + 1, bf16=True)
     ids = synth.iid_actions(len(table), (n_seq, T), args.seed + 2)
-    ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=T)
+    ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=T, **(preset or {}))
     wd = {k: _dev(v) for k, v in w.items()}
     xd, idd = _dev(x), _dev(ids)
     kc = torch.zeros((n_seq, shape.n_kv_heads, T, shape.head_dim), dtype=torch.bfloat16, device="cuda")
@@ -401,7 +401,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c5", "c4", "c5d", "c4p", "refresh", "episode"])
+    ap.add_argument("--workload", default="c2", choices=["c2", "c2p", "c3", "c5", "c4", "c5d", "c4p", "refresh", "episode"])
     ap.add_argument("--seed", type=int, default=1234)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -417,6 +417,11 @@ def main():
     if args.workload == "c2":
         res = run_layer(args, synth.LLAMA_1B, 4, 8, 1024, synth.TABLE_C2,
                         "C2: Llama-3.2-1B-shaped decoder layer, bf16, 4 inputs x 8 schedules x 1024 tokens")
+    elif args.workload == "c2p":
+        res = run_layer(args, synth.LLAMA_1B, 4, 8, 1024, synth.TABLE_C2,
+                        "C2 under the configuration of the paper's runs (pages of 16 keys, 4 sink + 2 window keys, pruning at the "
+                        "MLP input, quantiser on the MLP output): Llama-3.2-1B-shaped decoder layer, bf16, 4 inputs x 8 schedules "
+                        "x 1024 tokens", preset=sol.PAPER_PRESET)
     elif args.workload == "c3":
         import dataclasses
         shape = dataclasses.replace(synth.LLAMA_1B, n_layers=16, vocab=128256)

@@ -264,7 +264,7 @@ struct Carver {
 
 struct LayerWs {
     RowAct *ra; int32_t *row_bucket, *perm, *bucket_off, *seq_order;
-    void *h, *qb, *a, *vt;
+    void *h, *qb, *a, *vt, *pm;
     float *big32, *o32, *x2, *hn32;
 };
 
@@ -298,6 +298,8 @@ static void carve_layer(Carver &c, const sol_model_cfg &g, int64_t n_seq, int64_
     // transposed V copy for the tiled attention kernel (batched bf16 pass only)
     const bool tiled = g.dtype == SOL_BF16 && T >= 16 && L_max <= 4096;
     w.vt = c.take(tiled ? es * n_seq * g.n_kv_heads * g.head_dim * (size_t)attn_tile_lpadv(L_max) : 0);
+    // per-key page extremes for the tiled kernels under the page rule
+    w.pm = c.take(tiled && g.page_size > 1 ? attn_tile_pages_meta_bytes(n_seq, g.n_kv_heads, L_max, g.head_dim) : 0);
 }
 
 static int64_t lm_chunk_rows(const sol_model_cfg &g, int64_t M)
@@ -414,8 +416,11 @@ static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_i
         AttnOpts opt;
         if (!dense_pass) { opt.page = g.page_size; opt.n_sink = g.n_sink; opt.n_window = g.n_window; }   // dense rows keep every key under any rule
         const bool fast = mfma && opt.plain();       // the tiled and decode kernels know the plain top-k rule only
-        const bool tiled = fast && w.vt && T >= 16 && L_max <= 4096 &&
-                           launch_attn_tile(w.qb, kc, vc, w.vt, w.big32, w.o32, w.ra, pos0, n_seq, T, L_max, Hq, Hkv, dh, st);
+        bool tiled = fast && w.vt && T >= 16 && L_max <= 4096 &&
+                     launch_attn_tile(w.qb, kc, vc, w.vt, w.big32, w.o32, w.ra, pos0, n_seq, T, L_max, Hq, Hkv, dh, st);
+        if (!tiled && mfma && opt.page > 1 && w.vt && w.pm && T >= 16 && L_max <= 4096 &&
+            attn_tile_pages_sel_bytes(M, Hq, L_max, opt.page) <= 4 * (size_t)M * nqkv)   // the masks live in big32
+            tiled = launch_attn_tile_pages(w.qb, kc, vc, w.vt, w.pm, w.big32, w.o32, w.ra, pos0, n_seq, T, L_max, Hq, Hkv, dh, opt, st);
         bool dec = !tiled && fast && T == 1 && pos0 &&
                    launch_attn_decode(w.qb, kc, vc, w.o32, w.ra, pos0, w.seq_order, n_seq, L_max, Hq, Hkv, dh, ctx->d_flags, st);
         if (!tiled && !dec && mfma && T == 1 && pos0 && page_meta && opt.page > 1) {

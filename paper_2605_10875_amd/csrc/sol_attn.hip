@@ -1751,6 +1751,389 @@ static bool launch_attn_pv_t(const void *q, const void *kc, const void *vt, cons
     return true;
 }
 
+// =================================================================================================
+// Batched bf16 attention under the page rule (page size S a power of two, 4 <= S <= 64), sink / window keys.
+//   k_page_prefix_meta : pm[j] = channel-wise [max | min] over the keys of j's page up to j (2 * dh values per key).
+//                        The last key of a full page carries the page's extremes; row p is the partial page of the
+//                        query at position p.
+//   k_attn_select_pages: per (16 query rows, head): page bounds [max(q,0) | min(q,0)] . pm on MFMA (full pages as one
+//                        tile product, the partial page of every query as the diagonal of one more tile), then per
+//                        row the top ceil(b / S) bounds, ties to the lower page -> a bit mask of kept pages.
+//   k_attn_pv_pages    : k_attn_pv with the mask (and the forced keys) as keep rule and a running maximum, since the
+//                        largest kept score is not known beforehand.
+// =================================================================================================
+template <int DH>
+__global__ void __launch_bounds__(256)
+k_page_prefix_meta(const bf16_t *__restrict__ kc, const int32_t *__restrict__ pos0, bf16_t *__restrict__ pm, int Tn, int S,
+                   int L_max, int Hkv)
+{
+    constexpr int LPK = DH / 8, PPB = 256 / LPK;
+    const int s = blockIdx.z, kvh = blockIdx.y;
+    const int u = blockIdx.x * PPB + threadIdx.x / LPK, cs = threadIdx.x % LPK;
+    const int p0 = pos0 ? pos0[s] : 0;
+    if (p0 < 0 || p0 + Tn > L_max) return;
+    const int n = p0 + Tn, j0 = u * S;
+    if (j0 >= n) return;
+    const int j1 = j0 + S < n ? j0 + S : n;
+    const bf16_t *kb = kc + ((int64_t)s * Hkv + kvh) * (int64_t)L_max * DH + cs * 8;
+    bf16_t *pb = pm + ((int64_t)s * Hkv + kvh) * (int64_t)L_max * (2 * DH) + cs * 8;
+    float mx[8], mn[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { mx[e] = -INFINITY; mn[e] = INFINITY; }
+    for (int j = j0; j < j1; ++j) {
+        const u32x4_a v = *reinterpret_cast<const u32x4_a *>(kb + (int64_t)j * DH);
+        u32x4_a omx, omn;
+#pragma unroll
+        for (int wi = 0; wi < 4; ++wi) {
+            const float a = __uint_as_float(v[wi] << 16), b = __uint_as_float(v[wi] & 0xFFFF0000u);
+            mx[2 * wi] = fmaxf(mx[2 * wi], a); mn[2 * wi] = fminf(mn[2 * wi], a);
+            mx[2 * wi + 1] = fmaxf(mx[2 * wi + 1], b); mn[2 * wi + 1] = fminf(mn[2 * wi + 1], b);
+            omx[wi] = (__float_as_uint(mx[2 * wi]) >> 16) | (__float_as_uint(mx[2 * wi + 1]) & 0xFFFF0000u);
+            omn[wi] = (__float_as_uint(mn[2 * wi]) >> 16) | (__float_as_uint(mn[2 * wi + 1]) & 0xFFFF0000u);
+        }
+        *reinterpret_cast<u32x4_a *>(pb + (int64_t)j * (2 * DH)) = omx;
+        *reinterpret_cast<u32x4_a *>(pb + (int64_t)j * (2 * DH) + DH) = omn;
+    }
+}
+
+template <int DH, int W>
+__global__ void __launch_bounds__(256)
+k_attn_select_pages(const bf16_t *__restrict__ q, const bf16_t *__restrict__ pm, unsigned long long *__restrict__ selp,
+                    const RowAct *__restrict__ ra, const int32_t *__restrict__ pos0, int Tn, int L_max, int Hq, int Hkv,
+                    int log2S)
+{
+    constexpr int KK = DH / 32, KK2 = 2 * KK, PS = 64 * W + 4, BQ = 16;
+    __shared__ float sb[BQ][PS];                             // bounds of the full pages, [query][page]
+    __shared__ float sd[BQ];                                 // bound of each query's own (partial) page
+    const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, lg = lane >> 4;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int q0 = blockIdx.x * BQ, h = blockIdx.y, s = blockIdx.z;
+    const int kvh = h / (Hq / Hkv);
+    const int p0 = pos0 ? pos0[s] : 0;
+    if (p0 < 0 || p0 + Tn > L_max) return;
+    const int S = 1 << log2S;
+    const int q_last = (q0 + BQ - 1 < Tn ? q0 + BQ - 1 : Tn - 1);
+    const int u_max = (p0 + q_last) >> log2S;                // last page any query of the block touches
+    const bf16_t *pmb = pm + ((int64_t)s * Hkv + kvh) * (int64_t)L_max * (2 * DH);
+
+    // queries as MFMA B operand: column l16 = query q0 + l16, doubled row [max(q, 0) | min(q, 0)]
+    bf16x8_a qq[KK2];
+    {
+        const int qi = q0 + l16 < Tn ? q0 + l16 : Tn - 1;
+        const bf16_t *qp = q + ((int64_t)s * Tn + qi) * (int64_t)(Hq * DH) + (int64_t)h * DH + lg * 8;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+            const u32x4_a raw = *reinterpret_cast<const u32x4_a *>(qp + kk * 32);
+            u32x4_a a, b;
+#pragma unroll
+            for (int wi = 0; wi < 4; ++wi) { a[wi] = q_split_pair(raw[wi], false); b[wi] = q_split_pair(raw[wi], true); }
+            qq[kk] = __builtin_bit_cast(bf16x8_a, a);
+            qq[KK + kk] = __builtin_bit_cast(bf16x8_a, b);
+        }
+    }
+    // full pages: tile pt holds pages 16 pt .. 16 pt + 15; page u is read from the row of its last key
+    const int n_pt = (u_max + 16) >> 4;
+    for (int pt = w; pt < n_pt; pt += 4) {
+        int j = (((pt * 16 + l16) + 1) << log2S) - 1;
+        j = j < L_max ? j : L_max - 1;                       // pages past the live keys are masked below
+        const bf16_t *mp = pmb + (int64_t)j * (2 * DH) + lg * 8;
+        floatx4_a acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < KK2; ++kk) {
+            const bf16x8_a mf = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(mp + kk * 32));
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(mf, qq[kk], acc, 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) sb[l16][pt * 16 + lg * 4 + r] = acc[r];
+    }
+    if (w == 3) {                                            // the queries' own pages: row m = the key of query m; diagonal
+        int j = p0 + q0 + l16;
+        j = j < p0 + Tn ? j : p0 + Tn - 1;
+        const bf16_t *mp = pmb + (int64_t)j * (2 * DH) + lg * 8;
+        floatx4_a acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < KK2; ++kk) {
+            const bf16x8_a mf = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(mp + kk * 32));
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(mf, qq[kk], acc, 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            if (lg * 4 + r == l16) sd[l16] = acc[r];
+    }
+    __syncthreads();
+
+    // ---- per query row: the top ceil(b / S) pages ------------------------------------------------
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    for (int i = 4 * w; i < 4 * w + 4; ++i) {
+        const int qi = q0 + i;
+        if (qi >= Tn) break;                                 // uniform
+        const int p = p0 + qi, n = p + 1, u_p = p >> log2S, npg = u_p + 1;
+        const RowAct act = ra[(int64_t)s * Tn + qi];
+        const int b = __builtin_amdgcn_readfirstlane(budget_ceil(act.keep_num, act.keep_den, n));
+        int np = (b + S - 1) >> log2S;
+        np = np < npg ? np : npg;
+        unsigned long long mask[W];
+        if (b >= n || np >= npg) {
+#pragma unroll
+            for (int ww = 0; ww < W; ++ww) mask[ww] = ~0ull;
+        } else {
+            uint32_t key[W];
+            uint32_t kmax = 0u, kmin = 0xFFFFFFFFu;
+#pragma unroll
+            for (int ww = 0; ww < W; ++ww) {
+                const int u = 64 * ww + lane;
+                const float v = u < u_p ? sb[i][u] : sd[i];
+                key[ww] = u <= u_p ? score_key(v) : 0u;
+                if (u <= u_p) { kmax = key[ww] > kmax ? key[ww] : kmax; kmin = key[ww] < kmin ? key[ww] : kmin; }
+            }
+            uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)wave_min_u32(kmin));
+            uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)wave_max_u32(kmax));
+            auto count_ge = [&](uint32_t t) -> int {
+                int c = 0;
+#pragma unroll
+                for (int ww = 0; ww < W; ++ww) c += __popcll(__ballot(key[ww] >= t));
+                return c;
+            };
+            bool exact = false;                              // invariant: count(key >= lo) >= np, count(key >= hi + 1) < np
+            while (lo < hi) {
+                const uint32_t mid = lo + ((hi - lo + 1u) >> 1);
+                const int c = count_ge(mid);
+                if (c == np) { lo = mid; exact = true; break; }
+                if (c > np) lo = mid; else hi = mid - 1u;
+            }
+            const uint32_t thr = lo;
+            int quota = 64 * W;                              // tied pages kept, lowest pages first
+            if (!exact) {
+                const int n_ge = count_ge(thr);
+                if (n_ge > np) quota = np - (thr == 0xFFFFFFFFu ? 0 : count_ge(thr + 1u));
+            }
+#pragma unroll
+            for (int ww = 0; ww < W; ++ww) {
+                const bool tie = key[ww] == thr && 64 * ww + lane <= u_p;
+                const unsigned long long bal = __ballot(tie);
+                const bool keep = key[ww] > thr || (tie && __popcll(bal & lt_mask) < quota);
+                mask[ww] = __ballot(keep);
+                const int total = __popcll(bal);
+                quota = quota > total ? quota - total : 0;
+            }
+        }
+        if (lane == 0) {
+            unsigned long long *o = selp + (((int64_t)s * Tn + qi) * Hq + h) * W;
+#pragma unroll
+            for (int ww = 0; ww < W; ++ww) o[ww] = mask[ww];
+        }
+    }
+}
+
+template <int DH, int G, int W>
+__global__ void __launch_bounds__(G * 64)
+k_attn_pv_pages(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf16_t *__restrict__ vt,
+                const unsigned long long *__restrict__ selp, float *__restrict__ o32, const int32_t *__restrict__ pos0, int Tn,
+                int L_max, int Hq, int Hkv, int lpadv, float scale, int log2S, int n_sink, int n_window)
+{
+    constexpr int NT = G * 64, KK = DH / 32, DT = DH / 16, KC = 64, QT = 32;
+    constexpr int KP = DH / 8;
+    constexpr int K_PIECES = KC * KP / NT, V_PIECES = DH * (KC / 8) / NT;
+    constexpr int K_BYTES = KC * DH * 2, STAGE = 2 * K_BYTES;
+    static_assert(KC * KP % NT == 0 && DH * (KC / 8) % NT == 0, "chunk / thread mismatch");
+    extern __shared__ __align__(16) unsigned char pvl[];
+
+    const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, lg = lane >> 4;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int qb = (int)gridDim.x - 1 - (int)blockIdx.x;
+    const int kvh = blockIdx.y, s = blockIdx.z, h = kvh * G + w;
+    const int p0 = pos0 ? pos0[s] : 0;
+    if (p0 < 0 || p0 + Tn > L_max) return;
+    const int q0 = qb * QT;
+    const int rows = (Tn - q0 < QT) ? (Tn - q0) : QT;
+    const int n_max = p0 + q0 + rows;
+    const int n_chunks = (n_max + KC - 1) / KC;
+    const bf16_t *kbase = kc + ((int64_t)s * Hkv + kvh) * (int64_t)L_max * DH;
+    const bf16_t *vbase = vt + ((int64_t)s * Hkv + kvh) * (int64_t)DH * lpadv;
+    const float sl2 = scale * 1.44269504088896341f;          // scores in the log2 domain
+
+    bf16x8_a qf[2][KK];
+    unsigned long long mask[2][W];
+    float m_run[2] = {-INFINITY, -INFINITY}, den[2] = {0.f, 0.f};
+    int pos[2], sink_end[2], win_begin[2];
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+        const int qi = q0 + 16 * qt + l16;
+        const bool live = qi < Tn;
+        const int qr = live ? qi : Tn - 1;
+        const bf16_t *qp = q + ((int64_t)s * Tn + qr) * (int64_t)(Hq * DH) + (int64_t)h * DH + lg * 8;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk)
+            qf[qt][kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(qp + kk * 32));
+        const unsigned long long *mp = selp + (((int64_t)s * Tn + qr) * Hq + h) * W;
+#pragma unroll
+        for (int ww = 0; ww < W; ++ww) mask[qt][ww] = mp[ww];
+        pos[qt] = live ? p0 + qi : -1;                      // dead rows of a ragged block keep nothing
+        const int n = p0 + qi + 1;
+        sink_end[qt] = n_sink < n ? n_sink : n;
+        win_begin[qt] = n - n_window > sink_end[qt] ? n - n_window : sink_end[qt];
+    }
+
+    floatx4_a oacc[2][DT];
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) oacc[qt][dt] = floatx4_a{0.f, 0.f, 0.f, 0.f};
+
+    u32x4_a kreg0[K_PIECES], vreg0[V_PIECES], kreg1[K_PIECES], vreg1[V_PIECES];
+#define SOL_PV_GLOAD(KR, VR, CH_)                                                                                  \
+    {                                                                                                      \
+        const int key0_ = (CH_) * KC;                                                                      \
+        _Pragma("unroll") for (int i = 0; i < K_PIECES; ++i) {                                             \
+            const int pc = i * NT + tid, row = pc / KP, piece = pc - row * KP;                             \
+            int key = key0_ + row;                                                                         \
+            if (key >= n_max) key = n_max - 1;                                                             \
+            KR[i] = *reinterpret_cast<const u32x4_a *>(kbase + (int64_t)key * DH + piece * 8);             \
+        }                                                                                                  \
+        _Pragma("unroll") for (int i = 0; i < V_PIECES; ++i) {                                             \
+            const int pc = i * NT + tid, d = pc >> 3, piece = pc & 7;                                      \
+            VR[i] = *reinterpret_cast<const u32x4_a *>(vbase + (int64_t)d * lpadv + key0_ + piece * 8);    \
+        }                                                                                                  \
+    }
+#define SOL_PV_LSTORE(KR, VR, STG_)                                                                                \
+    {                                                                                                      \
+        unsigned char *kb_ = pvl + (STG_) * STAGE, *vb_ = kb_ + K_BYTES;                                   \
+        _Pragma("unroll") for (int i = 0; i < K_PIECES; ++i) {                                             \
+            const int pc = i * NT + tid, row = pc / KP, piece = pc - row * KP;                             \
+            *reinterpret_cast<u32x4_a *>(kb_ + row * (DH * 2) + ((piece ^ pv_swz_k<DH>(row)) << 4)) = KR[i]; \
+        }                                                                                                  \
+        _Pragma("unroll") for (int i = 0; i < V_PIECES; ++i) {                                             \
+            const int pc = i * NT + tid, d = pc >> 3, piece = pc & 7;                                      \
+            *reinterpret_cast<u32x4_a *>(vb_ + d * (KC * 2) + ((piece ^ ((d >> 1) & 7)) << 4)) = VR[i];    \
+        }                                                                                                  \
+    }
+    SOL_PV_GLOAD(kreg0, vreg0, 0);
+    SOL_PV_LSTORE(kreg0, vreg0, 0);
+    if (1 < n_chunks) SOL_PV_GLOAD(kreg1, vreg1, 1);
+    __syncthreads();
+    for (int ch = 0; ch < n_chunks; ++ch) {
+        const int stg = ch & 1;
+        if (stg == 0) {
+            if (ch + 1 < n_chunks) SOL_PV_LSTORE(kreg1, vreg1, 1);
+            if (ch + 2 < n_chunks) SOL_PV_GLOAD(kreg0, vreg0, ch + 2);
+        } else {
+            if (ch + 1 < n_chunks) SOL_PV_LSTORE(kreg0, vreg0, 0);
+            if (ch + 2 < n_chunks) SOL_PV_GLOAD(kreg1, vreg1, ch + 2);
+        }
+        const unsigned char *kb = pvl + stg * STAGE, *vb = kb + K_BYTES;
+#pragma unroll
+        for (int cc = 0; cc < 2; ++cc) {
+            const int kb32 = ch * KC + cc * 32;
+            if (kb32 < n_max) {
+                floatx4_a st[2][2];
+#pragma unroll
+                for (int kt = 0; kt < 2; ++kt) {
+                    const int krow = cc * 32 + 8 * (l16 >> 2) + 4 * kt + (l16 & 3);
+                    bf16x8_a kf[KK];
+#pragma unroll
+                    for (int kk = 0; kk < KK; ++kk)
+                        kf[kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(
+                            kb + krow * (DH * 2) + (((kk * 4 + lg) ^ pv_swz_k<DH>(krow)) << 4)));
+#pragma unroll
+                    for (int qt = 0; qt < 2; ++qt) {
+                        floatx4_a acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                        for (int kk = 0; kk < KK; ++kk)
+                            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kk], qf[qt][kk], acc, 0, 0, 0);
+                        st[qt][kt] = acc;
+                    }
+                }
+                // keep rule, running maximum (log2 domain), numerators as hi + lo bf16 pairs
+                bf16x8_a phi[2], plo[2];
+                float fac[2];
+                bool grew = false;
+                const int kfirst = kb32 + 8 * lg;
+#pragma unroll
+                for (int qt = 0; qt < 2; ++qt) {
+                    float x[8];
+                    float m_loc = -INFINITY;
+#pragma unroll
+                    for (int kt = 0; kt < 2; ++kt) {
+                        const int j0 = kfirst + 4 * kt;      // 4 consecutive keys of one page (S >= 4)
+                        const int u = j0 >> log2S;
+                        unsigned long long word = mask[qt][0];
+#pragma unroll
+                        for (int ww = 1; ww < W; ++ww) word = (u >> 6) == ww ? mask[qt][ww] : word;
+                        const bool bit = ((word >> (u & 63)) & 1ull) != 0ull;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const int j = j0 + r;
+                            const bool keep = (bit || j < sink_end[qt] || j >= win_begin[qt]) && j <= pos[qt];
+                            x[4 * kt + r] = keep ? st[qt][kt][r] * sl2 : -INFINITY;
+                            m_loc = fmaxf(m_loc, x[4 * kt + r]);
+                        }
+                    }
+                    m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 16));
+                    m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32));
+                    const float m_new = fmaxf(m_run[qt], m_loc);
+                    const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+                    grew |= m_new > m_run[qt];
+                    fac[qt] = __builtin_amdgcn_exp2f(m_run[qt] - m_safe);     // exp2(-inf) = 0 before the first kept key
+                    m_run[qt] = m_new;
+                    float p[8], psum = 0.f;
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) { p[i] = __builtin_amdgcn_exp2f(x[i] - m_safe); psum += p[i]; }
+                    den[qt] = den[qt] * fac[qt] + psum;
+                    u32x4_a hi, lo;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        hi[i] = pack_bf16x2(p[2 * i], p[2 * i + 1]);
+                        lo[i] = pack_bf16x2(p[2 * i] - __uint_as_float(hi[i] << 16), p[2 * i + 1] - __uint_as_float(hi[i] & 0xFFFF0000u));
+                    }
+                    phi[qt] = __builtin_bit_cast(bf16x8_a, hi);
+                    plo[qt] = __builtin_bit_cast(bf16x8_a, lo);
+                }
+                if (__ballot(grew) != 0ull) {                // some row's maximum moved: rescale what is accumulated
+#pragma unroll
+                    for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const float fo = __shfl(fac[qt], 4 * lg + r);    // accumulator register r is query 4 lg + r
+#pragma unroll
+                            for (int dt = 0; dt < DT; ++dt) oacc[qt][dt][r] *= fo;
+                        }
+                }
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) {
+                    const int d = dt * 16 + l16;
+                    const bf16x8_a vf = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(
+                        vb + d * (KC * 2) + (((cc * 4 + lg) ^ ((d >> 1) & 7)) << 4)));
+#pragma unroll
+                    for (int qt = 0; qt < 2; ++qt) {
+                        oacc[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(plo[qt], vf, oacc[qt][dt], 0, 0, 0);
+                        oacc[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(phi[qt], vf, oacc[qt][dt], 0, 0, 0);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+    }
+#undef SOL_PV_GLOAD
+#undef SOL_PV_LSTORE
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+        float dsum = den[qt];
+        dsum += __shfl_xor(dsum, 16);
+        dsum += __shfl_xor(dsum, 32);
+        const float inv = dsum > 0.f ? 1.0f / dsum : 0.f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float iv = __shfl(inv, 4 * lg + r);
+            const int qi = q0 + 16 * qt + 4 * lg + r;
+            if (qi < Tn) {
+                float *op = o32 + ((int64_t)s * Tn + qi) * (int64_t)(Hq * DH) + (int64_t)h * DH + l16;
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) op[dt * 16] = oacc[qt][dt][r] * iv;
+            }
+        }
+    }
+}
+
 int attn_tile_lpadv(int L_max) { return (L_max + 63) & ~63; }
 size_t attn_tile_sel_bytes(int64_t rows, int Hq) { return (size_t)rows * Hq * sizeof(SelRow); }
 
@@ -1790,6 +2173,76 @@ bool launch_attn_tile(const void *q, const void *k_cache, const void *v_cache, v
     if (G == 4) { SOL_PV(4); }
     SOL_PV(8);
 #undef SOL_PV
+}
+
+template <int DH, int W>
+static bool launch_attn_tile_pages_t(const void *q, const void *kc, const void *vt, void *pm, void *selp, float *o32,
+                                     const RowAct *ra, const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv,
+                                     int lpadv, int log2S, AttnOpts opt, hipStream_t st)
+{
+    const int S = 1 << log2S, G = Hq / Hkv;
+    constexpr int ppb = 256 / (DH / 8);
+    hipLaunchKernelGGL(k_page_prefix_meta<DH>, dim3(((L_max + S - 1) / S + ppb - 1) / ppb, Hkv, n_seq), dim3(256), 0, st,
+                       (const bf16_t *)kc, pos0, (bf16_t *)pm, T, S, L_max, Hkv);
+    hipLaunchKernelGGL((k_attn_select_pages<DH, W>), dim3((T + 15) / 16, Hq, n_seq), dim3(256), 0, st, (const bf16_t *)q,
+                       (const bf16_t *)pm, (unsigned long long *)selp, ra, pos0, T, L_max, Hq, Hkv, log2S);
+    const size_t lds = 4 * (size_t)64 * DH * 2;
+    const float scale = 1.0f / sqrtf((float)DH);
+#define SOL_PVP(G_)                                                                                                  \
+    {                                                                                                                \
+        auto kern = k_attn_pv_pages<DH, G_, W>;                                                                      \
+        static bool attr_done = false;                                                                               \
+        if (!attr_done) {                                                                                            \
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                    (int)lds) != hipSuccess)                                                         \
+                return false;                                                                                        \
+            attr_done = true;                                                                                        \
+        }                                                                                                            \
+        hipLaunchKernelGGL(kern, dim3((T + 31) / 32, Hkv, n_seq), dim3(G_ * 64), lds, st, (const bf16_t *)q,         \
+                           (const bf16_t *)kc, (const bf16_t *)vt, (const unsigned long long *)selp, o32, pos0, T, L_max, Hq, \
+                           Hkv, lpadv, scale, log2S, opt.n_sink, opt.n_window);                                      \
+        return true;                                                                                                 \
+    }
+    if (G == 1) SOL_PVP(1)
+    if (G == 2) SOL_PVP(2)
+    if (G == 4) SOL_PVP(4)
+    SOL_PVP(8)
+#undef SOL_PVP
+}
+
+size_t attn_tile_pages_meta_bytes(int64_t n_seq, int Hkv, int L_max, int dh) { return (size_t)n_seq * Hkv * L_max * 2 * dh * 2; }
+size_t attn_tile_pages_sel_bytes(int64_t rows, int Hq, int L_max, int S) { return (size_t)rows * Hq * (((L_max + S - 1) / S + 63) / 64) * 8; }
+
+// Batched bf16 attention under the page rule: page size a power of two in [4, 64], at most 256 pages, the limits of
+// launch_attn_tile otherwise. pm: attn_tile_pages_meta_bytes of scratch, selp: attn_tile_pages_sel_bytes.
+bool launch_attn_tile_pages(const void *q, const void *k_cache, const void *v_cache, void *vt, void *pm, void *selp,
+                            float *o32, const RowAct *ra, const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv,
+                            int dh, AttnOpts opt, hipStream_t st)
+{
+    if ((int64_t)n_seq * T <= 0) return true;
+    const int G = Hkv > 0 ? Hq / Hkv : 0, S = opt.page;
+    if ((dh != 64 && dh != 128) || L_max > 4096 || T < 16 || G * Hkv != Hq || (G != 1 && G != 2 && G != 4 && G != 8))
+        return false;
+    if (S < 4 || S > 64 || (S & (S - 1)) || !pm || !vt) return false;
+    int log2S = 0;
+    while ((1 << log2S) < S) ++log2S;
+    const int n_words = ((L_max + S - 1) / S + 63) / 64;
+    if (n_words > 4) return false;
+    const int lpadv = attn_tile_lpadv(L_max);
+    const dim3 tg((lpadv + 63) / 64, Hkv, n_seq);
+    if (dh == 64)
+        hipLaunchKernelGGL((k_transpose_v<64>), tg, dim3(256), 0, st, (const bf16_t *)v_cache, (bf16_t *)vt, pos0, T,
+                           L_max, Hkv, lpadv);
+    else
+        hipLaunchKernelGGL((k_transpose_v<128>), tg, dim3(256), 0, st, (const bf16_t *)v_cache, (bf16_t *)vt, pos0, T,
+                           L_max, Hkv, lpadv);
+#define SOL_TP(W_)                                                                                                   \
+    return dh == 64 ? launch_attn_tile_pages_t<64, W_>(q, k_cache, vt, pm, selp, o32, ra, pos0, n_seq, T, L_max, Hq, Hkv, lpadv, log2S, opt, st) \
+                    : launch_attn_tile_pages_t<128, W_>(q, k_cache, vt, pm, selp, o32, ra, pos0, n_seq, T, L_max, Hq, Hkv, lpadv, log2S, opt, st)
+    if (n_words == 1) { SOL_TP(1); }
+    if (n_words == 2) { SOL_TP(2); }
+    SOL_TP(4);
+#undef SOL_TP
 }
 
 }  // namespace sol

@@ -151,6 +151,14 @@ bool launch_attn_tile(const void *q, const void *k_cache, const void *v_cache, v
                       const RowAct *ra, const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv, int dh,
                       hipStream_t st);
 size_t attn_tile_sel_bytes(int64_t rows, int Hq);
+// The same under the page rule (page size a power of two in [4, 64], at most 256 pages) with sink / window keys:
+// per-key prefix extremes of the pages (pm scratch), a bit mask of kept pages per (row, head) (selp scratch), then
+// the flash-style kernel with a running maximum.
+bool launch_attn_tile_pages(const void *q, const void *k_cache, const void *v_cache, void *vt, void *pm, void *selp,
+                            float *o32, const RowAct *ra, const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv,
+                            int dh, AttnOpts opt, hipStream_t st);
+size_t attn_tile_pages_meta_bytes(int64_t n_seq, int Hkv, int L_max, int dh);
+size_t attn_tile_pages_sel_bytes(int64_t rows, int Hq, int L_max, int S);
 int attn_tile_lpadv(int L_max);
 
 // ---- reward reduction (sol_reward.hip) ----------------------------------------------------------
