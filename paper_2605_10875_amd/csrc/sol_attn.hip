@@ -1925,6 +1925,18 @@ k_attn_select_pages(const bf16_t *__restrict__ q, const bf16_t *__restrict__ pm,
     }
 }
 
+// maximum over the four lanes l16, l16 + 16, l16 + 32, l16 + 48 with the gfx950 lane-swap instructions (vector ALU
+// only: v_permlane32_swap exchanges the upper half of one operand with the lower half of the other,
+// v_permlane16_swap the odd rows of 16 lanes of one with the even rows of the other)
+typedef uint32_t u32x2_a __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float max_over_lane_groups(float v)
+{
+    const u32x2_a a = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    const u32x2_a b = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+
 template <int DH, int G, int W>
 __global__ void __launch_bounds__(G * 64)
 k_attn_pv_pages(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf16_t *__restrict__ vt,
@@ -2044,10 +2056,13 @@ k_attn_pv_pages(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, con
                     }
                 }
                 // keep rule, running maximum (log2 domain), numerators as hi + lo bf16 pairs
-                bf16x8_a phi[2], plo[2];
-                float fac[2];
+                bf16x8_a phi[2], plo[2];                    // numerators as hi + lo bf16 pairs (single bf16 numerators cost
+                float fac[2];                               // ~1e-2 of a short row: measured, not taken)
                 bool grew = false;
                 const int kfirst = kb32 + 8 * lg;
+                // sub-chunks wholly before every query of the block and free of sink / window keys need the page
+                // bit only (one test per 4 keys, folded into the scaling as an additive 0 / -inf)
+                const bool plain = kb32 + 31 <= p0 + q0 && kb32 >= n_sink && kb32 + 31 < p0 + q0 + 1 - n_window;
 #pragma unroll
                 for (int qt = 0; qt < 2; ++qt) {
                     float x[8];
@@ -2060,16 +2075,24 @@ k_attn_pv_pages(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, con
 #pragma unroll
                         for (int ww = 1; ww < W; ++ww) word = (u >> 6) == ww ? mask[qt][ww] : word;
                         const bool bit = ((word >> (u & 63)) & 1ull) != 0ull;
+                        if (plain) {
+                            const float off = bit ? 0.f : -INFINITY;
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            const int j = j0 + r;
-                            const bool keep = (bit || j < sink_end[qt] || j >= win_begin[qt]) && j <= pos[qt];
-                            x[4 * kt + r] = keep ? st[qt][kt][r] * sl2 : -INFINITY;
-                            m_loc = fmaxf(m_loc, x[4 * kt + r]);
+                            for (int r = 0; r < 4; ++r) {
+                                x[4 * kt + r] = __builtin_fmaf(st[qt][kt][r], sl2, off);
+                                m_loc = fmaxf(m_loc, x[4 * kt + r]);
+                            }
+                        } else {
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) {
+                                const int j = j0 + r;
+                                const bool keep = (bit || j < sink_end[qt] || j >= win_begin[qt]) && j <= pos[qt];
+                                x[4 * kt + r] = keep ? st[qt][kt][r] * sl2 : -INFINITY;
+                                m_loc = fmaxf(m_loc, x[4 * kt + r]);
+                            }
                         }
                     }
-                    m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 16));
-                    m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32));
+                    m_loc = max_over_lane_groups(m_loc);
                     const float m_new = fmaxf(m_run[qt], m_loc);
                     const float m_safe = m_new == -INFINITY ? 0.f : m_new;
                     grew |= m_new > m_run[qt];
