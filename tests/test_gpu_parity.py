@@ -1,7 +1,7 @@
 """GPU parity proper: the HIP path, called through the C ABI, against the CPU oracle on the same
 seeded synthetic inputs.
 
-Tolerances (written here, derived in the design doc). max-rel = max|gpu - ref| / max|ref| over the tensor,
+Tolerances (written here, each with its reason). max-rel = max|gpu - ref| / max|ref| over the tensor,
 evaluated per token row.
   fp32 configuration: rows within 1e-4, NLL within 1e-3 nats.
   bf16 configuration: rows within 2e-2 and NLL within 1e-2 nats against the oracle run with the

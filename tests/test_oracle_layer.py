@@ -110,14 +110,14 @@ def test_dense_action_is_the_textbook_layer():
     assert np.array_equal(out_p, out) and np.array_equal(kc2, kc)
 
 
-@pytest.mark.parametrize("preset", ["northstar", "paper_sites"])
+@pytest.mark.parametrize("preset", ["linear_input_sites", "paper_sites"])
 def test_action_conditioned_layer_against_witness(preset):
     table = synth.action_table((0.25, 0.5, 1.0), (0.0, 0.25, 0.5), (4, 8, 16))
     w = synth.layer_weights(SHAPE, 21, std=0.15)
     n, T = 2, 14
     x = synth.hidden_states(n, T, SHAPE.d_model, 22)
     ids = synth.iid_actions(len(table), (n, T), 23)
-    if preset == "northstar":
+    if preset == "linear_input_sites":
         kw = dict()
         wkw = dict()
     else:
@@ -140,7 +140,7 @@ def test_action_conditioned_layer_against_witness(preset):
                 top = sorted(range(i + 1), key=lambda j: (-row[j], j))[:b]
                 assert km[s, i, h, :i + 1].sum() == b and km[s, i, h, i + 1:].sum() == 0
                 assert set(np.nonzero(km[s, i, h])[0]) == set(top)
-            if preset == "northstar" and table[ids[s, i]][4] >= 16:   # small codes round to 0
+            if preset == "linear_input_sites" and table[ids[s, i]][4] >= 16:   # small codes round to 0
                 mnum, mden = table[ids[s, i]][2:4]
                 m = math.ceil(mnum * SHAPE.d_ff / mden)
                 assert np.count_nonzero(taps["mlp_act"][s, i]) == m
