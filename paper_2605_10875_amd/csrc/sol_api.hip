@@ -416,7 +416,9 @@ static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_i
         AttnOpts opt;
         if (!dense_pass) { opt.page = g.page_size; opt.n_sink = g.n_sink; opt.n_window = g.n_window; }   // dense rows keep every key under any rule
         const bool fast = mfma && opt.plain();       // the tiled and decode kernels know the plain top-k rule only
-        bool tiled = fast && w.vt && T >= 16 && L_max <= 4096 &&
+        bool tiled = dense_pass && mfma && w.vt && T >= 16 && L_max <= 4096 &&
+                     launch_attn_tile_dense(w.qb, kc, vc, w.vt, w.o32, pos0, n_seq, T, L_max, Hq, Hkv, dh, st);
+        tiled = tiled || fast && w.vt && T >= 16 && L_max <= 4096 &&
                      launch_attn_tile(w.qb, kc, vc, w.vt, w.big32, w.o32, w.ra, pos0, n_seq, T, L_max, Hq, Hkv, dh, st);
         if (!tiled && mfma && opt.page > 1 && w.vt && w.pm && T >= 16 && L_max <= 4096 &&
             attn_tile_pages_sel_bytes(M, Hq, L_max, opt.page) <= 4 * (size_t)M * nqkv)   // the masks live in big32

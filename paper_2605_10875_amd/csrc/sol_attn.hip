@@ -1977,9 +1977,9 @@ k_attn_pv_pages(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, con
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk)
             qf[qt][kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(qp + kk * 32));
-        const unsigned long long *mp = selp + (((int64_t)s * Tn + qr) * Hq + h) * W;
 #pragma unroll
-        for (int ww = 0; ww < W; ++ww) mask[qt][ww] = mp[ww];
+        for (int ww = 0; ww < W; ++ww)                      // no masks at all: every page of every row is kept
+            mask[qt][ww] = selp ? selp[(((int64_t)s * Tn + qr) * Hq + h) * W + ww] : ~0ull;
         pos[qt] = live ? p0 + qi : -1;                      // dead rows of a ragged block keep nothing
         const int n = p0 + qi + 1;
         sink_end[qt] = n_sink < n ? n_sink : n;
@@ -2184,6 +2184,7 @@ bool launch_attn_tile(const void *q, const void *k_cache, const void *v_cache, v
                   : launch_attn_select_t<BQ, SL, 128, 8>(q, k_cache, sel, ra, pos0, n_seq, T, L_max, Hq, Hkv, st)
     if (L_max <= 256) { SOL_SEL(32, 4); }
     else if (L_max <= 1024) { SOL_SEL(16, 16); }
+    else if (L_max <= 1280) { SOL_SEL(8, 20); }             // a 1024-token prefix plus a short episode
     else if (L_max <= 2048) { SOL_SEL(8, 32); }
     else { SOL_SEL(8, 64); }
 #undef SOL_SEL
@@ -2231,6 +2232,49 @@ static bool launch_attn_tile_pages_t(const void *q, const void *kc, const void *
     if (G == 4) SOL_PVP(4)
     SOL_PVP(8)
 #undef SOL_PVP
+}
+
+// Dense causal attention for rows that keep every key (prefill, cache refresh): the flash-style kernel alone, with
+// its running maximum, no threshold pass. Shapes of launch_attn_tile.
+bool launch_attn_tile_dense(const void *q, const void *k_cache, const void *v_cache, void *vt, float *o32,
+                            const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv, int dh, hipStream_t st)
+{
+    if ((int64_t)n_seq * T <= 0) return true;
+    const int G = Hkv > 0 ? Hq / Hkv : 0;
+    if ((dh != 64 && dh != 128) || L_max > 4096 || T < 16 || G * Hkv != Hq || (G != 1 && G != 2 && G != 4 && G != 8) || !vt)
+        return false;
+    const int lpadv = attn_tile_lpadv(L_max);
+    const dim3 tg((lpadv + 63) / 64, Hkv, n_seq);
+    if (dh == 64)
+        hipLaunchKernelGGL((k_transpose_v<64>), tg, dim3(256), 0, st, (const bf16_t *)v_cache, (bf16_t *)vt, pos0, T,
+                           L_max, Hkv, lpadv);
+    else
+        hipLaunchKernelGGL((k_transpose_v<128>), tg, dim3(256), 0, st, (const bf16_t *)v_cache, (bf16_t *)vt, pos0, T,
+                           L_max, Hkv, lpadv);
+    const size_t lds = 4 * (size_t)64 * dh * 2;
+    const float scale = 1.0f / sqrtf((float)dh);
+#define SOL_PVD(DH_, G_)                                                                                             \
+    {                                                                                                                \
+        auto kern = k_attn_pv_pages<DH_, G_, 1>;                                                                     \
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,    \
+                                (int)lds) != hipSuccess)                                                             \
+            return false;                                                                                            \
+        hipLaunchKernelGGL(kern, dim3((T + 31) / 32, Hkv, n_seq), dim3(G_ * 64), lds, st, (const bf16_t *)q,         \
+                           (const bf16_t *)k_cache, (const bf16_t *)vt, (const unsigned long long *)nullptr, o32, pos0, T, \
+                           L_max, Hq, Hkv, lpadv, scale, 6, 0, 0);                                                   \
+        return true;                                                                                                 \
+    }
+    if (dh == 64) {
+        if (G == 1) SOL_PVD(64, 1)
+        if (G == 2) SOL_PVD(64, 2)
+        if (G == 4) SOL_PVD(64, 4)
+        SOL_PVD(64, 8)
+    }
+    if (G == 1) SOL_PVD(128, 1)
+    if (G == 2) SOL_PVD(128, 2)
+    if (G == 4) SOL_PVD(128, 4)
+    SOL_PVD(128, 8)
+#undef SOL_PVD
 }
 
 size_t attn_tile_pages_meta_bytes(int64_t n_seq, int Hkv, int L_max, int dh) { return (size_t)n_seq * Hkv * L_max * 2 * dh * 2; }

@@ -158,6 +158,9 @@ bool launch_attn_tile_pages(const void *q, const void *k_cache, const void *v_ca
                             float *o32, const RowAct *ra, const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv,
                             int dh, AttnOpts opt, hipStream_t st);
 size_t attn_tile_pages_meta_bytes(int64_t n_seq, int Hkv, int L_max, int dh);
+// Dense causal attention (every row keeps every key): the flash-style kernel alone. Shapes of launch_attn_tile.
+bool launch_attn_tile_dense(const void *q, const void *k_cache, const void *v_cache, void *vt, float *o32,
+                            const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv, int dh, hipStream_t st);
 size_t attn_tile_pages_sel_bytes(int64_t rows, int Hq, int L_max, int S);
 int attn_tile_lpadv(int L_max);
 
