@@ -197,7 +197,8 @@ int sol_decode_step_paged(sol_ctx *ctx, const sol_model_weights *weights,
  * [n_seq][T][d_model]). pos0: device int32 [n_seq]; pos0[s] + T > L_max sets the cache-overflow flag and skips
  * the sequence. k_cache, v_cache: host arrays of n_layers device pointers. page_meta: NULL, or the per-layer
  * page metadata buffers, whose pages holding rewritten keys are rebuilt. x_out: device [n_seq][T][d_model], the
- * last layer's output, may be NULL. Workspace: sol_workspace_bytes(cfg, SOL_OP_KV_REFRESH, n_seq, T, L_max). */
+ * last layer's output, may be NULL. Workspace: sol_workspace_bytes(cfg, SOL_OP_KV_REFRESH, n_seq, T, L_max).
+ * n_seq * T == 0 is a no-op. */
 int sol_kv_refresh(sol_ctx *ctx, const sol_model_weights *weights,
                    const int32_t *token_ids, const void *x_in, const int32_t *pos0,
                    void *const *k_cache, void *const *v_cache, void *const *page_meta,
@@ -212,7 +213,8 @@ int sol_kv_refresh(sol_ctx *ctx, const sol_model_weights *weights,
  * It equals sol_schedule_loglik on the P + T tokens with the dense action on the prefix, restricted to the last T
  * positions, without running the prefix K times. prefix_tokens: device int32 [B][P]; tokens, targets: device int32
  * [B][T]; action_ids: device int32 [B][K][T]; nll_out: device float [B][K][T]. The prefix is dense whatever cfg
- * says. Workspace: sol_episode_workspace_bytes(cfg, B, K, P, T) (holds one layer's caches for B * K sequences). */
+ * says. Workspace: sol_episode_workspace_bytes(cfg, B, K, P, T) (holds one layer's caches for B * K sequences).
+ * B * K * T == 0 is a no-op; P must be positive. */
 size_t sol_episode_workspace_bytes(const sol_model_cfg *cfg, int B, int K, int P, int T);
 int sol_episode_loglik(sol_ctx *ctx, const sol_model_weights *weights, const int32_t *prefix_tokens,
                        const int32_t *tokens, const int32_t *targets, const int32_t *action_ids,
@@ -232,7 +234,7 @@ int sol_episode_loglik(sol_ctx *ctx, const sol_model_weights *weights, const int
  * [B][3] = (C_kappa, C_rho, C_eta) per input. Outputs are device float arrays: avg_out [B][G][3], penalty_out
  * [B][G], returns_out [B][G][T] (each may be NULL), signal_out and adv_out [B][G][T] (required; they must not
  * alias nll). An action id outside the table counts as action 0 and sets the bad-action flag.
- * Workspace: sol_workspace_bytes(cfg, SOL_OP_REWARD, B, T, 0) bytes. */
+ * Workspace: sol_workspace_bytes(cfg, SOL_OP_REWARD, B, T, 0) bytes. B * G * T == 0 is a no-op. */
 typedef struct {
     float alpha_kappa, alpha_rho, alpha_eta;  /* trade-off weights, >= 0                     */
     float tau;                                /* tolerance band, >= 0                        */

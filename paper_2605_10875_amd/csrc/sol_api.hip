@@ -699,6 +699,8 @@ extern "C" int sol_kv_refresh(sol_ctx *ctx, const sol_model_weights *mw, const i
     if (!mw || !mw->layers) return fail(ctx, SOL_ERR_INVALID_ARG, "weights are NULL");
     for (int l = 0; l < g.n_layers; ++l)
         if (int rc = check_layer_weights(ctx, &mw->layers[l])) return rc;
+    if (n_seq < 0 || T < 0 || L_max <= 0) return fail(ctx, SOL_ERR_INVALID_ARG, "negative size");
+    if ((int64_t)n_seq * T == 0) return SOL_OK;                // nothing to refresh (pointers may be NULL then)
     if (!token_ids && !x_in) return fail(ctx, SOL_ERR_INVALID_ARG, "token_ids and x_in are both NULL");
     if (token_ids && !mw->embed) return fail(ctx, SOL_ERR_INVALID_ARG, "token_ids given but weights->embed is NULL");
     if (!pos0 || !k_cache || !v_cache) return fail(ctx, SOL_ERR_INVALID_ARG, "a data pointer is NULL");
@@ -753,9 +755,10 @@ extern "C" int sol_reward_advantages(sol_ctx *ctx, const float *nll, const int32
                                      float *adv_out, void *workspace, size_t ws_bytes, void *stream)
 {
     if (!ctx) return SOL_ERR_INVALID_ARG;
+    if (B < 0 || G < 0 || T < 0) return fail(ctx, SOL_ERR_INVALID_ARG, "negative size");
+    if ((int64_t)B * G * T == 0) return SOL_OK;                // nothing to reduce (pointers may be NULL then)
     if (!nll || !action_ids || !targets || !rc || !signal_out || !adv_out)
         return fail(ctx, SOL_ERR_INVALID_ARG, "a data pointer is NULL");
-    if (B < 0 || G < 0 || T < 0) return fail(ctx, SOL_ERR_INVALID_ARG, "negative size");
     if (!(rc->alpha_kappa >= 0.f) || !(rc->alpha_rho >= 0.f) || !(rc->alpha_eta >= 0.f) || !(rc->tau >= 0.f) ||
         !(rc->gamma > 0.f && rc->gamma <= 1.f) || !(rc->eps >= 0.f))
         return fail(ctx, SOL_ERR_INVALID_ARG, "reward cfg: weights, tau, eps must be >= 0 and gamma in (0, 1]");
@@ -866,9 +869,10 @@ extern "C" int sol_episode_loglik(sol_ctx *ctx, const sol_model_weights *mw, con
         return fail(ctx, SOL_ERR_INVALID_ARG, "weights are NULL");
     for (int l = 0; l < g.n_layers; ++l)
         if (int rc = check_layer_weights(ctx, &mw->layers[l])) return rc;
+    if (B < 0 || K < 0 || T < 0 || P <= 0) return fail(ctx, SOL_ERR_INVALID_ARG, "negative size or empty prefix");
+    if ((int64_t)B * K * T == 0) return SOL_OK;                // no controlled step (pointers may be NULL then)
     if (!prefix_tokens || !tokens || !targets || !action_ids || !nll_out)
         return fail(ctx, SOL_ERR_INVALID_ARG, "a data pointer is NULL");
-    if (B < 0 || K < 0 || T < 0 || P <= 0) return fail(ctx, SOL_ERR_INVALID_ARG, "negative size or empty prefix");
     if (g.vocab <= 0) return fail(ctx, SOL_ERR_INVALID_ARG, "vocab must be positive");
     if ((int64_t)P + T > g.max_positions) return fail(ctx, SOL_ERR_INVALID_ARG, "P + T exceeds cfg.max_positions");
     if ((g.head_dim * esize(g.dtype)) % 16) return fail(ctx, SOL_ERR_UNSUPPORTED, "head rows must be a multiple of 16 bytes");

@@ -253,7 +253,8 @@ class Sol:
         [0, cache_len[s]); returns the new buffer [n_seq][Hkv][pages][2 * head_dim]."""
         n_seq, hkv, L_max, dh = k_cache.shape
         pages = (L_max + self.cfg.page_size - 1) // self.cfg.page_size
-        assert self.L.sol_page_meta_bytes(C.byref(self.cfg), n_seq, L_max) == n_seq * hkv * pages * 2 * dh * k_cache.element_size()
+        need = self.L.sol_page_meta_bytes(C.byref(self.cfg), n_seq, L_max)
+        assert need in (0, n_seq * hkv * pages * 2 * dh * k_cache.element_size())     # 0: no metadata for this configuration
         meta = torch.zeros((n_seq, hkv, pages, 2 * dh), dtype=k_cache.dtype, device="cuda")
         self._check(self.L.sol_page_meta_build(self.handle, _ptr(k_cache), _ptr(_i32(cache_len)), n_seq, L_max,
                                                _ptr(meta), _stream(stream)))
