@@ -214,7 +214,11 @@ int sol_kv_refresh(sol_ctx *ctx, const sol_model_weights *weights,
  * positions, without running the prefix K times. prefix_tokens: device int32 [B][P]; tokens, targets: device int32
  * [B][T]; action_ids: device int32 [B][K][T]; nll_out: device float [B][K][T]. The prefix is dense whatever cfg
  * says. Workspace: sol_episode_workspace_bytes(cfg, B, K, P, T) (holds one layer's caches for B * K sequences).
- * B * K * T == 0 is a no-op; P must be positive. */
+ * B * K * T == 0 is a no-op; P must be positive. The K schedules of an input read its prefix cache in place when
+ * the tiled attention kernels cover the shape (bf16, page_size 1 without sink / window keys, P a multiple of 64,
+ * T >= 16, P + T <= 4096); otherwise each schedule works on a copy. The environment variable
+ * SOL_EPISODE_COPY_PREFIX=1 (read at the first call) forces the copies: a debugging aid, the results are the same
+ * bit for bit. */
 size_t sol_episode_workspace_bytes(const sol_model_cfg *cfg, int B, int K, int P, int T);
 int sol_episode_loglik(sol_ctx *ctx, const sol_model_weights *weights, const int32_t *prefix_tokens,
                        const int32_t *tokens, const int32_t *targets, const int32_t *action_ids,

@@ -6,6 +6,7 @@
 #include <cstdio>
 #include <cstring>
 #include <map>
+#include <cstdlib>
 #include <string>
 #include <utility>
 #include <vector>
@@ -373,7 +374,7 @@ static void prepare_actions(sol_ctx *ctx, const int32_t *ids, int64_t M, LayerWs
 // Launch sequence of one decoder layer (actions already decoded into w.ra / w.perm).
 static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_in, void *x_out, const int32_t *pos0,
                       void *kc, void *vc, int n_seq, int T, int L_max, LayerWs &w, hipStream_t st,
-                      void *page_meta = nullptr, bool dense_pass = false)
+                      void *page_meta = nullptr, bool dense_pass = false, const PrefixView *pv = nullptr)
 {
     const sol_model_cfg &g = ctx->cfg;
     const int dt = g.dtype;
@@ -388,6 +389,10 @@ static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_i
     }
     const bool mfma = dt == SOL_BF16;
     const bool skinny = mfma && M <= 64 && d % 64 == 0 && nq % 64 == 0 && dff % 64 == 0;   // decode: HBM-bound GEMMs
+    // shared prefix: the own caches hold positions P.. only; their writers get the base minus P rows
+    const int crows = pv ? pv->crows : 0;
+    void *kcw = pv ? (void *)((char *)kc - esize(dt) * (size_t)pv->P * dh) : kc;
+    void *vcw = pv ? (void *)((char *)vc - esize(dt) * (size_t)pv->P * dh) : vc;
     bool fused_qkv = false;
     int ns_qkv = 1;
     {   // q/k/v projections (+ rotary and cache write when fused)
@@ -397,8 +402,8 @@ static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_i
             if (!launch_gemm_skinny(w.h, d, lw->wq, nq, lw->wk, nkv, lw->wv, nkv, (int)M, d, w.big32, ns_qkv, st))
                 return fail(ctx, SOL_ERR_UNSUPPORTED, "skinny GEMM: unsupported shape");
         } else {
-            fused_qkv = mfma && launch_gemm_qkv_rope(w.h, lw->wq, lw->wk, lw->wv, w.qb, kc, vc, ctx->d_rope, pos0, n_seq,
-                                                     T, L_max, Hq, Hkv, dh, d, ctx->d_flags, w.big32, st);
+            fused_qkv = mfma && launch_gemm_qkv_rope(w.h, lw->wq, lw->wk, lw->wv, w.qb, kcw, vcw, ctx->d_rope, pos0, n_seq,
+                                                     T, L_max, Hq, Hkv, dh, d, ctx->d_flags, w.big32, st, crows);
             if (!fused_qkv) {
                 launch_gemm_generic(w.h, dt, d, lw->wq, dt, d, w.big32, nqkv, M, nq, d, st);
                 launch_gemm_generic(w.h, dt, d, lw->wk, dt, d, w.big32 + nq, nqkv, M, nkv, d, st);
@@ -408,15 +413,21 @@ static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_i
     }
     if (!fused_qkv) {   // rotary, cache write
         STAGE(ctx, ST_ROPE, st);
-        launch_rope_store(w.big32, w.qb, kc, vc, dt, ctx->d_rope, pos0, n_seq, T, L_max, Hq, Hkv, dh, ctx->d_flags, st,
-                          ns_qkv);
+        launch_rope_store(w.big32, w.qb, kcw, vcw, dt, ctx->d_rope, pos0, n_seq, T, L_max, Hq, Hkv, dh, ctx->d_flags, st,
+                          ns_qkv, crows);
     }
     {   // scores, budgeted selection, softmax over kept keys, times V
         STAGE(ctx, ST_ATTN, st);
         AttnOpts opt;
         if (!dense_pass) { opt.page = g.page_size; opt.n_sink = g.n_sink; opt.n_window = g.n_window; }   // dense rows keep every key under any rule
         const bool fast = mfma && opt.plain();       // the tiled and decode kernels know the plain top-k rule only
-        bool tiled = dense_pass && mfma && w.vt && T >= 16 && L_max <= 4096 &&
+        if (pv) {   // sequences on shared prefix caches: the tiled kernels with two-segment addressing, or nothing
+            if (!mfma || !opt.plain() || !w.vt ||
+                !launch_attn_tile_prefix(w.qb, kc, vc, w.vt, w.big32, w.o32, w.ra, pos0, n_seq, T, Hq, Hkv, dh, *pv, st))
+                return fail(ctx, SOL_ERR_UNSUPPORTED, "shared-prefix attention: shape outside the tiled kernels");
+        }
+        bool tiled = pv != nullptr;
+        tiled = tiled || dense_pass && mfma && w.vt && T >= 16 && L_max <= 4096 &&
                      launch_attn_tile_dense(w.qb, kc, vc, w.vt, w.o32, pos0, n_seq, T, L_max, Hq, Hkv, dh, st);
         tiled = tiled || fast && w.vt && T >= 16 && L_max <= 4096 &&
                      launch_attn_tile(w.qb, kc, vc, w.vt, w.big32, w.o32, w.ra, pos0, n_seq, T, L_max, Hq, Hkv, dh, st);
@@ -821,27 +832,30 @@ extern "C" int sol_schedule_loglik(sol_ctx *ctx, const sol_model_weights *mw, co
 // episode pass: dense prefill once per input, then K schedules of T controlled steps on top of it
 // ------------------------------------------------------------------------------------------------
 struct EpisodeWs {
+    bool twoseg;                           // the schedules read the prefix caches in place (no per-schedule copies)
     LayerWs pre, suf;
     void *pxa, *pxb, *pkc, *pvc;          // prefix activations (ping-pong) and one layer's prefix cache
     StackWs st;                            // suffix activations, one layer's caches, LM head scratch
     int32_t *pos0;
 };
 
-static void carve_episode(Carver &c, const sol_model_cfg &g, int64_t B, int64_t K, int64_t P, int64_t T, EpisodeWs &w)
+static void carve_episode_as(Carver &c, const sol_model_cfg &g, int64_t B, int64_t K, int64_t P, int64_t T, bool twoseg,
+                             EpisodeWs &w)
 {
     const size_t es = esize(g.dtype);
     const int64_t N = B * K, M = N * T;
+    w.twoseg = twoseg;
     carve_layer(c, g, B, P, (int)P, w.pre);
     w.pxa = c.take(es * B * P * g.d_model);
     w.pxb = c.take(es * B * P * g.d_model);
     const size_t pc = es * B * g.n_kv_heads * P * g.head_dim;
     w.pkc = c.take(pc);
     w.pvc = c.take(pc);
-    carve_layer(c, g, N, T, (int)(P + T), w.suf);
+    carve_layer(c, g, N, T, (int)(twoseg ? T : P + T), w.suf);
     w.st.xa = c.take(es * M * g.d_model);
     w.st.xb = c.take(es * M * g.d_model);
     w.st.hf = c.take(es * M * g.d_model);
-    const size_t sc = es * N * g.n_kv_heads * (P + T) * g.head_dim;
+    const size_t sc = es * N * g.n_kv_heads * (twoseg ? T : P + T) * g.head_dim;
     w.st.kc = c.take(sc);
     w.st.vc = c.take(sc);
     size_t head_bytes = 4 * lm_chunk_rows(g, M) * (size_t)(g.vocab > 0 ? g.vocab : 1);
@@ -849,6 +863,26 @@ static void carve_episode(Carver &c, const sol_model_cfg &g, int64_t B, int64_t 
         head_bytes = gemm_nll_scratch_bytes(M, g.vocab);
     w.st.logits = (float *)c.take(head_bytes);
     w.pos0 = (int32_t *)c.take(4 * N);
+}
+
+// The in-place layout is taken when the tiled kernels cover the shape with two-segment addressing (that depends on
+// sizes and on the distances inside the workspace only, so sizing and running agree); otherwise every schedule
+// gets a copy of the prefix cache.
+static void carve_episode(Carver &c, const sol_model_cfg &g, int64_t B, int64_t K, int64_t P, int64_t T, EpisodeWs &w)
+{
+    static const bool copy_forced = [] { const char *e = getenv("SOL_EPISODE_COPY_PREFIX"); return e && e[0] == '1'; }();
+    bool twoseg = !copy_forced && g.dtype == SOL_BF16 && g.page_size == 1 && g.n_sink == 0 && g.n_window == 0 && T >= 16 &&
+                  P % 64 == 0 && P + T <= 4096;
+    if (twoseg) {
+        Carver trial((void *)(uintptr_t)(1u << 20));       // never dereferenced: only the distances between the pieces count
+        EpisodeWs t;
+        carve_episode_as(trial, g, B, K, P, T, true, t);
+        PrefixView pv;
+        pv.k = (const bf16_t *)t.pkc; pv.P = (int)P; pv.K = (int)K; pv.crows = (int)T;
+        twoseg = t.suf.vt && t.pre.vt &&
+                 attn_tile_prefix_ok(t.st.kc, (int)(B * K), (int)T, g.n_q_heads, g.n_kv_heads, g.head_dim, pv);
+    }
+    carve_episode_as(c, g, B, K, P, T, twoseg, w);
 }
 
 extern "C" size_t sol_episode_workspace_bytes(const sol_model_cfg *cfg, int B, int K, int P, int T)
@@ -902,9 +936,17 @@ extern "C" int sol_episode_loglik(sol_ctx *ctx, const sol_model_weights *mw, con
         // layer l of the prefix (dense, once per input) fills the prefix cache; every schedule starts from a copy
         if (int rc = layer_impl(ctx, &mw->layers[l], pcur, pnxt, nullptr, w.pkc, w.pvc, B, P, P, w.pre, st, nullptr, true)) return rc;
         std::swap(pcur, pnxt);
-        launch_bcast_prefix(w.pkc, w.st.kc, N, K, g.n_kv_heads, P, L, g.head_dim, esize(g.dtype), st);
-        launch_bcast_prefix(w.pvc, w.st.vc, N, K, g.n_kv_heads, P, L, g.head_dim, esize(g.dtype), st);
-        if (int rc = layer_impl(ctx, &mw->layers[l], cur, nxt, w.pos0, w.st.kc, w.st.vc, N, T, L, w.suf, st)) return rc;
+        if (w.twoseg) {   // the schedules read the prefix K (and the transposed V the prefix pass left in its workspace) in place
+            PrefixView pv;
+            pv.k = (const bf16_t *)w.pkc; pv.vt = (const bf16_t *)w.pre.vt;
+            pv.P = P; pv.K = K; pv.lpadv = attn_tile_lpadv(P); pv.crows = T;
+            if (int rc = layer_impl(ctx, &mw->layers[l], cur, nxt, w.pos0, w.st.kc, w.st.vc, N, T, L, w.suf, st, nullptr, false, &pv))
+                return rc;
+        } else {
+            launch_bcast_prefix(w.pkc, w.st.kc, N, K, g.n_kv_heads, P, L, g.head_dim, esize(g.dtype), st);
+            launch_bcast_prefix(w.pvc, w.st.vc, N, K, g.n_kv_heads, P, L, g.head_dim, esize(g.dtype), st);
+            if (int rc = layer_impl(ctx, &mw->layers[l], cur, nxt, w.pos0, w.st.kc, w.st.vc, N, T, L, w.suf, st)) return rc;
+        }
         std::swap(cur, nxt);
     }
     return nll_impl(ctx, mw, cur, M, w.st, targets, K, T, true, nll_out, st);

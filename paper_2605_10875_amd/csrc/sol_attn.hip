@@ -449,11 +449,14 @@ __device__ unsigned long long *g_sel_stamps;
 // so the global-load latency of the score phase is hidden. Blocks are dealt to the nb workgroups of a
 // (sequence, head) in zigzag order (k-th visit: block nb*k + bi for even k, nb*k + nb-1-bi for odd k),
 // which gives every workgroup the same number of causal keys.
-template <int BQ, int SLOTS, int DH, int NW>
+// PRE: keys [0, pv.P) of sequence s are read from the prefix cache of input s / pv.K (shared by the pv.K schedules
+// of that input), keys from pv.P on from the sequence's own cache kc, which holds positions pv.P.. only
+// ([n_seq][Hkv][crows][DH]); pv.P is a multiple of 64 and the two caches lie less than 2^31 elements apart.
+template <int BQ, int SLOTS, int DH, int NW, bool PRE>
 __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(SLOTS <= 16 ? 4 : 2, SLOTS <= 16 ? 4 : 8)))
 k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRow *__restrict__ sel,
               const RowAct *__restrict__ ra, const int32_t *__restrict__ pos0, int Tn, int L_max, int Hq, int Hkv,
-              float scale, int nb)
+              float scale, int nb, PrefixView pv)
 {
     constexpr int LPAD = SLOTS * 64, LS = LPAD + 4;        // row stride = 4 mod 64 floats: the 16 query rows of a
                                                            // 128-bit store hit 16 different bank groups
@@ -471,6 +474,12 @@ k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRo
     const int kvh = h / (Hq / Hkv);
     // wave-uniform bases + 32-bit per-lane offsets: one address register per load instead of two
     const bf16_t *kbase = kc + ((int64_t)s * Hkv + kvh) * (int64_t)L_max * DH;
+    uint32_t kdelta = 0u;                                   // PRE: offset of the own cache (minus P rows) from the prefix cache
+    if constexpr (PRE) {
+        const bf16_t *own = kc + ((int64_t)s * Hkv + kvh) * (int64_t)pv.crows * DH - (int64_t)pv.P * DH;
+        kbase = pv.k + ((int64_t)(s / pv.K) * Hkv + kvh) * (int64_t)pv.P * DH;
+        kdelta = (uint32_t)__builtin_amdgcn_readfirstlane((int)(own - kbase));
+    }
     const bf16_t *qbase = q + (int64_t)s * Tn * (int64_t)(Hq * DH) + (int64_t)h * DH;
     const int l16 = lane & 15, lg = lane >> 4;
 
@@ -493,7 +502,8 @@ k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRo
             if ((w + u * NW) * 16 < nmax_) {                /* tiles beyond the block's last key are never used */ \
                 int key = key0_ + u * NW * 16;                                                             \
                 if (key >= nmax_) key = nmax_ - 1;                                                         \
-                const uint32_t ko = (uint32_t)key * (uint32_t)DH + (uint32_t)(lg * 8);                     \
+                uint32_t ko = (uint32_t)key * (uint32_t)DH + (uint32_t)(lg * 8);                           \
+                if constexpr (PRE) ko += key >= pv.P ? kdelta : 0u;                                        \
                 _Pragma("unroll") for (int kk = 0; kk < KK; ++kk)                                          \
                     kf[u][kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(kbase + ko + kk * 32)); \
             }                                                                                              \
@@ -536,7 +546,8 @@ k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRo
             for (int u = 0; u < UA; ++u) {
                 int key = (kt0 + u * NW) * 16 + l16;
                 if (key >= n_max) key = n_max - 1;
-                const uint32_t ko = (uint32_t)key * (uint32_t)DH + (uint32_t)(lg * 8);
+                uint32_t ko = (uint32_t)key * (uint32_t)DH + (uint32_t)(lg * 8);
+                if constexpr (PRE) ko += key >= pv.P ? kdelta : 0u;
 #pragma unroll
                 for (int kk = 0; kk < KK; ++kk)
                     kf[u][kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(kbase + ko + kk * 32));
@@ -636,11 +647,13 @@ __device__ __forceinline__ void pv_probs(const floatx4_a (&st)[2], float scale, 
     plo = __builtin_bit_cast(bf16x8_a, lo);
 }
 
-template <int DH, int G>
+// PRE: as in k_attn_select; vt then is the transposed copy of the own cache ([n_seq][Hkv][DH][lpadv], positions
+// pv.P..) and pv.vt that of the prefix cache ([inputs][Hkv][DH][pv.lpadv]); 64-key chunks never straddle pv.P.
+template <int DH, int G, bool PRE>
 __global__ void __launch_bounds__(G * 64)
 k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf16_t *__restrict__ vt,
           const SelRow *__restrict__ sel, float *__restrict__ o32, const int32_t *__restrict__ pos0, int Tn, int L_max, int Hq,
-          int Hkv, int lpadv, float scale)
+          int Hkv, int lpadv, float scale, PrefixView pv)
 {
     constexpr int NT = G * 64, KK = DH / 32, DT = DH / 16, KC = 64, QT = 32;
     constexpr int KP = DH / 8;                              // 16-byte pieces per K row
@@ -661,6 +674,13 @@ k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf1
     const int n_chunks = (n_max + KC - 1) / KC;
     const bf16_t *kbase = kc + ((int64_t)s * Hkv + kvh) * (int64_t)L_max * DH;
     const bf16_t *vbase = vt + ((int64_t)s * Hkv + kvh) * (int64_t)DH * lpadv;
+    const bf16_t *kpre = nullptr, *vpre = nullptr;
+    if constexpr (PRE) {                                    // own segment addressed by absolute key: bases minus P keys
+        kbase = kc + ((int64_t)s * Hkv + kvh) * (int64_t)pv.crows * DH - (int64_t)pv.P * DH;
+        vbase = vbase - pv.P;
+        kpre = pv.k + ((int64_t)(s / pv.K) * Hkv + kvh) * (int64_t)pv.P * DH;
+        vpre = pv.vt + ((int64_t)(s / pv.K) * Hkv + kvh) * (int64_t)DH * pv.lpadv;
+    }
 
     // per-lane query state: lane l16 of every lane group owns query q0 + 16*qt + l16
     bf16x8_a qf[2][KK];
@@ -694,15 +714,18 @@ k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf1
 #define SOL_PV_GLOAD(KR, VR, CH_)                                                                                  \
     {                                                                                                      \
         const int key0_ = (CH_) * KC;                                                                      \
+        const bool pre_ = PRE && key0_ < pv.P;              /* chunk-uniform: P is a multiple of the chunk */ \
+        const bf16_t *kb_ = pre_ ? kpre : kbase, *vb_ = pre_ ? vpre : vbase;                               \
+        const int64_t vs_ = pre_ ? pv.lpadv : lpadv;                                                       \
         _Pragma("unroll") for (int i = 0; i < K_PIECES; ++i) {                                             \
             const int pc = i * NT + tid, row = pc / KP, piece = pc - row * KP;                             \
             int key = key0_ + row;                                                                         \
             if (key >= n_max) key = n_max - 1;              /* never used unmasked: beyond every row */     \
-            KR[i] = *reinterpret_cast<const u32x4_a *>(kbase + (int64_t)key * DH + piece * 8);             \
+            KR[i] = *reinterpret_cast<const u32x4_a *>(kb_ + (int64_t)key * DH + piece * 8);               \
         }                                                                                                  \
         _Pragma("unroll") for (int i = 0; i < V_PIECES; ++i) {                                             \
             const int pc = i * NT + tid, d = pc >> 3, piece = pc & 7;                                      \
-            VR[i] = *reinterpret_cast<const u32x4_a *>(vbase + (int64_t)d * lpadv + key0_ + piece * 8);    \
+            VR[i] = *reinterpret_cast<const u32x4_a *>(vb_ + (int64_t)d * vs_ + key0_ + piece * 8);        \
         }                                                                                                  \
     }
 #define SOL_PV_LSTORE(KR, VR, STG_)                                                                                \
@@ -1710,11 +1733,11 @@ k_transpose_v(const bf16_t *__restrict__ vc, bf16_t *__restrict__ vt, const int3
     }
 }
 
-template <int BQ, int SLOTS, int DH, int NW>
+template <int BQ, int SLOTS, int DH, int NW, bool PRE = false>
 static bool launch_attn_select_t(const void *q, const void *kc, SelRow *sel, const RowAct *ra, const int32_t *pos0,
-                                 int n_seq, int Tn, int L_max, int Hq, int Hkv, hipStream_t st)
+                                 int n_seq, int Tn, int L_max, int Hq, int Hkv, hipStream_t st, PrefixView pv = PrefixView())
 {
-    auto kern = k_attn_select<BQ, SLOTS, DH, NW>;
+    auto kern = k_attn_select<BQ, SLOTS, DH, NW, PRE>;
     const size_t lds = (size_t)BQ * (SLOTS * 64 + 4) * 4;
     static bool attr_done = false;
     if (!attr_done) {
@@ -1729,15 +1752,16 @@ static bool launch_attn_select_t(const void *q, const void *kc, SelRow *sel, con
     if (nb > n_qb) nb = n_qb;
     if (nb < 1) nb = 1;
     hipLaunchKernelGGL(kern, dim3(nb, Hq, n_seq), dim3(NW * 64), lds, st, (const bf16_t *)q, (const bf16_t *)kc, sel, ra,
-                       pos0, Tn, L_max, Hq, Hkv, 1.0f / sqrtf((float)DH), nb);
+                       pos0, Tn, L_max, Hq, Hkv, 1.0f / sqrtf((float)DH), nb, pv);
     return true;
 }
 
-template <int DH, int G>
+template <int DH, int G, bool PRE = false>
 static bool launch_attn_pv_t(const void *q, const void *kc, const void *vt, const SelRow *sel, float *o32,
-                             const int32_t *pos0, int n_seq, int Tn, int L_max, int Hq, int Hkv, int lpadv, hipStream_t st)
+                             const int32_t *pos0, int n_seq, int Tn, int L_max, int Hq, int Hkv, int lpadv, hipStream_t st,
+                             PrefixView pv = PrefixView())
 {
-    auto kern = k_attn_pv<DH, G>;
+    auto kern = k_attn_pv<DH, G, PRE>;
     const size_t lds = 4 * (size_t)64 * DH * 2;
     static bool attr_done = false;
     if (!attr_done) {
@@ -1747,7 +1771,7 @@ static bool launch_attn_pv_t(const void *q, const void *kc, const void *vt, cons
         attr_done = true;
     }
     hipLaunchKernelGGL(kern, dim3((Tn + 31) / 32, Hkv, n_seq), dim3(G * 64), lds, st, (const bf16_t *)q, (const bf16_t *)kc,
-                       (const bf16_t *)vt, sel, o32, pos0, Tn, L_max, Hq, Hkv, lpadv, 1.0f / sqrtf((float)DH));
+                       (const bf16_t *)vt, sel, o32, pos0, Tn, L_max, Hq, Hkv, lpadv, 1.0f / sqrtf((float)DH), pv);
     return true;
 }
 
@@ -2192,6 +2216,67 @@ bool launch_attn_tile(const void *q, const void *k_cache, const void *v_cache, v
 #define SOL_PV(G_)                                                                                                   \
     return dh == 64 ? launch_attn_pv_t<64, G_>(q, k_cache, vt, sel, o32, pos0, n_seq, T, L_max, Hq, Hkv, lpadv, st)  \
                     : launch_attn_pv_t<128, G_>(q, k_cache, vt, sel, o32, pos0, n_seq, T, L_max, Hq, Hkv, lpadv, st)
+    if (G == 1) { SOL_PV(1); }
+    if (G == 2) { SOL_PV(2); }
+    if (G == 4) { SOL_PV(4); }
+    SOL_PV(8);
+#undef SOL_PV
+}
+
+// launch_attn_tile for sequences that share prefix caches (PrefixView): k_cache / v_cache hold positions pv.P.. only
+// ([n_seq][Hkv][pv.crows][dh]), vt is scratch for their transposed copy ([n_seq][Hkv][dh][attn_tile_lpadv(pv.crows)]);
+// every sequence's T rows sit at positions pv.P .. pv.P + T - 1. Returns false (nothing launched) outside the shapes
+// of launch_attn_tile, if pv.P is not a multiple of 64 or the caches lie 2^31 elements or more apart.
+// shape and address limits of launch_attn_tile_prefix (only differences of the pointers are looked at)
+bool attn_tile_prefix_ok(const void *k_cache, int n_seq, int T, int Hq, int Hkv, int dh, const PrefixView &pv)
+{
+    const int G = Hkv > 0 ? Hq / Hkv : 0, L_max = pv.P + T;
+    if ((dh != 64 && dh != 128) || L_max > 4096 || T < 16 || G * Hkv != Hq || (G != 1 && G != 2 && G != 4 && G != 8))
+        return false;
+    if (pv.P <= 0 || pv.P % 64 || pv.K < 1 || T > pv.crows) return false;
+    // the threshold kernel reaches a sequence's own keys as a 32-bit element offset from its input's prefix cache:
+    // (own cache of (s, kvh), minus P rows) - (prefix cache of (s / K, kvh)) must lie in [0, 2^31 - a row span) for
+    // every (s, kvh); the difference is linear in input, schedule and head, so the corners decide
+    if (n_seq % pv.K) return false;
+    const int64_t base = (const bf16_t *)k_cache - pv.k - (int64_t)pv.P * dh;
+    for (int c = 0; c < 8; ++c) {
+        const int64_t b = (c & 1) ? n_seq / pv.K - 1 : 0, k = (c & 2) ? pv.K - 1 : 0, kv = (c & 4) ? Hkv - 1 : 0;
+        const int64_t diff = base + ((b * pv.K + k) * Hkv + kv) * (int64_t)pv.crows * dh - (b * Hkv + kv) * (int64_t)pv.P * dh;
+        if (diff < 0 || diff >= (1ll << 31) - (int64_t)(L_max + 1) * dh) return false;
+    }
+    return true;
+}
+
+bool launch_attn_tile_prefix(const void *q, const void *k_cache, const void *v_cache, void *vt, void *sel_ws, float *o32,
+                             const RowAct *ra, const int32_t *pos0, int n_seq, int T, int Hq, int Hkv, int dh, PrefixView pv,
+                             hipStream_t st)
+{
+    if ((int64_t)n_seq * T <= 0) return true;
+    if (!pv.k || !pv.vt || !attn_tile_prefix_ok(k_cache, n_seq, T, Hq, Hkv, dh, pv)) return false;
+    const int G = Hq / Hkv, L_max = pv.P + T;
+    const int lpadv = attn_tile_lpadv(pv.crows);
+    SelRow *sel = (SelRow *)sel_ws;
+    const dim3 tg((lpadv + 63) / 64, Hkv, n_seq);
+    if (dh == 64)
+        hipLaunchKernelGGL((k_transpose_v<64>), tg, dim3(256), 0, st, (const bf16_t *)v_cache, (bf16_t *)vt,
+                           (const int32_t *)nullptr, T, pv.crows, Hkv, lpadv);
+    else
+        hipLaunchKernelGGL((k_transpose_v<128>), tg, dim3(256), 0, st, (const bf16_t *)v_cache, (bf16_t *)vt,
+                           (const int32_t *)nullptr, T, pv.crows, Hkv, lpadv);
+    bool ok;
+#define SOL_SEL(BQ, SL)                                                                                              \
+    ok = dh == 64 ? launch_attn_select_t<BQ, SL, 64, 8, true>(q, k_cache, sel, ra, pos0, n_seq, T, L_max, Hq, Hkv, st, pv) \
+                  : launch_attn_select_t<BQ, SL, 128, 8, true>(q, k_cache, sel, ra, pos0, n_seq, T, L_max, Hq, Hkv, st, pv)
+    if (L_max <= 256) { SOL_SEL(32, 4); }
+    else if (L_max <= 1024) { SOL_SEL(16, 16); }
+    else if (L_max <= 1280) { SOL_SEL(8, 20); }
+    else if (L_max <= 2048) { SOL_SEL(8, 32); }
+    else { SOL_SEL(8, 64); }
+#undef SOL_SEL
+    if (!ok) return false;
+#define SOL_PV(G_)                                                                                                   \
+    return dh == 64 ? launch_attn_pv_t<64, G_, true>(q, k_cache, vt, sel, o32, pos0, n_seq, T, L_max, Hq, Hkv, lpadv, st, pv)  \
+                    : launch_attn_pv_t<128, G_, true>(q, k_cache, vt, sel, o32, pos0, n_seq, T, L_max, Hq, Hkv, lpadv, st, pv)
     if (G == 1) { SOL_PV(1); }
     if (G == 2) { SOL_PV(2); }
     if (G == 4) { SOL_PV(4); }

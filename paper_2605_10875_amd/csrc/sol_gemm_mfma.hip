@@ -582,10 +582,11 @@ constexpr int SOL_WN = 128;
 
 bool launch_gemm_qkv_rope(const void *h, const void *wq, const void *wk, const void *wv, void *q, void *kc, void *vc,
                           const float2 *rope, const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv, int dh,
-                          int d, int *flags, void *row_sp_ws, hipStream_t st)
+                          int d, int *flags, void *row_sp_ws, hipStream_t st, int cache_rows)
 {
     const int nq = Hq * dh, nkv = Hkv * dh;
     if ((dh != 64 && dh != 128) || nq % 256 || nkv % 256) return false;      // heads must not straddle wave tiles
+    const int crows = cache_rows > 0 ? cache_rows : L_max;                    // rows of a (sequence, KV head) in the caches
     const int64_t M = (int64_t)n_seq * T;
     if (M <= 0) return true;
     if (d % (2 * BK) || d < 2 * BK) return false;
@@ -596,10 +597,10 @@ bool launch_gemm_qkv_rope(const void *h, const void *wq, const void *wk, const v
     int2 *row_sp = (int2 *)row_sp_ws;
     hipLaunchKernelGGL(k_row_positions, dim3((unsigned)((M + 255) / 256)), dim3(256), 0, st, pos0, M, T, L_max, row_sp, flags);
     if (dh == 64) {
-        EpiQkvRope<64> epi{(bf16_t *)q, (bf16_t *)kc, (bf16_t *)vc, rope, row_sp, L_max, Hq, Hkv};
+        EpiQkvRope<64> epi{(bf16_t *)q, (bf16_t *)kc, (bf16_t *)vc, rope, row_sp, crows, Hq, Hkv};
         return launch_mfma<SOL_TILE_QKV>((const bf16_t *)h, d, bm, M, nq + 2 * nkv, d, epi, st);
     }
-    EpiQkvRope<128> epi{(bf16_t *)q, (bf16_t *)kc, (bf16_t *)vc, rope, row_sp, L_max, Hq, Hkv};
+    EpiQkvRope<128> epi{(bf16_t *)q, (bf16_t *)kc, (bf16_t *)vc, rope, row_sp, crows, Hq, Hkv};
     return launch_mfma<SOL_TILE_QKV>((const bf16_t *)h, d, bm, M, nq + 2 * nkv, d, epi, st);
 }
 

