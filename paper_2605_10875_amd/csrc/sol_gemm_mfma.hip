@@ -680,9 +680,11 @@ constexpr int SK_XROW = SK_KC * 2 + 16;    // padded LDS row of activations (byt
 template <int MT>                           // MT tiles of 32 tokens (1: M <= 32, 2: M <= 64)
 __global__ void __launch_bounds__(256)
 k_gemm_skinny(const bf16_t *__restrict__ x, int64_t ldx, BMap bmap, int M, int Nv, int K, int k_per_split,
-              float *__restrict__ partial)
+              float *__restrict__ partial, int xrow)
 {
-    extern __shared__ __align__(16) unsigned char xs[];      // [MT*32][SK_XROW]
+    extern __shared__ __align__(16) unsigned char xs[];      // [MT*32][xrow]: xrow = padded bytes of a staged row (the
+                                                             // chunk is no longer than a split: short splits leave room
+                                                             // for more workgroups per CU)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n0 = (blockIdx.x * 4 + wave) * 32;
@@ -720,7 +722,7 @@ k_gemm_skinny(const bf16_t *__restrict__ x, int64_t ldx, BMap bmap, int M, int N
             _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                \
                 const bf16x8_t af = __builtin_bit_cast(bf16x8_t, WA[u][j]);                                \
                 _Pragma("unroll") for (int t = 0; t < MT; ++t) {                                           \
-                    const unsigned char *xp = xs + (t * 32 + r) * SK_XROW + ((KOFF_) + u * 64 + h * 32 + j * 8) * 2; \
+                    const unsigned char *xp = xs + (t * 32 + r) * xrow + ((KOFF_) + u * 64 + h * 32 + j * 8) * 2; \
                     const bf16x8_t bfr = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t *>(xp)); \
                     acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfr, acc[t], 0, 0, 0);            \
                 }                                                                                          \
@@ -738,7 +740,7 @@ k_gemm_skinny(const bf16_t *__restrict__ x, int64_t ldx, BMap bmap, int M, int N
             const int m = idx / pieces, p = idx - m * pieces;
             u32x4_t v = {0u, 0u, 0u, 0u};
             if (m < M) v = *reinterpret_cast<const u32x4_t *>(x + (int64_t)m * ldx + kc + p * 8);
-            *reinterpret_cast<u32x4_t *>(xs + m * SK_XROW + p * 16) = v;
+            *reinterpret_cast<u32x4_t *>(xs + m * xrow + p * 16) = v;
         }
         __syncthreads();
         if (live) {
@@ -791,16 +793,16 @@ static bool launch_skinny(const bf16_t *x, int64_t ldx, const BMap &bm, int M, i
     if (k_per_split % 64) return false;
     const dim3 grid((Nv + 127) / 128, nsplit);
     static bool attr_done = false;
-    const size_t lds = (size_t)64 * SK_XROW;
     if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(k_gemm_skinny<2>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)lds) != hipSuccess) return false;
+                                (int)((size_t)64 * SK_XROW)) != hipSuccess) return false;
         attr_done = true;
     }
+    const int xrow = (k_per_split < SK_KC ? k_per_split : SK_KC) * 2 + 16;
     if (M <= 32)
-        hipLaunchKernelGGL((k_gemm_skinny<1>), grid, dim3(256), (size_t)32 * SK_XROW, st, x, ldx, bm, M, Nv, K, k_per_split, partial);
+        hipLaunchKernelGGL((k_gemm_skinny<1>), grid, dim3(256), (size_t)32 * xrow, st, x, ldx, bm, M, Nv, K, k_per_split, partial, xrow);
     else
-        hipLaunchKernelGGL((k_gemm_skinny<2>), grid, dim3(256), lds, st, x, ldx, bm, M, Nv, K, k_per_split, partial);
+        hipLaunchKernelGGL((k_gemm_skinny<2>), grid, dim3(256), (size_t)64 * xrow, st, x, ldx, bm, M, Nv, K, k_per_split, partial, xrow);
     return true;
 }
 
