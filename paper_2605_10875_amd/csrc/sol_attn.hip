@@ -987,33 +987,39 @@ k_attn_decode(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const
             qf[kk] = __builtin_bit_cast(bf16x8_a, v);
         }
         const int n_kt = (n + 15) >> 4;
-        constexpr int U = 4;
-        for (int kt0 = w; kt0 < n_kt; kt0 += DEC_WAVES * U) {
-            bf16x8_a kf[U][KK];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                int key = (kt0 + u * DEC_WAVES) * 16 + l16;
-                if (key >= n) key = n - 1;
-                const bf16_t *kp = kbase + (int64_t)key * DH + lg * 8;
-#pragma unroll
-                for (int kk = 0; kk < KK; ++kk)
-                    kf[u][kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(kp + kk * 32));
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int kt = kt0 + u * DEC_WAVES;
-                if (kt < n_kt) {
-                    floatx4_a acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int kk = 0; kk < KK; ++kk)
-                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[u][kk], qf[kk], acc, 0, 0, 0);
-                    if (l16 < DEC_HPB) {
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) sc[l16 * LPAD + kt * 16 + lg * 4 + r] = acc[r] * scale;
-                    }
-                }
-            }
+        // two register sets of key tiles: the loads of the next group are in flight while this group is multiplied
+        constexpr int U = DH == 64 ? 4 : 2, STEP = DEC_WAVES * U;
+        bf16x8_a kfa[U][KK], kfb[U][KK];
+#define SOL_DEC_LOADK(KF, KT0_)                                                                            \
+    _Pragma("unroll") for (int u = 0; u < U; ++u) {                                                        \
+        int key = ((KT0_) + u * DEC_WAVES) * 16 + l16;                                                     \
+        if (key >= n) key = n - 1;                                                                         \
+        const bf16_t *kp = kbase + (int64_t)key * DH + lg * 8;                                             \
+        _Pragma("unroll") for (int kk = 0; kk < KK; ++kk)                                                  \
+            KF[u][kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(kp + kk * 32));    \
+    }
+#define SOL_DEC_MMAK(KF, KT0_)                                                                             \
+    _Pragma("unroll") for (int u = 0; u < U; ++u) {                                                        \
+        const int kt = (KT0_) + u * DEC_WAVES;                                                             \
+        if (kt < n_kt) {                                                                                   \
+            floatx4_a acc = {0.f, 0.f, 0.f, 0.f};                                                          \
+            _Pragma("unroll") for (int kk = 0; kk < KK; ++kk)                                              \
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(KF[u][kk], qf[kk], acc, 0, 0, 0);            \
+            if (l16 < DEC_HPB) {                                                                           \
+                _Pragma("unroll") for (int r = 0; r < 4; ++r) sc[l16 * LPAD + kt * 16 + lg * 4 + r] = acc[r] * scale; \
+            }                                                                                              \
+        }                                                                                                  \
+    }
+        int kt0 = w;
+        if (kt0 < n_kt) SOL_DEC_LOADK(kfa, kt0);
+        for (; kt0 < n_kt; kt0 += 2 * STEP) {
+            if (kt0 + STEP < n_kt) SOL_DEC_LOADK(kfb, kt0 + STEP);
+            SOL_DEC_MMAK(kfa, kt0);
+            if (kt0 + 2 * STEP < n_kt) SOL_DEC_LOADK(kfa, kt0 + 2 * STEP);
+            if (kt0 + STEP < n_kt) SOL_DEC_MMAK(kfb, kt0 + STEP);
         }
+#undef SOL_DEC_LOADK
+#undef SOL_DEC_MMAK
     }
     __syncthreads();
     DEC_T(2)
