@@ -380,23 +380,6 @@ __device__ __forceinline__ void gemm_epilogue(const floatx16_t (&acc)[TM][TN], c
     }
 }
 
-// 16 bytes from a wave-uniform base plus a 32-bit byte offset per lane. Issued as inline assembly so that the waits
-// are the kernel's own: the compiler's counter model loses track of which loads of a software pipeline are still in
-// flight across the loop's back edge and waits for loads issued only one step earlier. Every use of the result must
-// be preceded by a vm_wait that covers it, and no register of a pending load may die before such a wait.
-__device__ __forceinline__ u32x4_t gload16(const bf16_t *base, uint32_t byte_off)
-{
-    u32x4_t v;
-    asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(v) : "v"(byte_off), "s"(base));
-    return v;
-}
-// s_waitcnt vmcnt(N) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt and lgkmcnt fields left at "no wait")
-template <int N> __device__ __forceinline__ void vm_wait()
-{
-    static_assert(N >= 0 && N < 64, "vmcnt has six bits");
-    __builtin_amdgcn_s_waitcnt(((N >> 4) << 14) | 0x0F70 | (N & 15));
-}
-
 #ifdef SOL_GEMM_TIMING
 __device__ unsigned long long *g_gemm_stamps;
 #define GT_STAMP(i) if (threadIdx.x == 0 && g_gemm_stamps) g_gemm_stamps[(size_t)blockIdx.x * 4 + (i)] = __builtin_readcyclecounter()
@@ -444,12 +427,12 @@ k_gemm_mfma(const bf16_t *__restrict__ A, int64_t lda, BMap bmap, int64_t M, int
     for (int p = 0; p < A_PASSES; ++p) {
         int64_t rl = p * ROWS_PER_PASS + r_in_pass;
         if (m0 + rl >= M) rl = M - 1 - m0;                  // ragged last tile: re-read the last row, never stored
-        a_off[p] = ((uint32_t)(rl * lda) + (uint32_t)(chunk * 8)) * 2u;   // bytes
+        a_off[p] = (uint32_t)(rl * lda) + (uint32_t)(chunk * 8);
     }
     const bf16_t *b_base[B_PASSES];                         // uniform: first weight row of each pass
 #pragma unroll
     for (int p = 0; p < B_PASSES; ++p) b_base[p] = bmap.row(n0 + p * ROWS_PER_PASS);
-    const uint32_t b_off = ((uint32_t)r_in_pass * (uint32_t)bmap.ld + (uint32_t)(chunk * 8)) * 2u;   // bytes
+    const uint32_t b_off = (uint32_t)r_in_pass * (uint32_t)bmap.ld + (uint32_t)(chunk * 8);
     const int a_dst0 = r_in_pass * 128 + ((chunk ^ SOL_SWZ(r_in_pass)) << 4);
     const int b_dst0 = BM * 128 + a_dst0;
 
@@ -475,10 +458,11 @@ k_gemm_mfma(const bf16_t *__restrict__ A, int64_t lda, BMap bmap, int64_t M, int
 #define SOL_G_LOAD(RA, RB, KT_)                                                                            \
     {                                                                                                      \
         const int koff_ = ((KT_) < KT ? (KT_) : KT - 1) * BK; /* past the end: re-read the last slice */   \
-        _Pragma("unroll") for (int p = 0; p < A_PASSES; ++p) RA[p] = gload16(a_base + koff_, a_off[p]);    \
-        _Pragma("unroll") for (int p = 0; p < B_PASSES; ++p) RB[p] = gload16(b_base[p] + koff_, b_off);    \
+        _Pragma("unroll") for (int p = 0; p < A_PASSES; ++p)                                               \
+            RA[p] = *reinterpret_cast<const u32x4_t *>(a_base + koff_ + a_off[p]);                         \
+        _Pragma("unroll") for (int p = 0; p < B_PASSES; ++p)                                               \
+            RB[p] = *reinterpret_cast<const u32x4_t *>(b_base[p] + koff_ + b_off);                         \
     }
-    constexpr int SET_LOADS = A_PASSES + B_PASSES;          // loads of one register set
 #define SOL_L_STORE(RA, RB, STAGE_)                                                                        \
     {                                                                                                      \
         _Pragma("unroll") for (int p = 0; p < A_PASSES; ++p)                                               \
@@ -518,51 +502,21 @@ k_gemm_mfma(const bf16_t *__restrict__ A, int64_t lda, BMap bmap, int64_t M, int
         __builtin_amdgcn_sched_group_barrier(0x200, (A_PASSES + B_PASSES + TM * TN - 1) / (TM * TN), 0);   \
         __builtin_amdgcn_sched_group_barrier(0x020, (A_PASSES + B_PASSES + TM * TN - 1) / (TM * TN), 0);   \
     }
-    // last k-group of a step, in issue order: behind each MFMA one fragment read of the next stage (the first TM + TN
-    // MFMAs), one staging write of the landed register set and the global load that refills that register
-    static_assert(TM * TN == A_PASSES + B_PASSES, "one staging write and one load per MFMA of a k-group");
-#define SOL_TAIL(CUR_, NXT_, RA, RB, KT_LOAD_)                                                             \
-    {                                                                                                      \
-        const int koff_ = ((KT_LOAD_) < KT ? (KT_LOAD_) : KT - 1) * BK;                                    \
-        const int coff_ = ((fk ^ fsw) << 4);                                                               \
-        _Pragma("unroll") for (int m = 0; m < TM * TN; ++m) {                                              \
-            acc[m / TN][m % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[m / TN], fb1[m % TN],        \
-                                                                         acc[m / TN][m % TN], 0, 0, 0);    \
-            if (m < TM) fa0[m] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t *>(          \
-                            (NXT_) + a_frag0 + m * 32 * 128 + coff_));                                     \
-            else if (m < TM + TN) fb0[m - TM] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t *>( \
-                            (NXT_) + b_frag0 + (m - TM) * 32 * 128 + coff_));                              \
-            if (m < A_PASSES) {                                                                            \
-                *reinterpret_cast<u32x4_t *>((CUR_) + a_dst0 + m * ROWS_PER_PASS * 128) = RA[m];           \
-                RA[m] = gload16(a_base + koff_, a_off[m]);                                                 \
-            } else {                                                                                       \
-                *reinterpret_cast<u32x4_t *>((CUR_) + b_dst0 + (m - A_PASSES) * ROWS_PER_PASS * 128) = RB[m - A_PASSES]; \
-                RB[m - A_PASSES] = gload16(b_base[m - A_PASSES] + koff_, b_off);                           \
-            }                                                                                              \
-            SOL_FENCE;                                                                                     \
-        }                                                                                                  \
-    }
 #define SOL_STEP(CUR_, NXT_, RA, RB, KT_LOAD_)                                                             \
     SOL_F_READ(fa1, fb1, CUR_, 1); SOL_MMA(fa0, fb0); SOL_ORDER_RM; SOL_FENCE;                             \
     SOL_F_READ(fa0, fb0, CUR_, 2); SOL_MMA(fa1, fb1); SOL_ORDER_RM; SOL_FENCE;                             \
     SOL_F_READ(fa1, fb1, CUR_, 3); SOL_MMA(fa0, fb0); SOL_ORDER_RM; SOL_FENCE;                             \
     __syncthreads();                                                                                       \
     SOL_FENCE;                                                                                             \
-    vm_wait<SET_LOADS>();      /* this set has landed (two steps old); the other one stays in flight */    \
-    SOL_FENCE;                                                                                             \
-    SOL_TAIL(CUR_, NXT_, RA, RB, KT_LOAD_);
+    SOL_F_READ(fa0, fb0, NXT_, 0); SOL_L_STORE(RA, RB, CUR_); SOL_G_LOAD(RA, RB, KT_LOAD_);                \
+    SOL_MMA(fa1, fb1); SOL_ORDER_TAIL; SOL_FENCE;
 
     unsigned char *const stage0 = lds, *const stage1 = lds + STAGE_BYTES;
     GT_STAMP(0);
     SOL_G_LOAD(ra0, rb0, 0);
     SOL_G_LOAD(ra1, rb1, 1);
-    vm_wait<SET_LOADS>();
-    SOL_FENCE;
     SOL_L_STORE(ra0, rb0, stage0);
-    vm_wait<0>();
-    SOL_FENCE;
     SOL_L_STORE(ra1, rb1, stage1);
-    SOL_FENCE;
     SOL_G_LOAD(ra0, rb0, 2);
     SOL_G_LOAD(ra1, rb1, 3);
     __syncthreads();
@@ -572,7 +526,6 @@ k_gemm_mfma(const bf16_t *__restrict__ A, int64_t lda, BMap bmap, int64_t M, int
         SOL_STEP(stage0, stage1, ra0, rb0, kt + 4);
         SOL_STEP(stage1, stage0, ra1, rb1, kt + 5);
     }
-    vm_wait<0>();                                           // the last (unused) loads must land before their registers are reused
     __syncthreads();
     GT_STAMP(2);
 #undef SOL_G_LOAD
@@ -580,7 +533,6 @@ k_gemm_mfma(const bf16_t *__restrict__ A, int64_t lda, BMap bmap, int64_t M, int
 #undef SOL_F_READ
 #undef SOL_MMA
 #undef SOL_STEP
-#undef SOL_TAIL
 #undef SOL_ORDER_RM
 #undef SOL_ORDER_TAIL
 #undef SOL_FENCE
