@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the action-conditioned decoder-layer path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c2p|c3|c5|c4|c5d|c4p|refresh|episode]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c2p|c3|c5|c4|c5d|c4p|refresh|episode|episodep]
 
 A step is one pass of the measured unit over one batch of seeded synthetic input that is already
 resident in HBM. Default workload: the Llama-3.2-1B-shaped decoder layer, 4 inputs x 8 schedules
@@ -307,7 +307,7 @@ def run_decode(args, shape, B, L, table, name, n_layers, preset=None):
     return res
 
 
-def run_episode(args, shape, B, K, P, T, table, name):
+def run_episode(args, shape, B, K, P, T, table, name, preset=None):
     """Episode pass (sol_episode_loglik): dense prefill of P tokens once per input, K schedules of T steps on it."""
     gen = torch.Generator(device="cuda").manual_seed(args.seed)
 
@@ -323,7 +323,7 @@ def run_episode(args, shape, B, K, P, T, table, name):
     prefix = _dev(rng.integers(0, shape.vocab, (B, P)).astype(np.int32))
     tokens, targets = synth.tokens_and_targets(B, T, shape.vocab, args.seed + 1)
     ids = synth.markov_actions(len(table), B * K, T, args.seed + 2).reshape(B, K, T)
-    ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=P + T)
+    ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=P + T, **(preset or {}))
     tk, tg, idd = _dev(tokens), _dev(targets), _dev(ids)
     nll = torch.empty((B, K, T), dtype=torch.float32, device="cuda")
     need = int(ctx.L.sol_episode_workspace_bytes(ctx.cfg, B, K, P, T))
@@ -401,7 +401,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c2", choices=["c2", "c2p", "c3", "c5", "c4", "c5d", "c4p", "refresh", "episode"])
+    ap.add_argument("--workload", default="c2", choices=["c2", "c2p", "c3", "c5", "c4", "c5d", "c4p", "refresh", "episode", "episodep"])
     ap.add_argument("--seed", type=int, default=1234)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -439,6 +439,14 @@ def main():
         res = run_episode(args, shape, 8, 32, 1024, 16, synth.TABLE_C2,
                           "Episode pass: Llama-3.2-1B-shaped 16-layer stack + LM head + NLL, bf16, 8 inputs, dense prefill of "
                           "1024 tokens once per input, 32 schedules x 16 controlled steps on it")
+    elif args.workload == "episodep":
+        import dataclasses
+        shape = dataclasses.replace(synth.LLAMA_1B, n_layers=16, vocab=128256)
+        res = run_episode(args, shape, 8, 32, 1024, 16, synth.TABLE_C2,
+                          "Episode pass under the configuration of the paper's runs (pages of 16 keys, 4 sink + 2 window keys, "
+                          "pruning at the MLP input, quantiser on the MLP output): Llama-3.2-1B-shaped 16-layer stack + LM head + "
+                          "NLL, bf16, 8 inputs, dense prefill of 1024 tokens once per input, 32 schedules x 16 controlled steps "
+                          "on it", preset=sol.PAPER_PRESET)
     elif args.workload == "refresh":
         res = run_refresh(args, synth.LLAMA_1B, 64, 4096, 16, 16,
                           "KV-cache refresh: Llama-3.2-1B-shaped 16-layer stack, bf16, 64 sequences x 4096-token caches, "

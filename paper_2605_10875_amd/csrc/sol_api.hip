@@ -422,9 +422,14 @@ static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_i
         if (!dense_pass) { opt.page = g.page_size; opt.n_sink = g.n_sink; opt.n_window = g.n_window; }   // dense rows keep every key under any rule
         const bool fast = mfma && opt.plain();       // the tiled and decode kernels know the plain top-k rule only
         if (pv) {   // sequences on shared prefix caches: the tiled kernels with two-segment addressing, or nothing
-            if (!mfma || !opt.plain() || !w.vt ||
-                !launch_attn_tile_prefix(w.qb, kc, vc, w.vt, w.big32, w.o32, w.ra, pos0, n_seq, T, Hq, Hkv, dh, *pv, st))
-                return fail(ctx, SOL_ERR_UNSUPPORTED, "shared-prefix attention: shape outside the tiled kernels");
+            bool ok = mfma && w.vt;
+            if (ok && opt.plain())
+                ok = launch_attn_tile_prefix(w.qb, kc, vc, w.vt, w.big32, w.o32, w.ra, pos0, n_seq, T, Hq, Hkv, dh, *pv, st);
+            else if (ok)   // page rule (the masks live in big32)
+                ok = opt.page > 1 && w.pm && attn_tile_pages_sel_bytes(M, Hq, pv->P + T, opt.page) <= 4 * (size_t)M * nqkv &&
+                     launch_attn_tile_pages_prefix(w.qb, kc, vc, w.vt, w.pm, w.big32, w.o32, w.ra, pos0, n_seq, T, Hq, Hkv,
+                                                   dh, opt, *pv, st);
+            if (!ok) return fail(ctx, SOL_ERR_UNSUPPORTED, "shared-prefix attention: shape outside the tiled kernels");
         }
         bool tiled = pv != nullptr;
         tiled = tiled || dense_pass && mfma && w.vt && T >= 16 && L_max <= 4096 &&
@@ -871,16 +876,22 @@ static void carve_episode_as(Carver &c, const sol_model_cfg &g, int64_t B, int64
 static void carve_episode(Carver &c, const sol_model_cfg &g, int64_t B, int64_t K, int64_t P, int64_t T, EpisodeWs &w)
 {
     static const bool copy_forced = [] { const char *e = getenv("SOL_EPISODE_COPY_PREFIX"); return e && e[0] == '1'; }();
-    bool twoseg = !copy_forced && g.dtype == SOL_BF16 && g.page_size == 1 && g.n_sink == 0 && g.n_window == 0 && T >= 16 &&
-                  P % 64 == 0 && P + T <= 4096;
+    const bool plain = g.page_size == 1 && g.n_sink == 0 && g.n_window == 0;
+    bool twoseg = !copy_forced && g.dtype == SOL_BF16 && (plain || g.page_size > 1) && T >= 16 && P % 64 == 0 &&
+                  P + T <= 4096;
     if (twoseg) {
         Carver trial((void *)(uintptr_t)(1u << 20));       // never dereferenced: only the distances between the pieces count
         EpisodeWs t;
         carve_episode_as(trial, g, B, K, P, T, true, t);
         PrefixView pv;
         pv.k = (const bf16_t *)t.pkc; pv.P = (int)P; pv.K = (int)K; pv.crows = (int)T;
+        const int64_t M = B * K * T;
+        const int nqkv = (g.n_q_heads + 2 * g.n_kv_heads) * g.head_dim;
         twoseg = t.suf.vt && t.pre.vt &&
-                 attn_tile_prefix_ok(t.st.kc, (int)(B * K), (int)T, g.n_q_heads, g.n_kv_heads, g.head_dim, pv);
+                 (plain ? attn_tile_prefix_ok(t.st.kc, (int)(B * K), (int)T, g.n_q_heads, g.n_kv_heads, g.head_dim, pv)
+                        : t.suf.pm && t.pre.pm &&
+                          attn_tile_pages_prefix_ok((int)(B * K), (int)T, g.n_q_heads, g.n_kv_heads, g.head_dim, g.page_size, pv) &&
+                          attn_tile_pages_sel_bytes(M, g.n_q_heads, (int)(P + T), g.page_size) <= 4 * (size_t)M * nqkv);
     }
     carve_episode_as(c, g, B, K, P, T, twoseg, w);
 }
@@ -940,6 +951,11 @@ extern "C" int sol_episode_loglik(sol_ctx *ctx, const sol_model_weights *mw, con
             PrefixView pv;
             pv.k = (const bf16_t *)w.pkc; pv.vt = (const bf16_t *)w.pre.vt;
             pv.P = P; pv.K = K; pv.lpadv = attn_tile_lpadv(P); pv.crows = T;
+            if (g.page_size > 1) {   // page rule: the prefix keys' metadata rows, once per input (the dense prefix pass has no use for them)
+                if (!launch_page_prefix_meta(w.pkc, w.pre.pm, B, P, g.n_kv_heads, g.head_dim, g.page_size, st))
+                    return fail(ctx, SOL_ERR_UNSUPPORTED, "shared-prefix attention: page size outside the tiled kernels");
+                pv.pm = (const bf16_t *)w.pre.pm;
+            }
             if (int rc = layer_impl(ctx, &mw->layers[l], cur, nxt, w.pos0, w.st.kc, w.st.vc, N, T, L, w.suf, st, nullptr, false, &pv))
                 return rc;
         } else {

@@ -1826,11 +1826,14 @@ k_page_prefix_meta(const bf16_t *__restrict__ kc, const int32_t *__restrict__ po
     }
 }
 
-template <int DH, int W>
+// PRE (shared prefix, as in k_attn_select): pm holds the metadata rows of the sequence's own keys (positions pv.P..,
+// [n_seq][Hkv][pv.crows][2 * DH]), pv.pm those of the prefix keys of input s / pv.K ([inputs][Hkv][pv.P][2 * DH]);
+// pv.P is a multiple of 16 pages, so a tile of 16 pages lies on one side.
+template <int DH, int W, bool PRE>
 __global__ void __launch_bounds__(256)
 k_attn_select_pages(const bf16_t *__restrict__ q, const bf16_t *__restrict__ pm, unsigned long long *__restrict__ selp,
                     const RowAct *__restrict__ ra, const int32_t *__restrict__ pos0, int Tn, int L_max, int Hq, int Hkv,
-                    int log2S)
+                    int log2S, PrefixView pv)
 {
     constexpr int KK = DH / 32, KK2 = 2 * KK, PS = 64 * W + 4, BQ = 16;
     __shared__ float sb[BQ][PS];                             // bounds of the full pages, [query][page]
@@ -1845,6 +1848,11 @@ k_attn_select_pages(const bf16_t *__restrict__ q, const bf16_t *__restrict__ pm,
     const int q_last = (q0 + BQ - 1 < Tn ? q0 + BQ - 1 : Tn - 1);
     const int u_max = (p0 + q_last) >> log2S;                // last page any query of the block touches
     const bf16_t *pmb = pm + ((int64_t)s * Hkv + kvh) * (int64_t)L_max * (2 * DH);
+    const bf16_t *pmb_pre = nullptr;
+    if constexpr (PRE) {                                     // own rows addressed by absolute key: base minus P rows
+        pmb = pm + ((int64_t)s * Hkv + kvh) * (int64_t)pv.crows * (2 * DH) - (int64_t)pv.P * (2 * DH);
+        pmb_pre = pv.pm + ((int64_t)(s / pv.K) * Hkv + kvh) * (int64_t)pv.P * (2 * DH);
+    }
 
     // queries as MFMA B operand: column l16 = query q0 + l16, doubled row [max(q, 0) | min(q, 0)]
     bf16x8_a qq[KK2];
@@ -1866,7 +1874,7 @@ k_attn_select_pages(const bf16_t *__restrict__ q, const bf16_t *__restrict__ pm,
     for (int pt = w; pt < n_pt; pt += 4) {
         int j = (((pt * 16 + l16) + 1) << log2S) - 1;
         j = j < L_max ? j : L_max - 1;                       // pages past the live keys are masked below
-        const bf16_t *mp = pmb + (int64_t)j * (2 * DH) + lg * 8;
+        const bf16_t *mp = ((PRE && ((pt * 16) << log2S) < pv.P) ? pmb_pre : pmb) + (int64_t)j * (2 * DH) + lg * 8;
         floatx4_a acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kk = 0; kk < KK2; ++kk) {
@@ -1967,11 +1975,12 @@ __device__ __forceinline__ float max_over_lane_groups(float v)
     return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
 }
 
-template <int DH, int G, int W>
+// PRE: two-segment addressing as in k_attn_pv.
+template <int DH, int G, int W, bool PRE>
 __global__ void __launch_bounds__(G * 64)
 k_attn_pv_pages(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf16_t *__restrict__ vt,
                 const unsigned long long *__restrict__ selp, float *__restrict__ o32, const int32_t *__restrict__ pos0, int Tn,
-                int L_max, int Hq, int Hkv, int lpadv, float scale, int log2S, int n_sink, int n_window)
+                int L_max, int Hq, int Hkv, int lpadv, float scale, int log2S, int n_sink, int n_window, PrefixView pv)
 {
     constexpr int NT = G * 64, KK = DH / 32, DT = DH / 16, KC = 64, QT = 32;
     constexpr int KP = DH / 8;
@@ -1992,6 +2001,13 @@ k_attn_pv_pages(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, con
     const int n_chunks = (n_max + KC - 1) / KC;
     const bf16_t *kbase = kc + ((int64_t)s * Hkv + kvh) * (int64_t)L_max * DH;
     const bf16_t *vbase = vt + ((int64_t)s * Hkv + kvh) * (int64_t)DH * lpadv;
+    const bf16_t *kpre = nullptr, *vpre = nullptr;
+    if constexpr (PRE) {                                    // own segment addressed by absolute key: bases minus P keys
+        kbase = kc + ((int64_t)s * Hkv + kvh) * (int64_t)pv.crows * DH - (int64_t)pv.P * DH;
+        vbase = vbase - pv.P;
+        kpre = pv.k + ((int64_t)(s / pv.K) * Hkv + kvh) * (int64_t)pv.P * DH;
+        vpre = pv.vt + ((int64_t)(s / pv.K) * Hkv + kvh) * (int64_t)DH * pv.lpadv;
+    }
     const float sl2 = scale * 1.44269504088896341f;          // scores in the log2 domain
 
     bf16x8_a qf[2][KK];
@@ -2026,15 +2042,18 @@ k_attn_pv_pages(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, con
 #define SOL_PV_GLOAD(KR, VR, CH_)                                                                                  \
     {                                                                                                      \
         const int key0_ = (CH_) * KC;                                                                      \
+        const bool pre_ = PRE && key0_ < pv.P;              /* chunk-uniform: P is a multiple of the chunk */ \
+        const bf16_t *kb_ = pre_ ? kpre : kbase, *vb_ = pre_ ? vpre : vbase;                               \
+        const int64_t vs_ = pre_ ? pv.lpadv : lpadv;                                                       \
         _Pragma("unroll") for (int i = 0; i < K_PIECES; ++i) {                                             \
             const int pc = i * NT + tid, row = pc / KP, piece = pc - row * KP;                             \
             int key = key0_ + row;                                                                         \
             if (key >= n_max) key = n_max - 1;                                                             \
-            KR[i] = *reinterpret_cast<const u32x4_a *>(kbase + (int64_t)key * DH + piece * 8);             \
+            KR[i] = *reinterpret_cast<const u32x4_a *>(kb_ + (int64_t)key * DH + piece * 8);               \
         }                                                                                                  \
         _Pragma("unroll") for (int i = 0; i < V_PIECES; ++i) {                                             \
             const int pc = i * NT + tid, d = pc >> 3, piece = pc & 7;                                      \
-            VR[i] = *reinterpret_cast<const u32x4_a *>(vbase + (int64_t)d * lpadv + key0_ + piece * 8);    \
+            VR[i] = *reinterpret_cast<const u32x4_a *>(vb_ + (int64_t)d * vs_ + key0_ + piece * 8);        \
         }                                                                                                  \
     }
 #define SOL_PV_LSTORE(KR, VR, STG_)                                                                                \
@@ -2290,22 +2309,27 @@ bool launch_attn_tile_prefix(const void *q, const void *k_cache, const void *v_c
 #undef SOL_PV
 }
 
-template <int DH, int W>
+// PRE: kc / vt / pm belong to the sequences' own keys (pv.crows rows each, positions pv.P..), L_max = pv.P + T.
+template <int DH, int W, bool PRE = false>
 static bool launch_attn_tile_pages_t(const void *q, const void *kc, const void *vt, void *pm, void *selp, float *o32,
                                      const RowAct *ra, const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv,
-                                     int lpadv, int log2S, AttnOpts opt, hipStream_t st)
+                                     int lpadv, int log2S, AttnOpts opt, hipStream_t st, PrefixView pv = PrefixView())
 {
     const int S = 1 << log2S, G = Hq / Hkv;
     constexpr int ppb = 256 / (DH / 8);
-    hipLaunchKernelGGL(k_page_prefix_meta<DH>, dim3(((L_max + S - 1) / S + ppb - 1) / ppb, Hkv, n_seq), dim3(256), 0, st,
-                       (const bf16_t *)kc, pos0, (bf16_t *)pm, T, S, L_max, Hkv);
-    hipLaunchKernelGGL((k_attn_select_pages<DH, W>), dim3((T + 15) / 16, Hq, n_seq), dim3(256), 0, st, (const bf16_t *)q,
-                       (const bf16_t *)pm, (unsigned long long *)selp, ra, pos0, T, L_max, Hq, Hkv, log2S);
+    if (PRE)   // metadata of the own keys, by local row (pages do not straddle pv.P)
+        hipLaunchKernelGGL(k_page_prefix_meta<DH>, dim3(((pv.crows + S - 1) / S + ppb - 1) / ppb, Hkv, n_seq), dim3(256), 0,
+                           st, (const bf16_t *)kc, (const int32_t *)nullptr, (bf16_t *)pm, T, S, pv.crows, Hkv);
+    else
+        hipLaunchKernelGGL(k_page_prefix_meta<DH>, dim3(((L_max + S - 1) / S + ppb - 1) / ppb, Hkv, n_seq), dim3(256), 0, st,
+                           (const bf16_t *)kc, pos0, (bf16_t *)pm, T, S, L_max, Hkv);
+    hipLaunchKernelGGL((k_attn_select_pages<DH, W, PRE>), dim3((T + 15) / 16, Hq, n_seq), dim3(256), 0, st, (const bf16_t *)q,
+                       (const bf16_t *)pm, (unsigned long long *)selp, ra, pos0, T, L_max, Hq, Hkv, log2S, pv);
     const size_t lds = 4 * (size_t)64 * DH * 2;
     const float scale = 1.0f / sqrtf((float)DH);
 #define SOL_PVP(G_)                                                                                                  \
     {                                                                                                                \
-        auto kern = k_attn_pv_pages<DH, G_, W>;                                                                      \
+        auto kern = k_attn_pv_pages<DH, G_, W, PRE>;                                                                 \
         static bool attr_done = false;                                                                               \
         if (!attr_done) {                                                                                            \
             if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
@@ -2315,7 +2339,7 @@ static bool launch_attn_tile_pages_t(const void *q, const void *kc, const void *
         }                                                                                                            \
         hipLaunchKernelGGL(kern, dim3((T + 31) / 32, Hkv, n_seq), dim3(G_ * 64), lds, st, (const bf16_t *)q,         \
                            (const bf16_t *)kc, (const bf16_t *)vt, (const unsigned long long *)selp, o32, pos0, T, L_max, Hq, \
-                           Hkv, lpadv, scale, log2S, opt.n_sink, opt.n_window);                                      \
+                           Hkv, lpadv, scale, log2S, opt.n_sink, opt.n_window, pv);                                  \
         return true;                                                                                                 \
     }
     if (G == 1) SOL_PVP(1)
@@ -2346,13 +2370,13 @@ bool launch_attn_tile_dense(const void *q, const void *k_cache, const void *v_ca
     const float scale = 1.0f / sqrtf((float)dh);
 #define SOL_PVD(DH_, G_)                                                                                             \
     {                                                                                                                \
-        auto kern = k_attn_pv_pages<DH_, G_, 1>;                                                                     \
+        auto kern = k_attn_pv_pages<DH_, G_, 1, false>;                                                              \
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,    \
                                 (int)lds) != hipSuccess)                                                             \
             return false;                                                                                            \
         hipLaunchKernelGGL(kern, dim3((T + 31) / 32, Hkv, n_seq), dim3(G_ * 64), lds, st, (const bf16_t *)q,         \
                            (const bf16_t *)k_cache, (const bf16_t *)vt, (const unsigned long long *)nullptr, o32, pos0, T, \
-                           L_max, Hq, Hkv, lpadv, scale, 6, 0, 0);                                                   \
+                           L_max, Hq, Hkv, lpadv, scale, 6, 0, 0, PrefixView());                                     \
         return true;                                                                                                 \
     }
     if (dh == 64) {
@@ -2401,6 +2425,64 @@ bool launch_attn_tile_pages(const void *q, const void *k_cache, const void *v_ca
     if (n_words == 2) { SOL_TP(2); }
     SOL_TP(4);
 #undef SOL_TP
+}
+
+// Prefix side of the shared-prefix variant: the metadata rows of the prefix keys, once per input and layer.
+bool launch_page_prefix_meta(const void *k_cache, void *pm, int n_seq, int P, int Hkv, int dh, int S, hipStream_t st)
+{
+    if ((int64_t)n_seq * P <= 0) return true;
+    if ((dh != 64 && dh != 128) || S < 4 || S > 64 || (S & (S - 1)) || !pm) return false;
+    const int ppb = 256 / (dh / 8);
+    const dim3 grid(((P + S - 1) / S + ppb - 1) / ppb, Hkv, n_seq);
+    if (dh == 64)
+        hipLaunchKernelGGL(k_page_prefix_meta<64>, grid, dim3(256), 0, st, (const bf16_t *)k_cache, (const int32_t *)nullptr,
+                           (bf16_t *)pm, P, S, P, Hkv);
+    else
+        hipLaunchKernelGGL(k_page_prefix_meta<128>, grid, dim3(256), 0, st, (const bf16_t *)k_cache, (const int32_t *)nullptr,
+                           (bf16_t *)pm, P, S, P, Hkv);
+    return true;
+}
+
+// shapes launch_attn_tile_pages_prefix takes
+bool attn_tile_pages_prefix_ok(int n_seq, int T, int Hq, int Hkv, int dh, int S, const PrefixView &pv)
+{
+    const int G = Hkv > 0 ? Hq / Hkv : 0, L_max = pv.P + T;
+    if ((dh != 64 && dh != 128) || L_max > 4096 || T < 16 || G * Hkv != Hq || (G != 1 && G != 2 && G != 4 && G != 8))
+        return false;
+    if (S < 4 || S > 64 || (S & (S - 1)) || ((L_max + S - 1) / S + 63) / 64 > 4) return false;
+    // chunks of 64 keys and tiles of 16 pages must lie on one side of the prefix boundary
+    return pv.P > 0 && pv.P % 64 == 0 && pv.P % (16 * S) == 0 && pv.K >= 1 && n_seq % pv.K == 0 && T <= pv.crows;
+}
+
+// launch_attn_tile_pages for sequences that share prefix caches (PrefixView: pv.k, pv.vt and pv.pm of the input's
+// prefix, written by the prefix pass and launch_page_prefix_meta); k_cache / v_cache / vt / pm hold the sequences'
+// own pv.crows positions from pv.P on.
+bool launch_attn_tile_pages_prefix(const void *q, const void *k_cache, const void *v_cache, void *vt, void *pm, void *selp,
+                                   float *o32, const RowAct *ra, const int32_t *pos0, int n_seq, int T, int Hq, int Hkv,
+                                   int dh, AttnOpts opt, PrefixView pv, hipStream_t st)
+{
+    if ((int64_t)n_seq * T <= 0) return true;
+    const int S = opt.page;
+    if (!pv.k || !pv.vt || !pv.pm || !pm || !vt || !attn_tile_pages_prefix_ok(n_seq, T, Hq, Hkv, dh, S, pv)) return false;
+    const int L_max = pv.P + T;
+    int log2S = 0;
+    while ((1 << log2S) < S) ++log2S;
+    const int n_words = ((L_max + S - 1) / S + 63) / 64;
+    const int lpadv = attn_tile_lpadv(pv.crows);
+    const dim3 tg((lpadv + 63) / 64, Hkv, n_seq);
+    if (dh == 64)
+        hipLaunchKernelGGL((k_transpose_v<64>), tg, dim3(256), 0, st, (const bf16_t *)v_cache, (bf16_t *)vt,
+                           (const int32_t *)nullptr, T, pv.crows, Hkv, lpadv);
+    else
+        hipLaunchKernelGGL((k_transpose_v<128>), tg, dim3(256), 0, st, (const bf16_t *)v_cache, (bf16_t *)vt,
+                           (const int32_t *)nullptr, T, pv.crows, Hkv, lpadv);
+#define SOL_TPP(W_)                                                                                                  \
+    return dh == 64 ? launch_attn_tile_pages_t<64, W_, true>(q, k_cache, vt, pm, selp, o32, ra, pos0, n_seq, T, L_max, Hq, Hkv, lpadv, log2S, opt, st, pv) \
+                    : launch_attn_tile_pages_t<128, W_, true>(q, k_cache, vt, pm, selp, o32, ra, pos0, n_seq, T, L_max, Hq, Hkv, lpadv, log2S, opt, st, pv)
+    if (n_words == 1) { SOL_TPP(1); }
+    if (n_words == 2) { SOL_TPP(2); }
+    SOL_TPP(4);
+#undef SOL_TPP
 }
 
 }  // namespace sol

@@ -151,7 +151,13 @@ bool launch_attn_decode_paged(const void *q, const void *k_cache, const void *v_
 struct PrefixView {
     const bf16_t *k = nullptr, *vt = nullptr;
     int P = 0, K = 1, lpadv = 0, crows = 0;
+    const bf16_t *pm = nullptr;           // page rule: metadata rows of the prefix keys ([inputs][Hkv][P][2 * dh])
 };
+bool launch_page_prefix_meta(const void *k_cache, void *pm, int n_seq, int P, int Hkv, int dh, int S, hipStream_t st);
+bool attn_tile_pages_prefix_ok(int n_seq, int T, int Hq, int Hkv, int dh, int S, const PrefixView &pv);
+bool launch_attn_tile_pages_prefix(const void *q, const void *k_cache, const void *v_cache, void *vt, void *pm, void *selp,
+                                   float *o32, const RowAct *ra, const int32_t *pos0, int n_seq, int T, int Hq, int Hkv,
+                                   int dh, AttnOpts opt, PrefixView pv, hipStream_t st);
 // Batched bf16 attention (L_max <= 4096, head_dim 64 or 128, 1/2/4/8 query heads per KV head): a threshold
 // kernel followed by a flash-style masked softmax * V kernel. vt is workspace for the transposed V copy
 // (n_seq * Hkv * dh * attn_tile_lpadv(L_max) elements), sel_ws for the per-(row, head) thresholds

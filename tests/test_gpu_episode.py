@@ -64,9 +64,12 @@ def test_bf16_episode_pass(shape, P, T, K):
         (np.median(err), err.max())
 
 
-def test_bf16_episode_pass_paper_configuration():
+@pytest.mark.parametrize("P,T,K", [(48, 8, 3), (256, 16, 3), (256, 40, 2)])
+def test_bf16_episode_pass_paper_configuration(P, T, K):
+    """Pages of 16 keys, sink and window keys, pruning at the MLP input, quantiser on the MLP output. A prefix of a multiple
+    of 16 pages and at least 16 steps: prefix caches and prefix page metadata read in place; (48, 8): copies."""
     table = synth.action_table((0.125, 0.5, 1.0), (0.0, 0.75), (6, 16))
-    nll, ref, ids = _run(SMALL_GQA, table, sol.BF16, 1, 3, 48, 8, 8200, **sol.PAPER_PRESET)
+    nll, ref, ids = _run(SMALL_GQA, table, sol.BF16, 1, K, P, T, 8200 + P + T, **sol.PAPER_PRESET)
     err = np.abs(nll - ref)
     assert np.median(err) < 1e-2 and err.max() < 0.5, (np.median(err), err.max())
 
@@ -87,8 +90,10 @@ def test_identical_schedules_give_identical_likelihoods():
     assert all(np.array_equal(nll[0, 0], nll[0, k]) for k in range(1, 5))
 
 
-def test_reading_the_prefix_in_place_equals_working_on_copies():
-    """The two layouts of the episode pass run the same arithmetic on the same values: bit-identical likelihoods.
+@pytest.mark.parametrize("preset,P", [("{}", 192), ("sol.PAPER_PRESET", 256)])
+def test_reading_the_prefix_in_place_equals_working_on_copies(preset, P):
+    """The two layouts of the episode pass run the same arithmetic on the same values: bit-identical likelihoods, under
+    the plain top-k rule and under the page rule with sink / window keys.
     The copying layout is forced through the library's environment switch in a child process."""
     import os
     import subprocess
@@ -104,14 +109,15 @@ def test_reading_the_prefix_in_place_equals_working_on_copies():
         "layers = [dev_weights(synth.layer_weights(shape, 8400 + l, bf16=True), sol.BF16) for l in range(2)]\n"
         "head = dev_weights(synth.head_weights(shape, 8410, bf16=True), sol.BF16)\n"
         "rng = np.random.default_rng(8411)\n"
-        "prefix = rng.integers(0, shape.vocab, (3, 192)).astype(np.int32)\n"
+        "prefix = rng.integers(0, shape.vocab, (3, %d)).astype(np.int32)\n"
         "tokens, targets = synth.tokens_and_targets(3, 24, shape.vocab, 8412)\n"
         "ids = synth.iid_actions(len(table), (3, 5, 24), 8413)\n"
-        "ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=216)\n"
+        "ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=%d, **%s)\n"
         "nll = host(ctx.episode_loglik(layers, head, dev(prefix), dev(tokens), dev(targets), dev(ids)))\n"
         "assert ctx.device_status() == sol.OK\n"
         "np.save(sys.argv[1], nll)\n"
-    ) % (os.path.dirname(os.path.dirname(os.path.abspath(__file__))), os.path.dirname(os.path.abspath(__file__)))
+    ) % (os.path.dirname(os.path.dirname(os.path.abspath(__file__))), os.path.dirname(os.path.abspath(__file__)), P, P + 24,
+         preset)
     outs = []
     with tempfile.TemporaryDirectory() as td:
         for flag in ("0", "1"):
