@@ -1975,14 +1975,15 @@ __device__ __forceinline__ float max_over_lane_groups(float v)
     return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
 }
 
-// PRE: two-segment addressing as in k_attn_pv.
-template <int DH, int G, int W, bool PRE>
+// PRE: two-segment addressing as in k_attn_pv. NQT: query tiles of 16 rows per workgroup (2; 1 for passes of at most
+// 16 rows per sequence, where a second tile would be all dead rows).
+template <int DH, int G, int W, bool PRE, int NQT>
 __global__ void __launch_bounds__(G * 64)
 k_attn_pv_pages(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf16_t *__restrict__ vt,
                 const unsigned long long *__restrict__ selp, float *__restrict__ o32, const int32_t *__restrict__ pos0, int Tn,
                 int L_max, int Hq, int Hkv, int lpadv, float scale, int log2S, int n_sink, int n_window, PrefixView pv)
 {
-    constexpr int NT = G * 64, KK = DH / 32, DT = DH / 16, KC = 64, QT = 32;
+    constexpr int NT = G * 64, KK = DH / 32, DT = DH / 16, KC = 64, QT = 16 * NQT;
     constexpr int KP = DH / 8;
     constexpr int K_PIECES = KC * KP / NT, V_PIECES = DH * (KC / 8) / NT;
     constexpr int K_BYTES = KC * DH * 2, STAGE = 2 * K_BYTES;
@@ -2010,12 +2011,14 @@ k_attn_pv_pages(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, con
     }
     const float sl2 = scale * 1.44269504088896341f;          // scores in the log2 domain
 
-    bf16x8_a qf[2][KK];
-    unsigned long long mask[2][W];
-    float m_run[2] = {-INFINITY, -INFINITY}, den[2] = {0.f, 0.f};
-    int pos[2], sink_end[2], win_begin[2];
+    bf16x8_a qf[NQT][KK];
+    unsigned long long mask[NQT][W];
+    float m_run[NQT], den[NQT];
+    int pos[NQT], sink_end[NQT], win_begin[NQT];
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
+    for (int qt = 0; qt < NQT; ++qt) {
+        m_run[qt] = -INFINITY;
+        den[qt] = 0.f;
         const int qi = q0 + 16 * qt + l16;
         const bool live = qi < Tn;
         const int qr = live ? qi : Tn - 1;
@@ -2032,9 +2035,9 @@ k_attn_pv_pages(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, con
         win_begin[qt] = n - n_window > sink_end[qt] ? n - n_window : sink_end[qt];
     }
 
-    floatx4_a oacc[2][DT];
+    floatx4_a oacc[NQT][DT];
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt)
+    for (int qt = 0; qt < NQT; ++qt)
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) oacc[qt][dt] = floatx4_a{0.f, 0.f, 0.f, 0.f};
 
@@ -2086,7 +2089,7 @@ k_attn_pv_pages(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, con
         for (int cc = 0; cc < 2; ++cc) {
             const int kb32 = ch * KC + cc * 32;
             if (kb32 < n_max) {
-                floatx4_a st[2][2];
+                floatx4_a st[NQT][2];
 #pragma unroll
                 for (int kt = 0; kt < 2; ++kt) {
                     const int krow = cc * 32 + 8 * (l16 >> 2) + 4 * kt + (l16 & 3);
@@ -2096,7 +2099,7 @@ k_attn_pv_pages(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, con
                         kf[kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(
                             kb + krow * (DH * 2) + (((kk * 4 + lg) ^ pv_swz_k<DH>(krow)) << 4)));
 #pragma unroll
-                    for (int qt = 0; qt < 2; ++qt) {
+                    for (int qt = 0; qt < NQT; ++qt) {
                         floatx4_a acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                         for (int kk = 0; kk < KK; ++kk)
@@ -2105,15 +2108,15 @@ k_attn_pv_pages(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, con
                     }
                 }
                 // keep rule, running maximum (log2 domain), numerators as hi + lo bf16 pairs
-                bf16x8_a phi[2], plo[2];                    // numerators as hi + lo bf16 pairs (single bf16 numerators cost
-                float fac[2];                               // ~1e-2 of a short row: measured, not taken)
+                bf16x8_a phi[NQT], plo[NQT];                    // numerators as hi + lo bf16 pairs (single bf16 numerators cost
+                float fac[NQT];                               // ~1e-2 of a short row: measured, not taken)
                 bool grew = false;
                 const int kfirst = kb32 + 8 * lg;
                 // sub-chunks wholly before every query of the block and free of sink / window keys need the page
                 // bit only (one test per 4 keys, folded into the scaling as an additive 0 / -inf)
                 const bool plain = kb32 + 31 <= p0 + q0 && kb32 >= n_sink && kb32 + 31 < p0 + q0 + 1 - n_window;
 #pragma unroll
-                for (int qt = 0; qt < 2; ++qt) {
+                for (int qt = 0; qt < NQT; ++qt) {
                     float x[8];
                     float m_loc = -INFINITY;
 #pragma unroll
@@ -2162,7 +2165,7 @@ k_attn_pv_pages(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, con
                 }
                 if (__ballot(grew) != 0ull) {                // some row's maximum moved: rescale what is accumulated
 #pragma unroll
-                    for (int qt = 0; qt < 2; ++qt)
+                    for (int qt = 0; qt < NQT; ++qt)
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
                             const float fo = __shfl(fac[qt], 4 * lg + r);    // accumulator register r is query 4 lg + r
@@ -2176,7 +2179,7 @@ k_attn_pv_pages(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, con
                     const bf16x8_a vf = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(
                         vb + d * (KC * 2) + (((cc * 4 + lg) ^ ((d >> 1) & 7)) << 4)));
 #pragma unroll
-                    for (int qt = 0; qt < 2; ++qt) {
+                    for (int qt = 0; qt < NQT; ++qt) {
                         oacc[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(plo[qt], vf, oacc[qt][dt], 0, 0, 0);
                         oacc[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(phi[qt], vf, oacc[qt][dt], 0, 0, 0);
                     }
@@ -2188,7 +2191,7 @@ k_attn_pv_pages(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, con
 #undef SOL_PV_GLOAD
 #undef SOL_PV_LSTORE
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
+    for (int qt = 0; qt < NQT; ++qt) {
         float dsum = den[qt];
         dsum += __shfl_xor(dsum, 16);
         dsum += __shfl_xor(dsum, 32);
@@ -2327,9 +2330,9 @@ static bool launch_attn_tile_pages_t(const void *q, const void *kc, const void *
                        (const bf16_t *)pm, (unsigned long long *)selp, ra, pos0, T, L_max, Hq, Hkv, log2S, pv);
     const size_t lds = 4 * (size_t)64 * DH * 2;
     const float scale = 1.0f / sqrtf((float)DH);
-#define SOL_PVP(G_)                                                                                                  \
+#define SOL_PVP(G_, NQT_)                                                                                            \
     {                                                                                                                \
-        auto kern = k_attn_pv_pages<DH, G_, W, PRE>;                                                                 \
+        auto kern = k_attn_pv_pages<DH, G_, W, PRE, NQT_>;                                                           \
         static bool attr_done = false;                                                                               \
         if (!attr_done) {                                                                                            \
             if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
@@ -2337,15 +2340,21 @@ static bool launch_attn_tile_pages_t(const void *q, const void *kc, const void *
                 return false;                                                                                        \
             attr_done = true;                                                                                        \
         }                                                                                                            \
-        hipLaunchKernelGGL(kern, dim3((T + 31) / 32, Hkv, n_seq), dim3(G_ * 64), lds, st, (const bf16_t *)q,         \
+        hipLaunchKernelGGL(kern, dim3((T + 16 * NQT_ - 1) / (16 * NQT_), Hkv, n_seq), dim3(G_ * 64), lds, st, (const bf16_t *)q, \
                            (const bf16_t *)kc, (const bf16_t *)vt, (const unsigned long long *)selp, o32, pos0, T, L_max, Hq, \
                            Hkv, lpadv, scale, log2S, opt.n_sink, opt.n_window, pv);                                  \
         return true;                                                                                                 \
     }
-    if (G == 1) SOL_PVP(1)
-    if (G == 2) SOL_PVP(2)
-    if (G == 4) SOL_PVP(4)
-    SOL_PVP(8)
+    if (T <= 16) {                                           // one tile of 16 query rows per workgroup
+        if (G == 1) SOL_PVP(1, 1)
+        if (G == 2) SOL_PVP(2, 1)
+        if (G == 4) SOL_PVP(4, 1)
+        SOL_PVP(8, 1)
+    }
+    if (G == 1) SOL_PVP(1, 2)
+    if (G == 2) SOL_PVP(2, 2)
+    if (G == 4) SOL_PVP(4, 2)
+    SOL_PVP(8, 2)
 #undef SOL_PVP
 }
 
@@ -2368,17 +2377,18 @@ bool launch_attn_tile_dense(const void *q, const void *k_cache, const void *v_ca
                            L_max, Hkv, lpadv);
     const size_t lds = 4 * (size_t)64 * dh * 2;
     const float scale = 1.0f / sqrtf((float)dh);
-#define SOL_PVD(DH_, G_)                                                                                             \
+#define SOL_PVD2(DH_, G_, NQT_)                                                                                      \
     {                                                                                                                \
-        auto kern = k_attn_pv_pages<DH_, G_, 1, false>;                                                              \
+        auto kern = k_attn_pv_pages<DH_, G_, 1, false, NQT_>;                                                        \
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,    \
                                 (int)lds) != hipSuccess)                                                             \
             return false;                                                                                            \
-        hipLaunchKernelGGL(kern, dim3((T + 31) / 32, Hkv, n_seq), dim3(G_ * 64), lds, st, (const bf16_t *)q,         \
+        hipLaunchKernelGGL(kern, dim3((T + 16 * NQT_ - 1) / (16 * NQT_), Hkv, n_seq), dim3(G_ * 64), lds, st, (const bf16_t *)q, \
                            (const bf16_t *)k_cache, (const bf16_t *)vt, (const unsigned long long *)nullptr, o32, pos0, T, \
                            L_max, Hq, Hkv, lpadv, scale, 6, 0, 0, PrefixView());                                     \
         return true;                                                                                                 \
     }
+#define SOL_PVD(DH_, G_) { if (T <= 16) SOL_PVD2(DH_, G_, 1) SOL_PVD2(DH_, G_, 2) }
     if (dh == 64) {
         if (G == 1) SOL_PVD(64, 1)
         if (G == 2) SOL_PVD(64, 2)
@@ -2390,6 +2400,7 @@ bool launch_attn_tile_dense(const void *q, const void *k_cache, const void *v_ca
     if (G == 4) SOL_PVD(128, 4)
     SOL_PVD(128, 8)
 #undef SOL_PVD
+#undef SOL_PVD2
 }
 
 size_t attn_tile_pages_meta_bytes(int64_t n_seq, int Hkv, int L_max, int dh) { return (size_t)n_seq * Hkv * L_max * 2 * dh * 2; }
