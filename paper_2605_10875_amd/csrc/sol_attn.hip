@@ -649,13 +649,14 @@ __device__ __forceinline__ void pv_probs(const floatx4_a (&st)[2], float scale, 
 
 // PRE: as in k_attn_select; vt then is the transposed copy of the own cache ([n_seq][Hkv][DH][lpadv], positions
 // pv.P..) and pv.vt that of the prefix cache ([inputs][Hkv][DH][pv.lpadv]); 64-key chunks never straddle pv.P.
-template <int DH, int G, bool PRE>
+// NQT: query tiles of 16 rows per workgroup (2; 1 for passes of at most 16 rows per sequence).
+template <int DH, int G, bool PRE, int NQT>
 __global__ void __launch_bounds__(G * 64)
 k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf16_t *__restrict__ vt,
           const SelRow *__restrict__ sel, float *__restrict__ o32, const int32_t *__restrict__ pos0, int Tn, int L_max, int Hq,
           int Hkv, int lpadv, float scale, PrefixView pv)
 {
-    constexpr int NT = G * 64, KK = DH / 32, DT = DH / 16, KC = 64, QT = 32;
+    constexpr int NT = G * 64, KK = DH / 32, DT = DH / 16, KC = 64, QT = 16 * NQT;
     constexpr int KP = DH / 8;                              // 16-byte pieces per K row
     constexpr int K_PIECES = KC * KP / NT, V_PIECES = DH * (KC / 8) / NT;
     constexpr int K_BYTES = KC * DH * 2, STAGE = 2 * K_BYTES;
@@ -683,11 +684,12 @@ k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf1
     }
 
     // per-lane query state: lane l16 of every lane group owns query q0 + 16*qt + l16
-    bf16x8_a qf[2][KK];
-    float thr[2], mxl[2], den[2] = {0.f, 0.f};
-    int jstar[2], pos[2];
+    bf16x8_a qf[NQT][KK];
+    float thr[NQT], mxl[NQT], den[NQT];
+    int jstar[NQT], pos[NQT];
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
+    for (int qt = 0; qt < NQT; ++qt) {
+        den[qt] = 0.f;
         const int qi = q0 + 16 * qt + l16;
         const bool live = qi < Tn;
         const int qr = live ? qi : Tn - 1;
@@ -701,11 +703,11 @@ k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf1
         jstar[qt] = sr.jstar;
         pos[qt] = p0 + qi;
     }
-    const bool any_ties = __ballot(jstar[0] != 0x7FFFFFFF || jstar[1] != 0x7FFFFFFF) != 0ull;
+    const bool any_ties = __ballot(jstar[0] != 0x7FFFFFFF || jstar[NQT - 1] != 0x7FFFFFFF) != 0ull;
 
-    floatx4_a oacc[2][DT];
+    floatx4_a oacc[NQT][DT];
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt)
+    for (int qt = 0; qt < NQT; ++qt)
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) oacc[qt][dt] = floatx4_a{0.f, 0.f, 0.f, 0.f};
 
@@ -762,7 +764,7 @@ k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf1
             const int kb32 = ch * KC + cc * 32;             // first key of this 32-key sub-chunk
             if (kb32 < n_max) {
                 // scores: MFMA row m of tile kt is key  kb32 + 8*(m >> 2) + 4*kt + (m & 3)
-                floatx4_a st[2][2];                         // [qt][kt]
+                floatx4_a st[NQT][2];                         // [qt][kt]
 #pragma unroll
                 for (int kt = 0; kt < 2; ++kt) {
                     const int krow = cc * 32 + 8 * (l16 >> 2) + 4 * kt + (l16 & 3);
@@ -772,7 +774,7 @@ k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf1
                         kf[kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(
                             kb + krow * (DH * 2) + (((kk * 4 + lg) ^ pv_swz_k<DH>(krow)) << 4)));
 #pragma unroll
-                    for (int qt = 0; qt < 2; ++qt) {
+                    for (int qt = 0; qt < NQT; ++qt) {
                         floatx4_a acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                         for (int kk = 0; kk < KK; ++kk)
@@ -780,11 +782,11 @@ k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf1
                         st[qt][kt] = acc;
                     }
                 }
-                bf16x8_a phi[2], plo[2];
+                bf16x8_a phi[NQT], plo[NQT];
                 const int kfirst = kb32 + 8 * lg;
                 const bool diag = kb32 + 31 > p0 + q0;      // some key of the sub-chunk is beyond some query
 #pragma unroll
-                for (int qt = 0; qt < 2; ++qt) {
+                for (int qt = 0; qt < NQT; ++qt) {
                     if (any_ties) pv_probs<true, true>(st[qt], scale, thr[qt], mxl[qt], jstar[qt], pos[qt], kfirst, den[qt], phi[qt], plo[qt]);
                     else if (diag) pv_probs<true, false>(st[qt], scale, thr[qt], mxl[qt], jstar[qt], pos[qt], kfirst, den[qt], phi[qt], plo[qt]);
                     else pv_probs<false, false>(st[qt], scale, thr[qt], mxl[qt], jstar[qt], pos[qt], kfirst, den[qt], phi[qt], plo[qt]);
@@ -795,7 +797,7 @@ k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf1
                     const bf16x8_a vf = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(
                         vb + d * (KC * 2) + (((cc * 4 + lg) ^ ((d >> 1) & 7)) << 4)));
 #pragma unroll
-                    for (int qt = 0; qt < 2; ++qt) {
+                    for (int qt = 0; qt < NQT; ++qt) {
                         oacc[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(plo[qt], vf, oacc[qt][dt], 0, 0, 0);
                         oacc[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(phi[qt], vf, oacc[qt][dt], 0, 0, 0);
                     }
@@ -809,7 +811,7 @@ k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf1
 
     // ---- normalise and store: accumulator lane (l16, lg) register r is query 4*lg + r, column 16*dt + l16 ----
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
+    for (int qt = 0; qt < NQT; ++qt) {
         float dsum = den[qt];
         dsum += __shfl_xor(dsum, 16);
         dsum += __shfl_xor(dsum, 32);
@@ -1767,17 +1769,24 @@ static bool launch_attn_pv_t(const void *q, const void *kc, const void *vt, cons
                              const int32_t *pos0, int n_seq, int Tn, int L_max, int Hq, int Hkv, int lpadv, hipStream_t st,
                              PrefixView pv = PrefixView())
 {
-    auto kern = k_attn_pv<DH, G, PRE>;
     const size_t lds = 4 * (size_t)64 * DH * 2;
     static bool attr_done = false;
     if (!attr_done) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)lds) != hipSuccess)
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(k_attn_pv<DH, G, PRE, 1>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void *>(k_attn_pv<DH, G, PRE, 2>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return false;
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3((Tn + 31) / 32, Hkv, n_seq), dim3(G * 64), lds, st, (const bf16_t *)q, (const bf16_t *)kc,
-                       (const bf16_t *)vt, sel, o32, pos0, Tn, L_max, Hq, Hkv, lpadv, 1.0f / sqrtf((float)DH), pv);
+    if (Tn <= 16)                                            // one tile of 16 query rows per workgroup
+        hipLaunchKernelGGL((k_attn_pv<DH, G, PRE, 1>), dim3(1, Hkv, n_seq), dim3(G * 64), lds, st, (const bf16_t *)q,
+                           (const bf16_t *)kc, (const bf16_t *)vt, sel, o32, pos0, Tn, L_max, Hq, Hkv, lpadv,
+                           1.0f / sqrtf((float)DH), pv);
+    else
+        hipLaunchKernelGGL((k_attn_pv<DH, G, PRE, 2>), dim3((Tn + 31) / 32, Hkv, n_seq), dim3(G * 64), lds, st,
+                           (const bf16_t *)q, (const bf16_t *)kc, (const bf16_t *)vt, sel, o32, pos0, Tn, L_max, Hq, Hkv, lpadv,
+                           1.0f / sqrtf((float)DH), pv);
     return true;
 }
 
