@@ -81,7 +81,7 @@ def test_quant_codes_bit_exact(n):
         assert np.array_equal(zhat[r], o), r
 
 
-@pytest.mark.parametrize("n,dtype,rows", [(1024, "bf16", 24), (8192, "bf16", 24), (8192, "bf16", 600), (14336, "bf16", 24),
+@pytest.mark.parametrize("n,dtype,rows", [(1024, "bf16", 24), (8192, "bf16", 24), (8192, "bf16", 600), (14336, "bf16", 24), (14336, "bf16", 600),
                                           (11264, "bf16", 24), (768, "bf16", 24), (1024, "f32", 24), (8192, "f32", 24)])
 def test_prune_quant_kernel_bit_exact(n, dtype, rows):
     """The production prune + quantise kernel (wave-per-row for bf16 rows of 512*k channels, workgroup
