@@ -90,7 +90,8 @@ def test_identical_schedules_give_identical_likelihoods():
     assert all(np.array_equal(nll[0, 0], nll[0, k]) for k in range(1, 5))
 
 
-@pytest.mark.parametrize("preset,P", [("{}", 192), ("sol.PAPER_PRESET", 256)])
+@pytest.mark.parametrize("preset,P", [("{}", 192), ("sol.PAPER_PRESET", 256), ("dict(sol.PAPER_PRESET, page_size=4)", 64),
+                                      ("dict(sol.PAPER_PRESET, page_size=64, n_sink=0)", 1024)])
 def test_reading_the_prefix_in_place_equals_working_on_copies(preset, P):
     """The two layouts of the episode pass run the same arithmetic on the same values: bit-identical likelihoods, under
     the plain top-k rule and under the page rule with sink / window keys.
@@ -116,13 +117,16 @@ def test_reading_the_prefix_in_place_equals_working_on_copies(preset, P):
         "nll = host(ctx.episode_loglik(layers, head, dev(prefix), dev(tokens), dev(targets), dev(ids)))\n"
         "assert ctx.device_status() == sol.OK\n"
         "np.save(sys.argv[1], nll)\n"
+        "np.save(sys.argv[1] + '.ws.npy', np.int64(ctx.L.sol_episode_workspace_bytes(ctx.cfg, 3, 5, prefix.shape[1], 24)))\n"
     ) % (os.path.dirname(os.path.dirname(os.path.abspath(__file__))), os.path.dirname(os.path.abspath(__file__)), P, P + 24,
          preset)
-    outs = []
+    outs, sizes = [], []
     with tempfile.TemporaryDirectory() as td:
         for flag in ("0", "1"):
             path = os.path.join(td, f"nll{flag}.npy")
             env = dict(os.environ, SOL_EPISODE_COPY_PREFIX=flag)
             subprocess.run([sys.executable, "-c", code, path], check=True, env=env, timeout=300)
             outs.append(np.load(path))
+            sizes.append(int(np.load(path + ".ws.npy")))
     assert np.isfinite(outs[0]).all() and np.array_equal(outs[0], outs[1])
+    assert sizes[0] < sizes[1], sizes          # the in-place layout was the one that ran: no per-schedule prefix copies
