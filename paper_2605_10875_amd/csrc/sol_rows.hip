@@ -660,8 +660,12 @@ typedef short i16x2_r __attribute__((ext_vector_type(2)));
 // NWV waves share a row (NWV = 1: one wave per row, for many rows; NWV = 4: a workgroup per row, for the few
 // rows of a decode step, where the latency of one row's search is what counts). Wave v holds chunks
 // [v * CW, (v + 1) * CW) of 512 channels each; counts are combined through LDS.
+// The row takes 4 registers per chunk; without a floor on the waves per SIMD the compiler spreads the unrolled passes
+// over the whole register file (256 registers, one wave per SIMD) and nothing hides the latency of the DPP
+// reductions and ballots: the floor caps the registers at 128 (rows of up to 16 chunks per wave) or 168.
 template <int CHUNKS, int NWV>
 __global__ void __launch_bounds__(64 * NWV)
+__attribute__((amdgpu_waves_per_eu(CHUNKS / NWV <= 16 ? 4 : 3, 8)))
 k_prune_fq_wave(bf16_t *__restrict__ a, const RowAct *__restrict__ ra, const int32_t *__restrict__ perm, int quant,
                 int prune, int64_t M)
 {
@@ -794,6 +798,7 @@ k_prune_fq_wave(bf16_t *__restrict__ a, const RowAct *__restrict__ ra, const int
                 if (!keep) d[c][e >> 1] &= (e & 1) ? 0x0000FFFFu : 0xFFFF0000u;
             }
             quota = quota > total ? quota - total : 0;
+            __builtin_amdgcn_sched_barrier(0);               // one chunk's ballots at a time
         }
     }
 #undef SOL_ROW_COMBINE
@@ -806,6 +811,7 @@ k_prune_fq_wave(bf16_t *__restrict__ a, const RowAct *__restrict__ ra, const int
             for (int wi = 0; wi < 4; ++wi) {
                 const float v0 = __uint_as_float(d[c][wi] << 16), v1 = __uint_as_float(d[c][wi] & 0xFFFF0000u);
                 d[c][wi] = pack_bf16x2(fq_code(v0, s, qmax) * s, fq_code(v1, s, qmax) * s);
+                if (wi & 1) __builtin_amdgcn_sched_barrier(0);   // four divisions in flight are enough: more only cost registers
             }
     }
 #pragma unroll
