@@ -1987,7 +1987,10 @@ __device__ __forceinline__ float max_over_lane_groups(float v)
 // PRE: two-segment addressing as in k_attn_pv. NQT: query tiles of 16 rows per workgroup (2; 1 for passes of at most
 // 16 rows per sequence, where a second tile would be all dead rows).
 template <int DH, int G, int W, bool PRE, int NQT>
-__global__ void __launch_bounds__(G * 64)
+// (head size 64: a floor of 3 / 4 waves per SIMD caps the registers at 168 / 128; left alone the compiler takes 218 and
+// 138 and the exp / pack chains of the softmax have nothing to overlap with: 0.94 -> 0.74 ms at C2 under the paper's
+// configuration)
+__global__ void __launch_bounds__(G * 64) __attribute__((amdgpu_waves_per_eu(DH == 64 ? (NQT == 1 ? 4 : 3) : 1, 8)))
 k_attn_pv_pages(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf16_t *__restrict__ vt,
                 const unsigned long long *__restrict__ selp, float *__restrict__ o32, const int32_t *__restrict__ pos0, int Tn,
                 int L_max, int Hq, int Hkv, int lpadv, float scale, int log2S, int n_sink, int n_window, PrefixView pv)
