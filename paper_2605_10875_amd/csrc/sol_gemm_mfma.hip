@@ -380,6 +380,16 @@ __device__ __forceinline__ void gemm_epilogue(const floatx16_t (&acc)[TM][TN], c
     }
 }
 
+// 16 bytes per lane from global memory straight into LDS: lane l's piece lands at lds_addr + 16 * l
+__device__ __forceinline__ void dtl16(const bf16_t *base, uint32_t byte_off, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_addr) : "memory", "m0");
+}
+template <int N> __device__ __forceinline__ void vm_wait()
+{
+    __builtin_amdgcn_s_waitcnt(((N >> 4) << 14) | 0x0F70 | (N & 15));
+}
+
 #ifdef SOL_GEMM_TIMING
 __device__ unsigned long long *g_gemm_stamps;
 #define GT_STAMP(i) if (threadIdx.x == 0 && g_gemm_stamps) g_gemm_stamps[(size_t)blockIdx.x * 4 + (i)] = __builtin_readcyclecounter()
@@ -396,7 +406,6 @@ k_gemm_mfma(const bf16_t *__restrict__ A, int64_t lda, BMap bmap, int64_t M, int
     constexpr int TM = WM / 32, TN = WN / 32;
     constexpr int ROWS_PER_PASS = NT / 8;                 // 8 threads (16-byte chunks) per 128-byte row
     constexpr int A_PASSES = BM / ROWS_PER_PASS, B_PASSES = BN / ROWS_PER_PASS;
-    constexpr int STAGE_BYTES = (BM + BN) * 128;
     static_assert(BM % ROWS_PER_PASS == 0 && BN % ROWS_PER_PASS == 0, "tile / thread mismatch");
     extern __shared__ __align__(16) unsigned char lds[];
 
@@ -427,14 +436,12 @@ k_gemm_mfma(const bf16_t *__restrict__ A, int64_t lda, BMap bmap, int64_t M, int
     for (int p = 0; p < A_PASSES; ++p) {
         int64_t rl = p * ROWS_PER_PASS + r_in_pass;
         if (m0 + rl >= M) rl = M - 1 - m0;                  // ragged last tile: re-read the last row, never stored
-        a_off[p] = (uint32_t)(rl * lda) + (uint32_t)(chunk * 8);
+        a_off[p] = ((uint32_t)(rl * lda) + (uint32_t)((chunk ^ SOL_SWZ(r_in_pass)) * 8)) * 2u;   // bytes; lane = LDS slot
     }
     const bf16_t *b_base[B_PASSES];                         // uniform: first weight row of each pass
 #pragma unroll
     for (int p = 0; p < B_PASSES; ++p) b_base[p] = bmap.row(n0 + p * ROWS_PER_PASS);
-    const uint32_t b_off = (uint32_t)r_in_pass * (uint32_t)bmap.ld + (uint32_t)(chunk * 8);
-    const int a_dst0 = r_in_pass * 128 + ((chunk ^ SOL_SWZ(r_in_pass)) << 4);
-    const int b_dst0 = BM * 128 + a_dst0;
+    const uint32_t b_off = ((uint32_t)r_in_pass * (uint32_t)bmap.ld + (uint32_t)((chunk ^ SOL_SWZ(r_in_pass)) * 8)) * 2u;
 
     floatx16_t acc[TM][TN];
 #pragma unroll
@@ -444,33 +451,11 @@ k_gemm_mfma(const bf16_t *__restrict__ A, int64_t lda, BMap bmap, int64_t M, int
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // Software pipeline, three K slices deep in memory and two fragment sets deep in registers.
-    // LDS holds slices kt and kt+1; one register set holds slice kt+2 (loaded two steps ago, so HBM
-    // latency is covered by two steps of MFMAs), the other is being loaded with slice kt+3. Inside a
-    // step the A/B fragments of k-group kk+1 are read from LDS while the MFMAs of k-group kk issue, and
-    // the single barrier of a step sits before its last k-group: after it the finished stage is
-    // overwritten with slice kt+2, the first fragments of the next stage are read and the next global
-    // loads are issued, all in the shadow of the last k-group's MFMAs.
-    // (macros, not lambdas: register arrays captured by reference would be demoted to scratch)
-    u32x4_t ra0[A_PASSES], rb0[B_PASSES], ra1[A_PASSES], rb1[B_PASSES];
+    // Two LDS stages filled by LDS-direct loads: slice kt+2 is requested into the stage of slice kt right after the
+    // barrier that ends the reads of slice kt, and must have landed by the next step's barrier.
     bf16x8_t fa0[TM], fb0[TN], fa1[TM], fb1[TN];
     const int KT = K / BK;
-#define SOL_G_LOAD(RA, RB, KT_)                                                                            \
-    {                                                                                                      \
-        const int koff_ = ((KT_) < KT ? (KT_) : KT - 1) * BK; /* past the end: re-read the last slice */   \
-        _Pragma("unroll") for (int p = 0; p < A_PASSES; ++p)                                               \
-            RA[p] = *reinterpret_cast<const u32x4_t *>(a_base + koff_ + a_off[p]);                         \
-        _Pragma("unroll") for (int p = 0; p < B_PASSES; ++p)                                               \
-            RB[p] = *reinterpret_cast<const u32x4_t *>(b_base[p] + koff_ + b_off);                         \
-    }
-#define SOL_L_STORE(RA, RB, STAGE_)                                                                        \
-    {                                                                                                      \
-        _Pragma("unroll") for (int p = 0; p < A_PASSES; ++p)                                               \
-            *reinterpret_cast<u32x4_t *>((STAGE_) + a_dst0 + p * ROWS_PER_PASS * 128) = RA[p];             \
-        _Pragma("unroll") for (int p = 0; p < B_PASSES; ++p)                                               \
-            *reinterpret_cast<u32x4_t *>((STAGE_) + b_dst0 + p * ROWS_PER_PASS * 128) = RB[p];             \
-    }
-    // fragment read offsets (row = lane % 32 of the MFMA tile, k chunk = 2*kk + lane/32)
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const int frow = lane & 31, fk = lane >> 5, fsw = SOL_SWZ(frow);
     const int a_frag0 = (wm * WM + frow) * 128;
     const int b_frag0 = BM * 128 + (wn * WN + frow) * 128;
@@ -486,56 +471,65 @@ k_gemm_mfma(const bf16_t *__restrict__ A, int64_t lda, BMap bmap, int64_t M, int
     _Pragma("unroll") for (int i = 0; i < TM; ++i) _Pragma("unroll") for (int j = 0; j < TN; ++j)          \
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(FA[i], FB[j], acc[i][j], 0, 0, 0);
 #define SOL_FENCE __builtin_amdgcn_sched_barrier(0)
-    // one step: CUR_ holds the slice being multiplied, NXT_ the next one; (RA, RB) holds the slice after that
-    // scheduling groups (in issue order): every LDS read of the next fragments, LDS write and global load
-    // rides in the issue shadow of an MFMA (a 32x32x16 MFMA keeps the matrix pipe busy for 32 cycles)
 #define SOL_ORDER_RM                                                                                       \
     _Pragma("unroll") for (int i_ = 0; i_ < TM + TN; ++i_) {                                               \
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                 \
         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                                 \
     }                                                                                                      \
     __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - (TM + TN), 0);
-#define SOL_ORDER_TAIL                                                                                     \
-    _Pragma("unroll") for (int i_ = 0; i_ < TM * TN; ++i_) {                                               \
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                 \
-        if (i_ < TM + TN) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                               \
-        __builtin_amdgcn_sched_group_barrier(0x200, (A_PASSES + B_PASSES + TM * TN - 1) / (TM * TN), 0);   \
-        __builtin_amdgcn_sched_group_barrier(0x020, (A_PASSES + B_PASSES + TM * TN - 1) / (TM * TN), 0);   \
+    // all passes of slice KT_ into the stage at LDS byte offset STG_
+#define SOL_DTL_ONE(P_, KT_, STG_)                                                                         \
+    {                                                                                                      \
+        const int koff_ = ((KT_) < KT ? (KT_) : KT - 1) * BK;                                              \
+        if ((P_) < A_PASSES) dtl16(a_base + koff_, a_off[(P_)], (uint32_t)((STG_) + (P_) * ROWS_PER_PASS * 128 + wave_u * 1024)); \
+        else dtl16(b_base[(P_) - A_PASSES] + koff_, b_off, (uint32_t)((STG_) + BM * 128 + ((P_) - A_PASSES) * ROWS_PER_PASS * 128 + wave_u * 1024)); \
     }
-#define SOL_STEP(CUR_, NXT_, RA, RB, KT_LOAD_)                                                             \
+    static_assert(TM * TN == A_PASSES + B_PASSES && ROWS_PER_PASS == 32, "one LDS-direct load per MFMA of a k-group");
+#define SOL_STEP(CUR_, NXT_, CURO_, KT_LOAD_)                                                              \
     SOL_F_READ(fa1, fb1, CUR_, 1); SOL_MMA(fa0, fb0); SOL_ORDER_RM; SOL_FENCE;                             \
     SOL_F_READ(fa0, fb0, CUR_, 2); SOL_MMA(fa1, fb1); SOL_ORDER_RM; SOL_FENCE;                             \
     SOL_F_READ(fa1, fb1, CUR_, 3); SOL_MMA(fa0, fb0); SOL_ORDER_RM; SOL_FENCE;                             \
+    vm_wait<0>();                                                                                          \
     __syncthreads();                                                                                       \
     SOL_FENCE;                                                                                             \
-    SOL_F_READ(fa0, fb0, NXT_, 0); SOL_L_STORE(RA, RB, CUR_); SOL_G_LOAD(RA, RB, KT_LOAD_);                \
-    SOL_MMA(fa1, fb1); SOL_ORDER_TAIL; SOL_FENCE;
+    {                                                                                                      \
+        const int coff_ = ((fk ^ fsw) << 4);                                                               \
+        _Pragma("unroll") for (int m = 0; m < TM * TN; ++m) {                                              \
+            acc[m / TN][m % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[m / TN], fb1[m % TN],        \
+                                                                         acc[m / TN][m % TN], 0, 0, 0);    \
+            if (m < TM) fa0[m] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t *>(          \
+                            (NXT_) + a_frag0 + m * 32 * 128 + coff_));                                     \
+            else if (m < TM + TN) fb0[m - TM] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t *>( \
+                            (NXT_) + b_frag0 + (m - TM) * 32 * 128 + coff_));                              \
+            SOL_DTL_ONE(m, KT_LOAD_, CURO_);                                                               \
+            SOL_FENCE;                                                                                     \
+        }                                                                                                  \
+    }
 
-    unsigned char *const stage0 = lds, *const stage1 = lds + STAGE_BYTES;
+    constexpr int STAGE_BYTES2 = (BM + BN) * 128;
+    unsigned char *const stage0 = lds, *const stage1 = lds + STAGE_BYTES2;
     GT_STAMP(0);
-    SOL_G_LOAD(ra0, rb0, 0);
-    SOL_G_LOAD(ra1, rb1, 1);
-    SOL_L_STORE(ra0, rb0, stage0);
-    SOL_L_STORE(ra1, rb1, stage1);
-    SOL_G_LOAD(ra0, rb0, 2);
-    SOL_G_LOAD(ra1, rb1, 3);
+#pragma unroll
+    for (int p = 0; p < A_PASSES + B_PASSES; ++p) SOL_DTL_ONE(p, 0, 0);
+#pragma unroll
+    for (int p = 0; p < A_PASSES + B_PASSES; ++p) SOL_DTL_ONE(p, 1, STAGE_BYTES2);
+    vm_wait<0>();
     __syncthreads();
     SOL_F_READ(fa0, fb0, stage0, 0);
     GT_STAMP(1);
     for (int kt = 0; kt < KT; kt += 2) {                    // KT is even (K is a multiple of 128)
-        SOL_STEP(stage0, stage1, ra0, rb0, kt + 4);
-        SOL_STEP(stage1, stage0, ra1, rb1, kt + 5);
+        SOL_STEP(stage0, stage1, 0, kt + 2);
+        SOL_STEP(stage1, stage0, STAGE_BYTES2, kt + 3);
     }
+    vm_wait<0>();
     __syncthreads();
     GT_STAMP(2);
-#undef SOL_G_LOAD
-#undef SOL_L_STORE
 #undef SOL_F_READ
 #undef SOL_MMA
 #undef SOL_STEP
 #undef SOL_ORDER_RM
-#undef SOL_ORDER_TAIL
 #undef SOL_FENCE
+#undef SOL_DTL_ONE
 
     // ---- epilogue straight from the accumulators (tiles that lie wholly inside the matrix take the
     // version without row checks) ----
