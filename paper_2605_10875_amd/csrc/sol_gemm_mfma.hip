@@ -79,6 +79,7 @@ __device__ __forceinline__ void store_bf16_rows2(bf16_t *p0, bf16_t *p1, bool ok
 struct NoAux {};
 
 struct EpiStoreF32 {
+    static constexpr bool persistent_walk = true;
     float *C; int64_t ldc;
     template <int TN> using Aux = NoAux;
     template <int TN> __device__ __forceinline__ void preload0(int64_t, int64_t, NoAux &) const {}
@@ -100,6 +101,7 @@ template <int TN> struct AuxRows { float a0[TN], a1[TN]; };
 
 // x2 = resid + acc  (fp32 out), resid in bf16
 struct EpiResidF32 {
+    static constexpr bool persistent_walk = false;   // measured: 0.30 -> 0.42 ms for the C2 o-projection under the persistent walk
     const bf16_t *resid; float *out; int64_t ld;
     template <int TN> using Aux = AuxRows<TN>;
     template <int TN> __device__ __forceinline__ void preload0(int64_t, int64_t, AuxRows<TN> &) const {}
@@ -128,6 +130,7 @@ struct EpiResidF32 {
 
 // out = bf16(x2 + acc), x2 in fp32
 struct EpiResidOut {
+    static constexpr bool persistent_walk = true;
     const float *x2; bf16_t *out; int64_t ld;
     template <int TN> using Aux = AuxRows<TN>;
     template <int TN> __device__ __forceinline__ void preload0(int64_t, int64_t, AuxRows<TN> &) const {}
@@ -154,6 +157,7 @@ struct EpiResidOut {
 
 // a = bf16(silu(gate) * up); the wave tile's first WN/2 columns are gate, the rest the matching up
 struct EpiSiluMul {
+    static constexpr bool persistent_walk = true;
     bf16_t *a; int64_t ld;   // [M][d_ff]
     template <int TN> using Aux = NoAux;
     template <int TN> __device__ __forceinline__ void preload0(int64_t, int64_t, NoAux &) const {}
@@ -184,6 +188,7 @@ template <int TN> struct AuxRope { float2 t0[TN], t1[TN]; int2 sp0, sp1; };
 
 template <int DHT>                                      // head size: 64 or 128
 struct EpiQkvRope {
+    static constexpr bool persistent_walk = true;
     bf16_t *q, *kc, *vc;
     const float2 *rope; const int2 *row_sp;
     int L_max, Hq, Hkv;
@@ -276,6 +281,7 @@ struct OpMaxF { __device__ __forceinline__ float operator()(float a, float b) co
 struct AuxTgt { int t0, t1; };
 
 struct EpiNllPart {
+    static constexpr bool persistent_walk = true;
     float2 *part;               // [M][n_wt]
     float *tgt_logit;           // [M]
     const int32_t *row_tgt;     // [M] target token of each row, inside [0, V)
@@ -397,7 +403,11 @@ __device__ unsigned long long *g_gemm_stamps;
 #define GT_STAMP(i)
 #endif
 
-template <int BM, int BN, int WM, int WN, class Epi>
+// PERSIST: one workgroup per CU walks every tile of its slot in the XCD's band (tile index + workgroups per XCD) and
+// the pipeline runs across the tile boundary: the last two K steps of a tile request the first two slices of the next
+// one, so only a workgroup's first tile starts cold. (The pipeline's state between steps is LDS only, no registers,
+// so the epilogue in between costs it nothing.)
+template <int BM, int BN, int WM, int WN, class Epi, bool PERSIST>
 __global__ void __launch_bounds__((BM / WM) * (BN / WN) * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
 k_gemm_mfma(const bf16_t *__restrict__ A, int64_t lda, BMap bmap, int64_t M, int Nv, int K, int tiles_m, int tiles_n,
             Epi epi)
@@ -415,14 +425,11 @@ k_gemm_mfma(const bf16_t *__restrict__ A, int64_t lda, BMap bmap, int64_t M, int
     // ---- XCD-aware tile mapping: workgroup b runs on XCD b % 8; XCD x owns a contiguous band ----
     const int n_tiles = tiles_m * tiles_n;
     const int per_xcd = (n_tiles + 7) / 8;
-    const int lin = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
-    if (lin >= n_tiles) return;
+    const int band_end = ((int)(blockIdx.x & 7) + 1) * per_xcd < n_tiles ? ((int)(blockIdx.x & 7) + 1) * per_xcd : n_tiles;
+    const int lin_step = (int)(gridDim.x >> 3);             // PERSIST: workgroups per XCD
+    int lin = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    if (lin >= band_end) return;
     const int group_sz = GROUP_M * tiles_n;
-    const int grp = lin / group_sz, in_grp = lin - grp * group_sz;
-    const int rows_here = (tiles_m - grp * GROUP_M) < GROUP_M ? (tiles_m - grp * GROUP_M) : GROUP_M;
-    const int tm = grp * GROUP_M + in_grp % rows_here, tn = in_grp / rows_here;
-    const int64_t m0 = (int64_t)tm * BM;
-    const int n0 = tn * BN;
 
     // ---- per-thread global sources and LDS destinations of the staged K slices ----
     // A pass covers ROWS_PER_PASS rows (8 threads x 16 bytes per 128-byte row). Sources are wave-uniform
@@ -430,26 +437,34 @@ k_gemm_mfma(const bf16_t *__restrict__ A, int64_t lda, BMap bmap, int64_t M, int
     // pass (ROWS_PER_PASS is a multiple of 16), so one destination offset serves all passes.
     static_assert(ROWS_PER_PASS % 16 == 0, "swizzle must repeat from pass to pass");
     const int chunk = tid & 7, r_in_pass = tid >> 3;
-    const bf16_t *const a_base = A + m0 * lda;              // uniform
+    const bf16_t *a_base;                                   // uniform
     uint32_t a_off[A_PASSES];
-#pragma unroll
-    for (int p = 0; p < A_PASSES; ++p) {
-        int64_t rl = p * ROWS_PER_PASS + r_in_pass;
-        if (m0 + rl >= M) rl = M - 1 - m0;                  // ragged last tile: re-read the last row, never stored
-        a_off[p] = ((uint32_t)(rl * lda) + (uint32_t)((chunk ^ SOL_SWZ(r_in_pass)) * 8)) * 2u;   // bytes; lane = LDS slot
-    }
     const bf16_t *b_base[B_PASSES];                         // uniform: first weight row of each pass
-#pragma unroll
-    for (int p = 0; p < B_PASSES; ++p) b_base[p] = bmap.row(n0 + p * ROWS_PER_PASS);
+    // sources of tile LIN_, its first row and first virtual column
+#define SOL_TILE_SRC(LIN_, M0_, N0_)                                                                       \
+    {                                                                                                      \
+        const int grp_ = (LIN_) / group_sz, in_grp_ = (LIN_) - grp_ * group_sz;                            \
+        const int rows_here_ = (tiles_m - grp_ * GROUP_M) < GROUP_M ? (tiles_m - grp_ * GROUP_M) : GROUP_M; \
+        M0_ = (int64_t)(grp_ * GROUP_M + in_grp_ % rows_here_) * BM;                                       \
+        N0_ = (in_grp_ / rows_here_) * BN;                                                                 \
+        a_base = A + M0_ * lda;                                                                            \
+        _Pragma("unroll") for (int p = 0; p < A_PASSES; ++p) {                                             \
+            int64_t rl = p * ROWS_PER_PASS + r_in_pass;                                                    \
+            if (M0_ + rl >= M) rl = M - 1 - M0_;   /* ragged last tile: re-read the last row, never stored */ \
+            a_off[p] = ((uint32_t)(rl * lda) + (uint32_t)((chunk ^ SOL_SWZ(r_in_pass)) * 8)) * 2u;   /* bytes; lane = LDS slot */ \
+        }                                                                                                  \
+        _Pragma("unroll") for (int p = 0; p < B_PASSES; ++p) b_base[p] = bmap.row(N0_ + p * ROWS_PER_PASS); \
+    }
+    int64_t m0, m0_next = 0;
+    int n0, n0_next = 0;
+    SOL_TILE_SRC(lin, m0, n0);
     const uint32_t b_off = ((uint32_t)r_in_pass * (uint32_t)bmap.ld + (uint32_t)((chunk ^ SOL_SWZ(r_in_pass)) * 8)) * 2u;
 
     floatx16_t acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+#define SOL_ACC_ZERO                                                                                       \
+    _Pragma("unroll") for (int i = 0; i < TM; ++i) _Pragma("unroll") for (int j = 0; j < TN; ++j)          \
+        _Pragma("unroll") for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    SOL_ACC_ZERO;
 
     // Two LDS stages filled by LDS-direct loads: slice kt+2 is requested into the stage of slice kt right after the
     // barrier that ends the reads of slice kt, and must have landed by the next step's barrier.
@@ -517,32 +532,75 @@ k_gemm_mfma(const bf16_t *__restrict__ A, int64_t lda, BMap bmap, int64_t M, int
     __syncthreads();
     SOL_F_READ(fa0, fb0, stage0, 0);
     GT_STAMP(1);
-    for (int kt = 0; kt < KT; kt += 2) {                    // KT is even (K is a multiple of 128)
-        SOL_STEP(stage0, stage1, 0, kt + 2);
-        SOL_STEP(stage1, stage0, STAGE_BYTES2, kt + 3);
+    const int vcol_w = wn * WN;
+    const int64_t row_w = wm * WM + 4 * (lane >> 5);
+    if constexpr (!PERSIST) {
+        for (int kt = 0; kt < KT; kt += 2) {                // KT is even (K is a multiple of 128)
+            SOL_STEP(stage0, stage1, 0, kt + 2);
+            SOL_STEP(stage1, stage0, STAGE_BYTES2, kt + 3);
+        }
+        vm_wait<0>();
+        __syncthreads();
+        GT_STAMP(2);
+    } else {
+        for (;;) {
+            const bool more = lin + lin_step < band_end;
+            for (int kt = 0; kt < KT - 2; kt += 2) {
+                SOL_STEP(stage0, stage1, 0, kt + 2);
+                SOL_STEP(stage1, stage0, STAGE_BYTES2, kt + 3);
+            }
+            // the last two steps request slices 0 and 1 of the next tile (of this tile again after the last one:
+            // never used)
+            SOL_TILE_SRC(more ? lin + lin_step : lin, m0_next, n0_next);
+            SOL_STEP(stage0, stage1, 0, 0);
+            SOL_STEP(stage1, stage0, STAGE_BYTES2, 1);
+            // stage 0 holds the next tile's slice 0 and its first fragments are in registers; slice 1 is on its way
+            // into stage 1 and is waited for in the next tile's first step
+            gemm_epilogue<true, TM, TN>(acc, epi, m0 + row_w, M, n0 + vcol_w, lane & 31);   // M % BM == 0 (launcher): with
+            if (!more) break;                               // both epilogue versions in the loop the compiler spills the accumulators
+            SOL_ACC_ZERO;
+            lin += lin_step; m0 = m0_next; n0 = n0_next;
+        }
+        vm_wait<0>();                                       // no LDS-direct load outlives its workgroup
+        return;
     }
-    vm_wait<0>();
-    __syncthreads();
-    GT_STAMP(2);
 #undef SOL_F_READ
 #undef SOL_MMA
 #undef SOL_STEP
 #undef SOL_ORDER_RM
 #undef SOL_FENCE
 #undef SOL_DTL_ONE
+#undef SOL_TILE_SRC
+#undef SOL_ACC_ZERO
 
     // ---- epilogue straight from the accumulators (tiles that lie wholly inside the matrix take the
     // version without row checks) ----
-    const int vcol0 = n0 + wn * WN;
-    const int64_t row_w = m0 + wm * WM + 4 * (lane >> 5);
-    if (m0 + BM <= M) gemm_epilogue<true, TM, TN>(acc, epi, row_w, M, vcol0, lane & 31);
-    else gemm_epilogue<false, TM, TN>(acc, epi, row_w, M, vcol0, lane & 31);
+    if (m0 + BM <= M) gemm_epilogue<true, TM, TN>(acc, epi, m0 + row_w, M, n0 + vcol_w, lane & 31);
+    else gemm_epilogue<false, TM, TN>(acc, epi, m0 + row_w, M, n0 + vcol_w, lane & 31);
     GT_STAMP(3);
 }
 
 // ------------------------------------------------------------------------------------------------
 // launchers
 // ------------------------------------------------------------------------------------------------
+// compute units of the current device (one persistent workgroup each), 0 if the query fails
+static int device_cus()
+{
+    static int cus[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+    if (!cus[dev]) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+        cus[dev] = n;
+    }
+    return cus[dev];
+}
+
+#ifndef SOL_GEMM_PERSIST
+#define SOL_GEMM_PERSIST 1
+#endif
+
 template <int BM, int BN, int WM, int WN, class Epi>
 static bool launch_mfma(const bf16_t *A, int64_t lda, const BMap &bmap, int64_t M, int Nv, int K, const Epi &epi,
                         hipStream_t st)
@@ -551,18 +609,27 @@ static bool launch_mfma(const bf16_t *A, int64_t lda, const BMap &bmap, int64_t 
     if (Nv % BN || K % (2 * BK) || K < 2 * BK) return false;
     constexpr int NT = (BM / WM) * (BN / WN) * 64;
     constexpr size_t lds = 2 * (size_t)(BM + BN) * 128;
-    auto kern = k_gemm_mfma<BM, BN, WM, WN, Epi>;
+    auto kern = k_gemm_mfma<BM, BN, WM, WN, Epi, false>;
+    auto kern_p = k_gemm_mfma<BM, BN, WM, WN, Epi, true>;
     static bool attr_done = false;
     if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void *>(kern_p), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)lds) != hipSuccess)
             return false;
         attr_done = true;
     }
     const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = Nv / BN;
     const int n_tiles = tiles_m * tiles_n;
-    const int grid = ((n_tiles + 7) / 8) * 8;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), lds, st, A, lda, bmap, M, Nv, K, tiles_m, tiles_n, epi);
+    const int per_xcd = (n_tiles + 7) / 8;
+    // several tiles per CU and no ragged tile: the persistent walk, one workgroup per CU (CUs / 8 per XCD)
+    const int wg_xcd = device_cus() / 8;
+    if (SOL_GEMM_PERSIST && Epi::persistent_walk && wg_xcd > 0 && per_xcd > wg_xcd && M % BM == 0) {
+        hipLaunchKernelGGL(kern_p, dim3(wg_xcd * 8), dim3(NT), lds, st, A, lda, bmap, M, Nv, K, tiles_m, tiles_n, epi);
+        return true;
+    }
+    hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(NT), lds, st, A, lda, bmap, M, Nv, K, tiles_m, tiles_n, epi);
     return true;
 }
 
