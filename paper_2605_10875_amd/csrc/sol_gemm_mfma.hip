@@ -6,12 +6,14 @@
 // up interleaved in 64-column halves so that SiLU(gate)*up is formed inside one wave tile).
 //
 // Tiling: workgroup tile BM x BN, K step 64; waves in a (BM/WM) x (BN/WN) grid, each wave owning
-// WM x WN = (WM/32) x (WN/32) MFMA tiles of 32x32 in accumulator registers. A and B K-slices are
-// staged through LDS (two stages, XOR-swizzled 16-byte chunks so that the 128-bit fragment reads
-// are bank-conflict free) with the next slice prefetched into registers while the MFMAs of the
-// current slice issue. Workgroups are mapped to tiles XCD-aware: each of the 8 XCDs walks its own
-// contiguous band of the tile grid in groups of GROUP_M tile rows, so the tiles resident on an
-// XCD at any time share A rows and B columns in that XCD's L2.
+// WM x WN = (WM/32) x (WN/32) MFMA tiles of 32x32 in accumulator registers. A and B K-slices go
+// from global memory straight into LDS (LDS-direct loads; two stages, XOR-swizzled 16-byte chunks
+// so that the 128-bit fragment reads are bank-conflict free): the slice after next is requested
+// while the MFMAs of the current slice's last k-group issue. Workgroups are mapped to tiles
+// XCD-aware: each of the 8 XCDs walks its own contiguous band of the tile grid in groups of
+// GROUP_M tile rows, so the tiles resident on an XCD at any time share A rows and B columns in
+// that XCD's L2; with several tiles per CU one persistent workgroup per CU walks its share of the
+// band and the load pipeline runs across tile boundaries.
 //
 // Epilogue: functors consume the accumulators in their MFMA register layout, two rows at a time
 // (rotary + cache write, residual add, SiLU(gate)*up, plain store); bf16 outputs are paired up across
@@ -386,13 +388,20 @@ __device__ __forceinline__ void gemm_epilogue(const floatx16_t (&acc)[TM][TN], c
     }
 }
 
-// 16 bytes per lane from global memory straight into LDS: lane l's piece lands at lds_addr + 16 * l
+// 16 bytes per lane from global memory (wave-uniform base + 32-bit byte offset per lane) straight into LDS: lane l's
+// piece lands at lds_addr + 16 * l (M0 holds the wave's LDS byte address; one wait state between writing M0 and the
+// load). Written as inline assembly because the compiler, which sees an LDS write it cannot place, would wait for
+// the load before the next LDS read of any stage. The kernel therefore owns the waits: vm_wait<0>() before the
+// barrier that publishes a stage, and before a workgroup ends. The kernel must have no static LDS (the dynamic
+// segment then starts at LDS address 0).
 __device__ __forceinline__ void dtl16(const bf16_t *base, uint32_t byte_off, uint32_t lds_addr)
 {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_addr) : "memory", "m0");
 }
+// s_waitcnt vmcnt(N) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, the expcnt and lgkmcnt fields at "no wait")
 template <int N> __device__ __forceinline__ void vm_wait()
 {
+    static_assert(N >= 0 && N < 64, "vmcnt has six bits");
     __builtin_amdgcn_s_waitcnt(((N >> 4) << 14) | 0x0F70 | (N & 15));
 }
 
