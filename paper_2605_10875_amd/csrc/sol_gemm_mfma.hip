@@ -477,7 +477,7 @@ k_gemm_mfma(const bf16_t *__restrict__ A, int64_t lda, BMap bmap, int64_t M, int
 
     // Two LDS stages filled by LDS-direct loads: slice kt+2 is requested into the stage of slice kt right after the
     // barrier that ends the reads of slice kt, and must have landed by the next step's barrier.
-    bf16x8_t fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+    bf16x8_t fa0[TM], fb0[TN], fa1[TM], fb1[TN], fa2[TM], fb2[TN], fa3[TM], fb3[TN];   // one set per k-group of a step
     const int KT = K / BK;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const int frow = lane & 31, fk = lane >> 5, fsw = SOL_SWZ(frow);
@@ -509,26 +509,35 @@ k_gemm_mfma(const bf16_t *__restrict__ A, int64_t lda, BMap bmap, int64_t M, int
         else dtl16(b_base[(P_) - A_PASSES] + koff_, b_off, (uint32_t)((STG_) + BM * 128 + ((P_) - A_PASSES) * ROWS_PER_PASS * 128 + wave_u * 1024)); \
     }
     static_assert(TM * TN == A_PASSES + B_PASSES && ROWS_PER_PASS == 32, "one LDS-direct load per MFMA of a k-group");
-#define SOL_STEP(CUR_, NXT_, CURO_, KT_LOAD_)                                                              \
-    SOL_F_READ(fa1, fb1, CUR_, 1); SOL_MMA(fa0, fb0); SOL_ORDER_RM; SOL_FENCE;                             \
-    SOL_F_READ(fa0, fb0, CUR_, 2); SOL_MMA(fa1, fb1); SOL_ORDER_RM; SOL_FENCE;                             \
-    SOL_F_READ(fa1, fb1, CUR_, 3); SOL_MMA(fa0, fb0); SOL_ORDER_RM; SOL_FENCE;                             \
-    vm_wait<0>();                                                                                          \
-    __syncthreads();                                                                                       \
-    SOL_FENCE;                                                                                             \
+    // one k-group of the second half of a step, in issue order: behind each MFMA one fragment read (the first TM + TN
+    // MFMAs: k-group KK_ of the next slice into the set (FRA, FRB)) and behind every second MFMA one LDS-direct
+    // request (passes P0_ .. P0_ + 7 of slice KT_LOAD_ into the stage that was just read out)
+#define SOL_MMA_DTL(FA, FB, FRA, FRB, STG_, KK_, P0_, KT_LOAD_, CURO_)                                     \
     {                                                                                                      \
-        const int coff_ = ((fk ^ fsw) << 4);                                                               \
+        const int coff_ = ((((KK_) * 2 + fk) ^ fsw) << 4);                                                 \
         _Pragma("unroll") for (int m = 0; m < TM * TN; ++m) {                                              \
-            acc[m / TN][m % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[m / TN], fb1[m % TN],        \
+            acc[m / TN][m % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(FA[m / TN], FB[m % TN],          \
                                                                          acc[m / TN][m % TN], 0, 0, 0);    \
-            if (m < TM) fa0[m] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t *>(          \
-                            (NXT_) + a_frag0 + m * 32 * 128 + coff_));                                     \
-            else if (m < TM + TN) fb0[m - TM] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t *>( \
-                            (NXT_) + b_frag0 + (m - TM) * 32 * 128 + coff_));                              \
-            SOL_DTL_ONE(m, KT_LOAD_, CURO_);                                                               \
+            if (m < TM) FRA[m] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t *>(          \
+                            (STG_) + a_frag0 + m * 32 * 128 + coff_));                                     \
+            else if (m < TM + TN) FRB[m - TM] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t *>( \
+                            (STG_) + b_frag0 + (m - TM) * 32 * 128 + coff_));                              \
+            if (m & 1) SOL_DTL_ONE((P0_) + m / 2, KT_LOAD_, CURO_);                                        \
             SOL_FENCE;                                                                                     \
         }                                                                                                  \
     }
+    // One step. Fragments are read two k-groups ahead (four register sets), so the reads of the current stage are
+    // over after the second k-group: the barrier sits there, and the second half of the step requests slice
+    // KT_LOAD_ into the stage just read out (CURO_ = its LDS byte offset) while it reads the first two k-groups of
+    // the next stage. The requests of the previous step must have landed before the barrier publishes their stage.
+#define SOL_STEP(CUR_, NXT_, CURO_, KT_LOAD_)                                                              \
+    SOL_F_READ(fa2, fb2, CUR_, 2); SOL_MMA(fa0, fb0); SOL_ORDER_RM; SOL_FENCE;                             \
+    SOL_F_READ(fa3, fb3, CUR_, 3); SOL_MMA(fa1, fb1); SOL_ORDER_RM; SOL_FENCE;                             \
+    vm_wait<0>();                                                                                          \
+    __syncthreads();                                                                                       \
+    SOL_FENCE;                                                                                             \
+    SOL_MMA_DTL(fa2, fb2, fa0, fb0, NXT_, 0, 0, KT_LOAD_, CURO_);                                          \
+    SOL_MMA_DTL(fa3, fb3, fa1, fb1, NXT_, 1, (A_PASSES + B_PASSES) / 2, KT_LOAD_, CURO_);
 
     constexpr int STAGE_BYTES2 = (BM + BN) * 128;
     unsigned char *const stage0 = lds, *const stage1 = lds + STAGE_BYTES2;
@@ -540,6 +549,7 @@ k_gemm_mfma(const bf16_t *__restrict__ A, int64_t lda, BMap bmap, int64_t M, int
     vm_wait<0>();
     __syncthreads();
     SOL_F_READ(fa0, fb0, stage0, 0);
+    SOL_F_READ(fa1, fb1, stage0, 1);
     GT_STAMP(1);
     const int vcol_w = wn * WN;
     const int64_t row_w = wm * WM + 4 * (lane >> 5);
@@ -576,6 +586,7 @@ k_gemm_mfma(const bf16_t *__restrict__ A, int64_t lda, BMap bmap, int64_t M, int
 #undef SOL_F_READ
 #undef SOL_MMA
 #undef SOL_STEP
+#undef SOL_MMA_DTL
 #undef SOL_ORDER_RM
 #undef SOL_FENCE
 #undef SOL_DTL_ONE
