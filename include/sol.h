@@ -299,6 +299,11 @@ int sol_test_prune_quant(void *a, int dtype, int rows, int n, const int32_t *m, 
 int sol_test_quant_codes(const float *z, int rows, int n, const int32_t *bits,
                          int32_t *codes_out, float *scale_out, float *zhat_out, void *stream);
 
+/* The layer's bf16 MFMA GEMM on caller data: c[M][N] (fp32) = a[M][K] (bf16) * w[N][K]^T (bf16), fp32
+ * accumulation (Method, Eq. 1: every linear map of the frozen layer is this product). N a multiple of
+ * 256 and K a multiple of 128, else SOL_ERR_UNSUPPORTED; M >= 0 (ragged last tile allowed). */
+int sol_test_gemm(const void *a, const void *w, float *c, int M, int N, int K, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -988,6 +988,15 @@ extern "C" int sol_test_topk_select(const float *scores, int rows, int n_cols, c
     return launch_status();
 }
 
+extern "C" int sol_test_gemm(const void *a, const void *w, float *c, int M, int N, int K, void *stream)
+{
+    if (M < 0 || N <= 0 || K <= 0) return SOL_ERR_INVALID_ARG;
+    if (M == 0) return SOL_OK;
+    if (!a || !w || !c) return SOL_ERR_INVALID_ARG;
+    if (!launch_gemm_f32(a, w, c, N, M, N, K, (hipStream_t)stream)) return SOL_ERR_UNSUPPORTED;
+    return launch_status();
+}
+
 extern "C" int sol_test_prune_mask(const float *a, int rows, int n, const int32_t *m, uint8_t *keep_out, void *stream)
 {
     if (rows < 0 || n < 0) return SOL_ERR_INVALID_ARG;

@@ -25,7 +25,8 @@ EXPORTS = ("sol_validate_config", "sol_create", "sol_destroy", "sol_last_error",
            "sol_page_meta_bytes", "sol_page_meta_build", "sol_decode_step_paged", "sol_kv_refresh",
            "sol_reward_advantages", "sol_episode_workspace_bytes", "sol_episode_loglik",
            "sol_profile_enable", "sol_profile_read",
-           "sol_test_topk_select", "sol_test_prune_mask", "sol_test_prune_quant", "sol_test_quant_codes")
+           "sol_test_topk_select", "sol_test_prune_mask", "sol_test_prune_quant", "sol_test_quant_codes",
+           "sol_test_gemm")
 
 
 class RewardCfg(C.Structure):
@@ -117,6 +118,7 @@ def lib():
         L.sol_profile_read.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(C.c_char_p), C.POINTER(C.c_float),
                                        C.POINTER(C.c_int)]
         L.sol_test_topk_select.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.sol_test_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
         L.sol_test_prune_mask.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
         L.sol_test_prune_quant.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
                                            C.c_size_t, C.c_void_p]
@@ -380,6 +382,17 @@ def topk_select(scores, n_valid, k, stream=None):
     if rc:
         raise SolError(rc, "sol_test_topk_select")
     return keep
+
+
+def gemm(a, w, stream=None):
+    """a bf16 [M][K], w bf16 [N][K] (cuda): fp32 [M][N] = a * w^T by the layer's MFMA GEMM."""
+    M, K = a.shape
+    N = w.shape[0]
+    c = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    rc = lib().sol_test_gemm(_ptr(a), _ptr(w), _ptr(c), M, N, K, _stream(stream))
+    if rc:
+        raise SolError(rc, "sol_test_gemm")
+    return c
 
 
 def prune_mask(a, m, stream=None):
