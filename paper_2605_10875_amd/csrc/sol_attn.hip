@@ -361,6 +361,65 @@ __device__ __forceinline__ int wave_tie_last(const uint32_t (&key)[SLOTS], int n
     return result;
 }
 
+// number of keys >= pivot, the pivot in a vector register (the same value in every lane). NG > 0: the first NG groups of
+// 256 columns; NG == 0: every group that starts below n
+template <int SLOTS, int NG>
+__device__ __forceinline__ int wave_count_ge_v(const uint32_t (&key)[SLOTS], int n, uint32_t pivot)
+{
+    int cnt = 0;
+#pragma unroll
+    for (int j = 0; j < (NG ? NG : SLOTS / 4); ++j)
+        if (NG || 256 * j < n) {
+            unsigned long long m[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) asm("v_cmp_ge_u32_e64 %0, %1, %2" : "=s"(m[e]) : "v"(key[4 * j + e]), "v"(pivot));
+            cnt += (__popcll(m[0]) + __popcll(m[1])) + (__popcll(m[2]) + __popcll(m[3]));
+        }
+    return cnt;
+}
+
+// One row's search from the bracket [lo, hi] (count(key >= lo) >= b, count(key >= hi + 1) < b): returns the bracket
+// closed on the threshold key (lo == hi), or exact = true and lo = a pivot with exactly b keys at or above it.
+// With g(x) = #(key >= x) - b + 1/2, g(lo) > 0 > g(hi + 1). The pivot is the zero of the straight line through the
+// two ends in the score domain (regula falsi with the Illinois correction: an end that stays put twice has its
+// weight halved); on smooth score distributions this lands between the b-th and (b+1)-th largest score in about 6
+// steps where bisection of the key needs about 14. A guess outside (lo, hi], or more than 12 steps, falls back to
+// the midpoint of the key range, which bounds the worst case.
+// The bracket and the line live in vector registers and are updated by selects although every lane holds the same
+// values: the loop is bound by the scalar unit, which already counts the compare masks, and a CU has four vector
+// pipes to its one scalar pipe.
+template <int SLOTS, int NG>
+__device__ __forceinline__ uint32_t wave_search_thr(const uint32_t (&key)[SLOTS], int n, int b, uint32_t lo_s, uint32_t hi_s,
+                                                    bool &exact)
+{
+    uint32_t lo = lo_s, hi = hi_s;
+    asm volatile("" : "+v"(lo), "+v"(hi));               // from here on the compiler treats the bracket as per-lane data
+    float flo = score_unkey(lo), fhi = score_unkey(hi), glo = (float)(n - b) + 0.5f, ghi = 0.5f - (float)b;
+    int side = 0;
+    exact = false;
+    for (int it = 0; __ballot(lo < hi) != 0ull; ++it) {
+        const float fp = __builtin_fmaf(fhi - flo, glo * __builtin_amdgcn_rcpf(glo - ghi), flo);
+        const uint32_t ufp = __float_as_uint(fp);         // as score_key; which of the two zeros' keys a pivot takes is immaterial
+        uint32_t mid = (ufp & 0x80000000u) ? ~ufp : (ufp | 0x80000000u);
+        if (__ballot((mid > lo) & (mid <= hi) & (it < 12)) == 0ull) mid = lo + ((hi - lo + 1u) >> 1);
+        const int cnt = wave_count_ge_v<SLOTS, NG>(key, n, mid);
+        if (cnt == b) { exact = true; lo = mid; break; }
+        const float g = (float)(cnt - b) + 0.5f;
+        const bool up = cnt > b;                          // the pivot becomes the lower end, else pivot - 1 the upper
+        const uint32_t end = up ? mid : mid - 1u;
+        const float fend = score_unkey(end);
+        const float glo_w = side < 0 ? glo * 0.5f : glo, ghi_w = side > 0 ? ghi * 0.5f : ghi;
+        lo = up ? end : lo;
+        hi = up ? hi : end;
+        flo = up ? fend : flo;
+        fhi = up ? fhi : fend;
+        glo = up ? g : glo_w;
+        ghi = up ? ghi_w : g;
+        side = up ? 1 : -1;
+    }
+    return (uint32_t)__builtin_amdgcn_readfirstlane((int)lo);
+}
+
 // finishes one row's search from the bracket [lo, hi] (see wave_select_topk): returns the threshold key
 // and the index of the last kept key among those equal to it (INT_MAX when all of them are kept)
 template <int SLOTS>
@@ -368,34 +427,21 @@ __device__ __forceinline__ uint32_t wave_select_thr(const uint32_t (&key)[SLOTS]
                                                     uint32_t hi_in, int lane, int &jstar)
 {
     const int n = __builtin_amdgcn_readfirstlane(n_in), b = __builtin_amdgcn_readfirstlane(b_in);
-    uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)lo_in);
-    uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)hi_in);
+    const uint32_t lo0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)lo_in);
+    const uint32_t hi0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)hi_in);
     jstar = 0x7FFFFFFF;
-    // With g(x) = #(key >= x) - b + 1/2, g(lo) > 0 > g(hi + 1). The pivot is the zero of the straight line
-    // through the two ends in the score domain (regula falsi with the Illinois correction: an end that
-    // stays put twice has its weight halved); on smooth score distributions this lands between the b-th
-    // and (b+1)-th largest score in about 6 steps where bisection of the key needs about 14. A guess
-    // outside (lo, hi], or more than 12 steps, falls back to the midpoint of the key range, which bounds
-    // the worst case.
-    float flo = score_unkey(lo), fhi = score_unkey(hi), glo = (float)(n - b) + 0.5f, ghi = 0.5f - (float)b;
-    int side = 0;
-    for (int it = 0; lo < hi; ++it) {
-        const float fp = __builtin_fmaf(fhi - flo, glo * __builtin_amdgcn_rcpf(glo - ghi), flo);
-        uint32_t mid = (uint32_t)__builtin_amdgcn_readfirstlane((int)score_key(fp));
-        if (it >= 12 || !(mid > lo && mid <= hi)) mid = lo + ((hi - lo + 1u) >> 1);
-        const int cnt = wave_count_ge<SLOTS>(key, n, mid);
-        if (cnt == b) return mid;
-        const float g = (float)(cnt - b) + 0.5f;
-        if (cnt > b) {
-            lo = mid; flo = score_unkey(mid); glo = g;
-            if (side > 0) ghi *= 0.5f;
-            side = 1;
-        } else {
-            hi = mid - 1u; fhi = score_unkey(hi); ghi = g;
-            if (side < 0) glo *= 0.5f;
-            side = -1;
-        }
+    bool exact;
+    uint32_t lo;
+    if constexpr (SLOTS <= 16) {                         // one copy of the loop per row length in groups: no per-step dispatch
+        const int ng = (n + 255) >> 8;
+        if (ng <= 1) lo = wave_search_thr<SLOTS, 1>(key, n, b, lo0, hi0, exact);
+        else if (SLOTS >= 8 && ng == 2) lo = wave_search_thr<SLOTS, SLOTS >= 8 ? 2 : 1>(key, n, b, lo0, hi0, exact);
+        else if (SLOTS >= 12 && ng == 3) lo = wave_search_thr<SLOTS, SLOTS >= 12 ? 3 : 1>(key, n, b, lo0, hi0, exact);
+        else lo = wave_search_thr<SLOTS, SLOTS / 4>(key, n, b, lo0, hi0, exact);
+    } else {
+        lo = wave_search_thr<SLOTS, 0>(key, n, b, lo0, hi0, exact);
     }
+    if (exact) return lo;
     const int n_ge = wave_count_ge<SLOTS>(key, n, lo);
     if (n_ge > b) {                                      // more keys equal to the threshold than the budget has room for
         const int n_gt = (lo == 0xFFFFFFFFu) ? 0 : wave_count_ge<SLOTS>(key, n, lo + 1u);
@@ -410,35 +456,42 @@ template <int SLOTS>
 __device__ __forceinline__ void sel_row_load(const float *row, int n, int lane, uint32_t (&key)[SLOTS], uint32_t &kmax_out,
                                              uint32_t &kmin_out)
 {
-    uint32_t kmax = 0u, kmin = 0xFFFFFFFFu;
+    // score_key as shift / or / xor; the extremes are taken on the floats (three-input max and min), which order like the keys
+    auto to_key = [](float v) {
+        const uint32_t u = __float_as_uint(v);
+        return u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);
+    };
+    float fmax = -__builtin_inff(), fmin = __builtin_inff();
 #pragma unroll
     for (int j = 0; j < SLOTS / 4; ++j) {
         if (256 * (j + 1) <= n) {                          // every column of the group is a key of the row
-            const f32x4_a v = *reinterpret_cast<const f32x4_a *>(row + 256 * j + 4 * lane);
+            f32x4_a v = *reinterpret_cast<const f32x4_a *>(row + 256 * j + 4 * lane);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const uint32_t kv = score_key(v[e]);
-                key[4 * j + e] = kv;
-                kmax = kv > kmax ? kv : kmax;
-                kmin = kv < kmin ? kv : kmin;
+                v[e] += 0.0f;                              // -0 + 0 = +0
+                key[4 * j + e] = to_key(v[e]);
             }
+            fmax = __builtin_fmaxf(__builtin_fmaxf(fmax, v[0]), v[1]);
+            fmax = __builtin_fmaxf(__builtin_fmaxf(fmax, v[2]), v[3]);
+            fmin = __builtin_fminf(__builtin_fminf(fmin, v[0]), v[1]);
+            fmin = __builtin_fminf(__builtin_fminf(fmin, v[2]), v[3]);
         } else if (256 * j < n) {
             const f32x4_a v = *reinterpret_cast<const f32x4_a *>(row + 256 * j + 4 * lane);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const bool valid = 256 * j + 4 * lane + e < n;
-                const uint32_t kv = valid ? score_key(v[e]) : 0u;
-                key[4 * j + e] = kv;
-                kmax = kv > kmax ? kv : kmax;
-                kmin = (valid && kv < kmin) ? kv : kmin;
+                const float ve = v[e] + 0.0f;
+                key[4 * j + e] = valid ? to_key(ve) : 0u;
+                fmax = valid ? __builtin_fmaxf(fmax, ve) : fmax;
+                fmin = valid ? __builtin_fminf(fmin, ve) : fmin;
             }
         } else {
 #pragma unroll
             for (int e = 0; e < 4; ++e) key[4 * j + e] = 0u;
         }
     }
-    kmax_out = wave_max_u32(kmax);
-    kmin_out = wave_min_u32(kmin);
+    kmax_out = wave_max_u32(to_key(fmax));                 // a lane without a valid column holds -inf / +inf: below / above every score
+    kmin_out = wave_min_u32(to_key(fmin));
 }
 
 #ifdef SOL_SEL_TIMING
