@@ -379,12 +379,12 @@ __device__ __forceinline__ int wave_count_ge_v(const uint32_t (&key)[SLOTS], int
 }
 
 // One row's search from the bracket [lo, hi] (count(key >= lo) >= b, count(key >= hi + 1) < b): returns the bracket
-// closed on the threshold key (lo == hi), or exact = true and lo = a pivot with exactly b keys at or above it.
+// closed on the threshold key (lo == hi), or exact = true and a pivot with exactly b keys at or above it.
 // With g(x) = #(key >= x) - b + 1/2, g(lo) > 0 > g(hi + 1). The pivot is the zero of the straight line through the
-// two ends in the score domain (regula falsi with the Illinois correction: an end that stays put twice has its
-// weight halved); on smooth score distributions this lands between the b-th and (b+1)-th largest score in about 6
-// steps where bisection of the key needs about 14. A guess outside (lo, hi], or more than 12 steps, falls back to
-// the midpoint of the key range, which bounds the worst case.
+// two ends in the score domain (regula falsi with the Illinois correction: an end that stays put twice in a row has
+// its weight halved), clamped into (lo, hi] so that every step shrinks the bracket; on smooth score distributions
+// this lands between the b-th and (b+1)-th largest score in about 6 steps where bisection of the key needs about
+// 14. From the 13th step on the pivot is the midpoint of the key range, which bounds the worst case.
 // The bracket and the line live in vector registers and are updated by selects although every lane holds the same
 // values: the loop is bound by the scalar unit, which already counts the compare masks, and a CU has four vector
 // pipes to its one scalar pipe.
@@ -395,27 +395,28 @@ __device__ __forceinline__ uint32_t wave_search_thr(const uint32_t (&key)[SLOTS]
     uint32_t lo = lo_s, hi = hi_s;
     asm volatile("" : "+v"(lo), "+v"(hi));               // from here on the compiler treats the bracket as per-lane data
     float flo = score_unkey(lo), fhi = score_unkey(hi), glo = (float)(n - b) + 0.5f, ghi = 0.5f - (float)b;
-    int side = 0;
+    float w_up = 1.0f, w_dn = 1.0f;                      // what the end that stays put is scaled by if the step goes up / down
     exact = false;
     for (int it = 0; __ballot(lo < hi) != 0ull; ++it) {
         const float fp = __builtin_fmaf(fhi - flo, glo * __builtin_amdgcn_rcpf(glo - ghi), flo);
         const uint32_t ufp = __float_as_uint(fp);         // as score_key; which of the two zeros' keys a pivot takes is immaterial
-        uint32_t mid = (ufp & 0x80000000u) ? ~ufp : (ufp | 0x80000000u);
-        if (__ballot((mid > lo) & (mid <= hi) & (it < 12)) == 0ull) mid = lo + ((hi - lo + 1u) >> 1);
+        uint32_t mid = ufp ^ ((uint32_t)((int32_t)ufp >> 31) | 0x80000000u);
+        mid = mid > lo ? mid : lo + 1u;
+        mid = mid < hi ? mid : hi;
+        if (it >= 12) mid = lo + ((hi - lo + 1u) >> 1);
         const int cnt = wave_count_ge_v<SLOTS, NG>(key, n, mid);
         if (cnt == b) { exact = true; lo = mid; break; }
-        const float g = (float)(cnt - b) + 0.5f;
+        const float g = (float)(cnt - b) + 0.5f, fmid = score_unkey(mid);
         const bool up = cnt > b;                          // the pivot becomes the lower end, else pivot - 1 the upper
-        const uint32_t end = up ? mid : mid - 1u;
-        const float fend = score_unkey(end);
-        const float glo_w = side < 0 ? glo * 0.5f : glo, ghi_w = side > 0 ? ghi * 0.5f : ghi;
-        lo = up ? end : lo;
-        hi = up ? hi : end;
-        flo = up ? fend : flo;
-        fhi = up ? fhi : fend;
+        const float glo_w = glo * w_dn, ghi_w = ghi * w_up;
+        lo = up ? mid : lo;
+        hi = up ? hi : mid - 1u;
+        flo = up ? fmid : flo;
+        fhi = up ? fhi : fmid;
         glo = up ? g : glo_w;
         ghi = up ? ghi_w : g;
-        side = up ? 1 : -1;
+        w_up = up ? 0.5f : 1.0f;
+        w_dn = up ? 1.0f : 0.5f;
     }
     return (uint32_t)__builtin_amdgcn_readfirstlane((int)lo);
 }
