@@ -394,7 +394,11 @@ __device__ __forceinline__ uint32_t wave_search_thr(const uint32_t (&key)[SLOTS]
 {
     uint32_t lo = lo_s, hi = hi_s;
     asm volatile("" : "+v"(lo), "+v"(hi));               // from here on the compiler treats the bracket as per-lane data
-    float flo = score_unkey(lo), fhi = score_unkey(hi), glo = (float)(n - b) + 0.5f, ghi = 0.5f - (float)b;
+    // counts enter the line as log-odds, t(c) = log2((c + 1/2) / (n - c + 1/2)) - t(b - 1/2): for bell-shaped score
+    // distributions t is close to linear in the score where the count itself is S-shaped
+    const float nh = (float)n + 0.5f, t_b = __builtin_amdgcn_logf((float)b * __builtin_amdgcn_rcpf((float)(n - b) + 1.0f));
+    float flo = score_unkey(lo), fhi = score_unkey(hi);
+    float glo = __builtin_amdgcn_logf(nh * 2.0f) - t_b, ghi = -__builtin_amdgcn_logf(nh * 2.0f) - t_b;
     float w_up = 1.0f, w_dn = 1.0f;                      // what the end that stays put is scaled by if the step goes up / down
     exact = false;
     for (int it = 0; __ballot(lo < hi) != 0ull; ++it) {
@@ -406,7 +410,8 @@ __device__ __forceinline__ uint32_t wave_search_thr(const uint32_t (&key)[SLOTS]
         if (it >= 12) mid = lo + ((hi - lo + 1u) >> 1);
         const int cnt = wave_count_ge_v<SLOTS, NG>(key, n, mid);
         if (cnt == b) { exact = true; lo = mid; break; }
-        const float g = (float)(cnt - b) + 0.5f, fmid = score_unkey(mid);
+        const float cf = (float)cnt, fmid = score_unkey(mid);
+        const float g = __builtin_amdgcn_logf((cf + 0.5f) * __builtin_amdgcn_rcpf(nh - cf)) - t_b;
         const bool up = cnt > b;                          // the pivot becomes the lower end, else pivot - 1 the upper
         const float glo_w = glo * w_dn, ghi_w = ghi * w_up;
         lo = up ? mid : lo;
