@@ -285,6 +285,13 @@ int sol_profile_read(sol_ctx *ctx, void *stream, int max_stages, const char **na
  * for the k[r] largest allowed scores (ties to the lower j), 0 elsewhere. 1 <= k[r] <= n_valid[r]. */
 int sol_test_topk_select(const float *scores, int rows, int n_cols, const int32_t *n_valid,
                          const int32_t *k, uint8_t *keep_out, void *stream);
+/* The same decision taken by the row stage of the batched attention path (Method, "Actions and controlled
+ * execution", attention keep-rate: the budget's largest causal scores of a query, ties to the earlier key): fp32 score rows go through the
+ * key transform, threshold search and tie index of the threshold kernel, and keep_out is what the
+ * softmax kernel would keep from {threshold, tie index}. Arguments as sol_test_topk_select;
+ * n_cols <= 4096 (the longest row of the batched path), else SOL_ERR_UNSUPPORTED and nothing is written. */
+int sol_test_attn_threshold(const float *scores, int rows, int n_cols, const int32_t *n_valid,
+                            const int32_t *k, uint8_t *keep_out, void *stream);
 /* keep_out[r][c] = 1 for the m[r] largest |a[r][c]| (ties to the lower c). */
 int sol_test_prune_mask(const float *a, int rows, int n, const int32_t *m, uint8_t *keep_out,
                         void *stream);

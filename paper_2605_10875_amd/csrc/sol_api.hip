@@ -988,6 +988,16 @@ extern "C" int sol_test_topk_select(const float *scores, int rows, int n_cols, c
     return launch_status();
 }
 
+extern "C" int sol_test_attn_threshold(const float *scores, int rows, int n_cols, const int32_t *n_valid, const int32_t *k,
+                                       uint8_t *keep_out, void *stream)
+{
+    if (rows < 0 || n_cols < 0) return SOL_ERR_INVALID_ARG;
+    if (rows == 0 || n_cols == 0) return SOL_OK;
+    if (!scores || !n_valid || !k || !keep_out) return SOL_ERR_INVALID_ARG;
+    if (!launch_test_attn_threshold(scores, rows, n_cols, n_valid, k, keep_out, (hipStream_t)stream)) return SOL_ERR_UNSUPPORTED;
+    return launch_status();
+}
+
 extern "C" int sol_test_gemm(const void *a, const void *w, float *c, int M, int N, int K, void *stream)
 {
     if (M < 0 || N <= 0 || K <= 0) return SOL_ERR_INVALID_ARG;

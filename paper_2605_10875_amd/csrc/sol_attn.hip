@@ -665,6 +665,46 @@ k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRo
 #undef SOL_SEL_MFMA
 }
 
+// Unit hook: the row stage of k_attn_select (keys from an fp32 score row in LDS, threshold search, tie index) on caller
+// rows, one wave per row; keep[r][j] = 1 for the kept columns, by the same rule k_attn_pv applies to {thr, jstar}.
+template <int SLOTS>
+__global__ void __launch_bounds__(64) k_test_select_rows(const float *__restrict__ scores, int n_cols, const int32_t *__restrict__ n_valid,
+                                                         const int32_t *__restrict__ kk, uint8_t *__restrict__ keep)
+{
+    extern __shared__ __align__(16) float sc[];              // [SLOTS * 64]
+    const int lane = threadIdx.x, r = blockIdx.x;
+    const float *row = scores + (int64_t)r * n_cols;
+    const int n = n_valid[r], b = kk[r];
+    for (int j = lane; j < SLOTS * 64; j += 64) sc[j] = j < n ? row[j] : 0.f;
+    __syncthreads();
+    uint32_t key[SLOTS], kmax, kmin;
+    sel_row_load<SLOTS>(sc, n, lane, key, kmax, kmin);
+    uint32_t thr = 0u;
+    int js = 0x7FFFFFFF;
+    if (b < n) thr = wave_select_thr<SLOTS>(key, n, b, kmin, kmax, lane, js);
+    const float fthr = thr ? score_unkey(thr) : -__builtin_inff();
+    for (int j = lane; j < n_cols; j += 64) {
+        const float sv = j < n ? sc[j] : 0.f;
+        keep[(int64_t)r * n_cols + j] = (j < n && (sv > fthr || (sv == fthr && j <= js))) ? 1 : 0;
+    }
+}
+
+bool launch_test_attn_threshold(const float *scores, int rows, int n_cols, const int32_t *n_valid, const int32_t *k,
+                                uint8_t *keep_out, hipStream_t st)
+{
+    if (n_cols > 4096) return false;
+#define SOL_TSEL(SL)                                                                                                 \
+    hipLaunchKernelGGL((k_test_select_rows<SL>), dim3(rows), dim3(64), (size_t)(SL) * 64 * 4, st, scores, n_cols, n_valid, k, \
+                       keep_out)
+    if (n_cols <= 256) SOL_TSEL(4);                          // the variants of launch_attn_tile
+    else if (n_cols <= 1024) SOL_TSEL(16);
+    else if (n_cols <= 1280) SOL_TSEL(20);
+    else if (n_cols <= 2048) SOL_TSEL(32);
+    else SOL_TSEL(64);
+#undef SOL_TSEL
+    return true;
+}
+
 // ---- k_attn_pv -------------------------------------------------------------------------------------
 // LDS chunk layouts (bf16, 16-byte pieces XOR-swizzled so that the 128-bit fragment reads of 16 lanes
 // hit 16 different bank groups):

@@ -67,6 +67,9 @@ void launch_embed(const void *embed, const int32_t *tokens, void *x, int dtype, 
 void launch_nll_rows(const float *logits, int64_t rows, int V, const int32_t *targets, int64_t row0, int G, int T,
                      bool broadcast_g, float *nll, hipStream_t st);
 // unit hooks
+// the row stage of the batched threshold kernel on caller rows (n_cols <= 4096, else false and nothing launched)
+bool launch_test_attn_threshold(const float *scores, int rows, int n_cols, const int32_t *n_valid, const int32_t *k,
+                                uint8_t *keep_out, hipStream_t st);
 void launch_test_topk(const float *scores, int rows, int n_cols, const int32_t *n_valid, const int32_t *k,
                       uint8_t *keep, hipStream_t st);
 void launch_test_prune(const float *a, int rows, int n, const int32_t *m, uint8_t *keep, hipStream_t st);

@@ -26,7 +26,7 @@ EXPORTS = ("sol_validate_config", "sol_create", "sol_destroy", "sol_last_error",
            "sol_reward_advantages", "sol_episode_workspace_bytes", "sol_episode_loglik",
            "sol_profile_enable", "sol_profile_read",
            "sol_test_topk_select", "sol_test_prune_mask", "sol_test_prune_quant", "sol_test_quant_codes",
-           "sol_test_gemm")
+           "sol_test_gemm", "sol_test_attn_threshold")
 
 
 class RewardCfg(C.Structure):
@@ -118,6 +118,7 @@ def lib():
         L.sol_profile_read.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(C.c_char_p), C.POINTER(C.c_float),
                                        C.POINTER(C.c_int)]
         L.sol_test_topk_select.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.sol_test_attn_threshold.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.sol_test_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
         L.sol_test_prune_mask.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
         L.sol_test_prune_quant.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -381,6 +382,17 @@ def topk_select(scores, n_valid, k, stream=None):
                                     _stream(stream))
     if rc:
         raise SolError(rc, "sol_test_topk_select")
+    return keep
+
+
+def attn_threshold(scores, n_valid, k, stream=None):
+    """As topk_select, through the row stage of the batched threshold kernel (n_cols <= 4096)."""
+    rows, n_cols = scores.shape
+    keep = torch.zeros((rows, n_cols), dtype=torch.uint8, device="cuda")
+    rc = lib().sol_test_attn_threshold(_ptr(scores), rows, n_cols, _ptr(_i32(n_valid)), _ptr(_i32(k)), _ptr(keep),
+                                       _stream(stream))
+    if rc:
+        raise SolError(rc, "sol_test_attn_threshold")
     return keep
 
 

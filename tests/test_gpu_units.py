@@ -24,6 +24,10 @@ def _rows(rng, rows, n, kind):
         return np.full((rows, n), 1.25, np.float32)
     if kind == "wide":                      # many binades, both signs
         return (rng.standard_normal((rows, n)) * np.exp(rng.uniform(-20, 20, (rows, n)))).astype(np.float32)
+    if kind == "heavy":                     # heavy tails plus a few outliers at the start of the row (sink keys)
+        x = rng.standard_normal((rows, n)) * np.abs(rng.standard_normal((rows, n))) * 1.3
+        x[:, :min(4, n)] += 6.0
+        return x.astype(np.float32)
     raise ValueError(kind)
 
 
@@ -46,6 +50,36 @@ def test_topk_select_bit_exact(n, kind):
         want[:n_valid[r]] = oracle.select_keys(s[r, :n_valid[r]], int(k[r]))
         assert np.array_equal(keep[r], want), (r, n_valid[r], k[r])
         assert keep[r].sum() == k[r]
+
+
+@pytest.mark.parametrize("n", [1, 2, 63, 64, 65, 255, 256, 257, 700, 1024, 1025, 1280, 1281, 2048, 2049, 4096])
+@pytest.mark.parametrize("kind", ["normal", "ties", "const", "wide", "heavy"])
+def test_attn_threshold_stage_bit_exact(n, kind):
+    """the threshold search of the batched attention path (every row-length variant) against the definition"""
+    rng = np.random.default_rng(n * 11 + len(kind))
+    rows = 24
+    s = _rows(rng, rows, n, kind)
+    n_valid = rng.integers(1, n + 1, rows).astype(np.int32)
+    n_valid[0] = n
+    k = np.array([rng.integers(1, nv + 1) for nv in n_valid], np.int32)
+    k[0] = n
+    k[1] = 1
+    k[2] = max(1, n_valid[2] - 1)
+    for r, frac in zip(range(3, 9), (0.125, 0.25, 0.5, 0.75, 0.9, 0.02)):      # the action table's keep-rates
+        n_valid[r] = n
+        k[r] = max(1, int(np.ceil(frac * n)))
+    keep = host(sol.attn_threshold(dev(s), dev(n_valid), dev(k))).astype(np.uint8)
+    for r in range(rows):
+        want = np.zeros(n, np.uint8)
+        want[:n_valid[r]] = oracle.select_keys(s[r, :n_valid[r]], int(k[r]))
+        assert np.array_equal(keep[r], want), (r, n_valid[r], k[r])
+
+
+def test_attn_threshold_stage_rejects_long_rows():
+    s = torch.zeros((1, 4097), dtype=torch.float32, device="cuda")
+    one = torch.ones(1, dtype=torch.int32, device="cuda")
+    with pytest.raises(sol.SolError):
+        sol.attn_threshold(s, one, one)
 
 
 @pytest.mark.parametrize("n", [1, 96, 1024, 8192, 14336])
