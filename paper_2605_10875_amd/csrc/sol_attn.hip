@@ -512,7 +512,8 @@ __device__ unsigned long long *g_sel_stamps;
 // of that input), keys from pv.P on from the sequence's own cache kc, which holds positions pv.P.. only
 // ([n_seq][Hkv][crows][DH]); pv.P is a multiple of 64 and the two caches lie less than 2^31 elements apart.
 template <int BQ, int SLOTS, int DH, int NW, bool PRE>
-__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(SLOTS <= 16 ? 4 : 2, SLOTS <= 16 ? 4 : 8)))
+__global__ void __launch_bounds__(NW * 64)
+__attribute__((amdgpu_waves_per_eu(SLOTS <= 16 || (SLOTS <= 32 && DH <= 64) ? 4 : SLOTS <= 32 ? 3 : 2, SLOTS <= 16 ? 4 : 8)))
 k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRow *__restrict__ sel,
               const RowAct *__restrict__ ra, const int32_t *__restrict__ pos0, int Tn, int L_max, int Hq, int Hkv,
               float scale, int nb, PrefixView pv)
@@ -746,11 +747,16 @@ __device__ __forceinline__ void pv_probs(const floatx4_a (&st)[2], float scale, 
     plo = __builtin_bit_cast(bf16x8_a, lo);
 }
 
+#ifdef SOL_PV_TIMING
+__device__ unsigned long long *g_pv_stamps;
+#endif
 // PRE: as in k_attn_select; vt then is the transposed copy of the own cache ([n_seq][Hkv][DH][lpadv], positions
 // pv.P..) and pv.vt that of the prefix cache ([inputs][Hkv][DH][pv.lpadv]); 64-key chunks never straddle pv.P.
 // NQT: query tiles of 16 rows per workgroup (2; 1 for passes of at most 16 rows per sequence).
+// Head size 64 with 4+ heads per group: three waves per SIMD (168 registers) are kept; without the floor the walk over
+// two blocks takes 186 and only two workgroups fit a CU.
 template <int DH, int G, bool PRE, int NQT>
-__global__ void __launch_bounds__(G * 64)
+__global__ void __launch_bounds__(G * 64) __attribute__((amdgpu_waves_per_eu(DH == 64 && G >= 4 ? 3 : 1, 8)))
 k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf16_t *__restrict__ vt,
           const SelRow *__restrict__ sel, float *__restrict__ o32, const int32_t *__restrict__ pos0, int Tn, int L_max, int Hq,
           int Hkv, int lpadv, float scale, PrefixView pv)
@@ -764,10 +770,23 @@ k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf1
 
     const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, lg = lane >> 4;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int qb = (int)gridDim.x - 1 - (int)blockIdx.x;   // heaviest blocks first
     const int kvh = blockIdx.y, s = blockIdx.z, h = kvh * G + w;
     const int p0 = pos0 ? pos0[s] : 0;
     if (p0 < 0 || p0 + Tn > L_max) return;
+    // A workgroup takes query blocks n_qb - 1 - x and x: every workgroup streams the same number of causal keys.
+    // With one block per workgroup the lifetimes differ by a factor of up to n_qb, and slots freed by the short
+    // workgroups of a launch were seen to stay empty until the long ones around them had ended.
+    const int n_qb = (Tn + QT - 1) / QT;
+#ifdef SOL_PV_TIMING
+    const unsigned long long t_begin = __builtin_readcyclecounter(), rt_begin = __builtin_amdgcn_s_memrealtime();
+    unsigned long long tacc[4] = {0, 0, 0, 0}, tprev = t_begin, n_chunks_sum = 0;
+#define PV_T(i) { const unsigned long long t_ = __builtin_readcyclecounter(); tacc[i] += t_ - tprev; tprev = t_; }
+#else
+#define PV_T(i)
+#endif
+    for (int pass = 0; pass < 2; ++pass) {
+    const int qb = pass == 0 ? n_qb - 1 - (int)blockIdx.x : (int)blockIdx.x;
+    if (pass == 1 && qb >= n_qb - 1 - (int)blockIdx.x) break;          // the middle block of an odd count is its own partner
     const int q0 = qb * QT;
     const int rows = (Tn - q0 < QT) ? (Tn - q0) : QT;
     const int n_max = p0 + q0 + rows;                      // keys seen by the block's last live row
@@ -848,6 +867,7 @@ k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf1
     SOL_PV_LSTORE(kreg0, vreg0, 0);
     if (1 < n_chunks) SOL_PV_GLOAD(kreg1, vreg1, 1);
     __syncthreads();
+    PV_T(0);
     for (int ch = 0; ch < n_chunks; ++ch) {
         const int stg = ch & 1;
         if (stg == 0) {
@@ -858,6 +878,7 @@ k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf1
             if (ch + 2 < n_chunks) SOL_PV_GLOAD(kreg1, vreg1, ch + 2);
         }
         const unsigned char *kb = pvl + stg * STAGE, *vb = kb + K_BYTES;
+        PV_T(1);
 #pragma unroll
         for (int cc = 0; cc < 2; ++cc) {
             const int kb32 = ch * KC + cc * 32;             // first key of this 32-key sub-chunk
@@ -903,8 +924,13 @@ k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf1
                 }
             }
         }
-        __syncthreads();
+        PV_T(2);
+        __syncthreads();                                   // also frees both stages for the workgroup's next block
+        PV_T(3);
     }
+#ifdef SOL_PV_TIMING
+    n_chunks_sum += n_chunks;
+#endif
 #undef SOL_PV_GLOAD
 #undef SOL_PV_LSTORE
 
@@ -926,6 +952,20 @@ k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf1
             }
         }
     }
+    }   // pass
+#ifdef SOL_PV_TIMING
+    if (tid == 0 && g_pv_stamps) {
+        unsigned long long *o = g_pv_stamps + ((size_t)(blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 8;
+        for (int i = 0; i < 3; ++i) o[i] = tacc[i];
+        o[3] = ((unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 20) << 32) |    // XCC_ID, HW_ID
+               (unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 4);
+        o[4] = n_chunks_sum;
+        o[5] = __builtin_readcyclecounter() - t_begin;      // lifetime in cycles
+        o[6] = rt_begin;                                    // begin / end on the constant 100 MHz clock
+        o[7] = __builtin_amdgcn_s_memrealtime();
+    }
+#endif
+#undef PV_T
 }
 
 // =================================================================================================
@@ -1883,7 +1923,7 @@ static bool launch_attn_pv_t(const void *q, const void *kc, const void *vt, cons
                            (const bf16_t *)kc, (const bf16_t *)vt, sel, o32, pos0, Tn, L_max, Hq, Hkv, lpadv,
                            1.0f / sqrtf((float)DH), pv);
     else
-        hipLaunchKernelGGL((k_attn_pv<DH, G, PRE, 2>), dim3((Tn + 31) / 32, Hkv, n_seq), dim3(G * 64), lds, st,
+        hipLaunchKernelGGL((k_attn_pv<DH, G, PRE, 2>), dim3(((Tn + 31) / 32 + 1) / 2, Hkv, n_seq), dim3(G * 64), lds, st,
                            (const bf16_t *)q, (const bf16_t *)kc, (const bf16_t *)vt, sel, o32, pos0, Tn, L_max, Hq, Hkv, lpadv,
                            1.0f / sqrtf((float)DH), pv);
     return true;
@@ -2103,10 +2143,13 @@ k_attn_pv_pages(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, con
 
     const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, lg = lane >> 4;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int qb = (int)gridDim.x - 1 - (int)blockIdx.x;
     const int kvh = blockIdx.y, s = blockIdx.z, h = kvh * G + w;
     const int p0 = pos0 ? pos0[s] : 0;
     if (p0 < 0 || p0 + Tn > L_max) return;
+    const int n_qb = (Tn + QT - 1) / QT;
+    for (int pass = 0; pass < 2; ++pass) {                  // query blocks n_qb - 1 - x and x, as in k_attn_pv
+    const int qb = pass == 0 ? n_qb - 1 - (int)blockIdx.x : (int)blockIdx.x;
+    if (pass == 1 && qb >= n_qb - 1 - (int)blockIdx.x) break;
     const int q0 = qb * QT;
     const int rows = (Tn - q0 < QT) ? (Tn - q0) : QT;
     const int n_max = p0 + q0 + rows;
@@ -2318,6 +2361,7 @@ k_attn_pv_pages(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, con
             }
         }
     }
+    }   // pass
 }
 
 int attn_tile_lpadv(int L_max) { return (L_max + 63) & ~63; }
@@ -2451,7 +2495,7 @@ static bool launch_attn_tile_pages_t(const void *q, const void *kc, const void *
                 return false;                                                                                        \
             attr_done = true;                                                                                        \
         }                                                                                                            \
-        hipLaunchKernelGGL(kern, dim3((T + 16 * NQT_ - 1) / (16 * NQT_), Hkv, n_seq), dim3(G_ * 64), lds, st, (const bf16_t *)q, \
+        hipLaunchKernelGGL(kern, dim3(((T + 16 * NQT_ - 1) / (16 * NQT_) + 1) / 2, Hkv, n_seq), dim3(G_ * 64), lds, st, (const bf16_t *)q, \
                            (const bf16_t *)kc, (const bf16_t *)vt, (const unsigned long long *)selp, o32, pos0, T, L_max, Hq, \
                            Hkv, lpadv, scale, log2S, opt.n_sink, opt.n_window, pv);                                  \
         return true;                                                                                                 \
@@ -2494,7 +2538,7 @@ bool launch_attn_tile_dense(const void *q, const void *k_cache, const void *v_ca
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,    \
                                 (int)lds) != hipSuccess)                                                             \
             return false;                                                                                            \
-        hipLaunchKernelGGL(kern, dim3((T + 16 * NQT_ - 1) / (16 * NQT_), Hkv, n_seq), dim3(G_ * 64), lds, st, (const bf16_t *)q, \
+        hipLaunchKernelGGL(kern, dim3(((T + 16 * NQT_ - 1) / (16 * NQT_) + 1) / 2, Hkv, n_seq), dim3(G_ * 64), lds, st, (const bf16_t *)q, \
                            (const bf16_t *)k_cache, (const bf16_t *)vt, (const unsigned long long *)nullptr, o32, pos0, T, \
                            L_max, Hq, Hkv, lpadv, scale, 6, 0, 0, PrefixView());                                     \
         return true;                                                                                                 \
