@@ -501,6 +501,8 @@ __device__ __forceinline__ void sel_row_load(const float *row, int n, int lane, 
 }
 
 #ifdef SOL_SEL_TIMING
+// instrumentation for a host-side probe that defines SOL_SEL_TIMING and includes this file: 8 words per workgroup
+// (cycles in the five phases of a visit, visits, begin and end on the 100 MHz clock)
 __device__ unsigned long long *g_sel_stamps;
 #endif
 // A workgroup walks several blocks of BQ query rows of one (sequence, head): while the waves search the
@@ -585,6 +587,7 @@ k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRo
     if (qb >= n_qb) return;
     SOL_SEL_LOAD(qb);
 #ifdef SOL_SEL_TIMING
+    const unsigned long long rt_begin = __builtin_amdgcn_s_memrealtime();
     unsigned long long tacc[6] = {0, 0, 0, 0, 0, 0}, tprev = __builtin_readcyclecounter();
 #define SEL_T(i) { const unsigned long long t_ = __builtin_readcyclecounter(); tacc[i] += t_ - tprev; tprev = t_; }
 #else
@@ -659,6 +662,8 @@ k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRo
         unsigned long long *o = g_sel_stamps + ((size_t)(blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 8;
         for (int i = 0; i < 5; ++i) o[i] = tacc[i];
         o[5] = visit;
+        o[6] = rt_begin;                                    // begin / end on the constant 100 MHz clock
+        o[7] = __builtin_amdgcn_s_memrealtime();
     }
 #endif
 #undef SEL_T
@@ -748,6 +753,8 @@ __device__ __forceinline__ void pv_probs(const floatx4_a (&st)[2], float scale, 
 }
 
 #ifdef SOL_PV_TIMING
+// instrumentation for a host-side probe that defines SOL_PV_TIMING and includes this file: 8 words per workgroup
+// (cycles in staging / compute / barrier, hardware ids, chunks, lifetime in cycles, begin and end on the 100 MHz clock)
 __device__ unsigned long long *g_pv_stamps;
 #endif
 // PRE: as in k_attn_select; vt then is the transposed copy of the own cache ([n_seq][Hkv][DH][lpadv], positions
