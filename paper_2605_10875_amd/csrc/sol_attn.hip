@@ -777,7 +777,21 @@ k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf1
 
     const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, lg = lane >> 4;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int kvh = blockIdx.y, s = blockIdx.z, h = kvh * G + w;
+    // Workgroups go to the 8 XCDs round-robin in launch order; the gridDim.x workgroups of a (sequence, KV head) read the
+    // same K and V, so they are renumbered to share an XCD (and its L2): of 8 * gridDim.x consecutive workgroups, those
+    // with the same launch index modulo 8 form one group.
+    int bx = blockIdx.x, kvh = blockIdx.y, s = blockIdx.z;
+    {
+        const int nbx = gridDim.x, n_grp = (int)(gridDim.y * gridDim.z);
+        if (n_grp % 8 == 0) {
+            const int id = bx + nbx * (kvh + (int)gridDim.y * s), chunk = id / (8 * nbx), within = id - chunk * (8 * nbx);
+            const int g = chunk * 8 + (within & 7);
+            bx = within >> 3;
+            kvh = g % (int)gridDim.y;
+            s = g / (int)gridDim.y;
+        }
+    }
+    const int h = kvh * G + w;
     const int p0 = pos0 ? pos0[s] : 0;
     if (p0 < 0 || p0 + Tn > L_max) return;
     // A workgroup takes query blocks n_qb - 1 - x and x: every workgroup streams the same number of causal keys.
@@ -792,8 +806,8 @@ k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf1
 #define PV_T(i)
 #endif
     for (int pass = 0; pass < 2; ++pass) {
-    const int qb = pass == 0 ? n_qb - 1 - (int)blockIdx.x : (int)blockIdx.x;
-    if (pass == 1 && qb >= n_qb - 1 - (int)blockIdx.x) break;          // the middle block of an odd count is its own partner
+    const int qb = pass == 0 ? n_qb - 1 - bx : bx;
+    if (pass == 1 && qb >= n_qb - 1 - bx) break;            // the middle block of an odd count is its own partner
     const int q0 = qb * QT;
     const int rows = (Tn - q0 < QT) ? (Tn - q0) : QT;
     const int n_max = p0 + q0 + rows;                      // keys seen by the block's last live row
