@@ -38,7 +38,8 @@ class LayerWeights(C.Structure):
 
 
 class Taps(C.Structure):
-    _fields_ = [("keep_mask", C.POINTER(C.c_uint8)), ("attn_out", _FP), ("mlp_act", _FP), ("x_mid", _FP)]
+    _fields_ = [("keep_mask", C.POINTER(C.c_uint8)), ("attn_out", _FP), ("mlp_act", _FP), ("x_mid", _FP),
+                ("q_rot", _FP), ("h2", _FP), ("h1", _FP)]
 
 
 _lib = None
@@ -207,6 +208,15 @@ def layer_forward(cfg, table, w, x_in, action_ids, k_cache, v_cache, pos0=None, 
     if "x_mid" in taps:
         res["x_mid"] = np.zeros((n_seq, T, d), np.float32)
         tp.x_mid = _p(res["x_mid"])
+    if "q_rot" in taps:
+        res["q_rot"] = np.zeros((n_seq, T, cfg.n_q_heads * cfg.head_dim), np.float32)
+        tp.q_rot = _p(res["q_rot"])
+    if "h2" in taps:
+        res["h2"] = np.zeros((n_seq, T, d), np.float32)
+        tp.h2 = _p(res["h2"])
+    if "h1" in taps:
+        res["h1"] = np.zeros((n_seq, T, d), np.float32)
+        tp.h1 = _p(res["h1"])
     rc = lib().orc_layer_forward(C.byref(cfg), table, C.c_int32(len(table)), C.byref(ws),
                                  _p(x_in), _p(x_out), _p(ids, C.c_int32),
                                  _p(p0, C.c_int32) if p0 is not None else None,

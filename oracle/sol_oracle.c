@@ -377,6 +377,8 @@ int32_t orc_layer_forward(const orc_cfg *cfg, const orc_action *table, int32_t n
         }
     }
     if (taps && taps->attn_out) memcpy(taps->attn_out, ob, sizeof(float) * (size_t)(M * Hq * dh));
+    if (taps && taps->q_rot) memcpy(taps->q_rot, qb, sizeof(float) * (size_t)(M * Hq * dh));
+    if (taps && taps->h1) memcpy(taps->h1, h1, sizeof(float) * (size_t)(M * d));
 
     /* steps 7-12: site B, output projection + residual, post norm, MLP under prune / quant */
     #pragma omp parallel for schedule(dynamic, 1)
@@ -433,6 +435,7 @@ int32_t orc_layer_forward(const orc_cfg *cfg, const orc_action *table, int32_t n
     }
     if (taps && taps->mlp_act) memcpy(taps->mlp_act, ab, sizeof(float) * (size_t)(M * dff));
     if (taps && taps->x_mid) memcpy(taps->x_mid, x2, sizeof(float) * (size_t)(M * d));
+    if (taps && taps->h2) memcpy(taps->h2, h2, sizeof(float) * (size_t)(M * d));
 
     free(h1); free(qb); free(ob); free(x2); free(h2); free(ab);
     return 0;

@@ -18,7 +18,11 @@
  *
  * Pins (tests/test_oracle_*.py): dense special case against PyTorch CPU
  * primitives; brute-force rank selection on tiny inputs; closed forms for the
- * quantiser, the page bound, softmax and NLL; batched == step-wise; causality.
+ * quantiser, the page bound, softmax and NLL; batched == step-wise; causality;
+ * the bf16-store mode against a float64 witness that rounds through
+ * torch.bfloat16 at exactly the hand-over points (and must disagree when any
+ * one of them is left out); the page rule inside the layer against a numpy
+ * page ranking on the witness's own q and k.
  * No value printed by the paper exists for any operator (the paper gives no
  * worked numeric example), so against the paper's own numbers parity is
  * unpinned; the invariants above are the whole net.
@@ -118,6 +122,12 @@ typedef struct {
     float   *attn_out;   /* [n_seq*T][n_q_heads*head_dim], before site B      */
     float   *mlp_act;    /* [n_seq*T][d_ff], after prune + site D             */
     float   *x_mid;      /* [n_seq*T][d_model], residual after attention      */
+    float   *q_rot;      /* [n_seq*T][n_q_heads*head_dim], queries after the
+                            rotary embedding, as attention reads them         */
+    float   *h2;         /* [n_seq*T][d_model], MLP input as the gate / up
+                            projections read it (after norm, prune, site C)   */
+    float   *h1;         /* [n_seq*T][d_model], input of the q/k/v projections
+                            (after the input norm and site A)                 */
 } orc_taps;
 
 /* One decoder layer over T tokens per sequence. Token i of sequence s sits at

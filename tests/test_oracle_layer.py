@@ -32,12 +32,26 @@ def _rope_complex(x, pos, theta):
     return torch.cat([xc.real, xc.imag], -1)
 
 
-def witness_layer(shape, w, x, table, ids, keep_mask=None, quant_sites=oracle.QS_NORTHSTAR, prune_site=0):
-    """float64 layer for pos0 = 0. keep_mask [n,T,Hq,T] (from the oracle's tap) or None = causal dense."""
+def witness_layer(shape, w, x, table, ids, keep_mask=None, quant_sites=oracle.QS_NORTHSTAR, prune_site=0,
+                  act_bf16=False, drop=None, full=False):
+    """float64 layer for pos0 = 0. keep_mask [n,T,Hq,T] (from the oracle's tap) or None = causal dense.
+    Values are narrowed to float32 wherever the method stores a tensor (storage is fp32, sums are fp64).
+    act_bf16: the tensors handed from one operator to the next (h1, q, k, v, o, h2, a before and after the
+    prune / quantiser, layer output) make a round trip through torch.bfloat16; the residual x2 does not.
+    drop: name of one of those hand-over points whose rounding is left out (to show that the comparison notices).
+    full: return a dict of every intermediate instead of (out, scores, a)."""
     W = {k: torch.from_numpy(v).double() for k, v in w.items()}
     x = torch.from_numpy(x).double()
     n, T, d = x.shape
     Hq, Hkv, dh = shape.n_q_heads, shape.n_kv_heads, shape.head_dim
+
+    def f32(t):
+        return t.float().double()
+
+    def bf(t, name):
+        if not act_bf16 or name in (drop if isinstance(drop, tuple) else (drop,)):
+            return t
+        return t.float().to(torch.bfloat16).double()
 
     def fq(t, site):
         if not (quant_sites & site):
@@ -59,11 +73,11 @@ def witness_layer(shape, w, x, table, ids, keep_mask=None, quant_sites=oracle.QS
                 out[s, i] = t[s, i] * torch.from_numpy(keep).double()
         return out
 
-    h1 = fq(_rms(x, W["w_in_norm"], shape.rms_eps).float().double(), oracle.QS_QKV_IN)
+    h1 = bf(fq(f32(_rms(x, W["w_in_norm"], shape.rms_eps)), oracle.QS_QKV_IN), "h1")
     pos = torch.arange(T)
-    q = _rope_complex((h1 @ W["wq"].T).view(n, T, Hq, dh), pos, shape.rope_theta)
-    k = _rope_complex((h1 @ W["wk"].T).view(n, T, Hkv, dh), pos, shape.rope_theta)
-    v = (h1 @ W["wv"].T).view(n, T, Hkv, dh)
+    q = bf(f32(_rope_complex(f32(h1 @ W["wq"].T).view(n, T, Hq, dh), pos, shape.rope_theta)), "q")
+    k = bf(f32(_rope_complex(f32(h1 @ W["wk"].T).view(n, T, Hkv, dh), pos, shape.rope_theta)), "k")
+    v = bf(f32(h1 @ W["wv"].T).view(n, T, Hkv, dh), "v")
     qh = q.permute(0, 2, 1, 3)
     kh = k.permute(0, 2, 1, 3).repeat_interleave(Hq // Hkv, dim=1)
     vh = v.permute(0, 2, 1, 3).repeat_interleave(Hq // Hkv, dim=1)
@@ -73,21 +87,26 @@ def witness_layer(shape, w, x, table, ids, keep_mask=None, quant_sites=oracle.QS
         km = torch.from_numpy(keep_mask[:, :, :, :T].astype(bool)).permute(0, 2, 1, 3)   # [n,Hq,T,T]
         bias = torch.where(km, 0.0, -math.inf).double()
         o = F.scaled_dot_product_attention(qh, kh, vh, attn_mask=bias)
-    o = o.permute(0, 2, 1, 3).reshape(n, T, Hq * dh)
-    o = fq(o.float().double(), oracle.QS_O_IN)
-    x2 = x + o @ W["wo"].T
-    h2 = _rms(x2, W["w_post_norm"], shape.rms_eps).float().double()
+    o_raw = f32(o.permute(0, 2, 1, 3).reshape(n, T, Hq * dh))
+    o = bf(fq(o_raw, oracle.QS_O_IN), "o")
+    x2 = f32(x + f32(o @ W["wo"].T))
+    h2 = f32(_rms(x2, W["w_post_norm"], shape.rms_eps))
     if prune_site == 1:
         h2 = prune(h2)
-    h2 = fq(h2, oracle.QS_GATEUP_IN)
-    a = (F.silu(h2 @ W["w_gate"].T) * (h2 @ W["w_up"].T)).float().double()
+    h2 = bf(fq(h2, oracle.QS_GATEUP_IN), "h2")
+    gate, up = f32(h2 @ W["w_gate"].T), f32(h2 @ W["w_up"].T)
+    a = bf(f32(F.silu(gate) * up), "a")
     if prune_site == 0:
         a = prune(a)
-    a = fq(a, oracle.QS_DOWN_IN)
-    z = a @ W["w_down"].T
-    z = fq(z.float().double(), oracle.QS_MLP_OUT)
+    a = bf(fq(a, oracle.QS_DOWN_IN), "a_quant")
+    z = f32(a @ W["w_down"].T)
+    z = fq(z, oracle.QS_MLP_OUT)
+    out = bf(f32(x2 + z), "out")
     scores = (qh @ kh.transpose(-1, -2)) / math.sqrt(dh)
-    return (x2 + z).numpy(), scores.numpy(), a.numpy()
+    if full:
+        return dict(out=out.numpy(), scores=scores.numpy(), a=a.numpy(), q=q.numpy(), k=k.numpy(), v=v.numpy(),
+                    h1=h1.numpy(), h2=h2.numpy(), x2=x2.numpy(), o_raw=o_raw.numpy())
+    return out.numpy(), scores.numpy(), a.numpy()
 
 
 def _caches(shape, n_seq, L):
@@ -144,6 +163,107 @@ def test_action_conditioned_layer_against_witness(preset):
                 mnum, mden = table[ids[s, i]][2:4]
                 m = math.ceil(mnum * SHAPE.d_ff / mden)
                 assert np.count_nonzero(taps["mlp_act"][s, i]) == m
+
+
+HAND_OVER_POINTS = ("h1", "q", "k", "v", "o", "h2", "a", "a_quant", "out")
+
+
+def _bf16_case():
+    table = synth.action_table((0.25, 0.5, 1.0), (0.0, 0.25, 0.5), (4, 8, 16))
+    w = synth.layer_weights(SHAPE, 121, std=0.15, bf16=True)
+    n, T = 2, 14
+    x = synth.hidden_states(n, T, SHAPE.d_model, 122, bf16=True)
+    ids = synth.iid_actions(len(table), (n, T), 123)
+    return table, w, x, ids, n, T
+
+
+def _bf16_diffs(o_out, o_taps, o_kc, o_vc, wit):
+    """largest |oracle - witness| of every tensor the oracle exposes, relative to that tensor's largest value"""
+    pairs = {"out": (o_out, wit["out"]), "x2": (o_taps["x_mid"], wit["x2"]), "a": (o_taps["mlp_act"], wit["a"]),
+             "q": (o_taps["q_rot"], wit["q"].reshape(o_taps["q_rot"].shape)), "h1": (o_taps["h1"], wit["h1"]),
+             "h2": (o_taps["h2"], wit["h2"]), "o_raw": (o_taps["attn_out"], wit["o_raw"]),
+             "k": (o_kc.transpose(0, 2, 1, 3), wit["k"]), "v": (o_vc.transpose(0, 2, 1, 3), wit["v"])}
+    return {name: float(np.abs(a - b).max() / np.abs(b).max()) for name, (a, b) in pairs.items()}
+
+
+@pytest.mark.parametrize("sites", ["linear_input_sites", "paper_sites"])
+def test_bf16_store_mode_rounds_exactly_at_the_hand_over_points(sites):
+    """The bf16-store mode is the reference of every bf16 GPU comparison, so its rounding points are pinned: a
+    float64 witness that sends exactly the tensors handed from one operator to the next (h1, q, k, v, o, h2, the
+    SiLU(gate)*up product before and after prune + quantiser, the layer output; not the residual x2) through
+    torch.bfloat16 must reproduce every exposed tensor, and leaving out any single one of those roundings in the
+    witness must break the agreement, i.e. the comparison notices a missing rounding anywhere."""
+    table, w, x, ids, n, T = _bf16_case()
+    kw = dict() if sites == "linear_input_sites" else dict(prune_site=1, quant_sites=oracle.QS_PAPER)
+    cfg, tab = oracle.make_cfg(SHAPE, act_bf16=True, **kw), oracle.make_table(table)
+    kc, vc = _caches(SHAPE, n, T)
+    out, taps = oracle.layer_forward(cfg, tab, w, x, ids, kc, vc,
+                                     taps=("keep_mask", "mlp_act", "x_mid", "q_rot", "h1", "h2", "attn_out"))
+    wit = witness_layer(SHAPE, w, x, table, ids, keep_mask=taps["keep_mask"], act_bf16=True, full=True, **kw)
+    diffs = _bf16_diffs(out, taps, kc, vc, wit)
+    assert max(diffs.values()) < 1e-6, diffs
+    for t in (out, kc, vc, taps["mlp_act"], taps["q_rot"], taps["h1"], taps["h2"]):
+        assert np.array_equal(t, synth.round_to_bf16(t))
+    assert not np.array_equal(taps["x_mid"], synth.round_to_bf16(taps["x_mid"]))        # the residual stays fp32
+    points = list(HAND_OVER_POINTS)
+    if sites == "paper_sites":       # nothing sits between the two roundings of the SiLU(gate)*up product there: one point
+        points = [p for p in points if p not in ("a", "a_quant")] + [("a", "a_quant")]
+    for point in points:
+        mutant = witness_layer(SHAPE, w, x, table, ids, keep_mask=taps["keep_mask"], act_bf16=True, drop=point,
+                               full=True, **kw)
+        worst = max(_bf16_diffs(out, taps, kc, vc, mutant).values())
+        assert worst > 1e-4, (point, worst)
+
+
+def _page_rule_sets(q, k, i, num, den, S, n_sink, n_window):
+    """Appendix "Quest masking", written out in numpy for one (query, head): pages of S keys from key 0 over the
+    n = i + 1 allowed keys, bound sum_c max(q_c max_c, q_c min_c), the ceil(b / S) best pages (ties to the lower
+    page) kept whole, plus the first n_sink and last n_window allowed keys; b >= n keeps everything."""
+    n = i + 1
+    b = max(1, min(n, -(-num * n // den)))
+    if b >= n:
+        return set(range(n))
+    pages = -(-n // S)
+    bound = []
+    for u in range(pages):
+        rows = k[u * S:min(u * S + S, n)]
+        bound.append(float(np.maximum(q * rows.max(axis=0), q * rows.min(axis=0)).sum()))
+    best = sorted(range(pages), key=lambda u: (-bound[u], u))[:-(-b // S)]
+    kept = {j for u in best for j in range(u * S, min(u * S + S, n))}
+    return kept | set(range(min(n_sink, n))) | set(range(max(0, n - n_window), n))
+
+
+@pytest.mark.parametrize("S,n_sink,n_window,T", [(4, 4, 2, 40), (16, 4, 2, 50), (16, 0, 0, 70), (8, 3, 5, 33)])
+@pytest.mark.parametrize("sites", ["linear_input_sites", "paper_sites"])
+def test_page_rule_layer_against_witness(S, n_sink, n_window, T, sites):
+    """The page rule at layer level: which query, which keys and how many of them reach the page selection inside
+    the layer. The attended sets tapped from the layer must equal the page ranking recomputed in numpy from the
+    witness's own rotated q and k (unscaled q, pages over the allowed keys only, forced keys on top), and the layer
+    output must equal the witness layer run with those sets."""
+    table = synth.action_table((0.125, 0.25, 0.5, 1.0), (0.0, 0.5), (4, 16))
+    w = synth.layer_weights(SHAPE, 131, std=0.15)
+    n = 2
+    x = synth.hidden_states(n, T, SHAPE.d_model, 132)
+    ids = synth.iid_actions(len(table), (n, T), 133)
+    kw = dict() if sites == "linear_input_sites" else dict(prune_site=1, quant_sites=oracle.QS_PAPER)
+    cfg = oracle.make_cfg(SHAPE, page_size=S, n_sink=n_sink, n_window=n_window, **kw)
+    kc, vc = _caches(SHAPE, n, T)
+    out, taps = oracle.layer_forward(cfg, oracle.make_table(table), w, x, ids, kc, vc, taps=("keep_mask", "mlp_act"))
+    wit = witness_layer(SHAPE, w, x, table, ids, keep_mask=taps["keep_mask"], full=True, **kw)
+    assert np.abs(out - wit["out"]).max() < 2e-5 * np.abs(wit["out"]).max()
+    assert np.abs(taps["mlp_act"] - wit["a"]).max() < 2e-5 * np.abs(wit["a"]).max()
+    km = taps["keep_mask"]
+    grp = SHAPE.n_q_heads // SHAPE.n_kv_heads
+    sparse_rows = 0
+    for s in range(n):
+        for i in range(T):
+            num, den = table[ids[s, i]][:2]
+            for h in range(SHAPE.n_q_heads):
+                want = _page_rule_sets(wit["q"][s, i, h], wit["k"][s, :, h // grp], i, num, den, S, n_sink, n_window)
+                got = set(np.nonzero(km[s, i, h])[0].tolist())
+                assert got == want, (s, i, h, sorted(got ^ want))
+                sparse_rows += len(want) < i + 1
+    assert sparse_rows > n * T * SHAPE.n_q_heads // 4          # the case really exercises the page selection
 
 
 def test_keep_all_budget_is_bitwise_dense_attention():
