@@ -1,6 +1,6 @@
 """Compile the HIP sources under csrc/ for gfx950 into paper_2605_10875_amd/libsol.so.
 
-Each source is compiled to an object file under csrc/_build/ (in parallel; an object is reused when it is
+Each source is compiled to an object file under _build/ (in parallel; an object is reused when it is
 newer than its source and every header, unless force=True), then the objects are linked."""
 import glob
 import os
@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
-OBJ = os.path.join(CSRC, "_build")
+OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsol.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
