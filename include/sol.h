@@ -86,9 +86,7 @@ typedef struct {
                                on top of the chosen pages                                        */
     int32_t prune_site;     /* 0 = SiLU(gate)*up intermediate (keep ceil(rho d_ff) channels),
                                1 = MLP input after the post-attention norm (ceil(rho d_model))   */
-    uint32_t quant_sites;   /* any subset of SOL_QS_ALL_LINEAR_INPUTS | SOL_QS_MLP_OUT.
-                               Configurations other than page_size 1, no forced keys run the
-                               general attention kernel (no tiled / decode fast path yet)        */
+    uint32_t quant_sites;   /* any subset of SOL_QS_ALL_LINEAR_INPUTS | SOL_QS_MLP_OUT           */
 } sol_model_cfg;
 
 typedef struct {  /* device pointers, element type cfg.dtype */
@@ -216,9 +214,8 @@ int sol_kv_refresh(sol_ctx *ctx, const sol_model_weights *weights,
  * says. Workspace: sol_episode_workspace_bytes(cfg, B, K, P, T) (holds one layer's caches for B * K sequences).
  * B * K * T == 0 is a no-op; P must be positive. The K schedules of an input read its prefix cache in place when
  * the tiled attention kernels cover the shape (bf16, page_size 1 without sink / window keys, P a multiple of 64,
- * T >= 16, P + T <= 4096); otherwise each schedule works on a copy. The environment variable
- * SOL_EPISODE_COPY_PREFIX=1 (read at the first call) forces the copies: a debugging aid, the results are the same
- * bit for bit. */
+ * T >= 16, P + T <= 4096, or the page rule with P a multiple of 16 pages); otherwise each schedule works on a
+ * copy, with the same results bit for bit (sol_test_episode_loglik_copies below forces the copies). */
 size_t sol_episode_workspace_bytes(const sol_model_cfg *cfg, int B, int K, int P, int T);
 int sol_episode_loglik(sol_ctx *ctx, const sol_model_weights *weights, const int32_t *prefix_tokens,
                        const int32_t *tokens, const int32_t *targets, const int32_t *action_ids,
@@ -307,9 +304,42 @@ int sol_test_quant_codes(const float *z, int rows, int n, const int32_t *bits,
                          int32_t *codes_out, float *scale_out, float *zhat_out, void *stream);
 
 /* The layer's bf16 MFMA GEMM on caller data: c[M][N] (fp32) = a[M][K] (bf16) * w[N][K]^T (bf16), fp32
- * accumulation (Method, Eq. 1: every linear map of the frozen layer is this product). N a multiple of
+ * accumulation: the product behind every linear map of the frozen layer (the paper takes the Llama block as
+ * given; Appendix "Structured MLP activation pruning" writes the MLP as such products). N a multiple of
  * 256 and K a multiple of 128, else SOL_ERR_UNSUPPORTED; M >= 0 (ragged last tile allowed). */
 int sol_test_gemm(const void *a, const void *w, float *c, int M, int N, int K, void *stream);
+
+/* ---- stage hooks: one stage of sol_layer_forward on caller-supplied operands, through the same dispatch and
+ * kernels as the layer, so that a comparison with a reference crosses at most one quantiser. Workspace:
+ * sol_workspace_bytes(cfg, SOL_OP_LAYER_FORWARD, n_seq, T, L_max). */
+
+/* Attention stage (Appendix "Token sparsity via Quest"): q device [n_seq][T][n_q_heads*head_dim] of cfg.dtype,
+ * queries after the rotary embedding; k_cache / v_cache as in sol_layer_forward, already holding the keys and
+ * values of positions [0, pos0[s] + T); token i of sequence s attends positions [0, pos0[s] + i] under
+ * action_ids[s][i] and cfg's selection rule. o_out: device float [n_seq][T][n_q_heads*head_dim], the attention
+ * output before the quantiser of the output projection's input. */
+int sol_test_attention_stage(sol_ctx *ctx, const void *q, const int32_t *action_ids, const int32_t *pos0,
+                             void *k_cache, void *v_cache, int n_seq, int T, int L_max, float *o_out,
+                             void *workspace, size_t ws_bytes, void *stream);
+
+/* MLP stage (Appendix "Structured MLP activation pruning", "Activation quantization"): h2 device [n_seq][T][d_model]
+ * of cfg.dtype, the MLP input as the gate / up projections read it (after norm, MLP-input pruning and its quantiser);
+ * x2 device float [n_seq][T][d_model], the residual after attention. Runs gate / up, SiLU(gate)*up, magnitude pruning
+ * and the quantiser of the down projection's input, the down projection, the MLP-output quantiser if enabled, and
+ * the residual add. a_out: NULL or device [n_seq][T][d_ff] of cfg.dtype, the down projection's input; x_out: device
+ * [n_seq][T][d_model] of cfg.dtype. Workspace sized with L_max = T. */
+int sol_test_mlp_stage(sol_ctx *ctx, const sol_layer_weights *w, const void *h2, const float *x2,
+                       const int32_t *action_ids, int n_seq, int T, void *a_out, void *x_out,
+                       void *workspace, size_t ws_bytes, void *stream);
+
+/* sol_episode_loglik with every schedule working on its own copy of the prefix cache, whatever the shape (the
+ * fall-back layout of that entry point); workspace sized by sol_test_episode_copies_workspace_bytes. The results
+ * equal sol_episode_loglik's bit for bit. */
+size_t sol_test_episode_copies_workspace_bytes(const sol_model_cfg *cfg, int B, int K, int P, int T);
+int sol_test_episode_loglik_copies(sol_ctx *ctx, const sol_model_weights *weights, const int32_t *prefix_tokens,
+                                   const int32_t *tokens, const int32_t *targets, const int32_t *action_ids,
+                                   int B, int K, int P, int T, float *nll_out,
+                                   void *workspace, size_t ws_bytes, void *stream);
 
 #ifdef __cplusplus
 }

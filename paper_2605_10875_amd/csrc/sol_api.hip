@@ -6,7 +6,6 @@
 #include <cstdio>
 #include <cstring>
 #include <map>
-#include <cstdlib>
 #include <string>
 #include <utility>
 #include <vector>
@@ -371,52 +370,25 @@ static void prepare_actions(sol_ctx *ctx, const int32_t *ids, int64_t M, LayerWs
         launch_bucket_sort(w.row_bucket, M, ctx->n_buckets, w.perm, w.bucket_off, st);
 }
 
-// Launch sequence of one decoder layer (actions already decoded into w.ra / w.perm).
-static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_in, void *x_out, const int32_t *pos0,
-                      void *kc, void *vc, int n_seq, int T, int L_max, LayerWs &w, hipStream_t st,
-                      void *page_meta = nullptr, bool dense_pass = false, const PrefixView *pv = nullptr)
+// Few rows (a decode step): the linear layers are bound by reading their weights once and take the skinny GEMM.
+static bool use_skinny(const sol_model_cfg &g, int64_t M)
+{
+    return g.dtype == SOL_BF16 && M <= 64 && g.d_model % 64 == 0 && (g.n_q_heads * g.head_dim) % 64 == 0 && g.d_ff % 64 == 0;
+}
+
+// Attention stage of the layer: causal scores over cache positions [0, pos], the budgeted selection of the token's
+// action, softmax over the kept keys, times V. Reads w.qb and the caches, writes w.o32 (fp32, before the quantiser of
+// the output projection's input); w.vt / w.pm / w.big32 are scratch.
+static int attn_stage(sol_ctx *ctx, LayerWs &w, const int32_t *pos0, void *kc, void *vc, int n_seq, int T, int L_max,
+                      hipStream_t st, void *page_meta, bool dense_pass, const PrefixView *pv)
 {
     const sol_model_cfg &g = ctx->cfg;
     const int dt = g.dtype;
     const int64_t M = (int64_t)n_seq * T;
-    const int d = g.d_model, Hq = g.n_q_heads, Hkv = g.n_kv_heads, dh = g.head_dim, dff = g.d_ff;
-    const int nq = Hq * dh, nkv = Hkv * dh, nqkv = nq + 2 * nkv;
-    const uint32_t qs = g.quant_sites;
-
-    {   // input norm + quantise (linear-input site of q/k/v)
-        STAGE(ctx, ST_NORM_IN, st);
-        launch_rmsnorm_fq(x_in, dt, nullptr, nullptr, lw->w_in_norm, dt, w.h, dt, w.ra, qs & SOL_QS_QKV_IN, M, d, g.rms_eps, st);
-    }
+    const int Hq = g.n_q_heads, Hkv = g.n_kv_heads, dh = g.head_dim;
+    const int nqkv = (Hq + 2 * Hkv) * dh;
     const bool mfma = dt == SOL_BF16;
-    const bool skinny = mfma && M <= 64 && d % 64 == 0 && nq % 64 == 0 && dff % 64 == 0;   // decode: HBM-bound GEMMs
-    // shared prefix: the own caches hold positions P.. only; their writers get the base minus P rows
-    const int crows = pv ? pv->crows : 0;
-    void *kcw = pv ? (void *)((char *)kc - esize(dt) * (size_t)pv->P * dh) : kc;
-    void *vcw = pv ? (void *)((char *)vc - esize(dt) * (size_t)pv->P * dh) : vc;
-    bool fused_qkv = false;
-    int ns_qkv = 1;
-    {   // q/k/v projections (+ rotary and cache write when fused)
-        STAGE(ctx, ST_QKV, st);
-        if (skinny) {
-            ns_qkv = skinny_splits((int)M, nqkv, d);
-            if (!launch_gemm_skinny(w.h, d, lw->wq, nq, lw->wk, nkv, lw->wv, nkv, (int)M, d, w.big32, ns_qkv, st))
-                return fail(ctx, SOL_ERR_UNSUPPORTED, "skinny GEMM: unsupported shape");
-        } else {
-            fused_qkv = mfma && launch_gemm_qkv_rope(w.h, lw->wq, lw->wk, lw->wv, w.qb, kcw, vcw, ctx->d_rope, pos0, n_seq,
-                                                     T, L_max, Hq, Hkv, dh, d, ctx->d_flags, w.big32, st, crows);
-            if (!fused_qkv) {
-                launch_gemm_generic(w.h, dt, d, lw->wq, dt, d, w.big32, nqkv, M, nq, d, st);
-                launch_gemm_generic(w.h, dt, d, lw->wk, dt, d, w.big32 + nq, nqkv, M, nkv, d, st);
-                launch_gemm_generic(w.h, dt, d, lw->wv, dt, d, w.big32 + nq + nkv, nqkv, M, nkv, d, st);
-            }
-        }
-    }
-    if (!fused_qkv) {   // rotary, cache write
-        STAGE(ctx, ST_ROPE, st);
-        launch_rope_store(w.big32, w.qb, kcw, vcw, dt, ctx->d_rope, pos0, n_seq, T, L_max, Hq, Hkv, dh, ctx->d_flags, st,
-                          ns_qkv, crows);
-    }
-    {   // scores, budgeted selection, softmax over kept keys, times V
+    {
         STAGE(ctx, ST_ATTN, st);
         AttnOpts opt;
         if (!dense_pass) { opt.page = g.page_size; opt.n_sink = g.n_sink; opt.n_window = g.n_window; }   // dense rows keep every key under any rule
@@ -452,6 +424,114 @@ static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_i
             !launch_attn_rows(w.qb, kc, vc, dt, w.o32, w.ra, pos0, n_seq, T, L_max, Hq, Hkv, dh, ctx->d_flags, st, opt))
             return fail(ctx, SOL_ERR_UNSUPPORTED, "attention: L_max too long for the on-chip score rows of this build");
     }
+    return SOL_OK;
+}
+
+// MLP stage of the layer from its input on: gate / up projections, SiLU(gate)*up, magnitude pruning and the
+// quantiser of the down projection's input, down projection, (quantiser of the MLP output,) residual add.
+// Reads w.h (the MLP input as the projections take it) and w.x2 (fp32 residual after attention), writes w.a and x_out.
+static int mlp_stage(sol_ctx *ctx, const sol_layer_weights *lw, LayerWs &w, void *x_out, int64_t M, bool skinny,
+                     hipStream_t st)
+{
+    const sol_model_cfg &g = ctx->cfg;
+    const int dt = g.dtype;
+    const int d = g.d_model, dff = g.d_ff;
+    const uint32_t qs = g.quant_sites;
+    const bool mfma = dt == SOL_BF16;
+    bool fused_gu = false;
+    int ns_gu = 1;
+    {   // gate / up (+ SiLU(gate)*up when fused)
+        STAGE(ctx, ST_GATEUP, st);
+        if (skinny) {
+            ns_gu = skinny_splits((int)M, 2 * dff, d);
+            if (!launch_gemm_skinny(w.h, d, lw->w_gate, dff, lw->w_up, dff, nullptr, 0, (int)M, d, w.big32, ns_gu, st))
+                return fail(ctx, SOL_ERR_UNSUPPORTED, "skinny GEMM (gate / up): unsupported shape");
+        } else {
+            fused_gu = mfma && launch_gemm_gateup_silu(w.h, lw->w_gate, lw->w_up, w.a, M, dff, d, st);
+            if (!fused_gu) {
+                launch_gemm_generic(w.h, dt, d, lw->w_gate, dt, d, w.big32, 2 * (int64_t)dff, M, dff, d, st);
+                launch_gemm_generic(w.h, dt, d, lw->w_up, dt, d, w.big32 + dff, 2 * (int64_t)dff, M, dff, d, st);
+            }
+        }
+    }
+    if (!fused_gu) {   // SiLU(gate)*up
+        STAGE(ctx, ST_SILU, st);
+        launch_silu_mul(w.big32, w.a, dt, M, dff, st, ns_gu);
+    }
+    {   // magnitude pruning + quantise (down input), rows visited in bucket order
+        STAGE(ctx, ST_PRUNE, st);
+        if (g.prune_site == 0 || (qs & SOL_QS_DOWN_IN))      // (pruning elsewhere and no quantiser here: nothing to do)
+            launch_prune_fq(w.a, dt, w.ra, w.perm, qs & SOL_QS_DOWN_IN, M, dff, st, g.prune_site == 0);
+    }
+    bool fused_down = false;
+    int ns_down = 1;
+    const bool q_out = (qs & SOL_QS_MLP_OUT) != 0;   // the MLP output is quantised as a whole row before the residual add
+    {   // down projection (+ residual when fused)
+        STAGE(ctx, ST_DOWN, st);
+        if (skinny) {
+            ns_down = skinny_splits((int)M, d, dff);
+            if (!launch_gemm_skinny(w.a, dff, lw->w_down, d, nullptr, 0, nullptr, 0, (int)M, dff, w.big32, ns_down, st))
+                return fail(ctx, SOL_ERR_UNSUPPORTED, "skinny GEMM (down): unsupported shape");
+        } else {
+            fused_down = mfma && !q_out && launch_gemm_resid_out(w.a, lw->w_down, w.x2, x_out, M, d, dff, st);
+            if (!fused_down && !(mfma && launch_gemm_f32(w.a, lw->w_down, w.big32, d, M, d, dff, st)))
+                launch_gemm_generic(w.a, dt, dff, lw->w_down, dt, dff, w.big32, d, M, d, dff, st);
+        }
+    }
+    if (!fused_down) {   // residual
+        STAGE(ctx, ST_RESID, st);
+        if (q_out) launch_resid_out_fq(w.x2, w.big32, x_out, dt, w.ra, M, d, st, ns_down);
+        else launch_resid_out(w.x2, w.big32, x_out, dt, M, d, st, ns_down);
+    }
+    return SOL_OK;
+}
+
+// Launch sequence of one decoder layer (actions already decoded into w.ra / w.perm).
+static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_in, void *x_out, const int32_t *pos0,
+                      void *kc, void *vc, int n_seq, int T, int L_max, LayerWs &w, hipStream_t st,
+                      void *page_meta = nullptr, bool dense_pass = false, const PrefixView *pv = nullptr)
+{
+    const sol_model_cfg &g = ctx->cfg;
+    const int dt = g.dtype;
+    const int64_t M = (int64_t)n_seq * T;
+    const int d = g.d_model, Hq = g.n_q_heads, Hkv = g.n_kv_heads, dh = g.head_dim, dff = g.d_ff;
+    const int nq = Hq * dh, nkv = Hkv * dh, nqkv = nq + 2 * nkv;
+    const uint32_t qs = g.quant_sites;
+
+    {   // input norm + quantise (linear-input site of q/k/v)
+        STAGE(ctx, ST_NORM_IN, st);
+        launch_rmsnorm_fq(x_in, dt, nullptr, nullptr, lw->w_in_norm, dt, w.h, dt, w.ra, qs & SOL_QS_QKV_IN, M, d, g.rms_eps, st);
+    }
+    const bool mfma = dt == SOL_BF16;
+    const bool skinny = use_skinny(g, M);                      // decode: HBM-bound GEMMs
+    // shared prefix: the own caches hold positions P.. only; their writers get the base minus P rows
+    const int crows = pv ? pv->crows : 0;
+    void *kcw = pv ? (void *)((char *)kc - esize(dt) * (size_t)pv->P * dh) : kc;
+    void *vcw = pv ? (void *)((char *)vc - esize(dt) * (size_t)pv->P * dh) : vc;
+    bool fused_qkv = false;
+    int ns_qkv = 1;
+    {   // q/k/v projections (+ rotary and cache write when fused)
+        STAGE(ctx, ST_QKV, st);
+        if (skinny) {
+            ns_qkv = skinny_splits((int)M, nqkv, d);
+            if (!launch_gemm_skinny(w.h, d, lw->wq, nq, lw->wk, nkv, lw->wv, nkv, (int)M, d, w.big32, ns_qkv, st))
+                return fail(ctx, SOL_ERR_UNSUPPORTED, "skinny GEMM: unsupported shape");
+        } else {
+            fused_qkv = mfma && launch_gemm_qkv_rope(w.h, lw->wq, lw->wk, lw->wv, w.qb, kcw, vcw, ctx->d_rope, pos0, n_seq,
+                                                     T, L_max, Hq, Hkv, dh, d, ctx->d_flags, w.big32, st, crows);
+            if (!fused_qkv) {
+                launch_gemm_generic(w.h, dt, d, lw->wq, dt, d, w.big32, nqkv, M, nq, d, st);
+                launch_gemm_generic(w.h, dt, d, lw->wk, dt, d, w.big32 + nq, nqkv, M, nkv, d, st);
+                launch_gemm_generic(w.h, dt, d, lw->wv, dt, d, w.big32 + nq + nkv, nqkv, M, nkv, d, st);
+            }
+        }
+    }
+    if (!fused_qkv) {   // rotary, cache write
+        STAGE(ctx, ST_ROPE, st);
+        launch_rope_store(w.big32, w.qb, kcw, vcw, dt, ctx->d_rope, pos0, n_seq, T, L_max, Hq, Hkv, dh, ctx->d_flags, st,
+                          ns_qkv, crows);
+    }
+    if (int rc = attn_stage(ctx, w, pos0, kc, vc, n_seq, T, L_max, st, page_meta, dense_pass, pv)) return rc;
     {   // quantise (o-proj input)
         STAGE(ctx, ST_QUANT_O, st);
         launch_fq_rows(w.o32, w.qb, dt, w.ra, qs & SOL_QS_O_IN, M, nq, st);
@@ -462,7 +542,8 @@ static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_i
         STAGE(ctx, ST_OPROJ, st);
         if (skinny) {
             ns_o = skinny_splits((int)M, d, nq);
-            launch_gemm_skinny(w.qb, nq, lw->wo, d, nullptr, 0, nullptr, 0, (int)M, nq, w.big32, ns_o, st);
+            if (!launch_gemm_skinny(w.qb, nq, lw->wo, d, nullptr, 0, nullptr, 0, (int)M, nq, w.big32, ns_o, st))
+                return fail(ctx, SOL_ERR_UNSUPPORTED, "skinny GEMM (output projection): unsupported shape");
         } else {
             fused_o = mfma && launch_gemm_resid_f32(w.qb, lw->wo, x_in, w.x2, M, d, nq, st);
             if (!fused_o) launch_gemm_generic(w.qb, dt, nq, lw->wo, dt, nq, w.big32, d, M, d, nq, st);
@@ -491,49 +572,7 @@ static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_i
             launch_fq_rows(w.hn32, w.h, dt, w.ra, false, M, d, st);
         }
     }
-    bool fused_gu = false;
-    int ns_gu = 1;
-    {   // gate / up (+ SiLU(gate)*up when fused)
-        STAGE(ctx, ST_GATEUP, st);
-        if (skinny) {
-            ns_gu = skinny_splits((int)M, 2 * dff, d);
-            launch_gemm_skinny(w.h, d, lw->w_gate, dff, lw->w_up, dff, nullptr, 0, (int)M, d, w.big32, ns_gu, st);
-        } else {
-            fused_gu = mfma && launch_gemm_gateup_silu(w.h, lw->w_gate, lw->w_up, w.a, M, dff, d, st);
-            if (!fused_gu) {
-                launch_gemm_generic(w.h, dt, d, lw->w_gate, dt, d, w.big32, 2 * (int64_t)dff, M, dff, d, st);
-                launch_gemm_generic(w.h, dt, d, lw->w_up, dt, d, w.big32 + dff, 2 * (int64_t)dff, M, dff, d, st);
-            }
-        }
-    }
-    if (!fused_gu) {   // SiLU(gate)*up
-        STAGE(ctx, ST_SILU, st);
-        launch_silu_mul(w.big32, w.a, dt, M, dff, st, ns_gu);
-    }
-    {   // magnitude pruning + quantise (down input), rows visited in bucket order
-        STAGE(ctx, ST_PRUNE, st);
-        if (g.prune_site == 0 || (qs & SOL_QS_DOWN_IN))      // (pruning elsewhere and no quantiser here: nothing to do)
-            launch_prune_fq(w.a, dt, w.ra, w.perm, qs & SOL_QS_DOWN_IN, M, dff, st, g.prune_site == 0);
-    }
-    bool fused_down = false;
-    int ns_down = 1;
-    const bool q_out = (qs & SOL_QS_MLP_OUT) != 0;   // the MLP output is quantised as a whole row before the residual add
-    {   // down projection (+ residual when fused)
-        STAGE(ctx, ST_DOWN, st);
-        if (skinny) {
-            ns_down = skinny_splits((int)M, d, dff);
-            launch_gemm_skinny(w.a, dff, lw->w_down, d, nullptr, 0, nullptr, 0, (int)M, dff, w.big32, ns_down, st);
-        } else {
-            fused_down = mfma && !q_out && launch_gemm_resid_out(w.a, lw->w_down, w.x2, x_out, M, d, dff, st);
-            if (!fused_down && !(mfma && launch_gemm_f32(w.a, lw->w_down, w.big32, d, M, d, dff, st)))
-                launch_gemm_generic(w.a, dt, dff, lw->w_down, dt, dff, w.big32, d, M, d, dff, st);
-        }
-    }
-    if (!fused_down) {   // residual
-        STAGE(ctx, ST_RESID, st);
-        if (q_out) launch_resid_out_fq(w.x2, w.big32, x_out, dt, w.ra, M, d, st, ns_down);
-        else launch_resid_out(w.x2, w.big32, x_out, dt, M, d, st, ns_down);
-    }
+    if (int rc = mlp_stage(ctx, lw, w, x_out, M, skinny, st)) return rc;
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(ctx, SOL_ERR_HIP, std::string("kernel launch: ") + hipGetErrorString(e));
     return SOL_OK;
@@ -873,9 +912,9 @@ static void carve_episode_as(Carver &c, const sol_model_cfg &g, int64_t B, int64
 // The in-place layout is taken when the tiled kernels cover the shape with two-segment addressing (that depends on
 // sizes and on the distances inside the workspace only, so sizing and running agree); otherwise every schedule
 // gets a copy of the prefix cache.
-static void carve_episode(Carver &c, const sol_model_cfg &g, int64_t B, int64_t K, int64_t P, int64_t T, EpisodeWs &w)
+static void carve_episode(Carver &c, const sol_model_cfg &g, int64_t B, int64_t K, int64_t P, int64_t T, EpisodeWs &w,
+                          bool copy_forced = false)
 {
-    static const bool copy_forced = [] { const char *e = getenv("SOL_EPISODE_COPY_PREFIX"); return e && e[0] == '1'; }();
     const bool plain = g.page_size == 1 && g.n_sink == 0 && g.n_window == 0;
     bool twoseg = !copy_forced && g.dtype == SOL_BF16 && (plain || g.page_size > 1) && T >= 16 && P % 64 == 0 &&
                   P + T <= 4096;
@@ -896,17 +935,27 @@ static void carve_episode(Carver &c, const sol_model_cfg &g, int64_t B, int64_t 
     carve_episode_as(c, g, B, K, P, T, twoseg, w);
 }
 
-extern "C" size_t sol_episode_workspace_bytes(const sol_model_cfg *cfg, int B, int K, int P, int T)
+static size_t episode_ws_bytes(const sol_model_cfg *cfg, int B, int K, int P, int T, bool copy_forced)
 {
     if (!cfg || B <= 0 || K <= 0 || P <= 0 || T <= 0) return 0;
     Carver c(nullptr);
-    EpisodeWs w; carve_episode(c, *cfg, B, K, P, T, w);
+    EpisodeWs w; carve_episode(c, *cfg, B, K, P, T, w, copy_forced);
     return c.off + 256;
 }
 
-extern "C" int sol_episode_loglik(sol_ctx *ctx, const sol_model_weights *mw, const int32_t *prefix_tokens,
-                                  const int32_t *tokens, const int32_t *targets, const int32_t *action_ids, int B, int K,
-                                  int P, int T, float *nll_out, void *workspace, size_t ws_bytes, void *stream)
+extern "C" size_t sol_episode_workspace_bytes(const sol_model_cfg *cfg, int B, int K, int P, int T)
+{
+    return episode_ws_bytes(cfg, B, K, P, T, false);
+}
+
+extern "C" size_t sol_test_episode_copies_workspace_bytes(const sol_model_cfg *cfg, int B, int K, int P, int T)
+{
+    return episode_ws_bytes(cfg, B, K, P, T, true);
+}
+
+static int episode_impl(sol_ctx *ctx, const sol_model_weights *mw, const int32_t *prefix_tokens,
+                        const int32_t *tokens, const int32_t *targets, const int32_t *action_ids, int B, int K,
+                        int P, int T, float *nll_out, void *workspace, size_t ws_bytes, void *stream, bool copy_forced)
 {
     if (!ctx) return SOL_ERR_INVALID_ARG;
     const sol_model_cfg &g = ctx->cfg;
@@ -922,12 +971,12 @@ extern "C" int sol_episode_loglik(sol_ctx *ctx, const sol_model_weights *mw, con
     if ((int64_t)P + T > g.max_positions) return fail(ctx, SOL_ERR_INVALID_ARG, "P + T exceeds cfg.max_positions");
     if ((g.head_dim * esize(g.dtype)) % 16) return fail(ctx, SOL_ERR_UNSUPPORTED, "head rows must be a multiple of 16 bytes");
     if ((int64_t)B * K * T == 0) return SOL_OK;
-    const size_t need = sol_episode_workspace_bytes(&g, B, K, P, T);
+    const size_t need = episode_ws_bytes(&g, B, K, P, T, copy_forced);
     if (!workspace || ws_bytes < need)
         return fail(ctx, SOL_ERR_WORKSPACE, "workspace too small: need " + std::to_string(need) + " bytes");
     hipStream_t st = (hipStream_t)stream;
     Carver c(workspace);
-    EpisodeWs w; carve_episode(c, g, B, K, P, T, w);
+    EpisodeWs w; carve_episode(c, g, B, K, P, T, w, copy_forced);
     const int N = B * K, L = P + T;
     const int64_t Mp = (int64_t)B * P, M = (int64_t)N * T;
     {   // plans: the prefix runs dense, the suffix under its schedules
@@ -968,9 +1017,82 @@ extern "C" int sol_episode_loglik(sol_ctx *ctx, const sol_model_weights *mw, con
     return nll_impl(ctx, mw, cur, M, w.st, targets, K, T, true, nll_out, st);
 }
 
+extern "C" int sol_episode_loglik(sol_ctx *ctx, const sol_model_weights *mw, const int32_t *prefix_tokens,
+                                  const int32_t *tokens, const int32_t *targets, const int32_t *action_ids, int B, int K,
+                                  int P, int T, float *nll_out, void *workspace, size_t ws_bytes, void *stream)
+{
+    return episode_impl(ctx, mw, prefix_tokens, tokens, targets, action_ids, B, K, P, T, nll_out, workspace, ws_bytes, stream,
+                        false);
+}
+
+extern "C" int sol_test_episode_loglik_copies(sol_ctx *ctx, const sol_model_weights *mw, const int32_t *prefix_tokens,
+                                              const int32_t *tokens, const int32_t *targets, const int32_t *action_ids,
+                                              int B, int K, int P, int T, float *nll_out, void *workspace, size_t ws_bytes,
+                                              void *stream)
+{
+    return episode_impl(ctx, mw, prefix_tokens, tokens, targets, action_ids, B, K, P, T, nll_out, workspace, ws_bytes, stream,
+                        true);
+}
+
 // ------------------------------------------------------------------------------------------------
 // unit hooks
 // ------------------------------------------------------------------------------------------------
+// Arguments every stage hook shares with sol_layer_forward.
+static int check_stage_args(sol_ctx *ctx, int n_seq, int T, int L_max, const void *workspace, size_t ws_bytes)
+{
+    if (n_seq < 0 || T < 0 || L_max <= 0) return fail(ctx, SOL_ERR_INVALID_ARG, "negative size");
+    if (L_max > ctx->cfg.max_positions) return fail(ctx, SOL_ERR_INVALID_ARG, "L_max exceeds cfg.max_positions");
+    if (T > L_max) return fail(ctx, SOL_ERR_CACHE_OVERFLOW, "T tokens cannot fit a cache of L_max positions");
+    const size_t need = sol_workspace_bytes(&ctx->cfg, SOL_OP_LAYER_FORWARD, n_seq, T, L_max);
+    if (!workspace || ws_bytes < need)
+        return fail(ctx, SOL_ERR_WORKSPACE, "workspace too small: need " + std::to_string(need) + " bytes");
+    return SOL_OK;
+}
+
+extern "C" int sol_test_attention_stage(sol_ctx *ctx, const void *q, const int32_t *action_ids, const int32_t *pos0,
+                                        void *k_cache, void *v_cache, int n_seq, int T, int L_max, float *o_out,
+                                        void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!ctx) return SOL_ERR_INVALID_ARG;
+    if (n_seq == 0 || T == 0) return SOL_OK;
+    if (!q || !action_ids || !k_cache || !v_cache || !o_out) return fail(ctx, SOL_ERR_INVALID_ARG, "a data pointer is NULL");
+    if (int rc = check_stage_args(ctx, n_seq, T, L_max, workspace, ws_bytes)) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    Carver c(workspace);
+    LayerWs lw; carve_layer(c, ctx->cfg, n_seq, T, L_max, lw);
+    prepare_actions(ctx, action_ids, (int64_t)n_seq * T, lw, st);
+    if (T == 1 && pos0) launch_seq_order(pos0, n_seq, lw.seq_order, st);
+    lw.qb = const_cast<void *>(q);             // the stage only reads the queries
+    lw.o32 = o_out;
+    if (int rc = attn_stage(ctx, lw, pos0, k_cache, v_cache, n_seq, T, L_max, st, nullptr, false, nullptr)) return rc;
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(ctx, SOL_ERR_HIP, std::string("kernel launch: ") + hipGetErrorString(e));
+    return SOL_OK;
+}
+
+extern "C" int sol_test_mlp_stage(sol_ctx *ctx, const sol_layer_weights *w, const void *h2, const float *x2,
+                                  const int32_t *action_ids, int n_seq, int T, void *a_out, void *x_out,
+                                  void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!ctx) return SOL_ERR_INVALID_ARG;
+    if (n_seq == 0 || T == 0) return SOL_OK;
+    if (!w || !w->w_gate || !w->w_up || !w->w_down) return fail(ctx, SOL_ERR_INVALID_ARG, "an MLP weight pointer is NULL");
+    if (!h2 || !x2 || !action_ids || !x_out) return fail(ctx, SOL_ERR_INVALID_ARG, "a data pointer is NULL");
+    if (int rc = check_stage_args(ctx, n_seq, T, T > 0 ? T : 1, workspace, ws_bytes)) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t M = (int64_t)n_seq * T;
+    Carver c(workspace);
+    LayerWs lw; carve_layer(c, ctx->cfg, n_seq, T, T, lw);
+    prepare_actions(ctx, action_ids, M, lw, st);
+    lw.h = const_cast<void *>(h2);             // read only from here on
+    lw.x2 = const_cast<float *>(x2);
+    if (a_out) lw.a = a_out;
+    if (int rc = mlp_stage(ctx, w, lw, x_out, M, use_skinny(ctx->cfg, M), st)) return rc;
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(ctx, SOL_ERR_HIP, std::string("kernel launch: ") + hipGetErrorString(e));
+    return SOL_OK;
+}
+
 static int launch_status()
 {
     hipError_t e = hipGetLastError();

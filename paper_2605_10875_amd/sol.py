@@ -26,7 +26,8 @@ EXPORTS = ("sol_validate_config", "sol_create", "sol_destroy", "sol_last_error",
            "sol_reward_advantages", "sol_episode_workspace_bytes", "sol_episode_loglik",
            "sol_profile_enable", "sol_profile_read",
            "sol_test_topk_select", "sol_test_prune_mask", "sol_test_prune_quant", "sol_test_quant_codes",
-           "sol_test_gemm", "sol_test_attn_threshold")
+           "sol_test_gemm", "sol_test_attn_threshold", "sol_test_attention_stage", "sol_test_mlp_stage",
+           "sol_test_episode_copies_workspace_bytes", "sol_test_episode_loglik_copies")
 
 
 class RewardCfg(C.Structure):
@@ -73,11 +74,16 @@ def lib_path():
 
 
 def lib():
-    """Loads libsol.so, building it first only if it has never been built."""
+    """Loads libsol.so, building it first only if it has never been built. A library older than its sources is
+    still loaded (a GPU machine runs what was built beforehand) but reported, so that stale results are not mistaken
+    for current ones."""
     global _lib
     if _lib is None:
         if not os.path.exists(_build.LIB):
             _build.build()
+        elif _build.is_stale():
+            import warnings
+            warnings.warn("libsol.so is older than its sources: run paper_2605_10875_amd/build.py", RuntimeWarning)
         L = C.CDLL(_build.LIB)
         L.sol_last_error.restype = C.c_char_p
         L.sol_last_error.argtypes = [C.c_void_p]
@@ -109,6 +115,13 @@ def lib():
         L.sol_episode_loglik.argtypes = [C.c_void_p, C.POINTER(ModelWeights), C.c_void_p, C.c_void_p, C.c_void_p,
                                          C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
                                          C.c_size_t, C.c_void_p]
+        L.sol_test_episode_copies_workspace_bytes.restype = C.c_size_t
+        L.sol_test_episode_copies_workspace_bytes.argtypes = L.sol_episode_workspace_bytes.argtypes
+        L.sol_test_episode_loglik_copies.argtypes = L.sol_episode_loglik.argtypes
+        L.sol_test_attention_stage.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                               C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.sol_test_mlp_stage.argtypes = [C.c_void_p, C.POINTER(LayerWeights), C.c_void_p, C.c_void_p, C.c_void_p,
+                                         C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.sol_page_meta_bytes.restype = C.c_size_t
         L.sol_page_meta_bytes.argtypes = [C.POINTER(ModelCfg), C.c_int, C.c_int]
         L.sol_page_meta_build.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
@@ -251,6 +264,32 @@ class Sol:
         self._check(rc)
         return x_out
 
+    def test_attention_stage(self, q, action_ids, k_cache, v_cache, pos0=None, stream=None):
+        """Stage hook: q [n_seq][T][Hq*dh] (storage dtype, after the rotary embedding) against caches that already
+        hold positions [0, pos0 + T). Returns the attention output float32 [n_seq][T][Hq*dh]."""
+        n_seq, T, _ = q.shape
+        L_max = k_cache.shape[2]
+        assert q.is_contiguous() and q.dtype == self.tdtype and k_cache.dtype == self.tdtype
+        o = torch.empty(q.shape, dtype=torch.float32, device="cuda")
+        ws = self.workspace(OP_LAYER_FORWARD, n_seq, T, L_max)
+        self._check(self.L.sol_test_attention_stage(self.handle, _ptr(q), _ptr(_i32(action_ids)), _ptr(_i32(pos0)),
+                                                    _ptr(k_cache), _ptr(v_cache), n_seq, T, L_max, _ptr(o), _ptr(ws),
+                                                    ws.numel(), _stream(stream)))
+        return o
+
+    def test_mlp_stage(self, w, h2, x2, action_ids, stream=None):
+        """Stage hook: h2 [n_seq][T][d] (storage dtype, the MLP input as the projections read it), x2 float32
+        [n_seq][T][d] (residual after attention). Returns (a [n_seq][T][d_ff], x_out [n_seq][T][d]), storage dtype."""
+        n_seq, T, d = h2.shape
+        assert h2.is_contiguous() and h2.dtype == self.tdtype and x2.dtype == torch.float32 and x2.is_contiguous()
+        a = torch.empty((n_seq, T, self.cfg.d_ff), dtype=self.tdtype, device="cuda")
+        out = torch.empty_like(h2)
+        ws = self.workspace(OP_LAYER_FORWARD, n_seq, T, T)
+        ls = self._layer_struct(w)
+        self._check(self.L.sol_test_mlp_stage(self.handle, C.byref(ls), _ptr(h2), _ptr(x2), _ptr(_i32(action_ids)),
+                                              n_seq, T, _ptr(a), _ptr(out), _ptr(ws), ws.numel(), _stream(stream)))
+        return a, out
+
     def page_meta_build(self, k_cache, cache_len, stream=None):
         """Page metadata (channel-wise maxima and minima per page) of one layer's key cache for keys
         [0, cache_len[s]); returns the new buffer [n_seq][Hkv][pages][2 * head_dim]."""
@@ -309,19 +348,22 @@ class Sol:
         return x_out
 
     def episode_loglik(self, layers, head, prefix_tokens, tokens, targets, action_ids, nll_out=None, workspace=None,
-                       stream=None):
+                       stream=None, force_copies=False):
         """prefix_tokens int32 [B][P]; tokens/targets int32 [B][T]; action_ids int32 [B][K][T]: dense prefill once per
-        input, then K schedules of T controlled steps on it. Returns nll float32 [B][K][T] (nats)."""
+        input, then K schedules of T controlled steps on it. Returns nll float32 [B][K][T] (nats).
+        force_copies: the test hook that gives every schedule its own copy of the prefix cache."""
         B, K, T = action_ids.shape
         P = prefix_tokens.shape[1]
         mw, keep = self._model_struct(layers, head)
         if nll_out is None:
             nll_out = torch.empty((B, K, T), dtype=torch.float32, device="cuda")
-        need = int(self.L.sol_episode_workspace_bytes(C.byref(self.cfg), B, K, P, T))
+        size_fn = self.L.sol_test_episode_copies_workspace_bytes if force_copies else self.L.sol_episode_workspace_bytes
+        run_fn = self.L.sol_test_episode_loglik_copies if force_copies else self.L.sol_episode_loglik
+        need = int(size_fn(C.byref(self.cfg), B, K, P, T))
         ws = workspace if workspace is not None else torch.empty(need, dtype=torch.uint8, device="cuda")
-        rc = self.L.sol_episode_loglik(self.handle, C.byref(mw), _ptr(_i32(prefix_tokens)), _ptr(_i32(tokens)),
-                                       _ptr(_i32(targets)), _ptr(_i32(action_ids)), B, K, P, T, _ptr(nll_out), _ptr(ws),
-                                       ws.numel(), _stream(stream))
+        rc = run_fn(self.handle, C.byref(mw), _ptr(_i32(prefix_tokens)), _ptr(_i32(tokens)),
+                    _ptr(_i32(targets)), _ptr(_i32(action_ids)), B, K, P, T, _ptr(nll_out), _ptr(ws),
+                    ws.numel(), _stream(stream))
         del keep
         self._check(rc)
         return nll_out

@@ -94,39 +94,24 @@ def test_identical_schedules_give_identical_likelihoods():
                                       ("dict(sol.PAPER_PRESET, page_size=64, n_sink=0)", 1024)])
 def test_reading_the_prefix_in_place_equals_working_on_copies(preset, P):
     """The two layouts of the episode pass run the same arithmetic on the same values: bit-identical likelihoods, under
-    the plain top-k rule and under the page rule with sink / window keys.
-    The copying layout is forced through the library's environment switch in a child process."""
-    import os
-    import subprocess
-    import sys
-    import tempfile
-    code = (
-        "import sys, numpy as np, torch\n"
-        "sys.path[:0] = [%r, %r]\n"
-        "from paper_2605_10875_amd import sol, synth\n"
-        "from gpu_util import dev, dev_weights, host\n"
-        "shape = synth.ModelShape(d_model=256, n_q_heads=8, n_kv_heads=2, head_dim=64, d_ff=768, n_layers=2, vocab=1024)\n"
-        "table = synth.action_table((0.125, 0.5, 1.0), (0.0, 0.75), (6, 16))\n"
-        "layers = [dev_weights(synth.layer_weights(shape, 8400 + l, bf16=True), sol.BF16) for l in range(2)]\n"
-        "head = dev_weights(synth.head_weights(shape, 8410, bf16=True), sol.BF16)\n"
-        "rng = np.random.default_rng(8411)\n"
-        "prefix = rng.integers(0, shape.vocab, (3, %d)).astype(np.int32)\n"
-        "tokens, targets = synth.tokens_and_targets(3, 24, shape.vocab, 8412)\n"
-        "ids = synth.iid_actions(len(table), (3, 5, 24), 8413)\n"
-        "ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=%d, **%s)\n"
-        "nll = host(ctx.episode_loglik(layers, head, dev(prefix), dev(tokens), dev(targets), dev(ids)))\n"
-        "assert ctx.device_status() == sol.OK\n"
-        "np.save(sys.argv[1], nll)\n"
-        "np.save(sys.argv[1] + '.ws.npy', np.int64(ctx.L.sol_episode_workspace_bytes(ctx.cfg, 3, 5, prefix.shape[1], 24)))\n"
-    ) % (os.path.dirname(os.path.dirname(os.path.abspath(__file__))), os.path.dirname(os.path.abspath(__file__)), P, P + 24,
-         preset)
+    the plain top-k rule and under the page rule with sink / window keys. The copying layout is forced through the
+    library's test hook."""
+    preset = eval(preset, {"sol": sol, "dict": dict})
+    shape = synth.ModelShape(d_model=256, n_q_heads=8, n_kv_heads=2, head_dim=64, d_ff=768, n_layers=2, vocab=1024)
+    table = synth.action_table((0.125, 0.5, 1.0), (0.0, 0.75), (6, 16))
+    layers = [dev_weights(synth.layer_weights(shape, 8400 + l, bf16=True), sol.BF16) for l in range(2)]
+    head = dev_weights(synth.head_weights(shape, 8410, bf16=True), sol.BF16)
+    rng = np.random.default_rng(8411)
+    prefix = rng.integers(0, shape.vocab, (3, P)).astype(np.int32)
+    tokens, targets = synth.tokens_and_targets(3, 24, shape.vocab, 8412)
+    ids = synth.iid_actions(len(table), (3, 5, 24), 8413)
+    ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=P + 24, **preset)
     outs, sizes = [], []
-    with tempfile.TemporaryDirectory() as td:
-        for flag in ("0", "1"):
-            path = os.path.join(td, f"nll{flag}.npy")
-            env = dict(os.environ, SOL_EPISODE_COPY_PREFIX=flag)
-            subprocess.run([sys.executable, "-c", code, path], check=True, env=env, timeout=300)
-            outs.append(np.load(path))
-            sizes.append(int(np.load(path + ".ws.npy")))
+    for copies in (False, True):
+        outs.append(host(ctx.episode_loglik(layers, head, dev(prefix), dev(tokens), dev(targets), dev(ids), force_copies=copies)))
+        assert ctx.device_status() == sol.OK
+        fn = ctx.L.sol_test_episode_copies_workspace_bytes if copies else ctx.L.sol_episode_workspace_bytes
+        sizes.append(int(fn(ctx.cfg, 3, 5, P, 24)))
+    ctx.close()
     assert np.isfinite(outs[0]).all() and np.array_equal(outs[0], outs[1])
     assert sizes[0] < sizes[1], sizes          # the in-place layout was the one that ran: no per-schedule prefix copies

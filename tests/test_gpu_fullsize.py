@@ -10,21 +10,9 @@ import torch
 import oracle
 from paper_2605_10875_amd import sol, synth
 
-from gpu_util import check_rows, dev, dev_weights, host
+from gpu_util import check_by_bit_class, check_rows, dev, dev_weights, host
 
 pytestmark = pytest.mark.gpu
-
-
-def _check_by_bits(out, ref, ids, table, what, pages=False):
-    bits = np.array([a[4] for a in table])[ids]
-    for b in sorted(set(bits.reshape(-1).tolist())):
-        if b >= 16:     # selection / pruning flips only: 2e-2, with a per-cent of rows allowed up to 5e-2 (a swapped
-            # key weighs ~1/k of a short row; 1 row in 256 was seen at 2.06e-2 at this size); a swapped page of 16
-            # keys weighs more: 5 % of the rows up to 5e-2 under the page rule
-            check_rows(out[bits == b], ref[bits == b], 2e-2, 5e-2, 0.05 if pages else 0.01, f"{what}: rows of {b}-bit actions")
-        else:
-            cap = max(2e-2, 6.0 / 2 ** (b - 1))
-            check_rows(out[bits == b], ref[bits == b], cap, cap, 0.0, f"{what}: rows of {b}-bit actions")
 
 
 @pytest.mark.parametrize("preset", [None, sol.PAPER_PRESET], ids=["exact-topk", "paper-configuration"])
@@ -47,9 +35,12 @@ def test_c2_full_size_layer_sampled_sequences(preset):
         vr = kr.copy()
         ref, _ = oracle.layer_forward(oracle.make_cfg(shape, quant_sites=qs, act_bf16=True, **opts), oracle.make_table(table),
                                       w, x[s:s + 1], ids[s:s + 1], kr, vr)
+        k32 = np.zeros_like(kr)
+        ref32, _ = oracle.layer_forward(oracle.make_cfg(shape, quant_sites=qs, **opts), oracle.make_table(table),
+                                        w, x[s:s + 1], ids[s:s + 1], k32, k32.copy())
         check_rows(host(kc[s]).transpose(1, 0, 2), kr[0].transpose(1, 0, 2), 2e-2, 0.3, 0.02, f"seq {s} K cache")
         check_rows(host(vc[s]).transpose(1, 0, 2), vr[0].transpose(1, 0, 2), 2e-2, 0.3, 0.02, f"seq {s} V cache")
-        _check_by_bits(host(out[s]), ref[0], ids[s], table, f"seq {s}", pages=bool(preset))
+        check_by_bit_class(host(out[s]), ref[0], ref32[0], ids[s], table, f"seq {s}", full_size=True, pages=bool(preset))
     # a sequence's result does not depend on the batch around it: rerun sequence 17 alone, compare bits
     solo_k = torch.zeros((1, shape.n_kv_heads, T, shape.head_dim), dtype=torch.bfloat16, device="cuda")
     solo = ctx.layer_forward(dev_weights(w, sol.BF16), dev(x[17:18], sol.BF16), dev(ids[17:18]), solo_k,
@@ -80,28 +71,45 @@ def test_c4_full_size_decode_sampled_sequence(preset):
     cache_len = rng.integers(L // 2, L + 1, B).astype(np.int32)
     cache_len[5] = L
     targets = rng.integers(0, shape.vocab, B).astype(np.int32)
-    s = 5
-    k_host = [k[s:s + 1].float().cpu().numpy().copy() for k in kcs]
-    v_host = [v[s:s + 1].float().cpu().numpy().copy() for v in vcs]
+    bits_all = np.array([t[4] for t in table])[ids]
+    sample = sorted({int(np.flatnonzero(bits_all == b)[0]) for b in sorted(set(bits_all.tolist()))} | {5})
+    k_host = [k[sample].float().cpu().numpy().copy() for k in kcs]
+    v_host = [v[sample].float().cpu().numpy().copy() for v in vcs]
     ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=L_max, quant_sites=qs, **opts)
     metas = [ctx.page_meta_build(k, dev(cache_len)) for k in kcs] if preset else None
     hid, nll = ctx.decode_step([dev_weights(w, sol.BF16) for w in layers], dev_weights(head, sol.BF16), dev(ids),
                                dev(cache_len), kcs, vcs, x_in=dev(x, sol.BF16), targets=dev(targets), page_meta=metas)
     assert ctx.device_status() == sol.OK
-    # oracle with one quantising-free copy of the action is not needed: compare layer 0's committed K/V
-    # exactly-ish and the final hidden state with the bit-width bound of the sequence's action
+    # the sampled sequences (one per bit-width class of the action table, plus a full-length one) by the oracle in
+    # both storage modes; the distance between the two modes is the yardstick for quantising sequences
+    k32, v32 = [k.copy() for k in k_host], [v.copy() for v in v_host]
     h_ref, nll_ref = oracle.decode_step(oracle.make_cfg(shape, quant_sites=qs, act_bf16=True, **opts), oracle.make_table(table), layers,
-                                        x[s:s + 1], ids[s:s + 1], cache_len[s:s + 1], k_host, v_host,
-                                        head["w_final_norm"], head["lm_head"], targets[s:s + 1])
-    p = int(cache_len[s])
-    check_rows(host(kcs[0][s, :, p]), k_host[0][0, :, p], 2e-2, 2e-2, 0.0, "layer-0 K row of the new token")
-    check_rows(host(vcs[0][s, :, p]), v_host[0][0, :, p], 2e-2, 2e-2, 0.0, "layer-0 V row of the new token")
-    bits = table[ids[s]][4]
-    cap = 2e-2 if bits >= 16 else max(2e-2, 6.0 / 2 ** (bits - 1))
-    err = float(np.abs(host(hid)[s] - h_ref[0]).max() / np.abs(h_ref).max())
-    print(f"decode seq {s}: action {table[ids[s]]}, hidden max-rel {err:.3e} (cap {cap:.2e}), "
-          f"nll gpu {float(nll[s]):.4f} oracle {float(nll_ref[0]):.4f}")
-    assert err < 16 * cap            # 16 layers: every layer may flip codes of its own
+                                        x[sample], ids[sample], cache_len[sample], k_host, v_host,
+                                        head["w_final_norm"], head["lm_head"], targets[sample])
+    h32, nll32 = oracle.decode_step(oracle.make_cfg(shape, quant_sites=qs, **opts), oracle.make_table(table), layers,
+                                    x[sample], ids[sample], cache_len[sample], k32, v32,
+                                    head["w_final_norm"], head["lm_head"], targets[sample])
+    scale = np.abs(h_ref).max()
+    e_gpu = np.abs(host(hid)[sample] - h_ref).max(axis=1) / scale
+    e_orc = np.abs(h32 - h_ref).max(axis=1) / scale
+    n_gpu, n_orc = np.abs(host(nll)[sample] - nll_ref), np.abs(nll32 - nll_ref)
+    bits = bits_all[sample]
+    for i, s in enumerate(sample):
+        p = int(cache_len[s])
+        check_rows(host(kcs[0][s, :, p]), k_host[0][i, :, p], 2e-2, 2e-2, 0.0, f"seq {s}: layer-0 K row of the new token")
+        check_rows(host(vcs[0][s, :, p]), v_host[0][i, :, p], 2e-2, 2e-2, 0.0, f"seq {s}: layer-0 V row of the new token")
+        print(f"decode seq {s}: action {table[ids[s]]}, hidden gpu-vs-bf16-store {e_gpu[i]:.3e} (oracles {e_orc[i]:.3e}), "
+              f"nll err {n_gpu[i]:.2e} (oracles {n_orc[i]:.2e})")
+    quiet = bits >= 16
+    # sequences that never quantise: the contract (2e-2 on the hidden state, 1e-2 nats), or, where the oracle's own two
+    # storage modes are further apart than that after this many layers, no further from the bf16-store oracle than
+    # the fp32-store oracle is
+    assert (e_gpu[quiet] < np.maximum(2e-2, 1.25 * e_orc[quiet] + 5e-3)).all()
+    assert (n_gpu[quiet] < np.maximum(1e-2, 1.25 * n_orc[quiet] + 2e-3)).all()
+    for i in np.flatnonzero(~quiet):
+        assert e_gpu[i] < max(2e-2, 6.0 / 2 ** (bits[i] - 1)) * shape.n_layers ** 0.5
+    assert e_gpu[~quiet].mean() <= 1.25 * e_orc[~quiet].mean() + 2e-3
+    assert n_gpu[~quiet].mean() <= 1.25 * n_orc[~quiet].mean() + 2e-3
     assert np.isfinite(host(nll)).all() and np.isfinite(host(hid)).all()
     ctx.close()
 
@@ -127,3 +135,168 @@ def test_long_rows_of_the_tiled_attention(T):
                                   kr.copy())
     check_rows(out, ref, 2e-2, 2e-2, 0.0, f"T={T}, selection and pruning only", median=1e-2)
     ctx.close()
+
+
+def _say(capsys, msg):
+    """progress line past pytest's capture: the oracle legs below run for a minute or more"""
+    with capsys.disabled():
+        print(msg, flush=True)
+
+
+def test_c5_full_size_layer_sampled_sequence(capsys):
+    """Llama-3.1-8B layer, 8 sequences x 4096 tokens (bench.py's c5 step: head_dim 128, rows of up to 4096 keys take
+    the 8-row variant of the threshold kernel, d_ff 14336 the seven-chunk prune kernel); sequence 3 against the
+    bf16-store oracle. The fp32-store leg is left out here (the oracle needs about half a minute per mode and
+    sequence at this size): quantising rows are held to the cap only, non-quantising rows to the contract."""
+    shape, table, n_seq, T, seed = synth.LLAMA_8B, synth.TABLE_C2, 8, 4096, 1234
+    w = synth.layer_weights(shape, seed, bf16=True)
+    x = synth.hidden_states(n_seq, T, shape.d_model, seed + 1, bf16=True)
+    ids = synth.iid_actions(len(table), (n_seq, T), seed + 2)
+    ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=T)
+    kc = torch.zeros((n_seq, shape.n_kv_heads, T, shape.head_dim), dtype=torch.bfloat16, device="cuda")
+    vc = torch.zeros_like(kc)
+    out = ctx.layer_forward(dev_weights(w, sol.BF16), dev(x, sol.BF16), dev(ids), kc, vc)
+    assert ctx.device_status() == sol.OK
+    ctx.close()
+    s = 3
+    _say(capsys, f"\n[c5] GPU layer done; oracle on sequence {s} ({T} tokens, {oracle.num_threads()} threads) ...")
+    kr = np.zeros((1, shape.n_kv_heads, T, shape.head_dim), np.float32)
+    vr = kr.copy()
+    ref, _ = oracle.layer_forward(oracle.make_cfg(shape, act_bf16=True), oracle.make_table(table), w, x[s:s + 1],
+                                  ids[s:s + 1], kr, vr)
+    _say(capsys, "[c5] oracle done")
+    check_rows(host(kc[s]).transpose(1, 0, 2), kr[0].transpose(1, 0, 2), 2e-2, 0.3, 0.02, f"seq {s} K cache")
+    check_rows(host(vc[s]).transpose(1, 0, 2), vr[0].transpose(1, 0, 2), 2e-2, 0.3, 0.02, f"seq {s} V cache")
+    check_by_bit_class(host(out[s]), ref[0], None, ids[s], table, f"seq {s}", full_size=True)
+
+
+def test_c5_decode_full_size_sampled_sequences():
+    """Llama-3.1-8B decode step, one layer, 32 sequences x 8192-token caches (bench.py's c5d: head_dim 128 in the
+    decode attention kernel at its longest cache); one sequence per bit-width class plus a full-length one."""
+    shape = dataclasses.replace(synth.LLAMA_8B, n_layers=1, vocab=2048)
+    table, B, L, seed = synth.TABLE_C2, 32, 8192, 4321
+    L_max = L + 8
+    gen = torch.Generator(device="cuda").manual_seed(seed)
+    layers = [synth.layer_weights(shape, seed, bf16=True)]
+    head = synth.head_weights(shape, seed + 100, bf16=True)
+    kcs = [torch.randn((B, shape.n_kv_heads, L_max, shape.head_dim), generator=gen, device="cuda").to(torch.bfloat16)]
+    vcs = [torch.randn((B, shape.n_kv_heads, L_max, shape.head_dim), generator=gen, device="cuda").to(torch.bfloat16)]
+    ids = synth.iid_actions(len(table), (B,), seed + 2)
+    x = synth.hidden_states(1, B, shape.d_model, seed + 3, bf16=True)[0]
+    rng = np.random.default_rng(seed + 4)
+    cache_len = rng.integers(L // 2, L + 1, B).astype(np.int32)
+    cache_len[5] = L
+    targets = rng.integers(0, shape.vocab, B).astype(np.int32)
+    bits_all = np.array([t[4] for t in table])[ids]
+    sample = sorted({int(np.flatnonzero(bits_all == b)[0]) for b in sorted(set(bits_all.tolist()))} | {5})
+    k_host = [kcs[0][sample].float().cpu().numpy().copy()]
+    v_host = [vcs[0][sample].float().cpu().numpy().copy()]
+    k32, v32 = [k_host[0].copy()], [v_host[0].copy()]
+    ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=L_max)
+    hid, nll = ctx.decode_step([dev_weights(layers[0], sol.BF16)], dev_weights(head, sol.BF16), dev(ids), dev(cache_len),
+                               kcs, vcs, x_in=dev(x, sol.BF16), targets=dev(targets))
+    assert ctx.device_status() == sol.OK
+    ctx.close()
+    h_ref, nll_ref = oracle.decode_step(oracle.make_cfg(shape, act_bf16=True), oracle.make_table(table), layers, x[sample],
+                                        ids[sample], cache_len[sample], k_host, v_host, head["w_final_norm"],
+                                        head["lm_head"], targets[sample])
+    h32, nll32 = oracle.decode_step(oracle.make_cfg(shape), oracle.make_table(table), layers, x[sample], ids[sample],
+                                    cache_len[sample], k32, v32, head["w_final_norm"], head["lm_head"], targets[sample])
+    scale = np.abs(h_ref).max()
+    e_gpu = np.abs(host(hid)[sample] - h_ref).max(axis=1) / scale
+    e_orc = np.abs(h32 - h_ref).max(axis=1) / scale
+    n_gpu, n_orc = np.abs(host(nll)[sample] - nll_ref), np.abs(nll32 - nll_ref)
+    bits = bits_all[sample]
+    for i, s in enumerate(sample):
+        p = int(cache_len[s])
+        check_rows(host(kcs[0][s, :, p]), k_host[0][i, :, p], 2e-2, 2e-2, 0.0, f"seq {s}: K row of the new token")
+        check_rows(host(vcs[0][s, :, p]), v_host[0][i, :, p], 2e-2, 2e-2, 0.0, f"seq {s}: V row of the new token")
+        print(f"decode seq {s}: action {table[ids[s]]}, hidden gpu-vs-bf16-store {e_gpu[i]:.3e} (oracles {e_orc[i]:.3e}), "
+              f"nll err {n_gpu[i]:.2e} (oracles {n_orc[i]:.2e})")
+    quiet = bits >= 16
+    # sequences that never quantise: the contract (2e-2 on the hidden state, 1e-2 nats), or, where the oracle's own two
+    # storage modes are further apart than that after this many layers, no further from the bf16-store oracle than
+    # the fp32-store oracle is
+    assert (e_gpu[quiet] < np.maximum(2e-2, 1.25 * e_orc[quiet] + 5e-3)).all()
+    assert (n_gpu[quiet] < np.maximum(1e-2, 1.25 * n_orc[quiet] + 2e-3)).all()
+    for i in np.flatnonzero(~quiet):
+        assert e_gpu[i] < max(2e-2, 6.0 / 2 ** (bits[i] - 1))
+    assert e_gpu[~quiet].mean() <= 1.25 * e_orc[~quiet].mean() + 2e-3
+    assert n_gpu[~quiet].mean() <= 1.25 * n_orc[~quiet].mean() + 2e-3
+
+
+def test_lm_head_nll_at_the_full_vocabulary():
+    """The fused LM head + NLL (per-tile maxima and sums of exponentials, logits never written) at the 501 column
+    tiles of the 128 256-token vocabulary, on a model small enough for the oracle to evaluate every row."""
+    shape = synth.ModelShape(d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=64, d_ff=512, n_layers=1, vocab=128256)
+    table = NOQUANT
+    layers = [synth.layer_weights(shape, 7100, bf16=True, std=0.05)]
+    head = synth.head_weights(shape, 7101, bf16=True, std=0.05)
+    B, G, T = 2, 2, 37
+    tokens, targets = synth.tokens_and_targets(B, T, shape.vocab, 7102)
+    targets[0, :4] = [0, shape.vocab - 1, 255, 256]                 # first / last entry, both sides of a tile edge
+    ids = synth.iid_actions(len(table), (B, G, T), 7103)
+    ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=T)
+    nll = host(ctx.schedule_loglik([dev_weights(layers[0], sol.BF16)], dev_weights(head, sol.BF16), dev(tokens),
+                                   dev(targets), dev(ids)))
+    assert ctx.device_status() == sol.OK
+    ctx.close()
+    ref = oracle.schedule_loglik(oracle.make_cfg(shape, act_bf16=True), oracle.make_table(table), head["embed"], layers,
+                                 head["w_final_norm"], head["lm_head"], tokens, targets, ids)
+    err = np.abs(nll - ref)
+    print(f"NLL at vocab {shape.vocab}: |gpu - oracle| median {np.median(err):.2e} max {err.max():.2e}; nll range "
+          f"{ref.min():.3f}..{ref.max():.3f}")
+    assert err.max() < 1e-2 and np.median(err) < 2e-3
+
+
+def test_c3_full_size_stack_sampled_schedules(capsys):
+    """Llama-3.2-1B stack, 16 layers + LM head + NLL, 2 inputs x 8 schedules x 2048 tokens, bursty Markov schedules
+    (bench.py's c3 step, one sol_schedule_loglik call).
+
+    Sixteen random-init layers amplify every difference: a 4-bit row of ONE layer already differs by ~10 % between the
+    oracle's own two storage modes (gpu_util.check_by_bit_class), and even the all-dense stack turns the bf16
+    rounding of the handed-over tensors into ~1e-2 nats at the output. A quantising schedule can therefore not be
+    compared token by token at this depth, and the contract of 1e-2 nats is replaced by the yardstick of the layer
+    tests: no further from the bf16-store oracle than the fp32-store oracle is. Two schedules of input 0 are
+    replaced by ones whose comparison is meaningful, and the oracle evaluates their first 512 positions (causality:
+    they do not depend on later ones) through all 16 layers and the 128 256-way head, in both storage modes:
+      schedule 0: the dense action on those positions (the Markov schedule afterwards);
+      schedule 1: a Markov schedule over the non-quantising actions only (key selection and pruning in every layer).
+    Schedule 7 of input 1 repeats schedule 5: identical schedules, identical likelihood bits at full size."""
+    shape = dataclasses.replace(synth.LLAMA_1B, n_layers=16, vocab=128256)
+    table, B, G, T, seed = synth.TABLE_C2, 2, 8, 2048, 1234
+    T_ref = 512
+    layers = [synth.layer_weights(shape, seed + l, bf16=True) for l in range(shape.n_layers)]
+    head = synth.head_weights(shape, seed + 100, bf16=True)
+    tokens, targets = synth.tokens_and_targets(B, T, shape.vocab, seed + 1)
+    ids = synth.markov_actions(len(table), B * G, T, seed + 2).reshape(B, G, T)
+    quiet_ids = np.array([i for i, a in enumerate(table) if a[4] >= 16], np.int32)
+    ids[0, 0, :T_ref] = table.index(synth.DENSE_ACTION)
+    ids[0, 1] = quiet_ids[synth.markov_actions(len(quiet_ids), 1, T, seed + 3)[0]]
+    ids[1, 7] = ids[1, 5]
+    ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=T)
+    lw = [dev_weights(w, sol.BF16) for w in layers]
+    nll = host(ctx.schedule_loglik(lw, dev_weights(head, sol.BF16), dev(tokens), dev(targets), dev(ids)))
+    assert ctx.device_status() == sol.OK
+    ctx.close()
+    del lw
+    torch.cuda.empty_cache()
+    assert np.isfinite(nll).all() and np.array_equal(nll[1, 7], nll[1, 5])
+    ref = {}
+    for bf in (True, False):
+        _say(capsys, f"\n[c3] oracle ({'bf16' if bf else 'fp32'}-store) on input 0, schedules 0 and 1, first {T_ref} positions x "
+                     f"{shape.n_layers} layers + head, {oracle.num_threads()} threads ...")
+        ref[bf] = oracle.schedule_loglik(oracle.make_cfg(shape, act_bf16=bf), oracle.make_table(table), head["embed"], layers,
+                                         head["w_final_norm"], head["lm_head"], tokens[:1, :T_ref], targets[:1, :T_ref],
+                                         ids[:1, :2, :T_ref])[0]
+    _say(capsys, "[c3] oracle done")
+    e_gpu, e_orc = np.abs(nll[0, :2, :T_ref] - ref[True]), np.abs(ref[False] - ref[True])
+    for g, name in ((0, "dense schedule"), (1, "non-quantising schedule")):
+        msg = (f"C3 NLL, {name}: |gpu - bf16-store oracle| median {np.median(e_gpu[g]):.2e} q90 {np.quantile(e_gpu[g], .9):.2e} "
+               f"max {e_gpu[g].max():.2e}; |fp32-store - bf16-store oracle| median {np.median(e_orc[g]):.2e} q90 "
+               f"{np.quantile(e_orc[g], .9):.2e} max {e_orc[g].max():.2e}; nll mean {ref[True][g].mean():.4f} "
+               f"(log vocab {np.log(shape.vocab):.4f})")
+        print(msg)
+        assert np.median(e_gpu[g]) <= 1.25 * np.median(e_orc[g]) + 1e-3, msg
+        assert np.quantile(e_gpu[g], .9) <= 1.25 * np.quantile(e_orc[g], .9) + 1e-3, msg
+        assert e_gpu[g].max() <= 2.0 * e_orc[g].max() + 1e-2, msg
