@@ -165,6 +165,24 @@ int sol_decode_step(sol_ctx *ctx, const sol_model_weights *weights,
                     void *x_out, const int32_t *targets, float *nll_out,
                     void *workspace, size_t ws_bytes, void *stream);
 
+/* sol_decode_step for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc. Same arguments, results and error behaviour as
+ * sol_decode_step, bit for bit, without the workspace: the step's scratch (K-split partial sums, the row plan,
+ * activations between the kernels, a chunk of logits) lives in a file-scope device array of
+ * sol_static_scratch_bytes() = 64 MiB that every GPU the library runs on holds until the process ends. The call
+ * allocates and frees nothing. A step whose sol_workspace_bytes(cfg, SOL_OP_DECODE_STEP, B, 1, L_max) exceeds that
+ * size is rejected with SOL_ERR_WORKSPACE before any launch (64 sequences of the Llama-3.2-1B shape need 51 MiB).
+ * The context must have been created on the device that is current at the call (SOL_ERR_INVALID_ARG otherwise).
+ * Every call on a GPU shares that GPU's one array: calls that overlap on one GPU (two streams, two contexts, two
+ * threads) race on it; the array keeps the last call's contents and nothing in it needs clearing between calls
+ * (every kernel of the step writes what it later reads). */
+size_t sol_static_scratch_bytes(void);
+int sol_decode_step_static(sol_ctx *ctx, const sol_model_weights *weights,
+                           const int32_t *token_ids, const void *x_in,
+                           const int32_t *action_ids, const int32_t *cache_len,
+                           void *const *k_cache, void *const *v_cache, int B, int L_max,
+                           void *x_out, const int32_t *targets, float *nll_out, void *stream);
+
 /* Page metadata for decoding under the page rule (cfg.page_size = S >= 2; Appendix "Quest masking": the
  * element-wise maximum and minimum of the keys of each page). One buffer per layer, device memory owned by
  * the caller, sol_page_meta_bytes(cfg, n_seq, L_max) bytes, laid out

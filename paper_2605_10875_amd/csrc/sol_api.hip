@@ -23,8 +23,16 @@ static const char *const STAGE_NAMES[ST_COUNT] = {
     "norm_post_quant", "gate_up_gemm", "silu_mul", "prune_quant", "down_gemm", "residual_out", "embed",
     "norm_final", "lm_head_gemm", "nll_rows"};
 
+// Scratch of sol_decode_step_static: callers that cannot allocate get the decode step's workspace from this
+// file-scope array instead. Every GPU holds its own copy at its own address; host code must not use the array's name
+// as an address but the pointer hipGetSymbolAddress returns for the current device (kept per context below).
+#define SOL_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+static __device__ __align__(256) unsigned char scratch[SOL_STATIC_SCRATCH_BYTES];
+
 struct sol_ctx {
     sol_model_cfg cfg;
+    int device = -1;               // the HIP device the context was created on
+    void *static_scratch = nullptr;    // that device's address of `scratch`
     int n_actions = 0;
     int n_buckets = 1;
     ActionDev *d_table = nullptr;
@@ -177,6 +185,10 @@ extern "C" int sol_create(const sol_model_cfg *cfg, const sol_action_def *table,
         return fail(nullptr, code, m2);
     };
     hipError_t e;
+    if ((e = hipGetDevice(&ctx->device)) != hipSuccess)
+        return cleanup(SOL_ERR_HIP, std::string("hipGetDevice: ") + hipGetErrorString(e));
+    if ((e = hipGetSymbolAddress(&ctx->static_scratch, HIP_SYMBOL(scratch))) != hipSuccess || !ctx->static_scratch)
+        return cleanup(SOL_ERR_HIP, std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(e));
     if ((e = hipMalloc((void **)&ctx->d_table, sizeof(ActionDev) * n_actions)) != hipSuccess)
         return cleanup(SOL_ERR_HIP, std::string("hipMalloc(table): ") + hipGetErrorString(e));
     if ((e = hipMalloc((void **)&ctx->d_rope, sizeof(float2) * rope.size())) != hipSuccess)
@@ -708,6 +720,28 @@ extern "C" int sol_decode_step(sol_ctx *ctx, const sol_model_weights *mw, const 
 {
     return decode_step_impl(ctx, mw, token_ids, x_in, action_ids, cache_len, k_cache, v_cache, nullptr, B, L_max, x_out,
                             targets, nll_out, workspace, ws_bytes, stream);
+}
+
+extern "C" size_t sol_static_scratch_bytes(void) { return SOL_STATIC_SCRATCH_BYTES; }
+
+extern "C" int sol_decode_step_static(sol_ctx *ctx, const sol_model_weights *mw, const int32_t *token_ids, const void *x_in,
+                                      const int32_t *action_ids, const int32_t *cache_len, void *const *k_cache,
+                                      void *const *v_cache, int B, int L_max, void *x_out, const int32_t *targets,
+                                      float *nll_out, void *stream)
+{
+    if (!ctx) return SOL_ERR_INVALID_ARG;
+    if (B < 0 || L_max <= 0) return fail(ctx, SOL_ERR_INVALID_ARG, "negative size");
+    int dev = -1;
+    SOL_HIP(ctx, hipGetDevice(&dev));
+    if (dev != ctx->device)
+        return fail(ctx, SOL_ERR_INVALID_ARG, "the context was created on device " + std::to_string(ctx->device) +
+                                              ", the current device is " + std::to_string(dev));
+    const size_t need = B > 0 ? sol_workspace_bytes(&ctx->cfg, SOL_OP_DECODE_STEP, B, 1, L_max) : 0;
+    if (need > SOL_STATIC_SCRATCH_BYTES)
+        return fail(ctx, SOL_ERR_WORKSPACE, "the step needs " + std::to_string(need) + " bytes of scratch, the static array holds " +
+                                            std::to_string(SOL_STATIC_SCRATCH_BYTES) + ": use sol_decode_step with a workspace");
+    return decode_step_impl(ctx, mw, token_ids, x_in, action_ids, cache_len, k_cache, v_cache, nullptr, B, L_max, x_out,
+                            targets, nll_out, ctx->static_scratch, SOL_STATIC_SCRATCH_BYTES, stream);
 }
 
 extern "C" int sol_decode_step_paged(sol_ctx *ctx, const sol_model_weights *mw, const int32_t *token_ids, const void *x_in,

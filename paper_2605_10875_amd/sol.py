@@ -27,7 +27,8 @@ EXPORTS = ("sol_validate_config", "sol_create", "sol_destroy", "sol_last_error",
            "sol_profile_enable", "sol_profile_read",
            "sol_test_topk_select", "sol_test_prune_mask", "sol_test_prune_quant", "sol_test_quant_codes",
            "sol_test_gemm", "sol_test_attn_threshold", "sol_test_attention_stage", "sol_test_mlp_stage",
-           "sol_test_episode_copies_workspace_bytes", "sol_test_episode_loglik_copies")
+           "sol_test_episode_copies_workspace_bytes", "sol_test_episode_loglik_copies",
+           "sol_static_scratch_bytes", "sol_decode_step_static")
 
 
 class RewardCfg(C.Structure):
@@ -100,6 +101,11 @@ def lib():
         L.sol_decode_step.argtypes = [C.c_void_p, C.POINTER(ModelWeights), C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int, C.c_int,
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.sol_static_scratch_bytes.restype = C.c_size_t
+        L.sol_static_scratch_bytes.argtypes = []
+        L.sol_decode_step_static.argtypes = [C.c_void_p, C.POINTER(ModelWeights), C.c_void_p, C.c_void_p, C.c_void_p,
+                                             C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int, C.c_int,
+                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.sol_decode_step_paged.argtypes = [C.c_void_p, C.POINTER(ModelWeights), C.c_void_p, C.c_void_p, C.c_void_p,
                                             C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
                                             C.POINTER(C.c_void_p), C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -327,6 +333,27 @@ class Sol:
         del keep
         self._check(rc)
         return x_out, nll
+
+    def decode_step_static(self, layers, head, action_ids, cache_len, k_caches, v_caches, token_ids=None, x_in=None,
+                           targets=None, x_out=None, nll_out=None, stream=None):
+        """decode_step without a workspace: the library's static device scratch is used and nothing is allocated by
+        the library (outputs given by the caller are written in place; missing ones are created here, by torch)."""
+        B = action_ids.shape[0]
+        L_max = k_caches[0].shape[2]
+        mw, keep = self._model_struct(layers, head)
+        kp = (C.c_void_p * len(k_caches))(*[t.data_ptr() for t in k_caches])
+        vp = (C.c_void_p * len(v_caches))(*[t.data_ptr() for t in v_caches])
+        if x_out is None:
+            x_out = torch.empty((B, self.cfg.d_model), dtype=self.tdtype, device="cuda")
+        if nll_out is None and targets is not None:
+            nll_out = torch.empty(B, dtype=torch.float32, device="cuda")
+        rc = self.L.sol_decode_step_static(self.handle, C.byref(mw), _ptr(_i32(token_ids)), _ptr(x_in),
+                                           _ptr(_i32(action_ids)), _ptr(_i32(cache_len)), kp, vp, B, L_max, _ptr(x_out),
+                                           _ptr(_i32(targets)), _ptr(nll_out) if targets is not None else None,
+                                           _stream(stream))
+        del keep
+        self._check(rc)
+        return x_out, (nll_out if targets is not None else None)
 
     def kv_refresh(self, layers, head, pos0, k_caches, v_caches, token_ids=None, x_in=None, page_meta=None,
                    want_hidden=True, workspace=None, stream=None):
