@@ -1,13 +1,20 @@
 #!/usr/bin/env python3
 """Benchmark of the action-conditioned decoder-layer path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c2p|c3|c5|c4|c5d|c4p|refresh|episode|episodep]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload all|c2|c2p|c3|c5|c4|c5d|c4p|refresh|episode|episodep]
 
 A step is one pass of the measured unit over one batch of seeded synthetic input that is already
-resident in HBM. Default workload: the Llama-3.2-1B-shaped decoder layer, 4 inputs x 8 schedules
-x 1024 tokens, bf16, i.i.d. actions from the 4x4x4 action space (one sol_layer_forward call).
-Prints ONE JSON line (metric, value, roofline of the dominant kernel measured with HIP events
-around the library's stages, and the CPU oracle timed on a bounded sample).
+resident in HBM. Default (`all`): the headline is C3, the largest single-GPU configuration and the one
+that runs the call the metric names (sol_schedule_loglik: Llama-3.2-1B-shaped 16-layer stack + LM head +
+NLL, 2 inputs x 8 schedules x 2048 tokens, bursty Markov schedules); the other roofline configurations
+(C2 and C5 layers, C4 and C5 decode steps) are timed in the same run and reported under "configs", each
+with its own roofline and cpu_baseline, so that the one line covers both halves of the metric
+(teacher-forced schedule-tokens/s and decode tokens/s). Prints ONE JSON line.
+
+Timing: W warm-up steps, then K steps bracketed by synchronisations (`ms_per_step`, `value`); every step is
+also bracketed by a pair of HIP events on the stream the library launches on, and the median of those K
+intervals is reported beside it (`ms_per_step_event_median`). Kernel times for the roofline come from HIP
+events the library records around its stages (sol_profile_*), on that same stream.
 """
 import argparse
 import json
@@ -54,26 +61,54 @@ def copy_calibration():
     del src, dst
 
 
-def measured_traffic(workload, kernel):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (None if absent)."""
+def kernel_sources_digest():
+    """Digest of the kernel sources: counters collected for other sources than the ones that run are not quoted."""
+    import glob
+    import hashlib
     import os
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic.json")
+    h = hashlib.sha1()
+    root = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2605_10875_amd", "csrc")
+    for p in sorted(glob.glob(os.path.join(root, "*.hip")) + glob.glob(os.path.join(root, "*.h"))):
+        h.update(open(p, "rb").read())
+    return h.hexdigest()[:16]
+
+
+def measured_counters(workload, kernel):
+    """What the committed rocprofv3 --pmc summaries (profiles/counters.json, written by bench_counters.py from
+    runs of this file) hold for `kernel` of `workload`: {"traffic": HBM bytes per launch, "mfma_util": share of the
+    kernel's busy cycles in which the matrix cores were busy, ...}; empty when absent or collected for other kernel
+    sources than the ones that run now."""
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "counters.json")
     try:
         with open(path) as f:
-            return json.load(f).get(workload, {}).get(kernel)
+            d = json.load(f)
     except (OSError, ValueError):
-        return None
+        return {}
+    if d.get("kernel_sources_digest") != kernel_sources_digest():
+        return {}
+    return d.get(workload, {}).get(kernel, {})
 
 
 def time_steps(fn, steps, warmup):
+    """(seconds per step by the wall clock around `steps` steps, median seconds per step by HIP event pairs)"""
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
     t0 = time.perf_counter()
-    for _ in range(steps):
+    for a, b in ev:
+        a.record()
         fn()
+        b.record()
     torch.cuda.synchronize()
-    return (time.perf_counter() - t0) / steps
+    wall = (time.perf_counter() - t0) / steps
+    return wall, float(np.median([a.elapsed_time(b) for a, b in ev])) * 1e-3
+
+
+def roofline_counters(workload, kernel):
+    c = measured_counters(workload, kernel)
+    return {"traffic": c.get("traffic"), "mfma_util": c.get("mfma_util")}
 
 
 def stage_times(ctx, fn, steps):
@@ -85,7 +120,23 @@ def stage_times(ctx, fn, steps):
     return {k: v[0] / steps for k, v in st.items()}, {k: v[1] // steps for k, v in st.items()}
 
 
-def run_layer(args, shape, n_inputs, G, T, table, name, preset=None):
+def _record(metric, units, sec, sec_ev, args, name, config, dtype="bf16"):
+    return {"metric": metric, "value": units / sec, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": sec * 1e3, "ms_per_step_event_median": sec_ev * 1e3,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+            "config": dict({"workload": name}, **config)}
+
+
+def _mfma_roofline(workload, dom, flops_per_launch, stages, launches):
+    per_launch_ms = stages[dom] / max(1, launches.get(dom, 1))
+    ach = flops_per_launch / (per_launch_ms * 1e-3) / 1e12
+    r = {"bound": "mfma", "kernel": dom, "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+         "frac": ach / PEAK_BF16_TFLOPS, "kernel_ms": per_launch_ms, "launches_per_step": launches.get(dom)}
+    r.update(roofline_counters(workload, dom))
+    return r
+
+
+def run_layer(args, shape, n_inputs, G, T, table, name, preset=None, workload="c2", oracle_tokens=2048):
     n_seq = n_inputs * G
     w = synth.layer_weights(shape, args.seed, bf16=True)
     x = synth.hidden_states(n_seq, T, shape.d_model, args.seed + 1, bf16=True)
@@ -101,7 +152,7 @@ def run_layer(args, shape, n_inputs, G, T, table, name, preset=None):
     def step():
         ctx.layer_forward(wd, xd, idd, kc, vc, x_out=out, workspace=ws)
 
-    sec = time_steps(step, args.steps, args.warmup)
+    sec, sec_ev = time_steps(step, args.steps, args.warmup)
     assert ctx.device_status() == sol.OK and bool(torch.isfinite(out.float()).all())
     stages, launches = stage_times(ctx, step, max(2, min(args.steps, 5)))
     tokens = n_seq * T
@@ -109,43 +160,36 @@ def run_layer(args, shape, n_inputs, G, T, table, name, preset=None):
     fl = layer_flops(shape, table, ids, pos)
     alg = fl["linear_dense"] + fl["down"] + fl["qk"] + fl["pv"]
     dense = fl["linear_dense"] + 2.0 * shape.d_ff * shape.d_model * tokens + 2 * fl["qk"]
-    dom = "gate_up_gemm"
-    dom_flops = 4.0 * shape.d_model * shape.d_ff * tokens           # 4 d d_ff per token
-    ach = dom_flops / (stages[dom] * 1e-3) / 1e12
-    res = {
-        "metric": "schedule_tokens_per_s", "value": tokens / sec, "unit": "tokens/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec * 1e3, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": name, "entry_point": "sol_layer_forward", "n_inputs": n_inputs, "schedules": G,
-                   "seq_len": T, "tokens_per_step": tokens, "actions": "iid uniform over %d" % len(table)},
-        "roofline": {"bound": "mfma", "kernel": dom, "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": ach / PEAK_BF16_TFLOPS, "traffic": measured_traffic(args.workload, dom),
-                     "kernel_ms": stages[dom],
-                     "launches_per_step": launches.get(dom)},
-        "layer": {"algorithmic_tflop": alg / 1e12, "algorithmic_tflops": alg / sec / 1e12,
-                  "algorithmic_frac_of_peak": alg / sec / 1e12 / PEAK_BF16_TFLOPS,
-                  "dense_equivalent_tflops": dense / sec / 1e12},
-        "stage_ms": {k: round(v, 4) for k, v in stages.items()},
-    }
+    res = _record("schedule_tokens_per_s", tokens, sec, sec_ev, args, name,
+                  {"entry_point": "sol_layer_forward", "n_inputs": n_inputs, "schedules": G, "seq_len": T,
+                   "tokens_per_step": tokens, "actions": "iid uniform over %d" % len(table)})
+    res["roofline"] = _mfma_roofline(workload, "gate_up_gemm", 4.0 * shape.d_model * shape.d_ff * tokens, stages, launches)
+    res["layer"] = {"algorithmic_tflop": alg / 1e12, "algorithmic_tflops": alg / sec / 1e12,
+                    "algorithmic_frac_of_peak": alg / sec / 1e12 / PEAK_BF16_TFLOPS,
+                    "dense_equivalent_tflops": dense / sec / 1e12}
+    res["stage_ms"] = {k: round(v, 4) for k, v in stages.items()}
     if not args.no_cpu_baseline:
         import oracle
-        cfg = oracle.make_cfg(shape, act_bf16=True)
-        ns = min(n_seq, max(1, (6 * 1024 * 2048) // (T * shape.d_model)))   # about 15 s of oracle work on 16 cores
-        kco = np.zeros((ns, shape.n_kv_heads, T, shape.head_dim), np.float32)
+        cfg = oracle.make_cfg(shape, act_bf16=True, **(preset or {}))
+        # a bounded sample: whole sequences while they fit `oracle_tokens` tokens of this shape, else the first
+        # tokens of sequence 0 (causality: their results do not depend on the rest of the sequence)
+        ns = max(1, min(n_seq, oracle_tokens // T))
+        Tn = min(T, oracle_tokens)
+        kco = np.zeros((ns, shape.n_kv_heads, Tn, shape.head_dim), np.float32)
         t0 = time.perf_counter()
-        ref, _ = oracle.layer_forward(cfg, oracle.make_table(table), w, x[:ns], ids[:ns], kco, kco.copy())
+        ref, _ = oracle.layer_forward(cfg, oracle.make_table(table), w, x[:ns, :Tn], ids[:ns, :Tn], kco, kco.copy())
         dt = time.perf_counter() - t0
-        got = out[:ns].float().cpu().numpy()
+        got = out[:ns, :Tn].float().cpu().numpy()
         err = (np.abs(got - ref).max(axis=2) / np.abs(ref).max()).ravel()
-        res["cpu_baseline"] = {"value": ns * T / dt, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
-                               "sample": "sequences 0..%d of %d, all %d tokens, one layer (%.1f s)" % (ns - 1, n_seq, T, dt),
+        res["cpu_baseline"] = {"value": ns * Tn / dt, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": "sequences 0..%d of %d, tokens 0..%d of %d, one layer (%.1f s)" % (ns - 1, n_seq, Tn - 1, T, dt),
                                "gpu_vs_oracle_row_err_median": float(np.median(err))}
     ctx.close()
     return res
 
 
-def run_stack(args, shape, B, G, T, table, name):
-    """Full stack + LM head + NLL (sol_schedule_loglik). Weights are drawn on the GPU (2.5 GB of them)."""
+def _gpu_stack_weights(args, shape):
+    """Random-init stack drawn on the GPU (2.5 GB at the 1B shape): N(0, 0.02) matrices, norm gains 1 + N(0, 0.1)."""
     gen = torch.Generator(device="cuda").manual_seed(args.seed)
 
     def rnd(*sz, std=0.02, mean=0.0):
@@ -156,6 +200,18 @@ def run_stack(args, shape, B, G, T, table, name):
                "wv": rnd(hkv * dh, d), "wo": rnd(d, hq * dh), "w_post_norm": rnd(d, std=0.1, mean=1.0),
                "w_gate": rnd(dff, d), "w_up": rnd(dff, d), "w_down": rnd(d, dff)} for _ in range(shape.n_layers)]
     head = {"embed": rnd(shape.vocab, d), "w_final_norm": rnd(d, std=0.1, mean=1.0), "lm_head": rnd(shape.vocab, d)}
+    return layers, head
+
+
+def _host(t):
+    return t.float().cpu().numpy()
+
+
+def run_stack(args, shape, B, G, T, table, name, workload="c3"):
+    """Full stack + LM head + NLL (sol_schedule_loglik). Weights are drawn on the GPU (2.5 GB of them)."""
+    import dataclasses
+    layers, head = _gpu_stack_weights(args, shape)
+    d, dff = shape.d_model, shape.d_ff
     tokens, targets = synth.tokens_and_targets(B, T, shape.vocab, args.seed + 1)
     ids = synth.markov_actions(len(table), B * G, T, args.seed + 2).reshape(B, G, T)
     ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=T)
@@ -166,32 +222,22 @@ def run_stack(args, shape, B, G, T, table, name):
     def step():
         ctx.schedule_loglik(layers, head, tk, tg, idd, nll_out=nll, workspace=ws)
 
-    sec = time_steps(step, args.steps, args.warmup)
+    sec, sec_ev = time_steps(step, args.steps, args.warmup)
     assert ctx.device_status() == sol.OK and bool(torch.isfinite(nll).all())
     stages, launches = stage_times(ctx, step, 2)
     tokens_n = B * G * T
     pos = np.tile(np.arange(T), (B * G, 1))
     fl = layer_flops(shape, table, ids.reshape(B * G, T), pos)
     alg = shape.n_layers * (fl["linear_dense"] + fl["down"] + fl["qk"] + fl["pv"]) + 2.0 * d * shape.vocab * tokens_n
-    dom = "gate_up_gemm"
-    dom_flops = 4.0 * d * dff * tokens_n                             # per launch (one layer)
-    per_launch_ms = stages[dom] / max(1, launches.get(dom, shape.n_layers))
-    ach = dom_flops / (per_launch_ms * 1e-3) / 1e12
-    res = {
-        "metric": "schedule_tokens_per_s", "value": tokens_n / sec, "unit": "tokens/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec * 1e3, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": name, "entry_point": "sol_schedule_loglik", "n_inputs": B, "schedules": G, "seq_len": T,
+    res = _record("schedule_tokens_per_s", tokens_n, sec, sec_ev, args, name,
+                  {"entry_point": "sol_schedule_loglik", "n_inputs": B, "schedules": G, "seq_len": T,
                    "layers": shape.n_layers, "vocab": shape.vocab, "tokens_per_step": tokens_n,
-                   "actions": "Markov chain over %d actions, stay-probability 0.8" % len(table)},
-        "roofline": {"bound": "mfma", "kernel": dom, "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": ach / PEAK_BF16_TFLOPS, "traffic": None, "kernel_ms": per_launch_ms,
-                     "launches_per_step": launches.get(dom)},
-        "stack": {"algorithmic_tflop": alg / 1e12, "algorithmic_tflops": alg / sec / 1e12,
-                  "algorithmic_frac_of_peak": alg / sec / 1e12 / PEAK_BF16_TFLOPS,
-                  "mean_nll_nats": float(nll.mean()), "log_vocab": float(np.log(shape.vocab))},
-        "stage_ms": {k: round(v, 4) for k, v in stages.items()},
-    }
+                   "actions": "Markov chain over %d actions, stay-probability 0.8" % len(table)})
+    res["roofline"] = _mfma_roofline(workload, "gate_up_gemm", 4.0 * d * dff * tokens_n, stages, launches)
+    res["stack"] = {"algorithmic_tflop": alg / 1e12, "algorithmic_tflops": alg / sec / 1e12,
+                    "algorithmic_frac_of_peak": alg / sec / 1e12 / PEAK_BF16_TFLOPS,
+                    "mean_nll_nats": float(nll.mean()), "log_vocab": float(np.log(shape.vocab))}
+    res["stage_ms"] = {k: round(v, 4) for k, v in stages.items()}
     # the step right after this pass: reward reduction on its NLL tensor (not part of the timed step)
     tg3 = torch.full((B, 3), 0.6, dtype=torch.float32, device="cuda")
     rw = lambda: ctx.reward_advantages(nll, idd, tg3, (4.0, 4.0, 4.0), 0.02, 0.85)
@@ -206,13 +252,38 @@ def run_stack(args, shape, B, G, T, table, name):
     assert bool(torch.isfinite(adv).all())
     res["reward_reduction"] = {"entry_point": "sol_reward_advantages", "ms": e0.elapsed_time(e1) / 10,
                                "values": tokens_n, "note": "includes the binding's five output allocations"}
+    if not args.no_cpu_baseline:
+        # The oracle cannot run the whole stack in bounded time (2.4 GFLOP per token in fp64 loops): it is timed on
+        # sequence 0 / schedule 0 through layer 0 at the full length, and on the final norm + LM head + NLL of the
+        # first 128 positions, and the two are scaled to 16 layers and all positions of that sequence.
+        import oracle
+        w0 = {k: _host(v) for k, v in layers[0].items()}
+        x0 = _host(head["embed"][tk[0].long()])[None]
+        kco = np.zeros((1, shape.n_kv_heads, T, shape.head_dim), np.float32)
+        t0 = time.perf_counter()
+        oracle.layer_forward(oracle.make_cfg(shape, act_bf16=True), oracle.make_table(table), w0, x0, ids[0, :1], kco, kco.copy())
+        t_layer = time.perf_counter() - t0
+        n_head = 128
+        none = dataclasses.replace(shape, n_layers=0)
+        emb, wf, lm = _host(head["embed"]), _host(head["w_final_norm"]), _host(head["lm_head"])
+        t0 = time.perf_counter()
+        oracle.schedule_loglik(oracle.make_cfg(none, act_bf16=True), oracle.make_table(table), emb, [], wf, lm,
+                               tokens[:1, :n_head], targets[:1, :n_head], ids[:1, :1, :n_head])
+        t_head = time.perf_counter() - t0
+        del emb, lm
+        total = shape.n_layers * t_layer + t_head * T / n_head
+        res["cpu_baseline"] = {"value": T / total, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": "sequence 0, schedule 0: layer 0 over all %d tokens (%.1f s) and final norm + LM head + "
+                                         "NLL of %d positions (%.1f s), scaled to %d layers and %d positions"
+                                         % (T, t_layer, n_head, t_head, shape.n_layers, T)}
     ctx.close()
     return res
 
 
-def run_decode(args, shape, B, L, table, name, n_layers, preset=None):
+def run_decode(args, shape, B, L, table, name, n_layers, preset=None, with_head=False, workload="c4"):
     """preset: None = exact per-key top-k, quantiser on the linear-layer inputs; a dict of configuration fields
-    (sol.PAPER_PRESET) = that configuration, decoded with caller-kept page metadata."""
+    (sol.PAPER_PRESET) = that configuration, decoded with caller-kept page metadata. with_head: the step ends with the
+    final norm, the LM head and the NLL of a target token."""
     import dataclasses
     shape = dataclasses.replace(shape, n_layers=n_layers)
     gen = torch.Generator(device="cuda").manual_seed(args.seed)
@@ -220,7 +291,12 @@ def run_decode(args, shape, B, L, table, name, n_layers, preset=None):
     lw = [{k: _dev(v) for k, v in layers[0].items()} for _ in range(1)]
     # every layer gets its own weight tensors (distinct HBM) with the same seeded values
     lw = lw + [{k: v.clone() for k, v in lw[0].items()} for _ in range(n_layers - 1)]
-    head = None
+    head, targets = None, None
+    if with_head:
+        head = {"embed": None,
+                "w_final_norm": (torch.randn(shape.d_model, generator=gen, device="cuda") * 0.1 + 1.0).to(torch.bfloat16),
+                "lm_head": (torch.randn((shape.vocab, shape.d_model), generator=gen, device="cuda") * 0.02).to(torch.bfloat16)}
+        targets = _dev(np.random.default_rng(args.seed + 5).integers(0, shape.vocab, B).astype(np.int32))
     L_max = L + 8
     kcs = [torch.randn((B, shape.n_kv_heads, L_max, shape.head_dim), generator=gen, device="cuda",
                        dtype=torch.float32).to(torch.bfloat16) for _ in range(n_layers)]
@@ -233,26 +309,28 @@ def run_decode(args, shape, B, L, table, name, n_layers, preset=None):
     idd = _dev(ids)
     ws = ctx.workspace(sol.OP_DECODE_STEP, B, 1, L_max)
     metas = [ctx.page_meta_build(k, cache_len) for k in kcs] if preset and preset.get("page_size", 1) > 1 else None
+    k0_before = kcs[0][:2].float().cpu().numpy().copy()         # for the oracle leg (the step appends to the caches)
+    v0_before = vcs[0][:2].float().cpu().numpy().copy()
 
     def step():
-        return ctx.decode_step(lw, head, idd, cache_len, kcs, vcs, x_in=x, workspace=ws, page_meta=metas)[0]
+        return ctx.decode_step(lw, head, idd, cache_len, kcs, vcs, x_in=x, workspace=ws, page_meta=metas, targets=targets)
 
     # The step is ~200 short kernels; replaying them as one HIP graph removes the host launch gaps
     # (the library only enqueues kernels on the caller's stream, so the caller may capture it).
-    x_out = torch.empty((B, shape.d_model), dtype=torch.bfloat16, device="cuda")
     for _ in range(2):
         step()
     torch.cuda.synchronize()
-    sec_eager = time_steps(step, max(2, args.steps // 2), 1)
+    sec_eager, _ = time_steps(step, max(2, args.steps // 2), 1)
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
-        hid_g = step()
-    sec = time_steps(graph.replay, args.steps, args.warmup)
-    hid = step()
+        hid_g, nll_g = step()
+    sec, sec_ev = time_steps(graph.replay, args.steps, args.warmup)
+    hid, nll = step()
     torch.cuda.synchronize()
     assert ctx.device_status() == sol.OK and bool(torch.isfinite(hid.float()).all())
     assert torch.equal(hid, hid_g), "graph replay and eager step disagree"
-    del x_out
+    if with_head:
+        assert bool(torch.isfinite(nll).all()) and torch.equal(nll, nll_g)
     stages, launches = stage_times(ctx, step, 2)
     # algorithmic bytes: weights once per layer, all of K, the V rows kept by at least one head of a group
     d, hq, hkv, dh, dff = shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_ff
@@ -262,6 +340,29 @@ def run_decode(args, shape, B, L, table, name, n_layers, preset=None):
     kk = np.clip(-(-(t[:, 0] * n) // t[:, 1]), 1, n)
     g = hq // hkv
     union = n * (1.0 - (1.0 - kk / n) ** g)                  # expected distinct rows over g independent heads
+    union_note = "expected union over %d independent heads" % g
+    cpu = None
+    if not args.no_cpu_baseline:
+        # oracle on sequences 0 and 1, layer 0: timed, and its realised kept sets give the distinct V rows per KV
+        # group, which correct the expectation used for the other sequences
+        import oracle
+        o_opts = dict(preset or {})
+        one = dataclasses.replace(shape, n_layers=1)
+        ns = min(2, B)
+        t0 = time.perf_counter()
+        _, taps = oracle.layer_forward(oracle.make_cfg(one, act_bf16=True, **o_opts), oracle.make_table(table), layers[0],
+                                       x[:ns].float().cpu().numpy()[:, None, :], ids[:ns, None], k0_before[:ns], v0_before[:ns],
+                                       pos0=np.full(ns, L, np.int32), taps=("keep_mask",))
+        dt = time.perf_counter() - t0
+        km = taps["keep_mask"][:, 0].reshape(ns, hkv, g, L_max)           # [seq][kv head][head of the group][key]
+        realised = km.any(axis=2).sum(axis=2).mean(axis=1)               # distinct rows per KV head, averaged over KV heads
+        ratio = float((realised / union[:ns]).mean())
+        union = union * ratio
+        union_note = ("expected union over %d independent heads, scaled by %.4f = realised / expected distinct V rows of the "
+                      "oracle's kept sets for sequences 0..%d in layer 0" % (g, ratio, ns - 1))
+        cpu = {"value": ns / (dt * n_layers), "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": "sequences 0..%d of %d, one layer timed (%.2f s), scaled to %d layers%s"
+               % (ns - 1, B, dt, n_layers, "; final norm + LM head + NLL not included" if with_head else "")}
     kv_bytes = float((hkv * dh * 2 * (n + union)).sum())
     if metas is not None:
         # page rule: the metadata rows (2 * dh values per page), then K and V rows of the pages kept by at least one
@@ -272,38 +373,25 @@ def run_decode(args, shape, B, L, table, name, n_layers, preset=None):
         upages = np.where(kk >= n, n_pages, n_pages * (1.0 - (1.0 - npg / n_pages) ** g))
         rows = np.minimum(upages * S + preset.get("n_sink", 0) + preset.get("n_window", 0), n)
         kv_bytes = float((hkv * dh * 2 * (2 * n_pages + 2 * rows)).sum())
-    alg_bytes = n_layers * (wbytes + kv_bytes)
+        union_note = "expected distinct pages over %d independent heads" % g
+    head_bytes = 2.0 * shape.vocab * d if with_head else 0.0
+    alg_bytes = n_layers * (wbytes + kv_bytes) + head_bytes
     dom = "attention_topk"
-    ach = (n_layers * kv_bytes) / (stages[dom] * 1e-3) / 1e9
-    res = {
-        "metric": "decode_tokens_per_s", "value": B / sec, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": name, "entry_point": "sol_decode_step_paged" if metas is not None else "sol_decode_step",
-                   "batch": B, "cache_len": L, "layers": n_layers,
-                   "launch": "one HIP graph replay per step", "ms_per_step_eager_launches": sec_eager * 1e3},
-        "roofline": {"bound": "hbm", "kernel": dom, "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                     "frac": ach / PEAK_HBM_GBS, "traffic": measured_traffic(args.workload, dom),
-                     "kernel_ms": stages[dom] / n_layers,
-                     "launches_per_step": launches.get(dom)},
-        "step": {"algorithmic_gb": alg_bytes / 1e9, "algorithmic_gbs": alg_bytes / sec / 1e9,
-                 "algorithmic_frac_of_peak": alg_bytes / sec / 1e9 / PEAK_HBM_GBS},
-        "stage_ms": {k: round(v, 4) for k, v in stages.items()},
-    }
-    if not args.no_cpu_baseline:
-        import oracle
-        o_opts = dict(preset or {})
-        k0 = [kcs[0][:1].float().cpu().numpy().copy()]
-        v0 = [vcs[0][:1].float().cpu().numpy().copy()]
-        one = dataclasses.replace(shape, n_layers=1)
-        t0 = time.perf_counter()
-        oracle.decode_step(oracle.make_cfg(one, act_bf16=True, **o_opts), oracle.make_table(table), layers[:1],
-                           x[:1].float().cpu().numpy(), ids[:1], np.array([L], np.int32), k0, v0)
-        dt = time.perf_counter() - t0
-        res["cpu_baseline"] = {"value": 1.0 / (dt * n_layers), "unit": "tokens/s", "cores": oracle.num_threads(),
-                               "kind": "oracle", "sample": "sequence 0 of %d, one layer timed (%.2f s), scaled to %d layers"
-                               % (B, dt, n_layers)}
-        del o_opts
+    per_launch_ms = stages[dom] / n_layers
+    ach = kv_bytes / (per_launch_ms * 1e-3) / 1e9
+    res = _record("decode_tokens_per_s", B, sec, sec_ev, args, name,
+                  {"entry_point": "sol_decode_step_paged" if metas is not None else "sol_decode_step",
+                   "batch": B, "cache_len": L, "layers": n_layers, "lm_head_and_nll": bool(with_head),
+                   "launch": "one HIP graph replay per step", "ms_per_step_eager_launches": sec_eager * 1e3})
+    res["roofline"] = {"bound": "hbm", "kernel": dom, "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                       "frac": ach / PEAK_HBM_GBS, "kernel_ms": per_launch_ms, "launches_per_step": launches.get(dom),
+                       "v_rows": union_note}
+    res["roofline"].update(roofline_counters(workload, dom))
+    res["step"] = {"algorithmic_gb": alg_bytes / 1e9, "algorithmic_gbs": alg_bytes / sec / 1e9,
+                   "algorithmic_frac_of_peak": alg_bytes / sec / 1e9 / PEAK_HBM_GBS}
+    res["stage_ms"] = {k: round(v, 4) for k, v in stages.items()}
+    if cpu:
+        res["cpu_baseline"] = cpu
     ctx.close()
     return res
 
@@ -333,7 +421,7 @@ def run_episode(args, shape, B, K, P, T, table, name, preset=None):
     def step():
         ctx.episode_loglik(layers, head, prefix, tk, tg, idd, nll_out=nll, workspace=ws)
 
-    sec = time_steps(step, args.steps, args.warmup)
+    sec, sec_ev = time_steps(step, args.steps, args.warmup)
     assert ctx.device_status() == sol.OK and bool(torch.isfinite(nll).all())
     stages, launches = stage_times(ctx, step, 2)
     dom = max(stages, key=stages.get)
@@ -342,7 +430,7 @@ def run_episode(args, shape, B, K, P, T, table, name, preset=None):
     alg = shape.n_layers * lin * (B * P + B * K * T) + 2.0 * d * shape.vocab * B * K * T
     res = {
         "metric": "controlled_steps_per_s", "value": B * K * T / sec, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "warmup": args.warmup, "ms_per_step": sec * 1e3, "ms_per_step_event_median": sec_ev * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": name, "entry_point": "sol_episode_loglik", "n_inputs": B, "schedules": K, "prefix": P,
                    "steps_per_episode": T, "layers": shape.n_layers, "vocab": shape.vocab,
@@ -376,7 +464,7 @@ def run_refresh(args, shape, B, L, T, n_layers, name):
     def step():
         return ctx.kv_refresh(lw, None, pos0, kcs, vcs, x_in=x, workspace=ws)
 
-    sec = time_steps(step, args.steps, args.warmup)
+    sec, sec_ev = time_steps(step, args.steps, args.warmup)
     out = step()
     torch.cuda.synchronize()
     assert ctx.device_status() == sol.OK and bool(torch.isfinite(out.float()).all())
@@ -387,7 +475,7 @@ def run_refresh(args, shape, B, L, T, n_layers, name):
     ach = n_layers * kv_bytes / (stages["attention_topk"] * 1e-3) / 1e9
     return {
         "metric": "refreshed_tokens_per_s", "value": B * T / sec, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "warmup": args.warmup, "ms_per_step": sec * 1e3, "ms_per_step_event_median": sec_ev * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": name, "entry_point": "sol_kv_refresh", "batch": B, "cache_len": L, "T": T, "layers": n_layers},
         "roofline": {"bound": "hbm", "kernel": "attention_topk", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
@@ -397,14 +485,66 @@ def run_refresh(args, shape, B, L, T, n_layers, name):
     }
 
 
+LAYER_1B = "Llama-3.2-1B-shaped decoder layer, bf16, 4 inputs x 8 schedules x 1024 tokens"
+PAPER_CFG = ("the configuration of the paper's runs (pages of 16 keys, 4 sink + 2 window keys, pruning at the MLP input, "
+             "quantiser on the MLP output)")
+
+
+def run_workload(args, wl):
+    import dataclasses
+    stack_shape = dataclasses.replace(synth.LLAMA_1B, n_layers=16, vocab=128256)
+    if wl == "c2":
+        return run_layer(args, synth.LLAMA_1B, 4, 8, 1024, synth.TABLE_C2, "C2: " + LAYER_1B, workload=wl)
+    if wl == "c2p":
+        return run_layer(args, synth.LLAMA_1B, 4, 8, 1024, synth.TABLE_C2, "C2 under " + PAPER_CFG + ": " + LAYER_1B,
+                         preset=sol.PAPER_PRESET, workload=wl)
+    if wl == "c3":
+        return run_stack(args, stack_shape, 2, 8, 2048, synth.TABLE_C2,
+                         "C3: Llama-3.2-1B-shaped 16-layer stack + LM head + NLL, bf16, 2 inputs x 8 schedules x 2048 tokens",
+                         workload=wl)
+    if wl == "c5":
+        return run_layer(args, synth.LLAMA_8B, 2, 4, 4096, synth.TABLE_C2,
+                         "C5: Llama-3.1-8B-shaped decoder layer, bf16, 2 inputs x 4 schedules x 4096 tokens", workload=wl,
+                         oracle_tokens=768)
+    if wl == "c4":
+        return run_decode(args, stack_shape, 64, 8192, synth.TABLE_C4,
+                          "C4: Llama-3.2-1B-shaped decode step, bf16, 64 sequences x 8192-token KV cache, 16 layers + final "
+                          "norm + LM head + NLL", 16, with_head=True, workload=wl)
+    if wl == "c4p":
+        return run_decode(args, stack_shape, 64, 8192, synth.TABLE_C4,
+                          "C4 under " + PAPER_CFG + ", page metadata kept by the caller: Llama-3.2-1B-shaped decode step, "
+                          "bf16, 64 sequences x 8192-token KV cache, 16 layers + final norm + LM head + NLL", 16,
+                          preset=sol.PAPER_PRESET, with_head=True, workload=wl)
+    if wl == "c5d":
+        return run_decode(args, synth.LLAMA_8B, 32, 8192, synth.TABLE_C2,
+                          "C5-decode: Llama-3.1-8B-shaped decode step, bf16, 32 sequences x 8192-token KV cache, 1 layer", 1,
+                          workload=wl)
+    if wl == "episode":
+        return run_episode(args, stack_shape, 8, 32, 1024, 16, synth.TABLE_C2,
+                           "Episode pass: Llama-3.2-1B-shaped 16-layer stack + LM head + NLL, bf16, 8 inputs, dense prefill of "
+                           "1024 tokens once per input, 32 schedules x 16 controlled steps on it")
+    if wl == "episodep":
+        return run_episode(args, stack_shape, 8, 32, 1024, 16, synth.TABLE_C2,
+                           "Episode pass under " + PAPER_CFG + ": Llama-3.2-1B-shaped 16-layer stack + LM head + NLL, bf16, 8 "
+                           "inputs, dense prefill of 1024 tokens once per input, 32 schedules x 16 controlled steps on it",
+                           preset=sol.PAPER_PRESET)
+    if wl == "refresh":
+        return run_refresh(args, synth.LLAMA_1B, 64, 4096, 16, 16,
+                           "KV-cache refresh: Llama-3.2-1B-shaped 16-layer stack, bf16, 64 sequences x 4096-token caches, "
+                           "dense pass over the last 16 tokens")
+    raise ValueError(wl)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c2", choices=["c2", "c2p", "c3", "c5", "c4", "c5d", "c4p", "refresh", "episode", "episodep"])
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="all",
+                    choices=["all", "c2", "c2p", "c3", "c5", "c4", "c5d", "c4p", "refresh", "episode", "episodep"])
     ap.add_argument("--seed", type=int, default=1234)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the two peak microbenchmarks")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (sequences are independent and would be sharded by input); "
@@ -415,51 +555,30 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     copy_calibration()
-    if args.workload == "c2":
-        res = run_layer(args, synth.LLAMA_1B, 4, 8, 1024, synth.TABLE_C2,
-                        "C2: Llama-3.2-1B-shaped decoder layer, bf16, 4 inputs x 8 schedules x 1024 tokens")
-    elif args.workload == "c2p":
-        res = run_layer(args, synth.LLAMA_1B, 4, 8, 1024, synth.TABLE_C2,
-                        "C2 under the configuration of the paper's runs (pages of 16 keys, 4 sink + 2 window keys, pruning at the "
-                        "MLP input, quantiser on the MLP output): Llama-3.2-1B-shaped decoder layer, bf16, 4 inputs x 8 schedules "
-                        "x 1024 tokens", preset=sol.PAPER_PRESET)
-    elif args.workload == "c3":
-        import dataclasses
-        shape = dataclasses.replace(synth.LLAMA_1B, n_layers=16, vocab=128256)
-        res = run_stack(args, shape, 2, 8, 2048, synth.TABLE_C2,
-                        "C3: Llama-3.2-1B-shaped 16-layer stack + LM head + NLL, bf16, 2 inputs x 8 schedules x 2048 tokens")
-    elif args.workload == "c5":
-        res = run_layer(args, synth.LLAMA_8B, 2, 4, 4096, synth.TABLE_C2,
-                        "C5: Llama-3.1-8B-shaped decoder layer, bf16, 2 inputs x 4 schedules x 4096 tokens")
-    elif args.workload == "c4":
-        res = run_decode(args, synth.LLAMA_1B, 64, 8192, synth.TABLE_C4,
-                         "C4: Llama-3.2-1B-shaped decode step, bf16, 64 sequences x 8192-token KV cache, 16 layers", 16)
-    elif args.workload == "episode":
-        import dataclasses
-        shape = dataclasses.replace(synth.LLAMA_1B, n_layers=16, vocab=128256)
-        res = run_episode(args, shape, 8, 32, 1024, 16, synth.TABLE_C2,
-                          "Episode pass: Llama-3.2-1B-shaped 16-layer stack + LM head + NLL, bf16, 8 inputs, dense prefill of "
-                          "1024 tokens once per input, 32 schedules x 16 controlled steps on it")
-    elif args.workload == "episodep":
-        import dataclasses
-        shape = dataclasses.replace(synth.LLAMA_1B, n_layers=16, vocab=128256)
-        res = run_episode(args, shape, 8, 32, 1024, 16, synth.TABLE_C2,
-                          "Episode pass under the configuration of the paper's runs (pages of 16 keys, 4 sink + 2 window keys, "
-                          "pruning at the MLP input, quantiser on the MLP output): Llama-3.2-1B-shaped 16-layer stack + LM head + "
-                          "NLL, bf16, 8 inputs, dense prefill of 1024 tokens once per input, 32 schedules x 16 controlled steps "
-                          "on it", preset=sol.PAPER_PRESET)
-    elif args.workload == "refresh":
-        res = run_refresh(args, synth.LLAMA_1B, 64, 4096, 16, 16,
-                          "KV-cache refresh: Llama-3.2-1B-shaped 16-layer stack, bf16, 64 sequences x 4096-token caches, "
-                          "dense pass over the last 16 tokens")
-    elif args.workload == "c4p":
-        res = run_decode(args, synth.LLAMA_1B, 64, 8192, synth.TABLE_C4,
-                         "C4 under the configuration of the paper's runs (pages of 16 keys, 4 sink + 2 window keys, pruning at "
-                         "the MLP input, quantiser on the MLP output), page metadata kept by the caller: Llama-3.2-1B-shaped "
-                         "decode step, bf16, 64 sequences x 8192-token KV cache, 16 layers", 16, preset=sol.PAPER_PRESET)
+    peaks = None
+    if not args.no_peaks:
+        tf, gb, rd = sol.measure_peaks()
+        peaks = {"mfma_bf16_tflops": tf, "mfma_bf16_published": PEAK_BF16_TFLOPS, "hbm_copy_gbs": gb, "hbm_read_gbs": rd,
+                 "hbm_published": PEAK_HBM_GBS,
+                 "note": "register-only 32x32x16 bf16 MFMA loop on every SIMD; 1 GiB device copy (bytes read + written); "
+                         "read-only sweep of 1 GiB"}
+    if args.workload == "all":
+        res = run_workload(args, "c3")
+        res["configs"] = {}
+        for wl in ("c2", "c5", "c4", "c5d"):
+            torch.cuda.empty_cache()
+            sub = run_workload(args, wl)
+            for k in ("n_gpus", "steps", "warmup", "higher_is_better", "scaling", "vs_baseline", "data"):
+                sub.pop(k, None)
+            res["configs"][wl] = sub
     else:
-        res = run_decode(args, synth.LLAMA_8B, 32, 8192, synth.TABLE_C2,
-                         "C5-decode: Llama-3.1-8B-shaped decode step, bf16, 32 sequences x 8192-token KV cache, 1 layer", 1)
+        res = run_workload(args, args.workload)
+    if peaks:
+        res["measured_peaks"] = peaks
+        for rec in [res] + list(res.get("configs", {}).values()):
+            r = rec["roofline"]
+            if r.get("bound") in ("mfma", "hbm") and "achieved" in r:
+                r["frac_of_measured_peak"] = r["achieved"] / (peaks["mfma_bf16_tflops"] if r["bound"] == "mfma" else max(peaks["hbm_copy_gbs"], peaks["hbm_read_gbs"]))
     print(json.dumps(res))
 
 

@@ -292,6 +292,15 @@ int sol_profile_enable(sol_ctx *ctx, int max_stage_records);
 int sol_profile_read(sol_ctx *ctx, void *stream, int max_stages, const char **names_out, float *ms_out,
                      int *calls_out);
 
+/* Measured peaks of the GPU the library runs on, for pricing rooflines beside the published figures: a register-only
+ * loop of bf16 32x32x16 MFMAs on every SIMD (TFLOP/s), a plain device copy of half of `scratch` into its other half
+ * (GB/s, bytes read plus bytes written) and a read-only sweep of that half (GB/s). scratch: device memory the caller
+ * owns, at least 64 MiB, best 2 GiB or more so that the sweeps do not live in the memory-side cache. `reps` launches
+ * of each are timed with events on `stream`; the call synchronises. Returns SOL_OK, SOL_ERR_INVALID_ARG,
+ * SOL_ERR_WORKSPACE (scratch too small) or SOL_ERR_HIP. */
+int sol_measure_peaks(void *scratch, size_t scratch_bytes, int reps, float *mfma_tflops_out, float *copy_gbs_out,
+                      float *read_gbs_out, void *stream);
+
 /* ---- unit hooks: the selection / quantisation device code on caller-supplied fp32 data ----
  * All pointers device; results are exact integer decisions and must match the definitions
  * bit for bit. */

@@ -28,7 +28,7 @@ EXPORTS = ("sol_validate_config", "sol_create", "sol_destroy", "sol_last_error",
            "sol_test_topk_select", "sol_test_prune_mask", "sol_test_prune_quant", "sol_test_quant_codes",
            "sol_test_gemm", "sol_test_attn_threshold", "sol_test_attention_stage", "sol_test_mlp_stage",
            "sol_test_episode_copies_workspace_bytes", "sol_test_episode_loglik_copies",
-           "sol_static_scratch_bytes", "sol_decode_step_static")
+           "sol_static_scratch_bytes", "sol_decode_step_static", "sol_measure_peaks")
 
 
 class RewardCfg(C.Structure):
@@ -441,6 +441,19 @@ class Sol:
 
     def device_status(self, stream=None):
         return int(self.L.sol_device_status(self.handle, _stream(stream)))
+
+
+def measure_peaks(scratch_bytes=2 << 30, reps=10, stream=None):
+    """(bf16 MFMA TFLOP/s, device copy GB/s, device read GB/s) this GPU reaches in the library's peak microbenchmarks."""
+    buf = torch.empty(scratch_bytes, dtype=torch.uint8, device="cuda").zero_()
+    tf, gb, rd = C.c_float(0), C.c_float(0), C.c_float(0)
+    L = lib()
+    L.sol_measure_peaks.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_float),
+                                    C.POINTER(C.c_float), C.c_void_p]
+    rc = L.sol_measure_peaks(_ptr(buf), buf.numel(), reps, C.byref(tf), C.byref(gb), C.byref(rd), _stream(stream))
+    if rc:
+        raise SolError(rc, "sol_measure_peaks")
+    return float(tf.value), float(gb.value), float(rd.value)
 
 
 def topk_select(scores, n_valid, k, stream=None):
