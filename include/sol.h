@@ -16,9 +16,9 @@
  *   - Errors: an int status is returned, no exception crosses the ABI; sol_last_error gives text.
  *     Everything that can be checked on the host (null pointers, shapes, table contents,
  *     workspace size, static cache overflow) is checked before the first launch. Conditions that
- *     live in device memory (an action id outside the table, pos0[s] + T > L_max) make the kernels
- *     treat the token as a dense-action token / skip the sequence and raise a sticky flag that
- *     sol_device_status reports.
+ *     live in device memory (an action id outside the table, pos0[s] + T > L_max, a token or target
+ *     id outside the vocabulary) make the kernels treat the token as a dense-action token / skip the
+ *     sequence / clamp the id, and raise a sticky flag that sol_device_status reports.
  *   - Layouts: row-major. Weight matrices are [out_features][in_features]. Activations are
  *     [n_seq][T][d_model]. KV caches are [n_seq][n_kv_heads][L_max][head_dim] with keys stored
  *     after the rotary embedding. Element type of weights, activations and caches is cfg.dtype.
@@ -277,8 +277,10 @@ int sol_schedule_loglik(sol_ctx *ctx, const sol_model_weights *weights,
                         void *workspace, size_t ws_bytes, void *stream);
 
 /* Synchronises `stream`, returns and clears the sticky device flags:
- * SOL_OK, SOL_ERR_ACTION (an action id outside the table was met and treated as dense) or
- * SOL_ERR_CACHE_OVERFLOW (a sequence was skipped because pos0 + T > L_max). */
+ * SOL_OK, SOL_ERR_CACHE_OVERFLOW (a sequence was skipped because pos0 + T > L_max), SOL_ERR_ACTION (an action id
+ * outside the table was met and treated as dense) or SOL_ERR_INVALID_ARG (a token id or a target id outside
+ * [0, vocab) was met and clamped into it: the embedding lookups and the NLLs of sol_schedule_loglik,
+ * sol_episode_loglik, sol_decode_step and sol_kv_refresh of that call are then those of the clamped ids). */
 int sol_device_status(sol_ctx *ctx, void *stream);
 
 /* Per-stage timing for measurement. sol_profile_enable(ctx, n) with n > 0 creates up to n pairs of

@@ -48,7 +48,9 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        path = _build.build(force=False)
+        # SOL_ORACLE_SANITIZE=1: the AddressSanitizer / UndefinedBehaviorSanitizer build (the process must have the
+        # sanitizer runtime preloaded; see tests/test_oracle_sanitizers.py)
+        path = _build.build(force=False, sanitize=os.environ.get("SOL_ORACLE_SANITIZE") == "1")
         _lib = C.CDLL(path)
         _lib.orc_budget.restype = C.c_int32
         _lib.orc_budget.argtypes = [C.c_uint32, C.c_uint32, C.c_int32]

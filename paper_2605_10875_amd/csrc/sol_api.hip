@@ -255,6 +255,7 @@ extern "C" int sol_device_status(sol_ctx *ctx, void *stream)
     if (f) SOL_HIP(ctx, hipMemset(ctx->d_flags, 0, sizeof(int)));
     if (f & FLAG_CACHE_OVERFLOW) return fail(ctx, SOL_ERR_CACHE_OVERFLOW, "a sequence's tokens did not fit its cache and were skipped");
     if (f & FLAG_BAD_ACTION) return fail(ctx, SOL_ERR_ACTION, "an action id outside the table was treated as the dense action");
+    if (f & FLAG_BAD_TOKEN) return fail(ctx, SOL_ERR_INVALID_ARG, "a token or target id outside the vocabulary was clamped into it");
     return SOL_OK;
 }
 
@@ -416,10 +417,10 @@ static int attn_stage(sol_ctx *ctx, LayerWs &w, const int32_t *pos0, void *kc, v
             if (!ok) return fail(ctx, SOL_ERR_UNSUPPORTED, "shared-prefix attention: shape outside the tiled kernels");
         }
         bool tiled = pv != nullptr;
-        tiled = tiled || dense_pass && mfma && w.vt && T >= 16 && L_max <= 4096 &&
-                     launch_attn_tile_dense(w.qb, kc, vc, w.vt, w.o32, pos0, n_seq, T, L_max, Hq, Hkv, dh, st);
-        tiled = tiled || fast && w.vt && T >= 16 && L_max <= 4096 &&
-                     launch_attn_tile(w.qb, kc, vc, w.vt, w.big32, w.o32, w.ra, pos0, n_seq, T, L_max, Hq, Hkv, dh, st);
+        tiled = tiled || (dense_pass && mfma && w.vt && T >= 16 && L_max <= 4096 &&
+                          launch_attn_tile_dense(w.qb, kc, vc, w.vt, w.o32, pos0, n_seq, T, L_max, Hq, Hkv, dh, st));
+        tiled = tiled || (fast && w.vt && T >= 16 && L_max <= 4096 &&
+                          launch_attn_tile(w.qb, kc, vc, w.vt, w.big32, w.o32, w.ra, pos0, n_seq, T, L_max, Hq, Hkv, dh, st));
         if (!tiled && mfma && opt.page > 1 && w.vt && w.pm && T >= 16 && L_max <= 4096 &&
             attn_tile_pages_sel_bytes(M, Hq, L_max, opt.page) <= 4 * (size_t)M * nqkv)   // the masks live in big32
             tiled = launch_attn_tile_pages(w.qb, kc, vc, w.vt, w.pm, w.big32, w.o32, w.ra, pos0, n_seq, T, L_max, Hq, Hkv, dh, opt, st);
@@ -506,7 +507,7 @@ static int layer_impl(sol_ctx *ctx, const sol_layer_weights *lw, const void *x_i
     const sol_model_cfg &g = ctx->cfg;
     const int dt = g.dtype;
     const int64_t M = (int64_t)n_seq * T;
-    const int d = g.d_model, Hq = g.n_q_heads, Hkv = g.n_kv_heads, dh = g.head_dim, dff = g.d_ff;
+    const int d = g.d_model, Hq = g.n_q_heads, Hkv = g.n_kv_heads, dh = g.head_dim;
     const int nq = Hq * dh, nkv = Hkv * dh, nqkv = nq + 2 * nkv;
     const uint32_t qs = g.quant_sites;
 
@@ -636,7 +637,7 @@ static int nll_impl(sol_ctx *ctx, const sol_model_weights *mw, const void *x, in
     bool fused = false;
     if (dt == SOL_BF16) {   // logits stay on chip: per-tile (max, sum of exponentials), folded per row afterwards
         STAGE(ctx, ST_LMHEAD, st);
-        fused = launch_gemm_nll(w.hf, mw->lm_head, targets, G, T, broadcast_g, nll_out, w.logits, M, g.vocab, g.d_model, st);
+        fused = launch_gemm_nll(w.hf, mw->lm_head, targets, G, T, broadcast_g, nll_out, w.logits, M, g.vocab, g.d_model, ctx->d_flags, st);
     }
     const int64_t chunk = lm_chunk_rows(g, M);
     const size_t es = esize(dt);
@@ -649,7 +650,7 @@ static int nll_impl(sol_ctx *ctx, const sol_model_weights *mw, const void *x, in
         }
         {
             STAGE(ctx, ST_NLL, st);
-            launch_nll_rows(w.logits, rows, g.vocab, targets, r0, G, T, broadcast_g, nll_out, st);
+            launch_nll_rows(w.logits, rows, g.vocab, targets, r0, G, T, broadcast_g, nll_out, ctx->d_flags, st);
         }
     }
     hipError_t e = hipGetLastError();
@@ -697,7 +698,7 @@ static int decode_step_impl(sol_ctx *ctx, const sol_model_weights *mw, const int
     launch_seq_order(cache_len, B, w.layer.seq_order, st);
     const void *cur = x_in;
     if (token_ids) {
-        launch_embed(mw->embed, token_ids, w.hf, g.dtype, B, 1, 1, g.d_model, g.vocab, st);
+        launch_embed(mw->embed, token_ids, w.hf, g.dtype, B, 1, 1, g.d_model, g.vocab, ctx->d_flags, st);
         cur = w.hf;
     }
     for (int l = 0; l < g.n_layers; ++l) {
@@ -819,7 +820,7 @@ extern "C" int sol_kv_refresh(sol_ctx *ctx, const sol_model_weights *mw, const i
     }
     const void *cur = x_in;
     if (token_ids) {
-        launch_embed(mw->embed, token_ids, xa, g.dtype, n_seq, 1, T, g.d_model, g.vocab, st);
+        launch_embed(mw->embed, token_ids, xa, g.dtype, n_seq, 1, T, g.d_model, g.vocab, ctx->d_flags, st);
         cur = xa;
     }
     for (int l = 0; l < g.n_layers; ++l) {
@@ -896,7 +897,7 @@ extern "C" int sol_schedule_loglik(sol_ctx *ctx, const sol_model_weights *mw, co
     prepare_actions(ctx, action_ids, M, w.layer, st);          // one plan, reused by every layer
     {
         STAGE(ctx, ST_EMBED, st);
-        launch_embed(mw->embed, tokens, w.xa, g.dtype, B, G, T, g.d_model, g.vocab, st);
+        launch_embed(mw->embed, tokens, w.xa, g.dtype, B, G, T, g.d_model, g.vocab, ctx->d_flags, st);
     }
     void *cur = w.xa, *nxt = w.xb;
     for (int l = 0; l < g.n_layers; ++l) {
@@ -1022,8 +1023,8 @@ static int episode_impl(sol_ctx *ctx, const sol_model_weights *mw, const int32_t
     prepare_actions(ctx, action_ids, M, w.suf, st);
     {
         STAGE(ctx, ST_EMBED, st);
-        launch_embed(mw->embed, prefix_tokens, w.pxa, g.dtype, B, 1, P, g.d_model, g.vocab, st);
-        launch_embed(mw->embed, tokens, w.st.xa, g.dtype, B, K, T, g.d_model, g.vocab, st);
+        launch_embed(mw->embed, prefix_tokens, w.pxa, g.dtype, B, 1, P, g.d_model, g.vocab, ctx->d_flags, st);
+        launch_embed(mw->embed, tokens, w.st.xa, g.dtype, B, K, T, g.d_model, g.vocab, ctx->d_flags, st);
     }
     void *pcur = w.pxa, *pnxt = w.pxb, *cur = w.st.xa, *nxt = w.st.xb;
     for (int l = 0; l < g.n_layers; ++l) {

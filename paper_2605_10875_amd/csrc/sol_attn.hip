@@ -500,11 +500,6 @@ __device__ __forceinline__ void sel_row_load(const float *row, int n, int lane, 
     kmin_out = wave_min_u32(to_key(fmin));
 }
 
-#ifdef SOL_SEL_TIMING
-// instrumentation for a host-side probe that defines SOL_SEL_TIMING and includes this file: 8 words per workgroup
-// (cycles in the five phases of a visit, visits, begin and end on the 100 MHz clock)
-__device__ unsigned long long *g_sel_stamps;
-#endif
 // A workgroup walks several blocks of BQ query rows of one (sequence, head): while the waves search the
 // thresholds of one block, the q and K fragments of the next are already on their way into registers,
 // so the global-load latency of the score phase is hidden. Blocks are dealt to the nb workgroups of a
@@ -586,13 +581,6 @@ k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRo
     int visit = 0, qb = bi;
     if (qb >= n_qb) return;
     SOL_SEL_LOAD(qb);
-#ifdef SOL_SEL_TIMING
-    const unsigned long long rt_begin = __builtin_amdgcn_s_memrealtime();
-    unsigned long long tacc[6] = {0, 0, 0, 0, 0, 0}, tprev = __builtin_readcyclecounter();
-#define SEL_T(i) { const unsigned long long t_ = __builtin_readcyclecounter(); tacc[i] += t_ - tprev; tprev = t_; }
-#else
-#define SEL_T(i)
-#endif
     while (true) {
         const int q0 = qb * BQ;
         const int rows = (Tn - q0 < BQ) ? (Tn - q0) : BQ;
@@ -621,17 +609,13 @@ k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRo
                 if (kt < n_kt) { SOL_SEL_MFMA(u, kt); }
             }
         }
-        SEL_T(0);
         if (tid == 0) next_row = NW;
         __syncthreads();
-        SEL_T(1);
         // ---- next block's fragments on their way while this block's rows are searched ----
         ++visit;
         const int qb_next = nb * visit + ((visit & 1) ? nb - 1 - bi : bi);
         const bool more = qb_next < n_qb;
         if (more) SOL_SEL_LOAD(qb_next);
-        SEL_T(2);
-
         // ---- per row: maximum, and the threshold when the budget is below the row length ----
         // the first NW rows go one to each wave, the others to whichever wave is free first
         for (int r = w; r < rows;) {
@@ -651,22 +635,10 @@ k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRo
             }
             r = __builtin_amdgcn_readfirstlane(r_next);
         }
-        SEL_T(3);
         if (!more) break;
         __syncthreads();                                   // every row is in registers or done: LDS may be overwritten
-        SEL_T(4);
         qb = qb_next;
     }
-#ifdef SOL_SEL_TIMING
-    if (tid == 0 && g_sel_stamps) {
-        unsigned long long *o = g_sel_stamps + ((size_t)(blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 8;
-        for (int i = 0; i < 5; ++i) o[i] = tacc[i];
-        o[5] = visit;
-        o[6] = rt_begin;                                    // begin / end on the constant 100 MHz clock
-        o[7] = __builtin_amdgcn_s_memrealtime();
-    }
-#endif
-#undef SEL_T
 #undef SOL_SEL_LOAD
 #undef SOL_SEL_MFMA
 }
@@ -752,11 +724,6 @@ __device__ __forceinline__ void pv_probs(const floatx4_a (&st)[2], float scale, 
     plo = __builtin_bit_cast(bf16x8_a, lo);
 }
 
-#ifdef SOL_PV_TIMING
-// instrumentation for a host-side probe that defines SOL_PV_TIMING and includes this file: 8 words per workgroup
-// (cycles in staging / compute / barrier, hardware ids, chunks, lifetime in cycles, begin and end on the 100 MHz clock)
-__device__ unsigned long long *g_pv_stamps;
-#endif
 // PRE: as in k_attn_select; vt then is the transposed copy of the own cache ([n_seq][Hkv][DH][lpadv], positions
 // pv.P..) and pv.vt that of the prefix cache ([inputs][Hkv][DH][pv.lpadv]); 64-key chunks never straddle pv.P.
 // NQT: query tiles of 16 rows per workgroup (2; 1 for passes of at most 16 rows per sequence).
@@ -798,13 +765,6 @@ k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf1
     // With one block per workgroup the lifetimes differ by a factor of up to n_qb, and slots freed by the short
     // workgroups of a launch were seen to stay empty until the long ones around them had ended.
     const int n_qb = (Tn + QT - 1) / QT;
-#ifdef SOL_PV_TIMING
-    const unsigned long long t_begin = __builtin_readcyclecounter(), rt_begin = __builtin_amdgcn_s_memrealtime();
-    unsigned long long tacc[4] = {0, 0, 0, 0}, tprev = t_begin, n_chunks_sum = 0;
-#define PV_T(i) { const unsigned long long t_ = __builtin_readcyclecounter(); tacc[i] += t_ - tprev; tprev = t_; }
-#else
-#define PV_T(i)
-#endif
     for (int pass = 0; pass < 2; ++pass) {
     const int qb = pass == 0 ? n_qb - 1 - bx : bx;
     if (pass == 1 && qb >= n_qb - 1 - bx) break;            // the middle block of an odd count is its own partner
@@ -888,7 +848,6 @@ k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf1
     SOL_PV_LSTORE(kreg0, vreg0, 0);
     if (1 < n_chunks) SOL_PV_GLOAD(kreg1, vreg1, 1);
     __syncthreads();
-    PV_T(0);
     for (int ch = 0; ch < n_chunks; ++ch) {
         const int stg = ch & 1;
         if (stg == 0) {
@@ -899,7 +858,6 @@ k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf1
             if (ch + 2 < n_chunks) SOL_PV_GLOAD(kreg1, vreg1, ch + 2);
         }
         const unsigned char *kb = pvl + stg * STAGE, *vb = kb + K_BYTES;
-        PV_T(1);
 #pragma unroll
         for (int cc = 0; cc < 2; ++cc) {
             const int kb32 = ch * KC + cc * 32;             // first key of this 32-key sub-chunk
@@ -945,13 +903,8 @@ k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf1
                 }
             }
         }
-        PV_T(2);
         __syncthreads();                                   // also frees both stages for the workgroup's next block
-        PV_T(3);
     }
-#ifdef SOL_PV_TIMING
-    n_chunks_sum += n_chunks;
-#endif
 #undef SOL_PV_GLOAD
 #undef SOL_PV_LSTORE
 
@@ -974,19 +927,6 @@ k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf1
         }
     }
     }   // pass
-#ifdef SOL_PV_TIMING
-    if (tid == 0 && g_pv_stamps) {
-        unsigned long long *o = g_pv_stamps + ((size_t)(blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 8;
-        for (int i = 0; i < 3; ++i) o[i] = tacc[i];
-        o[3] = ((unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 20) << 32) |    // XCC_ID, HW_ID
-               (unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 4);
-        o[4] = n_chunks_sum;
-        o[5] = __builtin_readcyclecounter() - t_begin;      // lifetime in cycles
-        o[6] = rt_begin;                                    // begin / end on the constant 100 MHz clock
-        o[7] = __builtin_amdgcn_s_memrealtime();
-    }
-#endif
-#undef PV_T
 }
 
 // =================================================================================================
@@ -1001,13 +941,6 @@ k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf1
 //   3. softmax numerators back to LDS, 4. V rows gathered where any head kept the key.
 // =================================================================================================
 constexpr int DEC_WAVES = 16, DEC_BLOCK = DEC_WAVES * 64, DEC_HPB = 4, DEC_GW = DEC_WAVES / DEC_HPB;
-#ifdef SOL_DEC_TIMING
-__device__ unsigned long long *g_dec_stamps;
-#define DEC_T(i) if (threadIdx.x == 0 && g_dec_stamps) g_dec_stamps[((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 8 + (i)] = __builtin_readcyclecounter();
-#else
-#define DEC_T(i)
-#endif
-
 // The last phases of the decode kernels: sc holds the softmax numerators of the HPB heads ([HPB][lpad], 0 for
 // dropped keys), s_den the per-wave partial denominators ([head][DEC_GW]); o_row receives HPB * DH outputs.
 //   4. o = sum_j p_j v_j, reading only V rows kept by at least one head; 5. reduction over lanes and waves.
@@ -1057,7 +990,6 @@ __device__ __forceinline__ void decode_pv_tail(float *sc, int lpad, int n, const
             }
         }
     }
-    DEC_T(6)
     // Reduce over the key slots of a wave (lanes with equal cs) by halving butterflies: at each step a lane
     // keeps one half of its values and hands the other half to its partner, so the 4 * VEC values per lane
     // end as 4 * VEC * LPK / 64 fully reduced ones; then across waves in fixed order.
@@ -1109,7 +1041,6 @@ k_attn_decode(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const
               const int32_t *__restrict__ seq_order, int L_max, int Hq, int Hkv, float scale, int *flags)
 {
     constexpr int KK = DH / 32, SLICE = SLOTS * 64, LPAD = SLICE * DEC_GW, NJ = SLOTS / 4;
-    constexpr int VEC = 8, LPK = DH / VEC, KPI = DEC_BLOCK / LPK;
     extern __shared__ __align__(16) float sc[];               // [DEC_HPB][LPAD]; later partial O [DEC_WAVES][HPB][DH]
     __shared__ int s_cnt[2][DEC_WAVES];
     __shared__ uint32_t s_min[DEC_WAVES], s_max[DEC_WAVES];
@@ -1120,7 +1051,6 @@ k_attn_decode(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kvh = blockIdx.x;
-    DEC_T(0)
     // Longest sequences first: workgroups are handed to compute units in launch order, one per CU, so with
     // mixed cache lengths the last round would otherwise wait for a long row that started late. seq_order
     // (k_seq_order, once per decode step) lists the sequences by decreasing cache length.
@@ -1136,7 +1066,6 @@ k_attn_decode(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const
     const bf16_t *kbase = kc + ((int64_t)s * Hkv + kvh) * (int64_t)L_max * DH;
     const bf16_t *vbase = vc + ((int64_t)s * Hkv + kvh) * (int64_t)L_max * DH;
     const int l16 = lane & 15, lg = lane >> 4;
-    DEC_T(1)
 
     // ---- 1. scores -----------------------------------------------------------------------------
     {
@@ -1184,7 +1113,6 @@ k_attn_decode(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const
 #undef SOL_DEC_MMAK
     }
     __syncthreads();
-    DEC_T(2)
 
     // ---- 2. selection: DEC_GW waves per head, each with SLICE columns in registers --------------
     const int head = w / DEC_GW, wg = w - head * DEC_GW;
@@ -1227,7 +1155,6 @@ k_attn_decode(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const
     lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)lo);
     hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)hi);
     const float mx = score_unkey(hi);                          // the head's best score, always kept
-    DEC_T(3)
     const RowAct act = ra[s];
     const int b = __builtin_amdgcn_readfirstlane(budget_ceil(act.keep_num, act.keep_den, n));   // 64-bit divide runs on the VALU
     uint32_t thr = 1u;                                         // budget keeps all: every valid key passes
@@ -1274,7 +1201,6 @@ k_attn_decode(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const
             __builtin_amdgcn_readfirstlane(s_done[par][0] & s_done[par][1] & s_done[par][2] & s_done[par][3]) != 0;
         if (all_done) break;                                   // uniform: every wave reads the same flags
     }
-    DEC_T(4)
     // Ties at the threshold go to the lower columns. Rare for fp32 scores, so the fix-up is a plain
     // loop by the first wave of the head over the row in LDS: tied keys beyond the quota get -inf.
     {
@@ -1329,10 +1255,8 @@ k_attn_decode(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const
     den = wave_sum_dpp(den);
     if (lane == 0) s_den[w] = den;
     __syncthreads();
-    DEC_T(5)
 
     decode_pv_tail<DH>(sc, LPAD, n, vbase, s_den, o32 + (int64_t)s * (Hq * DH) + (int64_t)h0 * DH);
-    DEC_T(7)
 }
 
 template <int DH, int SLOTS>

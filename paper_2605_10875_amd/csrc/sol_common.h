@@ -16,7 +16,7 @@ struct RowAct {
     int32_t  bits;                // activation bit-width; >= 16 bypasses the quantiser
 };
 
-enum { FLAG_BAD_ACTION = 1, FLAG_CACHE_OVERFLOW = 2 };
+enum { FLAG_BAD_ACTION = 1, FLAG_CACHE_OVERFLOW = 2, FLAG_BAD_TOKEN = 4 };
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
@@ -364,7 +364,6 @@ template <int SLOTS>
 __device__ __forceinline__ uint32_t wave_select_topk(uint32_t (&key)[SLOTS], int n_in, int b_in, uint32_t kmin,
                                                      uint32_t kmax, int lane)
 {
-    constexpr int NJ = SLOTS / 4;
     // every search variable is wave-uniform: scalar registers, scalar control flow around ballots
     const int n = __builtin_amdgcn_readfirstlane(n_in), b = __builtin_amdgcn_readfirstlane(b_in);
     uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)kmin);

@@ -327,13 +327,18 @@ struct EpiNllPart {
 
 // target token of every row (teacher-forced rows (b, g, t) share the targets of input b when broadcast_g)
 __global__ void __launch_bounds__(256)
-k_row_targets(const int32_t *__restrict__ targets, int64_t M, int G, int Tn, int broadcast_g, int V, int32_t *__restrict__ row_tgt)
+k_row_targets(const int32_t *__restrict__ targets, int64_t M, int G, int Tn, int broadcast_g, int V, int32_t *__restrict__ row_tgt,
+              int *__restrict__ flags)
 {
     const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (r >= M) return;
     const int64_t ti = broadcast_g ? (r / ((int64_t)G * Tn)) * Tn + (r % Tn) : r;
     int tg = targets[ti];
-    row_tgt[r] = tg < 0 ? 0 : (tg >= V ? V - 1 : tg);
+    if (tg < 0 || tg >= V) {                       // outside the vocabulary: clamped, and reported through the sticky flag
+        atomicOr(flags, FLAG_BAD_TOKEN);
+        tg = tg < 0 ? 0 : V - 1;
+    }
+    row_tgt[r] = tg;
 }
 
 // one wave per row: nll = max + log(sum_t s_t * exp(m_t - max)) - target logit
@@ -406,12 +411,7 @@ template <int N> __device__ __forceinline__ void vm_wait()
     __builtin_amdgcn_s_waitcnt(((N >> 4) << 14) | 0x0F70 | (N & 15));
 }
 
-#ifdef SOL_GEMM_TIMING
-__device__ unsigned long long *g_gemm_stamps;
-#define GT_STAMP(i) if (threadIdx.x == 0 && g_gemm_stamps) g_gemm_stamps[(size_t)blockIdx.x * 4 + (i)] = __builtin_readcyclecounter()
-#else
 #define GT_STAMP(i)
-#endif
 
 // PERSIST: one workgroup per CU walks every tile of its slot in the XCD's band (tile index + workgroups per XCD) and
 // the pipeline runs across the tile boundary: the last two K steps of a tile request the first two slices of the next
@@ -728,7 +728,7 @@ size_t gemm_nll_scratch_bytes(int64_t M, int V) { return (size_t)M * ((size_t)(V
 // nll[r] = logsumexp(hf[r] . lm_head^T) - (hf[r] . lm_head[target(r)]) without materialising the logits.
 // scratch: gemm_nll_scratch_bytes(M, V) bytes. Returns false (nothing launched) if the shape does not tile.
 bool launch_gemm_nll(const void *hf, const void *lm_head, const int32_t *targets, int G, int T, bool broadcast_g,
-                     float *nll, void *scratch, int64_t M, int V, int K, hipStream_t st)
+                     float *nll, void *scratch, int64_t M, int V, int K, int *flags, hipStream_t st)
 {
     if (M <= 0) return true;
     if (V % 256 || K % (2 * BK) || K < 2 * BK) return false;
@@ -737,7 +737,7 @@ bool launch_gemm_nll(const void *hf, const void *lm_head, const int32_t *targets
     float *tgt_logit = (float *)(part + (size_t)M * n_wt);
     int32_t *row_tgt = (int32_t *)(tgt_logit + M);
     hipLaunchKernelGGL(k_row_targets, dim3((unsigned)((M + 255) / 256)), dim3(256), 0, st, targets, M, G, T,
-                       broadcast_g ? 1 : 0, V, row_tgt);
+                       broadcast_g ? 1 : 0, V, row_tgt, flags);
     BMap bm{};
     bm.base[0] = (const bf16_t *)lm_head; bm.seg_end[0] = bm.seg_end[1] = bm.seg_end[2] = V; bm.mode = 0; bm.ld = K;
     EpiNllPart epi{part, tgt_logit, row_tgt, n_wt};

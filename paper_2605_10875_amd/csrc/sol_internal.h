@@ -60,12 +60,13 @@ void launch_resid_out(const float *x2, const float *z, void *out, int dtype, int
 // out = x2 + FQ(z, ra.bits): quantiser on the MLP block's output
 void launch_resid_out_fq(const float *x2, const float *z, void *out, int dtype, const RowAct *ra, int64_t M, int d,
                          hipStream_t st, int nsplit = 1);
-// x[n][t] = embed[tokens[b][t]]  for n = b*G + g
+// x[n][t] = embed[tokens[b][t]]  for n = b*G + g; a token id outside [0, vocab) is clamped and sets FLAG_BAD_TOKEN
+// (so do target ids in the two NLL paths below)
 void launch_embed(const void *embed, const int32_t *tokens, void *x, int dtype, int B, int G, int T, int d,
-                  int vocab, hipStream_t st);
+                  int vocab, int *flags, hipStream_t st);
 // nll[r] = logsumexp(logits[r]) - logits[r][target]; targets indexed through tgt_index(r)
 void launch_nll_rows(const float *logits, int64_t rows, int V, const int32_t *targets, int64_t row0, int G, int T,
-                     bool broadcast_g, float *nll, hipStream_t st);
+                     bool broadcast_g, float *nll, int *flags, hipStream_t st);
 // unit hooks
 // the row stage of the batched threshold kernel on caller rows (n_cols <= 4096, else false and nothing launched)
 bool launch_test_attn_threshold(const float *scores, int rows, int n_cols, const int32_t *n_valid, const int32_t *k,
@@ -109,7 +110,7 @@ bool launch_gemm_f32(const void *a, const void *w, float *C, int64_t ldc, int64_
 // LM head + NLL with the logits kept on chip (bf16, vocabulary a multiple of 256): nll[r] = logsumexp - target
 // logit. scratch: gemm_nll_scratch_bytes(M, V) bytes.
 bool launch_gemm_nll(const void *hf, const void *lm_head, const int32_t *targets, int G, int T, bool broadcast_g,
-                     float *nll, void *scratch, int64_t M, int V, int K, hipStream_t st);
+                     float *nll, void *scratch, int64_t M, int V, int K, int *flags, hipStream_t st);
 size_t gemm_nll_scratch_bytes(int64_t M, int V);
 
 // Skinny GEMM for M <= 64 rows (decode): partial[nsplit][M][n0+n1+n2] (fp32) = x * [w0; w1; w2]^T, K split over

@@ -989,27 +989,30 @@ void launch_resid_out_fq(const float *x2, const float *z, void *out, int dtype, 
 
 template <typename T>
 __global__ void k_embed(const T *__restrict__ embed, const int32_t *__restrict__ tokens, T *__restrict__ x, int G,
-                        int Tn, int d, int vocab)
+                        int Tn, int d, int vocab, int *__restrict__ flags)
 {
     const int64_t r = blockIdx.x;                 // row = (b*G + g)*T + t
     const int t = (int)(r % Tn);
     const int b = (int)(r / ((int64_t)G * Tn));
     int tok = tokens[(int64_t)b * Tn + t];
-    tok = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok);
+    if (tok < 0 || tok >= vocab) {                 // outside the vocabulary: clamped, and reported through the sticky flag
+        if (threadIdx.x == 0) atomicOr(flags, FLAG_BAD_TOKEN);
+        tok = tok < 0 ? 0 : vocab - 1;
+    }
     for (int j = threadIdx.x; j < d; j += blockDim.x) x[r * d + j] = embed[(int64_t)tok * d + j];
 }
 
 void launch_embed(const void *embed, const int32_t *tokens, void *x, int dtype, int B, int G, int T, int d, int vocab,
-                  hipStream_t st)
+                  int *flags, hipStream_t st)
 {
     const int64_t M = (int64_t)B * G * T;
     if (M <= 0) return;
     if (dtype == 0)
         hipLaunchKernelGGL((k_embed<float>), dim3((unsigned)M), dim3(256), 0, st, (const float *)embed, tokens,
-                           (float *)x, G, T, d, vocab);
+                           (float *)x, G, T, d, vocab, flags);
     else
         hipLaunchKernelGGL((k_embed<bf16_t>), dim3((unsigned)M), dim3(256), 0, st, (const bf16_t *)embed, tokens,
-                           (bf16_t *)x, G, T, d, vocab);
+                           (bf16_t *)x, G, T, d, vocab, flags);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1017,7 +1020,7 @@ void launch_embed(const void *embed, const int32_t *tokens, void *x, int dtype, 
 // ------------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(ROW_BLOCK)
 k_nll_rows(const float *__restrict__ logits, int V, const int32_t *__restrict__ targets, int64_t row0, int G, int Tn,
-           int broadcast_g, float *__restrict__ nll)
+           int broadcast_g, float *__restrict__ nll, int *__restrict__ flags)
 {
     __shared__ float red[ROW_BLOCK / 64];
     const int64_t lr = blockIdx.x, r = row0 + lr;
@@ -1031,17 +1034,20 @@ k_nll_rows(const float *__restrict__ logits, int V, const int32_t *__restrict__ 
     if (threadIdx.x == 0) {
         const int64_t ti = broadcast_g ? (r / ((int64_t)G * Tn)) * Tn + (r % Tn) : r;
         int tg = targets[ti];
-        tg = tg < 0 ? 0 : (tg >= V ? V - 1 : tg);
+        if (tg < 0 || tg >= V) {                   // outside the vocabulary: clamped, and reported through the sticky flag
+            atomicOr(flags, FLAG_BAD_TOKEN);
+            tg = tg < 0 ? 0 : V - 1;
+        }
         nll[r] = (mx + logf(se)) - l[tg];
     }
 }
 
 void launch_nll_rows(const float *logits, int64_t rows, int V, const int32_t *targets, int64_t row0, int G, int T,
-                     bool broadcast_g, float *nll, hipStream_t st)
+                     bool broadcast_g, float *nll, int *flags, hipStream_t st)
 {
     if (rows <= 0) return;
     hipLaunchKernelGGL(k_nll_rows, dim3((unsigned)rows), dim3(ROW_BLOCK), 0, st, logits, V, targets, row0, G, T,
-                       broadcast_g ? 1 : 0, nll);
+                       broadcast_g ? 1 : 0, nll, flags);
 }
 
 // ------------------------------------------------------------------------------------------------

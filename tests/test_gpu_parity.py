@@ -297,6 +297,23 @@ def test_device_flags_and_host_errors():
     with pytest.raises(sol.SolError) as e:
         ctx.layer_forward(w, x, dev(ids), small, small.clone())      # T > L_max
     assert e.value.code == sol.ERR_CACHE_OVERFLOW
+    # a token or target id outside the vocabulary is clamped and reported (both NLL paths: fused head at vocab 1024,
+    # materialised logits at vocab 1000)
+    for vocab in (1000, 1024):
+        shp = dataclasses.replace(shape, n_layers=1, vocab=vocab)
+        c2 = sol.Sol(shp, table, dtype=sol.BF16, max_positions=16)
+        head = dev_weights(synth.head_weights(shp, 5002, bf16=True), sol.BF16)
+        tokens, targets = synth.tokens_and_targets(1, 16, vocab, 5003)
+        acts = dev(np.zeros((1, 1, 16), np.int32))
+        good = host(c2.schedule_loglik([w], head, dev(tokens), dev(targets), acts))
+        assert c2.device_status() == sol.OK
+        for which in ("token", "target"):
+            bad_tok, bad_tgt = tokens.copy(), targets.copy()
+            (bad_tok if which == "token" else bad_tgt)[0, 5] = vocab + 7
+            got = host(c2.schedule_loglik([w], head, dev(bad_tok), dev(bad_tgt), acts))
+            assert c2.device_status() == sol.ERR_INVALID_ARG and c2.device_status() == sol.OK
+            assert np.isfinite(got).all() and np.array_equal(got[0, 0, :5], good[0, 0, :5])   # earlier positions untouched
+        c2.close()
     # empty batch is a no-op
     x0 = torch.zeros((0, 8, shape.d_model), dtype=torch.bfloat16, device="cuda")
     ctx.layer_forward(w, x0, torch.zeros((0, 8), dtype=torch.int32, device="cuda"), kc[:0], vc[:0])
