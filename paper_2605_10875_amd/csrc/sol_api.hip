@@ -277,7 +277,7 @@ struct Carver {
 
 struct LayerWs {
     RowAct *ra; int32_t *row_bucket, *perm, *bucket_off, *seq_order;
-    void *h, *qb, *a, *vt, *pm;
+    void *h, *qb, *a, *vt, *kf, *pm;
     float *big32, *o32, *x2, *hn32;
 };
 
@@ -311,6 +311,8 @@ static void carve_layer(Carver &c, const sol_model_cfg &g, int64_t n_seq, int64_
     // transposed V copy for the tiled attention kernel (batched bf16 pass only)
     const bool tiled = g.dtype == SOL_BF16 && T >= 16 && L_max <= 4096;
     w.vt = c.take(tiled ? es * n_seq * g.n_kv_heads * g.head_dim * (size_t)attn_tile_lpadv(L_max) : 0);
+    // K in MFMA operand order for the threshold kernel
+    w.kf = c.take(tiled ? es * n_seq * g.n_kv_heads * g.head_dim * (size_t)attn_tile_lpadv(L_max) : 0);
     // per-key page extremes for the tiled kernels under the page rule
     w.pm = c.take(tiled && g.page_size > 1 ? attn_tile_pages_meta_bytes(n_seq, g.n_kv_heads, L_max, g.head_dim) : 0);
 }
@@ -419,8 +421,8 @@ static int attn_stage(sol_ctx *ctx, LayerWs &w, const int32_t *pos0, void *kc, v
         bool tiled = pv != nullptr;
         tiled = tiled || (dense_pass && mfma && w.vt && T >= 16 && L_max <= 4096 &&
                           launch_attn_tile_dense(w.qb, kc, vc, w.vt, w.o32, pos0, n_seq, T, L_max, Hq, Hkv, dh, st));
-        tiled = tiled || (fast && w.vt && T >= 16 && L_max <= 4096 &&
-                          launch_attn_tile(w.qb, kc, vc, w.vt, w.big32, w.o32, w.ra, pos0, n_seq, T, L_max, Hq, Hkv, dh, st));
+        tiled = tiled || (fast && w.vt && w.kf && T >= 16 && L_max <= 4096 &&
+                          launch_attn_tile(w.qb, kc, vc, w.vt, w.kf, w.big32, w.o32, w.ra, pos0, n_seq, T, L_max, Hq, Hkv, dh, st));
         if (!tiled && mfma && opt.page > 1 && w.vt && w.pm && T >= 16 && L_max <= 4096 &&
             attn_tile_pages_sel_bytes(M, Hq, L_max, opt.page) <= 4 * (size_t)M * nqkv)   // the masks live in big32
             tiled = launch_attn_tile_pages(w.qb, kc, vc, w.vt, w.pm, w.big32, w.o32, w.ra, pos0, n_seq, T, L_max, Hq, Hkv, dh, opt, st);

@@ -323,6 +323,7 @@ typedef float f32x4_a __attribute__((ext_vector_type(4)));
 // with 8 consecutive keys, which is exactly the A operand of the P V product.
 // =================================================================================================
 struct __align__(16) SelRow { float thr, mx; int jstar; int pad; };
+__host__ __device__ __forceinline__ int attn_lpad64(int L_max) { return (L_max + 63) & ~63; }
 
 // column (256*j + 4*lane + e order) of the quota-th key equal to thr; quota >= 1 and at most the
 // number of such keys
@@ -508,7 +509,11 @@ __device__ __forceinline__ void sel_row_load(const float *row, int n, int lane, 
 // PRE: keys [0, pv.P) of sequence s are read from the prefix cache of input s / pv.K (shared by the pv.K schedules
 // of that input), keys from pv.P on from the sequence's own cache kc, which holds positions pv.P.. only
 // ([n_seq][Hkv][crows][DH]); pv.P is a multiple of 64 and the two caches lie less than 2^31 elements apart.
-template <int BQ, int SLOTS, int DH, int NW, bool PRE>
+// KF (not with PRE): kc is the copy of the K cache in MFMA operand order written by k_frag_k, in which the 16 bytes a
+// lane feeds to one MFMA are contiguous over the lanes: a fragment load reads 1 KB in a row (8 full cache lines)
+// where the same load from the cache itself picks 64-byte pieces out of 16 rows. The values in the registers are
+// the same either way.
+template <int BQ, int SLOTS, int DH, int NW, bool PRE, bool KF>
 __global__ void __launch_bounds__(NW * 64)
 __attribute__((amdgpu_waves_per_eu(SLOTS <= 16 || (SLOTS <= 32 && DH <= 64) ? 4 : SLOTS <= 32 ? 3 : 2, SLOTS <= 16 ? 4 : 8)))
 k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRow *__restrict__ sel,
@@ -518,7 +523,7 @@ k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRo
     constexpr int LPAD = SLOTS * 64, LS = LPAD + 4;        // row stride = 4 mod 64 floats: the 16 query rows of a
                                                            // 128-bit store hit 16 different bank groups
     constexpr int RT = (BQ + 15) / 16, KK = DH / 32;
-    constexpr int UA = (SLOTS <= 16 && DH <= 64) ? 8 : 4;  // key tiles in flight per wave
+    constexpr int UA = (SLOTS <= 16 && DH <= 64) ? 8 : 4;  // key tiles held per wave
     extern __shared__ __align__(16) float sc[];            // [BQ][LS]
     __shared__ int next_row;
 
@@ -530,7 +535,8 @@ k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRo
     const int n_qb = (Tn + BQ - 1) / BQ;
     const int kvh = h / (Hq / Hkv);
     // wave-uniform bases + 32-bit per-lane offsets: one address register per load instead of two
-    const bf16_t *kbase = kc + ((int64_t)s * Hkv + kvh) * (int64_t)L_max * DH;
+    static_assert(!(PRE && KF), "the operand-order copy covers one cache per sequence");
+    const bf16_t *kbase = kc + ((int64_t)s * Hkv + kvh) * (int64_t)(KF ? attn_lpad64(L_max) : L_max) * DH;
     uint32_t kdelta = 0u;                                   // PRE: offset of the own cache (minus P rows) from the prefix cache
     if constexpr (PRE) {
         const bf16_t *own = kc + ((int64_t)s * Hkv + kvh) * (int64_t)pv.crows * DH - (int64_t)pv.P * DH;
@@ -540,8 +546,42 @@ k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRo
     const bf16_t *qbase = q + (int64_t)s * Tn * (int64_t)(Hq * DH) + (int64_t)h * DH;
     const int l16 = lane & 15, lg = lane >> 4;
 
-    bf16x8_a qf[RT][KK], kf[UA][KK];
-    // q fragments and the first group of K tiles of query block QB_ (lane (l16, lg): row l16, 8 values at 8*lg)
+    // Rows longer than what the waves hold at once (SLOTS > 16): two register sets of UH key tiles each, one in flight
+    // while the other is multiplied. Shorter rows: one set, all of it loaded while the block before is searched.
+    constexpr bool DB = SLOTS > 16;
+    constexpr int UH = DB ? UA / 2 : UA;
+    bf16x8_a qf[RT][KK], ka[UH][KK], kb[DB ? UH : 1][KK];
+    // K tile KT_ (clamped to the last tile / key of the block) into SET_[U_]: lane (l16, lg) gets 8 channels at 8*lg of
+    // key 16*tile + l16 for every 32-channel piece
+#define SOL_SEL_LOADK(SET_, U_, KT_, KEY0_, NKEYS_)                                                        \
+    {                                                                                                      \
+        if constexpr (KF) {                                                                                \
+            int kt_ = (KT_);                                                                               \
+            if (kt_ * 16 >= (NKEYS_)) kt_ = ((NKEYS_) - 1) >> 4;                                           \
+            const uint32_t fo = (uint32_t)kt_ * (uint32_t)(KK * 512) + (uint32_t)((KEY0_) * 8);            \
+            _Pragma("unroll") for (int kk = 0; kk < KK; ++kk)                                              \
+                SET_[U_][kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(kbase + fo + kk * 512)); \
+        } else {                                                                                           \
+            int key = (KEY0_) + (U_) * NW * 16;                                                            \
+            if (key >= (NKEYS_)) key = (NKEYS_) - 1;                                                       \
+            uint32_t ko = (uint32_t)key * (uint32_t)DH + (uint32_t)(lg * 8);                               \
+            if constexpr (PRE) ko += key >= pv.P ? kdelta : 0u;                                            \
+            _Pragma("unroll") for (int kk = 0; kk < KK; ++kk)                                              \
+                SET_[U_][kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(kbase + ko + kk * 32)); \
+        }                                                                                                  \
+    }
+    // group of UH tiles from this wave's tile T0_ on (stride NW), if the group has a tile below the block's last key.
+    // EACH_: tiles past the last key are not loaded (the prefetch of the next block, issued before a long search);
+    // otherwise they re-read the last tile, which keeps the loads of a group free of branches.
+#define SOL_SEL_LOADG(SET_, T0_, NKEYS_, EACH_)                                                            \
+    if ((T0_) * 16 < (NKEYS_)) {                                                                           \
+        int key0_ = KF ? lane : (T0_) * 16 + l16;                                                          \
+        asm volatile("" : "+v"(key0_));   /* recomputed per group: hoisted copies of all the indices spill */ \
+        _Pragma("unroll") for (int u = 0; u < UH; ++u) {                                                   \
+            if (!(EACH_) || ((T0_) + u * NW) * 16 < (NKEYS_)) SOL_SEL_LOADK(SET_, u, (T0_) + u * NW, key0_, NKEYS_) \
+        }                                                                                                  \
+    }
+    // q fragments and the first two groups of K tiles of query block QB_
 #define SOL_SEL_LOAD(QB_)                                                                                  \
     {                                                                                                      \
         const int q0_ = (QB_) * BQ;                                                                        \
@@ -553,29 +593,24 @@ k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRo
             _Pragma("unroll") for (int kk = 0; kk < KK; ++kk)                                              \
                 qf[rt][kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(qbase + qo + kk * 32)); \
         }                                                                                                  \
-        int key0_ = w * 16 + l16;                                                                          \
-        asm volatile("" : "+v"(key0_));   /* recomputed per visit: hoisted copies of all UA indices spill */ \
-        _Pragma("unroll") for (int u = 0; u < UA; ++u) {                                                   \
-            if ((w + u * NW) * 16 < nmax_) {                /* tiles beyond the block's last key are never used */ \
-                int key = key0_ + u * NW * 16;                                                             \
-                if (key >= nmax_) key = nmax_ - 1;                                                         \
-                uint32_t ko = (uint32_t)key * (uint32_t)DH + (uint32_t)(lg * 8);                           \
-                if constexpr (PRE) ko += key >= pv.P ? kdelta : 0u;                                        \
-                _Pragma("unroll") for (int kk = 0; kk < KK; ++kk)                                          \
-                    kf[u][kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(kbase + ko + kk * 32)); \
-            }                                                                                              \
-        }                                                                                                  \
+        SOL_SEL_LOADG(ka, w, nmax_, true)                                                                  \
+        if constexpr (DB) SOL_SEL_LOADG(kb, w + UH * NW, nmax_, true)                                      \
     }
     // S^T tile = K tile (rows) x Q^T (columns): lane (l16, lg) gets keys 4*lg..4*lg+3 of query l16
-#define SOL_SEL_MFMA(U_, KT_)                                                                              \
+#define SOL_SEL_MFMA(SET_, U_, KT_)                                                                        \
     _Pragma("unroll") for (int rt = 0; rt < RT; ++rt) {                                                    \
         floatx4_a acc = {0.f, 0.f, 0.f, 0.f};                                                              \
         _Pragma("unroll") for (int kk = 0; kk < KK; ++kk)                                                  \
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[U_][kk], qf[rt][kk], acc, 0, 0, 0);           \
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(SET_[U_][kk], qf[rt][kk], acc, 0, 0, 0);         \
         const int row = rt * 16 + l16;                                                                     \
         if (row < BQ)                                                                                      \
             *reinterpret_cast<f32x4_a *>(sc + row * LS + (KT_) * 16 + 4 * lg) =                            \
                 f32x4_a{acc[0] * scale, acc[1] * scale, acc[2] * scale, acc[3] * scale};                   \
+    }
+#define SOL_SEL_MFMAG(SET_, T0_)                                                                           \
+    _Pragma("unroll") for (int u = 0; u < UH; ++u) {                                                       \
+        const int kt = (T0_) + u * NW;                                                                     \
+        if (kt < n_kt) { SOL_SEL_MFMA(SET_, u, kt); }                                                      \
     }
 
     int visit = 0, qb = bi;
@@ -586,27 +621,22 @@ k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRo
         const int rows = (Tn - q0 < BQ) ? (Tn - q0) : BQ;
         const int n_max = p0 + q0 + rows;
         const int n_kt = (n_max + 15) >> 4;
-        // ---- scores of this block into LDS ----
-#pragma unroll
-        for (int u = 0; u < UA; ++u) {
-            const int kt = w + u * NW;
-            if (kt < n_kt) { SOL_SEL_MFMA(u, kt); }
-        }
-        for (int kt0 = w + NW * UA; kt0 < n_kt; kt0 += NW * UA) {      // rows longer than the prefetched group
-#pragma unroll
-            for (int u = 0; u < UA; ++u) {
-                int key = (kt0 + u * NW) * 16 + l16;
-                if (key >= n_max) key = n_max - 1;
-                uint32_t ko = (uint32_t)key * (uint32_t)DH + (uint32_t)(lg * 8);
-                if constexpr (PRE) ko += key >= pv.P ? kdelta : 0u;
-#pragma unroll
-                for (int kk = 0; kk < KK; ++kk)
-                    kf[u][kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(kbase + ko + kk * 32));
+        // ---- scores of this block into LDS: the loads of a group of tiles go out while the group before it is multiplied ----
+        constexpr int GS = UH * NW;                         // tiles per group over the workgroup
+        if constexpr (DB) {
+            for (int t0 = w;; t0 += 2 * GS) {
+                SOL_SEL_MFMAG(ka, t0)
+                SOL_SEL_LOADG(ka, t0 + 2 * GS, n_max, false)
+                if (t0 + GS >= n_kt) break;
+                SOL_SEL_MFMAG(kb, t0 + GS)
+                SOL_SEL_LOADG(kb, t0 + 3 * GS, n_max, false)
+                if (t0 + 2 * GS >= n_kt) break;
             }
-#pragma unroll
-            for (int u = 0; u < UA; ++u) {
-                const int kt = kt0 + u * NW;
-                if (kt < n_kt) { SOL_SEL_MFMA(u, kt); }
+        } else {
+            SOL_SEL_MFMAG(ka, w)
+            for (int t0 = w + GS; t0 < n_kt; t0 += GS) {
+                SOL_SEL_LOADG(ka, t0, n_max, false)
+                SOL_SEL_MFMAG(ka, t0)
             }
         }
         if (tid == 0) next_row = NW;
@@ -639,8 +669,11 @@ k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRo
         __syncthreads();                                   // every row is in registers or done: LDS may be overwritten
         qb = qb_next;
     }
+#undef SOL_SEL_LOADK
+#undef SOL_SEL_LOADG
 #undef SOL_SEL_LOAD
 #undef SOL_SEL_MFMA
+#undef SOL_SEL_MFMAG
 }
 
 // Unit hook: the row stage of k_attn_select (keys from an fp32 score row in LDS, threshold search, tie index) on caller
@@ -1825,11 +1858,36 @@ k_transpose_v(const bf16_t *__restrict__ vc, bf16_t *__restrict__ vt, const int3
     }
 }
 
-template <int BQ, int SLOTS, int DH, int NW, bool PRE = false>
+// K cache [s][kvh][key][dh] -> kfr [s][kvh][tile of 16 keys][dh / 32][64 lanes][8]: lane (l16, lg) of piece kk holds
+// channels 32*kk + 8*lg .. + 7 of key 16*tile + l16, the A operand of mfma_f32_16x16x32_bf16 for that tile; keys from
+// pos0[s] + Tn on are zero. attn_lpad64(L_max) keys per (s, kvh).
+template <int DH>
+__global__ void __launch_bounds__(256)
+k_frag_k(const bf16_t *__restrict__ kc, bf16_t *__restrict__ kfr, const int32_t *__restrict__ pos0, int Tn, int L_max, int Hkv,
+         int lpad)
+{
+    constexpr int KP = DH / 8, KK = DH / 32;                // 16-byte pieces per key
+    const int kb = blockIdx.x * 64, kvh = blockIdx.y, s = blockIdx.z;
+    const int p0 = pos0 ? pos0[s] : 0;
+    int len = p0 + Tn;
+    if (p0 < 0 || len > L_max) len = 0;
+    const bf16_t *src = kc + ((int64_t)s * Hkv + kvh) * (int64_t)L_max * DH;
+    bf16_t *dst = kfr + ((int64_t)s * Hkv + kvh) * (int64_t)lpad * DH;
+    for (int idx = threadIdx.x; idx < 64 * KP; idx += 256) {
+        const int key = kb + idx / KP, p = idx % KP;
+        if (key >= lpad) break;
+        u32x4_a v = {0u, 0u, 0u, 0u};
+        if (key < len) v = *reinterpret_cast<const u32x4_a *>(src + (int64_t)key * DH + p * 8);
+        const int tile = key >> 4, l16 = key & 15, kk = p >> 2, lg = p & 3;
+        *reinterpret_cast<u32x4_a *>(dst + ((int64_t)(tile * KK + kk) * 64 + lg * 16 + l16) * 8) = v;
+    }
+}
+
+template <int BQ, int SLOTS, int DH, int NW, bool PRE = false, bool KF = false>
 static bool launch_attn_select_t(const void *q, const void *kc, SelRow *sel, const RowAct *ra, const int32_t *pos0,
                                  int n_seq, int Tn, int L_max, int Hq, int Hkv, hipStream_t st, PrefixView pv = PrefixView())
 {
-    auto kern = k_attn_select<BQ, SLOTS, DH, NW, PRE>;
+    auto kern = k_attn_select<BQ, SLOTS, DH, NW, PRE, KF>;
     const size_t lds = (size_t)BQ * (SLOTS * 64 + 4) * 4;
     static bool attr_done = false;
     if (!attr_done) {
@@ -2309,10 +2367,10 @@ k_attn_pv_pages(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, con
     }   // pass
 }
 
-int attn_tile_lpadv(int L_max) { return (L_max + 63) & ~63; }
+int attn_tile_lpadv(int L_max) { return attn_lpad64(L_max); }
 size_t attn_tile_sel_bytes(int64_t rows, int Hq) { return (size_t)rows * Hq * sizeof(SelRow); }
 
-bool launch_attn_tile(const void *q, const void *k_cache, const void *v_cache, void *vt, void *sel_ws, float *o32,
+bool launch_attn_tile(const void *q, const void *k_cache, const void *v_cache, void *vt, void *kfr, void *sel_ws, float *o32,
                       const RowAct *ra, const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv, int dh,
                       hipStream_t st)
 {
@@ -2329,16 +2387,23 @@ bool launch_attn_tile(const void *q, const void *k_cache, const void *v_cache, v
     else
         hipLaunchKernelGGL((k_transpose_v<128>), tg, dim3(256), 0, st, (const bf16_t *)v_cache, (bf16_t *)vt, pos0, T,
                            L_max, Hkv, lpadv);
+    // Long rows: K in MFMA operand order for the threshold kernel, which reads all causal keys once per block of 8 query
+    // rows (up to 1024 keys a block has 16 rows and the copy does not pay)
+    const bool frag = L_max > 1024;
+    if (frag && dh == 64)
+        hipLaunchKernelGGL((k_frag_k<64>), tg, dim3(256), 0, st, (const bf16_t *)k_cache, (bf16_t *)kfr, pos0, T, L_max, Hkv, lpadv);
+    else if (frag)
+        hipLaunchKernelGGL((k_frag_k<128>), tg, dim3(256), 0, st, (const bf16_t *)k_cache, (bf16_t *)kfr, pos0, T, L_max, Hkv, lpadv);
     // score rows of a workgroup stay in LDS: 16 rows x 1024 keys (66 KB) lets two workgroups share a CU
     bool ok;
-#define SOL_SEL(BQ, SL)                                                                                              \
-    ok = dh == 64 ? launch_attn_select_t<BQ, SL, 64, 8>(q, k_cache, sel, ra, pos0, n_seq, T, L_max, Hq, Hkv, st)     \
-                  : launch_attn_select_t<BQ, SL, 128, 8>(q, k_cache, sel, ra, pos0, n_seq, T, L_max, Hq, Hkv, st)
-    if (L_max <= 256) { SOL_SEL(32, 4); }
-    else if (L_max <= 1024) { SOL_SEL(16, 16); }
-    else if (L_max <= 1280) { SOL_SEL(8, 20); }             // a 1024-token prefix plus a short episode
-    else if (L_max <= 2048) { SOL_SEL(8, 32); }
-    else { SOL_SEL(8, 64); }
+#define SOL_SEL(BQ, SL, KF)                                                                                          \
+    ok = dh == 64 ? launch_attn_select_t<BQ, SL, 64, 8, false, KF>(q, KF ? kfr : k_cache, sel, ra, pos0, n_seq, T, L_max, Hq, Hkv, st)  \
+                  : launch_attn_select_t<BQ, SL, 128, 8, false, KF>(q, KF ? kfr : k_cache, sel, ra, pos0, n_seq, T, L_max, Hq, Hkv, st)
+    if (L_max <= 256) { SOL_SEL(32, 4, false); }
+    else if (L_max <= 1024) { SOL_SEL(16, 16, false); }
+    else if (L_max <= 1280) { SOL_SEL(8, 20, true); }       // a 1024-token prefix plus a short episode
+    else if (L_max <= 2048) { SOL_SEL(8, 32, true); }
+    else { SOL_SEL(8, 64, true); }
 #undef SOL_SEL
     if (!ok) return false;
 #define SOL_PV(G_)                                                                                                   \

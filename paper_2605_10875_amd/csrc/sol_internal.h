@@ -164,9 +164,9 @@ bool launch_attn_tile_pages_prefix(const void *q, const void *k_cache, const voi
                                    int dh, AttnOpts opt, PrefixView pv, hipStream_t st);
 // Batched bf16 attention (L_max <= 4096, head_dim 64 or 128, 1/2/4/8 query heads per KV head): a threshold
 // kernel followed by a flash-style masked softmax * V kernel. vt is workspace for the transposed V copy
-// (n_seq * Hkv * dh * attn_tile_lpadv(L_max) elements), sel_ws for the per-(row, head) thresholds
-// (attn_tile_sel_bytes(rows, Hq) bytes).
-bool launch_attn_tile(const void *q, const void *k_cache, const void *v_cache, void *vt, void *sel_ws, float *o32,
+// (n_seq * Hkv * dh * attn_tile_lpadv(L_max) elements), kfr for the copy of K in MFMA operand order (as many),
+// sel_ws for the per-(row, head) thresholds (attn_tile_sel_bytes(rows, Hq) bytes).
+bool launch_attn_tile(const void *q, const void *k_cache, const void *v_cache, void *vt, void *kfr, void *sel_ws, float *o32,
                       const RowAct *ra, const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv, int dh,
                       hipStream_t st);
 size_t attn_tile_sel_bytes(int64_t rows, int Hq);
