@@ -27,7 +27,8 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16_t;
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));   // native 16-byte vector (stays in registers)
 
 constexpr int BK = 64;               // K step (bf16 elements); one LDS row = 128 bytes = 8 chunks of 16 B
-constexpr int GROUP_M = 8;           // tile rows walked together by an XCD
+constexpr int GROUP_M = 4;           // tile rows walked together by an XCD: its 32 CUs then hold 4 x 8 tiles (measured on the
+                                     // 16 x 2048-token stack: 2, 4 within 1 %; 8: 2 - 4 % slower; 16: 4 - 8 % slower)
 // LDS has 64 banks of 4 bytes (256 B per clock): two 128-byte rows share one bank row, so the
 // 16-byte chunk index is XOR-ed with bits 1..3 of the row. Measured SQ_LDS_BANK_CONFLICT drops 32x
 // against swizzling with bits 0..2.
