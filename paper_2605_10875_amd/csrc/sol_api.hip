@@ -1037,6 +1037,8 @@ static int episode_impl(sol_ctx *ctx, const sol_model_weights *mw, const int32_t
             PrefixView pv;
             pv.k = (const bf16_t *)w.pkc; pv.vt = (const bf16_t *)w.pre.vt;
             pv.P = P; pv.K = K; pv.lpadv = attn_tile_lpadv(P); pv.crows = T;
+            if (g.page_size <= 1 && P + T > 1024 && w.pre.kf && launch_attn_frag_k(w.pkc, w.pre.kf, nullptr, B, P, P, g.n_kv_heads, g.head_dim, st))
+                pv.kf = (const bf16_t *)w.pre.kf;     // long rows: the threshold kernel reads the prefix keys in operand order
             if (g.page_size > 1) {   // page rule: the prefix keys' metadata rows, once per input (the dense prefix pass has no use for them)
                 if (!launch_page_prefix_meta(w.pkc, w.pre.pm, B, P, g.n_kv_heads, g.head_dim, g.page_size, st))
                     return fail(ctx, SOL_ERR_UNSUPPORTED, "shared-prefix attention: page size outside the tiled kernels");

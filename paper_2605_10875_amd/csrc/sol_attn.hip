@@ -509,10 +509,10 @@ __device__ __forceinline__ void sel_row_load(const float *row, int n, int lane, 
 // PRE: keys [0, pv.P) of sequence s are read from the prefix cache of input s / pv.K (shared by the pv.K schedules
 // of that input), keys from pv.P on from the sequence's own cache kc, which holds positions pv.P.. only
 // ([n_seq][Hkv][crows][DH]); pv.P is a multiple of 64 and the two caches lie less than 2^31 elements apart.
-// KF (not with PRE): kc is the copy of the K cache in MFMA operand order written by k_frag_k, in which the 16 bytes a
-// lane feeds to one MFMA are contiguous over the lanes: a fragment load reads 1 KB in a row (8 full cache lines)
-// where the same load from the cache itself picks 64-byte pieces out of 16 rows. The values in the registers are
-// the same either way.
+// KF: kc (with PRE: pv.kf, for the prefix keys) is the copy of the K cache in MFMA operand order written by k_frag_k,
+// in which the 16 bytes a lane feeds to one MFMA are contiguous over the lanes: a fragment load reads 1 KB in a row
+// (8 full cache lines) where the same load from the cache itself picks 64-byte pieces out of 16 rows. The values in
+// the registers are the same either way. With PRE the sequence's own keys (positions pv.P..) still come from its cache.
 template <int BQ, int SLOTS, int DH, int NW, bool PRE, bool KF>
 __global__ void __launch_bounds__(NW * 64)
 __attribute__((amdgpu_waves_per_eu(SLOTS <= 16 || (SLOTS <= 32 && DH <= 64) ? 4 : SLOTS <= 32 ? 3 : 2, SLOTS <= 16 ? 4 : 8)))
@@ -535,12 +535,11 @@ k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRo
     const int n_qb = (Tn + BQ - 1) / BQ;
     const int kvh = h / (Hq / Hkv);
     // wave-uniform bases + 32-bit per-lane offsets: one address register per load instead of two
-    static_assert(!(PRE && KF), "the operand-order copy covers one cache per sequence");
     const bf16_t *kbase = kc + ((int64_t)s * Hkv + kvh) * (int64_t)(KF ? attn_lpad64(L_max) : L_max) * DH;
     uint32_t kdelta = 0u;                                   // PRE: offset of the own cache (minus P rows) from the prefix cache
     if constexpr (PRE) {
         const bf16_t *own = kc + ((int64_t)s * Hkv + kvh) * (int64_t)pv.crows * DH - (int64_t)pv.P * DH;
-        kbase = pv.k + ((int64_t)(s / pv.K) * Hkv + kvh) * (int64_t)pv.P * DH;
+        kbase = (KF ? pv.kf : pv.k) + ((int64_t)(s / pv.K) * Hkv + kvh) * (int64_t)pv.P * DH;
         kdelta = (uint32_t)__builtin_amdgcn_readfirstlane((int)(own - kbase));
     }
     const bf16_t *qbase = q + (int64_t)s * Tn * (int64_t)(Hq * DH) + (int64_t)h * DH;
@@ -555,7 +554,18 @@ k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRo
     // key 16*tile + l16 for every 32-channel piece
 #define SOL_SEL_LOADK(SET_, U_, KT_, KEY0_, NKEYS_)                                                        \
     {                                                                                                      \
-        if constexpr (KF) {                                                                                \
+        if constexpr (KF && PRE) {      /* prefix tiles from the operand-order copy, own tiles from the own cache */ \
+            int kt_ = (KT_);                                                                               \
+            if (kt_ * 16 >= (NKEYS_)) kt_ = ((NKEYS_) - 1) >> 4;                                           \
+            const bool in_pre = kt_ * 16 < pv.P;            /* wave-uniform; pv.P is a multiple of 64 */   \
+            int key = kt_ * 16 + l16;                                                                      \
+            if (key >= (NKEYS_)) key = (NKEYS_) - 1;                                                       \
+            const uint32_t off = in_pre ? (uint32_t)kt_ * (uint32_t)(KK * 512) + (uint32_t)(lane * 8)      \
+                                        : kdelta + (uint32_t)key * (uint32_t)DH + (uint32_t)(lg * 8);      \
+            const uint32_t step = in_pre ? 512u : 32u;                                                     \
+            _Pragma("unroll") for (int kk = 0; kk < KK; ++kk)                                              \
+                SET_[U_][kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(kbase + off + kk * step)); \
+        } else if constexpr (KF) {                                                                         \
             int kt_ = (KT_);                                                                               \
             if (kt_ * 16 >= (NKEYS_)) kt_ = ((NKEYS_) - 1) >> 4;                                           \
             const uint32_t fo = (uint32_t)kt_ * (uint32_t)(KK * 512) + (uint32_t)((KEY0_) * 8);            \
@@ -2370,6 +2380,19 @@ k_attn_pv_pages(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, con
 int attn_tile_lpadv(int L_max) { return attn_lpad64(L_max); }
 size_t attn_tile_sel_bytes(int64_t rows, int Hq) { return (size_t)rows * Hq * sizeof(SelRow); }
 
+bool launch_attn_frag_k(const void *k_cache, void *kfr, const int32_t *pos0, int n_seq, int T, int L_max, int Hkv, int dh,
+                        hipStream_t st)
+{
+    if ((dh != 64 && dh != 128) || n_seq <= 0 || T <= 0 || L_max <= 0) return false;
+    const int lpad = attn_lpad64(L_max);
+    const dim3 tg(lpad / 64, Hkv, n_seq);
+    if (dh == 64)
+        hipLaunchKernelGGL((k_frag_k<64>), tg, dim3(256), 0, st, (const bf16_t *)k_cache, (bf16_t *)kfr, pos0, T, L_max, Hkv, lpad);
+    else
+        hipLaunchKernelGGL((k_frag_k<128>), tg, dim3(256), 0, st, (const bf16_t *)k_cache, (bf16_t *)kfr, pos0, T, L_max, Hkv, lpad);
+    return true;
+}
+
 bool launch_attn_tile(const void *q, const void *k_cache, const void *v_cache, void *vt, void *kfr, void *sel_ws, float *o32,
                       const RowAct *ra, const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv, int dh,
                       hipStream_t st)
@@ -2390,10 +2413,7 @@ bool launch_attn_tile(const void *q, const void *k_cache, const void *v_cache, v
     // Long rows: K in MFMA operand order for the threshold kernel, which reads all causal keys once per block of 8 query
     // rows (up to 1024 keys a block has 16 rows and the copy does not pay)
     const bool frag = L_max > 1024;
-    if (frag && dh == 64)
-        hipLaunchKernelGGL((k_frag_k<64>), tg, dim3(256), 0, st, (const bf16_t *)k_cache, (bf16_t *)kfr, pos0, T, L_max, Hkv, lpadv);
-    else if (frag)
-        hipLaunchKernelGGL((k_frag_k<128>), tg, dim3(256), 0, st, (const bf16_t *)k_cache, (bf16_t *)kfr, pos0, T, L_max, Hkv, lpadv);
+    if (frag && !launch_attn_frag_k(k_cache, kfr, pos0, n_seq, T, L_max, Hkv, dh, st)) return false;
     // score rows of a workgroup stay in LDS: 16 rows x 1024 keys (66 KB) lets two workgroups share a CU
     bool ok;
 #define SOL_SEL(BQ, SL, KF)                                                                                          \
@@ -2431,11 +2451,15 @@ bool attn_tile_prefix_ok(const void *k_cache, int n_seq, int T, int Hq, int Hkv,
     // (own cache of (s, kvh), minus P rows) - (prefix cache of (s / K, kvh)) must lie in [0, 2^31 - a row span) for
     // every (s, kvh); the difference is linear in input, schedule and head, so the corners decide
     if (n_seq % pv.K) return false;
-    const int64_t base = (const bf16_t *)k_cache - pv.k - (int64_t)pv.P * dh;
-    for (int c = 0; c < 8; ++c) {
-        const int64_t b = (c & 1) ? n_seq / pv.K - 1 : 0, k = (c & 2) ? pv.K - 1 : 0, kv = (c & 4) ? Hkv - 1 : 0;
-        const int64_t diff = base + ((b * pv.K + k) * Hkv + kv) * (int64_t)pv.crows * dh - (b * Hkv + kv) * (int64_t)pv.P * dh;
-        if (diff < 0 || diff >= (1ll << 31) - (int64_t)(L_max + 1) * dh) return false;
+    // (the same from the prefix's copy in operand order, when the view has one: same shape, same strides)
+    for (const bf16_t *pre : {pv.k, pv.kf}) {
+        if (!pre) continue;
+        const int64_t base = (const bf16_t *)k_cache - pre - (int64_t)pv.P * dh;
+        for (int c = 0; c < 8; ++c) {
+            const int64_t b = (c & 1) ? n_seq / pv.K - 1 : 0, k = (c & 2) ? pv.K - 1 : 0, kv = (c & 4) ? Hkv - 1 : 0;
+            const int64_t diff = base + ((b * pv.K + k) * Hkv + kv) * (int64_t)pv.crows * dh - (b * Hkv + kv) * (int64_t)pv.P * dh;
+            if (diff < 0 || diff >= (1ll << 31) - (int64_t)(L_max + 1) * dh) return false;
+        }
     }
     return true;
 }
@@ -2445,6 +2469,7 @@ bool launch_attn_tile_prefix(const void *q, const void *k_cache, const void *v_c
                              hipStream_t st)
 {
     if ((int64_t)n_seq * T <= 0) return true;
+    if (pv.kf && !attn_tile_prefix_ok(k_cache, n_seq, T, Hq, Hkv, dh, pv)) pv.kf = nullptr;   // copy out of reach: do without
     if (!pv.k || !pv.vt || !attn_tile_prefix_ok(k_cache, n_seq, T, Hq, Hkv, dh, pv)) return false;
     const int G = Hq / Hkv, L_max = pv.P + T;
     const int lpadv = attn_tile_lpadv(pv.crows);
@@ -2457,14 +2482,20 @@ bool launch_attn_tile_prefix(const void *q, const void *k_cache, const void *v_c
         hipLaunchKernelGGL((k_transpose_v<128>), tg, dim3(256), 0, st, (const bf16_t *)v_cache, (bf16_t *)vt,
                            (const int32_t *)nullptr, T, pv.crows, Hkv, lpadv);
     bool ok;
-#define SOL_SEL(BQ, SL)                                                                                              \
-    ok = dh == 64 ? launch_attn_select_t<BQ, SL, 64, 8, true>(q, k_cache, sel, ra, pos0, n_seq, T, L_max, Hq, Hkv, st, pv) \
-                  : launch_attn_select_t<BQ, SL, 128, 8, true>(q, k_cache, sel, ra, pos0, n_seq, T, L_max, Hq, Hkv, st, pv)
-    if (L_max <= 256) { SOL_SEL(32, 4); }
-    else if (L_max <= 1024) { SOL_SEL(16, 16); }
-    else if (L_max <= 1280) { SOL_SEL(8, 20); }
-    else if (L_max <= 2048) { SOL_SEL(8, 32); }
-    else { SOL_SEL(8, 64); }
+    // rows longer than 1024 keys read the prefix keys from their copy in operand order, if the view has one
+#define SOL_SEL(BQ, SL, KF)                                                                                          \
+    ok = dh == 64 ? launch_attn_select_t<BQ, SL, 64, 8, true, KF>(q, k_cache, sel, ra, pos0, n_seq, T, L_max, Hq, Hkv, st, pv) \
+                  : launch_attn_select_t<BQ, SL, 128, 8, true, KF>(q, k_cache, sel, ra, pos0, n_seq, T, L_max, Hq, Hkv, st, pv)
+    if (L_max <= 256) { SOL_SEL(32, 4, false); }
+    else if (L_max <= 1024) { SOL_SEL(16, 16, false); }
+    else if (!pv.kf) {
+        if (L_max <= 1280) { SOL_SEL(8, 20, false); }
+        else if (L_max <= 2048) { SOL_SEL(8, 32, false); }
+        else { SOL_SEL(8, 64, false); }
+    }
+    else if (L_max <= 1280) { SOL_SEL(8, 20, true); }
+    else if (L_max <= 2048) { SOL_SEL(8, 32, true); }
+    else { SOL_SEL(8, 64, true); }
 #undef SOL_SEL
     if (!ok) return false;
 #define SOL_PV(G_)                                                                                                   \

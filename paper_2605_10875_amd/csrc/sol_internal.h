@@ -154,6 +154,7 @@ bool launch_attn_decode_paged(const void *q, const void *k_cache, const void *v_
 // cache then holds positions P.. only, crows rows per (sequence, KV head). P a multiple of 64.
 struct PrefixView {
     const bf16_t *k = nullptr, *vt = nullptr;
+    const bf16_t *kf = nullptr;           // optional: the prefix K caches in MFMA operand order (launch_attn_frag_k)
     int P = 0, K = 1, lpadv = 0, crows = 0;
     const bf16_t *pm = nullptr;           // page rule: metadata rows of the prefix keys ([inputs][Hkv][P][2 * dh])
 };
@@ -170,6 +171,10 @@ bool launch_attn_tile(const void *q, const void *k_cache, const void *v_cache, v
                       const RowAct *ra, const int32_t *pos0, int n_seq, int T, int L_max, int Hq, int Hkv, int dh,
                       hipStream_t st);
 size_t attn_tile_sel_bytes(int64_t rows, int Hq);
+// K cache [n_seq][Hkv][L_max][dh] -> kfr [n_seq][Hkv][attn_tile_lpadv(L_max) / 16][dh / 32][64][8], the order in which
+// the threshold kernel's MFMAs take it (keys from pos0[s] + T on are zero; pos0 == nullptr: 0). False: head size.
+bool launch_attn_frag_k(const void *k_cache, void *kfr, const int32_t *pos0, int n_seq, int T, int L_max, int Hkv, int dh,
+                        hipStream_t st);
 // The same for sequences that share prefix caches: k_cache / v_cache hold positions pv.P.. only, vt is scratch for
 // their transposed copy (n_seq * Hkv * dh * attn_tile_lpadv(pv.crows) elements); the T rows of every sequence sit at
 // positions pv.P.. (pos0 must say so). False if a shape or address limit is not met (nothing launched).
