@@ -86,6 +86,39 @@ def test_attention_stage_on_the_oracles_q_k_v(shape, n_seq, T):
         assert (diff > 1).sum() == 0 and share <= 2 * q_max * 1e-4 + 1e-4
 
 
+@pytest.mark.parametrize("shape,L_max,starts,T", [
+    (HD64, 1300, (1200, 1000, 0), 70),          # 2048-key variant, cache lengths 1270 / 1070 / 70 in one launch
+    (HD128, 2500, (2400, 17), 96),              # 4096-key variant, head size 128
+], ids=["dh64-L1300", "dh128-L2500"])
+def test_attention_stage_on_a_chunk_behind_a_cache_prefix(shape, L_max, starts, T):
+    """The chunk's T rows sit at positions pos0[s] .. pos0[s] + T - 1 of caches that already hold pos0[s] keys (different
+    per sequence, L_max not a multiple of the kernels' tiles): the oracle first runs the prefix to fill the caches, then
+    the chunk; the GPU stage gets the oracle's rotated q of the chunk and the oracle's caches."""
+    table = synth.TABLE_C2
+    n_seq = len(starts)
+    w = synth.layer_weights(shape, 9200, bf16=True, std=0.05)
+    cfg, tab = oracle.make_cfg(shape, act_bf16=True), oracle.make_table(table)
+    kc = np.zeros((n_seq, shape.n_kv_heads, L_max, shape.head_dim), np.float32)
+    vc = np.zeros_like(kc)
+    for s, p in enumerate(starts):               # prefixes of different lengths, one sequence at a time
+        if p:
+            xp = synth.hidden_states(1, p, shape.d_model, 9210 + s, bf16=True)
+            idp = synth.iid_actions(len(table), (1, p), 9220 + s)
+            oracle.layer_forward(cfg, tab, w, xp, idp, kc[s:s + 1], vc[s:s + 1])
+    x = synth.hidden_states(n_seq, T, shape.d_model, 9201, bf16=True)
+    ids = synth.iid_actions(len(table), (n_seq, T), 9202)
+    pos0 = np.array(starts, np.int32)
+    _, tp = oracle.layer_forward(cfg, tab, w, x, ids, kc, vc, pos0=pos0, taps=("q_rot", "attn_out"))
+    ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=L_max)
+    o = host(ctx.test_attention_stage(dev(tp["q_rot"], sol.BF16), dev(ids), dev(kc, sol.BF16), dev(vc, sol.BF16), pos0=dev(pos0)))
+    assert ctx.device_status() == sol.OK
+    ctx.close()
+    err = _row_err(o, tp["attn_out"])
+    print(f"attention stage behind a prefix, dh={shape.head_dim} L_max={L_max}: row err median {np.median(err):.2e} "
+          f"max {err.max():.2e}; rows over 1e-3: {(err > 1e-3).mean():.4f}")
+    assert err.max() < 2e-2 and np.median(err) < 1e-4 and (err > 1e-3).mean() <= 0.01
+
+
 def _codes(a, bits):
     """integer codes of a stored (dequantised) row: the row's largest magnitude is q_max steps"""
     q_max = 2 ** (bits - 1) - 1
