@@ -337,7 +337,7 @@ static void carve_stack(Carver &c, const sol_model_cfg &g, int64_t n_seq, int64_
     carve_layer(c, g, n_seq, T, own_cache ? (int)T : 1 << 30, w.layer);
     w.xa = c.take(es * M * g.d_model);
     w.xb = c.take(es * M * g.d_model);
-    w.hf = c.take(es * M * g.d_model);
+    w.hf = c.take(es * gemm_nll_hf_rows(M) * g.d_model);          // the fused LM head reads whole tiles of rows
     const size_t cache = own_cache ? es * n_seq * g.n_kv_heads * T * g.head_dim : 0;
     w.kc = c.take(cache);
     w.vc = c.take(cache);
@@ -935,7 +935,7 @@ static void carve_episode_as(Carver &c, const sol_model_cfg &g, int64_t B, int64
     carve_layer(c, g, N, T, (int)(twoseg ? T : P + T), w.suf);
     w.st.xa = c.take(es * M * g.d_model);
     w.st.xb = c.take(es * M * g.d_model);
-    w.st.hf = c.take(es * M * g.d_model);
+    w.st.hf = c.take(es * gemm_nll_hf_rows(M) * g.d_model);
     const size_t sc = es * N * g.n_kv_heads * (twoseg ? T : P + T) * g.head_dim;
     w.st.kc = c.take(sc);
     w.st.vc = c.take(sc);

@@ -267,65 +267,9 @@ k_row_positions(const int32_t *__restrict__ pos0, int64_t M, int Tn, int L_max, 
     row_sp[row] = make_int2(s, bad ? -1 : p0 + i);
 }
 
-// LM head with the logits never written: per (row, 128-column wave tile) the maximum and the sum of
-// exp(logit - maximum), and the target's logit where the tile holds it; k_nll_finish folds the tiles of a
-// row into  logsumexp(logits) - logits[target]  (Method, Eq. 1, negated).
-template <class Op> __device__ __forceinline__ float reduce32(float v, Op op)
-{
-    // lanes 0..31 and 32..63 hold different rows: reduce within each half, result in every lane of the half
-    v = op(v, SOL_DPP(float, v, v, 0xB1, 0xF));     // quad_perm [1,0,3,2]
-    v = op(v, SOL_DPP(float, v, v, 0x4E, 0xF));     // quad_perm [2,3,0,1]
-    v = op(v, SOL_DPP(float, v, v, 0x141, 0xF));    // row_half_mirror
-    v = op(v, SOL_DPP(float, v, v, 0x140, 0xF));    // row_mirror
-    v = op(v, __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F)));   // lane ^ 16
-    return v;
-}
-struct OpMaxF { __device__ __forceinline__ float operator()(float a, float b) const { return fmaxf(a, b); } };
-
-struct AuxTgt { int t0, t1; };
-
-struct EpiNllPart {
-    static constexpr bool persistent_walk = true;
-    float2 *part;               // [M][n_wt]
-    float *tgt_logit;           // [M]
-    const int32_t *row_tgt;     // [M] target token of each row, inside [0, V)
-    int n_wt;
-    template <int TN> using Aux = AuxTgt;
-    template <int TN> __device__ __forceinline__ void preload0(int64_t row0, int64_t row1, AuxTgt &x) const
-    {
-        x.t0 = row_tgt[row0];
-        x.t1 = row_tgt[row1];
-    }
-    template <int TN> __device__ __forceinline__ void preload(int64_t, int64_t, bool, bool, int, int, AuxTgt &) const {}
-    template <int TN>
-    __device__ __forceinline__ void one_row(int64_t row, bool ok, int vcol0, int c, const float (&v)[TN], int tg) const
-    {
-        float mx = v[0];
-#pragma unroll
-        for (int j = 1; j < TN; ++j) mx = fmaxf(mx, v[j]);
-        mx = reduce32(mx, OpMaxF());
-        float se = 0.f;
-#pragma unroll
-        for (int j = 0; j < TN; ++j) se += __expf(v[j] - mx);
-        se = reduce32(se, OpAddF());
-        if (ok && c == 0) part[row * n_wt + vcol0 / (TN * 32)] = make_float2(mx, se);
-        const int rel = tg - vcol0;                     // the target's column inside this wave tile, if any
-        if (ok && rel >= 0 && rel < TN * 32 && (rel & 31) == c) {
-            float t = v[0];
-#pragma unroll
-            for (int j = 1; j < TN; ++j) t = (rel >> 5) == j ? v[j] : t;
-            tgt_logit[row] = t;
-        }
-    }
-    template <int TN>
-    __device__ __forceinline__ void rows2(int64_t row0, bool ok0, bool ok1, int vcol0, int c, const float (&v0)[TN],
-                                          const float (&v1)[TN], const AuxTgt &x) const
-    {
-        one_row<TN>(row0, ok0, vcol0, c, v0, x.t0);
-        one_row<TN>(row0 + 1, ok1, vcol0, c, v1, x.t1);
-    }
-};
-
+// LM head with the logits never written: per (token, tile of 128 vocabulary entries) the maximum and the sum of
+// exp(logit - maximum); k_nll_finish_cols folds the tiles of a token into  logsumexp(logits) - logits[target]
+// (Method, Eq. 1, negated), the target's logit coming from k_target_logit.
 // target token of every row (teacher-forced rows (b, g, t) share the targets of input b when broadcast_g)
 __global__ void __launch_bounds__(256)
 k_row_targets(const int32_t *__restrict__ targets, int64_t M, int G, int Tn, int broadcast_g, int V, int32_t *__restrict__ row_tgt,
@@ -342,26 +286,115 @@ k_row_targets(const int32_t *__restrict__ targets, int64_t M, int G, int Tn, int
     row_tgt[r] = tg;
 }
 
-// one wave per row: nll = max + log(sum_t s_t * exp(m_t - max)) - target logit
+// The product's rows are the vocabulary entries (A = the head's weights), its columns the tokens (B = the hidden
+// states, padded with zero rows to a multiple of the tile). A lane of the
+// accumulator layout then holds, for each of its TN tokens, 16 * TM logits of that token (the wave tile's 128 vocabulary
+// rows are split between the two halves of the wave), so the maximum and the sum of exponentials per (token, tile) are
+// sums over the lane's own registers plus ONE exchange with lane ^ 32 (with tokens as rows a lane holds one column
+// and every row costs two five-step butterflies), and the big operand (525 MB of weights at the Llama vocabulary) is
+// the one that each XCD streams once, while the hidden states, which the memory-side cache holds, are the ones read
+// again. part: [V / 128][Mp] (token fastest: a half-wave stores 32 consecutive entries; Mp = padded token count).
+// What a token gets does not depend on the other tokens of the call. The target's logit comes from k_target_logit,
+// since a lane would have to search its registers for it.
+__device__ __forceinline__ float swap_halves(float v, int lane)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, __builtin_bit_cast(int, v)));
+}
+struct EpiNllCols {
+    static constexpr bool persistent_walk = true;
+    static constexpr bool whole_tile = true;
+    float2 *part;               // [V / 128][Mp]
+    int64_t M;                  // Mp: tokens, padded to the tile
+    template <int TM, int TN>
+    __device__ __forceinline__ void tile(const floatx16_t (&acc)[TM][TN], int64_t vrow_w, int tcol_w, int lane) const
+    {
+        constexpr float LOG2E = 1.44269504088896341f;
+        float2 *dst = part + (vrow_w / (TM * 32)) * M + tcol_w + (lane & 31);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            float m = acc[0][j][0];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) m = fmaxf(m, acc[i][j][r]);
+            m = fmaxf(m, swap_halves(m, lane));
+            const float ml = m * LOG2E;
+            float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; r += 2) {
+                    s0 += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[i][j][r], LOG2E, -ml));
+                    s1 += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[i][j][r + 1], LOG2E, -ml));
+                }
+            float se = s0 + s1;
+            se += swap_halves(se, lane);
+            if (lane < 32) dst[32 * j] = make_float2(m, se);
+        }
+    }
+};
+
+// logit of each row's target: one wave per row, hf[r] . lm_head[target(r)] in fp32
 __global__ void __launch_bounds__(256)
-k_nll_finish(const float2 *__restrict__ part, const float *__restrict__ tgt_logit, int n_wt, int64_t M, float *__restrict__ nll)
+k_target_logit(const bf16_t *__restrict__ hf, const bf16_t *__restrict__ lm_head, const int32_t *__restrict__ row_tgt, int64_t M,
+               int K, float *__restrict__ tgt_logit)
 {
     const int lane = threadIdx.x & 63;
     const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (r >= M) return;
-    const float2 *p = part + r * n_wt;
-    float mx = -INFINITY;
-    for (int t = lane; t < n_wt; t += 64) mx = fmaxf(mx, p[t].x);
-    mx = wave_reduce_dpp<float>(mx, -INFINITY, OpMaxF());
-    float se = 0.f;
-    for (int t = lane; t < n_wt; t += 64) { const float2 q = p[t]; se += q.y * expf(q.x - mx); }
-    se = wave_sum_dpp(se);
-    if (lane == 0) nll[r] = (mx + logf(se)) - tgt_logit[r];
+    const bf16_t *a = hf + r * K, *b = lm_head + (int64_t)row_tgt[r] * K;
+    float acc = 0.f;
+    for (int k = lane * 8; k < K; k += 512) {
+        const uint4 x = *reinterpret_cast<const uint4 *>(a + k), y = *reinterpret_cast<const uint4 *>(b + k);
+        const uint32_t xs[4] = {x.x, x.y, x.z, x.w}, ys[4] = {y.x, y.y, y.z, y.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            acc = __builtin_fmaf(__uint_as_float(xs[e] << 16), __uint_as_float(ys[e] << 16), acc);
+            acc = __builtin_fmaf(__uint_as_float(xs[e] & 0xFFFF0000u), __uint_as_float(ys[e] & 0xFFFF0000u), acc);
+        }
+    }
+    acc = wave_sum_dpp(acc);
+    if (lane == 0) tgt_logit[r] = acc;
+}
+
+// nll = max + log(sum_t s_t * exp(m_t - max)) - target logit over part [n_wt][Mp]. A workgroup takes 64 rows; wave q
+// folds the tiles t = q, q + 16, ... of its 64 rows with a running maximum (a wave reads 64 consecutive entries of a
+// tile), then the 16 partial results of a row are folded in wave order: the same sequence of operations for every
+// row, whatever the batch.
+constexpr int NLL_FIN_WAVES = 16;
+__global__ void __launch_bounds__(NLL_FIN_WAVES * 64)
+k_nll_finish_cols(const float2 *__restrict__ part, const float *__restrict__ tgt_logit, int n_wt, int64_t M, int64_t Mp,
+                  float *__restrict__ nll)
+{
+    __shared__ float2 fold[NLL_FIN_WAVES][64];
+    const int rl = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int64_t r = (int64_t)blockIdx.x * 64 + rl;       // r < Mp: the grid covers ceil(M / 64) * 64 <= Mp rows
+    float mx = -INFINITY, se = 0.f;
+    for (int t = q; t < n_wt; t += NLL_FIN_WAVES) {
+        const float2 v = part[(int64_t)t * Mp + r];
+        const float m2 = fmaxf(mx, v.x);
+        se = se * expf(mx - m2) + v.y * expf(v.x - m2);
+        mx = m2;
+    }
+    fold[q][rl] = make_float2(mx, se);
+    __syncthreads();
+    if (q != 0 || r >= M) return;
+    for (int i = 1; i < NLL_FIN_WAVES; ++i) {
+        const float2 v = fold[i][rl];
+        if (v.x == -INFINITY) continue;                    // a wave without tiles (fewer than 16 tiles)
+        const float m2 = fmaxf(mx, v.x);
+        se = se * expf(mx - m2) + v.y * expf(v.x - m2);
+        mx = m2;
+    }
+    nll[r] = (mx + logf(se)) - tgt_logit[r];
 }
 
 // Register r of accumulator tile (i, j) is row 32*i + 8*(r/4) + 4*(lane/32) + r%4, column 32*j + lane%32
 // of the wave tile (row_w already holds the wave tile's first row + 4*(lane/32)). Per 32-row tile all
 // global reads of the epilogue are issued first, then the row pairs are combined and stored.
+template <class E, class = void> struct epi_whole_tile { static constexpr bool value = false; };
+template <class E> struct epi_whole_tile<E, decltype((void)E::whole_tile)> { static constexpr bool value = E::whole_tile; };
+
 template <bool FULL, int TM, int TN, class Epi>
 __device__ __forceinline__ void gemm_epilogue(const floatx16_t (&acc)[TM][TN], const Epi &epi, int64_t row_w, int64_t M,
                                               int vcol0, int c)
@@ -411,8 +444,6 @@ template <int N> __device__ __forceinline__ void vm_wait()
     static_assert(N >= 0 && N < 64, "vmcnt has six bits");
     __builtin_amdgcn_s_waitcnt(((N >> 4) << 14) | 0x0F70 | (N & 15));
 }
-
-#define GT_STAMP(i)
 
 // PERSIST: one workgroup per CU walks every tile of its slot in the XCD's band (tile index + workgroups per XCD) and
 // the pipeline runs across the tile boundary: the last two K steps of a tile request the first two slices of the next
@@ -543,7 +574,6 @@ k_gemm_mfma(const bf16_t *__restrict__ A, int64_t lda, BMap bmap, int64_t M, int
 
     constexpr int STAGE_BYTES2 = (BM + BN) * 128;
     unsigned char *const stage0 = lds, *const stage1 = lds + STAGE_BYTES2;
-    GT_STAMP(0);
 #pragma unroll
     for (int p = 0; p < A_PASSES + B_PASSES; ++p) SOL_DTL_ONE(p, 0, 0);
 #pragma unroll
@@ -552,7 +582,6 @@ k_gemm_mfma(const bf16_t *__restrict__ A, int64_t lda, BMap bmap, int64_t M, int
     __syncthreads();
     SOL_F_READ(fa0, fb0, stage0, 0);
     SOL_F_READ(fa1, fb1, stage0, 1);
-    GT_STAMP(1);
     const int vcol_w = wn * WN;
     const int64_t row_w = wm * WM + 4 * (lane >> 5);
     if constexpr (!PERSIST) {
@@ -562,7 +591,6 @@ k_gemm_mfma(const bf16_t *__restrict__ A, int64_t lda, BMap bmap, int64_t M, int
         }
         vm_wait<0>();
         __syncthreads();
-        GT_STAMP(2);
     } else {
         for (;;) {
             const bool more = lin + lin_step < band_end;
@@ -577,7 +605,8 @@ k_gemm_mfma(const bf16_t *__restrict__ A, int64_t lda, BMap bmap, int64_t M, int
             SOL_STEP(stage1, stage0, STAGE_BYTES2, 1);
             // stage 0 holds the next tile's slice 0 and its first fragments are in registers; slice 1 is on its way
             // into stage 1 and is waited for in the next tile's first step
-            gemm_epilogue<true, TM, TN>(acc, epi, m0 + row_w, M, n0 + vcol_w, lane & 31);   // M % BM == 0 (launcher): with
+            if constexpr (epi_whole_tile<Epi>::value) epi.template tile<TM, TN>(acc, m0 + wm * WM, n0 + vcol_w, lane);
+            else gemm_epilogue<true, TM, TN>(acc, epi, m0 + row_w, M, n0 + vcol_w, lane & 31);   // M % BM == 0 (launcher): with
             if (!more) break;                               // both epilogue versions in the loop the compiler spills the accumulators
             SOL_ACC_ZERO;
             lin += lin_step; m0 = m0_next; n0 = n0_next;
@@ -597,9 +626,12 @@ k_gemm_mfma(const bf16_t *__restrict__ A, int64_t lda, BMap bmap, int64_t M, int
 
     // ---- epilogue straight from the accumulators (tiles that lie wholly inside the matrix take the
     // version without row checks) ----
-    if (m0 + BM <= M) gemm_epilogue<true, TM, TN>(acc, epi, m0 + row_w, M, n0 + vcol_w, lane & 31);
-    else gemm_epilogue<false, TM, TN>(acc, epi, m0 + row_w, M, n0 + vcol_w, lane & 31);
-    GT_STAMP(3);
+    if constexpr (epi_whole_tile<Epi>::value) {             // (the launcher admits whole tiles only)
+        epi.template tile<TM, TN>(acc, m0 + wm * WM, n0 + vcol_w, lane);
+    } else {
+        if (m0 + BM <= M) gemm_epilogue<true, TM, TN>(acc, epi, m0 + row_w, M, n0 + vcol_w, lane & 31);
+        else gemm_epilogue<false, TM, TN>(acc, epi, m0 + row_w, M, n0 + vcol_w, lane & 31);
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -724,26 +756,34 @@ bool launch_gemm_f32(const void *a, const void *w, float *C, int64_t ldc, int64_
 }
 
 
-size_t gemm_nll_scratch_bytes(int64_t M, int V) { return (size_t)M * ((size_t)(V / SOL_WN) * sizeof(float2) + 8); }
+static int64_t nll_pad_rows(int64_t M) { return (M + 255) / 256 * 256; }
+int64_t gemm_nll_hf_rows(int64_t M) { return nll_pad_rows(M); }
+size_t gemm_nll_scratch_bytes(int64_t M, int V) { return (size_t)nll_pad_rows(M) * ((size_t)(V / SOL_WN) * sizeof(float2) + 8); }
 
 // nll[r] = logsumexp(hf[r] . lm_head^T) - (hf[r] . lm_head[target(r)]) without materialising the logits.
-// scratch: gemm_nll_scratch_bytes(M, V) bytes. Returns false (nothing launched) if the shape does not tile.
-bool launch_gemm_nll(const void *hf, const void *lm_head, const int32_t *targets, int G, int T, bool broadcast_g,
+// hf: [gemm_nll_hf_rows(M)][K], the first M rows filled (the padding rows are cleared here); scratch:
+// gemm_nll_scratch_bytes(M, V) bytes. Returns false (nothing launched) if the shape does not tile.
+bool launch_gemm_nll(void *hf, const void *lm_head, const int32_t *targets, int G, int T, bool broadcast_g,
                      float *nll, void *scratch, int64_t M, int V, int K, int *flags, hipStream_t st)
 {
     if (M <= 0) return true;
-    if (V % 256 || K % (2 * BK) || K < 2 * BK) return false;
+    const int64_t Mp = nll_pad_rows(M);
+    if (V % 256 || K % (2 * BK) || K < 2 * BK || Mp >= (1ll << 31)) return false;
     const int n_wt = V / SOL_WN;
     float2 *part = (float2 *)scratch;
-    float *tgt_logit = (float *)(part + (size_t)M * n_wt);
-    int32_t *row_tgt = (int32_t *)(tgt_logit + M);
+    float *tgt_logit = (float *)(part + (size_t)Mp * n_wt);
+    int32_t *row_tgt = (int32_t *)(tgt_logit + Mp);
     hipLaunchKernelGGL(k_row_targets, dim3((unsigned)((M + 255) / 256)), dim3(256), 0, st, targets, M, G, T,
                        broadcast_g ? 1 : 0, V, row_tgt, flags);
-    BMap bm{};
-    bm.base[0] = (const bf16_t *)lm_head; bm.seg_end[0] = bm.seg_end[1] = bm.seg_end[2] = V; bm.mode = 0; bm.ld = K;
-    EpiNllPart epi{part, tgt_logit, row_tgt, n_wt};
-    if (!launch_mfma<SOL_TILE>((const bf16_t *)hf, K, bm, M, V, K, epi, st)) return false;
-    hipLaunchKernelGGL(k_nll_finish, dim3((unsigned)((M + 3) / 4)), dim3(256), 0, st, part, tgt_logit, n_wt, M, nll);
+    if (Mp > M) launch_fill_i32((int32_t *)((bf16_t *)hf + M * K), 0, (Mp - M) * K / 2, st);   // K is even
+    BMap bt{};
+    bt.base[0] = (const bf16_t *)hf; bt.seg_end[0] = bt.seg_end[1] = bt.seg_end[2] = (int)Mp; bt.mode = 0; bt.ld = K;
+    EpiNllCols epc{part, Mp};
+    if (!launch_mfma<SOL_TILE>((const bf16_t *)lm_head, K, bt, V, (int)Mp, K, epc, st)) return false;
+    hipLaunchKernelGGL(k_target_logit, dim3((unsigned)((M + 3) / 4)), dim3(256), 0, st, (const bf16_t *)hf,
+                       (const bf16_t *)lm_head, row_tgt, M, K, tgt_logit);
+    hipLaunchKernelGGL(k_nll_finish_cols, dim3((unsigned)((M + 63) / 64)), dim3(NLL_FIN_WAVES * 64), 0, st, part, tgt_logit, n_wt,
+                       M, Mp, nll);
     return true;
 }
 

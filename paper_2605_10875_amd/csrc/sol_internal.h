@@ -108,10 +108,12 @@ bool launch_gemm_resid_out(const void *a, const void *w, const float *x2, void *
 bool launch_gemm_f32(const void *a, const void *w, float *C, int64_t ldc, int64_t M, int N, int K, hipStream_t st);
 
 // LM head + NLL with the logits kept on chip (bf16, vocabulary a multiple of 256): nll[r] = logsumexp - target
-// logit. scratch: gemm_nll_scratch_bytes(M, V) bytes.
-bool launch_gemm_nll(const void *hf, const void *lm_head, const int32_t *targets, int G, int T, bool broadcast_g,
+// logit. hf must have room for gemm_nll_hf_rows(M) rows (M rounded up to the GEMM's tile; the rows past M are
+// cleared by the call); scratch: gemm_nll_scratch_bytes(M, V) bytes.
+bool launch_gemm_nll(void *hf, const void *lm_head, const int32_t *targets, int G, int T, bool broadcast_g,
                      float *nll, void *scratch, int64_t M, int V, int K, int *flags, hipStream_t st);
 size_t gemm_nll_scratch_bytes(int64_t M, int V);
+int64_t gemm_nll_hf_rows(int64_t M);
 
 // Skinny GEMM for M <= 64 rows (decode): partial[nsplit][M][n0+n1+n2] (fp32) = x * [w0; w1; w2]^T, K split over
 // nsplit workgroup rows; the consumer kernels above fold the partial sums (their nsplit argument). The fp32

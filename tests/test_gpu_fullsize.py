@@ -225,28 +225,42 @@ def test_c5_decode_full_size_sampled_sequences():
     assert n_gpu[~quiet].mean() <= 1.25 * n_orc[~quiet].mean() + 2e-3
 
 
-def test_lm_head_nll_at_the_full_vocabulary():
-    """The fused LM head + NLL (per-tile maxima and sums of exponentials, logits never written) at the 501 column
-    tiles of the 128 256-token vocabulary, on a model small enough for the oracle to evaluate every row."""
+@pytest.mark.parametrize("T", [37, 256], ids=["148-rows", "1024-rows"])
+def test_lm_head_nll_at_the_full_vocabulary(T):
+    """The fused LM head + NLL (per-tile maxima and sums of exponentials, logits never written) at the 1002 tiles of the
+    128 256-token vocabulary, on a model small enough for the oracle to evaluate every row: 148 rows (one ragged tile
+    of token columns) and 1024 rows (four tiles, the persistent walk over 2004 tiles). Schedule 0 of every input is
+    the dense action, the other prunes and selects in the layer below. Both are held against the distance between the
+    oracle's two storage modes (the layer below hands bf16 tensors on, and a hidden element that rounds the other way
+    moves a logit by ~1e-3): median, 98th percentile and worst token no further from the bf16-store oracle than the
+    fp32-store oracle is, with floors of 1e-4, 1e-2 and 2e-2 nats."""
     shape = synth.ModelShape(d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=64, d_ff=512, n_layers=1, vocab=128256)
     table = NOQUANT
     layers = [synth.layer_weights(shape, 7100, bf16=True, std=0.05)]
     head = synth.head_weights(shape, 7101, bf16=True, std=0.05)
-    B, G, T = 2, 2, 37
+    B, G = 2, 2
     tokens, targets = synth.tokens_and_targets(B, T, shape.vocab, 7102)
     targets[0, :4] = [0, shape.vocab - 1, 255, 256]                 # first / last entry, both sides of a tile edge
     ids = synth.iid_actions(len(table), (B, G, T), 7103)
+    ids[:, 0] = table.index(synth.DENSE_ACTION)
     ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=T)
     nll = host(ctx.schedule_loglik([dev_weights(layers[0], sol.BF16)], dev_weights(head, sol.BF16), dev(tokens),
                                    dev(targets), dev(ids)))
     assert ctx.device_status() == sol.OK
     ctx.close()
-    ref = oracle.schedule_loglik(oracle.make_cfg(shape, act_bf16=True), oracle.make_table(table), head["embed"], layers,
-                                 head["w_final_norm"], head["lm_head"], tokens, targets, ids)
-    err = np.abs(nll - ref)
-    print(f"NLL at vocab {shape.vocab}: |gpu - oracle| median {np.median(err):.2e} max {err.max():.2e}; nll range "
-          f"{ref.min():.3f}..{ref.max():.3f}")
-    assert err.max() < 1e-2 and np.median(err) < 2e-3
+    mk = lambda bf: oracle.schedule_loglik(oracle.make_cfg(shape, act_bf16=bf), oracle.make_table(table), head["embed"],
+                                           layers, head["w_final_norm"], head["lm_head"], tokens, targets, ids)
+    ref, ref32 = mk(True), mk(False)
+    err, orc = np.abs(nll - ref), np.abs(ref - ref32)
+    for g, what in ((0, "dense schedule"), (1, "selecting / pruning schedule")):
+        e, o = err[:, g], orc[:, g]
+        print(f"NLL at vocab {shape.vocab}, {what}: |gpu - bf16-store oracle| median {np.median(e):.2e} q98 "
+              f"{np.quantile(e, .98):.2e} max {e.max():.2e} | fp32-store vs bf16-store oracle median {np.median(o):.2e} q98 "
+              f"{np.quantile(o, .98):.2e} max {o.max():.2e}; nll range {ref.min():.3f}..{ref.max():.3f}")
+        # the head adds nothing visible: the GPU is as close to the bf16-store oracle as the oracle's other mode is
+        assert np.median(e) < max(1e-4, 1.25 * np.median(o))
+        assert np.quantile(e, 0.98) < max(1e-2, 1.25 * np.quantile(o, 0.98))
+        assert e.max() < max(2e-2, 1.5 * o.max())
 
 
 def test_c3_full_size_stack_sampled_schedules(capsys):

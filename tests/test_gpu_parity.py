@@ -237,11 +237,13 @@ def test_bf16_decode_step(shape, B, L, dup):
     ctx.close()
 
 
-@pytest.mark.parametrize("vocab", [1000, 1024])            # 1024 tiles: the LM head runs on the MFMA GEMM
-def test_bf16_schedule_loglik_determinism_and_parity(vocab):
+# vocabulary 1024 tiles: the LM head runs on the MFMA GEMM; with 2 x 4 x 128 = 1024 rows in the orientation of the
+# full-size pass (vocabulary entries as rows, tokens as columns)
+@pytest.mark.parametrize("vocab,G,T", [(1000, 3, 48), (1024, 3, 48), (1024, 4, 128)])
+def test_bf16_schedule_loglik_determinism_and_parity(vocab, G, T):
     shape, table = dataclasses.replace(SMALL_GQA, vocab=vocab), synth.TABLE_C2
     layers, head = _stack(shape, 4000, True)
-    B, G, T = 2, 3, 48
+    B = 2
     tokens, targets = synth.tokens_and_targets(B, T, shape.vocab, 4001)
     ids = synth.markov_actions(len(table), B * G, T, 4002).reshape(B, G, T)
     ids[:, 2] = ids[:, 0]                                   # schedule 2 repeats schedule 0
@@ -258,8 +260,14 @@ def test_bf16_schedule_loglik_determinism_and_parity(vocab):
     ref = oracle.schedule_loglik(oracle.make_cfg(shape, act_bf16=True), oracle.make_table(table), head["embed"],
                                  layers, head["w_final_norm"], head["lm_head"], tokens, targets, ids)
     err = np.abs(nll - ref)
-    print("nll err: median %.2e  q98 %.2e  max %.2e" % (np.median(err), np.quantile(err, 0.98), err.max()))
-    assert np.median(err) < 1e-3 and np.quantile(err, 0.8) < 1e-2 and err.max() < 0.5
+    # quantising schedules: the yardstick is the distance between the oracle's own two storage modes
+    ref32 = oracle.schedule_loglik(oracle.make_cfg(shape, act_bf16=False), oracle.make_table(table), head["embed"],
+                                   layers, head["w_final_norm"], head["lm_head"], tokens, targets, ids)
+    e_orc = np.abs(ref - ref32)
+    print("nll err: median %.2e  q80 %.2e  q98 %.2e  max %.2e | fp32-store vs bf16-store oracle: median %.2e q80 %.2e" % (
+        np.median(err), np.quantile(err, 0.8), np.quantile(err, 0.98), err.max(), np.median(e_orc), np.quantile(e_orc, 0.8)))
+    assert np.median(err) < max(1e-3, 1.25 * np.median(e_orc)) and err.max() < 0.5
+    assert np.quantile(err, 0.8) < max(1e-2, 1.25 * np.quantile(e_orc, 0.8))
     # schedules that never quantise: every token within 1e-2 nats
     ctx2 = sol.Sol(shape, NOQUANT_TABLE, dtype=sol.BF16, max_positions=T)
     ids2 = synth.iid_actions(len(NOQUANT_TABLE), (B, G, T), 4003)
@@ -267,8 +275,12 @@ def test_bf16_schedule_loglik_determinism_and_parity(vocab):
     ref2 = oracle.schedule_loglik(oracle.make_cfg(shape, act_bf16=True), oracle.make_table(NOQUANT_TABLE),
                                   head["embed"], layers, head["w_final_norm"], head["lm_head"], tokens, targets, ids2)
     e2 = np.abs(nll2 - ref2)
-    print("no-quant nll err: median %.2e q95 %.2e max %.2e" % (np.median(e2), np.quantile(e2, 0.95), e2.max()))
-    assert np.quantile(e2, 0.95) < 1e-2 and e2.max() < 0.2
+    ref2_32 = oracle.schedule_loglik(oracle.make_cfg(shape, act_bf16=False), oracle.make_table(NOQUANT_TABLE),
+                                     head["embed"], layers, head["w_final_norm"], head["lm_head"], tokens, targets, ids2)
+    o2 = np.abs(ref2 - ref2_32)
+    print("no-quant nll err: median %.2e q95 %.2e max %.2e | oracles: median %.2e q95 %.2e max %.2e" % (
+        np.median(e2), np.quantile(e2, 0.95), e2.max(), np.median(o2), np.quantile(o2, 0.95), o2.max()))
+    assert np.median(e2) < 2e-3 and np.quantile(e2, 0.95) < max(1e-2, 1.25 * np.quantile(o2, 0.95)) and e2.max() < 0.2
     ctx2.close()
     ctx.close()
 
