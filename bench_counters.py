@@ -27,7 +27,7 @@ csv.field_size_limit(1 << 30)
 
 # stage name of bench.py -> substring of the kernel that dominates it
 DOMINANT = {"gate_up_gemm": "EpiSiluMul", "attention_topk": "k_attn_decode<", "attention_select": "k_attn_select<",
-            "prune_quant": "k_prune_fq_wave", "down_gemm": "EpiResidOut", "lm_head_gemm": "EpiNllPart"}
+            "prune_quant": "k_prune_fq_wave", "down_gemm": "EpiResidOut", "lm_head_gemm": "EpiNllCols"}
 TITLES = {"c2": "C2 (one Llama-3.2-1B-shaped layer, 32 x 1024 tokens)", "c3": "C3 (16-layer stack + LM head, 16 x 2048 tokens)",
           "c4": "C4 (decode step, 64 x 8192-token caches, 16 layers + LM head)", "c5": "C5 (one Llama-3.1-8B-shaped layer, 8 x 4096 tokens)",
           "c5d": "C5-decode (one 8B-shaped layer, 32 x 8192-token caches)", "c2p": "C2, the paper's own configuration",
