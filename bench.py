@@ -111,6 +111,16 @@ def roofline_counters(workload, kernel):
     return {"traffic": c.get("traffic"), "mfma_util": c.get("mfma_util")}
 
 
+def executed_mfma(workload, sec):
+    """MFMA flops the step executed by the hardware counter (all kernels; profiles/counters.json), as TFLOP per step,
+    TFLOP/s over this run's step time and fraction of the published peak; None without counters for these sources."""
+    fl = measured_counters(workload, "step").get("mfma_executed_flops")
+    if not fl:
+        return {"mfma_executed_tflop": None, "mfma_executed_tflops": None, "mfma_executed_frac_of_peak": None}
+    return {"mfma_executed_tflop": fl / 1e12, "mfma_executed_tflops": fl / sec / 1e12,
+            "mfma_executed_frac_of_peak": fl / sec / 1e12 / PEAK_BF16_TFLOPS}
+
+
 def stage_times(ctx, fn, steps):
     ctx.profile_enable(512 * steps + 64)
     for _ in range(steps):
@@ -167,6 +177,7 @@ def run_layer(args, shape, n_inputs, G, T, table, name, preset=None, workload="c
     res["layer"] = {"algorithmic_tflop": alg / 1e12, "algorithmic_tflops": alg / sec / 1e12,
                     "algorithmic_frac_of_peak": alg / sec / 1e12 / PEAK_BF16_TFLOPS,
                     "dense_equivalent_tflops": dense / sec / 1e12}
+    res["layer"].update(executed_mfma(workload, sec))
     res["stage_ms"] = {k: round(v, 4) for k, v in stages.items()}
     if not args.no_cpu_baseline:
         import oracle
@@ -237,6 +248,7 @@ def run_stack(args, shape, B, G, T, table, name, workload="c3"):
     res["stack"] = {"algorithmic_tflop": alg / 1e12, "algorithmic_tflops": alg / sec / 1e12,
                     "algorithmic_frac_of_peak": alg / sec / 1e12 / PEAK_BF16_TFLOPS,
                     "mean_nll_nats": float(nll.mean()), "log_vocab": float(np.log(shape.vocab))}
+    res["stack"].update(executed_mfma(workload, sec))
     res["stage_ms"] = {k: round(v, 4) for k, v in stages.items()}
     # the step right after this pass: reward reduction on its NLL tensor (not part of the timed step)
     tg3 = torch.full((B, 3), 0.6, dtype=torch.float32, device="cuda")

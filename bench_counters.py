@@ -120,6 +120,15 @@ def main():
                                   "write_bytes": int(wm * (1 << 20)) if wm is not None else None,
                                   "insts_valu": avg(c["SQ_INSTS_VALU"]) or None, "insts_salu": avg(c["SQ_INSTS_SALU"]) or None,
                                   "gui_active_cycles": act or None}
+        # MFMA flops the whole step executed (SQ_INSTS_VALU_MFMA_MOPS_BF16 counts units of 512 flops: the gate_up GEMM's
+        # 2^32 per launch are its 2 * 32768 * 2048 * 16384 flops), over all kernels of the library; steps run in the
+        # profiled process = launches of k_prepare_rows, which every entry point launches once
+        n_steps = next((len(sq[k]["GRBM_GUI_ACTIVE"]) for k in names if "k_prepare_rows" in k), 0)
+        if n_steps:
+            mops = sum(sum(sq[k]["SQ_INSTS_VALU_MFMA_MOPS_BF16"]) for k in names if "k_peak_" not in k)   # not the peak microbenchmarks
+            rec["step"] = {"mfma_executed_flops": mops * 512.0 / n_steps, "steps_profiled": n_steps}
+            lines += ["", "MFMA flops executed per step, all kernels (MFMA_MOPS_BF16 x 512 / %d steps): %.3f TFLOP" % (
+                n_steps, mops * 512.0 / n_steps / 1e12)]
         out[wl] = rec
         txt = os.path.join(ROOT, "profiles", "%s_counters.txt" % wl)
         open(txt, "w").write("\n".join(lines) + "\n")
