@@ -401,6 +401,11 @@ def run_decode(args, shape, B, L, table, name, n_layers, preset=None, with_head=
     res["roofline"].update(roofline_counters(workload, dom))
     res["step"] = {"algorithmic_gb": alg_bytes / 1e9, "algorithmic_gbs": alg_bytes / sec / 1e9,
                    "algorithmic_frac_of_peak": alg_bytes / sec / 1e9 / PEAK_HBM_GBS}
+    # what the counters saw the whole step move (FETCH_SIZE + WRITE_SIZE over all kernels; profiles/counters.json)
+    mc = measured_counters(workload, "step")
+    moved = (mc.get("fetch_bytes") or 0) + (mc.get("write_bytes") or 0)
+    res["step"].update({"measured_gb": moved / 1e9 if moved else None, "measured_gbs": moved / sec / 1e9 if moved else None,
+                        "measured_frac_of_peak": moved / sec / 1e9 / PEAK_HBM_GBS if moved else None})
     res["stage_ms"] = {k: round(v, 4) for k, v in stages.items()}
     if cpu:
         res["cpu_baseline"] = cpu

@@ -129,6 +129,14 @@ def main():
             rec["step"] = {"mfma_executed_flops": mops * 512.0 / n_steps, "steps_profiled": n_steps}
             lines += ["", "MFMA flops executed per step, all kernels (MFMA_MOPS_BF16 x 512 / %d steps): %.3f TFLOP" % (
                 n_steps, mops * 512.0 / n_steps / 1e12)]
+        # the step's traffic by the same counters, all kernels (scaled as above), for the HBM-bound records
+        nf = next((len(fe[k]["FETCH_SIZE"]) for k in fe if "k_prepare_rows" in k), 0)
+        nw = next((len(wr[k]["WRITE_SIZE"]) for k in wr if "k_prepare_rows" in k), 0)
+        if sf and sw and nf and nw:
+            fb = sum(sum(fe[k]["FETCH_SIZE"]) for k in fe if k.startswith("sol::") and "k_peak_" not in k) * sf * 1024.0 / nf
+            wb = sum(sum(wr[k]["WRITE_SIZE"]) for k in wr if k.startswith("sol::") and "k_peak_" not in k) * sw * 1024.0 / nw
+            rec.setdefault("step", {}).update({"fetch_bytes": fb, "write_bytes": wb})
+            lines += ["bytes fetched / written per step, all kernels: %.3f / %.3f GB" % (fb / 1e9, wb / 1e9)]
         out[wl] = rec
         txt = os.path.join(ROOT, "profiles", "%s_counters.txt" % wl)
         open(txt, "w").write("\n".join(lines) + "\n")
