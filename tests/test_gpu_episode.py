@@ -47,11 +47,13 @@ WIDE_HEADS = synth.ModelShape(d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=1
 
 
 @pytest.mark.parametrize("shape,P,T,K", [(SMALL_GQA, 64, 16, 4), (SMALL_GQA, 128, 40, 3), (WIDE_HEADS, 64, 16, 2),
-                                         (SMALL_GQA, 50, 4, 3), (SMALL_GQA, 72, 16, 2)])
+                                         (SMALL_GQA, 50, 4, 3), (SMALL_GQA, 72, 16, 2),
+                                         (SMALL_GQA, 1024, 16, 3), (WIDE_HEADS, 1088, 32, 2)])   # the paper's prefix length: rows over 1024 keys
 def test_bf16_episode_pass(shape, P, T, K):
     """Prefix a multiple of 64 and at least 16 steps: the schedules read the prefix caches in place (tiled kernels with
     two-segment addressing); (50, 4) and (72, 16): every schedule gets a copy (row-per-workgroup kernel for fewer than 16
-    steps, tiled kernels at pos0 = P otherwise)."""
+    steps, tiled kernels at pos0 = P otherwise). Prefixes of 1024 and more: the threshold kernel reads the prefix keys
+    from their copy in MFMA operand order and the schedule's own keys from its cache."""
     table = synth.action_table((0.125, 0.5, 1.0), (0.0, 0.75), (6, 16))
     nll, ref, ids = _run(shape, table, sol.BF16, 2, K, P, T, 8100 + T + P)
     bits = np.array([a[4] for a in table])[ids]
@@ -60,8 +62,9 @@ def test_bf16_episode_pass(shape, P, T, K):
     # entries moves every later step of that schedule)
     # (one swapped key among the 8-10 kept keys of a short row moves its NLL by a few 1e-2: one such step in ten allowed)
     clean = np.logical_and.accumulate(bits >= 16, axis=2)
-    assert (err[clean] < 5e-2).all() and (err[clean] < 2e-2).mean() >= 0.9 and np.median(err) < 1e-2 and err.max() < 0.5, \
-        (np.median(err), err.max())
+    over = int((err[clean] >= 2e-2).sum())                 # (a handful of clean steps: one such step is still one in ten)
+    assert (err[clean] < 5e-2).all() and over <= max(1, 0.1 * clean.sum()) and np.median(err) < 1e-2 and err.max() < 0.5, \
+        (np.median(err), err.max(), over, int(clean.sum()))
 
 
 @pytest.mark.parametrize("P,T,K", [(48, 8, 3), (256, 16, 3), (256, 40, 2)])
@@ -90,7 +93,7 @@ def test_identical_schedules_give_identical_likelihoods():
     assert all(np.array_equal(nll[0, 0], nll[0, k]) for k in range(1, 5))
 
 
-@pytest.mark.parametrize("preset,P", [("{}", 192), ("sol.PAPER_PRESET", 256), ("dict(sol.PAPER_PRESET, page_size=4)", 64),
+@pytest.mark.parametrize("preset,P", [("{}", 192), ("{}", 1024), ("sol.PAPER_PRESET", 256), ("dict(sol.PAPER_PRESET, page_size=4)", 64),
                                       ("dict(sol.PAPER_PRESET, page_size=64, n_sink=0)", 1024)])
 def test_reading_the_prefix_in_place_equals_working_on_copies(preset, P):
     """The two layouts of the episode pass run the same arithmetic on the same values: bit-identical likelihoods, under
