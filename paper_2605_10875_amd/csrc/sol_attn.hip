@@ -518,7 +518,7 @@ __global__ void __launch_bounds__(NW * 64)
 __attribute__((amdgpu_waves_per_eu(SLOTS <= 16 || (SLOTS <= 32 && DH <= 64) ? 4 : SLOTS <= 32 ? 3 : 2, SLOTS <= 16 ? 4 : 8)))
 k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRow *__restrict__ sel,
               const RowAct *__restrict__ ra, const int32_t *__restrict__ pos0, int Tn, int L_max, int Hq, int Hkv,
-              float scale, int nb, PrefixView pv)
+              float scale, int nb, PrefixView pv, int n_lo, int n_hi)
 {
     constexpr int LPAD = SLOTS * 64, LS = LPAD + 4;        // row stride = 4 mod 64 floats: the 16 query rows of a
                                                            // 128-bit store hit 16 different bank groups
@@ -532,7 +532,12 @@ k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRo
     const int bi = blockIdx.x, h = blockIdx.y, s = blockIdx.z;
     const int p0 = pos0 ? pos0[s] : 0;
     if (p0 < 0 || p0 + Tn > L_max) return;                 // flagged by the projection kernel; sequence skipped
-    const int n_qb = (Tn + BQ - 1) / BQ;
+    // this launch takes the rows whose key count n = p0 + row + 1 lies in (n_lo, n_hi]: rows [q_lo, q_hi) of the sequence
+    // (long sequences are split by row length over the kernel's variants; the blocks of BQ rows count from q_lo)
+    const int q_lo = n_lo - p0 < 0 ? 0 : (n_lo - p0 > Tn ? Tn : n_lo - p0);
+    const int q_hi = n_hi - p0 < 0 ? 0 : (n_hi - p0 > Tn ? Tn : n_hi - p0);
+    if (q_hi <= q_lo) return;                              // whole workgroup, before any barrier
+    const int n_qb = (q_hi - q_lo + BQ - 1) / BQ;
     const int kvh = h / (Hq / Hkv);
     // wave-uniform bases + 32-bit per-lane offsets: one address register per load instead of two
     const bf16_t *kbase = kc + ((int64_t)s * Hkv + kvh) * (int64_t)(KF ? attn_lpad64(L_max) : L_max) * DH;
@@ -594,8 +599,8 @@ k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRo
     // q fragments and the first two groups of K tiles of query block QB_
 #define SOL_SEL_LOAD(QB_)                                                                                  \
     {                                                                                                      \
-        const int q0_ = (QB_) * BQ;                                                                        \
-        const int nmax_ = p0 + (Tn < q0_ + BQ ? Tn : q0_ + BQ);                                            \
+        const int q0_ = q_lo + (QB_) * BQ;                                                                 \
+        const int nmax_ = p0 + (q_hi < q0_ + BQ ? q_hi : q0_ + BQ);                                        \
         _Pragma("unroll") for (int rt = 0; rt < RT; ++rt) {                                                \
             int qr = q0_ + rt * 16 + l16;                                                                  \
             if (qr >= Tn) qr = Tn - 1;                                                                     \
@@ -627,8 +632,8 @@ k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRo
     if (qb >= n_qb) return;
     SOL_SEL_LOAD(qb);
     while (true) {
-        const int q0 = qb * BQ;
-        const int rows = (Tn - q0 < BQ) ? (Tn - q0) : BQ;
+        const int q0 = q_lo + qb * BQ;
+        const int rows = (q_hi - q0 < BQ) ? (q_hi - q0) : BQ;
         const int n_max = p0 + q0 + rows;
         const int n_kt = (n_max + 15) >> 4;
         // ---- scores of this block into LDS: the loads of a group of tiles go out while the group before it is multiplied ----
@@ -1893,9 +1898,11 @@ k_frag_k(const bf16_t *__restrict__ kc, bf16_t *__restrict__ kfr, const int32_t 
     }
 }
 
+// rows whose key count lies in (n_lo, n_hi] (all rows by default); SLOTS * 64 >= min(n_hi, L_max) is the caller's business
 template <int BQ, int SLOTS, int DH, int NW, bool PRE = false, bool KF = false>
 static bool launch_attn_select_t(const void *q, const void *kc, SelRow *sel, const RowAct *ra, const int32_t *pos0,
-                                 int n_seq, int Tn, int L_max, int Hq, int Hkv, hipStream_t st, PrefixView pv = PrefixView())
+                                 int n_seq, int Tn, int L_max, int Hq, int Hkv, hipStream_t st, PrefixView pv = PrefixView(),
+                                 int n_lo = 0, int n_hi = 1 << 30)
 {
     auto kern = k_attn_select<BQ, SLOTS, DH, NW, PRE, KF>;
     const size_t lds = (size_t)BQ * (SLOTS * 64 + 4) * 4;
@@ -1907,12 +1914,15 @@ static bool launch_attn_select_t(const void *q, const void *kc, SelRow *sel, con
         attr_done = true;
     }
     // workgroups per (sequence, head): enough to fill the chip about eight times over, at most one per block
-    const int n_qb = (Tn + BQ - 1) / BQ;
+    int t_range = (n_hi < L_max ? n_hi : L_max) - n_lo;     // no sequence has more rows than that in the range
+    if (t_range > Tn) t_range = Tn;
+    if (t_range <= 0) return true;
+    const int n_qb = (t_range + BQ - 1) / BQ;
     int nb = (int)((4096 + (int64_t)Hq * n_seq - 1) / ((int64_t)Hq * n_seq));
     if (nb > n_qb) nb = n_qb;
     if (nb < 1) nb = 1;
     hipLaunchKernelGGL(kern, dim3(nb, Hq, n_seq), dim3(NW * 64), lds, st, (const bf16_t *)q, (const bf16_t *)kc, sel, ra,
-                       pos0, Tn, L_max, Hq, Hkv, 1.0f / sqrtf((float)DH), nb, pv);
+                       pos0, Tn, L_max, Hq, Hkv, 1.0f / sqrtf((float)DH), nb, pv, n_lo, n_hi);
     return true;
 }
 
@@ -2414,16 +2424,25 @@ bool launch_attn_tile(const void *q, const void *k_cache, const void *v_cache, v
     // rows (up to 1024 keys a block has 16 rows and the copy does not pay)
     const bool frag = L_max > 1024;
     if (frag && !launch_attn_frag_k(k_cache, kfr, pos0, n_seq, T, L_max, Hkv, dh, st)) return false;
-    // score rows of a workgroup stay in LDS: 16 rows x 1024 keys (66 KB) lets two workgroups share a CU
+    // score rows of a workgroup stay in LDS: 16 rows x 1024 keys (66 KB) lets two workgroups share a CU. A launch per
+    // class of row lengths: the rows of a long sequence that see at most 1024 (2048) keys go to the variant for that
+    // length, with its larger blocks and higher occupancy, not to the one the sequence's last row needs.
     bool ok;
-#define SOL_SEL(BQ, SL, KF)                                                                                          \
-    ok = dh == 64 ? launch_attn_select_t<BQ, SL, 64, 8, false, KF>(q, KF ? kfr : k_cache, sel, ra, pos0, n_seq, T, L_max, Hq, Hkv, st)  \
-                  : launch_attn_select_t<BQ, SL, 128, 8, false, KF>(q, KF ? kfr : k_cache, sel, ra, pos0, n_seq, T, L_max, Hq, Hkv, st)
-    if (L_max <= 256) { SOL_SEL(32, 4, false); }
-    else if (L_max <= 1024) { SOL_SEL(16, 16, false); }
-    else if (L_max <= 1280) { SOL_SEL(8, 20, true); }       // a 1024-token prefix plus a short episode
-    else if (L_max <= 2048) { SOL_SEL(8, 32, true); }
-    else { SOL_SEL(8, 64, true); }
+#define SOL_SEL(BQ, SL, KF, LO, HI)                                                                                  \
+    ok = dh == 64 ? launch_attn_select_t<BQ, SL, 64, 8, false, KF>(q, KF ? kfr : k_cache, sel, ra, pos0, n_seq, T, L_max, Hq, Hkv, st, PrefixView(), LO, HI)  \
+                  : launch_attn_select_t<BQ, SL, 128, 8, false, KF>(q, KF ? kfr : k_cache, sel, ra, pos0, n_seq, T, L_max, Hq, Hkv, st, PrefixView(), LO, HI)
+    constexpr int ALL = 1 << 30;
+    if (L_max <= 256) { SOL_SEL(32, 4, false, 0, ALL); }
+    else if (L_max <= 1024) { SOL_SEL(16, 16, false, 0, ALL); }
+    else {
+        SOL_SEL(16, 16, false, 0, 1024);
+        if (ok && L_max <= 1280) { SOL_SEL(8, 20, true, 1024, ALL); }       // a 1024-token prefix plus a short episode
+        else if (ok && L_max <= 2048) { SOL_SEL(8, 32, true, 1024, ALL); }
+        else if (ok) {
+            SOL_SEL(8, 32, true, 1024, 2048);
+            if (ok) { SOL_SEL(8, 64, true, 2048, ALL); }
+        }
+    }
 #undef SOL_SEL
     if (!ok) return false;
 #define SOL_PV(G_)                                                                                                   \
