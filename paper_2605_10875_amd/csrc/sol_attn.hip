@@ -445,6 +445,29 @@ __device__ __forceinline__ uint32_t wave_select_thr(const uint32_t (&key)[SLOTS]
         else if (SLOTS >= 8 && ng == 2) lo = wave_search_thr<SLOTS, SLOTS >= 8 ? 2 : 1>(key, n, b, lo0, hi0, exact);
         else if (SLOTS >= 12 && ng == 3) lo = wave_search_thr<SLOTS, SLOTS >= 12 ? 3 : 1>(key, n, b, lo0, hi0, exact);
         else lo = wave_search_thr<SLOTS, SLOTS / 4>(key, n, b, lo0, hi0, exact);
+    } else if constexpr (SLOTS == 20) {                  // rows of 1025..1280 keys (a 1024-token prefix plus a short episode)
+        if (((n + 255) >> 8) == 5) lo = wave_search_thr<SLOTS, 5>(key, n, b, lo0, hi0, exact);
+        else lo = wave_search_thr<SLOTS, 0>(key, n, b, lo0, hi0, exact);
+    } else if constexpr (SLOTS == 32) {                  // rows of 1025..2048 keys: 5..8 groups (shorter ones take the general loop)
+        const int ng = (n + 255) >> 8;
+        if (ng == 8) lo = wave_search_thr<SLOTS, 8>(key, n, b, lo0, hi0, exact);
+        else if (ng == 7) lo = wave_search_thr<SLOTS, 7>(key, n, b, lo0, hi0, exact);
+        else if (ng == 6) lo = wave_search_thr<SLOTS, 6>(key, n, b, lo0, hi0, exact);
+        else if (ng == 5) lo = wave_search_thr<SLOTS, 5>(key, n, b, lo0, hi0, exact);
+        else lo = wave_search_thr<SLOTS, 0>(key, n, b, lo0, hi0, exact);
+    } else if constexpr (SLOTS == 64) {                  // rows of 2049..4096 keys: 9..16 groups
+        const int ng = (n + 255) >> 8;
+        switch (ng) {
+        case 16: lo = wave_search_thr<SLOTS, 16>(key, n, b, lo0, hi0, exact); break;
+        case 15: lo = wave_search_thr<SLOTS, 15>(key, n, b, lo0, hi0, exact); break;
+        case 14: lo = wave_search_thr<SLOTS, 14>(key, n, b, lo0, hi0, exact); break;
+        case 13: lo = wave_search_thr<SLOTS, 13>(key, n, b, lo0, hi0, exact); break;
+        case 12: lo = wave_search_thr<SLOTS, 12>(key, n, b, lo0, hi0, exact); break;
+        case 11: lo = wave_search_thr<SLOTS, 11>(key, n, b, lo0, hi0, exact); break;
+        case 10: lo = wave_search_thr<SLOTS, 10>(key, n, b, lo0, hi0, exact); break;
+        case 9: lo = wave_search_thr<SLOTS, 9>(key, n, b, lo0, hi0, exact); break;
+        default: lo = wave_search_thr<SLOTS, 0>(key, n, b, lo0, hi0, exact); break;
+        }
     } else {
         lo = wave_search_thr<SLOTS, 0>(key, n, b, lo0, hi0, exact);
     }
