@@ -14,6 +14,7 @@
 //   - pages of S > 1 contiguous keys: a page's score is the upper bound sum_c max(q_c max_c, q_c min_c)
 //     over the channel-wise extremes of its allowed keys; the top ceil(b / S) pages are kept whole
 //     (ties to the lower page) together with the forced keys.
+#include <type_traits>
 #include "sol_internal.h"
 
 namespace sol {
@@ -328,7 +329,7 @@ __host__ __device__ __forceinline__ int attn_lpad64(int L_max) { return (L_max +
 // column (256*j + 4*lane + e order) of the quota-th key equal to thr; quota >= 1 and at most the
 // number of such keys
 template <int SLOTS>
-__device__ __forceinline__ int wave_tie_last(const uint32_t (&key)[SLOTS], int n, uint32_t thr, int quota, int lane)
+__device__ __forceinline__ int wave_tie_last(const float (&key)[SLOTS], int n, float thr, int quota, int lane)
 {
     int result = 0x7FFFFFFF;
     bool found = false;
@@ -362,10 +363,12 @@ __device__ __forceinline__ int wave_tie_last(const uint32_t (&key)[SLOTS], int n
     return result;
 }
 
-// number of keys >= pivot, the pivot in a vector register (the same value in every lane). NG > 0: the first NG groups of
-// 256 columns; NG == 0: every group that starts below n
+// number of scores >= pivot, the pivot in a vector register (the same value in every lane). NG > 0: the first NG groups of
+// 256 columns; NG == 0: every group that starts below n. The row is held as the scores themselves (-inf past its end)
+// and compared as floats: that counts what comparing order-preserving keys counts (-0 and +0 are one value either way,
+// subnormals are not flushed, there are no NaNs), and the row needs no conversion when it is loaded.
 template <int SLOTS, int NG>
-__device__ __forceinline__ int wave_count_ge_v(const uint32_t (&key)[SLOTS], int n, uint32_t pivot)
+__device__ __forceinline__ int wave_count_ge_v(const float (&key)[SLOTS], int n, float pivot)
 {
     int cnt = 0;
 #pragma unroll
@@ -373,10 +376,41 @@ __device__ __forceinline__ int wave_count_ge_v(const uint32_t (&key)[SLOTS], int
         if (NG || 256 * j < n) {
             unsigned long long m[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) asm("v_cmp_ge_u32_e64 %0, %1, %2" : "=s"(m[e]) : "v"(key[4 * j + e]), "v"(pivot));
+            for (int e = 0; e < 4; ++e) asm("v_cmp_ge_f32_e64 %0, %1, %2" : "=s"(m[e]) : "v"(key[4 * j + e]), "v"(pivot));
             cnt += (__popcll(m[0]) + __popcll(m[1])) + (__popcll(m[2]) + __popcll(m[3]));
         }
     return cnt;
+}
+
+// the same count with one dispatch per call on the row's number of 256-column groups ng = ceil(n / 256), for a search
+// loop that exists once (the variant with a side job): long rows only
+template <int SLOTS>
+__device__ __forceinline__ int wave_count_ge_sw(const float (&key)[SLOTS], int n, int ng, float pivot)
+{
+    static_assert(SLOTS == 20 || SLOTS == 32 || SLOTS == 64, "long-row variants");
+    if constexpr (SLOTS == 20) {
+        return ng == 5 ? wave_count_ge_v<SLOTS, 5>(key, n, pivot) : wave_count_ge_v<SLOTS, 0>(key, n, pivot);
+    } else if constexpr (SLOTS == 32) {
+        switch (ng) {
+        case 8: return wave_count_ge_v<SLOTS, 8>(key, n, pivot);
+        case 7: return wave_count_ge_v<SLOTS, 7>(key, n, pivot);
+        case 6: return wave_count_ge_v<SLOTS, 6>(key, n, pivot);
+        case 5: return wave_count_ge_v<SLOTS, 5>(key, n, pivot);
+        default: return wave_count_ge_v<SLOTS, 0>(key, n, pivot);
+        }
+    } else {
+        switch (ng) {
+        case 16: return wave_count_ge_v<SLOTS, 16>(key, n, pivot);
+        case 15: return wave_count_ge_v<SLOTS, 15>(key, n, pivot);
+        case 14: return wave_count_ge_v<SLOTS, 14>(key, n, pivot);
+        case 13: return wave_count_ge_v<SLOTS, 13>(key, n, pivot);
+        case 12: return wave_count_ge_v<SLOTS, 12>(key, n, pivot);
+        case 11: return wave_count_ge_v<SLOTS, 11>(key, n, pivot);
+        case 10: return wave_count_ge_v<SLOTS, 10>(key, n, pivot);
+        case 9: return wave_count_ge_v<SLOTS, 9>(key, n, pivot);
+        default: return wave_count_ge_v<SLOTS, 0>(key, n, pivot);
+        }
+    }
 }
 
 // One row's search from the bracket [lo, hi] (count(key >= lo) >= b, count(key >= hi + 1) < b): returns the bracket
@@ -389,9 +423,12 @@ __device__ __forceinline__ int wave_count_ge_v(const uint32_t (&key)[SLOTS], int
 // The bracket and the line live in vector registers and are updated by selects although every lane holds the same
 // values: the loop is bound by the scalar unit, which already counts the compare masks, and a CU has four vector
 // pipes to its one scalar pipe.
-template <int SLOTS, int NG>
-__device__ __forceinline__ uint32_t wave_search_thr(const uint32_t (&key)[SLOTS], int n, int b, uint32_t lo_s, uint32_t hi_s,
-                                                    bool &exact)
+// side: called once per step, after the count: work of the caller's that does not depend on the search and that the
+// steps' vector and scalar instructions can hide (k_attn_select: the score tiles of the workgroup's next block)
+struct NoSide { __device__ __forceinline__ void operator()() const {} };
+template <int SLOTS, int NG, class Side>
+__device__ __forceinline__ uint32_t wave_search_thr(const float (&key)[SLOTS], int n, int b, uint32_t lo_s, uint32_t hi_s,
+                                                    bool &exact, Side &side)
 {
     uint32_t lo = lo_s, hi = hi_s;
     asm volatile("" : "+v"(lo), "+v"(hi));               // from here on the compiler treats the bracket as per-lane data
@@ -409,9 +446,13 @@ __device__ __forceinline__ uint32_t wave_search_thr(const uint32_t (&key)[SLOTS]
         mid = mid > lo ? mid : lo + 1u;
         mid = mid < hi ? mid : hi;
         if (it >= 12) mid = lo + ((hi - lo + 1u) >> 1);
-        const int cnt = wave_count_ge_v<SLOTS, NG>(key, n, mid);
+        const float fmid = score_unkey(mid);
+        int cnt;
+        if constexpr (NG < 0) cnt = wave_count_ge_sw<SLOTS>(key, n, (n + 255) >> 8, fmid);
+        else cnt = wave_count_ge_v<SLOTS, NG>(key, n, fmid);
+        side();
         if (cnt == b) { exact = true; lo = mid; break; }
-        const float cf = (float)cnt, fmid = score_unkey(mid);
+        const float cf = (float)cnt;
         const float g = __builtin_amdgcn_logf((cf + 0.5f) * __builtin_amdgcn_rcpf(nh - cf)) - t_b;
         const bool up = cnt > b;                          // the pivot becomes the lower end, else pivot - 1 the upper
         const float glo_w = glo * w_dn, ghi_w = ghi * w_up;
@@ -429,9 +470,9 @@ __device__ __forceinline__ uint32_t wave_search_thr(const uint32_t (&key)[SLOTS]
 
 // finishes one row's search from the bracket [lo, hi] (see wave_select_topk): returns the threshold key
 // and the index of the last kept key among those equal to it (INT_MAX when all of them are kept)
-template <int SLOTS>
-__device__ __forceinline__ uint32_t wave_select_thr(const uint32_t (&key)[SLOTS], int n_in, int b_in, uint32_t lo_in,
-                                                    uint32_t hi_in, int lane, int &jstar)
+template <int SLOTS, class Side>
+__device__ __forceinline__ uint32_t wave_select_thr(const float (&key)[SLOTS], int n_in, int b_in, uint32_t lo_in,
+                                                    uint32_t hi_in, int lane, int &jstar, Side &side)
 {
     const int n = __builtin_amdgcn_readfirstlane(n_in), b = __builtin_amdgcn_readfirstlane(b_in);
     const uint32_t lo0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)lo_in);
@@ -439,68 +480,77 @@ __device__ __forceinline__ uint32_t wave_select_thr(const uint32_t (&key)[SLOTS]
     jstar = 0x7FFFFFFF;
     bool exact;
     uint32_t lo;
-    if constexpr (SLOTS <= 16) {                         // one copy of the loop per row length in groups: no per-step dispatch
+    if constexpr (!std::is_same<Side, NoSide>::value && SLOTS > 16) {
+        lo = wave_search_thr<SLOTS, -1, Side>(key, n, b, lo0, hi0, exact, side);   // the side job's code exists once
+    } else if constexpr (SLOTS <= 16) {                  // one copy of the loop per row length in groups: no per-step dispatch
         const int ng = (n + 255) >> 8;
-        if (ng <= 1) lo = wave_search_thr<SLOTS, 1>(key, n, b, lo0, hi0, exact);
-        else if (SLOTS >= 8 && ng == 2) lo = wave_search_thr<SLOTS, SLOTS >= 8 ? 2 : 1>(key, n, b, lo0, hi0, exact);
-        else if (SLOTS >= 12 && ng == 3) lo = wave_search_thr<SLOTS, SLOTS >= 12 ? 3 : 1>(key, n, b, lo0, hi0, exact);
-        else lo = wave_search_thr<SLOTS, SLOTS / 4>(key, n, b, lo0, hi0, exact);
+        if (ng <= 1) lo = wave_search_thr<SLOTS, 1, Side>(key, n, b, lo0, hi0, exact, side);
+        else if (SLOTS >= 8 && ng == 2) lo = wave_search_thr<SLOTS, (SLOTS >= 8 ? 2 : 1), Side>(key, n, b, lo0, hi0, exact, side);
+        else if (SLOTS >= 12 && ng == 3) lo = wave_search_thr<SLOTS, (SLOTS >= 12 ? 3 : 1), Side>(key, n, b, lo0, hi0, exact, side);
+        else lo = wave_search_thr<SLOTS, SLOTS / 4, Side>(key, n, b, lo0, hi0, exact, side);
     } else if constexpr (SLOTS == 20) {                  // rows of 1025..1280 keys (a 1024-token prefix plus a short episode)
-        if (((n + 255) >> 8) == 5) lo = wave_search_thr<SLOTS, 5>(key, n, b, lo0, hi0, exact);
-        else lo = wave_search_thr<SLOTS, 0>(key, n, b, lo0, hi0, exact);
+        if (((n + 255) >> 8) == 5) lo = wave_search_thr<SLOTS, 5, Side>(key, n, b, lo0, hi0, exact, side);
+        else lo = wave_search_thr<SLOTS, 0, Side>(key, n, b, lo0, hi0, exact, side);
     } else if constexpr (SLOTS == 32) {                  // rows of 1025..2048 keys: 5..8 groups (shorter ones take the general loop)
         const int ng = (n + 255) >> 8;
-        if (ng == 8) lo = wave_search_thr<SLOTS, 8>(key, n, b, lo0, hi0, exact);
-        else if (ng == 7) lo = wave_search_thr<SLOTS, 7>(key, n, b, lo0, hi0, exact);
-        else if (ng == 6) lo = wave_search_thr<SLOTS, 6>(key, n, b, lo0, hi0, exact);
-        else if (ng == 5) lo = wave_search_thr<SLOTS, 5>(key, n, b, lo0, hi0, exact);
-        else lo = wave_search_thr<SLOTS, 0>(key, n, b, lo0, hi0, exact);
+        if (ng == 8) lo = wave_search_thr<SLOTS, 8, Side>(key, n, b, lo0, hi0, exact, side);
+        else if (ng == 7) lo = wave_search_thr<SLOTS, 7, Side>(key, n, b, lo0, hi0, exact, side);
+        else if (ng == 6) lo = wave_search_thr<SLOTS, 6, Side>(key, n, b, lo0, hi0, exact, side);
+        else if (ng == 5) lo = wave_search_thr<SLOTS, 5, Side>(key, n, b, lo0, hi0, exact, side);
+        else lo = wave_search_thr<SLOTS, 0, Side>(key, n, b, lo0, hi0, exact, side);
     } else if constexpr (SLOTS == 64) {                  // rows of 2049..4096 keys: 9..16 groups
         const int ng = (n + 255) >> 8;
         switch (ng) {
-        case 16: lo = wave_search_thr<SLOTS, 16>(key, n, b, lo0, hi0, exact); break;
-        case 15: lo = wave_search_thr<SLOTS, 15>(key, n, b, lo0, hi0, exact); break;
-        case 14: lo = wave_search_thr<SLOTS, 14>(key, n, b, lo0, hi0, exact); break;
-        case 13: lo = wave_search_thr<SLOTS, 13>(key, n, b, lo0, hi0, exact); break;
-        case 12: lo = wave_search_thr<SLOTS, 12>(key, n, b, lo0, hi0, exact); break;
-        case 11: lo = wave_search_thr<SLOTS, 11>(key, n, b, lo0, hi0, exact); break;
-        case 10: lo = wave_search_thr<SLOTS, 10>(key, n, b, lo0, hi0, exact); break;
-        case 9: lo = wave_search_thr<SLOTS, 9>(key, n, b, lo0, hi0, exact); break;
-        default: lo = wave_search_thr<SLOTS, 0>(key, n, b, lo0, hi0, exact); break;
+        case 16: lo = wave_search_thr<SLOTS, 16, Side>(key, n, b, lo0, hi0, exact, side); break;
+        case 15: lo = wave_search_thr<SLOTS, 15, Side>(key, n, b, lo0, hi0, exact, side); break;
+        case 14: lo = wave_search_thr<SLOTS, 14, Side>(key, n, b, lo0, hi0, exact, side); break;
+        case 13: lo = wave_search_thr<SLOTS, 13, Side>(key, n, b, lo0, hi0, exact, side); break;
+        case 12: lo = wave_search_thr<SLOTS, 12, Side>(key, n, b, lo0, hi0, exact, side); break;
+        case 11: lo = wave_search_thr<SLOTS, 11, Side>(key, n, b, lo0, hi0, exact, side); break;
+        case 10: lo = wave_search_thr<SLOTS, 10, Side>(key, n, b, lo0, hi0, exact, side); break;
+        case 9: lo = wave_search_thr<SLOTS, 9, Side>(key, n, b, lo0, hi0, exact, side); break;
+        default: lo = wave_search_thr<SLOTS, 0, Side>(key, n, b, lo0, hi0, exact, side); break;
         }
     } else {
-        lo = wave_search_thr<SLOTS, 0>(key, n, b, lo0, hi0, exact);
+        lo = wave_search_thr<SLOTS, 0, Side>(key, n, b, lo0, hi0, exact, side);
     }
     if (exact) return lo;
-    const int n_ge = wave_count_ge<SLOTS>(key, n, lo);
+    float flo = score_unkey(lo), fnext = score_unkey(lo + 1u);
+    asm volatile("" : "+v"(flo), "+v"(fnext));           // vector registers, as the counting compare takes them
+    const int n_ge = wave_count_ge_v<SLOTS, 0>(key, n, flo);
     if (n_ge > b) {                                      // more keys equal to the threshold than the budget has room for
-        const int n_gt = (lo == 0xFFFFFFFFu) ? 0 : wave_count_ge<SLOTS>(key, n, lo + 1u);
-        jstar = wave_tie_last<SLOTS>(key, n, lo, b - n_gt, lane);
+        const int n_gt = (lo == 0xFFFFFFFFu) ? 0 : wave_count_ge_v<SLOTS, 0>(key, n, fnext);
+        jstar = wave_tie_last<SLOTS>(key, n, flo, b - n_gt, lane);
     }
     return lo;
 }
 
-// loads a score row from LDS: order-preserving keys (0 for columns >= n; -0.0 counts as +0.0 so that
-// equal floats have equal keys), row maximum and minimum key
 template <int SLOTS>
-__device__ __forceinline__ void sel_row_load(const float *row, int n, int lane, uint32_t (&key)[SLOTS], uint32_t &kmax_out,
+__device__ __forceinline__ uint32_t wave_select_thr(const float (&key)[SLOTS], int n_in, int b_in, uint32_t lo_in,
+                                                    uint32_t hi_in, int lane, int &jstar)
+{
+    NoSide none;
+    return wave_select_thr<SLOTS, NoSide>(key, n_in, b_in, lo_in, hi_in, lane, jstar, none);
+}
+
+// loads a score row from LDS as it is (-inf for columns >= n: below every pivot of the search); the row's maximum and
+// minimum come back as order-preserving keys (-0.0 counts as +0.0), the bracket the search starts from
+template <int SLOTS>
+__device__ __forceinline__ void sel_row_load(const float *row, int n, int lane, float (&key)[SLOTS], uint32_t &kmax_out,
                                              uint32_t &kmin_out)
 {
     // score_key as shift / or / xor; the extremes are taken on the floats (three-input max and min), which order like the keys
     auto to_key = [](float v) {
-        const uint32_t u = __float_as_uint(v);
+        const uint32_t u = __float_as_uint(v + 0.0f);      // -0 + 0 = +0
         return u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);
     };
     float fmax = -__builtin_inff(), fmin = __builtin_inff();
 #pragma unroll
     for (int j = 0; j < SLOTS / 4; ++j) {
         if (256 * (j + 1) <= n) {                          // every column of the group is a key of the row
-            f32x4_a v = *reinterpret_cast<const f32x4_a *>(row + 256 * j + 4 * lane);
+            const f32x4_a v = *reinterpret_cast<const f32x4_a *>(row + 256 * j + 4 * lane);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                v[e] += 0.0f;                              // -0 + 0 = +0
-                key[4 * j + e] = to_key(v[e]);
-            }
+            for (int e = 0; e < 4; ++e) key[4 * j + e] = v[e];
             fmax = __builtin_fmaxf(__builtin_fmaxf(fmax, v[0]), v[1]);
             fmax = __builtin_fmaxf(__builtin_fmaxf(fmax, v[2]), v[3]);
             fmin = __builtin_fminf(__builtin_fminf(fmin, v[0]), v[1]);
@@ -510,74 +560,21 @@ __device__ __forceinline__ void sel_row_load(const float *row, int n, int lane, 
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const bool valid = 256 * j + 4 * lane + e < n;
-                const float ve = v[e] + 0.0f;
-                key[4 * j + e] = valid ? to_key(ve) : 0u;
-                fmax = valid ? __builtin_fmaxf(fmax, ve) : fmax;
-                fmin = valid ? __builtin_fminf(fmin, ve) : fmin;
+                key[4 * j + e] = valid ? v[e] : -__builtin_inff();
+                fmax = valid ? __builtin_fmaxf(fmax, v[e]) : fmax;
+                fmin = valid ? __builtin_fminf(fmin, v[e]) : fmin;
             }
         } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) key[4 * j + e] = 0u;
+            for (int e = 0; e < 4; ++e) key[4 * j + e] = -__builtin_inff();
         }
     }
     kmax_out = wave_max_u32(to_key(fmax));                 // a lane without a valid column holds -inf / +inf: below / above every score
     kmin_out = wave_min_u32(to_key(fmin));
 }
 
-// A workgroup walks several blocks of BQ query rows of one (sequence, head): while the waves search the
-// thresholds of one block, the q and K fragments of the next are already on their way into registers,
-// so the global-load latency of the score phase is hidden. Blocks are dealt to the nb workgroups of a
-// (sequence, head) in zigzag order (k-th visit: block nb*k + bi for even k, nb*k + nb-1-bi for odd k),
-// which gives every workgroup the same number of causal keys.
-// PRE: keys [0, pv.P) of sequence s are read from the prefix cache of input s / pv.K (shared by the pv.K schedules
-// of that input), keys from pv.P on from the sequence's own cache kc, which holds positions pv.P.. only
-// ([n_seq][Hkv][crows][DH]); pv.P is a multiple of 64 and the two caches lie less than 2^31 elements apart.
-// KF: kc (with PRE: pv.kf, for the prefix keys) is the copy of the K cache in MFMA operand order written by k_frag_k,
-// in which the 16 bytes a lane feeds to one MFMA are contiguous over the lanes: a fragment load reads 1 KB in a row
-// (8 full cache lines) where the same load from the cache itself picks 64-byte pieces out of 16 rows. The values in
-// the registers are the same either way. With PRE the sequence's own keys (positions pv.P..) still come from its cache.
-template <int BQ, int SLOTS, int DH, int NW, bool PRE, bool KF>
-__global__ void __launch_bounds__(NW * 64)
-__attribute__((amdgpu_waves_per_eu(SLOTS <= 16 || (SLOTS <= 32 && DH <= 64) ? 4 : SLOTS <= 32 ? 3 : 2, SLOTS <= 16 ? 4 : 8)))
-k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRow *__restrict__ sel,
-              const RowAct *__restrict__ ra, const int32_t *__restrict__ pos0, int Tn, int L_max, int Hq, int Hkv,
-              float scale, int nb, PrefixView pv, int n_lo, int n_hi)
-{
-    constexpr int LPAD = SLOTS * 64, LS = LPAD + 4;        // row stride = 4 mod 64 floats: the 16 query rows of a
-                                                           // 128-bit store hit 16 different bank groups
-    constexpr int RT = (BQ + 15) / 16, KK = DH / 32;
-    constexpr int UA = (SLOTS <= 16 && DH <= 64) ? 8 : 4;  // key tiles held per wave
-    extern __shared__ __align__(16) float sc[];            // [BQ][LS]
-    __shared__ int next_row;
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int bi = blockIdx.x, h = blockIdx.y, s = blockIdx.z;
-    const int p0 = pos0 ? pos0[s] : 0;
-    if (p0 < 0 || p0 + Tn > L_max) return;                 // flagged by the projection kernel; sequence skipped
-    // this launch takes the rows whose key count n = p0 + row + 1 lies in (n_lo, n_hi]: rows [q_lo, q_hi) of the sequence
-    // (long sequences are split by row length over the kernel's variants; the blocks of BQ rows count from q_lo)
-    const int q_lo = n_lo - p0 < 0 ? 0 : (n_lo - p0 > Tn ? Tn : n_lo - p0);
-    const int q_hi = n_hi - p0 < 0 ? 0 : (n_hi - p0 > Tn ? Tn : n_hi - p0);
-    if (q_hi <= q_lo) return;                              // whole workgroup, before any barrier
-    const int n_qb = (q_hi - q_lo + BQ - 1) / BQ;
-    const int kvh = h / (Hq / Hkv);
-    // wave-uniform bases + 32-bit per-lane offsets: one address register per load instead of two
-    const bf16_t *kbase = kc + ((int64_t)s * Hkv + kvh) * (int64_t)(KF ? attn_lpad64(L_max) : L_max) * DH;
-    uint32_t kdelta = 0u;                                   // PRE: offset of the own cache (minus P rows) from the prefix cache
-    if constexpr (PRE) {
-        const bf16_t *own = kc + ((int64_t)s * Hkv + kvh) * (int64_t)pv.crows * DH - (int64_t)pv.P * DH;
-        kbase = (KF ? pv.kf : pv.k) + ((int64_t)(s / pv.K) * Hkv + kvh) * (int64_t)pv.P * DH;
-        kdelta = (uint32_t)__builtin_amdgcn_readfirstlane((int)(own - kbase));
-    }
-    const bf16_t *qbase = q + (int64_t)s * Tn * (int64_t)(Hq * DH) + (int64_t)h * DH;
-    const int l16 = lane & 15, lg = lane >> 4;
-
-    // Rows longer than what the waves hold at once (SLOTS > 16): two register sets of UH key tiles each, one in flight
-    // while the other is multiplied. Shorter rows: one set, all of it loaded while the block before is searched.
-    constexpr bool DB = SLOTS > 16;
-    constexpr int UH = DB ? UA / 2 : UA;
-    bf16x8_a qf[RT][KK], ka[UH][KK], kb[DB ? UH : 1][KK];
+// ---- pieces of k_attn_select's score phase; they expand where qf, kbase, kdelta, pv, sc, scale, lane, l16, lg, w and
+// n_kt (key tiles of the block) are in scope: the kernel itself and SelSide below ----
     // K tile KT_ (clamped to the last tile / key of the block) into SET_[U_]: lane (l16, lg) gets 8 channels at 8*lg of
     // key 16*tile + l16 for every 32-channel piece
 #define SOL_SEL_LOADK(SET_, U_, KT_, KEY0_, NKEYS_)                                                        \
@@ -651,17 +648,114 @@ k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRo
         if (kt < n_kt) { SOL_SEL_MFMA(SET_, u, kt); }                                                      \
     }
 
+
+// The score phase of k_attn_select as a side job of the threshold search (long rows): the fragments in registers and
+// what the macros above refer to, under the same names. One call multiplies the next two groups of key tiles of the
+// block [n_max keys, n_kt tiles] (one per register set) into the LDS rows sc and requests the two groups after them;
+// nothing once the block's tiles are through (tcur >= n_kt).
+template <int BQ, int SLOTS, int DH, int NW, bool PRE, bool KF> struct SelSide {
+    static constexpr int LPAD = SLOTS * 64, LS = LPAD + 4; // row stride = 4 mod 64 floats: the 16 query rows of a
+                                                           // 128-bit store hit 16 different bank groups
+    static constexpr int RT = (BQ + 15) / 16, KK = DH / 32;
+    static constexpr int UA = (SLOTS <= 16 && DH <= 64) ? 8 : 4;  // key tiles held per wave
+    // Rows longer than what the waves hold at once (SLOTS > 16): two register sets of UH key tiles each, one in flight
+    // while the other is multiplied. Shorter rows: one set, all of it loaded while the block before is searched.
+    static constexpr bool DB = SLOTS > 16;
+    static constexpr int UH = DB ? UA / 2 : UA;
+    static constexpr int GS = UH * NW;                     // tiles per group over the workgroup
+    bf16x8_a qf[RT][KK], ka[UH][KK], kb[DB ? UH : 1][KK];
+    const bf16_t *kbase;
+    uint32_t kdelta;
+    PrefixView pv;
+    float *sc;
+    float scale;
+    int lane, l16, lg, w;
+    int n_max, n_kt, tcur;
+    __device__ __forceinline__ void operator()()
+    {
+        if (tcur < n_kt) {
+            SOL_SEL_MFMAG(ka, tcur)
+            SOL_SEL_LOADG(ka, tcur + 2 * GS, n_max, false)
+            if (tcur + GS < n_kt) {
+                SOL_SEL_MFMAG(kb, tcur + GS)
+                SOL_SEL_LOADG(kb, tcur + 3 * GS, n_max, false)
+            }
+            tcur += 2 * GS;
+        }
+    }
+};
+
+// A workgroup walks several blocks of BQ query rows of one (sequence, head): while the waves search the
+// thresholds of one block, the q and K fragments of the next are already on their way into registers,
+// so the global-load latency of the score phase is hidden. Blocks are dealt to the nb workgroups of a
+// (sequence, head) in zigzag order (k-th visit: block nb*k + bi for even k, nb*k + nb-1-bi for odd k),
+// which gives every workgroup the same number of causal keys.
+// PRE: keys [0, pv.P) of sequence s are read from the prefix cache of input s / pv.K (shared by the pv.K schedules
+// of that input), keys from pv.P on from the sequence's own cache kc, which holds positions pv.P.. only
+// ([n_seq][Hkv][crows][DH]); pv.P is a multiple of 64 and the two caches lie less than 2^31 elements apart.
+// KF: kc (with PRE: pv.kf, for the prefix keys) is the copy of the K cache in MFMA operand order written by k_frag_k,
+// in which the 16 bytes a lane feeds to one MFMA are contiguous over the lanes: a fragment load reads 1 KB in a row
+// (8 full cache lines) where the same load from the cache itself picks 64-byte pieces out of 16 rows. The values in
+// the registers are the same either way. With PRE the sequence's own keys (positions pv.P..) still come from its cache.
+template <int BQ, int SLOTS, int DH, int NW, bool PRE, bool KF>
+__global__ void __launch_bounds__(NW * 64)
+__attribute__((amdgpu_waves_per_eu(SLOTS <= 16 || (SLOTS <= 32 && DH <= 64) ? 4 : SLOTS <= 32 ? 3 : 2, SLOTS <= 16 ? 4 : 8)))
+k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRow *__restrict__ sel,
+              const RowAct *__restrict__ ra, const int32_t *__restrict__ pos0, int Tn, int L_max, int Hq, int Hkv,
+              float scale, int nb, PrefixView pv, int n_lo, int n_hi)
+{
+    using Frags = SelSide<BQ, SLOTS, DH, NW, PRE, KF>;
+    constexpr int LS = Frags::LS, RT = Frags::RT, KK = Frags::KK, UH = Frags::UH, GS = Frags::GS;
+    constexpr bool DB = Frags::DB;
+    extern __shared__ __align__(16) float sc[];            // [BQ][LS]
+    __shared__ int next_row;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int bi = blockIdx.x, h = blockIdx.y, s = blockIdx.z;
+    const int p0 = pos0 ? pos0[s] : 0;
+    if (p0 < 0 || p0 + Tn > L_max) return;                 // flagged by the projection kernel; sequence skipped
+    // this launch takes the rows whose key count n = p0 + row + 1 lies in (n_lo, n_hi]: rows [q_lo, q_hi) of the sequence
+    // (long sequences are split by row length over the kernel's variants; the blocks of BQ rows count from q_lo)
+    const int q_lo = n_lo - p0 < 0 ? 0 : (n_lo - p0 > Tn ? Tn : n_lo - p0);
+    const int q_hi = n_hi - p0 < 0 ? 0 : (n_hi - p0 > Tn ? Tn : n_hi - p0);
+    if (q_hi <= q_lo) return;                              // whole workgroup, before any barrier
+    const int n_qb = (q_hi - q_lo + BQ - 1) / BQ;
+    const int kvh = h / (Hq / Hkv);
+    // wave-uniform bases + 32-bit per-lane offsets: one address register per load instead of two
+    const bf16_t *kbase = kc + ((int64_t)s * Hkv + kvh) * (int64_t)(KF ? attn_lpad64(L_max) : L_max) * DH;
+    uint32_t kdelta = 0u;                                   // PRE: offset of the own cache (minus P rows) from the prefix cache
+    if constexpr (PRE) {
+        const bf16_t *own = kc + ((int64_t)s * Hkv + kvh) * (int64_t)pv.crows * DH - (int64_t)pv.P * DH;
+        kbase = (KF ? pv.kf : pv.k) + ((int64_t)(s / pv.K) * Hkv + kvh) * (int64_t)pv.P * DH;
+        kdelta = (uint32_t)__builtin_amdgcn_readfirstlane((int)(own - kbase));
+    }
+    const bf16_t *qbase = q + (int64_t)s * Tn * (int64_t)(Hq * DH) + (int64_t)h * DH;
+    const int l16 = lane & 15, lg = lane >> 4;
+
+    Frags fr;                                              // the fragments, and the score phase as the search's side job
+    auto &qf = fr.qf;
+    auto &ka = fr.ka;
+    auto &kb = fr.kb;
+    fr.kbase = kbase, fr.kdelta = kdelta, fr.pv = pv, fr.sc = sc, fr.scale = scale;
+    fr.lane = lane, fr.l16 = l16, fr.lg = lg, fr.w = w;
+    fr.n_max = 0, fr.n_kt = 0, fr.tcur = 0;
     int visit = 0, qb = bi;
     if (qb >= n_qb) return;
     SOL_SEL_LOAD(qb);
-    while (true) {
-        const int q0 = q_lo + qb * BQ;
-        const int rows = (q_hi - q0 < BQ) ? (q_hi - q0) : BQ;
-        const int n_max = p0 + q0 + rows;
-        const int n_kt = (n_max + 15) >> 4;
-        // ---- scores of this block into LDS: the loads of a group of tiles go out while the group before it is multiplied ----
-        constexpr int GS = UH * NW;                         // tiles per group over the workgroup
-        if constexpr (DB) {
+    if constexpr (DB) {
+        // Long rows, one row per wave. The score phase is bound by what the CU's L1 delivers and the search by the
+        // vector and scalar pipes, so a wave does both at once: while it searches its row of block k (in registers; the
+        // LDS rows are free once every wave has taken its own) each step of the search also multiplies one group of key
+        // tiles of block k + 1 into LDS and requests the group after the next. What the search leaves over is done behind
+        // it. The barriers wait for LDS only (s_waitcnt lgkmcnt): global loads and the result's store stay in flight.
+        static_assert(BQ == NW, "one row per wave");
+#define SOL_SEL_BARRIER asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
+        {                                                   // scores of the workgroup's first block
+            const int q0 = q_lo + qb * BQ;
+            const int rows = (q_hi - q0 < BQ) ? (q_hi - q0) : BQ;
+            const int n_max = p0 + q0 + rows;
+            const int n_kt = (n_max + 15) >> 4;
             for (int t0 = w;; t0 += 2 * GS) {
                 SOL_SEL_MFMAG(ka, t0)
                 SOL_SEL_LOADG(ka, t0 + 2 * GS, n_max, false)
@@ -670,12 +764,55 @@ k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRo
                 SOL_SEL_LOADG(kb, t0 + 3 * GS, n_max, false)
                 if (t0 + 2 * GS >= n_kt) break;
             }
-        } else {
-            SOL_SEL_MFMAG(ka, w)
-            for (int t0 = w + GS; t0 < n_kt; t0 += GS) {
-                SOL_SEL_LOADG(ka, t0, n_max, false)
-                SOL_SEL_MFMAG(ka, t0)
+        }
+        while (true) {
+            const int q0 = q_lo + qb * BQ;
+            const int rows = (q_hi - q0 < BQ) ? (q_hi - q0) : BQ;
+            ++visit;
+            const int qb_next = nb * visit + ((visit & 1) ? nb - 1 - bi : bi);
+            const bool more = qb_next < n_qb;
+            const bool have = w < rows;                     // this wave's row of the block
+            const int n = p0 + q0 + w + 1;
+            RowAct act = RowAct();
+            if (have) act = ra[(int64_t)s * Tn + q0 + w];
+            fr.n_max = 0, fr.n_kt = 0;                      // the next block's
+            if (more) {
+                SOL_SEL_LOAD(qb_next);
+                const int q0n = q_lo + qb_next * BQ;
+                fr.n_max = p0 + (q_hi < q0n + BQ ? q_hi : q0n + BQ);
+                fr.n_kt = (fr.n_max + 15) >> 4;
             }
+            SOL_SEL_BARRIER;                                // the block's scores are complete
+            float key[SLOTS];
+            uint32_t kmax = 0u, kmin = 0u;
+            if (have) sel_row_load<SLOTS>(sc + w * LS, n, lane, key, kmax, kmin);
+            SOL_SEL_BARRIER;                                // every row is in registers: LDS may be overwritten
+            fr.tcur = w;
+            if (have) {
+                const int b = budget_ceil(act.keep_num, act.keep_den, n);
+                uint32_t thr = 0u;                          // key 0: below every score, everything kept
+                int js = 0x7FFFFFFF;
+                if (b < n) thr = wave_select_thr<SLOTS>(key, n, b, kmin, kmax, lane, js, fr);
+                if (lane == 0)
+                    sel[((int64_t)s * Tn + q0 + w) * Hq + h] =
+                        SelRow{thr ? score_unkey(thr) : -__builtin_inff(), score_unkey(kmax), js, 0};
+            }
+            if (!more) break;
+            while (fr.tcur < fr.n_kt) fr();
+            qb = qb_next;
+        }
+#undef SOL_SEL_BARRIER
+    } else {
+    while (true) {
+        const int q0 = q_lo + qb * BQ;
+        const int rows = (q_hi - q0 < BQ) ? (q_hi - q0) : BQ;
+        const int n_max = p0 + q0 + rows;
+        const int n_kt = (n_max + 15) >> 4;
+        // ---- scores of this block into LDS: the loads of a group of tiles go out while the group before it is multiplied ----
+        SOL_SEL_MFMAG(ka, w)
+        for (int t0 = w + GS; t0 < n_kt; t0 += GS) {
+            SOL_SEL_LOADG(ka, t0, n_max, false)
+            SOL_SEL_MFMAG(ka, t0)
         }
         if (tid == 0) next_row = NW;
         __syncthreads();
@@ -690,7 +827,8 @@ k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRo
             const int n = p0 + q0 + r + 1;
             const RowAct act = ra[(int64_t)s * Tn + q0 + r];
             const int b = budget_ceil(act.keep_num, act.keep_den, n);
-            uint32_t key[SLOTS], kmax, kmin;
+            float key[SLOTS];
+            uint32_t kmax, kmin;
             sel_row_load<SLOTS>(sc + r * LS, n, lane, key, kmax, kmin);
             uint32_t thr = 0u;                             // key 0: below every score, everything kept
             int js = 0x7FFFFFFF;
@@ -706,6 +844,7 @@ k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRo
         if (!more) break;
         __syncthreads();                                   // every row is in registers or done: LDS may be overwritten
         qb = qb_next;
+    }
     }
 #undef SOL_SEL_LOADK
 #undef SOL_SEL_LOADG
@@ -726,7 +865,8 @@ __global__ void __launch_bounds__(64) k_test_select_rows(const float *__restrict
     const int n = n_valid[r], b = kk[r];
     for (int j = lane; j < SLOTS * 64; j += 64) sc[j] = j < n ? row[j] : 0.f;
     __syncthreads();
-    uint32_t key[SLOTS], kmax, kmin;
+    float key[SLOTS];
+    uint32_t kmax, kmin;
     sel_row_load<SLOTS>(sc, n, lane, key, kmax, kmin);
     uint32_t thr = 0u;
     int js = 0x7FFFFFFF;
