@@ -443,10 +443,17 @@ __device__ __forceinline__ uint32_t wave_search_thr(const float (&key)[SLOTS], i
         const float fp = __builtin_fmaf(fhi - flo, glo * __builtin_amdgcn_rcpf(glo - ghi), flo);
         const uint32_t ufp = __float_as_uint(fp);         // as score_key; which of the two zeros' keys a pivot takes is immaterial
         uint32_t mid = ufp ^ ((uint32_t)((int32_t)ufp >> 31) | 0x80000000u);
-        mid = mid > lo ? mid : lo + 1u;
-        mid = mid < hi ? mid : hi;
-        if (it >= 12) mid = lo + ((hi - lo + 1u) >> 1);
-        const float fmid = score_unkey(mid);
+        mid = __builtin_elementwise_max(mid, lo + 1u);
+        mid = __builtin_elementwise_min(mid, hi);
+        if (it >= 12) {                                   // a branch that is hardly ever taken, not five instructions per step
+            mid = lo + ((hi - lo + 1u) >> 1);
+            asm volatile("" : "+v"(mid));
+        }
+        // score_unkey as a shift and one three-input bit operation (the sign mask passes through an empty asm, or the
+        // compiler turns it back into a compare and a select)
+        int32_t sgn = (int32_t)mid >> 31;
+        asm("" : "+v"(sgn));
+        const float fmid = __uint_as_float(mid ^ (~(uint32_t)sgn | 0x80000000u));
         int cnt;
         if constexpr (NG < 0) cnt = wave_count_ge_sw<SLOTS>(key, n, (n + 255) >> 8, fmid);
         else cnt = wave_count_ge_v<SLOTS, NG>(key, n, fmid);
