@@ -434,7 +434,10 @@ __device__ __forceinline__ uint32_t wave_search_thr(const float (&key)[SLOTS], i
     asm volatile("" : "+v"(lo), "+v"(hi));               // from here on the compiler treats the bracket as per-lane data
     // counts enter the line as log-odds, t(c) = log2((c + 1/2) / (n - c + 1/2)) - t(b - 1/2): for bell-shaped score
     // distributions t is close to linear in the score where the count itself is S-shaped
-    const float nh = (float)n + 0.5f, t_b = __builtin_amdgcn_logf((float)b * __builtin_amdgcn_rcpf((float)(n - b) + 1.0f));
+    // uniform and fixed over the loop: kept in scalar registers (the vector registers are what limits the kernel's occupancy)
+    const float nh = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int((float)n + 0.5f)));
+    const float t_b = __int_as_float(__builtin_amdgcn_readfirstlane(
+        __float_as_int(__builtin_amdgcn_logf((float)b * __builtin_amdgcn_rcpf((float)(n - b) + 1.0f)))));
     float flo = score_unkey(lo), fhi = score_unkey(hi);
     float glo = __builtin_amdgcn_logf(nh * 2.0f) - t_b, ghi = -__builtin_amdgcn_logf(nh * 2.0f) - t_b;
     float w_up = 1.0f, w_dn = 1.0f;                      // what the end that stays put is scaled by if the step goes up / down
@@ -445,7 +448,7 @@ __device__ __forceinline__ uint32_t wave_search_thr(const float (&key)[SLOTS], i
         uint32_t mid = ufp ^ ((uint32_t)((int32_t)ufp >> 31) | 0x80000000u);
         mid = __builtin_elementwise_max(mid, lo + 1u);
         mid = __builtin_elementwise_min(mid, hi);
-        if (it >= 12) {                                   // a branch that is hardly ever taken, not five instructions per step
+        if (__builtin_amdgcn_readfirstlane(it) >= 12) {   // a branch that is hardly ever taken, not five instructions per step
             mid = lo + ((hi - lo + 1u) >> 1);
             asm volatile("" : "+v"(mid));
         }
@@ -585,7 +588,8 @@ __device__ __forceinline__ void sel_row_load(const float *row, int n, int lane, 
     // K tile KT_ (clamped to the last tile / key of the block) into SET_[U_]: lane (l16, lg) gets 8 channels at 8*lg of
     // key 16*tile + l16 for every 32-channel piece
 #define SOL_SEL_LOADK(SET_, U_, KT_, KEY0_, NKEYS_)                                                        \
-    {                                                                                                      \
+    {   /* addresses as a uniform base plus a 32-bit byte offset per lane: one address register per load, no 64-bit sums */ \
+        const char *kb_ = reinterpret_cast<const char *>(kbase);                                           \
         if constexpr (KF && PRE) {      /* prefix tiles from the operand-order copy, own tiles from the own cache */ \
             int kt_ = (KT_);                                                                               \
             if (kt_ * 16 >= (NKEYS_)) kt_ = ((NKEYS_) - 1) >> 4;                                           \
@@ -594,22 +598,23 @@ __device__ __forceinline__ void sel_row_load(const float *row, int n, int lane, 
             if (key >= (NKEYS_)) key = (NKEYS_) - 1;                                                       \
             const uint32_t off = in_pre ? (uint32_t)kt_ * (uint32_t)(KK * 512) + (uint32_t)(lane * 8)      \
                                         : kdelta + (uint32_t)key * (uint32_t)DH + (uint32_t)(lg * 8);      \
-            const uint32_t step = in_pre ? 512u : 32u;                                                     \
+            const uint32_t step = in_pre ? 1024u : 64u;                                                    \
             _Pragma("unroll") for (int kk = 0; kk < KK; ++kk)                                              \
-                SET_[U_][kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(kbase + off + kk * step)); \
+                SET_[U_][kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(kb_ + (off * 2u + kk * step))); \
         } else if constexpr (KF) {                                                                         \
             int kt_ = (KT_);                                                                               \
             if (kt_ * 16 >= (NKEYS_)) kt_ = ((NKEYS_) - 1) >> 4;                                           \
-            const uint32_t fo = (uint32_t)kt_ * (uint32_t)(KK * 512) + (uint32_t)((KEY0_) * 8);            \
+            const uint32_t fo = ((uint32_t)kt_ * (uint32_t)(KK * 512) + (uint32_t)((KEY0_) * 8)) * 2u;     \
             _Pragma("unroll") for (int kk = 0; kk < KK; ++kk)                                              \
-                SET_[U_][kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(kbase + fo + kk * 512)); \
+                SET_[U_][kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(kb_ + fo + kk * 1024)); \
         } else {                                                                                           \
             int key = (KEY0_) + (U_) * NW * 16;                                                            \
             if (key >= (NKEYS_)) key = (NKEYS_) - 1;                                                       \
             uint32_t ko = (uint32_t)key * (uint32_t)DH + (uint32_t)(lg * 8);                               \
             if constexpr (PRE) ko += key >= pv.P ? kdelta : 0u;                                            \
+            ko *= 2u;                                                                                      \
             _Pragma("unroll") for (int kk = 0; kk < KK; ++kk)                                              \
-                SET_[U_][kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(kbase + ko + kk * 32)); \
+                SET_[U_][kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(kb_ + ko + kk * 64)); \
         }                                                                                                  \
     }
     // group of UH tiles from this wave's tile T0_ on (stride NW), if the group has a tile below the block's last key.
@@ -631,9 +636,10 @@ __device__ __forceinline__ void sel_row_load(const float *row, int n, int lane, 
         _Pragma("unroll") for (int rt = 0; rt < RT; ++rt) {                                                \
             int qr = q0_ + rt * 16 + l16;                                                                  \
             if (qr >= Tn) qr = Tn - 1;                                                                     \
-            const uint32_t qo = (uint32_t)qr * (uint32_t)(Hq * DH) + (uint32_t)(lg * 8);                   \
+            const uint32_t qo = ((uint32_t)qr * (uint32_t)(Hq * DH) + (uint32_t)(lg * 8)) * 2u;            \
             _Pragma("unroll") for (int kk = 0; kk < KK; ++kk)                                              \
-                qf[rt][kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(qbase + qo + kk * 32)); \
+                qf[rt][kk] = __builtin_bit_cast(bf16x8_a, *reinterpret_cast<const u32x4_a *>(              \
+                                                    reinterpret_cast<const char *>(qbase) + qo + kk * 64)); \
         }                                                                                                  \
         SOL_SEL_LOADG(ka, w, nmax_, true)                                                                  \
         if constexpr (DB) SOL_SEL_LOADG(kb, w + UH * NW, nmax_, true)                                      \
@@ -2590,9 +2596,9 @@ bool launch_attn_tile(const void *q, const void *k_cache, const void *v_cache, v
     else
         hipLaunchKernelGGL((k_transpose_v<128>), tg, dim3(256), 0, st, (const bf16_t *)v_cache, (bf16_t *)vt, pos0, T,
                            L_max, Hkv, lpadv);
-    // Long rows: K in MFMA operand order for the threshold kernel, which reads all causal keys once per block of 8 query
-    // rows (up to 1024 keys a block has 16 rows and the copy does not pay)
-    const bool frag = L_max > 1024;
+    // K in MFMA operand order for the threshold kernel, which reads all causal keys once per block of 8 or 16 query rows
+    // (up to 256 keys the copy does not pay)
+    const bool frag = L_max > 256;
     if (frag && !launch_attn_frag_k(k_cache, kfr, pos0, n_seq, T, L_max, Hkv, dh, st)) return false;
     // score rows of a workgroup stay in LDS: 16 rows x 1024 keys (66 KB) lets two workgroups share a CU. A launch per
     // class of row lengths: the rows of a long sequence that see at most 1024 (2048) keys go to the variant for that
@@ -2603,9 +2609,9 @@ bool launch_attn_tile(const void *q, const void *k_cache, const void *v_cache, v
                   : launch_attn_select_t<BQ, SL, 128, 8, false, KF>(q, KF ? kfr : k_cache, sel, ra, pos0, n_seq, T, L_max, Hq, Hkv, st, PrefixView(), LO, HI)
     constexpr int ALL = 1 << 30;
     if (L_max <= 256) { SOL_SEL(32, 4, false, 0, ALL); }
-    else if (L_max <= 1024) { SOL_SEL(16, 16, false, 0, ALL); }
+    else if (L_max <= 1024) { SOL_SEL(16, 16, true, 0, ALL); }
     else {
-        SOL_SEL(16, 16, false, 0, 1024);
+        SOL_SEL(16, 16, true, 0, 1024);
         if (ok && L_max <= 1280) { SOL_SEL(8, 20, true, 1024, ALL); }       // a 1024-token prefix plus a short episode
         else if (ok && L_max <= 2048) { SOL_SEL(8, 32, true, 1024, ALL); }
         else if (ok) {
