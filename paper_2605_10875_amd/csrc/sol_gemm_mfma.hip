@@ -254,6 +254,100 @@ struct EpiQkvRope {
     }
 };
 
+// The same epilogue for whole wave tiles whose 128 consecutive rows touch at most two sequences (Tn >= 128, M a
+// multiple of the tile height). EpiQkvRope reads a row's (sequence, position) and then, at an address that depends on
+// it, its cos / sin pairs: two exposed load latencies per block of 32 rows, about 16 us per tile under the GEMM's own
+// traffic, as long as the MFMA part of a K = 2048 tile. Here the positions come from arithmetic on the tile's first
+// row (two scalar loads of pos0 per tile), so every table load can be issued at once, and they run two groups of four
+// rows ahead of the rotation and the stores. Values and destinations are those of EpiQkvRope.
+template <int DHT>
+struct EpiQkvRopeTile {
+    static constexpr bool persistent_walk = true;
+    static constexpr bool whole_tile = true;
+    bf16_t *q, *kc, *vc;
+    const float2 *rope; const int32_t *pos0;
+    int Tn, L_chk, L_max, Hq, Hkv, n_seq;                // L_chk: positions a sequence may reach; L_max: rows of a cache slab
+    template <int TM, int TN>
+    __device__ __forceinline__ void tile(const floatx16_t (&acc)[TM][TN], int64_t row_w, int vcol_w, int lane) const
+    {
+        constexpr int dh = DHT, half = DHT / 2, ND = DHT / 64;   // ND: table columns a lane needs per row (c, c + 32, ..)
+        static_assert(TN * 32 == 128 && TM * 32 == 128, "128 x 128 wave tiles");
+        const int c = lane & 31, rg = lane >> 5;
+        const int nq = Hq * dh, nkv = Hkv * dh;
+        const int seg = vcol_w < nq ? 0 : (vcol_w < nq + nkv ? 1 : 2);        // the wave tile lies inside one of q / k / v
+        const int w0 = vcol_w - (seg == 0 ? 0 : (seg == 1 ? nq : nq + nkv));  // column inside the segment
+        const int hd = w0 / dh, wi = w0 - hd * dh;
+        const int hstep = (seg == 0 || dh >= TN * 32) ? 0 : (int)((int64_t)L_max * dh) - dh;   // next head inside the tile (dh = 64)
+        bf16_t *const cache = seg == 1 ? kc : vc;
+        // rows row_w + k, k < 128: sequence s0 up to its end, then s0 + 1
+        const int s0 = (int)(row_w / Tn), t0 = (int)(row_w - (int64_t)s0 * Tn);
+        const int pa = pos0 ? pos0[s0] : 0;
+        const int pb = (pos0 && s0 + 1 < n_seq) ? pos0[s0 + 1] : 0;
+        const bool va = pa >= 0 && pa + Tn <= L_chk, vb = pb >= 0 && pb + Tn <= L_chk;
+        constexpr int NCH = TM * 4;                              // groups of four rows (registers 4g .. 4g + 3 of block i)
+        float2 cs[3][4][ND];
+        auto row_pos = [&](int k, int &seq, int &pos, bool &ok) {
+            const int t = t0 + k;
+            const bool a = t < Tn;
+            seq = a ? s0 : s0 + 1;
+            pos = a ? pa + t : pb + (t - Tn);
+            ok = a ? va : vb;
+        };
+        auto load_group = [&](int n, float2 (&x)[4][ND]) {
+            if (seg < 2) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    int seq, pos;
+                    bool ok;
+                    row_pos((n >> 2) * 32 + 8 * (n & 3) + 4 * rg + e, seq, pos, ok);
+                    const float2 *tr = rope + (int64_t)(ok ? pos : 0) * half + c;
+#pragma unroll
+                    for (int dd = 0; dd < ND; ++dd) x[e][dd] = tr[32 * dd];
+                }
+            }
+        };
+        load_group(0, cs[0]);
+        load_group(1, cs[1]);
+#pragma unroll
+        for (int n = 0; n < NCH; ++n) {
+            if (n + 2 < NCH) load_group(n + 2, cs[(n + 2) % 3]);
+            const int i = n >> 2, g4 = n & 3;
+#pragma unroll
+            for (int e = 0; e < 4; e += 2) {                     // rows in pairs, as store_bf16_rows2 takes them
+                const int k = i * 32 + 8 * g4 + 4 * rg + e;
+                int sq0, ps0, sq1, ps1;
+                bool ok0, ok1;
+                row_pos(k, sq0, ps0, ok0);
+                row_pos(k + 1, sq1, ps1, ok1);
+                bf16_t *d0, *d1;
+                if (seg == 0) { d0 = q + (row_w + k) * (int64_t)nq + w0; d1 = d0 + nq; }
+                else {
+                    d0 = cache + (((int64_t)sq0 * Hkv + hd) * L_max + (ok0 ? ps0 : 0)) * dh + wi;
+                    d1 = cache + (((int64_t)sq1 * Hkv + hd) * L_max + (ok1 ? ps1 : 0)) * dh + wi;
+                }
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const int r = 4 * g4 + e;
+                    float o0 = acc[i][j][r], o1 = acc[i][j][r + 1];
+                    if (seg < 2) {                               // q or k: rotate
+                        const int cj0 = (32 * j) & (dh - 1);     // the tile's first column inside its head
+                        const bool lo = cj0 < half;
+                        const int jp = lo ? j + half / 32 : j - half / 32;   // tile of the partner column
+                        const int dd = (cj0 & (half - 1)) / 32;
+                        const float y0 = acc[i][jp][r], y1 = acc[i][jp][r + 1];
+                        const float2 a0 = cs[n % 3][e][dd], a1 = cs[n % 3][e + 1][dd];
+                        o0 = lo ? (o0 * a0.x - y0 * a0.y) : (o0 * a0.x + y0 * a0.y);
+                        o1 = lo ? (o1 * a1.x - y1 * a1.y) : (o1 * a1.x + y1 * a1.y);
+                    }
+                    const int hj = (32 * j) / dh;                // head inside the tile of column 32*j + c
+                    const int64_t off = (seg == 0) ? 32 * j : (int64_t)hj * hstep + 32 * j;
+                    store_bf16_rows2(d0 + off, d1 + off, ok0, ok1, c, o0, o1);
+                }
+            }
+        }
+    }
+};
+
 // row -> (sequence, absolute position), position -1 (and the overflow flag) if the sequence does not fit
 __global__ void __launch_bounds__(256)
 k_row_positions(const int32_t *__restrict__ pos0, int64_t M, int Tn, int L_max, int2 *__restrict__ row_sp, int *flags)
@@ -711,6 +805,14 @@ bool launch_gemm_qkv_rope(const void *h, const void *wq, const void *wk, const v
     bm.mode = 0; bm.half = 0; bm.ld = d;
     int2 *row_sp = (int2 *)row_sp_ws;
     hipLaunchKernelGGL(k_row_positions, dim3((unsigned)((M + 255) / 256)), dim3(256), 0, st, pos0, M, T, L_max, row_sp, flags);
+    if (M % 256 == 0 && T >= 128) {                      // whole tiles of at most two sequences each: positions by arithmetic
+        if (dh == 64) {
+            EpiQkvRopeTile<64> epi{(bf16_t *)q, (bf16_t *)kc, (bf16_t *)vc, rope, pos0, T, L_max, crows, Hq, Hkv, n_seq};
+            return launch_mfma<SOL_TILE_QKV>((const bf16_t *)h, d, bm, M, nq + 2 * nkv, d, epi, st);
+        }
+        EpiQkvRopeTile<128> epi{(bf16_t *)q, (bf16_t *)kc, (bf16_t *)vc, rope, pos0, T, L_max, crows, Hq, Hkv, n_seq};
+        return launch_mfma<SOL_TILE_QKV>((const bf16_t *)h, d, bm, M, nq + 2 * nkv, d, epi, st);
+    }
     if (dh == 64) {
         EpiQkvRope<64> epi{(bf16_t *)q, (bf16_t *)kc, (bf16_t *)vc, rope, row_sp, crows, Hq, Hkv};
         return launch_mfma<SOL_TILE_QKV>((const bf16_t *)h, d, bm, M, nq + 2 * nkv, d, epi, st);

@@ -157,6 +157,42 @@ def test_bf16_layer_with_prefix_cache_and_stepwise_equivalence():
     ctx.close()
 
 
+def test_bf16_layer_chunks_at_different_cache_positions_with_one_that_does_not_fit():
+    """4 sequences x 192 rows of a 1B-shaped layer: 768 rows = three 256-row GEMM tiles, whose 128-row wave tiles span
+    two sequences each (rows 128..255 are the end of sequence 0 and the start of sequence 1), so the q/k/v epilogue for
+    whole tiles derives (sequence, position) of its rows on both sides of a boundary; the chunks sit behind prefixes of
+    different lengths and sequence 2 does not fit its cache: it is skipped and reported, its cache stays as it was,
+    and the others match the oracle run on them alone."""
+    shape, table = synth.LLAMA_1B, synth.TABLE_C2
+    n_seq, T, L_max = 4, 192, 400
+    pos0 = np.array([0, 40, 300, 7], np.int32)               # 300 + 192 > 400
+    w = synth.layer_weights(shape, 2200, bf16=True)
+    x = synth.hidden_states(n_seq, T, shape.d_model, 2201, bf16=True)
+    ids = synth.iid_actions(len(table), (n_seq, T), 2202)
+    rng = np.random.default_rng(2203)
+    kc0 = torch.tensor(rng.standard_normal((n_seq, shape.n_kv_heads, L_max, shape.head_dim)).astype(np.float32))
+    kc0 = kc0.to(torch.bfloat16).float().numpy()             # prefix keys / values: bf16-representable
+    vc0 = torch.tensor(rng.standard_normal(kc0.shape).astype(np.float32)).to(torch.bfloat16).float().numpy()
+    ctx = sol.Sol(shape, table, dtype=sol.BF16, max_positions=L_max)
+    kc_d, vc_d = dev(kc0, sol.BF16), dev(vc0, sol.BF16)
+    out = host(ctx.layer_forward(dev_weights(w, sol.BF16), dev(x, sol.BF16), dev(ids), kc_d, vc_d, pos0=dev(pos0)))
+    assert ctx.device_status() == sol.ERR_CACHE_OVERFLOW and ctx.device_status() == sol.OK
+    kg, vg = host(kc_d), host(vc_d)
+    ctx.close()
+    assert np.array_equal(kg[2], kc0[2]) and np.array_equal(vg[2], vc0[2])     # the skipped sequence's cache is untouched
+    fit = [0, 1, 3]
+    kr, vr = kc0[fit].copy(), vc0[fit].copy()
+    refbf, kr, vr, _ = _oracle_layer(shape, table, w, x[fit], ids[fit], L_max, True, pos0=pos0[fit], kc=kr, vc=vr)
+    check_rows(kg[fit].transpose(0, 2, 1, 3), kr.transpose(0, 2, 1, 3), 2e-2, 0.3, 0.02, "K cache")
+    check_rows(vg[fit].transpose(0, 2, 1, 3), vr.transpose(0, 2, 1, 3), 2e-2, 0.3, 0.02, "V cache")
+    for j, sq in enumerate(fit):                              # rows before and after the chunk keep the prefix values
+        assert np.array_equal(kg[sq][:, :pos0[sq]], kc0[sq][:, :pos0[sq]])
+        assert np.array_equal(kg[sq][:, pos0[sq] + T:], kc0[sq][:, pos0[sq] + T:])
+    k32, v32 = kc0[fit].copy(), vc0[fit].copy()
+    ref32, _, _, _ = _oracle_layer(shape, table, w, x[fit], ids[fit], L_max, False, pos0=pos0[fit], kc=k32, vc=v32)
+    check_by_bit_class(out[fit], refbf, ref32, ids[fit], table, "layer output")
+
+
 def _stack(shape, seed, bf16):
     layers = [synth.layer_weights(shape, seed + l, bf16=bf16) for l in range(shape.n_layers)]
     return layers, synth.head_weights(shape, seed + 100, bf16=bf16)
