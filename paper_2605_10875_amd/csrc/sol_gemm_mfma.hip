@@ -196,6 +196,8 @@ struct EpiQkvRope {
     bf16_t *q, *kc, *vc;
     const float2 *rope; const int2 *row_sp;
     int L_max, Hq, Hkv;
+    const int *only_if_flagged;                          // not null: the kernel runs only if a sequence has been flagged (see EpiQkvRopeTile)
+    __device__ __forceinline__ bool run() const { return !only_if_flagged || (*only_if_flagged & FLAG_CACHE_OVERFLOW) != 0; }
     template <int TN> using Aux = AuxRope<TN>;
     template <int TN> __device__ __forceinline__ void preload0(int64_t row0, int64_t row1, AuxRope<TN> &x) const
     {
@@ -262,47 +264,76 @@ struct EpiQkvRope {
 // rows ahead of the rotation and the stores. Values and destinations are those of EpiQkvRope.
 template <int DHT>
 struct EpiQkvRopeTile {
-    static constexpr bool persistent_walk = true;
+    static constexpr bool persistent_walk = false;       // inside the persistent walk, next to the held fragments, it spills
     static constexpr bool whole_tile = true;
     bf16_t *q, *kc, *vc;
     const float2 *rope; const int32_t *pos0;
-    int Tn, L_chk, L_max, Hq, Hkv, n_seq;                // L_chk: positions a sequence may reach; L_max: rows of a cache slab
+    int Tn, L_max, Hq, Hkv, n_seq;                       // L_max: rows of a cache slab
+    const int *flags;
+    // flags not null: the kernel runs only while no sequence of the call has been flagged (k_row_positions, just before
+    // it, flags those that do not fit their cache): then every store is unconditional. Otherwise the launcher's second
+    // kernel, with EpiQkvRope and its per-row predicates, does the work (both versions in one kernel spill the
+    // accumulators). Without per-sequence start positions the host has checked that T rows fit: flags is null.
+    __device__ __forceinline__ bool run() const { return !flags || (*flags & FLAG_CACHE_OVERFLOW) == 0; }
     template <int TM, int TN>
     __device__ __forceinline__ void tile(const floatx16_t (&acc)[TM][TN], int64_t row_w, int vcol_w, int lane) const
+    {
+        // the wave tile's corner is the same in every lane; said so, what follows from it (segment, bases, positions)
+        // stays in scalar registers and the segment tests become branches instead of selects per value
+        const int vcol_u = __builtin_amdgcn_readfirstlane(vcol_w);
+        const int64_t row_u = (int64_t)(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(row_w >> 32)) << 32) |
+                                        (uint32_t)__builtin_amdgcn_readfirstlane((int)row_w));
+        // rows row_u + k, k < 128: sequence s0 up to its end, then s0 + 1
+        const int s0 = (int)(row_u / Tn), t0 = (int)(row_u - (int64_t)s0 * Tn);
+        const int pa = pos0 ? pos0[s0] : 0;
+        const int pb = (pos0 && s0 + 1 < n_seq) ? pos0[s0 + 1] : 0;
+        tile_rows<TM, TN>(acc, row_u, vcol_u, lane, s0, t0, pa, pb);
+    }
+    // Destinations are a uniform base per 32-column tile plus a 32-bit byte offset per lane. Of a pair of rows a lane
+    // stores one (even columns the first, odd columns the second: two bf16 of that row, its own and its neighbour's),
+    // so it needs the destination of that row only; the cos / sin pairs it needs for both.
+    template <int TM, int TN>
+    __device__ __forceinline__ void tile_rows(const floatx16_t (&acc)[TM][TN], int64_t row_w, int vcol_w, int lane, int s0,
+                                              int t0, int pa, int pb) const
     {
         constexpr int dh = DHT, half = DHT / 2, ND = DHT / 64;   // ND: table columns a lane needs per row (c, c + 32, ..)
         static_assert(TN * 32 == 128 && TM * 32 == 128, "128 x 128 wave tiles");
         const int c = lane & 31, rg = lane >> 5;
+        const bool odd = (c & 1) != 0;
         const int nq = Hq * dh, nkv = Hkv * dh;
         const int seg = vcol_w < nq ? 0 : (vcol_w < nq + nkv ? 1 : 2);        // the wave tile lies inside one of q / k / v
         const int w0 = vcol_w - (seg == 0 ? 0 : (seg == 1 ? nq : nq + nkv));  // column inside the segment
         const int hd = w0 / dh, wi = w0 - hd * dh;
         const int hstep = (seg == 0 || dh >= TN * 32) ? 0 : (int)((int64_t)L_max * dh) - dh;   // next head inside the tile (dh = 64)
-        bf16_t *const cache = seg == 1 ? kc : vc;
-        // rows row_w + k, k < 128: sequence s0 up to its end, then s0 + 1
-        const int s0 = (int)(row_w / Tn), t0 = (int)(row_w - (int64_t)s0 * Tn);
-        const int pa = pos0 ? pos0[s0] : 0;
-        const int pb = (pos0 && s0 + 1 < n_seq) ? pos0[s0 + 1] : 0;
-        const bool va = pa >= 0 && pa + Tn <= L_chk, vb = pb >= 0 && pb + Tn <= L_chk;
+        // row k of the tile lies (k < kx ? ca : cb) + k rows of rs bytes behind `base` (q: the tile's first row; caches:
+        // the slab of (s0, head hd), that of s0 + 1 being Hkv * L_max rows further on)
+        const int kx = Tn - t0;
+        char *base;
+        int ca, cb;
+        uint32_t rs;
+        if (seg == 0) { base = reinterpret_cast<char *>(q + row_w * (int64_t)nq + w0); ca = cb = 0; rs = (uint32_t)nq * 2u; }
+        else {
+            base = reinterpret_cast<char *>((seg == 1 ? kc : vc) + ((int64_t)s0 * Hkv + hd) * (int64_t)L_max * dh + wi);
+            ca = pa + t0; cb = Hkv * L_max + pb - kx; rs = (uint32_t)dh * 2u;
+        }
+        char *bj[TN];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bj[j] = base + (32 * j + ((32 * j) / dh) * hstep) * 2;
+        const uint32_t lane_col = (uint32_t)(c - (odd ? 1 : 0)) * 2u;
+        const int ta = pa + t0, tb = pb - kx;                    // position of row k: (k < kx ? ta : tb) + k
+        const char *const tbase = reinterpret_cast<const char *>(rope);
         constexpr int NCH = TM * 4;                              // groups of four rows (registers 4g .. 4g + 3 of block i)
         float2 cs[3][4][ND];
-        auto row_pos = [&](int k, int &seq, int &pos, bool &ok) {
-            const int t = t0 + k;
-            const bool a = t < Tn;
-            seq = a ? s0 : s0 + 1;
-            pos = a ? pa + t : pb + (t - Tn);
-            ok = a ? va : vb;
-        };
         auto load_group = [&](int n, float2 (&x)[4][ND]) {
             if (seg < 2) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    int seq, pos;
-                    bool ok;
-                    row_pos((n >> 2) * 32 + 8 * (n & 3) + 4 * rg + e, seq, pos, ok);
-                    const float2 *tr = rope + (int64_t)(ok ? pos : 0) * half + c;
+                    const int k = (n >> 2) * 32 + 8 * (n & 3) + 4 * rg + e;
+                    const bool a = k < kx;
+                    const int pos = (a ? ta : tb) + k;
+                    const uint32_t to = ((uint32_t)pos * (uint32_t)half + (uint32_t)c) * 8u;
 #pragma unroll
-                    for (int dd = 0; dd < ND; ++dd) x[e][dd] = tr[32 * dd];
+                    for (int dd = 0; dd < ND; ++dd) x[e][dd] = *reinterpret_cast<const float2 *>(tbase + to + dd * 256);
                 }
             }
         };
@@ -313,18 +344,10 @@ struct EpiQkvRopeTile {
             if (n + 2 < NCH) load_group(n + 2, cs[(n + 2) % 3]);
             const int i = n >> 2, g4 = n & 3;
 #pragma unroll
-            for (int e = 0; e < 4; e += 2) {                     // rows in pairs, as store_bf16_rows2 takes them
-                const int k = i * 32 + 8 * g4 + 4 * rg + e;
-                int sq0, ps0, sq1, ps1;
-                bool ok0, ok1;
-                row_pos(k, sq0, ps0, ok0);
-                row_pos(k + 1, sq1, ps1, ok1);
-                bf16_t *d0, *d1;
-                if (seg == 0) { d0 = q + (row_w + k) * (int64_t)nq + w0; d1 = d0 + nq; }
-                else {
-                    d0 = cache + (((int64_t)sq0 * Hkv + hd) * L_max + (ok0 ? ps0 : 0)) * dh + wi;
-                    d1 = cache + (((int64_t)sq1 * Hkv + hd) * L_max + (ok1 ? ps1 : 0)) * dh + wi;
-                }
+            for (int e = 0; e < 4; e += 2) {                     // rows in pairs
+                const int ko = i * 32 + 8 * g4 + 4 * rg + e + (odd ? 1 : 0);   // the row of the pair this lane stores
+                const bool a = ko < kx;
+                const uint32_t roff = (uint32_t)((a ? ca : cb) + ko) * rs + lane_col;
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
                     const int r = 4 * g4 + e;
@@ -339,10 +362,14 @@ struct EpiQkvRopeTile {
                         o0 = lo ? (o0 * a0.x - y0 * a0.y) : (o0 * a0.x + y0 * a0.y);
                         o1 = lo ? (o1 * a1.x - y1 * a1.y) : (o1 * a1.x + y1 * a1.y);
                     }
-                    const int hj = (32 * j) / dh;                // head inside the tile of column 32*j + c
-                    const int64_t off = (seg == 0) ? 32 * j : (int64_t)hj * hstep + 32 * j;
-                    store_bf16_rows2(d0 + off, d1 + off, ok0, ok1, c, o0, o1);
+                    // the neighbour's values of both rows (lanes c ^ 1); even columns store (own, neighbour's) of the
+                    // first row, odd columns (neighbour's, own) of the second
+                    const float n0 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, o0), 0xB1, 0xF, 0xF, false));
+                    const float n1 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, o1), 0xB1, 0xF, 0xF, false));
+                    const uint32_t pk = pack_bf16x2(odd ? n1 : o0, odd ? o1 : n0);
+                    *reinterpret_cast<uint32_t *>(bj[j] + roff) = pk;
                 }
+                __builtin_amdgcn_sched_barrier(0);               // one pair at a time: hoisted accumulator reads would spill
             }
         }
     }
@@ -486,6 +513,8 @@ k_nll_finish_cols(const float2 *__restrict__ part, const float *__restrict__ tgt
 // Register r of accumulator tile (i, j) is row 32*i + 8*(r/4) + 4*(lane/32) + r%4, column 32*j + lane%32
 // of the wave tile (row_w already holds the wave tile's first row + 4*(lane/32)). Per 32-row tile all
 // global reads of the epilogue are issued first, then the row pairs are combined and stored.
+template <class E, class = void> struct epi_gated { static constexpr bool value = false; };
+template <class E> struct epi_gated<E, decltype((void)&E::run)> { static constexpr bool value = true; };
 template <class E, class = void> struct epi_whole_tile { static constexpr bool value = false; };
 template <class E> struct epi_whole_tile<E, decltype((void)E::whole_tile)> { static constexpr bool value = E::whole_tile; };
 
@@ -555,6 +584,9 @@ k_gemm_mfma(const bf16_t *__restrict__ A, int64_t lda, BMap bmap, int64_t M, int
     static_assert(BM % ROWS_PER_PASS == 0 && BN % ROWS_PER_PASS == 0, "tile / thread mismatch");
     extern __shared__ __align__(16) unsigned char lds[];
 
+    if constexpr (epi_gated<Epi>::value) {
+        if (!epi.run()) return;                            // the whole grid, before any barrier
+    }
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / NWN, wn = wave - wm * NWN;
 
@@ -804,20 +836,30 @@ bool launch_gemm_qkv_rope(const void *h, const void *wq, const void *wk, const v
     bm.seg_end[0] = nq; bm.seg_end[1] = nq + nkv; bm.seg_end[2] = nq + 2 * nkv;
     bm.mode = 0; bm.half = 0; bm.ld = d;
     int2 *row_sp = (int2 *)row_sp_ws;
-    hipLaunchKernelGGL(k_row_positions, dim3((unsigned)((M + 255) / 256)), dim3(256), 0, st, pos0, M, T, L_max, row_sp, flags);
-    if (M % 256 == 0 && T >= 128) {                      // whole tiles of at most two sequences each: positions by arithmetic
-        if (dh == 64) {
-            EpiQkvRopeTile<64> epi{(bf16_t *)q, (bf16_t *)kc, (bf16_t *)vc, rope, pos0, T, L_max, crows, Hq, Hkv, n_seq};
-            return launch_mfma<SOL_TILE_QKV>((const bf16_t *)h, d, bm, M, nq + 2 * nkv, d, epi, st);
-        }
-        EpiQkvRopeTile<128> epi{(bf16_t *)q, (bf16_t *)kc, (bf16_t *)vc, rope, pos0, T, L_max, crows, Hq, Hkv, n_seq};
-        return launch_mfma<SOL_TILE_QKV>((const bf16_t *)h, d, bm, M, nq + 2 * nkv, d, epi, st);
-    }
+    // whole tiles of at most two sequences each: positions by arithmetic (the epilogue's 32-bit byte offsets span two
+    // cache slabs, 128 rows of q, and the cos / sin table); it runs unless k_row_positions has flagged a sequence, in
+    // which case the general kernel behind it does
+    const bool tiles = M % 256 == 0 && T >= 128 && (int64_t)(Hkv + 1) * crows * dh * 2 < (1ll << 31) &&
+                       (int64_t)L_max * dh * 4 < (1ll << 31);
+    const bool sure = pos0 == nullptr && T <= L_max;          // every sequence starts at 0 and fits: nothing to flag
+    int *gate = sure ? nullptr : flags;
+    if (!(tiles && sure))                                     // the rows' (sequence, position) table, and the flags
+        hipLaunchKernelGGL(k_row_positions, dim3((unsigned)((M + 255) / 256)), dim3(256), 0, st, pos0, M, T, L_max, row_sp, flags);
     if (dh == 64) {
-        EpiQkvRope<64> epi{(bf16_t *)q, (bf16_t *)kc, (bf16_t *)vc, rope, row_sp, crows, Hq, Hkv};
+        if (tiles) {
+            EpiQkvRopeTile<64> te{(bf16_t *)q, (bf16_t *)kc, (bf16_t *)vc, rope, pos0, T, crows, Hq, Hkv, n_seq, gate};
+            if (!launch_mfma<SOL_TILE_QKV>((const bf16_t *)h, d, bm, M, nq + 2 * nkv, d, te, st)) return false;
+            if (sure) return true;
+        }
+        EpiQkvRope<64> epi{(bf16_t *)q, (bf16_t *)kc, (bf16_t *)vc, rope, row_sp, crows, Hq, Hkv, tiles ? flags : nullptr};
         return launch_mfma<SOL_TILE_QKV>((const bf16_t *)h, d, bm, M, nq + 2 * nkv, d, epi, st);
     }
-    EpiQkvRope<128> epi{(bf16_t *)q, (bf16_t *)kc, (bf16_t *)vc, rope, row_sp, crows, Hq, Hkv};
+    if (tiles) {
+        EpiQkvRopeTile<128> te{(bf16_t *)q, (bf16_t *)kc, (bf16_t *)vc, rope, pos0, T, crows, Hq, Hkv, n_seq, gate};
+        if (!launch_mfma<SOL_TILE_QKV>((const bf16_t *)h, d, bm, M, nq + 2 * nkv, d, te, st)) return false;
+        if (sure) return true;
+    }
+    EpiQkvRope<128> epi{(bf16_t *)q, (bf16_t *)kc, (bf16_t *)vc, rope, row_sp, crows, Hq, Hkv, tiles ? flags : nullptr};
     return launch_mfma<SOL_TILE_QKV>((const bf16_t *)h, d, bm, M, nq + 2 * nkv, d, epi, st);
 }
 
