@@ -24,6 +24,9 @@ def _rows(rng, rows, n, kind):
         return np.full((rows, n), 1.25, np.float32)
     if kind == "wide":                      # many binades, both signs
         return (rng.standard_normal((rows, n)) * np.exp(rng.uniform(-20, 20, (rows, n)))).astype(np.float32)
+    if kind == "signed0":                   # both zeros, subnormals of both signs and a few ordinary values: compared as floats
+        vals = np.array([0.0, -0.0, 1e-42, -1e-42, 3e-39, -3e-39, 1.0, -1.0, 1.1754944e-38], np.float32)
+        return vals[rng.integers(0, len(vals), (rows, n))]
     if kind == "heavy":                     # heavy tails plus a few outliers at the start of the row (sink keys)
         x = rng.standard_normal((rows, n)) * np.abs(rng.standard_normal((rows, n))) * 1.3
         x[:, :min(4, n)] += 6.0
@@ -32,7 +35,7 @@ def _rows(rng, rows, n, kind):
 
 
 @pytest.mark.parametrize("n", [1, 2, 63, 64, 65, 257, 1024, 1025, 2048, 4096, 4097, 8192, 20000])
-@pytest.mark.parametrize("kind", ["normal", "ties", "const", "wide"])
+@pytest.mark.parametrize("kind", ["normal", "ties", "const", "wide", "signed0"])
 def test_topk_select_bit_exact(n, kind):
     rng = np.random.default_rng(n * 7 + len(kind))
     rows = 12
@@ -53,7 +56,7 @@ def test_topk_select_bit_exact(n, kind):
 
 
 @pytest.mark.parametrize("n", [1, 2, 63, 64, 65, 255, 256, 257, 700, 1024, 1025, 1280, 1281, 2048, 2049, 4096])
-@pytest.mark.parametrize("kind", ["normal", "ties", "const", "wide", "heavy"])
+@pytest.mark.parametrize("kind", ["normal", "ties", "const", "wide", "heavy", "signed0"])
 def test_attn_threshold_stage_bit_exact(n, kind):
     """the threshold search of the batched attention path (every row-length variant) against the definition"""
     rng = np.random.default_rng(n * 11 + len(kind))
