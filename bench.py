@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the action-conditioned decoder-layer path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload all|c2|c2p|c3|c5|c4|c5d|c4p|refresh|episode|episodep]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload all|c2|c2p|c3|c5|c4|c5d|c4p|refresh|episode|episodep|libgemm]
 
 A step is one pass of the measured unit over one batch of seeded synthetic input that is already
 resident in HBM. Default (`all`): the headline is C3, the largest single-GPU configuration and the one
@@ -552,13 +552,47 @@ def run_workload(args, wl):
     raise ValueError(wl)
 
 
+def run_libgemm(args):
+    """For scale only, not part of the product path: the plain bf16 GEMM that PyTorch dispatches to the vendor library
+    (no epilogue, C written as bf16) on the shapes of the layer GEMMs and the LM head, timed with events."""
+    shapes = [("gate_up_1b", 32768, 16384, 2048), ("down_1b", 32768, 2048, 8192), ("qkv_1b", 32768, 3072, 2048),
+              ("o_proj_1b", 32768, 2048, 2048), ("gate_up_8b", 32768, 28672, 4096), ("down_8b", 32768, 4096, 14336),
+              ("lm_head_1b", 32768, 128256, 2048)]
+    out = {}
+    g = torch.Generator(device="cuda").manual_seed(args.seed)
+    for name, M, N, K in shapes:
+        a = torch.randn((M, K), device="cuda", dtype=torch.float32, generator=g).to(torch.bfloat16)
+        w = torch.randn((N, K), device="cuda", dtype=torch.float32, generator=g).to(torch.bfloat16)
+        iters = max(3, min(args.steps, 5 if N > 100000 else args.steps))
+        for _ in range(max(1, min(args.warmup, 3))):
+            c = a @ w.t()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(iters):
+            c = a @ w.t()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / iters
+        out[name] = {"M": M, "N": N, "K": K, "ms": ms, "tflops": 2.0 * M * N * K / ms / 1e9}
+        del a, w, c
+        torch.cuda.empty_cache()
+    return {"metric": "library_gemm_tflops", "value": out["gate_up_1b"]["tflops"], "unit": "TFLOP/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": out["gate_up_1b"]["ms"], "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "plain bf16 GEMMs of the vendor library via torch.matmul on the layer's shapes (comparison only)"},
+            "roofline": {"bound": "mfma", "achieved": out["gate_up_1b"]["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                         "frac": out["gate_up_1b"]["tflops"] / PEAK_BF16_TFLOPS, "traffic": None},
+            "shapes": out}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="all",
-                    choices=["all", "c2", "c2p", "c3", "c5", "c4", "c5d", "c4p", "refresh", "episode", "episodep"])
+                    choices=["all", "c2", "c2p", "c3", "c5", "c4", "c5d", "c4p", "refresh", "episode", "episodep", "libgemm"])
     ap.add_argument("--seed", type=int, default=1234)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-peaks", action="store_true", help="skip the two peak microbenchmarks")
@@ -588,6 +622,8 @@ def main():
             for k in ("n_gpus", "steps", "warmup", "higher_is_better", "scaling", "vs_baseline", "data"):
                 sub.pop(k, None)
             res["configs"][wl] = sub
+    elif args.workload == "libgemm":
+        res = run_libgemm(args)
     else:
         res = run_workload(args, args.workload)
     if peaks:
