@@ -25,6 +25,8 @@ namespace sol {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16_t;
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));   // native 16-byte vector (stays in registers)
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int BK = 64;               // K step (bf16 elements); one LDS row = 128 bytes = 8 chunks of 16 B
 constexpr int GROUP_M = 4;           // tile rows walked together by an XCD: its 32 CUs then hold 4 x 8 tiles (measured on the
@@ -568,6 +570,61 @@ template <int N> __device__ __forceinline__ void vm_wait()
     __builtin_amdgcn_s_waitcnt(((N >> 4) << 14) | 0x0F70 | (N & 15));
 }
 
+// EpiResidF32 for whole tiles of a kernel that is not persistent (its two LDS stages are dead once the K loop is
+// over). In the accumulator layout a lane holds one column of four consecutive rows, so the plain epilogue issues a
+// 4-byte store and a 2-byte residual load per element: 1024 store and 1024 load instructions per tile through the
+// CU's one memory pipeline, which takes them at a few tens of cycles each whatever their size. Here the wave passes
+// its tile, 64 rows at a time, through its own quarter of the LDS and takes it back row-wise: a lane then owns four
+// consecutive columns of a row, reads the residual as 8 bytes and stores 16 (two whole 512-byte rows of the wave tile
+// per instruction): 64 + 64 instructions per wave tile instead of 256 + 256. Same values as EpiResidF32.
+struct EpiResidF32Tile {
+    static constexpr bool persistent_walk = false;
+    static constexpr bool whole_tile = true;
+    const bf16_t *resid; float *out; int64_t ld;
+    template <int TM, int TN>
+    __device__ __forceinline__ void tile(const floatx16_t (&acc)[TM][TN], int64_t row_w, int vcol_w, int lane) const
+    {
+        static_assert(TM * 32 == 128 && TN * 32 == 128, "128 x 128 wave tiles: 64 rows of fp32 fill the wave's 32 KB");
+        extern __shared__ __align__(16) unsigned char lds_all[];          // the kernel's dynamic segment (128 KB)
+        const int vcol_u = __builtin_amdgcn_readfirstlane(vcol_w);
+        const int64_t row_u = (int64_t)(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(row_w >> 32)) << 32) |
+                                        (uint32_t)__builtin_amdgcn_readfirstlane((int)row_w));
+        const int wave_u = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+        const int c = lane & 31, rg = lane >> 5;
+        unsigned char *const lw = lds_all + (uint32_t)wave_u * 32768u;    // [64 rows][128 fp32]
+        const char *const rbase = reinterpret_cast<const char *>(resid + row_u * ld + vcol_u);
+        char *const obase = reinterpret_cast<char *>(out + row_u * ld + vcol_u);
+        const uint32_t ld_u = (uint32_t)ld;                      // a wave tile spans 128 rows: offsets far below 2^32
+        // row-wise pass: instruction t of a half covers rows 2t and 2t + 1; this lane: row 2t + rg, columns 4c .. 4c + 3
+        const uint32_t el0 = (uint32_t)rg * ld_u + (uint32_t)c * 4u;
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf) {
+            u32x2_t rv[32];                                      // the half's residual, requested before the LDS round trip
+#pragma unroll
+            for (int t = 0; t < 32; ++t)
+                rv[t] = *reinterpret_cast<const u32x2_t *>(rbase + (el0 + (uint32_t)(hf * 64 + 2 * t) * ld_u) * 2u);
+#pragma unroll
+            for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int k = ii * 32 + 8 * (r >> 2) + (r & 3);   // row of the half, less the lane's 4 * rg
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        *reinterpret_cast<float *>(lw + (uint32_t)(k + 4 * rg) * 512u + (uint32_t)(c + 32 * j) * 4u) = acc[hf * 2 + ii][j][r];
+                }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the wave's own writes, read back by the wave: no barrier
+#pragma unroll
+            for (int t = 0; t < 32; ++t) {
+                const f32x4_t v = *reinterpret_cast<const f32x4_t *>(lw + (uint32_t)(2 * t + rg) * 512u + (uint32_t)c * 16u);
+                const f32x4_t o = {v[0] + __uint_as_float(rv[t][0] << 16), v[1] + __uint_as_float(rv[t][0] & 0xFFFF0000u),
+                                   v[2] + __uint_as_float(rv[t][1] << 16), v[3] + __uint_as_float(rv[t][1] & 0xFFFF0000u)};
+                *reinterpret_cast<f32x4_t *>(obase + (el0 + (uint32_t)(hf * 64 + 2 * t) * ld_u) * 4u) = o;
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the reads are over before the next half overwrites the rows
+        }
+    }
+};
+
 // PERSIST: one workgroup per CU walks every tile of its slot in the XCD's band (tile index + workgroups per XCD) and
 // the pipeline runs across the tile boundary: the last two K steps of a tile request the first two slices of the next
 // one, so only a workgroup's first tile starts cold. (The pipeline's state between steps is LDS only, no registers,
@@ -868,6 +925,10 @@ bool launch_gemm_resid_f32(const void *a, const void *w, const void *resid, floa
 {
     BMap bm{};
     bm.base[0] = (const bf16_t *)w; bm.seg_end[0] = bm.seg_end[1] = bm.seg_end[2] = N; bm.mode = 0; bm.ld = K;
+    if (M % 256 == 0) {                                   // whole tiles
+        EpiResidF32Tile te{(const bf16_t *)resid, out, N};
+        return launch_mfma<SOL_TILE>((const bf16_t *)a, K, bm, M, N, K, te, st);
+    }
     EpiResidF32 epi{(const bf16_t *)resid, out, N};
     return launch_mfma<SOL_TILE>((const bf16_t *)a, K, bm, M, N, K, epi, st);
 }
