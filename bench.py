@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the action-conditioned decoder-layer path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload all|c2|c2p|c3|c5|c4|c5d|c4p|refresh|episode|episodep|libgemm]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload all|c2|c2p|c3|c5|c5p|c4|c5d|c4p|refresh|episode|episodep|libgemm]
 
 A step is one pass of the measured unit over one batch of seeded synthetic input that is already
 resident in HBM. Default (`all`): the headline is C3, the largest single-GPU configuration and the one
@@ -523,6 +523,10 @@ def run_workload(args, wl):
         return run_layer(args, synth.LLAMA_8B, 2, 4, 4096, synth.TABLE_C2,
                          "C5: Llama-3.1-8B-shaped decoder layer, bf16, 2 inputs x 4 schedules x 4096 tokens", workload=wl,
                          oracle_tokens=768)
+    if wl == "c5p":
+        return run_layer(args, synth.LLAMA_8B, 2, 4, 4096, synth.TABLE_C2,
+                         "C5 under " + PAPER_CFG + ": Llama-3.1-8B-shaped decoder layer, bf16, 2 inputs x 4 schedules x 4096 "
+                         "tokens", preset=sol.PAPER_PRESET, workload=wl, oracle_tokens=768)
     if wl == "c4":
         return run_decode(args, stack_shape, 64, 8192, synth.TABLE_C4,
                           "C4: Llama-3.2-1B-shaped decode step, bf16, 64 sequences x 8192-token KV cache, 16 layers + final "
@@ -592,7 +596,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="all",
-                    choices=["all", "c2", "c2p", "c3", "c5", "c4", "c5d", "c4p", "refresh", "episode", "episodep", "libgemm"])
+                    choices=["all", "c2", "c2p", "c3", "c5", "c5p", "c4", "c5d", "c4p", "refresh", "episode", "episodep", "libgemm"])
     ap.add_argument("--seed", type=int, default=1234)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-peaks", action="store_true", help="skip the two peak microbenchmarks")

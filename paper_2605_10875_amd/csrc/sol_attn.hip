@@ -670,7 +670,7 @@ template <int BQ, int SLOTS, int DH, int NW, bool PRE, bool KF> struct SelSide {
     static constexpr int LPAD = SLOTS * 64, LS = LPAD + 4; // row stride = 4 mod 64 floats: the 16 query rows of a
                                                            // 128-bit store hit 16 different bank groups
     static constexpr int RT = (BQ + 15) / 16, KK = DH / 32;
-    static constexpr int UA = (SLOTS <= 16 && DH <= 64) ? 8 : 4;  // key tiles held per wave
+    static constexpr int UA = (SLOTS <= 16 && DH <= 64) ? 8 : (SLOTS <= 32 && DH > 64) ? 2 : 4;  // key tiles held per wave
     // Rows longer than what the waves hold at once (SLOTS > 16): two register sets of UH key tiles each, one in flight
     // while the other is multiplied. Shorter rows: one set, all of it loaded while the block before is searched.
     static constexpr bool DB = SLOTS > 16;
@@ -712,7 +712,7 @@ template <int BQ, int SLOTS, int DH, int NW, bool PRE, bool KF> struct SelSide {
 // the registers are the same either way. With PRE the sequence's own keys (positions pv.P..) still come from its cache.
 template <int BQ, int SLOTS, int DH, int NW, bool PRE, bool KF>
 __global__ void __launch_bounds__(NW * 64)
-__attribute__((amdgpu_waves_per_eu(SLOTS <= 16 || (SLOTS <= 32 && DH <= 64) ? 4 : SLOTS <= 32 ? 3 : 2, SLOTS <= 16 ? 4 : 8)))
+__attribute__((amdgpu_waves_per_eu(SLOTS <= 32 ? 4 : 2, SLOTS <= 16 ? 4 : 8)))
 k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRow *__restrict__ sel,
               const RowAct *__restrict__ ra, const int32_t *__restrict__ pos0, int Tn, int L_max, int Hq, int Hkv,
               float scale, int nb, PrefixView pv, int n_lo, int n_hi)
@@ -954,7 +954,7 @@ __device__ __forceinline__ void pv_probs(const floatx4_a (&st)[2], float scale, 
 // Head size 64 with 4+ heads per group: three waves per SIMD (168 registers) are kept; without the floor the walk over
 // two blocks takes 186 and only two workgroups fit a CU.
 template <int DH, int G, bool PRE, int NQT>
-__global__ void __launch_bounds__(G * 64) __attribute__((amdgpu_waves_per_eu(DH == 64 && G >= 4 ? 3 : 1, 8)))
+__global__ void __launch_bounds__(G * 64) __attribute__((amdgpu_waves_per_eu(DH == 64 && G >= 4 ? 4 : (DH == 128 && G >= 4 ? 2 : 1), 8)))
 k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf16_t *__restrict__ vt,
           const SelRow *__restrict__ sel, float *__restrict__ o32, const int32_t *__restrict__ pos0, int Tn, int L_max, int Hq,
           int Hkv, int lpadv, float scale, PrefixView pv)
@@ -1035,7 +1035,7 @@ k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf1
         for (int dt = 0; dt < DT; ++dt) oacc[qt][dt] = floatx4_a{0.f, 0.f, 0.f, 0.f};
 
     // staging: global -> registers -> LDS, one chunk ahead
-    u32x4_a kreg0[K_PIECES], vreg0[V_PIECES], kreg1[K_PIECES], vreg1[V_PIECES];
+    u32x4_a kreg0[K_PIECES], vreg0[V_PIECES];
 #define SOL_PV_GLOAD(KR, VR, CH_)                                                                                  \
     {                                                                                                      \
         const int key0_ = (CH_) * KC;                                                                      \
@@ -1070,17 +1070,13 @@ k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf1
     // registers into the other stage and chunk ch + 2 is fetched: global latency has a whole iteration to hide in
     SOL_PV_GLOAD(kreg0, vreg0, 0);
     SOL_PV_LSTORE(kreg0, vreg0, 0);
-    if (1 < n_chunks) SOL_PV_GLOAD(kreg1, vreg1, 1);
+    if (1 < n_chunks) SOL_PV_GLOAD(kreg0, vreg0, 1);
     __syncthreads();
     for (int ch = 0; ch < n_chunks; ++ch) {
         const int stg = ch & 1;
-        if (stg == 0) {
-            if (ch + 1 < n_chunks) SOL_PV_LSTORE(kreg1, vreg1, 1);
-            if (ch + 2 < n_chunks) SOL_PV_GLOAD(kreg0, vreg0, ch + 2);
-        } else {
-            if (ch + 1 < n_chunks) SOL_PV_LSTORE(kreg0, vreg0, 0);
-            if (ch + 2 < n_chunks) SOL_PV_GLOAD(kreg1, vreg1, ch + 2);
-        }
+        // one register set: what was fetched an iteration ago goes to LDS, then the set is requested again
+        if (ch + 1 < n_chunks) SOL_PV_LSTORE(kreg0, vreg0, stg ^ 1);
+        if (ch + 2 < n_chunks) SOL_PV_GLOAD(kreg0, vreg0, ch + 2);
         const unsigned char *kb = pvl + stg * STAGE, *vb = kb + K_BYTES;
 #pragma unroll
         for (int cc = 0; cc < 2; ++cc) {
@@ -2328,7 +2324,7 @@ template <int DH, int G, int W, bool PRE, int NQT>
 // (head size 64: a floor of 3 / 4 waves per SIMD caps the registers at 168 / 128; left alone the compiler takes 218 and
 // 138 and the exp / pack chains of the softmax have nothing to overlap with: 0.94 -> 0.74 ms at C2 under the paper's
 // configuration)
-__global__ void __launch_bounds__(G * 64) __attribute__((amdgpu_waves_per_eu(DH == 64 ? (NQT == 1 ? 4 : 3) : 1, 8)))
+__global__ void __launch_bounds__(G * 64) __attribute__((amdgpu_waves_per_eu(DH == 64 ? (NQT == 1 ? 4 : 3) : (G >= 4 ? 2 : 1), 8)))
 k_attn_pv_pages(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf16_t *__restrict__ vt,
                 const unsigned long long *__restrict__ selp, float *__restrict__ o32, const int32_t *__restrict__ pos0, int Tn,
                 int L_max, int Hq, int Hkv, int lpadv, float scale, int log2S, int n_sink, int n_window, PrefixView pv)
@@ -2394,7 +2390,7 @@ k_attn_pv_pages(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, con
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) oacc[qt][dt] = floatx4_a{0.f, 0.f, 0.f, 0.f};
 
-    u32x4_a kreg0[K_PIECES], vreg0[V_PIECES], kreg1[K_PIECES], vreg1[V_PIECES];
+    u32x4_a kreg0[K_PIECES], vreg0[V_PIECES];
 #define SOL_PV_GLOAD(KR, VR, CH_)                                                                                  \
     {                                                                                                      \
         const int key0_ = (CH_) * KC;                                                                      \
@@ -2426,17 +2422,13 @@ k_attn_pv_pages(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, con
     }
     SOL_PV_GLOAD(kreg0, vreg0, 0);
     SOL_PV_LSTORE(kreg0, vreg0, 0);
-    if (1 < n_chunks) SOL_PV_GLOAD(kreg1, vreg1, 1);
+    if (1 < n_chunks) SOL_PV_GLOAD(kreg0, vreg0, 1);
     __syncthreads();
     for (int ch = 0; ch < n_chunks; ++ch) {
         const int stg = ch & 1;
-        if (stg == 0) {
-            if (ch + 1 < n_chunks) SOL_PV_LSTORE(kreg1, vreg1, 1);
-            if (ch + 2 < n_chunks) SOL_PV_GLOAD(kreg0, vreg0, ch + 2);
-        } else {
-            if (ch + 1 < n_chunks) SOL_PV_LSTORE(kreg0, vreg0, 0);
-            if (ch + 2 < n_chunks) SOL_PV_GLOAD(kreg1, vreg1, ch + 2);
-        }
+        // one register set: what was fetched an iteration ago goes to LDS, then the set is requested again
+        if (ch + 1 < n_chunks) SOL_PV_LSTORE(kreg0, vreg0, stg ^ 1);
+        if (ch + 2 < n_chunks) SOL_PV_GLOAD(kreg0, vreg0, ch + 2);
         const unsigned char *kb = pvl + stg * STAGE, *vb = kb + K_BYTES;
 #pragma unroll
         for (int cc = 0; cc < 2; ++cc) {
