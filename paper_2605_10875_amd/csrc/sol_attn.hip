@@ -670,7 +670,10 @@ template <int BQ, int SLOTS, int DH, int NW, bool PRE, bool KF> struct SelSide {
     static constexpr int LPAD = SLOTS * 64, LS = LPAD + 4; // row stride = 4 mod 64 floats: the 16 query rows of a
                                                            // 128-bit store hit 16 different bank groups
     static constexpr int RT = (BQ + 15) / 16, KK = DH / 32;
-    static constexpr int UA = (SLOTS <= 16 && DH <= 64) ? 8 : (SLOTS <= 32 && DH > 64) ? 2 : 4;  // key tiles held per wave
+    // key tiles held per wave. Head size 128, rows up to 2048 keys: 2, with which the kernel fits 128 registers and a
+    // second workgroup fits the CU (4 tiles: 168 registers, one workgroup; 1.28 -> 0.83 ms for the 1025..2048-key rows
+    // of 4096-token sequences at the 8B shape)
+    static constexpr int UA = (SLOTS <= 16 && DH <= 64) ? 8 : (SLOTS <= 32 && DH > 64) ? 2 : 4;
     // Rows longer than what the waves hold at once (SLOTS > 16): two register sets of UH key tiles each, one in flight
     // while the other is multiplied. Shorter rows: one set, all of it loaded while the block before is searched.
     static constexpr bool DB = SLOTS > 16;
@@ -951,8 +954,10 @@ __device__ __forceinline__ void pv_probs(const floatx4_a (&st)[2], float scale, 
 // PRE: as in k_attn_select; vt then is the transposed copy of the own cache ([n_seq][Hkv][DH][lpadv], positions
 // pv.P..) and pv.vt that of the prefix cache ([inputs][Hkv][DH][pv.lpadv]); 64-key chunks never straddle pv.P.
 // NQT: query tiles of 16 rows per workgroup (2; 1 for passes of at most 16 rows per sequence).
-// Head size 64 with 4+ heads per group: three waves per SIMD (168 registers) are kept; without the floor the walk over
-// two blocks takes 186 and only two workgroups fit a CU.
+// Occupancy floors (4+ heads per group): four waves per SIMD at head size 64 (128 registers; the 18 values that do not
+// fit are spilled outside the chunk loop), two at head size 128 (256 registers, no spills). Left alone the compiler takes
+// 186 and 328 registers, and with one wave per SIMD the softmax's exp / pack chains and the MFMAs have nothing to
+// overlap with: 2.90 -> 1.81 ms per launch at the 8B shape with 4096-token sequences.
 template <int DH, int G, bool PRE, int NQT>
 __global__ void __launch_bounds__(G * 64) __attribute__((amdgpu_waves_per_eu(DH == 64 && G >= 4 ? 4 : (DH == 128 && G >= 4 ? 2 : 1), 8)))
 k_attn_pv(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf16_t *__restrict__ vt,
@@ -2323,7 +2328,8 @@ __device__ __forceinline__ float max_over_lane_groups(float v)
 template <int DH, int G, int W, bool PRE, int NQT>
 // (head size 64: a floor of 3 / 4 waves per SIMD caps the registers at 168 / 128; left alone the compiler takes 218 and
 // 138 and the exp / pack chains of the softmax have nothing to overlap with: 0.94 -> 0.74 ms at C2 under the paper's
-// configuration)
+// configuration; head size 128 with 4+ heads per group: 2 waves per SIMD, 256 registers instead of 410, 4.51 -> 2.44 ms
+// at the 8B shape with 4096-token sequences)
 __global__ void __launch_bounds__(G * 64) __attribute__((amdgpu_waves_per_eu(DH == 64 ? (NQT == 1 ? 4 : 3) : (G >= 4 ? 2 : 1), 8)))
 k_attn_pv_pages(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, const bf16_t *__restrict__ vt,
                 const unsigned long long *__restrict__ selp, float *__restrict__ o32, const int32_t *__restrict__ pos0, int Tn,
