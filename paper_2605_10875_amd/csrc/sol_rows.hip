@@ -662,10 +662,13 @@ typedef short i16x2_r __attribute__((ext_vector_type(2)));
 // [v * CW, (v + 1) * CW) of 512 channels each; counts are combined through LDS.
 // The row takes 4 registers per chunk; without a floor on the waves per SIMD the compiler spreads the unrolled passes
 // over the whole register file (256 registers, one wave per SIMD) and nothing hides the latency of the DPP
-// reductions and ballots: the floor caps the registers at 128 (rows of up to 16 chunks per wave) or 168.
+// reductions and ballots: the floor caps the registers at 128 for up to 16 chunks per wave (at 16 chunks 24 values
+// spill; three waves per SIMD without spills measure the same). Rows of more than 16 chunks are shared by four (or
+// two) waves also when there are many rows: one wave per row at 28 chunks either spills 196 values (three waves per
+// SIMD) or takes 256 registers; 0.99 / 0.71 / 0.65 ms for 32768 rows of 14336 (one wave spilling / one wave / four).
 template <int CHUNKS, int NWV>
 __global__ void __launch_bounds__(64 * NWV)
-__attribute__((amdgpu_waves_per_eu(CHUNKS / NWV <= 16 ? 4 : 3, 8)))
+__attribute__((amdgpu_waves_per_eu(CHUNKS / NWV <= 16 ? 4 : 2, 8)))
 k_prune_fq_wave(bf16_t *__restrict__ a, const RowAct *__restrict__ ra, const int32_t *__restrict__ perm, int quant,
                 int prune, int64_t M)
 {
@@ -841,8 +844,8 @@ void launch_prune_fq(void *a, int dtype, const RowAct *ra, const int32_t *perm, 
     case C:                                                                                                     \
         if (few) hipLaunchKernelGGL((k_prune_fq_wave<C, (C % 4 == 0 ? 4 : 1)>), grid, dim3(C % 4 == 0 ? 256 : 64), 0, st, \
                                     (bf16_t *)a, ra, perm, quant ? 1 : 0, prune ? 1 : 0, M);                    \
-        else hipLaunchKernelGGL((k_prune_fq_wave<C, 1>), grid, dim3(64), 0, st, (bf16_t *)a, ra, perm, quant ? 1 : 0, \
-                                prune ? 1 : 0, M);                                                              \
+        else hipLaunchKernelGGL((k_prune_fq_wave<C, (C > 16 ? (C % 4 == 0 ? 4 : 2) : 1)>), grid, dim3(64 * (C > 16 ? (C % 4 == 0 ? 4 : 2) : 1)), 0, st, (bf16_t *)a, ra, \
+                                perm, quant ? 1 : 0, prune ? 1 : 0, M);       /* rows of more than 16 chunks: four (two) waves */ \
         return;
         switch (dff / 512) {
             SOL_PRUNE_CASE(2) SOL_PRUNE_CASE(4) SOL_PRUNE_CASE(8) SOL_PRUNE_CASE(16) SOL_PRUNE_CASE(22)
