@@ -119,12 +119,13 @@ def test_quant_codes_bit_exact(n):
 
 
 @pytest.mark.parametrize("n,dtype,rows", [(1024, "bf16", 24), (8192, "bf16", 24), (8192, "bf16", 600), (14336, "bf16", 24), (14336, "bf16", 600),
-                                          (11264, "bf16", 24), (768, "bf16", 24), (1024, "f32", 24), (8192, "f32", 24)])
+                                          (11264, "bf16", 24), (11264, "bf16", 600), (768, "bf16", 24), (1024, "f32", 24),
+                                          (8192, "f32", 24)])
 def test_prune_quant_kernel_bit_exact(n, dtype, rows):
     """The production prune + quantise kernel (wave-per-row for bf16 rows of 512*k channels, workgroup
     radix select otherwise) against oracle top-m mask -> fake-quant -> storage rounding."""
     from paper_2605_10875_amd import synth
-    rng = np.random.default_rng(n)                                   # up to 512 rows: four waves per row; more: one
+    rng = np.random.default_rng(n)     # up to 512 rows: four waves per row; more: one, or four / two for rows over 8192 channels
     a = (rng.standard_normal((rows, n)) * rng.standard_normal((rows, n))).astype(np.float32) * 0.4
     a[3] = np.round(a[3] * 2) / 2                                   # few distinct values, many exact zeros
     a[4] = 0.0
