@@ -672,8 +672,10 @@ template <int BQ, int SLOTS, int DH, int NW, bool PRE, bool KF> struct SelSide {
     static constexpr int RT = (BQ + 15) / 16, KK = DH / 32;
     // key tiles held per wave. Head size 128, rows up to 2048 keys: 2, with which the kernel fits 128 registers and a
     // second workgroup fits the CU (4 tiles: 168 registers, one workgroup; 1.28 -> 0.83 ms for the 1025..2048-key rows
-    // of 4096-token sequences at the 8B shape)
-    static constexpr int UA = (SLOTS <= 16 && DH <= 64) ? 8 : (SLOTS <= 32 && DH > 64) ? 2 : 4;
+    // of 4096-token sequences at the 8B shape). The 20-slot variant at head size 64 likewise: 80 registers and 41 KB
+    // of LDS, so three workgroups share a CU (episode pass, 16 rows per sequence on a 1024-token prefix: 272 -> 199 us
+    // per launch; on long walks, rows of 1025..1280 keys at C3, it gains nothing over the 32-slot variant)
+    static constexpr int UA = (SLOTS <= 16 && DH <= 64) ? 8 : ((SLOTS <= 32 && DH > 64) || SLOTS == 20) ? 2 : 4;
     // Rows longer than what the waves hold at once (SLOTS > 16): two register sets of UH key tiles each, one in flight
     // while the other is multiplied. Shorter rows: one set, all of it loaded while the block before is searched.
     static constexpr bool DB = SLOTS > 16;
@@ -715,7 +717,7 @@ template <int BQ, int SLOTS, int DH, int NW, bool PRE, bool KF> struct SelSide {
 // the registers are the same either way. With PRE the sequence's own keys (positions pv.P..) still come from its cache.
 template <int BQ, int SLOTS, int DH, int NW, bool PRE, bool KF>
 __global__ void __launch_bounds__(NW * 64)
-__attribute__((amdgpu_waves_per_eu(SLOTS <= 32 ? 4 : 2, SLOTS <= 16 ? 4 : 8)))
+__attribute__((amdgpu_waves_per_eu(SLOTS == 20 && DH <= 64 ? 6 : SLOTS <= 32 ? 4 : 2, SLOTS <= 16 ? 4 : 8)))
 k_attn_select(const bf16_t *__restrict__ q, const bf16_t *__restrict__ kc, SelRow *__restrict__ sel,
               const RowAct *__restrict__ ra, const int32_t *__restrict__ pos0, int Tn, int L_max, int Hq, int Hkv,
               float scale, int nb, PrefixView pv, int n_lo, int n_hi)
