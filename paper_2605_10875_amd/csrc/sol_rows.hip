@@ -414,6 +414,29 @@ k_fq_rows_wave(const float *__restrict__ in, bf16_t *__restrict__ out, const Row
     }
 }
 
+// xsum = x + the K-split partial sums (folded in split order): what k_rmsnorm_fq_wave<.., true> computes in its first
+// step, as a kernel of its own with one thread per 4 elements, for shapes where the norm's few workgroups (4 rows each)
+// would each have to read hundreds of KB of partial sums
+template <typename TX>
+__global__ void __launch_bounds__(256)
+k_fold_resid(const TX *__restrict__ x, const float *__restrict__ add, int nsplit, int64_t split_stride,
+             float *__restrict__ xsum, int64_t n4)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n4) return;
+    float t[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
+    for (int sp = 0; sp < nsplit; ++sp) {
+        const f32x4_w a = *reinterpret_cast<const f32x4_w *>(add + sp * split_stride + 4 * i);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) t[e] += a[e];
+    }
+    f32x4_w v;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = ld(x + 4 * i + e) + t[e];
+    *reinterpret_cast<f32x4_w *>(xsum + 4 * i) = v;
+}
+
 template <typename TX, typename TW, typename TH>
 static void rmsnorm_dispatch3(const void *x, const float *add, int nsplit, float *xsum, const void *w, void *h,
                               const RowAct *ra, bool quant, int64_t M, int d, float eps, hipStream_t st)
@@ -430,6 +453,13 @@ bool launch_rmsnorm_fq(const void *x, int x_dtype, const float *add, float *xsum
     if (w_dtype == 1 && h_dtype == 1 && (d == 2048 || d == 4096) && (add != nullptr) == (xsum != nullptr)) {
         const dim3 grid((unsigned)((M + 3) / 4));
         const int64_t ss = M * (int64_t)d;
+        if (add && (int64_t)nsplit * 16 * d > (512 << 10)) {     // a workgroup's 4 rows of partial sums: too much for the few
+            const int64_t n4 = ss / 4;                           // workgroups of a short batch; fold with the whole chip first
+            const dim3 fg((unsigned)((n4 + 255) / 256));
+            if (x_dtype == 1) hipLaunchKernelGGL((k_fold_resid<bf16_t>), fg, dim3(256), 0, st, (const bf16_t *)x, add, nsplit, ss, xsum, n4);
+            else hipLaunchKernelGGL((k_fold_resid<float>), fg, dim3(256), 0, st, (const float *)x, add, nsplit, ss, xsum, n4);
+            x = xsum, x_dtype = 0, add = nullptr, xsum = nullptr, nsplit = 1;
+        }
 #define SOL_NORM_WAVE(TX, CH)                                                                                   \
     if (add)                                                                                                    \
         hipLaunchKernelGGL((k_rmsnorm_fq_wave<TX, CH, true>), grid, dim3(256), 0, st, (const TX *)x, add, nsplit, ss, \
