@@ -300,7 +300,7 @@ k_rmsnorm_fq_wave(const TX *__restrict__ x, const float *__restrict__ add, int n
 {
     constexpr int D = CH * 512;
     const int lane = threadIdx.x & 63;
-    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t r = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);   // 4 rows per workgroup, or 1 (few rows)
     if (r >= M) return;                                      // whole wave
     float v[CH][8];
 #pragma unroll
@@ -415,8 +415,8 @@ k_fq_rows_wave(const float *__restrict__ in, bf16_t *__restrict__ out, const Row
 }
 
 // xsum = x + the K-split partial sums (folded in split order): what k_rmsnorm_fq_wave<.., true> computes in its first
-// step, as a kernel of its own with one thread per 4 elements, for shapes where the norm's few workgroups (4 rows each)
-// would each have to read hundreds of KB of partial sums
+// step, as a kernel of its own with one thread per 4 elements, for the short batches of a decode step whose rows each
+// come with hundreds of KB of partial sums (the norm reads a row's sums with one wave)
 template <typename TX>
 __global__ void __launch_bounds__(256)
 k_fold_resid(const TX *__restrict__ x, const float *__restrict__ add, int nsplit, int64_t split_stride,
@@ -451,10 +451,11 @@ bool launch_rmsnorm_fq(const void *x, int x_dtype, const float *add, float *xsum
 {
     if (M <= 0) return true;
     if (w_dtype == 1 && h_dtype == 1 && (d == 2048 || d == 4096) && (add != nullptr) == (xsum != nullptr)) {
-        const dim3 grid((unsigned)((M + 3) / 4));
+        const int rpw = M <= 512 ? 1 : 4;                        // a decode step's few rows: one per workgroup, on as many CUs
+        const dim3 grid((unsigned)((M + rpw - 1) / rpw)), block(64 * rpw);
         const int64_t ss = M * (int64_t)d;
-        if (add && (int64_t)nsplit * 16 * d > (512 << 10)) {     // a workgroup's 4 rows of partial sums: too much for the few
-            const int64_t n4 = ss / 4;                           // workgroups of a short batch; fold with the whole chip first
+        if (add && rpw == 1 && (int64_t)nsplit * 4 * d > (128 << 10)) {   // a row's partial sums: too much for one wave to
+            const int64_t n4 = ss / 4;                           // read in a row (35 us for 256 KB); fold with the whole chip first
             const dim3 fg((unsigned)((n4 + 255) / 256));
             if (x_dtype == 1) hipLaunchKernelGGL((k_fold_resid<bf16_t>), fg, dim3(256), 0, st, (const bf16_t *)x, add, nsplit, ss, xsum, n4);
             else hipLaunchKernelGGL((k_fold_resid<float>), fg, dim3(256), 0, st, (const float *)x, add, nsplit, ss, xsum, n4);
@@ -462,10 +463,10 @@ bool launch_rmsnorm_fq(const void *x, int x_dtype, const float *add, float *xsum
         }
 #define SOL_NORM_WAVE(TX, CH)                                                                                   \
     if (add)                                                                                                    \
-        hipLaunchKernelGGL((k_rmsnorm_fq_wave<TX, CH, true>), grid, dim3(256), 0, st, (const TX *)x, add, nsplit, ss, \
+        hipLaunchKernelGGL((k_rmsnorm_fq_wave<TX, CH, true>), grid, block, 0, st, (const TX *)x, add, nsplit, ss, \
                            xsum, (const bf16_t *)w, (bf16_t *)h, ra, quant ? 1 : 0, M, eps, prune ? 1 : 0);     \
     else                                                                                                        \
-        hipLaunchKernelGGL((k_rmsnorm_fq_wave<TX, CH, false>), grid, dim3(256), 0, st, (const TX *)x, add, nsplit, ss, \
+        hipLaunchKernelGGL((k_rmsnorm_fq_wave<TX, CH, false>), grid, block, 0, st, (const TX *)x, add, nsplit, ss, \
                            xsum, (const bf16_t *)w, (bf16_t *)h, ra, quant ? 1 : 0, M, eps, prune ? 1 : 0)
         if (x_dtype == 1) { if (d == 2048) { SOL_NORM_WAVE(bf16_t, 4); } else { SOL_NORM_WAVE(bf16_t, 8); } }
         else { if (d == 2048) { SOL_NORM_WAVE(float, 4); } else { SOL_NORM_WAVE(float, 8); } }
