@@ -2028,27 +2028,41 @@ bool launch_attn_decode_paged(const void *q, const void *k_cache, const void *v_
     return false;
 }
 
-// V cache [s][kvh][key][dh] -> vt [s][kvh][dh][lpadv] for keys < pos0[s] + Tn, zero beyond.
+// V cache [s][kvh][key][dh] -> vt [s][kvh][dh][lpadv] for keys < pos0[s] + Tn, zero beyond (lpadv a multiple of 64).
+// 16 bytes per lane on both sides of memory: 8 channels of a key in, 8 keys of a channel out; the tile's LDS rows are
+// DH + 2 elements apart (an odd number of words), which puts the 8 keys a lane gathers for its output, and the lanes
+// of a wave, on different banks.
 template <int DH>
 __global__ void __launch_bounds__(256)
 k_transpose_v(const bf16_t *__restrict__ vc, bf16_t *__restrict__ vt, const int32_t *__restrict__ pos0, int Tn, int L_max,
               int Hkv, int lpadv)
 {
-    __shared__ bf16_t tile[64][DH + 2];
+    constexpr int KP = DH / 8;                               // 16-byte pieces per key
+    __shared__ __align__(4) bf16_t tile[64][DH + 2];
     const int kb = blockIdx.x * 64, kvh = blockIdx.y, s = blockIdx.z;
     const int p0 = pos0 ? pos0[s] : 0;
     int len = p0 + Tn;
     if (p0 < 0 || len > L_max) len = 0;
     const bf16_t *src = vc + ((int64_t)s * Hkv + kvh) * (int64_t)L_max * DH;
     bf16_t *dst = vt + ((int64_t)s * Hkv + kvh) * (int64_t)DH * lpadv;
-    for (int idx = threadIdx.x; idx < 64 * DH; idx += 256) {
-        const int k = idx / DH, d = idx - k * DH;
-        tile[k][d] = (kb + k < len) ? src[(int64_t)(kb + k) * DH + d] : (bf16_t)0;
+    for (int idx = threadIdx.x; idx < 64 * KP; idx += 256) {
+        const int k = idx / KP, p = idx - k * KP;
+        u32x4_a v = {0u, 0u, 0u, 0u};
+        if (kb + k < len) v = *reinterpret_cast<const u32x4_a *>(src + (int64_t)(kb + k) * DH + p * 8);
+        uint32_t *row = reinterpret_cast<uint32_t *>(&tile[k][p * 8]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) row[e] = v[e];
     }
     __syncthreads();
-    for (int idx = threadIdx.x; idx < 64 * DH; idx += 256) {
-        const int d = idx >> 6, k = idx & 63;
-        if (kb + k < lpadv) dst[(int64_t)d * lpadv + kb + k] = tile[k][d];
+    for (int idx = threadIdx.x; idx < DH * 8; idx += 256) {
+        const int d = idx >> 3, kp = idx & 7;                // channel d, keys kb + 8 * kp .. + 7
+        if (kb + kp * 8 < lpadv) {
+            u32x4_a o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                o[e] = (uint32_t)tile[kp * 8 + 2 * e][d] | ((uint32_t)tile[kp * 8 + 2 * e + 1][d] << 16);
+            *reinterpret_cast<u32x4_a *>(dst + (int64_t)d * lpadv + kb + kp * 8) = o;
+        }
     }
 }
 
